@@ -1,0 +1,236 @@
+/*
+ * harli.h -- C ABI of the MI355X (gfx950) hot path of Harli (arXiv 2511.11729):
+ * a memory-bound small-batch LLM decode step co-located on one GPU with a
+ * compute-bound LoRA finetune step, both drawing memory from one unified pool.
+ *
+ * General rules
+ *  - Every call returns a harli_status; nothing throws or aborts across the ABI;
+ *    out-parameters are written only on HARLI_OK.  harli_last_error() returns a
+ *    thread-local, human-readable description of the last failure.
+ *  - "device" pointers are HIP device addresses, "host" pointers ordinary memory.
+ *  - The caller owns the slab, all weights, adapters, input/output buffers and
+ *    both streams.  The library owns host bookkeeping, the per-context device
+ *    workspace it allocates in harli_ctx_create / harli_lora_attach, and the
+ *    harli_saved records (whose device bytes live inside the caller's slab).
+ *  - Compute calls are asynchronous on the stream they are given and never
+ *    synchronise the device.  A context may run harli_decode_step on one stream
+ *    and harli_lora_fwd/bwd on another concurrently (Sec. 7: two model instances
+ *    in one process, each on its own stream); two decode steps, or two finetune
+ *    calls, of the same context must not overlap.
+ *  - Storage type: HARLI_BF16 (weights, KV cache and saved activations are
+ *    bfloat16, accumulation is fp32) or HARLI_F32 (everything fp32).  Hidden
+ *    states crossing the ABI (x, y, dY, dX), RMSNorm gains, logits and adapter
+ *    gradients are always fp32.
+ *  - Linear weights are [out, in] row-major (y = x W^T), no biases.  LoRA A is
+ *    [in, r], B is [r, out], y = x W^T + (alpha/r) (x A) B.
+ *  - Rotary embedding pairs element i with i + head_dim/2.
+ */
+#ifndef HARLI_H
+#define HARLI_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  HARLI_OK = 0,
+  HARLI_ERR_INVALID = 1, /* bad argument or unsupported shape */
+  HARLI_ERR_OOM = 2,     /* the pool (or the device) cannot serve the request */
+  HARLI_ERR_STATE = 3,   /* call not valid in the object's current state */
+  HARLI_ERR_HIP = 4      /* a HIP runtime call failed */
+} harli_status;
+
+typedef enum { HARLI_BF16 = 0, HARLI_F32 = 1 } harli_dtype;
+
+const char* harli_status_str(harli_status s);
+const char* harli_last_error(void);
+/* Library version string (static storage). */
+const char* harli_version(void);
+
+/* ======================================================================== *
+ * Unified memory pool (Sec. 4.2, 4.4, 4.5).  Host-side bookkeeping over ONE
+ * caller-owned device slab; no call here touches device memory.
+ *
+ * Slab layout:  [ small-tensor pool | chunk 0 | chunk 1 | ... ]
+ *   chunk  = n_layers x 2 blocks (Sec. 4.2); FREE, KV or TENSOR; returns to
+ *            FREE when everything in it is released.
+ *   block  = block_bytes (2 MiB in the paper).  In a KV chunk, block
+ *            2*layer + kv holds that layer's K (kv=0) or V (kv=1).
+ *   page   = page_tokens (16) consecutive tokens; pages_per_block =
+ *            floor(block_bytes / (page_tokens * kv_row_bytes)).  A page id is
+ *            chunk * pages_per_block + slot and names the same token run in
+ *            every layer's K and V -- one column of the paper's 2-D grid.
+ *            Inside a page the element order is [kv head][token slot][head_dim]
+ *            (the paper fixes the grid, not the order inside an entry; head-major
+ *            keeps one head's 16 tokens contiguous for the attention kernel).
+ *   small  = buddy allocator, granule small_granule (2 KiB, Sec. 4.5), made of
+ *            arenas of block_bytes each.
+ * Placement policy is "lowest index first" everywhere, so ids and offsets are
+ * reproducible.  KV pages may take any FREE chunk; tensor allocations must
+ * leave kv_reserve_chunks FREE chunks behind (inference priority, Sec. 4.4)
+ * and get HARLI_ERR_OOM otherwise.
+ * All pool calls are thread-safe (one mutex) and O(chunks) at worst.
+ * ======================================================================== */
+typedef struct harli_pool harli_pool;
+
+typedef struct {
+  size_t block_bytes;       /* power-of-two multiple of small_granule; paper: 2 MiB */
+  int32_t n_layers;         /* layerNum of the inference model */
+  int32_t page_tokens;      /* tokens per KV page (16) */
+  size_t kv_row_bytes;      /* n_kv_heads * head_dim * element size */
+  size_t small_pool_bytes;  /* multiple of block_bytes (may be 0) */
+  size_t small_granule;     /* paper: 2 KiB */
+  int32_t kv_reserve_chunks;
+} harli_pool_cfg;
+
+typedef enum { HARLI_CLS_KV_PAGE = 0, HARLI_CLS_TENSOR = 1, HARLI_CLS_SMALL = 2, HARLI_CLS_AUTO = 3 } harli_class;
+
+typedef struct {
+  int32_t cls;      /* class that served the request (SMALL may fall back to TENSOR) */
+  int32_t page;     /* KV_PAGE: page id; otherwise -1 */
+  size_t offset;    /* TENSOR / SMALL: byte offset from the slab base */
+  size_t bytes;     /* bytes reserved (request rounded up to blocks / buddy order) */
+  void* ptr;        /* slab + offset (device); NULL for KV_PAGE */
+} harli_alloc;
+
+typedef struct {
+  int32_t n_chunks, free_chunks, kv_chunks, tensor_chunks;
+  int32_t pages_per_block, blocks_per_chunk;
+  int64_t kv_pages_live, tensor_blocks_live;
+  size_t small_bytes_live;     /* reserved bytes in the buddy pool */
+  size_t requested_bytes_live; /* sum of requested sizes of live TENSOR/SMALL allocations */
+  size_t reserved_bytes_live;  /* sum of reserved sizes of the same allocations */
+  int64_t small_fallbacks;     /* SMALL requests served by a TENSOR block */
+  int64_t pending_frees;       /* frees still waiting for their event */
+} harli_pool_stats_t;
+
+/* slab: device base address (never dereferenced); slab_bytes >= small_pool_bytes + one chunk. */
+harli_status harli_pool_create(void* slab, size_t slab_bytes, const harli_pool_cfg* cfg, harli_pool** out);
+void harli_pool_destroy(harli_pool* p);
+
+/* One allocation.  cls = KV_PAGE: n is ignored, one page is returned in out->page.
+ * TENSOR: n bytes, rounded up to whole blocks, contiguous.  SMALL: n < block_bytes,
+ * rounded up to small_granule * 2^k.  AUTO: SMALL if n < block_bytes else TENSOR. */
+harli_status harli_pool_alloc(harli_pool* p, harli_class cls, size_t n, harli_alloc* out);
+/* n_pages KV pages at once into page_ids (host).  All or nothing. */
+harli_status harli_pool_alloc_pages(harli_pool* p, int32_t n_pages, int32_t* page_ids);
+
+/* Release.  `event` is a hipEvent_t (or NULL): when given, the memory becomes
+ * reusable only once hipEventQuery(event) reports completion (polled on later
+ * pool calls); the caller keeps the event alive until then.  Double free or an
+ * unknown allocation is HARLI_ERR_INVALID. */
+harli_status harli_pool_free(harli_pool* p, const harli_alloc* a, void* event);
+harli_status harli_pool_free_pages(harli_pool* p, int32_t n_pages, const int32_t* page_ids, void* event);
+
+/* Byte offset from the slab base of page `page` of layer `layer`'s K (kv=0) or V (kv=1):
+ * small_pool_bytes + chunk*chunk_bytes + (2*layer+kv)*block_bytes + slot*page_bytes. */
+harli_status harli_pool_kv_addr(const harli_pool* p, int32_t page, int32_t layer, int32_t kv, size_t* byte_off);
+harli_status harli_pool_stats(harli_pool* p, harli_pool_stats_t* out);
+
+/* ======================================================================== *
+ * Model context: shapes plus BORROWED device pointers to the frozen weights.
+ * ======================================================================== */
+typedef struct harli_ctx harli_ctx;
+
+typedef struct {
+  int32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab;
+  float rms_eps;    /* 1e-6 */
+  float rope_base;  /* 10000 */
+  int32_t dtype;    /* harli_dtype: storage of weights, KV cache, saved activations */
+  int32_t max_batch;      /* largest decode batch (1..256) */
+  int32_t max_seq_len;    /* largest kv_len[b] + 1 a decode step may see */
+  int32_t max_ft_tokens;  /* largest B_f*S of a finetune call (0: finetune unused) */
+} harli_model_cfg;
+
+typedef struct {
+  const void *wq, *wk, *wv, *wo, *wg, *wu, *wd; /* device, [out,in], cfg.dtype */
+  const float *g1, *g2;                         /* device, [hidden] RMSNorm gains */
+} harli_layer_weights;
+
+typedef struct {
+  const harli_layer_weights* layers; /* host array of n_layers entries (copied) */
+  const void* emb;                   /* device [vocab, hidden] or NULL */
+  const float* g_final;              /* device [hidden] or NULL */
+  const void* w_lm;                  /* device [vocab, hidden] or NULL */
+} harli_weights;
+
+/* The pool supplies the KV cache geometry and the slab; it must outlive the context.
+ * Allocates a device workspace proportional to max_batch and max_ft_tokens. */
+harli_status harli_ctx_create(const harli_model_cfg* cfg, const harli_weights* w, harli_pool* pool, harli_ctx** out);
+void harli_ctx_destroy(harli_ctx* c);
+/* Diagnostic, SYNCHRONISES `hip_stream`: reports (and clears) whether any kernel of this
+ * context met a page id outside the pool or a token id outside the vocabulary.  Such
+ * entries are skipped by the kernels, never dereferenced. */
+harli_status harli_ctx_check(harli_ctx* c, void* hip_stream);
+
+/* ---- LoRA adapters (Sec. 2.1: only the adapters are trainable) -------------- */
+enum { HARLI_T_Q = 1, HARLI_T_K = 2, HARLI_T_V = 4, HARLI_T_O = 8, HARLI_T_GATE = 16, HARLI_T_UP = 32, HARLI_T_DOWN = 64 };
+
+typedef struct {
+  int32_t rank;
+  float alpha;       /* scale = alpha / rank */
+  uint32_t targets;  /* bit mask of HARLI_T_* */
+} harli_lora_cfg;
+
+/* A, B: host arrays of n_layers*7 device pointers indexed [layer*7 + t], t = 0..6
+ * for q,k,v,o,gate,up,down (entries of non-adapted projections are ignored).
+ * Borrowed; the caller may update their contents between calls (optimizer step).
+ * Also builds library-owned transposed copies of the frozen weights that the
+ * backward pass streams (dx = dy W needs W with `in` as the slow axis). */
+harli_status harli_lora_attach(harli_ctx* c, const harli_lora_cfg* cfg, void* const* A, void* const* B);
+
+/* ======================================================================== *
+ * Decode step (Sec. 2.1: one new token per sequence; Sec. 4.1: KV slots by index).
+ * For every layer: RMSNorm, Q/K/V projection, rotary embedding at position
+ * kv_len[b], append K/V to page page_table[b][kv_len[b]/page_tokens] at slot
+ * kv_len[b]%page_tokens, attention over positions 0..kv_len[b], output
+ * projection + residual, SwiGLU FFN + residual.  Base weights only.
+ * ======================================================================== */
+typedef struct {
+  int32_t batch;              /* 1..cfg.max_batch */
+  const int32_t* token_ids;   /* device [batch] (needs emb) or NULL */
+  const float* x_in;          /* device [batch, hidden], used when token_ids is NULL */
+  float* x_out;               /* device [batch, hidden]: hidden state after the last layer, or NULL */
+  float* logits;              /* device [batch, vocab] (needs g_final, w_lm) or NULL */
+  int32_t* next_token;        /* device [batch]: argmax of logits, ties to the lowest index, or NULL */
+  const int32_t* kv_len;      /* device [batch]: tokens cached BEFORE this step */
+  const int32_t* page_table;  /* device [batch, max_pages]: page ids; must already hold the page of position kv_len[b] */
+  int32_t max_pages;          /* row stride of page_table */
+  int32_t max_kv_len;         /* host-known upper bound of kv_len[b] + 1 (sizes the attention grid) */
+} harli_decode_batch;
+
+harli_status harli_decode_step(harli_ctx* c, const harli_decode_batch* b, void* hip_stream);
+
+/* ======================================================================== *
+ * Finetune unit (Sec. 6.1): one transformer layer x one micro-batch.
+ * ======================================================================== */
+typedef struct harli_saved harli_saved;
+
+/* Y = layer(X) with LoRA on the attached targets, causal attention over each of
+ * the B_f sequences of S tokens (positions 0..S-1).  X, Y: device [B_f*S, hidden]
+ * fp32.  The activations the backward pass needs are placed in buffers taken
+ * from the pool (TENSOR/SMALL classes) and returned in *saved; X itself is
+ * copied.  HARLI_ERR_OOM leaves nothing allocated. */
+harli_status harli_lora_fwd(harli_ctx* c, int32_t layer, const float* X, float* Y, int32_t B_f, int32_t S,
+                            harli_saved** saved, void* hip_stream);
+
+/* dX = d loss / dX given dY = d loss / dY (device [B_f*S, hidden] fp32).
+ * dA, dB: host arrays of 7 device pointers (q,k,v,o,gate,up,down; fp32, shapes
+ * of A and B); the adapter gradients are ACCUMULATED into them.  Frozen weights
+ * get no gradient.  Consumes `saved`: its pool memory is released with an event
+ * recorded on `hip_stream` after the last kernel. */
+harli_status harli_lora_bwd(harli_ctx* c, int32_t layer, const float* dY, float* dX, harli_saved* saved,
+                            float* const* dA, float* const* dB, void* hip_stream);
+
+/* Drop a saved record without running backward (forward-only unit). */
+harli_status harli_saved_release(harli_ctx* c, harli_saved* saved, void* hip_stream);
+/* Pool bytes a forward call of (B_f, S) reserves for its saved activations. */
+harli_status harli_saved_bytes(const harli_ctx* c, int32_t B_f, int32_t S, size_t* bytes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HARLI_H */

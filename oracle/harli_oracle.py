@@ -189,8 +189,12 @@ class PoolGeometry:
         return (self.small_pool_bytes + chunk * self.chunk_bytes
                 + (2 * layer + kv) * self.block_bytes + slot * self.page_bytes)
 
-    def token_offset(self, page: int, layer: int, kv: int, slot_in_page: int) -> int:
-        return self.kv_offset(page, layer, kv) + slot_in_page * self.kv_row_bytes
+    def head_offset(self, page: int, layer: int, kv: int, head: int, slot_in_page: int, head_bytes: int) -> int:
+        """Byte offset of one token's vector of one KV head.  Inside a page the
+        order is [kv head][token slot][head_dim]: the paper fixes the grid of
+        pages, not the order inside an entry, and head-major keeps the 16
+        tokens of one head contiguous."""
+        return self.kv_offset(page, layer, kv) + (head * self.page_tokens + slot_in_page) * head_bytes
 
 
 class PagedKV:
@@ -203,17 +207,19 @@ class PagedKV:
         assert geom.kv_row_bytes == n_kv * d * elem_bytes
         self.slab = np.zeros(geom.slab_bytes // elem_bytes, F) if slab is None else slab
 
-    def _row(self, page: int, layer: int, kv: int, slot: int) -> slice:
-        off = self.g.token_offset(page, layer, kv, slot)
+    def _vec(self, page: int, layer: int, kv: int, head: int, slot: int) -> slice:
+        off = self.g.head_offset(page, layer, kv, head, slot, self.d * self.eb)
         assert off % self.eb == 0
         e = off // self.eb
-        return slice(e, e + self.n_kv * self.d)
+        return slice(e, e + self.d)
 
     def write(self, table_row: Sequence[int], layer: int, pos: int, k: np.ndarray, v: np.ndarray):
         P = self.g.page_tokens
         page, slot = int(table_row[pos // P]), pos % P
-        self.slab[self._row(page, layer, 0, slot)] = np.asarray(k, F).reshape(-1)
-        self.slab[self._row(page, layer, 1, slot)] = np.asarray(v, F).reshape(-1)
+        k, v = np.asarray(k, F).reshape(self.n_kv, self.d), np.asarray(v, F).reshape(self.n_kv, self.d)
+        for c in range(self.n_kv):
+            self.slab[self._vec(page, layer, 0, c, slot)] = k[c]
+            self.slab[self._vec(page, layer, 1, c, slot)] = v[c]
 
     def gather(self, table_row: Sequence[int], layer: int, n: int):
         """K, V [n, n_kv, d] of logical positions 0..n-1."""
@@ -222,8 +228,9 @@ class PagedKV:
         V = np.empty((n, self.n_kv, self.d), F)
         for t in range(n):
             page, slot = int(table_row[t // P]), t % P
-            K[t] = self.slab[self._row(page, layer, 0, slot)].reshape(self.n_kv, self.d)
-            V[t] = self.slab[self._row(page, layer, 1, slot)].reshape(self.n_kv, self.d)
+            for c in range(self.n_kv):
+                K[t, c] = self.slab[self._vec(page, layer, 0, c, slot)]
+                V[t, c] = self.slab[self._vec(page, layer, 1, c, slot)]
         return K, V
 
 

@@ -177,8 +177,9 @@ class PoolModel:
                     self.small_free.add((off + (self.granule << o), o))
                 self.live[off] = (CLS_SMALL, self.granule << order)
                 return off, self.granule << order
-        self.small_fallbacks += 1                      # pool exhausted: one general block
-        return self.alloc_tensor(self.block_bytes)
+        got = self.alloc_tensor(self.block_bytes)      # pool exhausted: one general block
+        self.small_fallbacks += 1                      # counted only when the block was granted
+        return got
 
     def _free_small(self, off: int, nbytes: int) -> None:
         o = (nbytes // self.granule).bit_length() - 1

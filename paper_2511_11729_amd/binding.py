@@ -1,0 +1,274 @@
+"""ctypes binding of libharli.so: same names as include/harli.h, argument marshalling only.
+
+Every step of the path runs inside the HIP library; this module converts Python
+values to C structs and raises on a non-zero status.  It fails loudly if the
+library has not been built (`python -m paper_2511_11729_amd.build`).
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libharli.so")
+
+HARLI_OK, HARLI_ERR_INVALID, HARLI_ERR_OOM, HARLI_ERR_STATE, HARLI_ERR_HIP = range(5)
+HARLI_BF16, HARLI_F32 = 0, 1
+CLS_KV_PAGE, CLS_TENSOR, CLS_SMALL, CLS_AUTO = range(4)
+TARGET_BITS = {"q": 1, "k": 2, "v": 4, "o": 8, "gate": 16, "up": 32, "down": 64}
+TARGET_ORDER = ("q", "k", "v", "o", "gate", "up", "down")
+
+
+class HarliError(RuntimeError):
+    def __init__(self, status: int, msg: str):
+        super().__init__("harli status %d: %s" % (status, msg))
+        self.status = status
+
+
+class PoolCfg(C.Structure):
+    _fields_ = [("block_bytes", C.c_size_t), ("n_layers", C.c_int32), ("page_tokens", C.c_int32),
+                ("kv_row_bytes", C.c_size_t), ("small_pool_bytes", C.c_size_t), ("small_granule", C.c_size_t),
+                ("kv_reserve_chunks", C.c_int32)]
+
+
+class Alloc(C.Structure):
+    _fields_ = [("cls", C.c_int32), ("page", C.c_int32), ("offset", C.c_size_t), ("bytes", C.c_size_t),
+                ("ptr", C.c_void_p)]
+
+
+class PoolStats(C.Structure):
+    _fields_ = [("n_chunks", C.c_int32), ("free_chunks", C.c_int32), ("kv_chunks", C.c_int32),
+                ("tensor_chunks", C.c_int32), ("pages_per_block", C.c_int32), ("blocks_per_chunk", C.c_int32),
+                ("kv_pages_live", C.c_int64), ("tensor_blocks_live", C.c_int64), ("small_bytes_live", C.c_size_t),
+                ("requested_bytes_live", C.c_size_t), ("reserved_bytes_live", C.c_size_t),
+                ("small_fallbacks", C.c_int64), ("pending_frees", C.c_int64)]
+
+
+class ModelCfg(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("hidden", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("ffn", C.c_int32), ("vocab", C.c_int32), ("rms_eps", C.c_float),
+                ("rope_base", C.c_float), ("dtype", C.c_int32), ("max_batch", C.c_int32), ("max_seq_len", C.c_int32),
+                ("max_ft_tokens", C.c_int32)]
+
+
+class LayerWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("wq", "wk", "wv", "wo", "wg", "wu", "wd", "g1", "g2")]
+
+
+class Weights(C.Structure):
+    _fields_ = [("layers", C.POINTER(LayerWeights)), ("emb", C.c_void_p), ("g_final", C.c_void_p), ("w_lm", C.c_void_p)]
+
+
+class LoraCfg(C.Structure):
+    _fields_ = [("rank", C.c_int32), ("alpha", C.c_float), ("targets", C.c_uint32)]
+
+
+class DecodeBatch(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("token_ids", C.c_void_p), ("x_in", C.c_void_p), ("x_out", C.c_void_p),
+                ("logits", C.c_void_p), ("next_token", C.c_void_p), ("kv_len", C.c_void_p), ("page_table", C.c_void_p),
+                ("max_pages", C.c_int32), ("max_kv_len", C.c_int32)]
+
+
+_lib = None
+
+_SIGS = {
+    "harli_status_str": (C.c_char_p, [C.c_int]),
+    "harli_last_error": (C.c_char_p, []),
+    "harli_version": (C.c_char_p, []),
+    "harli_pool_create": (C.c_int, [C.c_void_p, C.c_size_t, C.POINTER(PoolCfg), C.POINTER(C.c_void_p)]),
+    "harli_pool_destroy": (None, [C.c_void_p]),
+    "harli_pool_alloc": (C.c_int, [C.c_void_p, C.c_int, C.c_size_t, C.POINTER(Alloc)]),
+    "harli_pool_alloc_pages": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_int32)]),
+    "harli_pool_free": (C.c_int, [C.c_void_p, C.POINTER(Alloc), C.c_void_p]),
+    "harli_pool_free_pages": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_int32), C.c_void_p]),
+    "harli_pool_kv_addr": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_size_t)]),
+    "harli_pool_stats": (C.c_int, [C.c_void_p, C.POINTER(PoolStats)]),
+    "harli_ctx_create": (C.c_int, [C.POINTER(ModelCfg), C.POINTER(Weights), C.c_void_p, C.POINTER(C.c_void_p)]),
+    "harli_ctx_destroy": (None, [C.c_void_p]),
+    "harli_ctx_check": (C.c_int, [C.c_void_p, C.c_void_p]),
+    "harli_lora_attach": (C.c_int, [C.c_void_p, C.POINTER(LoraCfg), C.POINTER(C.c_void_p), C.POINTER(C.c_void_p)]),
+    "harli_decode_step": (C.c_int, [C.c_void_p, C.POINTER(DecodeBatch), C.c_void_p]),
+    "harli_lora_fwd": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
+                                 C.POINTER(C.c_void_p), C.c_void_p]),
+    "harli_lora_bwd": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                 C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_void_p]),
+    "harli_saved_release": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
+    "harli_saved_bytes": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_size_t)]),
+}
+
+
+def lib() -> C.CDLL:
+    """The loaded library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libharli.so is missing: run `python -m paper_2511_11729_amd.build` "
+                               "(there is no CPU fallback)")
+        l = C.CDLL(LIB_PATH)
+        for name, (res, args) in _SIGS.items():
+            fn = getattr(l, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = l
+    return _lib
+
+
+def _check(status: int) -> None:
+    if status != HARLI_OK:
+        raise HarliError(status, lib().harli_last_error().decode())
+
+
+def _ptr(t) -> Optional[int]:
+    """Device (or host) address of a torch tensor, an int, or None."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream(s) -> Optional[int]:
+    if s is None:
+        return None
+    if isinstance(s, int):
+        return s
+    return s.cuda_stream
+
+
+# ----------------------------------------------------------------------------- pool
+class Pool:
+    """harli_pool_* over a caller-owned slab (a torch uint8 tensor or a raw address)."""
+
+    def __init__(self, slab, slab_bytes: int, *, block_bytes: int = 2 << 20, n_layers: int, page_tokens: int = 16,
+                 kv_row_bytes: int, small_pool_bytes: int = 0, small_granule: int = 2048, kv_reserve_chunks: int = 0):
+        self._slab = slab
+        self.cfg = PoolCfg(block_bytes, n_layers, page_tokens, kv_row_bytes, small_pool_bytes, small_granule,
+                           kv_reserve_chunks)
+        self.handle = C.c_void_p()
+        _check(lib().harli_pool_create(_ptr(slab), slab_bytes, C.byref(self.cfg), C.byref(self.handle)))
+
+    def close(self):
+        if self.handle:
+            lib().harli_pool_destroy(self.handle)
+            self.handle = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def alloc(self, cls: int, n: int = 0) -> Alloc:
+        a = Alloc()
+        _check(lib().harli_pool_alloc(self.handle, cls, n, C.byref(a)))
+        return a
+
+    def alloc_pages(self, n: int) -> List[int]:
+        ids = (C.c_int32 * max(n, 1))()
+        _check(lib().harli_pool_alloc_pages(self.handle, n, ids))
+        return list(ids[:n])
+
+    def free(self, a: Alloc, event=None) -> None:
+        _check(lib().harli_pool_free(self.handle, C.byref(a), _event(event)))
+
+    def free_pages(self, ids: Sequence[int], event=None) -> None:
+        arr = (C.c_int32 * max(len(ids), 1))(*ids)
+        _check(lib().harli_pool_free_pages(self.handle, len(ids), arr, _event(event)))
+
+    def kv_addr(self, page: int, layer: int, kv: int) -> int:
+        off = C.c_size_t()
+        _check(lib().harli_pool_kv_addr(self.handle, page, layer, kv, C.byref(off)))
+        return off.value
+
+    def stats(self) -> PoolStats:
+        s = PoolStats()
+        _check(lib().harli_pool_stats(self.handle, C.byref(s)))
+        return s
+
+
+def _event(e) -> Optional[int]:
+    if e is None:
+        return None
+    if isinstance(e, int):
+        return e
+    return e.cuda_event
+
+
+# ----------------------------------------------------------------------------- context
+class Context:
+    """harli_ctx_* ; `layers` is a list of dicts of torch tensors (wq..wd, g1, g2)."""
+
+    def __init__(self, pool: Pool, *, n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab=0,
+                 rms_eps=1e-6, rope_base=10000.0, dtype=HARLI_BF16, max_batch=16, max_seq_len=4096,
+                 max_ft_tokens=0, layers, emb=None, g_final=None, w_lm=None):
+        self.pool = pool
+        self._keep = (layers, emb, g_final, w_lm)
+        self.cfg = ModelCfg(n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab, rms_eps, rope_base, dtype,
+                            max_batch, max_seq_len, max_ft_tokens)
+        arr = (LayerWeights * n_layers)()
+        for i, lw in enumerate(layers):
+            for n in ("wq", "wk", "wv", "wo", "wg", "wu", "wd", "g1", "g2"):
+                setattr(arr[i], n, _ptr(lw[n]))
+        w = Weights(arr, _ptr(emb), _ptr(g_final), _ptr(w_lm))
+        self.handle = C.c_void_p()
+        _check(lib().harli_ctx_create(C.byref(self.cfg), C.byref(w), pool.handle, C.byref(self.handle)))
+
+    def close(self):
+        if self.handle:
+            lib().harli_ctx_destroy(self.handle)
+            self.handle = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def check(self, stream=None) -> None:
+        _check(lib().harli_ctx_check(self.handle, _stream(stream)))
+
+    def lora_attach(self, rank: int, alpha: float, targets: Sequence[str], A, B) -> None:
+        """A, B: per layer a dict target -> torch tensor."""
+        n_layers = self.cfg.n_layers
+        self._lora_keep = (A, B)
+        pa = (C.c_void_p * (n_layers * 7))()
+        pb = (C.c_void_p * (n_layers * 7))()
+        mask = 0
+        for t in targets:
+            mask |= TARGET_BITS[t]
+        for l in range(n_layers):
+            for i, t in enumerate(TARGET_ORDER):
+                if t in targets:
+                    pa[l * 7 + i] = _ptr(A[l][t])
+                    pb[l * 7 + i] = _ptr(B[l][t])
+        cfg = LoraCfg(rank, alpha, mask)
+        _check(lib().harli_lora_attach(self.handle, C.byref(cfg), pa, pb))
+
+    def decode_step(self, *, batch, kv_len, page_table, max_pages, max_kv_len, token_ids=None, x_in=None, x_out=None,
+                    logits=None, next_token=None, stream=None) -> None:
+        b = DecodeBatch(batch, _ptr(token_ids), _ptr(x_in), _ptr(x_out), _ptr(logits), _ptr(next_token), _ptr(kv_len),
+                        _ptr(page_table), max_pages, max_kv_len)
+        _check(lib().harli_decode_step(self.handle, C.byref(b), _stream(stream)))
+
+    def lora_fwd(self, layer: int, X, Y, B_f: int, S: int, stream=None) -> int:
+        saved = C.c_void_p()
+        _check(lib().harli_lora_fwd(self.handle, layer, _ptr(X), _ptr(Y), B_f, S, C.byref(saved), _stream(stream)))
+        return saved.value
+
+    def lora_bwd(self, layer: int, dY, dX, saved: int, dA, dB, stream=None) -> None:
+        """dA, dB: dict target -> fp32 torch tensor (accumulated into)."""
+        pa = (C.c_void_p * 7)()
+        pb = (C.c_void_p * 7)()
+        for i, t in enumerate(TARGET_ORDER):
+            if t in dA:
+                pa[i] = _ptr(dA[t])
+                pb[i] = _ptr(dB[t])
+        _check(lib().harli_lora_bwd(self.handle, layer, _ptr(dY), _ptr(dX), saved, pa, pb, _stream(stream)))
+
+    def saved_release(self, saved: int, stream=None) -> None:
+        _check(lib().harli_saved_release(self.handle, saved, _stream(stream)))
+
+    def saved_bytes(self, B_f: int, S: int) -> int:
+        n = C.c_size_t()
+        _check(lib().harli_saved_bytes(self.handle, B_f, S, C.byref(n)))
+        return n.value

@@ -1,0 +1,75 @@
+// Internal definition of the model context.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <vector>
+
+#include "common.h"
+
+#define HARLI_HIP(call)                                                                      \
+  do {                                                                                       \
+    hipError_t e_ = (call);                                                                  \
+    if (e_ != hipSuccess)                                                                    \
+      return harli::fail(HARLI_ERR_HIP, "%s failed: %s (%s:%d)", #call, hipGetErrorString(e_), __FILE__, __LINE__); \
+  } while (0)
+
+namespace harli {
+
+constexpr int kTargets = 7;  // q,k,v,o,gate,up,down
+
+struct LayerDev {
+  const void* w[kTargets];   // wq wk wv wo wg wu wd, [out,in]
+  void* wt[kTargets];        // library-owned transposes [in,out] for the backward pass (after lora_attach)
+  const float *g1, *g2;
+  void* A[kTargets];         // borrowed adapter pointers (NULL when not adapted)
+  void* B[kTargets];
+};
+
+// Device buffers of the decode path, sized by max_batch (rounded up to 16).
+struct DecodeWs {
+  int bpad = 0;
+  void *hx1 = nullptr, *obuf = nullptr, *hx2 = nullptr, *mbuf = nullptr;  // GEMM operands in storage dtype
+  float *qbuf = nullptr, *x1 = nullptr, *xa = nullptr, *xb = nullptr;    // fp32
+  float* ssq = nullptr;       // [2*L+1][bpad]
+  float* rope = nullptr;      // [bpad][d/2][2]
+  float* att_part = nullptr;  // [bpad][n_q][max_chunks][d+2]
+  int* att_cnt = nullptr;     // [bpad][n_kv]
+  float* scores = nullptr;    // fp32 path only: [bpad][n_q][max_seq_len]
+  int* err_flag = nullptr;    // device int set when a kernel sees an out-of-range page id
+  int max_chunks = 0;
+};
+
+}  // namespace harli
+
+struct harli_ctx {
+  harli_model_cfg cfg{};
+  harli_pool* pool = nullptr;
+  harli::KvGeom geom{};
+  char* slab = nullptr;
+  std::vector<harli::LayerDev> layers;
+  const void* emb = nullptr;
+  const float* g_final = nullptr;
+  const void* w_lm = nullptr;
+  harli::DecodeWs dw;
+  // LoRA / finetune state
+  bool lora_attached = false;
+  harli_lora_cfg lora{};
+  void* ft_ws = nullptr;     // finetune workspace (library-owned)
+  size_t ft_ws_bytes = 0;
+  int n_cu = 0;
+};
+
+namespace harli {
+// element size of the storage dtype
+inline size_t esize(const harli_ctx* c) { return c->cfg.dtype == HARLI_BF16 ? 2 : 4; }
+inline void proj_shape(const harli_model_cfg& m, int t, int* out, int* in) {
+  int q = m.n_q_heads * m.head_dim, kv = m.n_kv_heads * m.head_dim;
+  switch (t) {
+    case 0: *out = q; *in = m.hidden; break;
+    case 1: case 2: *out = kv; *in = m.hidden; break;
+    case 3: *out = m.hidden; *in = q; break;
+    case 4: case 5: *out = m.ffn; *in = m.hidden; break;
+    default: *out = m.hidden; *in = m.ffn; break;
+  }
+}
+}  // namespace harli

@@ -1,0 +1,148 @@
+// Model context: shapes, borrowed weight pointers and the library-owned device workspace.
+#include "ctx.h"
+
+using namespace harli;
+
+namespace harli {
+
+int event_done(void* hip_event) {
+  hipError_t e = hipEventQuery(static_cast<hipEvent_t>(hip_event));
+  if (e == hipSuccess) return 1;
+  if (e == hipErrorNotReady) return 0;
+  (void)hipGetLastError();
+  return -1;
+}
+
+template <typename T>
+static harli_status dev_alloc(T** p, size_t bytes, bool zero) {
+  HARLI_HIP(hipMalloc(reinterpret_cast<void**>(p), bytes ? bytes : 16));
+  if (zero) HARLI_HIP(hipMemset(*p, 0, bytes ? bytes : 16));
+  return HARLI_OK;
+}
+
+void free_finetune_state(harli_ctx* c);  // finetune.hip
+
+}  // namespace harli
+
+#define TRY(x)                       \
+  do {                               \
+    harli_status s_ = (x);           \
+    if (s_ != HARLI_OK) {            \
+      harli_ctx_destroy(c);          \
+      return s_;                     \
+    }                                \
+  } while (0)
+
+extern "C" harli_status harli_ctx_create(const harli_model_cfg* cfg, const harli_weights* w, harli_pool* pool,
+                                         harli_ctx** out) {
+  if (!cfg || !w || !pool || !out || !w->layers) return fail(HARLI_ERR_INVALID, "ctx_create: null argument");
+  const harli_model_cfg& m = *cfg;
+  if (m.n_layers < 1 || m.hidden < 1 || m.n_q_heads < 1 || m.n_kv_heads < 1 || m.head_dim < 2 || m.ffn < 1)
+    return fail(HARLI_ERR_INVALID, "ctx_create: non-positive shape");
+  if (m.n_q_heads % m.n_kv_heads != 0) return fail(HARLI_ERR_INVALID, "ctx_create: n_q_heads %% n_kv_heads != 0");
+  if (m.head_dim % 2 != 0) return fail(HARLI_ERR_INVALID, "ctx_create: head_dim must be even (rotary pairs)");
+  if (m.dtype != HARLI_BF16 && m.dtype != HARLI_F32) return fail(HARLI_ERR_INVALID, "ctx_create: unknown dtype");
+  if (m.max_batch < 1 || m.max_batch > 256) return fail(HARLI_ERR_INVALID, "ctx_create: max_batch outside 1..256");
+  if (m.max_seq_len < 1) return fail(HARLI_ERR_INVALID, "ctx_create: max_seq_len must be positive");
+  if (m.max_ft_tokens < 0) return fail(HARLI_ERR_INVALID, "ctx_create: negative max_ft_tokens");
+  const int QD = m.n_q_heads * m.head_dim;
+  if (m.dtype == HARLI_BF16) {
+    if (m.head_dim != 64 && m.head_dim != 128)
+      return fail(HARLI_ERR_INVALID, "ctx_create: bf16 kernels support head_dim 64 or 128, got %d", m.head_dim);
+    if (m.hidden % 8 || m.ffn % 8 || QD % 8)
+      return fail(HARLI_ERR_INVALID, "ctx_create: bf16 kernels need hidden, ffn and n_q*head_dim to be multiples of 8");
+    const int G = m.n_q_heads / m.n_kv_heads;
+    if (G != 1 && G != 2 && G != 4 && G != 8)
+      return fail(HARLI_ERR_INVALID, "ctx_create: query/KV head ratio %d is not supported", G);
+  }
+  KvGeom geom;
+  harli_pool_geom(pool, &geom);
+  const size_t eb = m.dtype == HARLI_BF16 ? 2 : 4;
+  if (geom.n_layers != m.n_layers) return fail(HARLI_ERR_INVALID, "ctx_create: pool has %d layers, model %d", geom.n_layers, m.n_layers);
+  if (geom.row_bytes != (unsigned long long)m.n_kv_heads * m.head_dim * eb)
+    return fail(HARLI_ERR_INVALID, "ctx_create: pool kv_row_bytes %llu != n_kv*head_dim*elem %zu", geom.row_bytes,
+                (size_t)m.n_kv_heads * m.head_dim * eb);
+  if (geom.page_tokens != 16) return fail(HARLI_ERR_INVALID, "ctx_create: kernels are built for 16-token pages");
+  for (int l = 0; l < m.n_layers; ++l) {
+    const harli_layer_weights& lw = w->layers[l];
+    if (!lw.wq || !lw.wk || !lw.wv || !lw.wo || !lw.wg || !lw.wu || !lw.wd || !lw.g1 || !lw.g2)
+      return fail(HARLI_ERR_INVALID, "ctx_create: layer %d has a null weight pointer", l);
+  }
+  if ((w->emb || w->w_lm) && m.vocab < 1) return fail(HARLI_ERR_INVALID, "ctx_create: vocab must be positive");
+
+  harli_ctx* c = new harli_ctx;
+  c->cfg = m;
+  c->pool = pool;
+  c->geom = geom;
+  c->slab = static_cast<char*>(harli_pool_slab(pool));
+  c->layers.resize(m.n_layers);
+  for (int l = 0; l < m.n_layers; ++l) {
+    const harli_layer_weights& lw = w->layers[l];
+    LayerDev& d = c->layers[l];
+    const void* ws[kTargets] = {lw.wq, lw.wk, lw.wv, lw.wo, lw.wg, lw.wu, lw.wd};
+    for (int t = 0; t < kTargets; ++t) {
+      d.w[t] = ws[t];
+      d.wt[t] = nullptr;
+      d.A[t] = d.B[t] = nullptr;
+    }
+    d.g1 = lw.g1;
+    d.g2 = lw.g2;
+  }
+  c->emb = w->emb;
+  c->g_final = w->g_final;
+  c->w_lm = w->w_lm;
+  int dev = 0;
+  hipDeviceProp_t prop;
+  if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) {
+    delete c;
+    return fail(HARLI_ERR_HIP, "ctx_create: no HIP device available");
+  }
+  c->n_cu = prop.multiProcessorCount;
+
+  DecodeWs& d = c->dw;
+  d.bpad = (m.max_batch + 15) / 16 * 16;
+  d.max_chunks = (m.max_seq_len + 255) / 256;
+  const size_t bp = d.bpad;
+  TRY(dev_alloc(&d.hx1, bp * m.hidden * 4, true));
+  TRY(dev_alloc(&d.obuf, bp * QD * 4, true));
+  TRY(dev_alloc(&d.hx2, bp * m.hidden * 4, true));
+  TRY(dev_alloc(&d.mbuf, bp * m.ffn * 4, true));
+  TRY(dev_alloc(&d.qbuf, bp * QD * 4, true));
+  TRY(dev_alloc(&d.x1, bp * m.hidden * 4, true));
+  TRY(dev_alloc(&d.xa, bp * m.hidden * 4, true));
+  TRY(dev_alloc(&d.xb, bp * m.hidden * 4, true));
+  TRY(dev_alloc(&d.ssq, bp * (2 * m.n_layers + 1) * 4, true));
+  TRY(dev_alloc(&d.rope, bp * m.head_dim * 4, true));
+  TRY(dev_alloc(&d.att_part, bp * m.n_q_heads * d.max_chunks * (m.head_dim + 2) * 4, true));
+  TRY(dev_alloc(&d.att_cnt, bp * m.n_kv_heads * 4, true));
+  TRY(dev_alloc(&d.err_flag, 16, true));
+  // fp32 path: scratch for attention scores, one row of max_seq_len per (sequence, query head)
+  if (m.dtype == HARLI_F32) TRY(dev_alloc(&d.scores, bp * m.n_q_heads * (size_t)m.max_seq_len * 4, true));
+  *out = c;
+  return HARLI_OK;
+}
+
+extern "C" void harli_ctx_destroy(harli_ctx* c) {
+  if (!c) return;
+  DecodeWs& d = c->dw;
+  void* bufs[] = {d.hx1, d.obuf, d.hx2, d.mbuf, d.qbuf, d.x1, d.xa, d.xb, d.ssq, d.rope, d.att_part, d.att_cnt, d.err_flag, d.scores};
+  for (void* p : bufs)
+    if (p) (void)hipFree(p);
+  free_finetune_state(c);
+  delete c;
+}
+
+extern "C" harli_status harli_ctx_check(harli_ctx* c, void* hip_stream) {
+  if (!c) return fail(HARLI_ERR_INVALID, "ctx_check: null context");
+  int flag = 0;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  HARLI_HIP(hipMemcpyAsync(&flag, c->dw.err_flag, sizeof(int), hipMemcpyDeviceToHost, st));
+  HARLI_HIP(hipStreamSynchronize(st));
+  if (flag) {
+    HARLI_HIP(hipMemsetAsync(c->dw.err_flag, 0, sizeof(int), st));
+    HARLI_HIP(hipStreamSynchronize(st));
+    return fail(HARLI_ERR_INVALID, "a kernel saw %s%s", (flag & 1) ? "a page id outside the pool " : "",
+                (flag & 2) ? "a token id outside the vocabulary" : "");
+  }
+  return HARLI_OK;
+}

@@ -53,6 +53,10 @@ def test_kv_offset_is_the_2d_grid():
     assert all(a[1] <= b[0] for a, b in zip(spans, spans[1:]))
     # one page id names the same column in every row of its chunk
     assert g.kv_offset(7, 2, 1) - g.kv_offset(7, 0, 0) == 5 * 4096
+    # inside a page: [kv head][token slot][head_dim]; 96 B rows = 3 heads x 8 x 4 B
+    assert g.head_offset(7, 1, 0, 0, 0, 32) == g.kv_offset(7, 1, 0)
+    assert g.head_offset(7, 1, 0, 2, 3, 32) == g.kv_offset(7, 1, 0) + (2 * 4 + 3) * 32
+    assert g.head_offset(7, 1, 0, 2, 3, 32) + 32 <= g.kv_offset(7, 1, 0) + g.page_bytes
 
 
 # ----------------------------------------------------------------------------- paged == contiguous
@@ -115,8 +119,9 @@ def test_page_walk_integer_round_trip():
     for layer in range(2):
         for t in range(n):
             for which in (0, 1):
-                off = geom.token_offset(int(table[t // 16]), layer, which, t % 16) // 4
-                want.update(range(off, off + 8))
+                for head in range(2):
+                    off = geom.head_offset(int(table[t // 16]), layer, which, head, t % 16, 16) // 4
+                    want.update(range(off, off + 4))
     # code 0 (t=0, layer=0, first element of K) is a legitimate zero
     assert set(touched.tolist()) <= want and len(want) - len(touched) <= 2
 
