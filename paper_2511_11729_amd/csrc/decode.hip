@@ -200,7 +200,7 @@ __global__ void __launch_bounds__(KW * 64) k_skinny(SkinnyArgs a) {
       } else {
         const int n = a.kv_len[jb];
         const int lp = n / a.geom.page_tokens, slot = n - lp * a.geom.page_tokens;
-        const int page = (lp < a.max_pages) ? a.page_table[(size_t)jb * a.max_pages + lp] : -1;
+        const int page = (n >= 0 && lp < a.max_pages) ? a.page_table[(size_t)jb * a.max_pages + lp] : -1;
         if (page < 0 || page >= a.geom.n_pages_total) {
           if (g == 0) atomicOr(a.err_flag, 1);
           continue;

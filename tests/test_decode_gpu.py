@@ -1,0 +1,139 @@
+"""GPU parity of harli_decode_step against the CPU oracle (through the C ABI).
+
+Bar: page-table / block indexing bit-exact (the set of slab elements the step changes is
+exactly the oracle's); fp outputs max-abs error <= 2e-2 * max|ref| and relative Frobenius
+error <= 5e-3 for bf16 storage with fp32 accumulation.
+"""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from tests.gpu_util import DecodeCase, assert_close
+
+pytestmark = pytest.mark.gpu
+
+
+def variant(idx, **kw):
+    w = wl.workload(idx)
+    return w, dataclasses.replace(w.model, **kw)
+
+
+def run_case(w, m, lengths, **kw):
+    case = DecodeCase(w, m, np.asarray(lengths, np.int32), **kw)
+    y = case.run_gpu()
+    ref = case.run_oracle()
+    stats = assert_close(y, ref, "decode output")
+    n = case.check_cache()
+    assert n == len(lengths) * m.n_layers * 2 * m.n_kv * m.head_dim
+    return case, stats
+
+
+def test_tiny_bf16_config0_shapes():
+    """Config 0's shapes (hidden 256, 4 x 64 heads, ffn 688 = 43 tiles, ragged) stored as bf16."""
+    w, m = variant(0, dtype="bf16")
+    run_case(w, m, wl.draw_lengths(w), block_bytes=64 << 10)
+
+
+@pytest.mark.parametrize("lengths", [
+    [0], [0, 1, 15, 16, 17], [255, 256, 257, 511, 512], [700, 3, 1300], [31] * 16, [40] * 17, list(range(5, 105, 3)),
+])
+def test_tiny_edge_lengths_and_batches(lengths):
+    """Empty cache, page boundaries (15/16/17), chunk boundaries (255/256/257), ragged mixes,
+    batch 16/17 (one and two MFMA column tiles) and 34 (three)."""
+    w, m = variant(0, dtype="bf16")
+    run_case(w, m, lengths, block_bytes=64 << 10)
+
+
+def test_batch_above_64_runs_in_passes():
+    w, m = variant(0, dtype="bf16")
+    run_case(w, m, [7 + (i * 5) % 90 for i in range(100)], block_bytes=64 << 10)
+
+
+@pytest.mark.parametrize("n_q,n_kv,d", [(8, 2, 64), (8, 8, 128), (8, 4, 128), (8, 2, 128), (8, 1, 128)])
+def test_head_layouts(n_q, n_kv, d):
+    """GQA ratios 1, 2, 4, 8 and both head sizes."""
+    w, m = variant(0, dtype="bf16", hidden=n_q * d // 2, n_q=n_q, n_kv=n_kv, head_dim=d, ffn=320)
+    run_case(w, m, [0, 37, 300, 16], block_bytes=256 << 10)
+
+
+def test_non_dividing_page_size():
+    """Pages that do not divide the block (3 per 64 KiB block with slack), several chunks."""
+    w, m = variant(0, dtype="bf16", hidden=640, n_q=5, n_kv=5, head_dim=128, ffn=256)
+    case, _ = run_case(w, m, [100, 33, 250], block_bytes=64 << 10)
+    assert case.geom.pages_per_block == 3 and case.pool.stats().kv_chunks > 3
+
+
+def test_three_layer_model_with_embedding_and_logits():
+    w, m = variant(0, dtype="bf16", n_layers=3, vocab=1000)
+    lengths = [12, 200, 0, 77]
+    case = DecodeCase(w, m, np.asarray(lengths, np.int32), full_model=True, block_bytes=64 << 10)
+    tok = wl.make_token_ids(dataclasses.replace(w, model=m), (4,))
+    hid = case.run_gpu(token_ids=tok)
+    ref_hid, ref_logits, ref_next = case.run_oracle(token_ids=tok)
+    assert_close(hid, ref_hid, "hidden state")
+    logits = case.logits_dev.cpu().numpy()
+    assert_close(logits, ref_logits, "logits")
+    case.check_cache()
+    nxt = case.next_dev.cpu().numpy()
+    # argmax is exact on the GPU's own logits (ties to the lowest index) ...
+    assert np.array_equal(nxt, np.argmax(logits, axis=-1))
+    # ... and equals the oracle's wherever the oracle's top-2 gap exceeds the tolerance
+    srt = np.sort(ref_logits, axis=-1)
+    clear = (srt[:, -1] - srt[:, -2]) > 4e-2 * np.max(np.abs(ref_logits))
+    assert np.array_equal(nxt[clear], ref_next[clear])
+
+
+def test_argmax_ties_go_to_the_lowest_index():
+    w, m = variant(0, dtype="bf16", n_layers=1, vocab=64)
+    case = DecodeCase(w, m, np.asarray([3, 9], np.int32), full_model=True, block_bytes=64 << 10)
+    # identical rows in the output layer give exactly equal logits
+    case.extras_np["wlm"][5] = case.extras_np["wlm"][40]
+    from tests.gpu_util import to_dev
+    case.wlm_dev.copy_(to_dev(case.extras_np["wlm"], "bf16"))
+    case.run_gpu(token_ids=[1, 2])
+    logits = case.logits_dev.cpu().numpy()
+    assert np.array_equal(logits[:, 5], logits[:, 40])
+    assert np.array_equal(case.next_dev.cpu().numpy(), np.argmax(logits, axis=-1))
+
+
+def test_out_of_range_page_id_is_reported_not_dereferenced():
+    from paper_2511_11729_amd import binding as hb
+    w, m = variant(0, dtype="bf16")
+    case = DecodeCase(w, m, np.asarray([20, 40], np.int32), block_bytes=64 << 10)
+    case.table_dev[1, 1] = 10_000_000
+    with pytest.raises(hb.HarliError) as e:
+        case.run_gpu()
+    assert "page id" in str(e.value)
+    case.table_dev[1, 1] = int(case.table[1, 1])
+    case.run_gpu()                                   # the flag was cleared; a clean step passes
+
+
+def test_config1_full_size_layer():
+    """The 7B-class layer at its real shape: batch 8, lengths uniform in [256, 2048]."""
+    w = wl.workload(1)
+    case, stats = run_case(w, w.model, wl.draw_lengths(w))
+    print("config 1 decode parity: max-abs ratio %.2e, rel-Fro %.2e" % stats)
+
+
+def test_two_steps_in_a_row_use_the_appended_token():
+    """Step t+1 attends to the K/V that step t appended (same context, same pages)."""
+    w, m = variant(0, dtype="bf16")
+    lengths = np.asarray([14, 30, 250], np.int32)
+    case = DecodeCase(w, m, lengths, block_bytes=64 << 10)
+    y1 = case.run_gpu()
+    ref1 = case.run_oracle()
+    assert_close(y1, ref1, "step 1")
+    # second step: feed y1 back in as the next input on both sides
+    case.x_dev.copy_(torch.from_numpy(ref1.astype(np.float32)))
+    case.kv_len_dev += 1
+    case.ctx.decode_step(batch=3, kv_len=case.kv_len_dev, page_table=case.table_dev, max_pages=case.max_pages,
+                         max_kv_len=int(lengths.max()) + 2, x_in=case.x_dev, x_out=case.y_dev)
+    torch.cuda.synchronize()
+    case.ctx.check()
+    from oracle import harli_oracle as O
+    from tests.gpu_util import shapes_of
+    ref2 = O.decode_model_paged(ref1.astype(np.float32), case.layers_np, None, shapes_of(m), case.okv, lengths + 1, case.table)
+    assert_close(case.y_dev.cpu().numpy(), ref2, "step 2")

@@ -20,6 +20,7 @@ from typing import Dict, Tuple
 import numpy as np
 
 LORA_TARGETS = ("q", "k", "v", "o", "gate", "up", "down")
+WEIGHT_NAME = dict(q="wq", k="wk", v="wv", o="wo", gate="wg", up="wu", down="wd")
 
 # random streams (second term of the seed)
 S_WEIGHTS, S_ADAPTERS, S_INPUTS, S_TARGETS, S_LENGTHS, S_PAGES, S_ARRIVALS, S_KV = range(8)
@@ -164,7 +165,7 @@ def make_layer_weights(w: Workload, layer: int = 0, model: ModelCfg | None = Non
     rng = rng_for(w.idx, S_WEIGHTS, layer)
     out = {}
     for p in LORA_TARGETS:
-        out["w" + p] = _store(_normal(rng, m.proj_shape(p), 0.02), m.dtype)
+        out[WEIGHT_NAME[p]] = _store(_normal(rng, m.proj_shape(p), 0.02), m.dtype)
     out["g1"] = (1.0 + _normal(rng, (m.hidden,), 0.02)).astype(np.float32)
     out["g2"] = (1.0 + _normal(rng, (m.hidden,), 0.02)).astype(np.float32)
     return out
