@@ -20,6 +20,7 @@ constexpr int kTargets = 7;  // q,k,v,o,gate,up,down
 struct LayerDev {
   const void* w[kTargets];   // wq wk wv wo wg wu wd, [out,in]
   void* wt[kTargets];        // library-owned transposes [in,out] for the backward pass (after lora_attach)
+  void* wp[kTargets];        // decode-private pre-shuffled copies: [0] = q,k,v stacked, [3] o, [4] gate, [5] up, [6] down
   const float *g1, *g2;
   void* A[kTargets];         // borrowed adapter pointers (NULL when not adapted)
   void* B[kTargets];
@@ -32,6 +33,7 @@ struct DecodeWs {
   float *qbuf = nullptr, *x1 = nullptr, *xa = nullptr, *xb = nullptr;    // fp32
   float* ssq = nullptr;       // [2*L+1][bpad]
   float* rope = nullptr;      // [bpad][d/2][2]
+  double* inv_freq = nullptr; // [d/2] base^(-2i/d)
   float* att_part = nullptr;  // [bpad][n_q][max_chunks][d+2]
   int* att_cnt = nullptr;     // [bpad][n_kv]
   float* scores = nullptr;    // fp32 path only: [bpad][n_q][max_seq_len]
@@ -50,6 +52,7 @@ struct harli_ctx {
   const void* emb = nullptr;
   const float* g_final = nullptr;
   const void* w_lm = nullptr;
+  void* wlm_p = nullptr;     // pre-shuffled output layer
   harli::DecodeWs dw;
   // LoRA / finetune state
   bool lora_attached = false;
@@ -60,6 +63,8 @@ struct harli_ctx {
 };
 
 namespace harli {
+size_t packed_weight_elems(int N, int K);
+harli_status pack_weight(const void* src, void* dst, int N, int K, int row_tile0, hipStream_t st);
 // element size of the storage dtype
 inline size_t esize(const harli_ctx* c) { return c->cfg.dtype == HARLI_BF16 ? 2 : 4; }
 inline void proj_shape(const harli_model_cfg& m, int t, int* out, int* in) {

@@ -1,6 +1,8 @@
 // Model context: shapes, borrowed weight pointers and the library-owned device workspace.
 #include "ctx.h"
 
+#include <cmath>
+
 using namespace harli;
 
 namespace harli {
@@ -83,6 +85,7 @@ extern "C" harli_status harli_ctx_create(const harli_model_cfg* cfg, const harli
     for (int t = 0; t < kTargets; ++t) {
       d.w[t] = ws[t];
       d.wt[t] = nullptr;
+      d.wp[t] = nullptr;
       d.A[t] = d.B[t] = nullptr;
     }
     d.g1 = lw.g1;
@@ -101,7 +104,7 @@ extern "C" harli_status harli_ctx_create(const harli_model_cfg* cfg, const harli
 
   DecodeWs& d = c->dw;
   d.bpad = (m.max_batch + 15) / 16 * 16;
-  d.max_chunks = (m.max_seq_len + 255) / 256;
+  d.max_chunks = (m.max_seq_len + 127) / 128;  // the smallest attention chunk is 128 tokens
   const size_t bp = d.bpad;
   TRY(dev_alloc(&d.hx1, bp * m.hidden * 4, true));
   TRY(dev_alloc(&d.obuf, bp * QD * 4, true));
@@ -113,11 +116,45 @@ extern "C" harli_status harli_ctx_create(const harli_model_cfg* cfg, const harli
   TRY(dev_alloc(&d.xb, bp * m.hidden * 4, true));
   TRY(dev_alloc(&d.ssq, bp * (2 * m.n_layers + 1) * 4, true));
   TRY(dev_alloc(&d.rope, bp * m.head_dim * 4, true));
+  {
+    TRY(dev_alloc(&d.inv_freq, (m.head_dim / 2) * sizeof(double), false));
+    std::vector<double> f(m.head_dim / 2);
+    for (int i = 0; i < m.head_dim / 2; ++i) f[i] = std::pow((double)m.rope_base, -2.0 * i / (double)m.head_dim);
+    if (hipMemcpy(d.inv_freq, f.data(), f.size() * sizeof(double), hipMemcpyHostToDevice) != hipSuccess) {
+      harli_ctx_destroy(c);
+      return fail(HARLI_ERR_HIP, "ctx_create: copying the rotary table failed");
+    }
+  }
   TRY(dev_alloc(&d.att_part, bp * m.n_q_heads * d.max_chunks * (m.head_dim + 2) * 4, true));
   TRY(dev_alloc(&d.att_cnt, bp * m.n_kv_heads * 4, true));
   TRY(dev_alloc(&d.err_flag, 16, true));
   // fp32 path: scratch for attention scores, one row of max_seq_len per (sequence, query head)
   if (m.dtype == HARLI_F32) TRY(dev_alloc(&d.scores, bp * m.n_q_heads * (size_t)m.max_seq_len * 4, true));
+  // decode-private pre-shuffled weights (bf16 path): the inference instance keeps its own copy
+  if (m.dtype == HARLI_BF16) {
+    const int KVD = m.n_kv_heads * m.head_dim;
+    for (int l = 0; l < m.n_layers; ++l) {
+      LayerDev& ld = c->layers[l];
+      TRY(dev_alloc(&ld.wp[0], packed_weight_elems(QD + 2 * KVD, m.hidden) * 2, false));
+      TRY(pack_weight(ld.w[0], ld.wp[0], QD, m.hidden, 0, nullptr));
+      TRY(pack_weight(ld.w[1], ld.wp[0], KVD, m.hidden, QD / 16, nullptr));
+      TRY(pack_weight(ld.w[2], ld.wp[0], KVD, m.hidden, (QD + KVD) / 16, nullptr));
+      for (int t = 3; t < kTargets; ++t) {
+        int o, i;
+        proj_shape(m, t, &o, &i);
+        TRY(dev_alloc(&ld.wp[t], packed_weight_elems(o, i) * 2, false));
+        TRY(pack_weight(ld.w[t], ld.wp[t], o, i, 0, nullptr));
+      }
+    }
+    if (c->w_lm) {
+      TRY(dev_alloc(&c->wlm_p, packed_weight_elems(m.vocab, m.hidden) * 2, false));
+      TRY(pack_weight(c->w_lm, c->wlm_p, m.vocab, m.hidden, 0, nullptr));
+    }
+    if (hipDeviceSynchronize() != hipSuccess) {
+      harli_ctx_destroy(c);
+      return fail(HARLI_ERR_HIP, "ctx_create: pre-shuffling the weights failed");
+    }
+  }
   *out = c;
   return HARLI_OK;
 }
@@ -125,9 +162,13 @@ extern "C" harli_status harli_ctx_create(const harli_model_cfg* cfg, const harli
 extern "C" void harli_ctx_destroy(harli_ctx* c) {
   if (!c) return;
   DecodeWs& d = c->dw;
-  void* bufs[] = {d.hx1, d.obuf, d.hx2, d.mbuf, d.qbuf, d.x1, d.xa, d.xb, d.ssq, d.rope, d.att_part, d.att_cnt, d.err_flag, d.scores};
+  void* bufs[] = {d.hx1, d.obuf, d.hx2, d.mbuf, d.qbuf, d.x1, d.xa, d.xb, d.ssq, d.rope, d.att_part, d.att_cnt, d.err_flag, d.scores, d.inv_freq};
   for (void* p : bufs)
     if (p) (void)hipFree(p);
+  for (LayerDev& ld : c->layers)
+    for (int t = 0; t < kTargets; ++t)
+      if (ld.wp[t]) (void)hipFree(ld.wp[t]);
+  if (c->wlm_p) (void)hipFree(c->wlm_p);
   free_finetune_state(c);
   delete c;
 }

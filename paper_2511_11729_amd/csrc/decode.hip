@@ -1,11 +1,12 @@
 // Decode step for gfx950 (Harli Sec. 2.1: one new token per sequence per step,
 // reusing the KV cache; Sec. 2.2.1: the step is bound by DRAM bandwidth -- its
 // GEMMs have M = batch -- so every kernel here is built around streaming the
-// weights and the paged KV cache from HBM exactly once).
+// weights and the paged KV cache from HBM exactly once, in 1 KiB contiguous
+// wavefront loads).
 //
 // Per layer, bf16 storage:
 //   skinny<QKV>     h W{q,k,v}^T, x rho, rotary embedding, q -> workspace, k/v -> KV pages
-//   paged_attn      split-KV attention over the page table + last-arriver merge
+//   paged_attn      split-KV attention over the page table (+ a small merge launch)
 //   skinny<RESID>   x1 = x + o Wo^T, next operand bf16(x1*g2), sum x1^2
 //   skinny<GATEUP>  m = silu(rho h2 Wg^T) * (rho h2 Wu^T)
 //   skinny<RESID>   y = x1 + m Wd^T, operand and sum of squares for the next layer
@@ -14,8 +15,14 @@
 //
 // The skinny GEMM keeps the batch (<= 64 rows per pass) as the MFMA "column"
 // operand and streams 16-row weight tiles as the "row" operand of
-// v_mfma_f32_16x16x32_bf16; the K range is split over the waves of a
-// workgroup and reduced through LDS, so epilogues see complete sums.
+// v_mfma_f32_16x16x32_bf16.  Both operands are stored in MFMA fragment order
+// (the decode instance keeps a pre-shuffled private copy of the frozen weights,
+// as the paper's inference instance keeps its own copy, Sec. 7): a 16 x 32 tile
+// is 64 lanes x 16 bytes, contiguous, so a wavefront load is one 1 KiB burst and
+// needs no LDS staging.  Address-scattered 16-byte loads (16 rows per
+// instruction) were measured at 3.6 TB/s against 5.0 TB/s for this layout.
+// A workgroup is TW tiles x KW waves; the KW waves split K and reduce through
+// LDS, so epilogues see complete sums.
 #include "ctx.h"
 #include "device_utils.h"
 
@@ -23,16 +30,21 @@ using namespace harli;
 
 namespace {
 
-constexpr int kChunkTokens = 256;  // tokens per attention workgroup
 constexpr int kPageTokens = 16;
 
 enum { MODE_QKV = 0, MODE_RESID = 1, MODE_GATEUP = 2, MODE_LM = 3 };
 
+// Element (jb, k) of an x operand with `steps` = ceil(K/32) k-steps, fragment order:
+// [batch tile][k-step][lane = (k%32)/8*16 + jb%16][8].
+__device__ __forceinline__ size_t xfrag_off(int jb, int k, int steps) {
+  return ((((size_t)(jb >> 4) * steps + (k >> 5)) * 64) + ((k >> 3) & 3) * 16 + (jb & 15)) * 8 + (k & 7);
+}
+
 struct SkinnyArgs {
-  const unsigned short* x;  // [rows][K] bf16 operand; row jb is batch entry jb
+  const unsigned short* x;  // fragment-order operand
   int B, b0, K;             // batch size, first batch row of this pass, contraction length
-  int n_rows;               // output rows per weight matrix (tail masking)
-  const unsigned short *w0, *w1, *w2;
+  int n_rows;               // output rows (tail masking of stores)
+  const unsigned short *w0, *w1;  // pre-shuffled weights
   const float* ssq_in;      // sum of squares of the operand's source row (rho), or null
   float eps, inv_dim;
   // QKV
@@ -48,144 +60,162 @@ struct SkinnyArgs {
   const float* res;
   float* out;
   const float* gnext;
-  unsigned short* hxn;
+  unsigned short* hxn;  // next operand (fragment order, K = n_rows) or null
   float* ssq_out;
   // GATEUP
-  unsigned short* mbuf;
+  unsigned short* mbuf;  // next operand (fragment order, K = n_rows)
   // LM
   float* logits;
 };
 
-template <int MODE>
-struct ModeTraits {
-  static constexpr int RT = (MODE == MODE_RESID) ? 1 : 2;
-};
-
 __device__ __forceinline__ uint4 ld16(const unsigned short* p) { return *reinterpret_cast<const uint4*>(p); }
 
-template <int MODE, int NB, int KW, int U>
-__global__ void __launch_bounds__(KW * 64) k_skinny(SkinnyArgs a) {
-  constexpr int RT = ModeTraits<MODE>::RT;
+template <int MODE, int NB, int TW, int KW, int U>
+__global__ void __launch_bounds__(TW * KW * 64) k_skinny(SkinnyArgs a) {
+  constexpr int WAVES = TW * KW;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int i16 = lane & 15, g = lane >> 4;
+  const int t_w = wave / KW, ks = wave - t_w * KW;
   const int wg = blockIdx.x;
+  const int steps = (a.K + 31) >> 5;
 
-  // ---- which weight rows this workgroup owns --------------------------------------
-  const unsigned short* wrow[RT];
-  int row0[RT];
-  int which = 0, hl = 0, pidx = 0;  // QKV bookkeeping
+  // ---- which 16-row weight tile this wave streams -----------------------------------
+  int which = 0, hl = 0, pidx = 0;  // QKV bookkeeping (uniform over the workgroup)
+  int row0[TW];                     // first output row of each tile of the workgroup
+  const unsigned short* wt;
   if (MODE == MODE_QKV) {
     const int half = a.d >> 1, pph = half >> 4;
-    int head = wg / pph;
+    const int head = wg / pph;
     pidx = wg - head * pph;
-    const unsigned short* W;
     if (head < a.n_q) {
-      which = 0; hl = head; W = a.w0;
+      which = 0; hl = head;
     } else if (head < a.n_q + a.n_kv) {
-      which = 1; hl = head - a.n_q; W = a.w1;
+      which = 1; hl = head - a.n_q;
     } else {
-      which = 2; hl = head - a.n_q - a.n_kv; W = a.w2;
+      which = 2; hl = head - a.n_q - a.n_kv;
     }
 #pragma unroll
-    for (int t = 0; t < RT; ++t) {
-      row0[t] = hl * a.d + t * half + pidx * 16;
-      wrow[t] = W + (size_t)(row0[t] + i16) * a.K;
-    }
+    for (int t = 0; t < TW; ++t) row0[t] = hl * a.d + t * half + pidx * 16;
+    // q, k and v are packed as one matrix with heads in the order q.., k.., v..
+    const int rt = (head * a.d + t_w * half + pidx * 16) >> 4;
+    wt = a.w0 + ((size_t)rt * steps * 64 + lane) * 8;
   } else if (MODE == MODE_GATEUP) {
-    row0[0] = wg * 16;
-    int r = min(row0[0] + i16, a.n_rows - 1);
-    wrow[0] = a.w0 + (size_t)r * a.K;
-    if (RT > 1) {
-      row0[RT - 1] = wg * 16;
-      wrow[RT - 1] = a.w1 + (size_t)r * a.K;
-    }
+#pragma unroll
+    for (int t = 0; t < TW; ++t) row0[t] = wg * 16;
+    wt = (t_w == 0 ? a.w0 : a.w1) + ((size_t)wg * steps * 64 + lane) * 8;
   } else {
 #pragma unroll
-    for (int t = 0; t < RT; ++t) {
-      row0[t] = (wg * RT + t) * 16;
-      int r = min(row0[t] + i16, a.n_rows - 1);
-      wrow[t] = a.w0 + (size_t)r * a.K;
+    for (int t = 0; t < TW; ++t) row0[t] = (wg * TW + t) * 16;
+    wt = a.w0 + ((size_t)(wg * TW + t_w) * steps * 64 + lane) * 8;
+  }
+  const bool tile_ok = row0[t_w < TW ? t_w : 0] < a.n_rows || MODE == MODE_QKV;
+
+  const unsigned short* xf0[NB];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) xf0[nb] = a.x + (((size_t)((a.b0 >> 4) + nb) * steps) * 64 + lane) * 8;
+
+  f32x4 acc[NB];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) acc[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  // ---- epilogue operands are fetched now, so that the epilogue issues no dependent load ----
+  const bool epi = wave < NB;  // wave nb finishes batch tile nb
+  const int jb = a.b0 + wave * 16 + i16;
+  const bool active = epi && jb < a.B;
+  float pre_ssq = 1.f;
+  float2 pre_cs[4];
+  float4 pre_res = make_float4(0.f, 0.f, 0.f, 0.f), pre_g = make_float4(0.f, 0.f, 0.f, 0.f);
+  int pre_page = -1, pre_slot = 0;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) pre_cs[e] = make_float2(1.f, 0.f);
+  if (active) {
+    if (MODE != MODE_RESID) pre_ssq = a.ssq_in[jb];
+    if (MODE == MODE_QKV) {
+      if (which != 2) {
+        const float* cs = a.rope + ((size_t)jb * (a.d >> 1) + pidx * 16 + 4 * g) * 2;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) pre_cs[e] = make_float2(cs[2 * e], cs[2 * e + 1]);
+      }
+      if (which != 0) {
+        const int n = a.kv_len[jb];
+        const int lp = n / a.geom.page_tokens;
+        pre_slot = n - lp * a.geom.page_tokens;
+        pre_page = (n >= 0 && lp < a.max_pages)
+                       ? a.page_table[(size_t)jb * a.max_pages + lp]
+                       : -1;
+      }
+    }
+    if (MODE == MODE_RESID) {
+      const int n0 = row0[0] + 4 * g;
+      if (n0 < a.n_rows) {
+        pre_res = *reinterpret_cast<const float4*>(a.res + (size_t)jb * a.n_rows + n0);
+        if (a.hxn) pre_g = *reinterpret_cast<const float4*>(a.gnext + n0);
+      }
     }
   }
 
-  // ---- K range of this wave ----------------------------------------------------------
-  const int steps = (a.K + 31) >> 5;
-  const int s_begin = (int)(((long long)steps * wave) / KW), s_end = (int)(((long long)steps * (wave + 1)) / KW);
-
-  const unsigned short* xrow[NB];
-  bool xok[NB];
+  // ---- stream: each instruction below reads 1 KiB contiguous per wave ---------------------
+  const int s_begin = (int)(((long long)steps * ks) / KW), s_end = (int)(((long long)steps * (ks + 1)) / KW);
+  if (tile_ok) {
+    int s = s_begin;
+    for (; s + U <= s_end; s += U) {
+      uint4 wf[U], xf[U][NB];
 #pragma unroll
-  for (int nb = 0; nb < NB; ++nb) {
-    int jb = a.b0 + nb * 16 + i16;
-    xok[nb] = jb < a.B;
-    xrow[nb] = a.x + (size_t)(xok[nb] ? jb : a.b0) * a.K;
-  }
-
-  f32x4 acc[RT][NB];
+      for (int u = 0; u < U; ++u) {
+        wf[u] = ld16(wt + (size_t)(s + u) * 512);
 #pragma unroll
-  for (int t = 0; t < RT; ++t)
+        for (int nb = 0; nb < NB; ++nb) xf[u][nb] = ld16(xf0[nb] + (size_t)(s + u) * 512);
+      }
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) acc[t][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-  const uint4 zero4 = make_uint4(0, 0, 0, 0);
-  for (int s = s_begin; s < s_end; s += U) {
-    uint4 wf[U][RT], xf[U][NB];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int k = ((s + u) << 5) + g * 8;
-      const bool ok = (s + u < s_end) && (k < a.K);
-#pragma unroll
-      for (int t = 0; t < RT; ++t) wf[u][t] = ok ? ld16(wrow[t] + k) : zero4;
-#pragma unroll
-      for (int nb = 0; nb < NB; ++nb) xf[u][nb] = (ok && xok[nb]) ? ld16(xrow[nb] + k) : zero4;
-    }
-#pragma unroll
-    for (int u = 0; u < U; ++u)
-#pragma unroll
-      for (int t = 0; t < RT; ++t)
+      for (int u = 0; u < U; ++u)
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
-          acc[t][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wf[u][t]),
-                                                               __builtin_bit_cast(bf16x8, xf[u][nb]), acc[t][nb], 0, 0, 0);
+          acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wf[u]),
+                                                            __builtin_bit_cast(bf16x8, xf[u][nb]), acc[nb], 0, 0, 0);
+    }
+    for (; s < s_end; ++s) {
+      const uint4 wf = ld16(wt + (size_t)s * 512);
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb)
+        acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+            __builtin_bit_cast(bf16x8, wf), __builtin_bit_cast(bf16x8, ld16(xf0[nb] + (size_t)s * 512)), acc[nb], 0, 0, 0);
+    }
   }
 
   // ---- reduce the K split through LDS ---------------------------------------------------
-  __shared__ float4 red[KW][RT][NB][64];
+  __shared__ float4 red[TW][KW][NB][64];
 #pragma unroll
-  for (int t = 0; t < RT; ++t)
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb)
-      red[wave][t][nb][lane] = make_float4(acc[t][nb][0], acc[t][nb][1], acc[t][nb][2], acc[t][nb][3]);
+  for (int nb = 0; nb < NB; ++nb) red[t_w][ks][nb][lane] = make_float4(acc[nb][0], acc[nb][1], acc[nb][2], acc[nb][3]);
   __syncthreads();
 
-  for (int nb = wave; nb < NB; nb += KW) {
-    float v[RT][4];
+  static_assert(NB <= WAVES, "one epilogue wave per batch tile");
+  if (epi) {
+    const int nb = wave;
+    float v[TW][4];
 #pragma unroll
-    for (int t = 0; t < RT; ++t) {
-      float4 sacc = red[0][t][nb][lane];
+    for (int t = 0; t < TW; ++t) {
+      float4 sacc = red[t][0][nb][lane];
 #pragma unroll
       for (int w = 1; w < KW; ++w) {
-        float4 o = red[w][t][nb][lane];
+        const float4 o = red[t][w][nb][lane];
         sacc.x += o.x; sacc.y += o.y; sacc.z += o.z; sacc.w += o.w;
       }
       v[t][0] = sacc.x; v[t][1] = sacc.y; v[t][2] = sacc.z; v[t][3] = sacc.w;
     }
     // this lane holds output rows row0 + 4g + {0..3} of batch entry jb
-    const int jb = a.b0 + nb * 16 + i16;
-    const bool active = jb < a.B;
     float rho = 1.f;
-    if (MODE != MODE_RESID && active) rho = rsqrtf(a.ssq_in[jb] * a.inv_dim + a.eps);
+    if (MODE != MODE_RESID && active) rho = rsqrtf(pre_ssq * a.inv_dim + a.eps);
 
     if (MODE == MODE_QKV) {
-      if (!active) continue;
+      if (!active) return;
       const int half = a.d >> 1;
       const int idx0 = pidx * 16 + 4 * g;  // rotation index of v[.][0]
       float r0[4], r1[4];
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        float a0 = v[0][e] * rho, a1 = v[1][e] * rho;
+        const float a0 = v[0][e] * rho, a1 = v[TW - 1][e] * rho;
         if (which != 2) {
-          const float2 cs = *reinterpret_cast<const float2*>(a.rope + ((size_t)jb * half + idx0 + e) * 2);
+          const float2 cs = pre_cs[e];
           r0[e] = a0 * cs.x - a1 * cs.y;
           r1[e] = a1 * cs.x + a0 * cs.y;
         } else {
@@ -198,12 +228,10 @@ __global__ void __launch_bounds__(KW * 64) k_skinny(SkinnyArgs a) {
         *reinterpret_cast<float4*>(q) = make_float4(r0[0], r0[1], r0[2], r0[3]);
         *reinterpret_cast<float4*>(q + half) = make_float4(r1[0], r1[1], r1[2], r1[3]);
       } else {
-        const int n = a.kv_len[jb];
-        const int lp = n / a.geom.page_tokens, slot = n - lp * a.geom.page_tokens;
-        const int page = (n >= 0 && lp < a.max_pages) ? a.page_table[(size_t)jb * a.max_pages + lp] : -1;
+        const int page = pre_page, slot = pre_slot;
         if (page < 0 || page >= a.geom.n_pages_total) {
           if (g == 0) atomicOr(a.err_flag, 1);
-          continue;
+          return;
         }
         // inside a page the order is [kv head][token slot][head_dim]
         char* base = a.slab + kv_page_off(a.geom, page, a.layer, which - 1) +
@@ -214,38 +242,37 @@ __global__ void __launch_bounds__(KW * 64) k_skinny(SkinnyArgs a) {
       }
     } else if (MODE == MODE_RESID) {
       const int n0 = row0[0] + 4 * g;
+      const int steps_n = (a.n_rows + 31) >> 5;
       float s2 = 0.f;
-      if (active) {
-        float o[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          o[e] = 0.f;
-          if (n0 + e < a.n_rows) {
-            o[e] = a.res[(size_t)jb * a.n_rows + n0 + e] + v[0][e];
-            a.out[(size_t)jb * a.n_rows + n0 + e] = o[e];
-            if (a.hxn) a.hxn[(size_t)jb * a.n_rows + n0 + e] = f2bf(o[e] * a.gnext[n0 + e]);
-            s2 += o[e] * o[e];
-          }
+      if (active && n0 < a.n_rows) {  // n_rows is a multiple of 8, so the four rows are all in or all out
+        const float4 r = pre_res;
+        const float o0 = r.x + v[0][0], o1 = r.y + v[0][1], o2 = r.z + v[0][2], o3 = r.w + v[0][3];
+        *reinterpret_cast<float4*>(a.out + (size_t)jb * a.n_rows + n0) = make_float4(o0, o1, o2, o3);
+        if (a.hxn) {
+          const float4 gn = pre_g;
+          *reinterpret_cast<uint2*>(a.hxn + xfrag_off(jb, n0, steps_n)) =
+              make_uint2(pack_bf2(o0 * gn.x, o1 * gn.y), pack_bf2(o2 * gn.z, o3 * gn.w));
         }
+        s2 = o0 * o0 + o1 * o1 + o2 * o2 + o3 * o3;
       }
       s2 += __shfl_xor(s2, 16, 64);
       s2 += __shfl_xor(s2, 32, 64);
       if (active && g == 0 && a.ssq_out) atomicAdd(a.ssq_out + jb, s2);
     } else if (MODE == MODE_GATEUP) {
-      if (!active) continue;
       const int n0 = row0[0] + 4 * g;
+      if (!active || n0 >= a.n_rows) return;
+      const int steps_n = (a.n_rows + 31) >> 5;
+      float m[4];
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        if (n0 + e < a.n_rows) {
-          float ga = v[0][e] * rho, up = v[1][e] * rho;
-          float m = ga / (1.f + __expf(-ga)) * up;
-          a.mbuf[(size_t)jb * a.n_rows + n0 + e] = f2bf(m);
-        }
+        const float ga = v[0][e] * rho, up = v[TW - 1][e] * rho;
+        m[e] = ga / (1.f + __expf(-ga)) * up;
       }
+      *reinterpret_cast<uint2*>(a.mbuf + xfrag_off(jb, n0, steps_n)) = make_uint2(pack_bf2(m[0], m[1]), pack_bf2(m[2], m[3]));
     } else {  // MODE_LM
-      if (!active) continue;
+      if (!active) return;
 #pragma unroll
-      for (int t = 0; t < RT; ++t) {
+      for (int t = 0; t < TW; ++t) {
         const int n0 = row0[t] + 4 * g;
 #pragma unroll
         for (int e = 0; e < 4; ++e)
@@ -256,14 +283,33 @@ __global__ void __launch_bounds__(KW * 64) k_skinny(SkinnyArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------------
+// One-time pre-shuffle of a [N][K] weight matrix into fragment order: tile (rt, s) of 16 rows x
+// 32 k is 64 lanes x 8 elements, lane = row%16 + 16*((k%32)/8); rows >= N and k >= K are zero.
+// ---------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) k_pack_weight(const unsigned short* src, unsigned short* dst, int N, int K,
+                                                     int steps, long long n_frag) {
+  const long long f = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (f >= n_frag) return;
+  const int lane = (int)(f & 63);
+  const long long tile = f >> 6;
+  const int s = (int)(tile % steps), rt = (int)(tile / steps);
+  const int n = rt * 16 + (lane & 15), k = s * 32 + (lane >> 4) * 8;
+  uint4 v = make_uint4(0, 0, 0, 0);
+  if (n < N && k < K) v = *reinterpret_cast<const uint4*>(src + (size_t)n * K + k);  // K % 8 == 0
+  *reinterpret_cast<uint4*>(dst + f * 8) = v;
+}
+
+// ---------------------------------------------------------------------------------------------
 // Step preparation: operand and sum of squares of the first layer, rotary table, cleared
-// accumulators.  One workgroup per sequence.
+// accumulators.  One workgroup per sequence; loads are issued in groups of four 16-byte words
+// so that the kernel costs a couple of memory round trips, not one per element.
 // ---------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(256) k_decode_prep(int H, int d, int n_ssq, int bpad, const int* token_ids,
                                                      const unsigned short* emb, int vocab, const float* x_in, float* xa,
                                                      const float* g1, unsigned short* hx1, float* ssq, float* rope,
-                                                     const int* kv_len, float rope_base, int* err_flag) {
+                                                     const int* kv_len, const double* inv_freq, int* err_flag) {
   const int b = blockIdx.x, tid = threadIdx.x;
+  const int steps = (H + 31) >> 5;
   float s2 = 0.f;
   int tok = 0;
   if (token_ids) {
@@ -273,11 +319,22 @@ __global__ void __launch_bounds__(256) k_decode_prep(int H, int d, int n_ssq, in
       tok = 0;
     }
   }
-  for (int k = tid; k < H; k += 256) {
-    float v = token_ids ? bf2f(emb[(size_t)tok * H + k]) : x_in[(size_t)b * H + k];
-    if (token_ids) xa[(size_t)b * H + k] = v;
-    hx1[(size_t)b * H + k] = f2bf(v * g1[k]);
-    s2 += v * v;
+  const int n4 = H >> 2;  // H % 8 == 0
+#pragma unroll 4
+  for (int k4 = tid; k4 < n4; k4 += 256) {
+    float4 v;
+    if (token_ids) {
+      const uint2 e = *reinterpret_cast<const uint2*>(emb + (size_t)tok * H + k4 * 4);
+      v = make_float4(__uint_as_float(e.x << 16), __uint_as_float(e.x & 0xffff0000u), __uint_as_float(e.y << 16),
+                      __uint_as_float(e.y & 0xffff0000u));
+      *reinterpret_cast<float4*>(xa + (size_t)b * H + k4 * 4) = v;
+    } else {
+      v = *reinterpret_cast<const float4*>(x_in + (size_t)b * H + k4 * 4);
+    }
+    const float4 gg = *reinterpret_cast<const float4*>(g1 + k4 * 4);
+    *reinterpret_cast<uint2*>(hx1 + xfrag_off(b, k4 * 4, steps)) =
+        make_uint2(pack_bf2(v.x * gg.x, v.y * gg.y), pack_bf2(v.z * gg.z, v.w * gg.w));
+    s2 += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
   }
   __shared__ float sh[4];
   s2 = wave_sum(s2);
@@ -288,63 +345,79 @@ __global__ void __launch_bounds__(256) k_decode_prep(int H, int d, int n_ssq, in
   const int half = d >> 1;
   const double pos = (double)kv_len[b];
   for (int i = tid; i < half; i += 256) {
-    double theta = exp(-2.0 * (double)i / (double)d * log((double)rope_base));
-    double ang = pos * theta;
-    rope[((size_t)b * half + i) * 2 + 0] = (float)cos(ang);
-    rope[((size_t)b * half + i) * 2 + 1] = (float)sin(ang);
+    // angle = pos * base^(-2i/d) in double, reduced to [-pi, pi] before the fp32 sin/cos
+    const double ang = pos * inv_freq[i];
+    const double red = ang - 6.283185307179586476925 * rint(ang * 0.15915494309189533577);
+    float sn, cs;
+    sincosf((float)red, &sn, &cs);
+    rope[((size_t)b * half + i) * 2 + 0] = cs;
+    rope[((size_t)b * half + i) * 2 + 1] = sn;
   }
 }
 
 // ---------------------------------------------------------------------------------------------
 // Paged attention for one new token per sequence (the bs*seqlen term of the paper's Eq. 1).
-// Workgroup = (256-token chunk, KV head, sequence); each wave takes 4 pages of 16 tokens,
-// issues all its K and V loads up front (16 B per lane, a page of one head is 4 KiB
-// contiguous), takes the dot products on the vector ALUs with wavefront shuffles, and the
-// workgroup merges its waves in LDS.  Sequences longer than one chunk write
-// (max, sum, unnormalised output) partials; the last workgroup to arrive merges them.
+// Workgroup = (chunk of CH tokens, KV head, sequence); each of the 4 waves takes CH/64 pages of
+// 16 tokens, issues all its K and V loads up front (16 B per lane; a page of one head is 4 KiB
+// contiguous, a wave instruction reads 1 KiB of it), takes the dot products on the vector ALUs
+// with wavefront shuffles, and the workgroup merges its waves in LDS.  With more than one chunk
+// in the grid every workgroup writes a (max, sum, unnormalised output) partial that
+// k_attn_merge combines.
 // ---------------------------------------------------------------------------------------------
-template <int D, int G>
+template <int D, int G, int CH>
 __global__ void __launch_bounds__(256) k_paged_attn(const float* qbuf, const int* kv_len, const int* page_table,
                                                     int max_pages, int layer, int n_q, int n_kv, const char* slab,
-                                                    KvGeom geom, float* part, int* cnt, int max_chunks,
-                                                    unsigned short* obuf, int* err_flag) {
+                                                    KvGeom geom, float* part, int max_chunks, unsigned short* obuf,
+                                                    int* err_flag) {
   constexpr int LPT = D / 8;         // lanes per token
   constexpr int TPI = 64 / LPT;      // tokens per load instruction
   constexpr int IT = kPageTokens / TPI;
-  constexpr int PW = kChunkTokens / kPageTokens / 4;  // pages per wave
+  constexpr int PW = CH / kPageTokens / 4;  // pages per wave
   const int b = blockIdx.z, c = blockIdx.y, ch = blockIdx.x;
   const int n_tot = kv_len[b] + 1;
-  if (ch * kChunkTokens >= n_tot) return;
-  const int nch = (n_tot + kChunkTokens - 1) / kChunkTokens;
+  if (ch * CH >= n_tot) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int dg = lane % LPT, tl = lane / LPT;
   const int QD = n_q * D;
 
+  // Every load below is unconditional so that all of them are in flight together: page ids
+  // past the end of the sequence are replaced by the sequence's last page (valid memory), and
+  // what they return is discarded by the `ok` masks.
   uint4 kf[PW][IT], vf[PW][IT];
   bool ok[PW][IT];
+  int pg[PW];
+  const int last_lp = min((n_tot - 1) / kPageTokens, max_pages - 1);
 #pragma unroll
   for (int pp = 0; pp < PW; ++pp) {
-    const int lp = ch * (kChunkTokens / kPageTokens) + wave * PW + pp;
+    const int lp = ch * (CH / kPageTokens) + wave * PW + pp;
+    pg[pp] = page_table[(size_t)b * max_pages + min(lp, last_lp)];
+  }
+#pragma unroll
+  for (int pp = 0; pp < PW; ++pp) {
+    const int lp = ch * (CH / kPageTokens) + wave * PW + pp;
     const int tb = lp * kPageTokens;
-    int page = -1;
-    if (tb < n_tot && lp < max_pages) {
-      page = page_table[(size_t)b * max_pages + lp];
-      if (page < 0 || page >= geom.n_pages_total) {
-        if (lane == 0) atomicOr(err_flag, 1);
-        page = -1;
-      }
+    bool pgok = lp <= last_lp;
+    if (pg[pp] < 0 || pg[pp] >= geom.n_pages_total) {
+      if (pgok && lane == 0) atomicOr(err_flag, 1);
+      pg[pp] = 0;
+      pgok = false;
     }
-    const size_t offk = page >= 0 ? kv_page_off(geom, page, layer, 0) : 0;
-    const size_t offv = page >= 0 ? kv_page_off(geom, page, layer, 1) : 0;
+    const size_t offk = kv_page_off(geom, pg[pp], layer, 0);
+    const size_t offv = kv_page_off(geom, pg[pp], layer, 1);
 #pragma unroll
     for (int it = 0; it < IT; ++it) {
       const int slot = it * TPI + tl;
-      ok[pp][it] = page >= 0 && (tb + slot) < n_tot;
+      ok[pp][it] = pgok && (tb + slot) < n_tot;
       const size_t eo = ((size_t)(c * kPageTokens + slot) * D + dg * 8) * sizeof(unsigned short);
-      kf[pp][it] = ok[pp][it] ? *reinterpret_cast<const uint4*>(slab + offk + eo) : make_uint4(0, 0, 0, 0);
-      vf[pp][it] = ok[pp][it] ? *reinterpret_cast<const uint4*>(slab + offv + eo) : make_uint4(0, 0, 0, 0);
+      kf[pp][it] = *reinterpret_cast<const uint4*>(slab + offk + eo);
+      vf[pp][it] = *reinterpret_cast<const uint4*>(slab + offv + eo);
     }
   }
+#pragma unroll
+  for (int pp = 0; pp < PW; ++pp)
+#pragma unroll
+    for (int it = 0; it < IT; ++it)
+      if (!ok[pp][it]) kf[pp][it] = vf[pp][it] = make_uint4(0, 0, 0, 0);
 
   // scores in the log2 domain: s = q.k / sqrt(D) * log2(e)
   const float scale = 1.4426950408889634f * rsqrtf((float)D);
@@ -413,7 +486,6 @@ __global__ void __launch_bounds__(256) k_paged_attn(const float* qbuf, const int
   }
 
   __shared__ float s_m[4][G], s_l[4][G], s_o[4][G][D];
-  __shared__ int s_last;
   if (tl == 0) {
 #pragma unroll
     for (int gq = 0; gq < G; ++gq) {
@@ -426,9 +498,10 @@ __global__ void __launch_bounds__(256) k_paged_attn(const float* qbuf, const int
     }
   }
   __syncthreads();
+  const int steps_o = (QD + 31) >> 5;
   for (int idx = tid; idx < G * D; idx += 256) {
     const int gq = idx / D, e = idx - gq * D;
-    float M = fmaxf(fmaxf(s_m[0][gq], s_m[1][gq]), fmaxf(s_m[2][gq], s_m[3][gq]));
+    const float M = fmaxf(fmaxf(s_m[0][gq], s_m[1][gq]), fmaxf(s_m[2][gq], s_m[3][gq]));
     float L = 0.f, o = 0.f;
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
@@ -437,8 +510,8 @@ __global__ void __launch_bounds__(256) k_paged_attn(const float* qbuf, const int
       o += s_o[w][gq][e] * f;
     }
     const int head = c * G + gq;
-    if (nch == 1) {
-      obuf[(size_t)b * QD + head * D + e] = f2bf(o / L);
+    if (gridDim.x == 1) {
+      obuf[xfrag_off(b, head * D + e, steps_o)] = f2bf(o / L);
     } else {
       float* p = part + (((size_t)b * n_q + head) * max_chunks + ch) * (D + 2);
       p[2 + e] = o;
@@ -448,31 +521,47 @@ __global__ void __launch_bounds__(256) k_paged_attn(const float* qbuf, const int
       }
     }
   }
-  if (nch == 1) return;
-  __threadfence();
-  __syncthreads();
-  if (tid == 0) {
-    const int old = atomicAdd(cnt + b * n_kv + c, 1);
-    s_last = (old == nch - 1);
-  }
-  __syncthreads();
-  if (!s_last) return;
-  __threadfence();
-  for (int idx = tid; idx < G * D; idx += 256) {
-    const int gq = idx / D, e = idx - gq * D;
-    const int head = c * G + gq;
-    const float* p = part + (((size_t)b * n_q + head) * max_chunks) * (D + 2);
-    float M = -INFINITY;
-    for (int i = 0; i < nch; ++i) M = fmaxf(M, __builtin_nontemporal_load(p + (size_t)i * (D + 2)));
-    float L = 0.f, o = 0.f;
-    for (int i = 0; i < nch; ++i) {
-      const float f = exp2f(__builtin_nontemporal_load(p + (size_t)i * (D + 2)) - M);
-      L += __builtin_nontemporal_load(p + (size_t)i * (D + 2) + 1) * f;
-      o += __builtin_nontemporal_load(p + (size_t)i * (D + 2) + 2 + e) * f;
+}
+
+// Merge of the per-chunk partials: one workgroup per (query head, sequence).  A separate launch
+// rather than a last-arriver merge inside the attention kernel: a device-scope fence per
+// workgroup writes back and invalidates the whole L2 of its XCD on this chip and was measured
+// at ten times the cost of the attention itself.
+template <int D, int CH>
+__global__ void __launch_bounds__(D) k_attn_merge(const float* part, const int* kv_len, int n_q, int max_chunks,
+                                                  unsigned short* obuf) {
+  const int head = blockIdx.x, b = blockIdx.y, e = threadIdx.x;
+  const int n_tot = kv_len[b] + 1;
+  const int nch = min((n_tot + CH - 1) / CH, max_chunks);
+  if (nch < 1) return;
+  const float* p = part + (((size_t)b * n_q + head) * max_chunks) * (D + 2);
+  float M = -INFINITY, L = 0.f, o = 0.f;
+  for (int i0 = 0; i0 < nch; i0 += 8) {  // eight chunks per round trip
+    float m[8], l[8], v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const float* pi = p + (size_t)min(i0 + u, nch - 1) * (D + 2);
+      m[u] = pi[0];
+      l[u] = pi[1];
+      v[u] = pi[2 + e];
     }
-    obuf[(size_t)b * QD + head * D + e] = f2bf(o / L);
+    float Mn = M;
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if (i0 + u < nch) Mn = fmaxf(Mn, m[u]);
+    const float f0 = (M == -INFINITY) ? 0.f : exp2f(M - Mn);
+    L *= f0;
+    o *= f0;
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if (i0 + u < nch) {
+        const float f = exp2f(m[u] - Mn);
+        L += l[u] * f;
+        o += v[u] * f;
+      }
+    M = Mn;
   }
-  if (tid == 0) cnt[b * n_kv + c] = 0;  // ready for the next step
+  obuf[xfrag_off(b, head * D + e, (n_q * D + 31) >> 5)] = f2bf(o / L);
 }
 
 __global__ void __launch_bounds__(256) k_argmax(const float* logits, int V, int* next_token) {
@@ -503,35 +592,59 @@ __global__ void __launch_bounds__(256) k_argmax(const float* logits, int V, int*
   if (tid == 0) next_token[b] = si[0];
 }
 
-template <int MODE, int NB, int KW, int U>
+template <int MODE, int NB, int TW, int KW, int U>
 void launch_skinny(const SkinnyArgs& a, int n_wg, hipStream_t st) {
-  hipLaunchKernelGGL((k_skinny<MODE, NB, KW, U>), dim3(n_wg), dim3(KW * 64), 0, st, a);
+  hipLaunchKernelGGL((k_skinny<MODE, NB, TW, KW, U>), dim3(n_wg), dim3(TW * KW * 64), 0, st, a);
 }
 
-template <int MODE>
-void dispatch_skinny(SkinnyArgs a, int n_wg, int kw8, hipStream_t st) {
-  // passes of at most 64 batch rows; NB = 16-row tiles per pass
+// passes of at most 64 batch rows; NB = 16-row batch tiles per pass
+template <int MODE, int TW, int KW>
+void dispatch_skinny(SkinnyArgs a, int n_wg, hipStream_t st) {
   for (int b0 = 0; b0 < a.B; b0 += 64) {
     a.b0 = b0;
     const int nb = (min(a.B - b0, 64) + 15) / 16;
-    if (nb == 1) {
-      if (kw8)
-        launch_skinny<MODE, 1, 8, 8>(a, n_wg, st);
-      else
-        launch_skinny<MODE, 1, 4, 4>(a, n_wg, st);
-    } else if (nb == 2) {
-      launch_skinny<MODE, 2, 4, 4>(a, n_wg, st);
-    } else {
-      launch_skinny<MODE, 4, 4, 2>(a, n_wg, st);
-    }
+    if (nb == 1)
+      launch_skinny<MODE, 1, TW, KW, 8>(a, n_wg, st);
+    else if (nb == 2)
+      launch_skinny<MODE, 2, TW, KW, 4>(a, n_wg, st);
+    else
+      launch_skinny<MODE, 4, TW, KW, 2>(a, n_wg, st);
   }
+}
+
+template <int D, int G, int CH>
+void launch_attn(harli_ctx* c, const harli_decode_batch* b, int layer, hipStream_t st) {
+  DecodeWs& w = c->dw;
+  const harli_model_cfg& m = c->cfg;
+  const int n_chunks = (b->max_kv_len + CH - 1) / CH;
+  hipLaunchKernelGGL((k_paged_attn<D, G, CH>), dim3(n_chunks, m.n_kv_heads, b->batch), dim3(256), 0, st, w.qbuf,
+                     b->kv_len, b->page_table, b->max_pages, layer, m.n_q_heads, m.n_kv_heads, c->slab, c->geom,
+                     w.att_part, w.max_chunks, static_cast<unsigned short*>(w.obuf), w.err_flag);
+  if (n_chunks > 1)
+    hipLaunchKernelGGL((k_attn_merge<D, CH>), dim3(m.n_q_heads, b->batch), dim3(D), 0, st, w.att_part, b->kv_len,
+                       m.n_q_heads, w.max_chunks, static_cast<unsigned short*>(w.obuf));
 }
 
 }  // namespace
 
 namespace harli {
+
 harli_status decode_step_f32(harli_ctx* c, const harli_decode_batch* b, hipStream_t st);  // decode_generic.hip
+
+size_t packed_weight_elems(int N, int K) { return (size_t)((N + 15) / 16) * ((K + 31) / 32) * 512; }
+
+// dst must hold packed_weight_elems(N, K) bf16; rows [row_tile0*16, ...) of the packed matrix are written
+harli_status pack_weight(const void* src, void* dst, int N, int K, int row_tile0, hipStream_t st) {
+  const int steps = (K + 31) / 32;
+  const long long n_frag = (long long)((N + 15) / 16) * steps * 64;
+  unsigned short* d = static_cast<unsigned short*>(dst) + (size_t)row_tile0 * steps * 512;
+  hipLaunchKernelGGL(k_pack_weight, dim3((unsigned)((n_frag + 255) / 256)), dim3(256), 0, st,
+                     static_cast<const unsigned short*>(src), d, N, K, steps, n_frag);
+  HARLI_HIP(hipGetLastError());
+  return HARLI_OK;
 }
+
+}  // namespace harli
 
 extern "C" harli_status harli_decode_step(harli_ctx* c, const harli_decode_batch* b, void* hip_stream) {
   if (!c || !b) return fail(HARLI_ERR_INVALID, "decode_step: null argument");
@@ -544,9 +657,8 @@ extern "C" harli_status harli_decode_step(harli_ctx* c, const harli_decode_batch
   if ((b->logits || b->next_token) && (!c->w_lm || !c->g_final))
     return fail(HARLI_ERR_INVALID, "decode_step: logits need g_final and w_lm");
   if (b->next_token && !b->logits) return fail(HARLI_ERR_INVALID, "decode_step: next_token needs a logits buffer");
-  if (b->max_kv_len < 1 || b->max_kv_len > c->dw.max_chunks * kChunkTokens)
-    return fail(HARLI_ERR_INVALID, "decode_step: max_kv_len %d outside 1..%d", b->max_kv_len,
-                c->dw.max_chunks * kChunkTokens);
+  if (b->max_kv_len < 1 || b->max_kv_len > m.max_seq_len)
+    return fail(HARLI_ERR_INVALID, "decode_step: max_kv_len %d outside 1..%d", b->max_kv_len, m.max_seq_len);
   if ((long long)b->max_pages * c->geom.page_tokens < b->max_kv_len)
     return fail(HARLI_ERR_INVALID, "decode_step: page table rows of %d pages cannot hold %d tokens", b->max_pages,
                 b->max_kv_len);
@@ -558,11 +670,10 @@ extern "C" harli_status harli_decode_step(harli_ctx* c, const harli_decode_batch
   const int n_ssq = 2 * L + 1;
   hipLaunchKernelGGL(k_decode_prep, dim3(B), dim3(256), 0, st, H, d, n_ssq, w.bpad, b->token_ids,
                      static_cast<const unsigned short*>(c->emb), m.vocab, b->x_in, w.xa, c->layers[0].g1,
-                     static_cast<unsigned short*>(w.hx1), w.ssq, w.rope, b->kv_len, m.rope_base, w.err_flag);
+                     static_cast<unsigned short*>(w.hx1), w.ssq, w.rope, b->kv_len, w.inv_freq, w.err_flag);
 
   const float* xcur = b->token_ids ? w.xa : b->x_in;
-  float* ping[2] = {w.xb, w.xa};  // layer l writes ping[l&1]; layer 0 may not overwrite xa (it can be the input)
-  const int n_chunks = (b->max_kv_len + kChunkTokens - 1) / kChunkTokens;
+  float* ping[2] = {w.xb, w.xa};  // layer l writes ping[l&1]; layer 0 must not overwrite xa (it can be its input)
   const int G = m.n_q_heads / m.n_kv_heads;
 
   for (int l = 0; l < L; ++l) {
@@ -576,9 +687,7 @@ extern "C" harli_status harli_decode_step(harli_ctx* c, const harli_decode_batch
     a.x = static_cast<const unsigned short*>(w.hx1);
     a.K = H;
     a.n_rows = QD;
-    a.w0 = static_cast<const unsigned short*>(lw.w[0]);
-    a.w1 = static_cast<const unsigned short*>(lw.w[1]);
-    a.w2 = static_cast<const unsigned short*>(lw.w[2]);
+    a.w0 = static_cast<const unsigned short*>(lw.wp[0]);
     a.ssq_in = w.ssq + (size_t)(2 * l) * w.bpad;
     a.qbuf = w.qbuf;
     a.rope = w.rope;
@@ -591,57 +700,49 @@ extern "C" harli_status harli_decode_step(harli_ctx* c, const harli_decode_batch
     a.d = d;
     a.slab = c->slab;
     a.geom = c->geom;
-    dispatch_skinny<MODE_QKV>(a, (m.n_q_heads + 2 * m.n_kv_heads) * (d / 32), 0, st);
+    dispatch_skinny<MODE_QKV, 2, 2>(a, (m.n_q_heads + 2 * m.n_kv_heads) * (d / 32), st);
     // --- attention
-    {
-      dim3 grid(n_chunks, m.n_kv_heads, B);
-#define HARLI_ATTN(DD, GG)                                                                                         \
-  hipLaunchKernelGGL((k_paged_attn<DD, GG>), grid, dim3(256), 0, st, w.qbuf, b->kv_len, b->page_table, b->max_pages, \
-                     l, m.n_q_heads, m.n_kv_heads, c->slab, c->geom, w.att_part, w.att_cnt, w.max_chunks,             \
-                     static_cast<unsigned short*>(w.obuf), w.err_flag)
-      if (d == 128 && G == 1) HARLI_ATTN(128, 1);
-      else if (d == 128 && G == 2) HARLI_ATTN(128, 2);
-      else if (d == 128 && G == 4) HARLI_ATTN(128, 4);
-      else if (d == 128 && G == 8) HARLI_ATTN(128, 8);
-      else if (d == 64 && G == 1) HARLI_ATTN(64, 1);
-      else if (d == 64 && G == 2) HARLI_ATTN(64, 2);
-      else if (d == 64 && G == 4) HARLI_ATTN(64, 4);
-      else return fail(HARLI_ERR_INVALID, "decode_step: head_dim %d with group %d is not supported", d, G);
-#undef HARLI_ATTN
-    }
+    if (d == 128 && G == 1) launch_attn<128, 1, 256>(c, b, l, st);
+    else if (d == 128 && G == 2) launch_attn<128, 2, 256>(c, b, l, st);
+    else if (d == 128 && G == 4) launch_attn<128, 4, 128>(c, b, l, st);
+    else if (d == 128 && G == 8) launch_attn<128, 8, 128>(c, b, l, st);
+    else if (d == 64 && G == 1) launch_attn<64, 1, 256>(c, b, l, st);
+    else if (d == 64 && G == 2) launch_attn<64, 2, 256>(c, b, l, st);
+    else if (d == 64 && G == 4) launch_attn<64, 4, 256>(c, b, l, st);
+    else return fail(HARLI_ERR_INVALID, "decode_step: head_dim %d with group %d is not supported", d, G);
     // --- output projection + residual, operand of the FFN
     a.x = static_cast<const unsigned short*>(w.obuf);
     a.K = QD;
     a.n_rows = H;
-    a.w0 = static_cast<const unsigned short*>(lw.w[3]);
+    a.w0 = static_cast<const unsigned short*>(lw.wp[3]);
     a.res = xcur;
     a.out = w.x1;
     a.gnext = lw.g2;
     a.hxn = static_cast<unsigned short*>(w.hx2);
     a.ssq_out = w.ssq + (size_t)(2 * l + 1) * w.bpad;
-    dispatch_skinny<MODE_RESID>(a, (H + 15) / 16, 1, st);
+    dispatch_skinny<MODE_RESID, 1, 8>(a, (H + 15) / 16, st);
     // --- gate/up + SwiGLU
     a.x = static_cast<const unsigned short*>(w.hx2);
     a.K = H;
     a.n_rows = F;
-    a.w0 = static_cast<const unsigned short*>(lw.w[4]);
-    a.w1 = static_cast<const unsigned short*>(lw.w[5]);
+    a.w0 = static_cast<const unsigned short*>(lw.wp[4]);
+    a.w1 = static_cast<const unsigned short*>(lw.wp[5]);
     a.ssq_in = w.ssq + (size_t)(2 * l + 1) * w.bpad;
     a.mbuf = static_cast<unsigned short*>(w.mbuf);
-    dispatch_skinny<MODE_GATEUP>(a, (F + 15) / 16, 0, st);
+    dispatch_skinny<MODE_GATEUP, 2, 4>(a, (F + 15) / 16, st);
     // --- down projection + residual, operand of the next layer (or of the output layer)
     const bool last = (l == L - 1);
     float* xnext = (last && b->x_out) ? b->x_out : ping[l & 1];
     a.x = static_cast<const unsigned short*>(w.mbuf);
     a.K = F;
     a.n_rows = H;
-    a.w0 = static_cast<const unsigned short*>(lw.w[6]);
+    a.w0 = static_cast<const unsigned short*>(lw.wp[6]);
     a.res = w.x1;
     a.out = xnext;
     a.gnext = last ? c->g_final : c->layers[l + 1].g1;
     a.hxn = (last && !b->logits) ? nullptr : static_cast<unsigned short*>(w.hx1);
     a.ssq_out = w.ssq + (size_t)(2 * l + 2) * w.bpad;
-    dispatch_skinny<MODE_RESID>(a, (H + 15) / 16, 1, st);
+    dispatch_skinny<MODE_RESID, 1, 8>(a, (H + 15) / 16, st);
     xcur = xnext;
   }
   if (b->logits) {
@@ -652,10 +753,10 @@ extern "C" harli_status harli_decode_step(harli_ctx* c, const harli_decode_batch
     a.x = static_cast<const unsigned short*>(w.hx1);
     a.K = H;
     a.n_rows = m.vocab;
-    a.w0 = static_cast<const unsigned short*>(c->w_lm);
+    a.w0 = static_cast<const unsigned short*>(c->wlm_p);
     a.ssq_in = w.ssq + (size_t)(2 * L) * w.bpad;
     a.logits = b->logits;
-    dispatch_skinny<MODE_LM>(a, (m.vocab + 31) / 32, 0, st);
+    dispatch_skinny<MODE_LM, 2, 4>(a, (m.vocab + 31) / 32, st);
     if (b->next_token) hipLaunchKernelGGL(k_argmax, dim3(B), dim3(256), 0, st, b->logits, m.vocab, b->next_token);
   }
   HARLI_HIP(hipGetLastError());

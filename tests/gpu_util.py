@@ -51,7 +51,7 @@ class DecodeCase:
     """One decode step on both sides.  `model` may differ from the workload's (shape variants)."""
 
     def __init__(self, w: wl.Workload, model: wl.ModelCfg, lengths, *, full_model=False, block_bytes=2 << 20,
-                 small_pool_bytes=0, extra_chunks=1, max_batch=None, reserve=0):
+                 small_pool_bytes=0, extra_chunks=1, max_batch=None, reserve=0, tweak=None):
         self.w, self.m = w, model
         m = model
         self.B = B = len(lengths)
@@ -59,6 +59,8 @@ class DecodeCase:
         eb = m.elem_bytes
         self.layers_np = [wl.make_layer_weights(w, l, m) for l in range(m.n_layers)]
         self.extras_np = wl.make_model_extras(w, m) if full_model else None
+        if tweak is not None:
+            tweak(self)          # edit the host-side weights before the context reads them
         self.x_np, self.kv_len, self.kv_np = wl.make_decode_inputs(w, B, m, lengths)
         P = 16
         n_pages = [(int(n) + 1 + P - 1) // P for n in self.kv_len]

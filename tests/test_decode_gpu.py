@@ -88,11 +88,9 @@ def test_three_layer_model_with_embedding_and_logits():
 
 def test_argmax_ties_go_to_the_lowest_index():
     w, m = variant(0, dtype="bf16", n_layers=1, vocab=64)
-    case = DecodeCase(w, m, np.asarray([3, 9], np.int32), full_model=True, block_bytes=64 << 10)
-    # identical rows in the output layer give exactly equal logits
-    case.extras_np["wlm"][5] = case.extras_np["wlm"][40]
-    from tests.gpu_util import to_dev
-    case.wlm_dev.copy_(to_dev(case.extras_np["wlm"], "bf16"))
+    def same_rows(case):             # identical rows in the output layer give exactly equal logits
+        case.extras_np["wlm"][5] = case.extras_np["wlm"][40]
+    case = DecodeCase(w, m, np.asarray([3, 9], np.int32), full_model=True, block_bytes=64 << 10, tweak=same_rows)
     case.run_gpu(token_ids=[1, 2])
     logits = case.logits_dev.cpu().numpy()
     assert np.array_equal(logits[:, 5], logits[:, 40])
