@@ -176,7 +176,8 @@ typedef struct {
 } harli_lora_cfg;
 
 /* A, B: host arrays of n_layers*7 device pointers indexed [layer*7 + t], t = 0..6
- * for q,k,v,o,gate,up,down (entries of non-adapted projections are ignored).
+ * for q,k,v,o,gate,up,down (entries of non-adapted projections are ignored);
+ * rank must be 8, 16, 32 or 64.
  * Borrowed; the caller may update their contents between calls (optimizer step).
  * Also builds library-owned transposed copies of the frozen weights that the
  * backward pass streams (dx = dy W needs W with `in` as the slow axis). */
@@ -213,7 +214,10 @@ typedef struct harli_saved harli_saved;
  * the B_f sequences of S tokens (positions 0..S-1).  X, Y: device [B_f*S, hidden]
  * fp32.  The activations the backward pass needs are placed in buffers taken
  * from the pool (TENSOR/SMALL classes) and returned in *saved; X itself is
- * copied.  HARLI_ERR_OOM leaves nothing allocated. */
+ * borrowed and must stay valid and unchanged until the matching harli_lora_bwd
+ * or harli_saved_release.  HARLI_ERR_OOM leaves nothing allocated.  S must be a
+ * multiple of 8; the first call of a (B_f, S) shape grows a library-owned
+ * device workspace (hipMalloc). */
 harli_status harli_lora_fwd(harli_ctx* c, int32_t layer, const float* X, float* Y, int32_t B_f, int32_t S,
                             harli_saved** saved, void* hip_stream);
 

@@ -1,0 +1,27 @@
+/*
+ * harli_debug.h -- test hooks of libharli.  NOT part of the stable ABI: they expose single
+ * kernels so that the GPU tests can check them in isolation.
+ */
+#ifndef HARLI_DEBUG_H
+#define HARLI_DEBUG_H
+
+#include "harli.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* C = alpha * (A1 . B1^T + A2 . B2^T) (+ res), the finetune unit's bf16 MFMA GEMM.
+ * A1 [M, K1], B1 [N, K1], optional A2 [M, K2], B2 [N, K2] (K2 = 0: absent): device 16-bit
+ * (half = 1: IEEE half, 0: bfloat16; the 16-bit outputs use the same type), row-major, contraction index contiguous.  Any of the outputs may be NULL: Cb bf16 [M, N],
+ * Cf fp32 [M, N] (with optional fp32 residual res [M, N]), Ct bf16 [N, M].
+ * causal: 0 full, 1 lower output tiles only, 2 upper output tiles only, 3 K loop up to the
+ * tile's last row, 4 K loop from the tile's first row (see the kernel for the exact meaning). */
+harli_status harli_dbg_gemm(const void* A1, const void* B1, int32_t K1, const void* A2, const void* B2, int32_t K2,
+                            int32_t M, int32_t N, float alpha, int32_t causal, int32_t half, void* Cb, float* Cf,
+                            const float* res, void* Ct, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HARLI_DEBUG_H */

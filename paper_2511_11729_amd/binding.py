@@ -95,6 +95,8 @@ _SIGS = {
                                  C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_void_p]),
     "harli_saved_release": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
     "harli_saved_bytes": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_size_t)]),
+    "harli_dbg_gemm": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
+                                 C.c_float, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
 }
 
 
@@ -272,3 +274,13 @@ class Context:
         n = C.c_size_t()
         _check(lib().harli_saved_bytes(self.handle, B_f, S, C.byref(n)))
         return n.value
+
+
+def dbg_gemm(A1, B1, *, A2=None, B2=None, alpha=1.0, causal=0, half=False, Cb=None, Cf=None, res=None, Ct=None,
+             stream=None) -> None:
+    """Test hook: C = alpha * (A1 B1^T + A2 B2^T) (+ res) on the finetune unit's bf16 MFMA GEMM."""
+    M, K1 = A1.shape
+    N = B1.shape[0]
+    K2 = A2.shape[1] if A2 is not None else 0
+    _check(lib().harli_dbg_gemm(_ptr(A1), _ptr(B1), K1, _ptr(A2), _ptr(B2), K2, M, N, alpha, causal, int(half), _ptr(Cb), _ptr(Cf),
+                                _ptr(res), _ptr(Ct), _stream(stream)))

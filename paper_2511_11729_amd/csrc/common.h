@@ -14,6 +14,7 @@ harli_status fail(harli_status s, const char* fmt, ...) __attribute__((format(pr
 // Returns 1 when the event has completed, 0 when it is still pending, -1 on error.
 // Provided by the HIP side of the library (or a stub in host-only test builds).
 int event_done(void* hip_event);
+void event_destroy(void* hip_event);
 
 // Geometry of the KV grid, handed to the decode kernels by value.
 struct KvGeom {

@@ -20,6 +20,7 @@ constexpr int kTargets = 7;  // q,k,v,o,gate,up,down
 struct LayerDev {
   const void* w[kTargets];   // wq wk wv wo wg wu wd, [out,in]
   void* wt[kTargets];        // library-owned transposes [in,out] for the backward pass (after lora_attach)
+  void* w16[kTargets];       // library-owned [out,in] copies in the finetune compute element (after lora_attach)
   void* wp[kTargets];        // decode-private pre-shuffled copies: [0] = q,k,v stacked, [3] o, [4] gate, [5] up, [6] down
   const float *g1, *g2;
   void* A[kTargets];         // borrowed adapter pointers (NULL when not adapted)

@@ -15,6 +15,8 @@ int event_done(void* hip_event) {
   return -1;
 }
 
+void event_destroy(void* hip_event) { (void)hipEventDestroy(static_cast<hipEvent_t>(hip_event)); }
+
 template <typename T>
 static harli_status dev_alloc(T** p, size_t bytes, bool zero) {
   HARLI_HIP(hipMalloc(reinterpret_cast<void**>(p), bytes ? bytes : 16));
@@ -86,6 +88,7 @@ extern "C" harli_status harli_ctx_create(const harli_model_cfg* cfg, const harli
       d.w[t] = ws[t];
       d.wt[t] = nullptr;
       d.wp[t] = nullptr;
+      d.w16[t] = nullptr;
       d.A[t] = d.B[t] = nullptr;
     }
     d.g1 = lw.g1;

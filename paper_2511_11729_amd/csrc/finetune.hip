@@ -1,21 +1,623 @@
-// LoRA finetune unit (placeholder until the MFMA kernels land).
+// LoRA finetune unit: one transformer layer x one micro-batch, forward and backward
+// (Harli Sec. 6.1 scheduling unit; Sec. 2.1: base parameters frozen, only the adapters get
+// gradients; Sec. 4: the activations kept for backward live in the unified pool).
+//
+// Forward  y = x W^T + s (x A) B  rides on one GEMM per projection: the adapter is a second K
+// segment [s x A | B^T] of the base GEMM.  Backward needs no weight gradients for the frozen
+// base: dx = dy W + (s dy B^T) A^T is again one multi-segment GEMM against a library-owned
+// transposed copy of W, and dA = x^T (s dy B^T), dB = (s x A)^T dy are skinny reductions over
+// the tokens.  Attention runs as batched GEMMs with causal tile skipping around element-wise
+// softmax / dS kernels.
+#include <algorithm>
+#include <cmath>
+#include <vector>
+
 #include "ctx.h"
+#include "ft_elem.h"
+#include "ft_kernels.h"
+#include "gemm.h"
+
 using namespace harli;
+
 namespace harli {
-void free_finetune_state(harli_ctx*) {}
+harli_status pool_free_owned(harli_pool* p, const harli_alloc* a, void* event);  // pool.cpp
 }
-extern "C" harli_status harli_lora_attach(harli_ctx*, const harli_lora_cfg*, void* const*, void* const*) {
-  return fail(HARLI_ERR_STATE, "lora_attach: not implemented yet");
+
+struct harli_saved {
+  int layer = 0, Bf = 0, S = 0, T = 0;
+  const float* X = nullptr;  // borrowed from the caller
+  harli_alloc big{};
+  std::vector<harli_alloc> small;
+  float *rho1 = nullptr, *rho2 = nullptr, *lse = nullptr, *x1 = nullptr;
+  bf *h = nullptr, *q = nullptr, *k = nullptr, *v = nullptr, *P = nullptr, *o = nullptr, *h2 = nullptr, *a = nullptr,
+     *u = nullptr, *m = nullptr;
+  bf* us[kTargets] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+};
+
+namespace {
+
+inline size_t al(size_t n) { return (n + 255) & ~size_t(255); }
+
+// workspace carved from one device allocation
+struct FtWs {
+  size_t bytes = 0;
+  char* base = nullptr;
+  float *scores = nullptr, *dP = nullptr, *ST = nullptr, *dPT = nullptr, *delta = nullptr, *dm = nullptr, *dh2 = nullptr,
+        *dx1 = nullptr, *dh = nullptr;
+  bf *vT = nullptr, *At = nullptr, *Bt = nullptr, *dyb = nullptr, *da = nullptr, *du = nullptr, *dx1b = nullptr, *dob = nullptr,
+     *doT = nullptr, *dS = nullptr, *PT = nullptr, *dST = nullptr, *qT = nullptr, *kT = nullptr, *dq = nullptr, *dkq = nullptr,
+     *dvq = nullptr, *dk = nullptr, *dv = nullptr, *gs = nullptr, *An = nullptr, *Bn = nullptr;
+  float* scale = nullptr;  // [0] sigma, [1] 1/sigma, [2] scratch: gradient scaling of the backward pass
+  int Bf = 0, S = 0;
+};
+
+struct FtState {
+  FtWs ws;
+};
+
+FtState* state(harli_ctx* c) { return static_cast<FtState*>(c->ft_ws); }
+
+struct Dims {
+  int T, H, QD, KVD, F, d, nq, nkv, G, r, Z;
+};
+
+Dims dims(const harli_ctx* c, int Bf, int S) {
+  const harli_model_cfg& m = c->cfg;
+  Dims D;
+  D.T = Bf * S;
+  D.H = m.hidden;
+  D.d = m.head_dim;
+  D.nq = m.n_q_heads;
+  D.nkv = m.n_kv_heads;
+  D.QD = D.nq * D.d;
+  D.KVD = D.nkv * D.d;
+  D.F = m.ffn;
+  D.G = D.nq / D.nkv;
+  D.r = c->lora.rank;
+  D.Z = Bf * D.nq;
+  return D;
 }
-extern "C" harli_status harli_lora_fwd(harli_ctx*, int32_t, const float*, float*, int32_t, int32_t, harli_saved**, void*) {
-  return fail(HARLI_ERR_STATE, "lora_fwd: not implemented yet");
+
+harli_status ensure_ws(harli_ctx* c, int Bf, int S) {
+  FtWs& w = state(c)->ws;
+  const Dims D = dims(c, Bf, S);
+  const size_t T = D.T, ZSS = (size_t)D.Z * S * S;
+  const size_t maxdim = std::max(std::max((size_t)D.H, (size_t)D.QD), (size_t)D.F);
+  size_t off = 0;
+  auto take = [&](size_t n) {
+    size_t o = off;
+    off += al(n);
+    return o;
+  };
+  const size_t o_scores = take(ZSS * 4), o_dP = take(ZSS * 4), o_ST = take(ZSS * 4), o_dPT = take(ZSS * 4);
+  const size_t o_dS = take(ZSS * 2), o_PT = take(ZSS * 2), o_dST = take(ZSS * 2);
+  const size_t o_delta = take((size_t)D.Z * S * 4);
+  const size_t o_dm = take(T * D.F * 4), o_dh2 = take(T * D.H * 4), o_dx1 = take(T * D.H * 4), o_dh = take(T * D.H * 4);
+  const size_t o_vT = take(T * D.KVD * 2), o_kT = take(T * D.KVD * 2), o_qT = take(T * D.QD * 2), o_doT = take(T * D.QD * 2);
+  const size_t o_At = take(maxdim * D.r * 2), o_Bt = take(maxdim * D.r * 2);
+  const size_t o_An = take(maxdim * D.r * 2), o_Bn = take(maxdim * D.r * 2), o_scale = take(64);
+  const size_t o_dyb = take(T * D.H * 2), o_da = take(T * D.F * 2), o_du = take(T * D.F * 2), o_dx1b = take(T * D.H * 2);
+  const size_t o_dob = take(T * D.QD * 2), o_dq = take(T * D.QD * 2), o_dkq = take(T * D.QD * 2), o_dvq = take(T * D.QD * 2);
+  const size_t o_dk = take(T * D.KVD * 2), o_dv = take(T * D.KVD * 2), o_gs = take(T * D.r * 2);
+  if (off > w.bytes) {
+    if (w.base) HARLI_HIP(hipFree(w.base));
+    w.base = nullptr;
+    w.bytes = 0;
+    HARLI_HIP(hipMalloc(reinterpret_cast<void**>(&w.base), off));
+    w.bytes = off;
+  }
+  char* b = w.base;
+  w.scores = (float*)(b + o_scores); w.dP = (float*)(b + o_dP); w.ST = (float*)(b + o_ST); w.dPT = (float*)(b + o_dPT);
+  w.dS = (bf*)(b + o_dS); w.PT = (bf*)(b + o_PT); w.dST = (bf*)(b + o_dST); w.delta = (float*)(b + o_delta);
+  w.dm = (float*)(b + o_dm); w.dh2 = (float*)(b + o_dh2); w.dx1 = (float*)(b + o_dx1); w.dh = (float*)(b + o_dh);
+  w.vT = (bf*)(b + o_vT); w.kT = (bf*)(b + o_kT); w.qT = (bf*)(b + o_qT); w.doT = (bf*)(b + o_doT);
+  w.At = (bf*)(b + o_At); w.Bt = (bf*)(b + o_Bt); w.dyb = (bf*)(b + o_dyb); w.da = (bf*)(b + o_da); w.du = (bf*)(b + o_du);
+  w.dx1b = (bf*)(b + o_dx1b); w.dob = (bf*)(b + o_dob); w.dq = (bf*)(b + o_dq); w.dkq = (bf*)(b + o_dkq);
+  w.dvq = (bf*)(b + o_dvq); w.dk = (bf*)(b + o_dk); w.dv = (bf*)(b + o_dv); w.gs = (bf*)(b + o_gs);
+  w.An = (bf*)(b + o_An); w.Bn = (bf*)(b + o_Bn); w.scale = (float*)(b + o_scale);
+  w.Bf = Bf;
+  w.S = S;
+  return HARLI_OK;
 }
-extern "C" harli_status harli_lora_bwd(harli_ctx*, int32_t, const float*, float*, harli_saved*, float* const*, float* const*, void*) {
-  return fail(HARLI_ERR_STATE, "lora_bwd: not implemented yet");
+
+inline bool adapted(const harli_ctx* c, int t) { return (c->lora.targets >> t) & 1u; }
+inline float lscale(const harli_ctx* c) { return c->lora.alpha / (float)c->lora.rank; }
+
+GemmArgs plain_gemm(int M, int N) {
+  GemmArgs g{};
+  g.M = M;
+  g.N = N;
+  g.nb1 = g.nb2 = 1;
+  g.alpha = 1.f;
+  g.causal = GEMM_FULL;
+  g.half = kFtHalf ? 1 : 0;
+  return g;
 }
-extern "C" harli_status harli_saved_release(harli_ctx*, harli_saved*, void*) {
-  return fail(HARLI_ERR_STATE, "saved_release: not implemented yet");
+void add_seg(GemmArgs& g, const bf* A, long long lda, const bf* B, long long ldb, int K) {
+  GemmSeg& s = g.seg[g.nseg++];
+  s = GemmSeg{};
+  s.A = A;
+  s.B = B;
+  s.K = K;
+  s.lda = lda;
+  s.ldb = ldb;
 }
-extern "C" harli_status harli_saved_bytes(const harli_ctx*, int32_t, int32_t, size_t*) {
-  return fail(HARLI_ERR_STATE, "saved_bytes: not implemented yet");
+
+// forward of one projection: out = xin . W^T (+ us . Bt^T), us = s * xin . A kept for backward
+harli_status proj_fwd(harli_ctx* c, const LayerDev& L, int t, const bf* xin, int T, harli_saved* sv, GemmArgs& g, hipStream_t st) {
+  int out, in;
+  proj_shape(c->cfg, t, &out, &in);
+  FtWs& w = state(c)->ws;
+  add_seg(g, xin, in, static_cast<const bf*>(L.w16[t]), in, in);
+  if (adapted(c, t)) {
+    const int r = c->lora.rank;
+    ft_transpose_from_bf16(static_cast<const bf*>(L.A[t]), w.At, in, r, st);   // A [in, r] -> [r, in]
+    ft_skinny_nt(xin, in, w.At, in, sv->us[t], r, T, r, in, lscale(c), st);     // us = s * x . A
+    ft_transpose_from_bf16(static_cast<const bf*>(L.B[t]), w.Bt, r, out, st);  // B [r, out] -> [out, r]
+    add_seg(g, sv->us[t], r, w.Bt, r, r);
+  }
+  return gemm_launch(g, 1, st);
+}
+
+// adapter gradients of one projection given dy (bf16 [T, out]) and its input xin (bf16 [T, in]);
+// leaves gs = s * dy . B^T in ws.gs and A (compute element, [in, r]) in ws.An for the caller's dx GEMM
+harli_status proj_grads(harli_ctx* c, const LayerDev& L, int t, const bf* dy, const bf* xin, int T, const harli_saved* sv,
+                        float* const* dA, float* const* dB, hipStream_t st) {
+  int out, in;
+  proj_shape(c->cfg, t, &out, &in);
+  FtWs& w = state(c)->ws;
+  const int r = c->lora.rank;
+  ft_from_bf16(static_cast<const bf*>(L.B[t]), w.Bn, (long long)r * out, st);
+  ft_from_bf16(static_cast<const bf*>(L.A[t]), w.An, (long long)in * r, st);
+  ft_skinny_nt(dy, out, w.Bn, out, w.gs, r, T, r, out, lscale(c), st);        // gs = s * dy . B^T   (carries sigma)
+  ft_lora_grad(xin, in, w.gs, r, dA[t], r, 1, T, in, r, w.scale + 1, st);     // dA += x^T gs / sigma
+  ft_lora_grad(dy, out, sv->us[t], r, dB[t], 1, out, T, out, r, w.scale + 1, st);  // dB += us^T dy / sigma
+  return HARLI_OK;
+}
+
+harli_status check_call(harli_ctx* c, int layer, int Bf, int S, const char* who) {
+  if (!c) return fail(HARLI_ERR_INVALID, "%s: null context", who);
+  if (c->cfg.dtype != HARLI_BF16) return fail(HARLI_ERR_INVALID, "%s: the finetune unit is built for bf16 storage", who);
+  if (!c->lora_attached) return fail(HARLI_ERR_STATE, "%s: call harli_lora_attach first", who);
+  if (layer < 0 || layer >= c->cfg.n_layers) return fail(HARLI_ERR_INVALID, "%s: layer %d out of range", who, layer);
+  if (Bf < 1 || S < 1 || (long long)Bf * S > c->cfg.max_ft_tokens)
+    return fail(HARLI_ERR_INVALID, "%s: %d x %d tokens exceed max_ft_tokens %d", who, Bf, S, c->cfg.max_ft_tokens);
+  if (S % 8) return fail(HARLI_ERR_INVALID, "%s: sequence length must be a multiple of 8", who);
+  return HARLI_OK;
+}
+
+struct SavedPlan {
+  size_t big_bytes;
+  size_t o_x1, o_h, o_q, o_k, o_v, o_P, o_o, o_h2, o_a, o_u, o_m;
+};
+
+SavedPlan plan_saved(const harli_ctx* c, const Dims& D, int S) {
+  SavedPlan p{};
+  size_t off = 0;
+  auto take = [&](size_t n) {
+    size_t o = off;
+    off += al(n);
+    return o;
+  };
+  const size_t T = D.T;
+  p.o_x1 = take(T * D.H * 4);
+  p.o_h = take(T * D.H * 2);
+  p.o_q = take(T * D.QD * 2);
+  p.o_k = take(T * D.KVD * 2);
+  p.o_v = take(T * D.KVD * 2);
+  p.o_P = take((size_t)D.Z * S * S * 2);
+  p.o_o = take(T * D.QD * 2);
+  p.o_h2 = take(T * D.H * 2);
+  p.o_a = take(T * D.F * 2);
+  p.o_u = take(T * D.F * 2);
+  p.o_m = take(T * D.F * 2);
+  p.big_bytes = off;
+  return p;
+}
+
+void release_saved(harli_ctx* c, harli_saved* sv, hipStream_t st, bool with_event) {
+  auto rel = [&](const harli_alloc& a) {
+    void* ev = nullptr;
+    if (with_event) {
+      hipEvent_t e;
+      if (hipEventCreateWithFlags(&e, hipEventDisableTiming) == hipSuccess) {
+        if (hipEventRecord(e, st) == hipSuccess)
+          ev = e;
+        else
+          (void)hipEventDestroy(e);
+      }
+    }
+    (void)pool_free_owned(c->pool, &a, ev);
+  };
+  if (sv->big.ptr) rel(sv->big);
+  for (const harli_alloc& a : sv->small) rel(a);
+  delete sv;
+}
+
+}  // namespace
+
+namespace harli {
+void free_finetune_state(harli_ctx* c) {
+  for (LayerDev& L : c->layers)
+    for (int t = 0; t < kTargets; ++t)
+      if (L.wt[t]) {
+        (void)hipFree(L.wt[t]);
+        L.wt[t] = nullptr;
+        if (L.w16[t]) (void)hipFree(L.w16[t]);
+        L.w16[t] = nullptr;
+      }
+  if (c->ft_ws) {
+    FtState* s = state(c);
+    if (s->ws.base) (void)hipFree(s->ws.base);
+    delete s;
+    c->ft_ws = nullptr;
+  }
+}
+}  // namespace harli
+
+extern "C" harli_status harli_lora_attach(harli_ctx* c, const harli_lora_cfg* cfg, void* const* A, void* const* B) {
+  if (!c || !cfg || !A || !B) return fail(HARLI_ERR_INVALID, "lora_attach: null argument");
+  if (c->cfg.dtype != HARLI_BF16) return fail(HARLI_ERR_INVALID, "lora_attach: the finetune unit is built for bf16 storage");
+  if (cfg->rank != 8 && cfg->rank != 16 && cfg->rank != 32 && cfg->rank != 64)
+    return fail(HARLI_ERR_INVALID, "lora_attach: rank must be 8, 16, 32 or 64, got %d", cfg->rank);
+  if (cfg->targets == 0 || cfg->targets >= (1u << kTargets)) return fail(HARLI_ERR_INVALID, "lora_attach: bad target mask");
+  if (c->cfg.max_ft_tokens < 1) return fail(HARLI_ERR_STATE, "lora_attach: the context was created with max_ft_tokens = 0");
+  for (int l = 0; l < c->cfg.n_layers; ++l)
+    for (int t = 0; t < kTargets; ++t)
+      if (((cfg->targets >> t) & 1u) && (!A[l * kTargets + t] || !B[l * kTargets + t]))
+        return fail(HARLI_ERR_INVALID, "lora_attach: layer %d target %d has a null adapter", l, t);
+  c->lora = *cfg;
+  for (int l = 0; l < c->cfg.n_layers; ++l) {
+    LayerDev& L = c->layers[l];
+    for (int t = 0; t < kTargets; ++t) {
+      const bool on = (cfg->targets >> t) & 1u;
+      L.A[t] = on ? A[l * kTargets + t] : nullptr;
+      L.B[t] = on ? B[l * kTargets + t] : nullptr;
+      if (!L.wt[t]) {  // finetune-private copies of the frozen weights in the compute element:
+        int out, in;   // W [out, in] for the forward pass and WT [in, out] for dx = dy W
+        proj_shape(c->cfg, t, &out, &in);
+        HARLI_HIP(hipMalloc(&L.wt[t], (size_t)out * in * 2));
+        ft_transpose_from_bf16(static_cast<const bf*>(L.w[t]), static_cast<bf*>(L.wt[t]), out, in, nullptr);
+        HARLI_HIP(hipMalloc(&L.w16[t], (size_t)out * in * 2));
+        ft_from_bf16(static_cast<const bf*>(L.w[t]), static_cast<bf*>(L.w16[t]), (long long)out * in, nullptr);
+      }
+    }
+  }
+  HARLI_HIP(hipDeviceSynchronize());
+  if (!c->ft_ws) c->ft_ws = new FtState;
+  c->lora_attached = true;
+  return HARLI_OK;
+}
+
+extern "C" harli_status harli_saved_bytes(const harli_ctx* c, int32_t B_f, int32_t S, size_t* bytes) {
+  if (!c || !bytes || B_f < 1 || S < 1) return fail(HARLI_ERR_INVALID, "saved_bytes: bad argument");
+  if (!c->lora_attached) return fail(HARLI_ERR_STATE, "saved_bytes: call harli_lora_attach first");
+  const Dims D = dims(c, B_f, S);
+  size_t n = plan_saved(c, D, S).big_bytes;
+  n += 2 * (size_t)D.T * 4 + (size_t)D.Z * S * 4;
+  for (int t = 0; t < kTargets; ++t)
+    if (adapted(c, t)) n += (size_t)D.T * D.r * 2;
+  *bytes = n;
+  return HARLI_OK;
+}
+
+extern "C" harli_status harli_lora_fwd(harli_ctx* c, int32_t layer, const float* X, float* Y, int32_t B_f, int32_t S,
+                                       harli_saved** saved, void* hip_stream) {
+  harli_status s = check_call(c, layer, B_f, S, "lora_fwd");
+  if (s != HARLI_OK) return s;
+  if (!X || !Y || !saved) return fail(HARLI_ERR_INVALID, "lora_fwd: null argument");
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const harli_model_cfg& m = c->cfg;
+  const Dims D = dims(c, B_f, S);
+  const LayerDev& L = c->layers[layer];
+  s = ensure_ws(c, B_f, S);
+  if (s != HARLI_OK) return s;
+  FtWs& w = state(c)->ws;
+
+  // ---- activations kept for backward come from the unified pool ----
+  harli_saved* sv = new harli_saved;
+  sv->layer = layer;
+  sv->Bf = B_f;
+  sv->S = S;
+  sv->T = D.T;
+  sv->X = X;
+  const SavedPlan pl = plan_saved(c, D, S);
+  s = harli_pool_alloc(c->pool, HARLI_CLS_AUTO, pl.big_bytes, &sv->big);
+  if (s != HARLI_OK) {
+    delete sv;
+    return s;
+  }
+  auto small = [&](size_t n, void** p) -> harli_status {
+    harli_alloc a{};
+    harli_status r = harli_pool_alloc(c->pool, HARLI_CLS_AUTO, n, &a);
+    if (r != HARLI_OK) return r;
+    sv->small.push_back(a);
+    *p = a.ptr;
+    return HARLI_OK;
+  };
+  s = small((size_t)D.T * 4, reinterpret_cast<void**>(&sv->rho1));
+  if (s == HARLI_OK) s = small((size_t)D.T * 4, reinterpret_cast<void**>(&sv->rho2));
+  if (s == HARLI_OK) s = small((size_t)D.Z * S * 4, reinterpret_cast<void**>(&sv->lse));
+  for (int t = 0; t < kTargets && s == HARLI_OK; ++t)
+    if (adapted(c, t)) s = small((size_t)D.T * D.r * 2, reinterpret_cast<void**>(&sv->us[t]));
+  if (s != HARLI_OK) {
+    release_saved(c, sv, st, false);  // nothing was launched on these buffers
+    return s;
+  }
+  char* bb = static_cast<char*>(sv->big.ptr);
+  sv->x1 = (float*)(bb + pl.o_x1); sv->h = (bf*)(bb + pl.o_h); sv->q = (bf*)(bb + pl.o_q); sv->k = (bf*)(bb + pl.o_k);
+  sv->v = (bf*)(bb + pl.o_v); sv->P = (bf*)(bb + pl.o_P); sv->o = (bf*)(bb + pl.o_o); sv->h2 = (bf*)(bb + pl.o_h2);
+  sv->a = (bf*)(bb + pl.o_a); sv->u = (bf*)(bb + pl.o_u); sv->m = (bf*)(bb + pl.o_m);
+
+#define RUN(x)                          \
+  do {                                  \
+    harli_status r_ = (x);              \
+    if (r_ != HARLI_OK) {               \
+      release_saved(c, sv, st, true);   \
+      return r_;                        \
+    }                                   \
+  } while (0)
+
+  const int T = D.T;
+  ft_rmsnorm_fwd(X, L.g1, sv->h, sv->rho1, T, D.H, m.rms_eps, st);
+  {
+    GemmArgs g = plain_gemm(T, D.QD);
+    g.Cb = sv->q; g.ldcb = D.QD;
+    RUN(proj_fwd(c, L, 0, sv->h, T, sv, g, st));
+  }
+  {
+    GemmArgs g = plain_gemm(T, D.KVD);
+    g.Cb = sv->k; g.ldcb = D.KVD;
+    RUN(proj_fwd(c, L, 1, sv->h, T, sv, g, st));
+  }
+  {
+    GemmArgs g = plain_gemm(T, D.KVD);
+    g.Cb = sv->v; g.ldcb = D.KVD;
+    RUN(proj_fwd(c, L, 2, sv->h, T, sv, g, st));
+  }
+  ft_rope(sv->q, T, S, D.nq, D.d, c->dw.inv_freq, false, st);
+  ft_rope(sv->k, T, S, D.nkv, D.d, c->dw.inv_freq, false, st);
+  ft_transpose_heads(sv->v, w.vT, B_f, S, D.nkv, D.d, st);
+  const long long SS = (long long)S * S;
+  const int batches = B_f * D.nq;
+  {  // scores[z][q][k] = q . k / sqrt(d), lower triangle only
+    GemmArgs g = plain_gemm(S, S);
+    g.nb1 = D.nkv; g.nb2 = D.G;
+    g.alpha = 1.f / std::sqrt((float)D.d);
+    g.causal = GEMM_OUT_LOWER;
+    add_seg(g, sv->q, D.QD, sv->k, D.KVD, D.d);
+    g.seg[0].a_bs0 = (long long)S * D.QD; g.seg[0].a_bs1 = (long long)D.G * D.d; g.seg[0].a_bs2 = D.d;
+    g.seg[0].b_bs0 = (long long)S * D.KVD; g.seg[0].b_bs1 = D.d; g.seg[0].b_bs2 = 0;
+    g.Cf = w.scores; g.ldcf = S;
+    g.cf_bs0 = (long long)D.nq * SS; g.cf_bs1 = (long long)D.G * SS; g.cf_bs2 = SS;
+    RUN(gemm_launch(g, batches, st));
+  }
+  ft_softmax_causal(w.scores, sv->P, sv->lse, batches, S, st);
+  {  // o = P . V
+    GemmArgs g = plain_gemm(S, D.d);
+    g.nb1 = D.nkv; g.nb2 = D.G;
+    g.causal = GEMM_K_UPTO_M;
+    add_seg(g, sv->P, S, w.vT, S, S);
+    g.seg[0].a_bs0 = (long long)D.nq * SS; g.seg[0].a_bs1 = (long long)D.G * SS; g.seg[0].a_bs2 = SS;
+    g.seg[0].b_bs0 = (long long)D.KVD * S; g.seg[0].b_bs1 = (long long)D.d * S; g.seg[0].b_bs2 = 0;
+    g.Cb = sv->o; g.ldcb = D.QD;
+    g.cb_bs0 = (long long)S * D.QD; g.cb_bs1 = (long long)D.G * D.d; g.cb_bs2 = D.d;
+    RUN(gemm_launch(g, batches, st));
+  }
+  {  // x1 = X + o Wo^T
+    GemmArgs g = plain_gemm(T, D.H);
+    g.Cf = sv->x1; g.ldcf = D.H; g.res = X;
+    RUN(proj_fwd(c, L, 3, sv->o, T, sv, g, st));
+  }
+  ft_rmsnorm_fwd(sv->x1, L.g2, sv->h2, sv->rho2, T, D.H, m.rms_eps, st);
+  {
+    GemmArgs g = plain_gemm(T, D.F);
+    g.Cb = sv->a; g.ldcb = D.F;
+    RUN(proj_fwd(c, L, 4, sv->h2, T, sv, g, st));
+  }
+  {
+    GemmArgs g = plain_gemm(T, D.F);
+    g.Cb = sv->u; g.ldcb = D.F;
+    RUN(proj_fwd(c, L, 5, sv->h2, T, sv, g, st));
+  }
+  ft_silu_mul(sv->a, sv->u, sv->m, (long long)T * D.F, st);
+  {  // Y = x1 + m Wd^T
+    GemmArgs g = plain_gemm(T, D.H);
+    g.Cf = Y; g.ldcf = D.H; g.res = sv->x1;
+    RUN(proj_fwd(c, L, 6, sv->m, T, sv, g, st));
+  }
+  if (hipGetLastError() != hipSuccess) {
+    release_saved(c, sv, st, true);
+    return fail(HARLI_ERR_HIP, "lora_fwd: a kernel launch failed");
+  }
+  *saved = sv;
+  return HARLI_OK;
+}
+
+extern "C" harli_status harli_lora_bwd(harli_ctx* c, int32_t layer, const float* dY, float* dX, harli_saved* sv,
+                                       float* const* dA, float* const* dB, void* hip_stream) {
+  if (!sv) return fail(HARLI_ERR_INVALID, "lora_bwd: null saved record");
+  harli_status s = check_call(c, layer, sv->Bf, sv->S, "lora_bwd");
+  if (s != HARLI_OK) return s;
+  if (!dY || !dX || !dA || !dB) return fail(HARLI_ERR_INVALID, "lora_bwd: null argument");
+  if (sv->layer != layer) return fail(HARLI_ERR_INVALID, "lora_bwd: saved record belongs to layer %d", sv->layer);
+  for (int t = 0; t < kTargets; ++t)
+    if (adapted(c, t) && (!dA[t] || !dB[t])) return fail(HARLI_ERR_INVALID, "lora_bwd: null gradient buffer for target %d", t);
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const int B_f = sv->Bf, S = sv->S;
+  const Dims D = dims(c, B_f, S);
+  const LayerDev& L = c->layers[layer];
+  s = ensure_ws(c, B_f, S);
+  if (s != HARLI_OK) return s;
+  FtWs& w = state(c)->ws;
+  const int T = D.T;
+  const long long SS = (long long)S * S;
+  const int batches = B_f * D.nq;
+  const float scale = 1.f / std::sqrt((float)D.d);
+
+#define RUNB(x)                         \
+  do {                                  \
+    harli_status r_ = (x);              \
+    if (r_ != HARLI_OK) return r_;      \
+  } while (0)
+
+  // ---- FFN ----
+  ft_make_scale(dY, (long long)T * D.H, w.scale, st);
+  ft_f32_to_e(dY, w.dyb, (long long)T * D.H, w.scale, st);  // every gradient below carries the factor sigma
+  {
+    GemmArgs g = plain_gemm(T, D.F);  // dm = dy Wd (+ gs A_d^T)
+    add_seg(g, w.dyb, D.H, static_cast<const bf*>(L.wt[6]), D.H, D.H);
+    if (adapted(c, 6)) {
+      RUNB(proj_grads(c, L, 6, w.dyb, sv->m, T, sv, dA, dB, st));
+      add_seg(g, w.gs, D.r, w.An, D.r, D.r);
+    }
+    g.Cf = w.dm; g.ldcf = D.F;
+    RUNB(gemm_launch(g, 1, st));
+  }
+  ft_swiglu_bwd(w.dm, sv->a, sv->u, w.da, w.du, (long long)T * D.F, st);
+  {
+    GemmArgs g = plain_gemm(T, D.H);  // dh2 = da Wg + du Wu
+    add_seg(g, w.da, D.F, static_cast<const bf*>(L.wt[4]), D.F, D.F);
+    add_seg(g, w.du, D.F, static_cast<const bf*>(L.wt[5]), D.F, D.F);
+    g.Cf = w.dh2; g.ldcf = D.H;
+    RUNB(gemm_launch(g, 1, st));
+    for (int t = 4; t <= 5; ++t)
+      if (adapted(c, t)) {  // dh2 += gs_t A_t^T
+        RUNB(proj_grads(c, L, t, t == 4 ? w.da : w.du, sv->h2, T, sv, dA, dB, st));
+        GemmArgs g2 = plain_gemm(T, D.H);
+        add_seg(g2, w.gs, D.r, w.An, D.r, D.r);
+        g2.Cf = w.dh2; g2.ldcf = D.H; g2.res = w.dh2;
+        RUNB(gemm_launch(g2, 1, st));
+      }
+  }
+  ft_rmsnorm_bwd(w.dh2, sv->x1, sv->rho2, L.g2, dY, w.dx1, T, D.H, w.scale, nullptr, st);
+  // ---- attention output projection ----
+  ft_f32_to_e(w.dx1, w.dx1b, (long long)T * D.H, nullptr, st);
+  {
+    GemmArgs g = plain_gemm(T, D.QD);  // do = dx1 Wo
+    add_seg(g, w.dx1b, D.H, static_cast<const bf*>(L.wt[3]), D.H, D.H);
+    if (adapted(c, 3)) {
+      RUNB(proj_grads(c, L, 3, w.dx1b, sv->o, T, sv, dA, dB, st));
+      add_seg(g, w.gs, D.r, w.An, D.r, D.r);
+    }
+    g.Cb = w.dob; g.ldcb = D.QD;
+    RUNB(gemm_launch(g, 1, st));
+  }
+  // ---- attention ----
+  ft_attn_delta(w.dob, sv->o, w.delta, B_f, S, D.nq, D.d, st);
+  auto qlike = [&](GemmSeg& sg, bool is_a) {  // operand laid out like q: [T, n_q*d], batch (b, c, g)
+    (is_a ? sg.a_bs0 : sg.b_bs0) = (long long)S * D.QD;
+    (is_a ? sg.a_bs1 : sg.b_bs1) = (long long)D.G * D.d;
+    (is_a ? sg.a_bs2 : sg.b_bs2) = D.d;
+  };
+  auto klike = [&](GemmSeg& sg, bool is_a) {  // like k / v: [T, n_kv*d]
+    (is_a ? sg.a_bs0 : sg.b_bs0) = (long long)S * D.KVD;
+    (is_a ? sg.a_bs1 : sg.b_bs1) = D.d;
+    (is_a ? sg.a_bs2 : sg.b_bs2) = 0;
+  };
+  auto sslike = [&](GemmSeg& sg) {  // A operand [Z][S][S]
+    sg.a_bs0 = (long long)D.nq * SS; sg.a_bs1 = (long long)D.G * SS; sg.a_bs2 = SS;
+  };
+  auto qT_like = [&](GemmSeg& sg) {  // B operand [Bf][n_q*d][S]
+    sg.b_bs0 = (long long)D.QD * S; sg.b_bs1 = (long long)D.G * D.d * S; sg.b_bs2 = (long long)D.d * S;
+  };
+  auto ss_out = [&](GemmArgs& g, float* C) {
+    g.Cf = C; g.ldcf = S;
+    g.cf_bs0 = (long long)D.nq * SS; g.cf_bs1 = (long long)D.G * SS; g.cf_bs2 = SS;
+  };
+  auto q_out = [&](GemmArgs& g, bf* C) {
+    g.Cb = C; g.ldcb = D.QD;
+    g.cb_bs0 = (long long)S * D.QD; g.cb_bs1 = (long long)D.G * D.d; g.cb_bs2 = D.d;
+  };
+  {  // dP = dO V^T (lower)
+    GemmArgs g = plain_gemm(S, S);
+    g.nb1 = D.nkv; g.nb2 = D.G; g.causal = GEMM_OUT_LOWER;
+    add_seg(g, w.dob, D.QD, sv->v, D.KVD, D.d);
+    qlike(g.seg[0], true); klike(g.seg[0], false);
+    ss_out(g, w.dP);
+    RUNB(gemm_launch(g, batches, st));
+  }
+  ft_attn_ds(sv->P, w.dP, w.delta, w.dS, batches, S, st);
+  {  // ST = K Q^T / sqrt(d) (upper, rows = keys)
+    GemmArgs g = plain_gemm(S, S);
+    g.nb1 = D.nkv; g.nb2 = D.G; g.causal = GEMM_OUT_UPPER; g.alpha = scale;
+    add_seg(g, sv->k, D.KVD, sv->q, D.QD, D.d);
+    klike(g.seg[0], true); qlike(g.seg[0], false);
+    ss_out(g, w.ST);
+    RUNB(gemm_launch(g, batches, st));
+  }
+  {  // dPT = V dO^T (upper)
+    GemmArgs g = plain_gemm(S, S);
+    g.nb1 = D.nkv; g.nb2 = D.G; g.causal = GEMM_OUT_UPPER;
+    add_seg(g, sv->v, D.KVD, w.dob, D.QD, D.d);
+    klike(g.seg[0], true); qlike(g.seg[0], false);
+    ss_out(g, w.dPT);
+    RUNB(gemm_launch(g, batches, st));
+  }
+  ft_attn_ds_t(w.ST, w.dPT, sv->lse, w.delta, w.PT, w.dST, batches, S, st);
+  ft_transpose_heads(w.dob, w.doT, B_f, S, D.nq, D.d, st);
+  ft_transpose_heads(sv->q, w.qT, B_f, S, D.nq, D.d, st);
+  ft_transpose_heads(sv->k, w.kT, B_f, S, D.nkv, D.d, st);
+  {  // dV (per query head) = PT dO
+    GemmArgs g = plain_gemm(S, D.d);
+    g.nb1 = D.nkv; g.nb2 = D.G; g.causal = GEMM_K_FROM_M;
+    add_seg(g, w.PT, S, w.doT, S, S);
+    sslike(g.seg[0]); qT_like(g.seg[0]);
+    q_out(g, w.dvq);
+    RUNB(gemm_launch(g, batches, st));
+  }
+  {  // dK (per query head) = dST Q / sqrt(d)
+    GemmArgs g = plain_gemm(S, D.d);
+    g.nb1 = D.nkv; g.nb2 = D.G; g.causal = GEMM_K_FROM_M; g.alpha = scale;
+    add_seg(g, w.dST, S, w.qT, S, S);
+    sslike(g.seg[0]); qT_like(g.seg[0]);
+    q_out(g, w.dkq);
+    RUNB(gemm_launch(g, batches, st));
+  }
+  {  // dQ = dS K / sqrt(d)
+    GemmArgs g = plain_gemm(S, D.d);
+    g.nb1 = D.nkv; g.nb2 = D.G; g.causal = GEMM_K_UPTO_M; g.alpha = scale;
+    add_seg(g, w.dS, S, w.kT, S, S);
+    sslike(g.seg[0]);
+    g.seg[0].b_bs0 = (long long)D.KVD * S; g.seg[0].b_bs1 = (long long)D.d * S; g.seg[0].b_bs2 = 0;
+    q_out(g, w.dq);
+    RUNB(gemm_launch(g, batches, st));
+  }
+  const bf *dk = w.dkq, *dv = w.dvq;
+  if (D.G > 1) {
+    ft_sum_groups(w.dkq, w.dk, T, D.nkv, D.G, D.d, st);
+    ft_sum_groups(w.dvq, w.dv, T, D.nkv, D.G, D.d, st);
+    dk = w.dk;
+    dv = w.dv;
+  }
+  ft_rope(w.dq, T, S, D.nq, D.d, c->dw.inv_freq, true, st);
+  ft_rope(const_cast<bf*>(dk), T, S, D.nkv, D.d, c->dw.inv_freq, true, st);
+  // ---- q, k, v projections ----
+  {
+    GemmArgs g = plain_gemm(T, D.H);  // dh = dq Wq + dk Wk + dv Wv
+    add_seg(g, w.dq, D.QD, static_cast<const bf*>(L.wt[0]), D.QD, D.QD);
+    add_seg(g, dk, D.KVD, static_cast<const bf*>(L.wt[1]), D.KVD, D.KVD);
+    add_seg(g, dv, D.KVD, static_cast<const bf*>(L.wt[2]), D.KVD, D.KVD);
+    g.Cf = w.dh; g.ldcf = D.H;
+    RUNB(gemm_launch(g, 1, st));
+    const bf* dys[3] = {w.dq, dk, dv};
+    for (int t = 0; t < 3; ++t)
+      if (adapted(c, t)) {
+        RUNB(proj_grads(c, L, t, dys[t], sv->h, T, sv, dA, dB, st));
+        GemmArgs g2 = plain_gemm(T, D.H);
+        add_seg(g2, w.gs, D.r, w.An, D.r, D.r);
+        g2.Cf = w.dh; g2.ldcf = D.H; g2.res = w.dh;
+        RUNB(gemm_launch(g2, 1, st));
+      }
+  }
+  ft_rmsnorm_bwd(w.dh, sv->X, sv->rho1, L.g1, w.dx1, dX, T, D.H, nullptr, w.scale + 1, st);
+  HARLI_HIP(hipGetLastError());
+  release_saved(c, sv, st, true);
+  return HARLI_OK;
+}
+
+extern "C" harli_status harli_saved_release(harli_ctx* c, harli_saved* saved, void* hip_stream) {
+  if (!c || !saved) return fail(HARLI_ERR_INVALID, "saved_release: null argument");
+  release_saved(c, saved, static_cast<hipStream_t>(hip_stream), true);
+  return HARLI_OK;
 }

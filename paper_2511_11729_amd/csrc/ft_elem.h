@@ -1,0 +1,24 @@
+// 16-bit element type of the finetune unit's activations, gradients and weight copies.
+// HARLI_FT_HALF = 1 (default): IEEE half.  0: bfloat16 (kept for comparison; at hidden 4096 it
+// misses the parity bar -- see device_utils.h).
+#pragma once
+#include "device_utils.h"
+
+#ifndef HARLI_FT_HALF
+#define HARLI_FT_HALF 1
+#endif
+
+namespace harli {
+#if HARLI_FT_HALF
+__device__ __forceinline__ unsigned short F2E(float f) { return f2h(f); }
+__device__ __forceinline__ float E2F(unsigned short e) { return h2f(e); }
+__device__ __forceinline__ unsigned PACK2(float lo, float hi) { return pack_h2(lo, hi); }
+__device__ __forceinline__ void UNPACK8(const uint4& u, float* f) { unpack8h(u, f); }
+#else
+__device__ __forceinline__ unsigned short F2E(float f) { return f2bf(f); }
+__device__ __forceinline__ float E2F(unsigned short e) { return bf2f(e); }
+__device__ __forceinline__ unsigned PACK2(float lo, float hi) { return pack_bf2(lo, hi); }
+__device__ __forceinline__ void UNPACK8(const uint4& u, float* f) { unpack8(u, f); }
+#endif
+constexpr bool kFtHalf = HARLI_FT_HALF != 0;
+}  // namespace harli

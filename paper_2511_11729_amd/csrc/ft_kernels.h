@@ -1,0 +1,52 @@
+// Element-wise, reduction and skinny kernels of the finetune unit (launch wrappers).
+// All tensors are device pointers; "bf" = one 16-bit element (the compute element of ft_elem.h unless a
+// name says bf16), rows are token-major.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "common.h"
+
+namespace harli {
+typedef unsigned short bf;
+
+// h = bf16(x * rho * g), rho = rsqrt(mean x^2 + eps) (also stored)
+void ft_rmsnorm_fwd(const float* x, const float* g, bf* h, float* rho, int T, int H, float eps, hipStream_t st);
+// dx = dres + rho * (dh*g - xhat * mean(dh*g*xhat)), xhat = x*rho;  dh is fp32
+// res_mul / out_mul: optional device scalars: dx = out_mul * (dres * res_mul + ...)
+void ft_rmsnorm_bwd(const float* dh, const float* x, const float* rho, const float* g, const float* dres, float* dx, int T,
+                    int H, const float* res_mul, const float* out_mul, hipStream_t st);
+// rotary embedding in place on [T, heads*d] bf16, position = t % S; inverse rotates by the negative angle
+void ft_rope(bf* t, int T, int S, int heads, int d, const double* inv_freq, bool inverse, hipStream_t st);
+// causal softmax of fp32 scores [Z][S][S] (already scaled) -> P bf16 (zeros above the diagonal), lse [Z][S] (natural log)
+void ft_softmax_causal(const float* sc, bf* P, float* lse, int Z, int S, hipStream_t st);
+void ft_silu_mul(const bf* a, const bf* u, bf* m, long long n, hipStream_t st);
+// da = dm*u*sig(a)*(1 + a(1-sig(a))), du = dm*a*sig(a);  dm fp32
+void ft_swiglu_bwd(const float* dm, const bf* a, const bf* u, bf* da, bf* du, long long n, hipStream_t st);
+// y = 16-bit(x * *scale)   (scale: optional device scalar)
+void ft_f32_to_e(const float* x, bf* y, long long n, const float* scale, hipStream_t st);
+// scale[0] = sigma = power of two bringing max|x| to 2^8, scale[1] = 1/sigma (scale[2] is scratch)
+void ft_make_scale(const float* x, long long n, float* scale, hipStream_t st);
+// bf16 storage -> compute element: plain copy and [R][C] -> [C][R] transpose
+void ft_from_bf16(const bf* in, bf* out, long long n, hipStream_t st);
+void ft_transpose_from_bf16(const bf* in, bf* out, int R, int C, hipStream_t st);
+// batched transpose: in [Z][R][C] (row stride ldi, batch stride bsi) -> out [Z][C][R]
+void ft_transpose(const bf* in, bf* out, int Z, int R, int C, long long ldi, long long bsi, long long ldo, long long bso,
+                  hipStream_t st);
+// head-wise transpose of a [T, heads*d] tensor into [Bf][heads][d][S]
+void ft_transpose_heads(const bf* in, bf* out, int Bf, int S, int heads, int d, hipStream_t st);
+// delta[z][q] = sum_e dO[b*S+q][h*d+e] * O[...], z = b*heads + h
+void ft_attn_delta(const bf* dO, const bf* O, float* delta, int Bf, int S, int heads, int d, hipStream_t st);
+// dS = P * (dP - delta[q]) for k <= q, else 0;  P bf16 [Z][S][S], dP fp32
+void ft_attn_ds(const bf* P, const float* dP, const float* delta, bf* dS, int Z, int S, hipStream_t st);
+// transposed orientation [Z][k][q]: PT = exp(ST - lse[q]), dST = PT * (dPT - delta[q]) for q >= k, else 0
+void ft_attn_ds_t(const float* ST, const float* dPT, const float* lse, const float* delta, bf* PT, bf* dST, int Z, int S,
+                  hipStream_t st);
+// skinny NT GEMM: C[M, N] = alpha * X[M, K] . Bm[N, K]^T, N <= 64 and N % 16 == 0 after padding by the caller's layout
+void ft_skinny_nt(const bf* X, long long ldx, const bf* Bm, long long ldb, bf* C, long long ldc, int M, int N, int K,
+                  float alpha, hipStream_t st);
+// G[j*sj + r*sr] += sum_t X[t][j] * U[t][r]   (fp32 atomics), X [T, J] bf16, U [T, R] bf16, R <= 64
+void ft_lora_grad(const bf* X, long long ldx, const bf* U, long long ldu, float* G, long long sj, long long sr, int T, int J,
+                  int R, const float* out_mul, hipStream_t st);
+// sum GQA query-head groups: dk[T][n_kv*d] = sum_g dkq[T][(c*G+g)*d + e]
+void ft_sum_groups(const bf* in, bf* out, int T, int n_kv, int G, int d, hipStream_t st);
+}  // namespace harli

@@ -1,0 +1,433 @@
+// Element-wise, reduction and skinny kernels of the LoRA finetune unit (Harli Sec. 2.1: forward,
+// backward with adapter gradients only; Sec. 6.1: one transformer layer per call).  These are
+// the HBM-bound pieces between the MFMA GEMMs: every kernel reads and writes each element once
+// with 8- or 16-byte accesses.
+#include "ft_kernels.h"
+
+#include "ft_elem.h"
+
+namespace harli {
+namespace {
+
+__device__ __forceinline__ float block_sum_256(float v, float* sh) {
+  v = wave_sum(v);
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+  __syncthreads();
+  const float r = sh[0] + sh[1] + sh[2] + sh[3];
+  __syncthreads();
+  return r;
+}
+
+// ---------------------------------------------------------------- RMSNorm
+__global__ void __launch_bounds__(256) k_rmsnorm_fwd(const float* x, const float* g, bf* h, float* rho, int H, float eps) {
+  __shared__ float sh[4];
+  const int t = blockIdx.x, tid = threadIdx.x;
+  const float* xr = x + (size_t)t * H;
+  float s2 = 0.f;
+  for (int k = tid * 4; k < H; k += 1024) {
+    const float4 v = *reinterpret_cast<const float4*>(xr + k);
+    s2 += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+  }
+  s2 = block_sum_256(s2, sh);
+  const float r = rsqrtf(s2 / (float)H + eps);
+  if (tid == 0) rho[t] = r;
+  for (int k = tid * 4; k < H; k += 1024) {
+    const float4 v = *reinterpret_cast<const float4*>(xr + k);
+    const float4 gg = *reinterpret_cast<const float4*>(g + k);
+    *reinterpret_cast<uint2*>(h + (size_t)t * H + k) =
+        make_uint2(PACK2(v.x * r * gg.x, v.y * r * gg.y), PACK2(v.z * r * gg.z, v.w * r * gg.w));
+  }
+}
+
+__global__ void __launch_bounds__(256) k_rmsnorm_bwd(const float* dh, const float* x, const float* rho, const float* g,
+                                                     const float* dres, float* dx, int H, const float* res_mul,
+                                                     const float* out_mul) {
+  __shared__ float sh[4];
+  const int t = blockIdx.x, tid = threadIdx.x;
+  const float r = rho[t];
+  const float rm = res_mul ? *res_mul : 1.f, om = out_mul ? *out_mul : 1.f;
+  const float* xr = x + (size_t)t * H;
+  const float* dr = dh + (size_t)t * H;
+  float dot = 0.f;
+  for (int k = tid * 4; k < H; k += 1024) {
+    const float4 v = *reinterpret_cast<const float4*>(xr + k);
+    const float4 d = *reinterpret_cast<const float4*>(dr + k);
+    const float4 gg = *reinterpret_cast<const float4*>(g + k);
+    dot += d.x * gg.x * v.x + d.y * gg.y * v.y + d.z * gg.z * v.z + d.w * gg.w * v.w;
+  }
+  dot = block_sum_256(dot, sh);
+  const float c = dot * r * r / (float)H;  // mean(dh*g*xhat) * rho, with xhat = x * rho
+  for (int k = tid * 4; k < H; k += 1024) {
+    const float4 v = *reinterpret_cast<const float4*>(xr + k);
+    const float4 d = *reinterpret_cast<const float4*>(dr + k);
+    const float4 gg = *reinterpret_cast<const float4*>(g + k);
+    const float4 rs = *reinterpret_cast<const float4*>(dres + (size_t)t * H + k);
+    float4 o;
+    o.x = om * (rs.x * rm + r * (d.x * gg.x - v.x * c));
+    o.y = om * (rs.y * rm + r * (d.y * gg.y - v.y * c));
+    o.z = om * (rs.z * rm + r * (d.z * gg.z - v.z * c));
+    o.w = om * (rs.w * rm + r * (d.w * gg.w - v.w * c));
+    *reinterpret_cast<float4*>(dx + (size_t)t * H + k) = o;
+  }
+}
+
+// ---------------------------------------------------------------- rotary embedding, pairs (i, i + d/2)
+__global__ void __launch_bounds__(256) k_rope(bf* x, int S, int heads, int d, const double* inv_freq, float sign) {
+  const int t = blockIdx.x, half = d >> 1;
+  const double pos = (double)(t % S);
+  bf* row = x + (size_t)t * heads * d;
+  for (int idx = threadIdx.x; idx < heads * half; idx += 256) {
+    const int hh = idx / half, i = idx - hh * half;
+    const double ang = pos * inv_freq[i];
+    const double red = ang - 6.283185307179586476925 * rint(ang * 0.15915494309189533577);
+    float sn, cs;
+    sincosf((float)red, &sn, &cs);
+    sn *= sign;
+    bf* p = row + hh * d + i;
+    const float lo = E2F(p[0]), hi = E2F(p[half]);
+    p[0] = F2E(lo * cs - hi * sn);
+    p[half] = F2E(hi * cs + lo * sn);
+  }
+}
+
+// ---------------------------------------------------------------- causal softmax, one wave per row
+__global__ void __launch_bounds__(256) k_softmax_causal(const float* sc, bf* P, float* lse, int S, long long rows) {
+  const long long row = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const int lane = threadIdx.x & 63;
+  const int q = (int)(row % S);
+  const float* s = sc + row * S;
+  float mx = -INFINITY;
+  for (int k = lane; k <= q; k += 64) mx = fmaxf(mx, s[k]);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+  float sum = 0.f;
+  for (int k = lane; k <= q; k += 64) sum += __expf(s[k] - mx);
+  sum = wave_sum(sum);
+  const float inv = 1.f / sum;
+  bf* p = P + row * S;
+  for (int k = lane; k < S; k += 64) p[k] = (k <= q) ? F2E(__expf(s[k] - mx) * inv) : (bf)0;
+  if (lane == 0) lse[row] = mx + __logf(sum);
+}
+
+// ---------------------------------------------------------------- SwiGLU
+__global__ void __launch_bounds__(256) k_silu_mul(const bf* a, const bf* u, bf* m, long long n8) {
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n8) return;
+  const uint4 av = reinterpret_cast<const uint4*>(a)[i], uv = reinterpret_cast<const uint4*>(u)[i];
+  float af[8], uf[8], o[8];
+  UNPACK8(av, af);
+  UNPACK8(uv, uf);
+#pragma unroll
+  for (int e = 0; e < 8; ++e) o[e] = af[e] / (1.f + __expf(-af[e])) * uf[e];
+  reinterpret_cast<uint4*>(m)[i] = make_uint4(PACK2(o[0], o[1]), PACK2(o[2], o[3]), PACK2(o[4], o[5]), PACK2(o[6], o[7]));
+}
+
+__global__ void __launch_bounds__(256) k_swiglu_bwd(const float* dm, const bf* a, const bf* u, bf* da, bf* du, long long n8) {
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n8) return;
+  const uint4 av = reinterpret_cast<const uint4*>(a)[i], uv = reinterpret_cast<const uint4*>(u)[i];
+  const float4 d0 = reinterpret_cast<const float4*>(dm)[2 * i], d1 = reinterpret_cast<const float4*>(dm)[2 * i + 1];
+  const float d[8] = {d0.x, d0.y, d0.z, d0.w, d1.x, d1.y, d1.z, d1.w};
+  float af[8], uf[8], oa[8], ou[8];
+  UNPACK8(av, af);
+  UNPACK8(uv, uf);
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const float sg = 1.f / (1.f + __expf(-af[e]));
+    oa[e] = d[e] * uf[e] * sg * (1.f + af[e] * (1.f - sg));
+    ou[e] = d[e] * af[e] * sg;
+  }
+  reinterpret_cast<uint4*>(da)[i] = make_uint4(PACK2(oa[0], oa[1]), PACK2(oa[2], oa[3]), PACK2(oa[4], oa[5]), PACK2(oa[6], oa[7]));
+  reinterpret_cast<uint4*>(du)[i] = make_uint4(PACK2(ou[0], ou[1]), PACK2(ou[2], ou[3]), PACK2(ou[4], ou[5]), PACK2(ou[6], ou[7]));
+}
+
+// ---------------------------------------------------------------- transposes (64 x 64 tiles through LDS)
+template <bool FROM_BF16>
+__global__ void __launch_bounds__(256) k_transpose(const bf* in, bf* out, int R, int C, long long ldi, long long bsi,
+                                                   long long ldo, long long bso) {
+  __shared__ bf tile[64][66];
+  const bf* src = in + blockIdx.z * bsi;
+  bf* dst = out + blockIdx.z * bso;
+  const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  for (int r = ty; r < 64; r += 4)
+    tile[r][tx] = (r0 + r < R && c0 + tx < C) ? src[(long long)(r0 + r) * ldi + c0 + tx] : (bf)0;
+  __syncthreads();
+  for (int c = ty; c < 64; c += 4)
+    if (c0 + c < C && r0 + tx < R) dst[(long long)(c0 + c) * ldo + r0 + tx] = FROM_BF16 ? F2E(bf2f(tile[tx][c])) : tile[tx][c];
+}
+
+// storage bf16 -> compute element (identity when the element type is bf16)
+__global__ void __launch_bounds__(256) k_from_bf16(const bf* in, bf* out, long long n) {
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) out[i] = F2E(bf2f(in[i]));
+}
+
+// ---------------------------------------------------------------- gradient scaling
+// The backward pass is linear in dY, so dY is multiplied by a power of two sigma that brings its
+// largest magnitude to 2^8 before it is rounded to 16 bits, and 1/sigma is applied where the
+// fp32 results leave the unit (dX, dA, dB).  scale[0] = sigma, scale[1] = 1/sigma.
+__global__ void __launch_bounds__(256) k_amax(const float* x, long long n4, unsigned* amax_bits) {
+  float m = 0.f;
+  for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n4; i += (long long)gridDim.x * 256) {
+    const float4 v = reinterpret_cast<const float4*>(x)[i];
+    m = fmaxf(fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))), m);
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
+  if ((threadIdx.x & 63) == 0) atomicMax(amax_bits, __float_as_uint(m));  // non-negative floats order like their bits
+}
+__global__ void k_scale_reset(unsigned* amax_bits) { *amax_bits = 0u; }
+__global__ void k_scale_make(const unsigned* amax_bits, float* scale) {
+  const float a = __uint_as_float(*amax_bits);
+  float sg = 1.f;
+  if (a > 0.f && a < INFINITY) {
+    int e;
+    frexpf(a, &e);                       // a = f * 2^e, f in [0.5, 1)
+    sg = ldexpf(1.f, min(max(8 - e, -100), 100));
+  }
+  scale[0] = sg;
+  scale[1] = 1.f / sg;
+}
+__global__ void __launch_bounds__(256) k_f32_to_e_scaled(const float* x, bf* y, long long n4, const float* scale) {
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n4) return;
+  const float sg = scale ? *scale : 1.f;
+  const float4 v = reinterpret_cast<const float4*>(x)[i];
+  reinterpret_cast<uint2*>(y)[i] = make_uint2(PACK2(v.x * sg, v.y * sg), PACK2(v.z * sg, v.w * sg));
+}
+
+// ---------------------------------------------------------------- attention backward helpers
+__global__ void __launch_bounds__(256) k_attn_delta(const bf* dO, const bf* O, float* delta, int Bf, int S, int heads, int d) {
+  // one wave per (token, head)
+  const long long idx = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const long long total = (long long)Bf * S * heads;
+  if (idx >= total) return;
+  const int lane = threadIdx.x & 63;
+  const long long t = idx / heads;
+  const int h = (int)(idx - t * heads);
+  const bf* a = dO + t * heads * d + h * d;
+  const bf* b = O + t * heads * d + h * d;
+  float s = 0.f;
+  for (int e = lane; e < d; e += 64) s += E2F(a[e]) * E2F(b[e]);
+  s = wave_sum(s);
+  if (lane == 0) {
+    const long long bb = t / S, q = t - bb * S;
+    delta[(bb * heads + h) * S + q] = s;
+  }
+}
+
+__global__ void __launch_bounds__(256) k_attn_ds(const bf* P, const float* dP, const float* delta, bf* dS, int S, long long rows) {
+  const long long row = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const int lane = threadIdx.x & 63;
+  const int q = (int)(row % S);
+  const float dl = delta[row];
+  for (int k = lane; k < S; k += 64)
+    dS[row * S + k] = (k <= q) ? F2E(E2F(P[row * S + k]) * (dP[row * S + k] - dl)) : (bf)0;
+}
+
+__global__ void __launch_bounds__(256) k_attn_ds_t(const float* ST, const float* dPT, const float* lse, const float* delta,
+                                                   bf* PT, bf* dST, int S, long long rows) {
+  // row = (z, key index); columns are query positions
+  const long long row = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const int lane = threadIdx.x & 63;
+  const long long z = row / S;
+  const int kk = (int)(row - z * S);
+  const float* l = lse + z * S;
+  const float* dl = delta + z * S;
+  for (int q = lane; q < S; q += 64) {
+    bf p = 0, ds = 0;
+    if (q >= kk) {
+      const float pf = __expf(ST[row * S + q] - l[q]);
+      p = F2E(pf);
+      ds = F2E(pf * (dPT[row * S + q] - dl[q]));
+    }
+    PT[row * S + q] = p;
+    dST[row * S + q] = ds;
+  }
+}
+
+// ---------------------------------------------------------------- skinny NT GEMM (LoRA down-projection x.A and dy.B^T)
+// Workgroup = 16 rows of X, 4 waves split K, one 16x16x32 MFMA column tile per 16 outputs.
+template <int NT>
+__global__ void __launch_bounds__(256) k_skinny_nt(const bf* X, long long ldx, const bf* Bm, long long ldb, bf* C,
+                                                   long long ldc, int M, int N, int K, float alpha) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, i16 = lane & 15, g = lane >> 4;
+  const int m0 = blockIdx.x * 16;
+  const int mr = min(m0 + i16, M - 1);
+  const bf* xr = X + (long long)mr * ldx + g * 8;
+  const bf* br[NT];
+#pragma unroll
+  for (int t = 0; t < NT; ++t) br[t] = Bm + (long long)min(t * 16 + i16, N - 1) * ldb + g * 8;
+  f32x4 acc[NT];
+#pragma unroll
+  for (int t = 0; t < NT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+  const int steps = (K + 31) >> 5;
+  const int s0 = steps * wave / 4, s1 = steps * (wave + 1) / 4;
+  for (int s = s0; s < s1; ++s) {
+    const int k = s << 5;
+    const bool ok = k + g * 8 < K;
+    const int kc = ok ? k : 0;
+    uint4 xf = *reinterpret_cast<const uint4*>(xr + kc);
+    if (!ok) xf = make_uint4(0, 0, 0, 0);
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      const uint4 bfr = *reinterpret_cast<const uint4*>(br[t] + kc);
+      // rows of X are the MFMA "row" operand, rows of Bm the "column" operand: D[m][n]
+#if HARLI_FT_HALF
+      acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, xf), __builtin_bit_cast(f16x8, bfr), acc[t], 0, 0, 0);
+#else
+      acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, xf), __builtin_bit_cast(bf16x8, bfr), acc[t], 0, 0, 0);
+#endif
+    }
+  }
+  __shared__ float4 red[4][NT][64];
+#pragma unroll
+  for (int t = 0; t < NT; ++t) red[wave][t][lane] = make_float4(acc[t][0], acc[t][1], acc[t][2], acc[t][3]);
+  __syncthreads();
+  if (wave == 0) {
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      float4 s = red[0][t][lane];
+      for (int w = 1; w < 4; ++w) {
+        const float4 o = red[w][t][lane];
+        s.x += o.x; s.y += o.y; s.z += o.z; s.w += o.w;
+      }
+      // lane holds D[m = 4g + e][n = i16]
+      const int n = t * 16 + i16;
+      const float v[4] = {s.x, s.y, s.z, s.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int m = m0 + 4 * g + e;
+        if (m < M && n < N) C[(long long)m * ldc + n] = F2E(v[e] * alpha);
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------- adapter gradients: G[j, r] += sum_t X[t, j] U[t, r]
+template <int R>
+__global__ void __launch_bounds__(256) k_lora_grad(const bf* X, long long ldx, const bf* U, long long ldu, float* G,
+                                                   long long sj, long long sr, int T, int J, int tchunk,
+                                                   const float* out_mul) {
+  const int j = blockIdx.x * 256 + threadIdx.x;
+  const int t0 = blockIdx.y * tchunk, t1 = min(T, t0 + tchunk);
+  float acc[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) acc[r] = 0.f;
+  const int jc = min(j, J - 1);
+  for (int t = t0; t < t1; ++t) {
+    const float xv = E2F(X[(long long)t * ldx + jc]);
+    const bf* u = U + (long long)t * ldu;  // uniform over the workgroup: scalar loads
+#pragma unroll
+    for (int r = 0; r < R; r += 2) {
+      const unsigned w = *reinterpret_cast<const unsigned*>(u + r);
+      acc[r] += xv * E2F((unsigned short)(w & 0xffffu));
+      acc[r + 1] += xv * E2F((unsigned short)(w >> 16));
+    }
+  }
+  if (j < J) {
+    const float om = out_mul ? *out_mul : 1.f;
+#pragma unroll
+    for (int r = 0; r < R; ++r) atomicAdd(G + (long long)j * sj + (long long)r * sr, acc[r] * om);
+  }
+}
+
+__global__ void __launch_bounds__(256) k_sum_groups(const bf* in, bf* out, long long total, int n_kv, int G, int d) {
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= total) return;
+  const int kvd = n_kv * d;
+  const long long t = i / kvd;
+  const int rem = (int)(i - t * kvd), c = rem / d, e = rem - c * d;
+  float s = 0.f;
+  for (int g = 0; g < G; ++g) s += E2F(in[t * (long long)kvd * G + (c * G + g) * d + e]);
+  out[i] = F2E(s);
+}
+
+inline unsigned nblk(long long n, int per) { return (unsigned)((n + per - 1) / per); }
+
+}  // namespace
+
+void ft_rmsnorm_fwd(const float* x, const float* g, bf* h, float* rho, int T, int H, float eps, hipStream_t st) {
+  hipLaunchKernelGGL(k_rmsnorm_fwd, dim3(T), dim3(256), 0, st, x, g, h, rho, H, eps);
+}
+void ft_rmsnorm_bwd(const float* dh, const float* x, const float* rho, const float* g, const float* dres, float* dx, int T,
+                    int H, const float* res_mul, const float* out_mul, hipStream_t st) {
+  hipLaunchKernelGGL(k_rmsnorm_bwd, dim3(T), dim3(256), 0, st, dh, x, rho, g, dres, dx, H, res_mul, out_mul);
+}
+void ft_rope(bf* t, int T, int S, int heads, int d, const double* inv_freq, bool inverse, hipStream_t st) {
+  hipLaunchKernelGGL(k_rope, dim3(T), dim3(256), 0, st, t, S, heads, d, inv_freq, inverse ? -1.f : 1.f);
+}
+void ft_softmax_causal(const float* sc, bf* P, float* lse, int Z, int S, hipStream_t st) {
+  const long long rows = (long long)Z * S;
+  hipLaunchKernelGGL(k_softmax_causal, dim3(nblk(rows, 4)), dim3(256), 0, st, sc, P, lse, S, rows);
+}
+void ft_silu_mul(const bf* a, const bf* u, bf* m, long long n, hipStream_t st) {
+  hipLaunchKernelGGL(k_silu_mul, dim3(nblk(n / 8, 256)), dim3(256), 0, st, a, u, m, n / 8);
+}
+void ft_swiglu_bwd(const float* dm, const bf* a, const bf* u, bf* da, bf* du, long long n, hipStream_t st) {
+  hipLaunchKernelGGL(k_swiglu_bwd, dim3(nblk(n / 8, 256)), dim3(256), 0, st, dm, a, u, da, du, n / 8);
+}
+void ft_f32_to_e(const float* x, bf* y, long long n, const float* scale, hipStream_t st) {
+  hipLaunchKernelGGL(k_f32_to_e_scaled, dim3(nblk(n / 4, 256)), dim3(256), 0, st, x, y, n / 4, scale);
+}
+void ft_transpose(const bf* in, bf* out, int Z, int R, int C, long long ldi, long long bsi, long long ldo, long long bso,
+                  hipStream_t st) {
+  hipLaunchKernelGGL(k_transpose<false>, dim3((C + 63) / 64, (R + 63) / 64, Z), dim3(256), 0, st, in, out, R, C, ldi, bsi, ldo, bso);
+}
+void ft_transpose_from_bf16(const bf* in, bf* out, int R, int C, hipStream_t st) {
+  hipLaunchKernelGGL(k_transpose<true>, dim3((C + 63) / 64, (R + 63) / 64, 1), dim3(256), 0, st, in, out, R, C,
+                     (long long)C, 0LL, (long long)R, 0LL);
+}
+void ft_from_bf16(const bf* in, bf* out, long long n, hipStream_t st) {
+  hipLaunchKernelGGL(k_from_bf16, dim3(nblk(n, 256)), dim3(256), 0, st, in, out, n);
+}
+void ft_make_scale(const float* x, long long n, float* scale, hipStream_t st) {
+  unsigned* bits = reinterpret_cast<unsigned*>(scale + 2);
+  hipLaunchKernelGGL(k_scale_reset, dim3(1), dim3(1), 0, st, bits);
+  hipLaunchKernelGGL(k_amax, dim3(1024), dim3(256), 0, st, x, n / 4, bits);
+  hipLaunchKernelGGL(k_scale_make, dim3(1), dim3(1), 0, st, bits, scale);
+}
+void ft_transpose_heads(const bf* in, bf* out, int Bf, int S, int heads, int d, hipStream_t st) {
+  // per sequence b: [S][heads*d] -> [heads*d][S] = [heads][d][S]
+  ft_transpose(in, out, Bf, S, heads * d, (long long)heads * d, (long long)S * heads * d, S, (long long)S * heads * d, st);
+}
+void ft_attn_delta(const bf* dO, const bf* O, float* delta, int Bf, int S, int heads, int d, hipStream_t st) {
+  const long long total = (long long)Bf * S * heads;
+  hipLaunchKernelGGL(k_attn_delta, dim3(nblk(total, 4)), dim3(256), 0, st, dO, O, delta, Bf, S, heads, d);
+}
+void ft_attn_ds(const bf* P, const float* dP, const float* delta, bf* dS, int Z, int S, hipStream_t st) {
+  const long long rows = (long long)Z * S;
+  hipLaunchKernelGGL(k_attn_ds, dim3(nblk(rows, 4)), dim3(256), 0, st, P, dP, delta, dS, S, rows);
+}
+void ft_attn_ds_t(const float* ST, const float* dPT, const float* lse, const float* delta, bf* PT, bf* dST, int Z, int S,
+                  hipStream_t st) {
+  const long long rows = (long long)Z * S;
+  hipLaunchKernelGGL(k_attn_ds_t, dim3(nblk(rows, 4)), dim3(256), 0, st, ST, dPT, lse, delta, PT, dST, S, rows);
+}
+void ft_skinny_nt(const bf* X, long long ldx, const bf* Bm, long long ldb, bf* C, long long ldc, int M, int N, int K,
+                  float alpha, hipStream_t st) {
+  const int nt = (N + 15) / 16;
+  const dim3 grid((M + 15) / 16), blk(256);
+  if (nt == 1) hipLaunchKernelGGL(k_skinny_nt<1>, grid, blk, 0, st, X, ldx, Bm, ldb, C, ldc, M, N, K, alpha);
+  else if (nt == 2) hipLaunchKernelGGL(k_skinny_nt<2>, grid, blk, 0, st, X, ldx, Bm, ldb, C, ldc, M, N, K, alpha);
+  else hipLaunchKernelGGL(k_skinny_nt<4>, grid, blk, 0, st, X, ldx, Bm, ldb, C, ldc, M, N, K, alpha);
+}
+void ft_lora_grad(const bf* X, long long ldx, const bf* U, long long ldu, float* G, long long sj, long long sr, int T, int J,
+                  int R, const float* out_mul, hipStream_t st) {
+  const int tchunk = 128;
+  const dim3 grid((J + 255) / 256, (T + tchunk - 1) / tchunk), blk(256);
+  if (R <= 8) hipLaunchKernelGGL(k_lora_grad<8>, grid, blk, 0, st, X, ldx, U, ldu, G, sj, sr, T, J, tchunk, out_mul);
+  else if (R <= 16) hipLaunchKernelGGL(k_lora_grad<16>, grid, blk, 0, st, X, ldx, U, ldu, G, sj, sr, T, J, tchunk, out_mul);
+  else if (R <= 32) hipLaunchKernelGGL(k_lora_grad<32>, grid, blk, 0, st, X, ldx, U, ldu, G, sj, sr, T, J, tchunk, out_mul);
+  else hipLaunchKernelGGL(k_lora_grad<64>, grid, blk, 0, st, X, ldx, U, ldu, G, sj, sr, T, J, tchunk, out_mul);
+}
+void ft_sum_groups(const bf* in, bf* out, int T, int n_kv, int G, int d, hipStream_t st) {
+  const long long total = (long long)T * n_kv * d;
+  hipLaunchKernelGGL(k_sum_groups, dim3(nblk(total, 256)), dim3(256), 0, st, in, out, total, n_kv, G, d);
+}
+
+}  // namespace harli

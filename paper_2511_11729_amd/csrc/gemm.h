@@ -1,0 +1,51 @@
+// 16-bit MFMA GEMM used by the finetune unit:  C[z] = alpha * sum_s A_s[z] . B_s[z]^T  (+ res)
+// Every operand is "NT": A_s is [M, K_s] and B_s is [N, K_s], both row-major with the
+// contraction index contiguous.  Up to four K segments accumulate into one output, which is
+// how the LoRA path rides on the base GEMM (y = [x | s*xA] . [W | B^T]^T, Sec. 2.1 LoRA) and
+// how gradients that sum over several projections are formed in one pass.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "common.h"
+
+namespace harli {
+
+constexpr int kGemmMaxSeg = 4;
+
+struct GemmSeg {
+  const unsigned short* A;  // bf16 [M, K], row stride lda
+  const unsigned short* B;  // bf16 [N, K], row stride ldb
+  int K;                    // multiple of 8
+  long long lda, ldb;
+  // batch strides (elements); z -> (z0, z1, z2) = (z / (nb1*nb2), (z / nb2) % nb1, z % nb2)
+  long long a_bs0, a_bs1, a_bs2, b_bs0, b_bs1, b_bs2;
+};
+
+enum GemmCausal {
+  GEMM_FULL = 0,
+  GEMM_OUT_LOWER = 1,  // only tiles touching n <= m are computed (rows = queries, cols = keys)
+  GEMM_OUT_UPPER = 2,  // only tiles touching n >= m are computed (rows = keys, cols = queries)
+  GEMM_K_UPTO_M = 3,   // A[m, k] is zero for k > m: the K loop stops at the tile's last row
+  GEMM_K_FROM_M = 4    // A[m, k] is zero for k < m: the K loop starts at the tile's first row
+};
+
+struct GemmArgs {
+  int M, N, nseg, nb1, nb2;  // nb1, nb2 >= 1; grid.z = number of batches
+  GemmSeg seg[kGemmMaxSeg];
+  float alpha;
+  int causal;
+  int half;  // operands and 16-bit outputs are IEEE half (1) or bfloat16 (0)
+  // outputs (any subset): bf16 row-major, fp32 row-major (optionally + res), bf16 transposed [N, M]
+  unsigned short* Cb;
+  long long ldcb, cb_bs0, cb_bs1, cb_bs2;
+  float* Cf;
+  const float* res;  // same layout as Cf
+  long long ldcf, cf_bs0, cf_bs1, cf_bs2;
+  unsigned short* Ct;
+  long long ldct, ct_bs0, ct_bs1, ct_bs2;
+};
+
+// Launches on `st`; batches = grid.z.  Shapes are validated (K % 8, pointers, strides % 8).
+harli_status gemm_launch(const GemmArgs& a, int batches, hipStream_t st);
+
+}  // namespace harli

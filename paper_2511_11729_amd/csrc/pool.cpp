@@ -76,6 +76,7 @@ struct Live {
 
 struct Pending {
   void* event;
+  bool own;  // the pool destroys the event once it has completed
   bool is_page;
   int32_t page;
   size_t offset;
@@ -284,6 +285,7 @@ struct harli_pool {
     for (size_t i = 0; i < pending.size(); ++i) {
       Pending& p = pending[i];
       if (event_done(p.event) != 0) {  // completed (or the query failed: do not leak)
+        if (p.own) event_destroy(p.event);
         if (p.is_page)
           release_page(p.page);
         else
@@ -354,7 +356,12 @@ harli_status harli_pool_create(void* slab, size_t slab_bytes, const harli_pool_c
   return HARLI_OK;
 }
 
-void harli_pool_destroy(harli_pool* p) { delete p; }
+void harli_pool_destroy(harli_pool* p) {
+  if (!p) return;
+  for (const Pending& q : p->pending)
+    if (q.own) event_destroy(q.event);
+  delete p;
+}
 
 harli_status harli_pool_alloc(harli_pool* p, harli_class cls, size_t n, harli_alloc* out) {
   if (!p || !out) return fail(HARLI_ERR_INVALID, "pool_alloc: null argument");
@@ -421,7 +428,7 @@ harli_status harli_pool_free(harli_pool* p, const harli_alloc* a, void* event) {
   for (const Pending& q : p->pending)
     if (!q.is_page && q.offset == a->offset) return fail(HARLI_ERR_INVALID, "pool_free: offset %zu freed twice", a->offset);
   if (event)
-    p->pending.push_back(Pending{event, false, -1, a->offset});
+    p->pending.push_back(Pending{event, false, false, -1, a->offset});
   else
     p->release(a->offset);
   return HARLI_OK;
@@ -441,7 +448,7 @@ harli_status harli_pool_free_pages(harli_pool* p, int32_t n_pages, const int32_t
   }
   for (int32_t i = 0; i < n_pages; ++i) {
     if (event)
-      p->pending.push_back(Pending{event, true, page_ids[i], 0});
+      p->pending.push_back(Pending{event, false, true, page_ids[i], 0});
     else
       p->release_page(page_ids[i]);
   }
@@ -494,3 +501,20 @@ void harli_pool_geom(const harli_pool* p, harli::KvGeom* g) {
 }
 
 }  // extern "C"
+
+namespace harli {
+// Release whose event the pool takes ownership of (library-internal: the finetune unit records
+// one event per released buffer and cannot know when the pool will have polled it).
+harli_status pool_free_owned(harli_pool* p, const harli_alloc* a, void* event) {
+  if (!event) return harli_pool_free(p, a, nullptr);
+  harli_status st = harli_pool_free(p, a, event);
+  if (st != HARLI_OK) {
+    event_destroy(event);
+    return st;
+  }
+  std::lock_guard<std::mutex> lk(p->mu);
+  for (Pending& q : p->pending)
+    if (q.event == event) q.own = true;
+  return HARLI_OK;
+}
+}  // namespace harli

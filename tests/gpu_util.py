@@ -168,3 +168,62 @@ class DecodeCase:
         assert np.max(np.abs(got - want)) <= tol_ratio * np.max(np.abs(want))
         assert rel_fro(got, want) <= 5e-3
         return len(changed_ref)
+
+
+class FinetuneCase:
+    """One finetune unit (layer forward + backward) on both sides."""
+
+    def __init__(self, w: wl.Workload, model: wl.ModelCfg, lora: wl.LoraCfg, ft: wl.FinetuneCfg, *,
+                 block_bytes=2 << 20, small_pool_bytes=8 << 20, zero_b=False, n_chunks=None):
+        self.w, self.m, self.lora, self.ft = w, model, lora, ft
+        m = model
+        self.W_np = wl.make_layer_weights(w, 0, m)
+        self.lora_np = wl.make_lora(w, 0, m, lora, zero_b=zero_b)
+        self.X_np, self.T_np = wl.make_finetune_inputs(w, m, ft)
+        T = ft.tokens
+        # a first context-free estimate of the pool size: activations + slack
+        Z = ft.micro_batch * m.n_q
+        est = (T * m.hidden * 12 + T * m.n_q * m.head_dim * 4 + T * m.n_kv * m.head_dim * 4 + T * m.ffn * 6
+               + Z * ft.seq_len * ft.seq_len * 2)
+        chunk = m.n_layers * 2 * block_bytes
+        n_chunks = n_chunks or (est // chunk + 4)
+        self.slab_bytes = small_pool_bytes + n_chunks * chunk
+        self.slab = torch.zeros(self.slab_bytes, dtype=torch.uint8, device=DEV)
+        self.pool = hb.Pool(self.slab, self.slab_bytes, block_bytes=block_bytes, n_layers=m.n_layers,
+                            kv_row_bytes=m.kv_row_bytes, small_pool_bytes=small_pool_bytes, kv_reserve_chunks=1)
+        self.layer_dev = {n: to_dev(self.W_np[n], m.dtype) for n in ("wq", "wk", "wv", "wo", "wg", "wu", "wd")}
+        self.layer_dev["g1"], self.layer_dev["g2"] = f32_dev(self.W_np["g1"]), f32_dev(self.W_np["g2"])
+        self.ctx = hb.Context(self.pool, n_layers=m.n_layers, hidden=m.hidden, n_q_heads=m.n_q, n_kv_heads=m.n_kv,
+                              head_dim=m.head_dim, ffn=m.ffn, rms_eps=m.rms_eps, rope_base=m.rope_base,
+                              dtype=hb.HARLI_BF16, max_batch=1, max_seq_len=16, max_ft_tokens=T,
+                              layers=[self.layer_dev])
+        self.A_dev = {p: to_dev(a, m.dtype) for p, (a, b) in self.lora_np.items()}
+        self.B_dev = {p: to_dev(b, m.dtype) for p, (a, b) in self.lora_np.items()}
+        self.ctx.lora_attach(lora.rank, lora.alpha, lora.targets, [self.A_dev], [self.B_dev])
+        self.X_dev = f32_dev(self.X_np.reshape(T, m.hidden))
+
+    def forward_gpu(self, stream=None):
+        T, H = self.ft.tokens, self.m.hidden
+        self.Y_dev = torch.empty(T, H, dtype=torch.float32, device=DEV)
+        self.saved = self.ctx.lora_fwd(0, self.X_dev, self.Y_dev, self.ft.micro_batch, self.ft.seq_len, stream=stream)
+        torch.cuda.synchronize()
+        return self.Y_dev.cpu().numpy().reshape(self.X_np.shape)
+
+    def backward_gpu(self, dY: np.ndarray, stream=None, accumulate_into=None):
+        T, H = self.ft.tokens, self.m.hidden
+        self.dY_dev = f32_dev(dY.reshape(T, H))
+        self.dX_dev = torch.empty(T, H, dtype=torch.float32, device=DEV)
+        if accumulate_into is None:
+            self.dA_dev = {p: torch.zeros(a.shape, dtype=torch.float32, device=DEV) for p, (a, b) in self.lora_np.items()}
+            self.dB_dev = {p: torch.zeros(b.shape, dtype=torch.float32, device=DEV) for p, (a, b) in self.lora_np.items()}
+        self.ctx.lora_bwd(0, self.dY_dev, self.dX_dev, self.saved, self.dA_dev, self.dB_dev, stream=stream)
+        torch.cuda.synchronize()
+        return (self.dX_dev.cpu().numpy().reshape(self.X_np.shape),
+                {p: (self.dA_dev[p].cpu().numpy(), self.dB_dev[p].cpu().numpy()) for p in self.dA_dev})
+
+    def oracle(self):
+        sh = shapes_of(self.m)
+        Y, saved = O.layer_forward(self.X_np, self.W_np, self.lora_np, self.lora.scale, sh)
+        loss, dY = O.mse_loss(Y, self.T_np)
+        dX, grads = O.layer_backward(dY, saved, self.W_np, self.lora_np, self.lora.scale, sh)
+        return Y, loss, dY, dX, grads

@@ -1,0 +1,116 @@
+"""GPU parity of harli_lora_fwd / harli_lora_bwd against the CPU oracle (through the C ABI).
+
+Bar for every tensor (Y, dX, dA, dB): max-abs error <= 2e-2 * max|ref| and relative Frobenius
+error <= 5e-3 (bf16 storage, fp32 accumulation).  The backward pass is fed the ORACLE's dY so
+that forward error is not charged to it.
+"""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from paper_2511_11729_amd import binding as hb
+from tests.gpu_util import FinetuneCase, assert_close
+
+pytestmark = pytest.mark.gpu
+
+
+def build(idx=0, lora=None, ft=None, zero_b=False, **model_kw):
+    w = wl.workload(idx)
+    m = dataclasses.replace(w.model, dtype="bf16", **model_kw)
+    return FinetuneCase(w, m, lora or w.lora, ft or w.finetune, zero_b=zero_b)
+
+
+def check(case, what=""):
+    from tests.gpu_util import max_abs_ratio, rel_fro
+    Y = case.forward_gpu()
+    refY, loss, dY, refdX, refg = case.oracle()
+    r = {"Y": (max_abs_ratio(Y, refY), rel_fro(Y, refY))}
+    live = case.pool.stats()
+    assert live.reserved_bytes_live >= case.ctx.saved_bytes(case.ft.micro_batch, case.ft.seq_len)   # activations sit in the unified pool
+    dX, g = case.backward_gpu(dY)
+    r["dX"] = (max_abs_ratio(dX, refdX), rel_fro(dX, refdX))
+    assert set(g) == set(refg) == set(case.lora.targets)
+    for p in g:
+        r["dA_" + p] = (max_abs_ratio(g[p][0], refg[p][0]), rel_fro(g[p][0], refg[p][0]))
+        r["dB_" + p] = (max_abs_ratio(g[p][1], refg[p][1]), rel_fro(g[p][1], refg[p][1]))
+    print(what, {k: "%.1e/%.1e" % v for k, v in r.items()})
+    bad = {k: v for k, v in r.items() if not (v[0] <= 2e-2 and v[1] <= 5e-3)}      # NaN fails too
+    assert not bad, "outside max-abs <= 2e-2*max|ref|, rel-Fro <= 5e-3: %s" % bad
+    st = case.pool.stats()                                                     # polls the release events
+    assert st.tensor_blocks_live == 0 and st.small_bytes_live == 0 and st.pending_frees == 0
+    assert st.free_chunks == st.n_chunks
+    return r
+
+
+def test_config0_shapes_bf16():
+    """hidden 256, 4 x 64 heads, ffn 688, r 8 on q and v, 2 x 128 tokens."""
+    check(build(0))
+
+
+def test_all_seven_targets_and_ragged_sequence():
+    w = wl.workload(0)
+    check(build(0, lora=wl.LoraCfg(16, 32.0, wl.LORA_TARGETS), ft=wl.FinetuneCfg(3, 72)))
+
+
+@pytest.mark.parametrize("n_q,n_kv,d", [(8, 2, 64), (4, 4, 128), (8, 1, 128)])
+def test_gqa_and_head_sizes(n_q, n_kv, d):
+    check(build(0, lora=wl.LoraCfg(8, 16.0, ("q", "k", "v", "o")), ft=wl.FinetuneCfg(2, 96),
+                hidden=n_q * d // 2, n_q=n_q, n_kv=n_kv, head_dim=d, ffn=320))
+
+
+def test_long_sequence_crosses_several_tiles():
+    check(build(0, ft=wl.FinetuneCfg(1, 600), lora=wl.LoraCfg(32, 64.0, ("q", "o", "down"))))
+
+
+def test_zero_b_gives_base_output_and_zero_dA():
+    """LoRA init property on the GPU path: with B = 0 the forward equals the base model and dA = 0 exactly."""
+    case = build(0, zero_b=True)
+    Y = case.forward_gpu()
+    base = build(0, lora=dataclasses.replace(case.lora), zero_b=True)
+    refY, _, dY, _, refg = case.oracle()
+    assert_close(Y, refY, "Y")
+    dX, g = case.backward_gpu(dY)
+    for p in g:
+        assert np.all(g[p][0] == 0.0)
+        assert_close(g[p][1], refg[p][1], "dB[%s]" % p)
+
+
+def test_gradients_accumulate():
+    case = build(0)
+    case.forward_gpu()
+    _, _, dY, _, refg = case.oracle()
+    case.backward_gpu(dY)
+    case.forward_gpu()
+    _, g2 = case.backward_gpu(dY, accumulate_into=True)
+    for p in g2:
+        assert_close(g2[p][0], 2 * refg[p][0], "2 dA[%s]" % p)
+        assert_close(g2[p][1], 2 * refg[p][1], "2 dB[%s]" % p)
+
+
+def test_forward_only_release_and_oom():
+    case = build(0)
+    case.forward_gpu()
+    case.ctx.saved_release(case.saved)
+    torch.cuda.synchronize()
+    st = case.pool.stats()
+    assert st.tensor_blocks_live == 0 and st.small_bytes_live == 0
+    # a pool too small for the activations: HARLI_ERR_OOM and nothing left allocated
+    w = wl.workload(0)
+    m = dataclasses.replace(w.model, dtype="bf16")
+    tight = FinetuneCase(w, m, w.lora, w.finetune, n_chunks=2, block_bytes=64 << 10, small_pool_bytes=1 << 20)
+    with pytest.raises(hb.HarliError) as e:
+        tight.forward_gpu()
+    assert e.value.status == hb.HARLI_ERR_OOM
+    st = tight.pool.stats()
+    assert st.tensor_blocks_live == 0 and st.small_bytes_live == 0
+
+
+def test_config1_full_size_layer():
+    """The 7B-class layer: 4 x 512 tokens, r 16 on q,k,v,o."""
+    w = wl.workload(1)
+    case = FinetuneCase(w, w.model, w.lora, w.finetune)
+    r = check(case)
+    print({k: "%.1e/%.1e" % v for k, v in r.items()})
