@@ -21,6 +21,14 @@ harli_status harli_dbg_gemm(const void* A1, const void* B1, int32_t K1, const vo
                             int32_t M, int32_t N, float alpha, int32_t causal, int32_t half, void* Cb, float* Cf,
                             const float* res, void* Ct, void* hip_stream);
 
+/* Kernel timing for the benchmark.  While enabled, every launch of the finetune unit's MFMA GEMM
+ * is bracketed by two HIP events on the stream it is launched on.  harli_prof_collect waits for
+ * them (it SYNCHRONISES on those events), returns the summed algorithmic flops (2*M*N*K per
+ * launch, half of that for causal launches), the summed event-to-event milliseconds and the
+ * launch count (all host pointers), and clears the record.  Not thread-safe. */
+harli_status harli_prof_enable(int32_t on);
+harli_status harli_prof_collect(double* gemm_flops, double* gemm_ms, int64_t* gemm_launches);
+
 #ifdef __cplusplus
 }
 #endif

@@ -95,6 +95,8 @@ _SIGS = {
                                  C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_void_p]),
     "harli_saved_release": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
     "harli_saved_bytes": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_size_t)]),
+    "harli_prof_enable": (C.c_int, [C.c_int32]),
+    "harli_prof_collect": (C.c_int, [C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
     "harli_dbg_gemm": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
                                  C.c_float, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
 }
@@ -284,3 +286,14 @@ def dbg_gemm(A1, B1, *, A2=None, B2=None, alpha=1.0, causal=0, half=False, Cb=No
     K2 = A2.shape[1] if A2 is not None else 0
     _check(lib().harli_dbg_gemm(_ptr(A1), _ptr(B1), K1, _ptr(A2), _ptr(B2), K2, M, N, alpha, causal, int(half), _ptr(Cb), _ptr(Cf),
                                 _ptr(res), _ptr(Ct), _stream(stream)))
+
+
+def prof_enable(on: bool) -> None:
+    _check(lib().harli_prof_enable(int(on)))
+
+
+def prof_collect():
+    """(gemm flops, gemm milliseconds, launches) since the last call; waits for the recorded events."""
+    f, t, n = C.c_double(), C.c_double(), C.c_int64()
+    _check(lib().harli_prof_collect(C.byref(f), C.byref(t), C.byref(n)))
+    return f.value, t.value, n.value

@@ -36,3 +36,16 @@ extern "C" harli_status harli_dbg_gemm(const void* A1, const void* B1, int32_t K
   g.ldct = M;
   return gemm_launch(g, 1, static_cast<hipStream_t>(hip_stream));
 }
+
+extern "C" harli_status harli_prof_enable(int32_t on) {
+  gemm_prof_enable(on != 0);
+  return HARLI_OK;
+}
+
+extern "C" harli_status harli_prof_collect(double* gemm_flops, double* gemm_ms, int64_t* gemm_launches) {
+  if (!gemm_flops || !gemm_ms || !gemm_launches) return fail(HARLI_ERR_INVALID, "prof_collect: null argument");
+  long long n = 0;
+  harli_status s = gemm_prof_collect(gemm_flops, gemm_ms, &n);
+  *gemm_launches = n;
+  return s;
+}

@@ -48,4 +48,9 @@ struct GemmArgs {
 // Launches on `st`; batches = grid.z.  Shapes are validated (K % 8, pointers, strides % 8).
 harli_status gemm_launch(const GemmArgs& a, int batches, hipStream_t st);
 
+// Per-launch timing for the benchmark: when enabled every gemm_launch is bracketed by two events on
+// its stream; collect() waits for them and returns the summed flops, milliseconds and launch count.
+void gemm_prof_enable(bool on);
+harli_status gemm_prof_collect(double* flops, double* ms, long long* launches);
+
 }  // namespace harli

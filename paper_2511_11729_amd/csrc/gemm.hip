@@ -9,6 +9,8 @@
 // that the workgroups sharing an L2 also share operand panels.
 #include "gemm.h"
 
+#include <vector>
+
 #include "ctx.h"
 #include "device_utils.h"
 
@@ -188,6 +190,44 @@ __global__ void __launch_bounds__(256) k_gemm(GemmArgs a, int tiles_n, int tiles
 
 }  // namespace
 
+// ---- optional per-launch timing (harli_prof_*): two events around every GEMM launch ----
+namespace {
+struct ProfRec {
+  hipEvent_t e0, e1;
+  double flops;
+};
+bool g_prof_on = false;
+std::vector<ProfRec> g_prof;
+}  // namespace
+
+void gemm_prof_enable(bool on) { g_prof_on = on; }
+
+harli_status gemm_prof_collect(double* flops, double* ms, long long* launches) {
+  double f = 0.0, t = 0.0;
+  for (ProfRec& r : g_prof) {
+    HARLI_HIP(hipEventSynchronize(r.e1));
+    float dt = 0.f;
+    HARLI_HIP(hipEventElapsedTime(&dt, r.e0, r.e1));
+    f += r.flops;
+    t += dt;
+    (void)hipEventDestroy(r.e0);
+    (void)hipEventDestroy(r.e1);
+  }
+  *flops = f;
+  *ms = t;
+  *launches = (long long)g_prof.size();
+  g_prof.clear();
+  return HARLI_OK;
+}
+
+// flops the launch is asked to perform: full products for GEMM_FULL, the causal half otherwise
+static double gemm_flops(const GemmArgs& a, int batches) {
+  double k = 0;
+  for (int s = 0; s < a.nseg; ++s) k += a.seg[s].K;
+  const double f = 2.0 * a.M * (double)a.N * k * batches;
+  return a.causal == GEMM_FULL ? f : 0.5 * f;
+}
+
 harli_status gemm_launch(const GemmArgs& a, int batches, hipStream_t st) {
   if (a.M < 1 || a.N < 1 || a.nseg < 1 || a.nseg > kGemmMaxSeg || batches < 1 || a.nb1 < 1 || a.nb2 < 1)
     return fail(HARLI_ERR_INVALID, "gemm: bad shape M %d N %d nseg %d batches %d", a.M, a.N, a.nseg, batches);
@@ -208,10 +248,21 @@ harli_status gemm_launch(const GemmArgs& a, int batches, hipStream_t st) {
   }
   const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
   const int total = tiles_m * tiles_n, chunk = (total + 7) / 8;
+  ProfRec rec{};
+  if (g_prof_on) {
+    HARLI_HIP(hipEventCreate(&rec.e0));
+    HARLI_HIP(hipEventCreate(&rec.e1));
+    rec.flops = gemm_flops(a, batches);
+    HARLI_HIP(hipEventRecord(rec.e0, st));
+  }
   if (a.half)
     hipLaunchKernelGGL(k_gemm<true>, dim3(chunk * 8, 1, batches), dim3(256), LDS_BYTES, st, a, tiles_n, total, chunk);
   else
     hipLaunchKernelGGL(k_gemm<false>, dim3(chunk * 8, 1, batches), dim3(256), LDS_BYTES, st, a, tiles_n, total, chunk);
+  if (g_prof_on) {
+    HARLI_HIP(hipEventRecord(rec.e1, st));
+    g_prof.push_back(rec);
+  }
   HARLI_HIP(hipGetLastError());
   return HARLI_OK;
 }

@@ -174,7 +174,7 @@ class FinetuneCase:
     """One finetune unit (layer forward + backward) on both sides."""
 
     def __init__(self, w: wl.Workload, model: wl.ModelCfg, lora: wl.LoraCfg, ft: wl.FinetuneCfg, *,
-                 block_bytes=2 << 20, small_pool_bytes=8 << 20, zero_b=False, n_chunks=None):
+                 block_bytes=2 << 20, small_pool_bytes=8 << 20, zero_b=False, n_chunks=None, sets=1):
         self.w, self.m, self.lora, self.ft = w, model, lora, ft
         m = model
         self.W_np = wl.make_layer_weights(w, 0, m)
@@ -186,7 +186,7 @@ class FinetuneCase:
         est = (T * m.hidden * 12 + T * m.n_q * m.head_dim * 4 + T * m.n_kv * m.head_dim * 4 + T * m.ffn * 6
                + Z * ft.seq_len * ft.seq_len * 2)
         chunk = m.n_layers * 2 * block_bytes
-        n_chunks = n_chunks or (est // chunk + 4)
+        n_chunks = n_chunks or sets * (est // chunk + 4)   # `sets` micro-batches may be in flight at once
         self.slab_bytes = small_pool_bytes + n_chunks * chunk
         self.slab = torch.zeros(self.slab_bytes, dtype=torch.uint8, device=DEV)
         self.pool = hb.Pool(self.slab, self.slab_bytes, block_bytes=block_bytes, n_layers=m.n_layers,
