@@ -23,18 +23,15 @@ constexpr int A_STAGE = BM * ROWB, B_STAGE = BN * ROWB, STAGE = A_STAGE + B_STAG
 constexpr int LDS_BYTES = 2 * STAGE;
 constexpr int A_CH = BM * (BK / 8) / 256, B_CH = BN * (BK / 8) / 256;  // 16-byte chunks per thread per stage
 
-struct StageCursor {
-  int seg, k0, kend;
-};
-
 __device__ __forceinline__ void seg_range(const GemmArgs& a, int s, int m0, int* kb, int* ke) {
   const int K = a.seg[s].K;
   *kb = (a.causal == GEMM_K_FROM_M) ? (m0 / BK) * BK : 0;
   *ke = (a.causal == GEMM_K_UPTO_M) ? min(K, m0 + BM) : K;
 }
 
+// one workgroup (4 waves, one per SIMD) per CU: let each wave use the whole 512-register file
 template <bool HALF>
-__global__ void __launch_bounds__(256) k_gemm(GemmArgs a, int tiles_n, int tiles_total, int chunk) {
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) k_gemm(GemmArgs a, int tiles_n, int tiles_total, int chunk, const uint4* zero16) {
   extern __shared__ __align__(16) char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
@@ -58,91 +55,141 @@ __global__ void __launch_bounds__(256) k_gemm(GemmArgs a, int tiles_n, int tiles
 
   // per-thread chunk coordinates (same for every stage)
   const int crow = tid >> 3, ckc = (tid & 7) * 8;
-  uint4 ra[A_CH], rb[B_CH];
+  // Two register stages (sets r and q) are in flight besides the two LDS stages: a stage's global
+  // loads are issued two compute phases (~0.9 us of MFMA work) before they are written to LDS.
+  // They are named scalars, not arrays: the arrays were left in scratch memory by the compiler.
+  static_assert(A_CH == 8 && B_CH == 4, "the staging macros below are written for 8 + 4 chunks per thread");
+  uint4 ra0, ra1, ra2, ra3, ra4, ra5, ra6, ra7, rb0, rb1, rb2, rb3;
+  uint4 qa0, qa1, qa2, qa3, qa4, qa5, qa6, qa7, qb0, qb1, qb2, qb3;
+  // Row pointers of the current K segment live in registers and advance by BK per stage, so a
+  // stage's loads need no address arithmetic beyond one select: out-of-range chunks (rows past
+  // M / N, k past the segment) read a zero word instead -- selecting the ADDRESS keeps every
+  // load unconditional (zeroing the loaded register made the compiler wait for each load in turn).
+  const unsigned short* pa[A_CH];
+  const unsigned short* pb[B_CH];
+  bool oka[A_CH], okb[B_CH];
+#pragma unroll
+  for (int i = 0; i < A_CH; ++i) oka[i] = m0 + crow + i * 32 < a.M;
+#pragma unroll
+  for (int i = 0; i < B_CH; ++i) okb[i] = n0 + crow + i * 32 < a.N;
+  int seg = -1, k0 = 0, kend = 0, Kseg = 0;
 
-  StageCursor cur;
-  cur.seg = 0;
-  seg_range(a, 0, m0, &cur.k0, &cur.kend);
-  while (cur.seg < a.nseg && cur.k0 >= cur.kend) {  // skip empty segments
-    ++cur.seg;
-    if (cur.seg < a.nseg) seg_range(a, cur.seg, m0, &cur.k0, &cur.kend);
+  // (written out with macros rather than lambdas: arrays captured by reference ended up in scratch)
+#define OPEN_SEG(found)                                                                                   \
+  do {                                                                                                    \
+    for (++seg; seg < a.nseg; ++seg) {                                                                    \
+      seg_range(a, seg, m0, &k0, &kend);                                                                  \
+      if (k0 < kend) break;                                                                               \
+    }                                                                                                     \
+    (found) = seg < a.nseg;                                                                               \
+    if (found) {                                                                                          \
+      const GemmSeg& sg = a.seg[seg];                                                                     \
+      Kseg = sg.K;                                                                                        \
+      const unsigned short* A_ = sg.A + z0 * sg.a_bs0 + z1 * sg.a_bs1 + z2 * sg.a_bs2;                    \
+      const unsigned short* B_ = sg.B + z0 * sg.b_bs0 + z1 * sg.b_bs1 + z2 * sg.b_bs2;                    \
+      _Pragma("unroll") for (int i = 0; i < A_CH; ++i)                                                    \
+          pa[i] = A_ + (long long)(m0 + crow + i * 32) * sg.lda + k0 + ckc;                               \
+      _Pragma("unroll") for (int i = 0; i < B_CH; ++i)                                                    \
+          pb[i] = B_ + (long long)(n0 + crow + i * 32) * sg.ldb + k0 + ckc;                               \
+    }                                                                                                     \
+  } while (0)
+#define LDA_(S, i) S##a##i = *((kok && oka[i]) ? reinterpret_cast<const uint4*>(pa[i]) : zero16)
+#define LDB_(S, i) S##b##i = *((kok && okb[i]) ? reinterpret_cast<const uint4*>(pb[i]) : zero16)
+  // loads one stage into register set S; `valid` false (past the last stage) turns every load into a
+  // read of the zero word, so the steady-state loop needs no branch around its loads
+#define FETCH(S, valid)                                                                                   \
+  do {                                                                                                    \
+    const bool kok = (valid) && (k0 + ckc < Kseg);                                                        \
+    LDA_(S, 0); LDA_(S, 1); LDA_(S, 2); LDA_(S, 3); LDA_(S, 4); LDA_(S, 5); LDA_(S, 6); LDA_(S, 7);       \
+    LDB_(S, 0); LDB_(S, 1); LDB_(S, 2); LDB_(S, 3);                                                       \
+  } while (0)
+#define STA_(S, i) *reinterpret_cast<uint4*>(sa_ + (crow + i * 32) * ROWB + ckc * 2) = S##a##i
+#define STB_(S, i) *reinterpret_cast<uint4*>(sb_ + (crow + i * 32) * ROWB + ckc * 2) = S##b##i
+#define STASH(S, buf_)                                                                                    \
+  do {                                                                                                    \
+    char* sa_ = smem + (buf_) * STAGE;                                                                    \
+    char* sb_ = sa_ + A_STAGE;                                                                            \
+    STA_(S, 0); STA_(S, 1); STA_(S, 2); STA_(S, 3); STA_(S, 4); STA_(S, 5); STA_(S, 6); STA_(S, 7);       \
+    STB_(S, 0); STB_(S, 1); STB_(S, 2); STB_(S, 3);                                                       \
+  } while (0)
+#define ADVANCE()                                                                                         \
+  do {                                                                                                    \
+    k0 += BK;                                                                                             \
+    _Pragma("unroll") for (int i = 0; i < A_CH; ++i) pa[i] += BK;                                         \
+    _Pragma("unroll") for (int i = 0; i < B_CH; ++i) pb[i] += BK;                                         \
+    if (k0 >= kend) {                                                                                     \
+      bool f_;                                                                                            \
+      OPEN_SEG(f_);                                                                                       \
+      (void)f_;                                                                                           \
+    }                                                                                                     \
+  } while (0)
+#define COMPUTE(buf_)                                                                                     \
+  do {                                                                                                    \
+    const char* sa_ = smem + (buf_) * STAGE + (wm * 128 + (lane & 31)) * ROWB + (lane >> 5) * 16;         \
+    const char* sb_ = smem + (buf_) * STAGE + A_STAGE + (wn * 64 + (lane & 31)) * ROWB + (lane >> 5) * 16; \
+    _Pragma("unroll") for (int sub = 0; sub < BK / 16; ++sub) {                                           \
+      uint4 fa[4], fb[2];                                                                                 \
+      _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                       \
+          fa[i] = *reinterpret_cast<const uint4*>(sa_ + i * 32 * ROWB + sub * 32);                        \
+      _Pragma("unroll") for (int j = 0; j < 2; ++j)                                                       \
+          fb[j] = *reinterpret_cast<const uint4*>(sb_ + j * 32 * ROWB + sub * 32);                        \
+      _Pragma("unroll") for (int i = 0; i < 4; ++i) _Pragma("unroll") for (int j = 0; j < 2; ++j)         \
+          acc[i][j] = HALF ? __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, fa[i]),     \
+                                                                    __builtin_bit_cast(f16x8, fb[j]), acc[i][j], 0, 0, 0)  \
+                           : __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[i]),   \
+                                                                     __builtin_bit_cast(bf16x8, fb[j]), acc[i][j], 0, 0, 0); \
+    }                                                                                                     \
+  } while (0)
+  // Global loads may not be scheduled across this point (the scheduler otherwise sinks them below
+  // the MFMA block and exposes their latency); ALU, MFMA and LDS instructions may.
+#define PIN_VMEM() __builtin_amdgcn_sched_barrier(0x1 | 0x2 | 0x4 | 0x8 | 0x80 | 0x100 | 0x200)
+
+  // number of K stages over all segments
+  int n_stage = 0;
+  for (int sgi = 0; sgi < a.nseg; ++sgi) {
+    int kb, ke;
+    seg_range(a, sgi, m0, &kb, &ke);
+    if (ke > kb) n_stage += (ke - kb + BK - 1) / BK;
   }
-
-  auto fetch = [&](const StageCursor& c) {
-    const GemmSeg& sg = a.seg[c.seg];
-    const unsigned short* A = sg.A + z0 * sg.a_bs0 + z1 * sg.a_bs1 + z2 * sg.a_bs2;
-    const unsigned short* B = sg.B + z0 * sg.b_bs0 + z1 * sg.b_bs1 + z2 * sg.b_bs2;
-    const int k = c.k0 + ckc;
-    const bool kok = k < sg.K;
-    const int kc = kok ? k : sg.K - 8;  // clamp: every load stays in bounds, tails are zeroed below
-#pragma unroll
-    for (int i = 0; i < A_CH; ++i) {
-      const int r = m0 + crow + i * 32;
-      const int rc = r < a.M ? r : a.M - 1;
-      ra[i] = *reinterpret_cast<const uint4*>(A + (long long)rc * sg.lda + kc);
-      if (!kok || r >= a.M) ra[i] = make_uint4(0, 0, 0, 0);
-    }
-#pragma unroll
-    for (int i = 0; i < B_CH; ++i) {
-      const int r = n0 + crow + i * 32;
-      const int rc = r < a.N ? r : a.N - 1;
-      rb[i] = *reinterpret_cast<const uint4*>(B + (long long)rc * sg.ldb + kc);
-      if (!kok || r >= a.N) rb[i] = make_uint4(0, 0, 0, 0);
-    }
-  };
-  auto stash = [&](int buf) {
-    char* sa = smem + buf * STAGE;
-    char* sb = sa + A_STAGE;
-#pragma unroll
-    for (int i = 0; i < A_CH; ++i) *reinterpret_cast<uint4*>(sa + (crow + i * 32) * ROWB + ckc * 2) = ra[i];
-#pragma unroll
-    for (int i = 0; i < B_CH; ++i) *reinterpret_cast<uint4*>(sb + (crow + i * 32) * ROWB + ckc * 2) = rb[i];
-  };
-  auto advance = [&](StageCursor& c) {
-    c.k0 += BK;
-    while (c.seg < a.nseg && c.k0 >= c.kend) {
-      ++c.seg;
-      if (c.seg < a.nseg) seg_range(a, c.seg, m0, &c.k0, &c.kend);
-    }
-  };
-
-  if (cur.seg < a.nseg) {
-    fetch(cur);
-    stash(0);
-    advance(cur);
-  }
-  __syncthreads();
-  int buf = 0;
-  bool more = true;
-  while (more) {
-    const bool have_next = cur.seg < a.nseg;
-    if (have_next) fetch(cur);
-    const char* sa = smem + buf * STAGE + (wm * 128 + (lane & 31)) * ROWB + (lane >> 5) * 16;
-    const char* sb = smem + buf * STAGE + A_STAGE + (wn * 64 + (lane & 31)) * ROWB + (lane >> 5) * 16;
-#pragma unroll
-    for (int sub = 0; sub < BK / 16; ++sub) {
-      uint4 fa[4], fb[2];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) fa[i] = *reinterpret_cast<const uint4*>(sa + i * 32 * ROWB + sub * 32);
-#pragma unroll
-      for (int j = 0; j < 2; ++j) fb[j] = *reinterpret_cast<const uint4*>(sb + j * 32 * ROWB + sub * 32);
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-          acc[i][j] = HALF ? __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, fa[i]),
-                                                                    __builtin_bit_cast(f16x8, fb[j]), acc[i][j], 0, 0, 0)
-                           : __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[i]),
-                                                                     __builtin_bit_cast(bf16x8, fb[j]), acc[i][j], 0, 0, 0);
-    }
-    if (have_next) {
-      stash(buf ^ 1);
-      advance(cur);
-    }
-    more = have_next;
-    buf ^= 1;
+  if (n_stage > 0) {
+    bool f0;
+    OPEN_SEG(f0);
+    (void)f0;
+    FETCH(r, true);  // stage 0
+    ADVANCE();
+    FETCH(q, n_stage > 1);  // stage 1
+    ADVANCE();
+    STASH(r, 0);
     __syncthreads();
+    // Straight-line body over PAIRS of stages (no exit in the middle: with one the compiler kept two
+    // copies of the accumulators and shuffled them between register files).  At the top LDS buffer 0
+    // holds stage st, set q holds stage st+1 (in flight), the cursor points at stage st+2.  With an
+    // odd number of stages the last half-iteration multiplies a stage of zeros.
+    for (int st = 0; st < n_stage; st += 2) {
+      FETCH(r, st + 2 < n_stage);
+      ADVANCE();
+      PIN_VMEM();
+      COMPUTE(0);
+      STASH(q, 1);  // stage st+1 (zeros past the end)
+      __syncthreads();
+      FETCH(q, st + 3 < n_stage);
+      ADVANCE();
+      PIN_VMEM();
+      COMPUTE(1);
+      STASH(r, 0);  // stage st+2
+      __syncthreads();
+    }
   }
+#undef OPEN_SEG
+#undef FETCH
+#undef LDA_
+#undef LDB_
+#undef STA_
+#undef STB_
+#undef STASH
+#undef ADVANCE
+#undef COMPUTE
+#undef PIN_VMEM
 
   // ---- epilogue: lane holds rows 8*(v/4) + 4*(lane/32) + v%4 of column lane%32 of each 32x32 tile ----
   const int col_l = lane & 31, rgrp = (lane >> 5) * 4;
@@ -241,7 +288,10 @@ harli_status gemm_launch(const GemmArgs& a, int batches, hipStream_t st) {
   if (!a.Cb && !a.Cf && !a.Ct) return fail(HARLI_ERR_INVALID, "gemm: no output");
   if (a.res && !a.Cf) return fail(HARLI_ERR_INVALID, "gemm: a residual needs the fp32 output");
   static bool attr_set = false;
+  static uint4* zero16 = nullptr;  // 256 zero bytes in device memory, kept for the life of the process
   if (!attr_set) {
+    HARLI_HIP(hipMalloc(reinterpret_cast<void**>(&zero16), 256));
+    HARLI_HIP(hipMemset(zero16, 0, 256));
     HARLI_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<true>), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES));
     HARLI_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<false>), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES));
     attr_set = true;
@@ -256,9 +306,9 @@ harli_status gemm_launch(const GemmArgs& a, int batches, hipStream_t st) {
     HARLI_HIP(hipEventRecord(rec.e0, st));
   }
   if (a.half)
-    hipLaunchKernelGGL(k_gemm<true>, dim3(chunk * 8, 1, batches), dim3(256), LDS_BYTES, st, a, tiles_n, total, chunk);
+    hipLaunchKernelGGL(k_gemm<true>, dim3(chunk * 8, 1, batches), dim3(256), LDS_BYTES, st, a, tiles_n, total, chunk, zero16);
   else
-    hipLaunchKernelGGL(k_gemm<false>, dim3(chunk * 8, 1, batches), dim3(256), LDS_BYTES, st, a, tiles_n, total, chunk);
+    hipLaunchKernelGGL(k_gemm<false>, dim3(chunk * 8, 1, batches), dim3(256), LDS_BYTES, st, a, tiles_n, total, chunk, zero16);
   if (g_prof_on) {
     HARLI_HIP(hipEventRecord(rec.e1, st));
     g_prof.push_back(rec);
