@@ -43,7 +43,7 @@ struct FtWs {
   size_t bytes = 0;
   char* base = nullptr;
   float *scores = nullptr, *dP = nullptr, *ST = nullptr, *dPT = nullptr, *delta = nullptr, *dm = nullptr, *dh2 = nullptr,
-        *dx1 = nullptr, *dh = nullptr;
+        *dx1 = nullptr, *dh = nullptr, *gpart = nullptr;
   bf *vT = nullptr, *At = nullptr, *Bt = nullptr, *dyb = nullptr, *da = nullptr, *du = nullptr, *dx1b = nullptr, *dob = nullptr,
      *doT = nullptr, *dS = nullptr, *PT = nullptr, *dST = nullptr, *qT = nullptr, *kT = nullptr, *dq = nullptr, *dkq = nullptr,
      *dvq = nullptr, *dk = nullptr, *dv = nullptr, *gs = nullptr, *An = nullptr, *Bn = nullptr;
@@ -99,6 +99,7 @@ harli_status ensure_ws(harli_ctx* c, int Bf, int S) {
   const size_t o_dyb = take(T * D.H * 2), o_da = take(T * D.F * 2), o_du = take(T * D.F * 2), o_dx1b = take(T * D.H * 2);
   const size_t o_dob = take(T * D.QD * 2), o_dq = take(T * D.QD * 2), o_dkq = take(T * D.QD * 2), o_dvq = take(T * D.QD * 2);
   const size_t o_dk = take(T * D.KVD * 2), o_dv = take(T * D.KVD * 2), o_gs = take(T * D.r * 2);
+  const size_t o_gpart = take(ft_lora_grad_ws_floats((int)maxdim, D.r) * 4);
   if (off > w.bytes) {
     if (w.base) HARLI_HIP(hipFree(w.base));
     w.base = nullptr;
@@ -114,6 +115,7 @@ harli_status ensure_ws(harli_ctx* c, int Bf, int S) {
   w.At = (bf*)(b + o_At); w.Bt = (bf*)(b + o_Bt); w.dyb = (bf*)(b + o_dyb); w.da = (bf*)(b + o_da); w.du = (bf*)(b + o_du);
   w.dx1b = (bf*)(b + o_dx1b); w.dob = (bf*)(b + o_dob); w.dq = (bf*)(b + o_dq); w.dkq = (bf*)(b + o_dkq);
   w.dvq = (bf*)(b + o_dvq); w.dk = (bf*)(b + o_dk); w.dv = (bf*)(b + o_dv); w.gs = (bf*)(b + o_gs);
+  w.gpart = (float*)(b + o_gpart);
   w.An = (bf*)(b + o_An); w.Bn = (bf*)(b + o_Bn); w.scale = (float*)(b + o_scale);
   w.Bf = Bf;
   w.S = S;
@@ -170,8 +172,8 @@ harli_status proj_grads(harli_ctx* c, const LayerDev& L, int t, const bf* dy, co
   ft_from_bf16(static_cast<const bf*>(L.B[t]), w.Bn, (long long)r * out, st);
   ft_from_bf16(static_cast<const bf*>(L.A[t]), w.An, (long long)in * r, st);
   ft_skinny_nt(dy, out, w.Bn, out, w.gs, r, T, r, out, lscale(c), st);        // gs = s * dy . B^T   (carries sigma)
-  ft_lora_grad(xin, in, w.gs, r, dA[t], r, 1, T, in, r, w.scale + 1, st);     // dA += x^T gs / sigma
-  ft_lora_grad(dy, out, sv->us[t], r, dB[t], 1, out, T, out, r, w.scale + 1, st);  // dB += us^T dy / sigma
+  ft_lora_grad(xin, in, w.gs, r, dA[t], r, 1, T, in, r, w.scale + 1, w.gpart, st);     // dA += x^T gs / sigma
+  ft_lora_grad(dy, out, sv->us[t], r, dB[t], 1, out, T, out, r, w.scale + 1, w.gpart, st);  // dB += us^T dy / sigma
   return HARLI_OK;
 }
 

@@ -44,9 +44,12 @@ void ft_attn_ds_t(const float* ST, const float* dPT, const float* lse, const flo
 // skinny NT GEMM: C[M, N] = alpha * X[M, K] . Bm[N, K]^T, N <= 64 and N % 16 == 0 after padding by the caller's layout
 void ft_skinny_nt(const bf* X, long long ldx, const bf* Bm, long long ldb, bf* C, long long ldc, int M, int N, int K,
                   float alpha, hipStream_t st);
-// G[j*sj + r*sr] += sum_t X[t][j] * U[t][r]   (fp32 atomics), X [T, J] bf16, U [T, R] bf16, R <= 64
+// G[j*sj + r*sr] += out_mul * sum_t X[t][j] * U[t][r];  X [T, J] and U [T, R] 16-bit, R in {8, 16, 32, 64}, J even,
+// one of sj, sr equal to 1.  `part` is scratch of ft_lora_grad_ws_floats(J, R) floats; G is read and written
+// without atomics, so no other work may update it concurrently.
+size_t ft_lora_grad_ws_floats(int J, int R);
 void ft_lora_grad(const bf* X, long long ldx, const bf* U, long long ldu, float* G, long long sj, long long sr, int T, int J,
-                  int R, const float* out_mul, hipStream_t st);
+                  int R, const float* out_mul, float* part, hipStream_t st);
 // sum GQA query-head groups: dk[T][n_kv*d] = sum_g dkq[T][(c*G+g)*d + e]
 void ft_sum_groups(const bf* in, bf* out, int T, int n_kv, int G, int d, hipStream_t st);
 }  // namespace harli

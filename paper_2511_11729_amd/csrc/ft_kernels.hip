@@ -4,6 +4,8 @@
 // with 8- or 16-byte accesses.
 #include "ft_kernels.h"
 
+#include <algorithm>
+
 #include "ft_elem.h"
 
 namespace harli {
@@ -169,14 +171,24 @@ __global__ void __launch_bounds__(256) k_from_bf16(const bf* in, bf* out, long l
 // largest magnitude to 2^8 before it is rounded to 16 bits, and 1/sigma is applied where the
 // fp32 results leave the unit (dX, dA, dB).  scale[0] = sigma, scale[1] = 1/sigma.
 __global__ void __launch_bounds__(256) k_amax(const float* x, long long n4, unsigned* amax_bits) {
+  // grid-stride over groups of 1024 float4, four independent 16-byte loads per thread in flight (indices past the
+  // end re-read the last element); one atomic per workgroup (same-address atomics serialise)
+  __shared__ float wmax[4];
   float m = 0.f;
-  for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n4; i += (long long)gridDim.x * 256) {
-    const float4 v = reinterpret_cast<const float4*>(x)[i];
-    m = fmaxf(fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))), m);
+  for (long long base = (long long)blockIdx.x * 1024 + threadIdx.x; base < n4; base += (long long)gridDim.x * 1024) {
+    float4 v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) v[u] = reinterpret_cast<const float4*>(x)[min(base + u * 256, n4 - 1)];
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      m = fmaxf(fmaxf(fmaxf(fabsf(v[u].x), fabsf(v[u].y)), fmaxf(fabsf(v[u].z), fabsf(v[u].w))), m);
   }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
-  if ((threadIdx.x & 63) == 0) atomicMax(amax_bits, __float_as_uint(m));  // non-negative floats order like their bits
+  if ((threadIdx.x & 63) == 0) wmax[threadIdx.x >> 6] = m;
+  __syncthreads();
+  if (threadIdx.x == 0)
+    atomicMax(amax_bits, __float_as_uint(fmaxf(fmaxf(wmax[0], wmax[1]), fmaxf(wmax[2], wmax[3]))));  // non-negative floats order like their bits
 }
 __global__ void k_scale_reset(unsigned* amax_bits) { *amax_bits = 0u; }
 __global__ void k_scale_make(const unsigned* amax_bits, float* scale) {
@@ -309,31 +321,65 @@ __global__ void __launch_bounds__(256) k_skinny_nt(const bf* X, long long ldx, c
 }
 
 // ---------------------------------------------------------------- adapter gradients: G[j, r] += sum_t X[t, j] U[t, r]
+// Two passes without atomics.  Pass 1: a workgroup covers 512 j x one token chunk; each thread owns two adjacent j
+// and all R ranks.  The U rows are widened to fp32 in LDS 64 tokens at a time and read as wave-wide broadcasts; X is
+// read as one 32-bit word per lane and token, eight tokens in flight (rows past the chunk reuse its last row against
+// zero U rows).  The chunk's sums go to part[chunk][r][j].  Pass 2 adds the chunks and accumulates into G.
+constexpr int kLgT = 64, kLgMaxChunks = 32;
 template <int R>
-__global__ void __launch_bounds__(256) k_lora_grad(const bf* X, long long ldx, const bf* U, long long ldu, float* G,
-                                                   long long sj, long long sr, int T, int J, int tchunk,
-                                                   const float* out_mul) {
-  const int j = blockIdx.x * 256 + threadIdx.x;
-  const int t0 = blockIdx.y * tchunk, t1 = min(T, t0 + tchunk);
-  float acc[R];
+__global__ void __launch_bounds__(256) k_lora_grad_part(const bf* X, long long ldx, const bf* U, long long ldu, float* part,
+                                                        int T, int J, int tpc) {
+  __shared__ __align__(16) float us[kLgT][R];
+  const int tid = threadIdx.x;
+  const int j0 = (blockIdx.x * 256 + tid) * 2;
+  const int c0 = blockIdx.y * tpc, c1 = min(T, c0 + tpc);
+  float a0[R], a1[R];
 #pragma unroll
-  for (int r = 0; r < R; ++r) acc[r] = 0.f;
-  const int jc = min(j, J - 1);
-  for (int t = t0; t < t1; ++t) {
-    const float xv = E2F(X[(long long)t * ldx + jc]);
-    const bf* u = U + (long long)t * ldu;  // uniform over the workgroup: scalar loads
+  for (int r = 0; r < R; ++r) a0[r] = a1[r] = 0.f;
+  for (int t0 = c0; t0 < c1; t0 += kLgT) {
+    const int nt = min(kLgT, c1 - t0);
+    __syncthreads();
+    for (int i = tid; i < kLgT * R; i += 256) {
+      const int t = i / R, r = i - t * R;
+      us[t][r] = t < nt ? E2F(U[(long long)(t0 + t) * ldu + r]) : 0.f;
+    }
+    __syncthreads();
+    const bf* xp = X + (long long)t0 * ldx + min(j0, J - 2);
+    for (int t = 0; t < kLgT; t += 8) {
+      unsigned xv[8];
 #pragma unroll
-    for (int r = 0; r < R; r += 2) {
-      const unsigned w = *reinterpret_cast<const unsigned*>(u + r);
-      acc[r] += xv * E2F((unsigned short)(w & 0xffffu));
-      acc[r + 1] += xv * E2F((unsigned short)(w >> 16));
+      for (int u = 0; u < 8; ++u) xv[u] = *reinterpret_cast<const unsigned*>(xp + (long long)min(t + u, nt - 1) * ldx);
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const float x0 = E2F((unsigned short)(xv[u] & 0xffffu)), x1 = E2F((unsigned short)(xv[u] >> 16));
+#pragma unroll
+        for (int r = 0; r < R; r += 4) {
+          const float4 uv = *reinterpret_cast<const float4*>(&us[t + u][r]);
+          a0[r] += x0 * uv.x, a0[r + 1] += x0 * uv.y, a0[r + 2] += x0 * uv.z, a0[r + 3] += x0 * uv.w;
+          a1[r] += x1 * uv.x, a1[r + 1] += x1 * uv.y, a1[r + 2] += x1 * uv.z, a1[r + 3] += x1 * uv.w;
+        }
+      }
     }
   }
-  if (j < J) {
-    const float om = out_mul ? *out_mul : 1.f;
+  if (j0 < J) {
+    float* p = part + (long long)blockIdx.y * R * J + j0;
 #pragma unroll
-    for (int r = 0; r < R; ++r) atomicAdd(G + (long long)j * sj + (long long)r * sr, acc[r] * om);
+    for (int r = 0; r < R; ++r) *reinterpret_cast<float2*>(p + (long long)r * J) = make_float2(a0[r], a1[r]);
   }
+}
+
+// G[j*sj + r*sr] += out_mul * sum_c part[c][r][j]: one thread per (r, j), lanes along j (the reads of part, 2 x
+// nchunk times the volume of G, are the contiguous side)
+__global__ void __launch_bounds__(256) k_lora_grad_reduce(const float* part, int nchunk, float* G, long long sj, long long sr,
+                                                          int J, long long RJ, const float* out_mul) {
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= RJ) return;
+  const int r = (int)(i / J), j = (int)(i - (long long)r * J);
+  float sum = 0.f;
+#pragma unroll 8
+  for (int c = 0; c < nchunk; ++c) sum += part[c * RJ + i];
+  float* g = G + (long long)j * sj + (long long)r * sr;
+  *g += sum * (out_mul ? *out_mul : 1.f);
 }
 
 __global__ void __launch_bounds__(256) k_sum_groups(const bf* in, bf* out, long long total, int n_kv, int G, int d) {
@@ -388,7 +434,7 @@ void ft_from_bf16(const bf* in, bf* out, long long n, hipStream_t st) {
 void ft_make_scale(const float* x, long long n, float* scale, hipStream_t st) {
   unsigned* bits = reinterpret_cast<unsigned*>(scale + 2);
   hipLaunchKernelGGL(k_scale_reset, dim3(1), dim3(1), 0, st, bits);
-  hipLaunchKernelGGL(k_amax, dim3(1024), dim3(256), 0, st, x, n / 4, bits);
+  hipLaunchKernelGGL(k_amax, dim3(std::min(nblk(n / 4, 1024), 1024u)), dim3(256), 0, st, x, n / 4, bits);
   hipLaunchKernelGGL(k_scale_make, dim3(1), dim3(1), 0, st, bits, scale);
 }
 void ft_transpose_heads(const bf* in, bf* out, int Bf, int S, int heads, int d, hipStream_t st) {
@@ -416,14 +462,22 @@ void ft_skinny_nt(const bf* X, long long ldx, const bf* Bm, long long ldb, bf* C
   else if (nt == 2) hipLaunchKernelGGL(k_skinny_nt<2>, grid, blk, 0, st, X, ldx, Bm, ldb, C, ldc, M, N, K, alpha);
   else hipLaunchKernelGGL(k_skinny_nt<4>, grid, blk, 0, st, X, ldx, Bm, ldb, C, ldc, M, N, K, alpha);
 }
+size_t ft_lora_grad_ws_floats(int J, int R) { return (size_t)kLgMaxChunks * J * R; }
+template <int R>
+static void lora_grad_launch(const bf* X, long long ldx, const bf* U, long long ldu, float* G, long long sj, long long sr, int T,
+                             int J, const float* out_mul, float* part, hipStream_t st) {
+  const int tpc = std::max(kLgT, ((T + kLgMaxChunks - 1) / kLgMaxChunks + kLgT - 1) / kLgT * kLgT);
+  const int nchunk = (T + tpc - 1) / tpc;
+  hipLaunchKernelGGL(k_lora_grad_part<R>, dim3((J + 511) / 512, nchunk), dim3(256), 0, st, X, ldx, U, ldu, part, T, J, tpc);
+  hipLaunchKernelGGL(k_lora_grad_reduce, dim3(nblk((long long)R * J, 256)), dim3(256), 0, st, part, nchunk, G, sj, sr, J, (long long)R * J,
+                     out_mul);
+}
 void ft_lora_grad(const bf* X, long long ldx, const bf* U, long long ldu, float* G, long long sj, long long sr, int T, int J,
-                  int R, const float* out_mul, hipStream_t st) {
-  const int tchunk = 128;
-  const dim3 grid((J + 255) / 256, (T + tchunk - 1) / tchunk), blk(256);
-  if (R <= 8) hipLaunchKernelGGL(k_lora_grad<8>, grid, blk, 0, st, X, ldx, U, ldu, G, sj, sr, T, J, tchunk, out_mul);
-  else if (R <= 16) hipLaunchKernelGGL(k_lora_grad<16>, grid, blk, 0, st, X, ldx, U, ldu, G, sj, sr, T, J, tchunk, out_mul);
-  else if (R <= 32) hipLaunchKernelGGL(k_lora_grad<32>, grid, blk, 0, st, X, ldx, U, ldu, G, sj, sr, T, J, tchunk, out_mul);
-  else hipLaunchKernelGGL(k_lora_grad<64>, grid, blk, 0, st, X, ldx, U, ldu, G, sj, sr, T, J, tchunk, out_mul);
+                  int R, const float* out_mul, float* part, hipStream_t st) {
+  if (R == 8) lora_grad_launch<8>(X, ldx, U, ldu, G, sj, sr, T, J, out_mul, part, st);
+  else if (R == 16) lora_grad_launch<16>(X, ldx, U, ldu, G, sj, sr, T, J, out_mul, part, st);
+  else if (R == 32) lora_grad_launch<32>(X, ldx, U, ldu, G, sj, sr, T, J, out_mul, part, st);
+  else lora_grad_launch<64>(X, ldx, U, ldu, G, sj, sr, T, J, out_mul, part, st);
 }
 void ft_sum_groups(const bf* in, bf* out, int T, int n_kv, int G, int d, hipStream_t st) {
   const long long total = (long long)T * n_kv * d;
