@@ -46,7 +46,7 @@ struct FtWs {
         *dx1 = nullptr, *dh = nullptr, *gpart = nullptr;
   bf *vT = nullptr, *At = nullptr, *Bt = nullptr, *dyb = nullptr, *da = nullptr, *du = nullptr, *dx1b = nullptr, *dob = nullptr,
      *doT = nullptr, *dS = nullptr, *PT = nullptr, *dST = nullptr, *qT = nullptr, *kT = nullptr, *dq = nullptr, *dkq = nullptr,
-     *dvq = nullptr, *dk = nullptr, *dv = nullptr, *gs = nullptr, *An = nullptr, *Bn = nullptr;
+     *dvq = nullptr, *dk = nullptr, *dv = nullptr, *gs[3] = {}, *An[3] = {}, *Bn = nullptr;
   float* scale = nullptr;  // [0] sigma, [1] 1/sigma, [2] scratch: gradient scaling of the backward pass
   int Bf = 0, S = 0;
 };
@@ -95,10 +95,10 @@ harli_status ensure_ws(harli_ctx* c, int Bf, int S) {
   const size_t o_dm = take(T * D.F * 4), o_dh2 = take(T * D.H * 4), o_dx1 = take(T * D.H * 4), o_dh = take(T * D.H * 4);
   const size_t o_vT = take(T * D.KVD * 2), o_kT = take(T * D.KVD * 2), o_qT = take(T * D.QD * 2), o_doT = take(T * D.QD * 2);
   const size_t o_At = take(maxdim * D.r * 2), o_Bt = take(maxdim * D.r * 2);
-  const size_t o_An = take(maxdim * D.r * 2), o_Bn = take(maxdim * D.r * 2), o_scale = take(64);
+  const size_t o_An = take(3 * al(maxdim * D.r * 2)), o_Bn = take(maxdim * D.r * 2), o_scale = take(64);
   const size_t o_dyb = take(T * D.H * 2), o_da = take(T * D.F * 2), o_du = take(T * D.F * 2), o_dx1b = take(T * D.H * 2);
   const size_t o_dob = take(T * D.QD * 2), o_dq = take(T * D.QD * 2), o_dkq = take(T * D.QD * 2), o_dvq = take(T * D.QD * 2);
-  const size_t o_dk = take(T * D.KVD * 2), o_dv = take(T * D.KVD * 2), o_gs = take(T * D.r * 2);
+  const size_t o_dk = take(T * D.KVD * 2), o_dv = take(T * D.KVD * 2), o_gs = take(3 * al(T * D.r * 2));
   const size_t o_gpart = take(ft_lora_grad_ws_floats((int)maxdim, D.r) * 4);
   if (off > w.bytes) {
     if (w.base) HARLI_HIP(hipFree(w.base));
@@ -114,9 +114,11 @@ harli_status ensure_ws(harli_ctx* c, int Bf, int S) {
   w.vT = (bf*)(b + o_vT); w.kT = (bf*)(b + o_kT); w.qT = (bf*)(b + o_qT); w.doT = (bf*)(b + o_doT);
   w.At = (bf*)(b + o_At); w.Bt = (bf*)(b + o_Bt); w.dyb = (bf*)(b + o_dyb); w.da = (bf*)(b + o_da); w.du = (bf*)(b + o_du);
   w.dx1b = (bf*)(b + o_dx1b); w.dob = (bf*)(b + o_dob); w.dq = (bf*)(b + o_dq); w.dkq = (bf*)(b + o_dkq);
-  w.dvq = (bf*)(b + o_dvq); w.dk = (bf*)(b + o_dk); w.dv = (bf*)(b + o_dv); w.gs = (bf*)(b + o_gs);
+  w.dvq = (bf*)(b + o_dvq); w.dk = (bf*)(b + o_dk); w.dv = (bf*)(b + o_dv); 
+  for (int i = 0; i < 3; ++i) w.gs[i] = (bf*)(b + o_gs + i * al(T * D.r * 2));
   w.gpart = (float*)(b + o_gpart);
-  w.An = (bf*)(b + o_An); w.Bn = (bf*)(b + o_Bn); w.scale = (float*)(b + o_scale);
+  for (int i = 0; i < 3; ++i) w.An[i] = (bf*)(b + o_An + i * al(maxdim * D.r * 2));
+  w.Bn = (bf*)(b + o_Bn); w.scale = (float*)(b + o_scale);
   w.Bf = Bf;
   w.S = S;
   return HARLI_OK;
@@ -162,17 +164,18 @@ harli_status proj_fwd(harli_ctx* c, const LayerDev& L, int t, const bf* xin, int
 }
 
 // adapter gradients of one projection given dy (bf16 [T, out]) and its input xin (bf16 [T, in]);
-// leaves gs = s * dy . B^T in ws.gs and A (compute element, [in, r]) in ws.An for the caller's dx GEMM
-harli_status proj_grads(harli_ctx* c, const LayerDev& L, int t, const bf* dy, const bf* xin, int T, const harli_saved* sv,
-                        float* const* dA, float* const* dB, hipStream_t st) {
+// leaves gs = s * dy . B^T in ws.gs[slot] and A (compute element, [in, r]) in ws.An[slot]: the caller adds them
+// to its dx GEMM as one more K segment (dx += gs . A^T)
+harli_status proj_grads(harli_ctx* c, const LayerDev& L, int t, int slot, const bf* dy, const bf* xin, int T,
+                        const harli_saved* sv, float* const* dA, float* const* dB, hipStream_t st) {
   int out, in;
   proj_shape(c->cfg, t, &out, &in);
   FtWs& w = state(c)->ws;
   const int r = c->lora.rank;
   ft_from_bf16(static_cast<const bf*>(L.B[t]), w.Bn, (long long)r * out, st);
-  ft_from_bf16(static_cast<const bf*>(L.A[t]), w.An, (long long)in * r, st);
-  ft_skinny_nt(dy, out, w.Bn, out, w.gs, r, T, r, out, lscale(c), st);        // gs = s * dy . B^T   (carries sigma)
-  ft_lora_grad(xin, in, w.gs, r, dA[t], r, 1, T, in, r, w.scale + 1, w.gpart, st);     // dA += x^T gs / sigma
+  ft_from_bf16(static_cast<const bf*>(L.A[t]), w.An[slot], (long long)in * r, st);
+  ft_skinny_nt(dy, out, w.Bn, out, w.gs[slot], r, T, r, out, lscale(c), st);        // gs = s * dy . B^T   (carries sigma)
+  ft_lora_grad(xin, in, w.gs[slot], r, dA[t], r, 1, T, in, r, w.scale + 1, w.gpart, st);     // dA += x^T gs / sigma
   ft_lora_grad(dy, out, sv->us[t], r, dB[t], 1, out, T, out, r, w.scale + 1, w.gpart, st);  // dB += us^T dy / sigma
   return HARLI_OK;
 }
@@ -470,8 +473,8 @@ extern "C" harli_status harli_lora_bwd(harli_ctx* c, int32_t layer, const float*
     GemmArgs g = plain_gemm(T, D.F);  // dm = dy Wd (+ gs A_d^T)
     add_seg(g, w.dyb, D.H, static_cast<const bf*>(L.wt[6]), D.H, D.H);
     if (adapted(c, 6)) {
-      RUNB(proj_grads(c, L, 6, w.dyb, sv->m, T, sv, dA, dB, st));
-      add_seg(g, w.gs, D.r, w.An, D.r, D.r);
+      RUNB(proj_grads(c, L, 6, 0, w.dyb, sv->m, T, sv, dA, dB, st));
+      add_seg(g, w.gs[0], D.r, w.An[0], D.r, D.r);
     }
     g.Cf = w.dm; g.ldcf = D.F;
     RUNB(gemm_launch(g, 1, st));
@@ -481,16 +484,13 @@ extern "C" harli_status harli_lora_bwd(harli_ctx* c, int32_t layer, const float*
     GemmArgs g = plain_gemm(T, D.H);  // dh2 = da Wg + du Wu
     add_seg(g, w.da, D.F, static_cast<const bf*>(L.wt[4]), D.F, D.F);
     add_seg(g, w.du, D.F, static_cast<const bf*>(L.wt[5]), D.F, D.F);
+    for (int t = 4; t <= 5; ++t)
+      if (adapted(c, t)) {  // dh2 += gs_t A_t^T as one more K segment
+        RUNB(proj_grads(c, L, t, t - 4, t == 4 ? w.da : w.du, sv->h2, T, sv, dA, dB, st));
+        add_seg(g, w.gs[t - 4], D.r, w.An[t - 4], D.r, D.r);
+      }
     g.Cf = w.dh2; g.ldcf = D.H;
     RUNB(gemm_launch(g, 1, st));
-    for (int t = 4; t <= 5; ++t)
-      if (adapted(c, t)) {  // dh2 += gs_t A_t^T
-        RUNB(proj_grads(c, L, t, t == 4 ? w.da : w.du, sv->h2, T, sv, dA, dB, st));
-        GemmArgs g2 = plain_gemm(T, D.H);
-        add_seg(g2, w.gs, D.r, w.An, D.r, D.r);
-        g2.Cf = w.dh2; g2.ldcf = D.H; g2.res = w.dh2;
-        RUNB(gemm_launch(g2, 1, st));
-      }
   }
   ft_rmsnorm_bwd(w.dh2, sv->x1, sv->rho2, L.g2, dY, w.dx1, T, D.H, w.scale, nullptr, st);
   // ---- attention output projection ----
@@ -499,8 +499,8 @@ extern "C" harli_status harli_lora_bwd(harli_ctx* c, int32_t layer, const float*
     GemmArgs g = plain_gemm(T, D.QD);  // do = dx1 Wo
     add_seg(g, w.dx1b, D.H, static_cast<const bf*>(L.wt[3]), D.H, D.H);
     if (adapted(c, 3)) {
-      RUNB(proj_grads(c, L, 3, w.dx1b, sv->o, T, sv, dA, dB, st));
-      add_seg(g, w.gs, D.r, w.An, D.r, D.r);
+      RUNB(proj_grads(c, L, 3, 0, w.dx1b, sv->o, T, sv, dA, dB, st));
+      add_seg(g, w.gs[0], D.r, w.An[0], D.r, D.r);
     }
     g.Cb = w.dob; g.ldcb = D.QD;
     RUNB(gemm_launch(g, 1, st));
@@ -600,17 +600,14 @@ extern "C" harli_status harli_lora_bwd(harli_ctx* c, int32_t layer, const float*
     add_seg(g, w.dq, D.QD, static_cast<const bf*>(L.wt[0]), D.QD, D.QD);
     add_seg(g, dk, D.KVD, static_cast<const bf*>(L.wt[1]), D.KVD, D.KVD);
     add_seg(g, dv, D.KVD, static_cast<const bf*>(L.wt[2]), D.KVD, D.KVD);
-    g.Cf = w.dh; g.ldcf = D.H;
-    RUNB(gemm_launch(g, 1, st));
     const bf* dys[3] = {w.dq, dk, dv};
     for (int t = 0; t < 3; ++t)
-      if (adapted(c, t)) {
-        RUNB(proj_grads(c, L, t, dys[t], sv->h, T, sv, dA, dB, st));
-        GemmArgs g2 = plain_gemm(T, D.H);
-        add_seg(g2, w.gs, D.r, w.An, D.r, D.r);
-        g2.Cf = w.dh; g2.ldcf = D.H; g2.res = w.dh;
-        RUNB(gemm_launch(g2, 1, st));
+      if (adapted(c, t)) {  // dh += gs_t A_t^T as one more K segment
+        RUNB(proj_grads(c, L, t, t, dys[t], sv->h, T, sv, dA, dB, st));
+        add_seg(g, w.gs[t], D.r, w.An[t], D.r, D.r);
       }
+    g.Cf = w.dh; g.ldcf = D.H;
+    RUNB(gemm_launch(g, 1, st));
   }
   ft_rmsnorm_bwd(w.dh, sv->X, sv->rho1, L.g1, w.dx1, dX, T, D.H, nullptr, w.scale + 1, st);
   HARLI_HIP(hipGetLastError());

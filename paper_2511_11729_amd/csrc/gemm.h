@@ -1,6 +1,6 @@
 // 16-bit MFMA GEMM used by the finetune unit:  C[z] = alpha * sum_s A_s[z] . B_s[z]^T  (+ res)
 // Every operand is "NT": A_s is [M, K_s] and B_s is [N, K_s], both row-major with the
-// contraction index contiguous.  Up to four K segments accumulate into one output, which is
+// contraction index contiguous.  Up to six K segments accumulate into one output, which is
 // how the LoRA path rides on the base GEMM (y = [x | s*xA] . [W | B^T]^T, Sec. 2.1 LoRA) and
 // how gradients that sum over several projections are formed in one pass.
 #pragma once
@@ -10,7 +10,7 @@
 
 namespace harli {
 
-constexpr int kGemmMaxSeg = 4;
+constexpr int kGemmMaxSeg = 6;
 
 struct GemmSeg {
   const unsigned short* A;  // bf16 [M, K], row stride lda
