@@ -38,6 +38,7 @@ struct DecodeWs {
   float* att_part = nullptr;  // [bpad][n_q][max_chunks][d+2]
   int* att_cnt = nullptr;     // [bpad][n_kv]
   float* scores = nullptr;    // fp32 path only: [bpad][n_q][max_seq_len]
+  float *fk = nullptr, *fv = nullptr, *fa = nullptr, *fu = nullptr;  // fp32 path only: k, v [bpad, n_kv*d]; gate, up [bpad, ffn]
   int* err_flag = nullptr;    // device int set when a kernel sees an out-of-range page id
   int max_chunks = 0;
 };

@@ -132,7 +132,13 @@ extern "C" harli_status harli_ctx_create(const harli_model_cfg* cfg, const harli
   TRY(dev_alloc(&d.att_cnt, bp * m.n_kv_heads * 4, true));
   TRY(dev_alloc(&d.err_flag, 16, true));
   // fp32 path: scratch for attention scores, one row of max_seq_len per (sequence, query head)
-  if (m.dtype == HARLI_F32) TRY(dev_alloc(&d.scores, bp * m.n_q_heads * (size_t)m.max_seq_len * 4, true));
+  if (m.dtype == HARLI_F32) {
+    TRY(dev_alloc(&d.scores, bp * m.n_q_heads * (size_t)m.max_seq_len * 4, true));
+    TRY(dev_alloc(&d.fk, bp * m.n_kv_heads * m.head_dim * 4, true));
+    TRY(dev_alloc(&d.fv, bp * m.n_kv_heads * m.head_dim * 4, true));
+    TRY(dev_alloc(&d.fa, bp * m.ffn * 4, true));
+    TRY(dev_alloc(&d.fu, bp * m.ffn * 4, true));
+  }
   // decode-private pre-shuffled weights (bf16 path): the inference instance keeps its own copy
   if (m.dtype == HARLI_BF16) {
     const int KVD = m.n_kv_heads * m.head_dim;
@@ -165,7 +171,7 @@ extern "C" harli_status harli_ctx_create(const harli_model_cfg* cfg, const harli
 extern "C" void harli_ctx_destroy(harli_ctx* c) {
   if (!c) return;
   DecodeWs& d = c->dw;
-  void* bufs[] = {d.hx1, d.obuf, d.hx2, d.mbuf, d.qbuf, d.x1, d.xa, d.xb, d.ssq, d.rope, d.att_part, d.att_cnt, d.err_flag, d.scores, d.inv_freq};
+  void* bufs[] = {d.hx1, d.obuf, d.hx2, d.mbuf, d.qbuf, d.x1, d.xa, d.xb, d.ssq, d.rope, d.att_part, d.att_cnt, d.err_flag, d.scores, d.inv_freq, d.fk, d.fv, d.fa, d.fu};
   for (void* p : bufs)
     if (p) (void)hipFree(p);
   for (LayerDev& ld : c->layers)

@@ -156,8 +156,9 @@ class DecodeCase:
             return O.decode_model_paged(self.x_np, self.layers_np, None, sh, kv, self.kv_len, self.table)
         return O.decode_model_paged(np.asarray(token_ids), self.layers_np, self.extras_np, sh, kv, self.kv_len, self.table)
 
-    def check_cache(self, tol_ratio=2e-2):
-        """Appended K/V: exactly the oracle's positions changed (bit-exact indexing), values within the bf16 bar."""
+    def check_cache(self, tol_ratio=2e-2, fro=5e-3):
+        """Appended K/V: exactly the oracle's positions changed (bit-exact indexing), values within the bar
+        (default: the bf16 one)."""
         img1 = self.slab_image()
         changed_gpu = np.flatnonzero(img1 != self.img0)
         ref = self.okv.slab
@@ -166,7 +167,7 @@ class DecodeCase:
         got = self._decode_img(img1)[changed_ref]
         want = ref[changed_ref]
         assert np.max(np.abs(got - want)) <= tol_ratio * np.max(np.abs(want))
-        assert rel_fro(got, want) <= 5e-3
+        assert rel_fro(got, want) <= fro
         return len(changed_ref)
 
 

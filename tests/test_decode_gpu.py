@@ -21,12 +21,19 @@ def variant(idx, **kw):
     return w, dataclasses.replace(w.model, **kw)
 
 
+# fp32 storage and arithmetic: unit round-off 6e-8, dot products of up to ~700 terms summed lane-wise then by a
+# butterfly (error ~ sqrt(K) u), seven chained steps and an fp32 exp -- 1e-4 of the largest output and 2e-5 in
+# relative Frobenius norm leave a factor ~10 of slack.
+F32_BAR = dict(max_ratio=1e-4, fro=2e-5)
+
+
 def run_case(w, m, lengths, **kw):
     case = DecodeCase(w, m, np.asarray(lengths, np.int32), **kw)
     y = case.run_gpu()
     ref = case.run_oracle()
-    stats = assert_close(y, ref, "decode output")
-    n = case.check_cache()
+    bar = F32_BAR if m.dtype == "f32" else {}
+    stats = assert_close(y, ref, "decode output", **bar)
+    n = case.check_cache(*((1e-4, 2e-5) if m.dtype == "f32" else ()))
     assert n == len(lengths) * m.n_layers * 2 * m.n_kv * m.head_dim
     return case, stats
 
@@ -135,3 +142,44 @@ def test_two_steps_in_a_row_use_the_appended_token():
     from tests.gpu_util import shapes_of
     ref2 = O.decode_model_paged(ref1.astype(np.float32), case.layers_np, None, shapes_of(m), case.okv, lengths + 1, case.table)
     assert_close(case.y_dev.cpu().numpy(), ref2, "step 2")
+
+
+# ---- fp32 storage (config 0 as written): every tensor fp32, generic kernels without tile restrictions ----
+
+def test_config0_fp32_as_written():
+    w = wl.workload(0)
+    assert w.model.dtype == "f32"
+    case, stats = run_case(w, w.model, wl.draw_lengths(w), block_bytes=64 << 10)
+    print("config 0 fp32 decode parity: max-abs ratio %.2e, rel-Fro %.2e" % stats)
+
+
+@pytest.mark.parametrize("lengths", [[0], [0, 1, 15, 16, 17], [255, 256, 257], [31] * 17, list(range(5, 105, 9))])
+def test_fp32_edge_lengths_and_batches(lengths):
+    """Empty cache, page boundaries, a batch that spans three 8-row tiles."""
+    w = wl.workload(0)
+    run_case(w, w.model, lengths, block_bytes=128 << 10)
+
+
+@pytest.mark.parametrize("hidden,n_q,n_kv,d,ffn", [(200, 6, 2, 20, 333), (96, 3, 1, 34, 70), (320, 2, 2, 160, 64)])
+def test_fp32_arbitrary_shapes(hidden, n_q, n_kv, d, ffn):
+    """Shapes that are multiples of nothing: grouped heads, head sizes above and below a wave, odd widths."""
+    w, m = variant(0, hidden=hidden, n_q=n_q, n_kv=n_kv, head_dim=d, ffn=ffn)
+    run_case(w, m, [0, 37, 130, 16], block_bytes=64 << 10)
+
+
+def test_fp32_three_layer_model_with_embedding_and_logits():
+    w, m = variant(0, n_layers=3, vocab=777)
+    lengths = [12, 100, 0, 77]
+    case = DecodeCase(w, m, np.asarray(lengths, np.int32), full_model=True, block_bytes=64 << 10)
+    tok = wl.make_token_ids(dataclasses.replace(w, model=m), (4,))
+    hid = case.run_gpu(token_ids=tok)
+    ref_hid, ref_logits, ref_next = case.run_oracle(token_ids=tok)
+    assert_close(hid, ref_hid, "hidden state", **F32_BAR)
+    logits = case.logits_dev.cpu().numpy()
+    assert_close(logits, ref_logits, "logits", **F32_BAR)
+    case.check_cache(1e-4, 2e-5)
+    nxt = case.next_dev.cpu().numpy()
+    assert np.array_equal(nxt, np.argmax(logits, axis=-1))
+    srt = np.sort(ref_logits, axis=-1)
+    clear = (srt[:, -1] - srt[:, -2]) > 2e-4 * np.max(np.abs(ref_logits))
+    assert np.array_equal(nxt[clear], ref_next[clear])
