@@ -48,6 +48,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--solo", action="store_true", help="also report each task running alone (default on)")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="after the timed region run three plain 256 MiB device copies: the known-size kernel that the "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU's share of the data-parallel path; --gpus %d is not supported "
@@ -284,6 +287,13 @@ def main():
         cpu = {"value": sb * ss / (c1 - c0), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
                "sample": "numpy fp64 layer forward+backward of %d x %d tokens (the 4 x 512 micro-batch) at full "
                          "7B-layer width, decode not running; %.1f s" % (sb, ss, c1 - c0)}
+
+    if args.calib_copy:
+        src = torch.full((64 << 20,), 1.0, dtype=torch.float32, device=dev)     # 256 MiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
 
     ach_tf = gemm_flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else float("nan")
     out = {

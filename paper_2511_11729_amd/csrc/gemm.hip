@@ -5,10 +5,11 @@
 // tile = 4 x 2 v_mfma_f32_32x32x16_bf16 accumulators (128 fp32 registers per lane).
 // Operands go global -> registers -> LDS (row-major rows of 64 k padded to 144 bytes, which
 // makes both the 16-byte row writes and the 32-row fragment reads bank-conflict free) with
-// two LDS stages and one barrier per K step.  Tiles are handed to XCDs in contiguous runs so
-// that the workgroups sharing an L2 also share operand panels.
+// two LDS stages and one barrier per K step.  Tiles are handed to XCDs in contiguous runs of
+// 4 x 8-tile blocks so that the workgroups sharing an L2 also share operand panels.
 #include "gemm.h"
 
+#include <algorithm>
 #include <vector>
 
 #include "ctx.h"
@@ -18,6 +19,7 @@ namespace harli {
 namespace {
 
 constexpr int BM = 256, BN = 128, BK = 64;
+constexpr int kGM = 4, kGN = 8;  // tiles per L2-sharing block (clipped to the tile grid)
 constexpr int ROWB = BK * 2 + 16;  // bytes per staged row
 constexpr int A_STAGE = BM * ROWB, B_STAGE = BN * ROWB, STAGE = A_STAGE + B_STAGE;
 constexpr int LDS_BYTES = 2 * STAGE;
@@ -31,16 +33,22 @@ __device__ __forceinline__ void seg_range(const GemmArgs& a, int s, int m0, int*
 
 // one workgroup (4 waves, one per SIMD) per CU: let each wave use the whole 512-register file
 template <bool HALF>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) k_gemm(GemmArgs a, int tiles_n, int tiles_total, int chunk, const uint4* zero16) {
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) k_gemm(GemmArgs a, int tiles_n, int tiles_total, int chunk, int GM, int GN, const uint4* zero16) {
   extern __shared__ __align__(16) char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
-  // XCD-aware tile order: workgroup w runs on XCD w % 8; give each XCD a contiguous run of tiles
+  // XCD-aware tile order: workgroup w runs on XCD w % 8.  Each XCD gets a contiguous run of slots, and slots
+  // walk the tile grid in blocks of GM x GN tiles, so the 32 workgroups resident on an XCD at a time share
+  // GM row panels of A and GN row panels of B in its L2 (4 + 8 panels instead of 1 + 32 for a row of tiles).
   const int w = blockIdx.x;
-  const int tile = (w & 7) * chunk + (w >> 3);
-  if (tile >= tiles_total) return;
-  const int tm = tile / tiles_n, tn = tile - tm * tiles_n;
+  const int slot = (w & 7) * chunk + (w >> 3);
+  if (slot >= tiles_total) return;
+  const int nbn = (tiles_n + GN - 1) / GN;
+  const int blk = slot / (GM * GN), within = slot - blk * (GM * GN);
+  const int bm = blk / nbn, bn = blk - bm * nbn;
+  const int tm = bm * GM + within / GN, tn = bn * GN + within % GN;
   const int m0 = tm * BM, n0 = tn * BN;
+  if (m0 >= a.M || n0 >= a.N) return;
   if (a.causal == GEMM_OUT_LOWER && n0 > m0 + BM - 1) return;
   if (a.causal == GEMM_OUT_UPPER && n0 + BN - 1 < m0) return;
   const int z = blockIdx.z, z2 = z % a.nb2, zq = z / a.nb2, z1 = zq % a.nb1, z0 = zq / a.nb1;
@@ -297,7 +305,9 @@ harli_status gemm_launch(const GemmArgs& a, int batches, hipStream_t st) {
     attr_set = true;
   }
   const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
-  const int total = tiles_m * tiles_n, chunk = (total + 7) / 8;
+  // slots: whole GM x GN blocks (tiles past the edge of the matrix return at once)
+  const int GM = std::min(kGM, tiles_m), GN = std::min(kGN, tiles_n);
+  const int total = ((tiles_m + GM - 1) / GM) * ((tiles_n + GN - 1) / GN) * GM * GN, chunk = (total + 7) / 8;
   ProfRec rec{};
   if (g_prof_on) {
     HARLI_HIP(hipEventCreate(&rec.e0));
@@ -306,9 +316,9 @@ harli_status gemm_launch(const GemmArgs& a, int batches, hipStream_t st) {
     HARLI_HIP(hipEventRecord(rec.e0, st));
   }
   if (a.half)
-    hipLaunchKernelGGL(k_gemm<true>, dim3(chunk * 8, 1, batches), dim3(256), LDS_BYTES, st, a, tiles_n, total, chunk, zero16);
+    hipLaunchKernelGGL(k_gemm<true>, dim3(chunk * 8, 1, batches), dim3(256), LDS_BYTES, st, a, tiles_n, total, chunk, GM, GN, zero16);
   else
-    hipLaunchKernelGGL(k_gemm<false>, dim3(chunk * 8, 1, batches), dim3(256), LDS_BYTES, st, a, tiles_n, total, chunk, zero16);
+    hipLaunchKernelGGL(k_gemm<false>, dim3(chunk * 8, 1, batches), dim3(256), LDS_BYTES, st, a, tiles_n, total, chunk, GM, GN, zero16);
   if (g_prof_on) {
     HARLI_HIP(hipEventRecord(rec.e1, st));
     g_prof.push_back(rec);
