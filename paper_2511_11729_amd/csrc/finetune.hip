@@ -14,6 +14,7 @@
 
 #include "ctx.h"
 #include "ft_elem.h"
+#include "ft_attention.h"
 #include "ft_kernels.h"
 #include "gemm.h"
 
@@ -81,7 +82,8 @@ Dims dims(const harli_ctx* c, int Bf, int S) {
 harli_status ensure_ws(harli_ctx* c, int Bf, int S) {
   FtWs& w = state(c)->ws;
   const Dims D = dims(c, Bf, S);
-  const size_t T = D.T, ZSS = (size_t)D.Z * S * S;
+  // the S x S score buffers exist only for head sizes the fused attention kernels do not cover
+  const size_t T = D.T, ZSS = ft_attn_supported(D.d) ? 0 : (size_t)D.Z * S * S;
   const size_t maxdim = std::max(std::max((size_t)D.H, (size_t)D.QD), (size_t)D.F);
   size_t off = 0;
   auto take = [&](size_t n) {
@@ -210,7 +212,7 @@ SavedPlan plan_saved(const harli_ctx* c, const Dims& D, int S) {
   p.o_q = take(T * D.QD * 2);
   p.o_k = take(T * D.KVD * 2);
   p.o_v = take(T * D.KVD * 2);
-  p.o_P = take((size_t)D.Z * S * S * 2);
+  p.o_P = take(ft_attn_supported(D.d) ? 0 : (size_t)D.Z * S * S * 2);
   p.o_o = take(T * D.QD * 2);
   p.o_h2 = take(T * D.H * 2);
   p.o_a = take(T * D.F * 2);
@@ -385,29 +387,33 @@ extern "C" harli_status harli_lora_fwd(harli_ctx* c, int32_t layer, const float*
   ft_transpose_heads(sv->v, w.vT, B_f, S, D.nkv, D.d, st);
   const long long SS = (long long)S * S;
   const int batches = B_f * D.nq;
-  {  // scores[z][q][k] = q . k / sqrt(d), lower triangle only
-    GemmArgs g = plain_gemm(S, S);
-    g.nb1 = D.nkv; g.nb2 = D.G;
-    g.alpha = 1.f / std::sqrt((float)D.d);
-    g.causal = GEMM_OUT_LOWER;
-    add_seg(g, sv->q, D.QD, sv->k, D.KVD, D.d);
-    g.seg[0].a_bs0 = (long long)S * D.QD; g.seg[0].a_bs1 = (long long)D.G * D.d; g.seg[0].a_bs2 = D.d;
-    g.seg[0].b_bs0 = (long long)S * D.KVD; g.seg[0].b_bs1 = D.d; g.seg[0].b_bs2 = 0;
-    g.Cf = w.scores; g.ldcf = S;
-    g.cf_bs0 = (long long)D.nq * SS; g.cf_bs1 = (long long)D.G * SS; g.cf_bs2 = SS;
-    RUN(gemm_launch(g, batches, st));
-  }
-  ft_softmax_causal(w.scores, sv->P, sv->lse, batches, S, st);
-  {  // o = P . V
-    GemmArgs g = plain_gemm(S, D.d);
-    g.nb1 = D.nkv; g.nb2 = D.G;
-    g.causal = GEMM_K_UPTO_M;
-    add_seg(g, sv->P, S, w.vT, S, S);
-    g.seg[0].a_bs0 = (long long)D.nq * SS; g.seg[0].a_bs1 = (long long)D.G * SS; g.seg[0].a_bs2 = SS;
-    g.seg[0].b_bs0 = (long long)D.KVD * S; g.seg[0].b_bs1 = (long long)D.d * S; g.seg[0].b_bs2 = 0;
-    g.Cb = sv->o; g.ldcb = D.QD;
-    g.cb_bs0 = (long long)S * D.QD; g.cb_bs1 = (long long)D.G * D.d; g.cb_bs2 = D.d;
-    RUN(gemm_launch(g, batches, st));
+  if (ft_attn_supported(D.d)) {
+    RUN(ft_attn_fwd(sv->q, sv->k, w.vT, sv->o, sv->lse, B_f, S, D.nq, D.nkv, D.d, st));
+  } else {
+    {  // scores[z][q][k] = q . k / sqrt(d), lower triangle only
+      GemmArgs g = plain_gemm(S, S);
+      g.nb1 = D.nkv; g.nb2 = D.G;
+      g.alpha = 1.f / std::sqrt((float)D.d);
+      g.causal = GEMM_OUT_LOWER;
+      add_seg(g, sv->q, D.QD, sv->k, D.KVD, D.d);
+      g.seg[0].a_bs0 = (long long)S * D.QD; g.seg[0].a_bs1 = (long long)D.G * D.d; g.seg[0].a_bs2 = D.d;
+      g.seg[0].b_bs0 = (long long)S * D.KVD; g.seg[0].b_bs1 = D.d; g.seg[0].b_bs2 = 0;
+      g.Cf = w.scores; g.ldcf = S;
+      g.cf_bs0 = (long long)D.nq * SS; g.cf_bs1 = (long long)D.G * SS; g.cf_bs2 = SS;
+      RUN(gemm_launch(g, batches, st));
+    }
+    ft_softmax_causal(w.scores, sv->P, sv->lse, batches, S, st);
+    {  // o = P . V
+      GemmArgs g = plain_gemm(S, D.d);
+      g.nb1 = D.nkv; g.nb2 = D.G;
+      g.causal = GEMM_K_UPTO_M;
+      add_seg(g, sv->P, S, w.vT, S, S);
+      g.seg[0].a_bs0 = (long long)D.nq * SS; g.seg[0].a_bs1 = (long long)D.G * SS; g.seg[0].a_bs2 = SS;
+      g.seg[0].b_bs0 = (long long)D.KVD * S; g.seg[0].b_bs1 = (long long)D.d * S; g.seg[0].b_bs2 = 0;
+      g.Cb = sv->o; g.ldcb = D.QD;
+      g.cb_bs0 = (long long)S * D.QD; g.cb_bs1 = (long long)D.G * D.d; g.cb_bs2 = D.d;
+      RUN(gemm_launch(g, batches, st));
+    }
   }
   {  // x1 = X + o Wo^T
     GemmArgs g = plain_gemm(T, D.H);
@@ -531,59 +537,64 @@ extern "C" harli_status harli_lora_bwd(harli_ctx* c, int32_t layer, const float*
     g.Cb = C; g.ldcb = D.QD;
     g.cb_bs0 = (long long)S * D.QD; g.cb_bs1 = (long long)D.G * D.d; g.cb_bs2 = D.d;
   };
-  {  // dP = dO V^T (lower)
-    GemmArgs g = plain_gemm(S, S);
-    g.nb1 = D.nkv; g.nb2 = D.G; g.causal = GEMM_OUT_LOWER;
-    add_seg(g, w.dob, D.QD, sv->v, D.KVD, D.d);
-    qlike(g.seg[0], true); klike(g.seg[0], false);
-    ss_out(g, w.dP);
-    RUNB(gemm_launch(g, batches, st));
-  }
-  ft_attn_ds(sv->P, w.dP, w.delta, w.dS, batches, S, st);
-  {  // ST = K Q^T / sqrt(d) (upper, rows = keys)
-    GemmArgs g = plain_gemm(S, S);
-    g.nb1 = D.nkv; g.nb2 = D.G; g.causal = GEMM_OUT_UPPER; g.alpha = scale;
-    add_seg(g, sv->k, D.KVD, sv->q, D.QD, D.d);
-    klike(g.seg[0], true); qlike(g.seg[0], false);
-    ss_out(g, w.ST);
-    RUNB(gemm_launch(g, batches, st));
-  }
-  {  // dPT = V dO^T (upper)
-    GemmArgs g = plain_gemm(S, S);
-    g.nb1 = D.nkv; g.nb2 = D.G; g.causal = GEMM_OUT_UPPER;
-    add_seg(g, sv->v, D.KVD, w.dob, D.QD, D.d);
-    klike(g.seg[0], true); qlike(g.seg[0], false);
-    ss_out(g, w.dPT);
-    RUNB(gemm_launch(g, batches, st));
-  }
-  ft_attn_ds_t(w.ST, w.dPT, sv->lse, w.delta, w.PT, w.dST, batches, S, st);
   ft_transpose_heads(w.dob, w.doT, B_f, S, D.nq, D.d, st);
   ft_transpose_heads(sv->q, w.qT, B_f, S, D.nq, D.d, st);
   ft_transpose_heads(sv->k, w.kT, B_f, S, D.nkv, D.d, st);
-  {  // dV (per query head) = PT dO
-    GemmArgs g = plain_gemm(S, D.d);
-    g.nb1 = D.nkv; g.nb2 = D.G; g.causal = GEMM_K_FROM_M;
-    add_seg(g, w.PT, S, w.doT, S, S);
-    sslike(g.seg[0]); qT_like(g.seg[0]);
-    q_out(g, w.dvq);
-    RUNB(gemm_launch(g, batches, st));
-  }
-  {  // dK (per query head) = dST Q / sqrt(d)
-    GemmArgs g = plain_gemm(S, D.d);
-    g.nb1 = D.nkv; g.nb2 = D.G; g.causal = GEMM_K_FROM_M; g.alpha = scale;
-    add_seg(g, w.dST, S, w.qT, S, S);
-    sslike(g.seg[0]); qT_like(g.seg[0]);
-    q_out(g, w.dkq);
-    RUNB(gemm_launch(g, batches, st));
-  }
-  {  // dQ = dS K / sqrt(d)
-    GemmArgs g = plain_gemm(S, D.d);
-    g.nb1 = D.nkv; g.nb2 = D.G; g.causal = GEMM_K_UPTO_M; g.alpha = scale;
-    add_seg(g, w.dS, S, w.kT, S, S);
-    sslike(g.seg[0]);
-    g.seg[0].b_bs0 = (long long)D.KVD * S; g.seg[0].b_bs1 = (long long)D.d * S; g.seg[0].b_bs2 = 0;
-    q_out(g, w.dq);
-    RUNB(gemm_launch(g, batches, st));
+  if (ft_attn_supported(D.d)) {
+    RUNB(ft_attn_bwd(sv->q, sv->k, sv->v, w.qT, w.kT, w.dob, w.doT, sv->lse, w.delta, w.dq, w.dkq, w.dvq, B_f, S, D.nq, D.nkv,
+                     D.d, st));
+  } else {
+    {  // dP = dO V^T (lower)
+      GemmArgs g = plain_gemm(S, S);
+      g.nb1 = D.nkv; g.nb2 = D.G; g.causal = GEMM_OUT_LOWER;
+      add_seg(g, w.dob, D.QD, sv->v, D.KVD, D.d);
+      qlike(g.seg[0], true); klike(g.seg[0], false);
+      ss_out(g, w.dP);
+      RUNB(gemm_launch(g, batches, st));
+    }
+    ft_attn_ds(sv->P, w.dP, w.delta, w.dS, batches, S, st);
+    {  // ST = K Q^T / sqrt(d) (upper, rows = keys)
+      GemmArgs g = plain_gemm(S, S);
+      g.nb1 = D.nkv; g.nb2 = D.G; g.causal = GEMM_OUT_UPPER; g.alpha = scale;
+      add_seg(g, sv->k, D.KVD, sv->q, D.QD, D.d);
+      klike(g.seg[0], true); qlike(g.seg[0], false);
+      ss_out(g, w.ST);
+      RUNB(gemm_launch(g, batches, st));
+    }
+    {  // dPT = V dO^T (upper)
+      GemmArgs g = plain_gemm(S, S);
+      g.nb1 = D.nkv; g.nb2 = D.G; g.causal = GEMM_OUT_UPPER;
+      add_seg(g, sv->v, D.KVD, w.dob, D.QD, D.d);
+      klike(g.seg[0], true); qlike(g.seg[0], false);
+      ss_out(g, w.dPT);
+      RUNB(gemm_launch(g, batches, st));
+    }
+    ft_attn_ds_t(w.ST, w.dPT, sv->lse, w.delta, w.PT, w.dST, batches, S, st);
+    {  // dV (per query head) = PT dO
+      GemmArgs g = plain_gemm(S, D.d);
+      g.nb1 = D.nkv; g.nb2 = D.G; g.causal = GEMM_K_FROM_M;
+      add_seg(g, w.PT, S, w.doT, S, S);
+      sslike(g.seg[0]); qT_like(g.seg[0]);
+      q_out(g, w.dvq);
+      RUNB(gemm_launch(g, batches, st));
+    }
+    {  // dK (per query head) = dST Q / sqrt(d)
+      GemmArgs g = plain_gemm(S, D.d);
+      g.nb1 = D.nkv; g.nb2 = D.G; g.causal = GEMM_K_FROM_M; g.alpha = scale;
+      add_seg(g, w.dST, S, w.qT, S, S);
+      sslike(g.seg[0]); qT_like(g.seg[0]);
+      q_out(g, w.dkq);
+      RUNB(gemm_launch(g, batches, st));
+    }
+    {  // dQ = dS K / sqrt(d)
+      GemmArgs g = plain_gemm(S, D.d);
+      g.nb1 = D.nkv; g.nb2 = D.G; g.causal = GEMM_K_UPTO_M; g.alpha = scale;
+      add_seg(g, w.dS, S, w.kT, S, S);
+      sslike(g.seg[0]);
+      g.seg[0].b_bs0 = (long long)D.KVD * S; g.seg[0].b_bs1 = (long long)D.d * S; g.seg[0].b_bs2 = 0;
+      q_out(g, w.dq);
+      RUNB(gemm_launch(g, batches, st));
+    }
   }
   const bf *dk = w.dkq, *dv = w.dvq;
   if (D.G > 1) {
