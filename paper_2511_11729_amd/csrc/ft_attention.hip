@@ -22,9 +22,12 @@ namespace {
 
 constexpr int KB = 64;            // rows of the streamed operand per block
 constexpr int TS = KB * 2 + 16;   // byte stride of a transposed tile row (64 columns + pad)
+// native vector types: arrays of them stay in registers (arrays of the HIP uint4 struct were left in scratch)
+typedef unsigned __attribute__((ext_vector_type(4))) u32x4;
+typedef unsigned __attribute__((ext_vector_type(2))) u32x2;
 constexpr float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
 
-__device__ __forceinline__ f32x16 mma32(const uint4& a, const uint4& b, f32x16 c) {
+__device__ __forceinline__ f32x16 mma32(const u32x4& a, const u32x4& b, f32x16 c) {
   if constexpr (kFtHalf)
     return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
   else
@@ -33,18 +36,18 @@ __device__ __forceinline__ f32x16 mma32(const uint4& a, const uint4& b, f32x16 c
 
 // A fragment of a row-major LDS tile (row stride RS bytes): rows sub*32 + lane%32, k = 16j + 8h .. +7
 template <int RS>
-__device__ __forceinline__ uint4 frag_rows(const char* tile, int sub, int j, int l31, int h) {
-  return *reinterpret_cast<const uint4*>(tile + (sub * 32 + l31) * RS + (16 * j + 8 * h) * 2);
+__device__ __forceinline__ u32x4 frag_rows(const char* tile, int sub, int j, int l31, int h) {
+  return *reinterpret_cast<const u32x4*>(tile + (sub * 32 + l31) * RS + (16 * j + 8 * h) * 2);
 }
 // A fragment of a transposed LDS tile [rows e][64 columns]: row et*32 + lane%32, columns of step (sub, jj) in the
 // accumulator-register order (see the file header)
-__device__ __forceinline__ uint4 frag_cols(const char* tile, int et, int sub, int jj, int l31, int h) {
+__device__ __forceinline__ u32x4 frag_cols(const char* tile, int et, int sub, int jj, int l31, int h) {
   const char* p = tile + (et * 32 + l31) * TS + (sub * 32 + 16 * jj + 4 * h) * 2;
-  const uint2 lo = *reinterpret_cast<const uint2*>(p), hi = *reinterpret_cast<const uint2*>(p + 16);
-  return make_uint4(lo.x, lo.y, hi.x, hi.y);
+  const u32x2 lo = *reinterpret_cast<const u32x2*>(p), hi = *reinterpret_cast<const u32x2*>(p + 16);
+  return u32x4{lo.x, lo.y, hi.x, hi.y};
 }
-__device__ __forceinline__ uint4 pack8(const f32x16& a, int o) {
-  return make_uint4(PACK2(a[o], a[o + 1]), PACK2(a[o + 2], a[o + 3]), PACK2(a[o + 4], a[o + 5]), PACK2(a[o + 6], a[o + 7]));
+__device__ __forceinline__ u32x4 pack8(const f32x16& a, int o) {
+  return u32x4{PACK2(a[o], a[o + 1]), PACK2(a[o + 2], a[o + 3]), PACK2(a[o + 4], a[o + 5]), PACK2(a[o + 6], a[o + 7])};
 }
 __device__ __forceinline__ f32x16 zero16f() {
   f32x16 z;
@@ -69,11 +72,11 @@ __global__ void __launch_bounds__(256) k_attn_fwd(const bf* __restrict__ q, cons
   const int QD = nq * D, KVD = nkv * D;
   const int q0 = qb * 128 + wave * 32, qrow = q0 + l31, qc = min(qrow, S - 1);
 
-  uint4 Qf[NJ];
+  u32x4 Qf[NJ];
   {
     const bf* qp = q + ((long long)b * S + qc) * QD + head * D + 8 * h;
 #pragma unroll
-    for (int j = 0; j < NJ; ++j) Qf[j] = *reinterpret_cast<const uint4*>(qp + 16 * j);
+    for (int j = 0; j < NJ; ++j) Qf[j] = *reinterpret_cast<const u32x4*>(qp + 16 * j);
   }
   f32x16 O[NE];
 #pragma unroll
@@ -84,14 +87,14 @@ __global__ void __launch_bounds__(256) k_attn_fwd(const bf* __restrict__ q, cons
   const bf* kbase = k + (long long)b * S * KVD + hk * D;
   const bf* vbase = vT + (long long)(b * nkv + hk) * D * S;
   // per-thread chunk coordinates of the two tiles (CPT 16-byte chunks each)
-  uint4 pk[CPT], pv[CPT];
+  u32x4 pk[CPT], pv[CPT];
 #define FWD_FETCH(kb_)                                                                                        \
   _Pragma("unroll") for (int i = 0; i < CPT; ++i) {                                                           \
     const int c = tid + 256 * i;                                                                              \
     const int kr = c / (D / 8), kc = c - kr * (D / 8);                                                        \
-    pk[i] = *reinterpret_cast<const uint4*>(kbase + (long long)min((kb_) * KB + kr, S - 1) * KVD + kc * 8);   \
+    pk[i] = *reinterpret_cast<const u32x4*>(kbase + (long long)min((kb_) * KB + kr, S - 1) * KVD + kc * 8);   \
     const int ve = c >> 3, vc = c & 7;                                                                        \
-    pv[i] = *reinterpret_cast<const uint4*>(vbase + (long long)ve * S + min((kb_) * KB + vc * 8, S - 8));     \
+    pv[i] = *reinterpret_cast<const u32x4*>(vbase + (long long)ve * S + min((kb_) * KB + vc * 8, S - 8));     \
   }
   FWD_FETCH(0)
   for (int kb = 0; kb < nkb; ++kb) {
@@ -100,9 +103,9 @@ __global__ void __launch_bounds__(256) k_attn_fwd(const bf* __restrict__ q, cons
     for (int i = 0; i < CPT; ++i) {
       const int c = tid + 256 * i;
       const int kr = c / (D / 8), kc = c - kr * (D / 8);
-      *reinterpret_cast<uint4*>(sK + kr * RS + kc * 16) = pk[i];
+      *reinterpret_cast<u32x4*>(sK + kr * RS + kc * 16) = pk[i];
       const int ve = c >> 3, vc = c & 7;
-      *reinterpret_cast<uint4*>(sV + ve * TS + vc * 16) = pv[i];
+      *reinterpret_cast<u32x4*>(sV + ve * TS + vc * 16) = pv[i];
     }
     __syncthreads();
     if (kb + 1 < nkb) { FWD_FETCH(kb + 1) }
@@ -148,7 +151,7 @@ __global__ void __launch_bounds__(256) k_attn_fwd(const bf* __restrict__ q, cons
     for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
       for (int jj = 0; jj < 2; ++jj) {
-        const uint4 pf = pack8(sc[sub], 8 * jj);
+        const u32x4 pf = pack8(sc[sub], 8 * jj);
 #pragma unroll
         for (int e = 0; e < NE; ++e) O[e] = mma32(frag_cols(sV, e, sub, jj, l31, h), pf, O[e]);
       }
@@ -161,8 +164,8 @@ __global__ void __launch_bounds__(256) k_attn_fwd(const bf* __restrict__ q, cons
     for (int e = 0; e < NE; ++e)
 #pragma unroll
       for (int g = 0; g < 4; ++g)
-        *reinterpret_cast<uint2*>(op + e * 32 + 8 * g + 4 * h) =
-            make_uint2(PACK2(O[e][4 * g] * inv, O[e][4 * g + 1] * inv), PACK2(O[e][4 * g + 2] * inv, O[e][4 * g + 3] * inv));
+        *reinterpret_cast<u32x2*>(op + e * 32 + 8 * g + 4 * h) =
+            u32x2{PACK2(O[e][4 * g] * inv, O[e][4 * g + 1] * inv), PACK2(O[e][4 * g + 2] * inv, O[e][4 * g + 3] * inv)};
     if (h == 0) lse[(long long)z * S + qrow] = (m_run + log2f(l_run)) * kLn2;
   }
 }
@@ -186,13 +189,13 @@ __global__ void __launch_bounds__(256) k_attn_bwd_dq(const bf* __restrict__ q, c
   const int QD = nq * D, KVD = nkv * D;
   const int q0 = qb * 128 + wave * 32, qrow = q0 + l31, qc = min(qrow, S - 1);
 
-  uint4 Qf[NJ], Gf[NJ];  // this lane's query row and its dO row as B operands
+  u32x4 Qf[NJ], Gf[NJ];  // this lane's query row and its dO row as B operands
   {
     const long long ro = ((long long)b * S + qc) * QD + head * D + 8 * h;
 #pragma unroll
     for (int j = 0; j < NJ; ++j) {
-      Qf[j] = *reinterpret_cast<const uint4*>(q + ro + 16 * j);
-      Gf[j] = *reinterpret_cast<const uint4*>(dO + ro + 16 * j);
+      Qf[j] = *reinterpret_cast<const u32x4*>(q + ro + 16 * j);
+      Gf[j] = *reinterpret_cast<const u32x4*>(dO + ro + 16 * j);
     }
   }
   const float lse2 = lse[(long long)z * S + qc] * kLog2e, dl = delta[(long long)z * S + qc];
@@ -204,16 +207,16 @@ __global__ void __launch_bounds__(256) k_attn_bwd_dq(const bf* __restrict__ q, c
   const bf* kbase = k + (long long)b * S * KVD + hk * D;
   const bf* vbase = v + (long long)b * S * KVD + hk * D;
   const bf* ktbase = kT + (long long)(b * nkv + hk) * D * S;
-  uint4 pk[CPT], pv[CPT], pt[CPT];
+  u32x4 pk[CPT], pv[CPT], pt[CPT];
 #define DQ_FETCH(kb_)                                                                                         \
   _Pragma("unroll") for (int i = 0; i < CPT; ++i) {                                                           \
     const int c = tid + 256 * i;                                                                              \
     const int kr = c / (D / 8), kc = c - kr * (D / 8);                                                        \
     const long long ro = (long long)min((kb_) * KB + kr, S - 1) * KVD + kc * 8;                               \
-    pk[i] = *reinterpret_cast<const uint4*>(kbase + ro);                                                      \
-    pv[i] = *reinterpret_cast<const uint4*>(vbase + ro);                                                      \
+    pk[i] = *reinterpret_cast<const u32x4*>(kbase + ro);                                                      \
+    pv[i] = *reinterpret_cast<const u32x4*>(vbase + ro);                                                      \
     const int te = c >> 3, tc = c & 7;                                                                        \
-    pt[i] = *reinterpret_cast<const uint4*>(ktbase + (long long)te * S + min((kb_) * KB + tc * 8, S - 8));    \
+    pt[i] = *reinterpret_cast<const u32x4*>(ktbase + (long long)te * S + min((kb_) * KB + tc * 8, S - 8));    \
   }
   DQ_FETCH(0)
   for (int kb = 0; kb < nkb; ++kb) {
@@ -222,10 +225,10 @@ __global__ void __launch_bounds__(256) k_attn_bwd_dq(const bf* __restrict__ q, c
     for (int i = 0; i < CPT; ++i) {
       const int c = tid + 256 * i;
       const int kr = c / (D / 8), kc = c - kr * (D / 8);
-      *reinterpret_cast<uint4*>(sK + kr * RS + kc * 16) = pk[i];
-      *reinterpret_cast<uint4*>(sV + kr * RS + kc * 16) = pv[i];
+      *reinterpret_cast<u32x4*>(sK + kr * RS + kc * 16) = pk[i];
+      *reinterpret_cast<u32x4*>(sV + kr * RS + kc * 16) = pv[i];
       const int te = c >> 3, tc = c & 7;
-      *reinterpret_cast<uint4*>(sKT + te * TS + tc * 16) = pt[i];
+      *reinterpret_cast<u32x4*>(sKT + te * TS + tc * 16) = pt[i];
     }
     __syncthreads();
     if (kb + 1 < nkb) { DQ_FETCH(kb + 1) }
@@ -246,7 +249,7 @@ __global__ void __launch_bounds__(256) k_attn_bwd_dq(const bf* __restrict__ q, c
       }
 #pragma unroll
       for (int jj = 0; jj < 2; ++jj) {
-        const uint4 df = pack8(sc, 8 * jj);
+        const u32x4 df = pack8(sc, 8 * jj);
 #pragma unroll
         for (int e = 0; e < NE; ++e) dQ[e] = mma32(frag_cols(sKT, e, sub, jj, l31, h), df, dQ[e]);
       }
@@ -259,8 +262,8 @@ __global__ void __launch_bounds__(256) k_attn_bwd_dq(const bf* __restrict__ q, c
     for (int e = 0; e < NE; ++e)
 #pragma unroll
       for (int g = 0; g < 4; ++g)
-        *reinterpret_cast<uint2*>(op + e * 32 + 8 * g + 4 * h) =
-            make_uint2(PACK2(dQ[e][4 * g] * scale, dQ[e][4 * g + 1] * scale), PACK2(dQ[e][4 * g + 2] * scale, dQ[e][4 * g + 3] * scale));
+        *reinterpret_cast<u32x2*>(op + e * 32 + 8 * g + 4 * h) =
+            u32x2{PACK2(dQ[e][4 * g] * scale, dQ[e][4 * g + 1] * scale), PACK2(dQ[e][4 * g + 2] * scale, dQ[e][4 * g + 3] * scale)};
   }
 }
 
@@ -288,13 +291,13 @@ __global__ void __launch_bounds__(256) k_attn_bwd_dkv(const bf* __restrict__ q, 
   const int QD = nq * D, KVD = nkv * D;
   const int k0 = kvb * 128 + wave * 32, krow = k0 + l31, kc_ = min(krow, S - 1);
 
-  uint4 Kf[NJ], Vf[NJ];  // this lane's key and value rows as B operands
+  u32x4 Kf[NJ], Vf[NJ];  // this lane's key and value rows as B operands
   {
     const long long ro = ((long long)b * S + kc_) * KVD + hk * D + 8 * h;
 #pragma unroll
     for (int j = 0; j < NJ; ++j) {
-      Kf[j] = *reinterpret_cast<const uint4*>(k + ro + 16 * j);
-      Vf[j] = *reinterpret_cast<const uint4*>(v + ro + 16 * j);
+      Kf[j] = *reinterpret_cast<const u32x4*>(k + ro + 16 * j);
+      Vf[j] = *reinterpret_cast<const u32x4*>(v + ro + 16 * j);
     }
   }
   f32x16 dV[NE], dK[NE];
@@ -308,19 +311,19 @@ __global__ void __launch_bounds__(256) k_attn_bwd_dkv(const bf* __restrict__ q, 
   const bf* gtbase = dOT + (long long)(b * nq + head) * D * S;
   const float* lbase = lse + (long long)z * S;
   const float* dbase = delta + (long long)z * S;
-  uint4 pq[CPT], pg[CPT], pqt[CPT], pgt[CPT];
+  u32x4 pq[CPT], pg[CPT], pqt[CPT], pgt[CPT];
   float pl;
 #define KV_FETCH(qb_)                                                                                          \
   _Pragma("unroll") for (int i = 0; i < CPT; ++i) {                                                            \
     const int c = tid + 256 * i;                                                                               \
     const int rr = c / (D / 8), rc = c - rr * (D / 8);                                                         \
     const long long ro = (long long)min((qb_) * KB + rr, S - 1) * QD + rc * 8;                                 \
-    pq[i] = *reinterpret_cast<const uint4*>(qbase + ro);                                                       \
-    pg[i] = *reinterpret_cast<const uint4*>(gbase + ro);                                                       \
+    pq[i] = *reinterpret_cast<const u32x4*>(qbase + ro);                                                       \
+    pg[i] = *reinterpret_cast<const u32x4*>(gbase + ro);                                                       \
     const int te = c >> 3, tc = c & 7;                                                                         \
     const long long to = (long long)te * S + min((qb_) * KB + tc * 8, S - 8);                                  \
-    pqt[i] = *reinterpret_cast<const uint4*>(qtbase + to);                                                     \
-    pgt[i] = *reinterpret_cast<const uint4*>(gtbase + to);                                                     \
+    pqt[i] = *reinterpret_cast<const u32x4*>(qtbase + to);                                                     \
+    pgt[i] = *reinterpret_cast<const u32x4*>(gtbase + to);                                                     \
   }                                                                                                            \
   {                                                                                                            \
     const int r = min((qb_) * KB + (tid & 63), S - 1);                                                         \
@@ -333,11 +336,11 @@ __global__ void __launch_bounds__(256) k_attn_bwd_dkv(const bf* __restrict__ q, 
     for (int i = 0; i < CPT; ++i) {
       const int c = tid + 256 * i;
       const int rr = c / (D / 8), rc = c - rr * (D / 8);
-      *reinterpret_cast<uint4*>(sQ + rr * RS + rc * 16) = pq[i];
-      *reinterpret_cast<uint4*>(sG + rr * RS + rc * 16) = pg[i];
+      *reinterpret_cast<u32x4*>(sQ + rr * RS + rc * 16) = pq[i];
+      *reinterpret_cast<u32x4*>(sG + rr * RS + rc * 16) = pg[i];
       const int te = c >> 3, tc = c & 7;
-      *reinterpret_cast<uint4*>(sQT + te * TS + tc * 16) = pqt[i];
-      *reinterpret_cast<uint4*>(sGT + te * TS + tc * 16) = pgt[i];
+      *reinterpret_cast<u32x4*>(sQT + te * TS + tc * 16) = pqt[i];
+      *reinterpret_cast<u32x4*>(sGT + te * TS + tc * 16) = pgt[i];
     }
     if (tid < 128) sL[tid] = pl;
     __syncthreads();
@@ -368,7 +371,7 @@ __global__ void __launch_bounds__(256) k_attn_bwd_dkv(const bf* __restrict__ q, 
       }
 #pragma unroll
       for (int jj = 0; jj < 2; ++jj) {
-        const uint4 pf = pack8(sc, 8 * jj), df = pack8(dp, 8 * jj);
+        const u32x4 pf = pack8(sc, 8 * jj), df = pack8(dp, 8 * jj);
 #pragma unroll
         for (int e = 0; e < NE; ++e) {
           dV[e] = mma32(frag_cols(sGT, e, sub, jj, l31, h), pf, dV[e]);
@@ -385,10 +388,10 @@ __global__ void __launch_bounds__(256) k_attn_bwd_dkv(const bf* __restrict__ q, 
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         const int eo = e * 32 + 8 * g + 4 * h;
-        *reinterpret_cast<uint2*>(dvq + ro + eo) =
-            make_uint2(PACK2(dV[e][4 * g], dV[e][4 * g + 1]), PACK2(dV[e][4 * g + 2], dV[e][4 * g + 3]));
-        *reinterpret_cast<uint2*>(dkq + ro + eo) =
-            make_uint2(PACK2(dK[e][4 * g] * scale, dK[e][4 * g + 1] * scale), PACK2(dK[e][4 * g + 2] * scale, dK[e][4 * g + 3] * scale));
+        *reinterpret_cast<u32x2*>(dvq + ro + eo) =
+            u32x2{PACK2(dV[e][4 * g], dV[e][4 * g + 1]), PACK2(dV[e][4 * g + 2], dV[e][4 * g + 3])};
+        *reinterpret_cast<u32x2*>(dkq + ro + eo) =
+            u32x2{PACK2(dK[e][4 * g] * scale, dK[e][4 * g + 1] * scale), PACK2(dK[e][4 * g + 2] * scale, dK[e][4 * g + 3] * scale)};
       }
   }
 }
