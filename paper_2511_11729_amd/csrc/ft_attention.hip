@@ -59,7 +59,7 @@ __device__ __forceinline__ f32x16 zero16f() {
 // -------------------------------------------------------------------------------------------- forward
 // grid (ceil(S/128), Bf*n_q); a workgroup owns 128 queries of one head, wave w the 32 queries 32w..32w+31.
 template <int D>
-__global__ void __launch_bounds__(256) k_attn_fwd(const bf* __restrict__ q, const bf* __restrict__ k, const bf* __restrict__ vT,
+__global__ void __launch_bounds__(256, 2) k_attn_fwd(const bf* __restrict__ q, const bf* __restrict__ k, const bf* __restrict__ vT,
                                                   bf* __restrict__ o, float* __restrict__ lse, int S, int nq, int nkv,
                                                   float scale_log2) {
   constexpr int RS = D * 2 + 16, NJ = D / 16, NE = D / 32, CPT = D / 32;
@@ -173,7 +173,7 @@ __global__ void __launch_bounds__(256) k_attn_fwd(const bf* __restrict__ q, cons
 // -------------------------------------------------------------------------------------------- backward: dQ
 // grid (ceil(S/128), Bf*n_q); same ownership as the forward kernel.  dQ^T[e][q] += K^T[e][k] dS^T[k][q].
 template <int D>
-__global__ void __launch_bounds__(256) k_attn_bwd_dq(const bf* __restrict__ q, const bf* __restrict__ k, const bf* __restrict__ v,
+__global__ void __launch_bounds__(256, 2) k_attn_bwd_dq(const bf* __restrict__ q, const bf* __restrict__ k, const bf* __restrict__ v,
                                                      const bf* __restrict__ kT, const bf* __restrict__ dO,
                                                      const float* __restrict__ lse, const float* __restrict__ delta,
                                                      bf* __restrict__ dq, int S, int nq, int nkv, float scale,
