@@ -1,8 +1,8 @@
 // 16-bit (half or bf16 operands, fp32 accumulate) MFMA GEMM for gfx950 (the compute-bound half of the co-located pair: Harli Sec. 1 /
 // Sec. 2.1 -- PEFT finetuning is dominated by frozen-base matrix multiplications).
 //
-// Workgroup tile 256 x 128, K step 64, 4 waves in a 2 x 2 arrangement, each wave a 128 x 64
-// tile = 4 x 2 v_mfma_f32_32x32x16_bf16 accumulators (128 fp32 registers per lane).
+// Workgroup tile 256 x 128, K step 64, 8 waves in a 4 x 2 arrangement, each wave a 64 x 64
+// tile = 2 x 2 v_mfma_f32_32x32x16 accumulators (64 fp32 registers per lane).
 // Operands go global -> registers -> LDS (row-major rows of 64 k padded to 144 bytes, which
 // makes both the 16-byte row writes and the 32-row fragment reads bank-conflict free) with
 // two LDS stages and one barrier per K step.  Tiles are handed to XCDs in contiguous runs of
@@ -23,7 +23,8 @@ constexpr int kGM = 4, kGN = 8;  // tiles per L2-sharing block (clipped to the t
 constexpr int ROWB = BK * 2 + 16;  // bytes per staged row
 constexpr int A_STAGE = BM * ROWB, B_STAGE = BN * ROWB, STAGE = A_STAGE + B_STAGE;
 constexpr int LDS_BYTES = 2 * STAGE;
-constexpr int A_CH = BM * (BK / 8) / 256, B_CH = BN * (BK / 8) / 256;  // 16-byte chunks per thread per stage
+constexpr int NT = 512;  // 8 waves, two per SIMD
+constexpr int A_CH = BM * (BK / 8) / NT, B_CH = BN * (BK / 8) / NT;  // 16-byte chunks per thread per stage
 
 __device__ __forceinline__ void seg_range(const GemmArgs& a, int s, int m0, int* kb, int* ke) {
   const int K = a.seg[s].K;
@@ -31,12 +32,14 @@ __device__ __forceinline__ void seg_range(const GemmArgs& a, int s, int m0, int*
   *ke = (a.causal == GEMM_K_UPTO_M) ? min(K, m0 + BM) : K;
 }
 
-// one workgroup (4 waves, one per SIMD) per CU: let each wave use the whole 512-register file
+// One workgroup of 8 waves per CU, two waves per SIMD (256 registers each): while one wave of a SIMD waits on its
+// staging loads, LDS writes or the barrier, the other one issues MFMAs.  (Four waves with twice the tile each and
+// the whole register file were 27 % slower: nothing covered those waits.)
 template <bool HALF>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) k_gemm(GemmArgs a, int tiles_n, int tiles_total, int chunk, int GM, int GN, const uint4* zero16) {
+__global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) k_gemm(GemmArgs a, int tiles_n, int tiles_total, int chunk, int GM, int GN, const uint4* zero16) {
   extern __shared__ __align__(16) char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave >> 1, wn = wave & 1;  // 4 x 2 waves of 64 x 64
   // XCD-aware tile order: workgroup w runs on XCD w % 8.  Each XCD gets a contiguous run of slots, and slots
   // walk the tile grid in blocks of GM x GN tiles, so the 32 workgroups resident on an XCD at a time share
   // GM row panels of A and GN row panels of B in its L2 (4 + 8 panels instead of 1 + 32 for a row of tiles).
@@ -53,9 +56,9 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
   if (a.causal == GEMM_OUT_UPPER && n0 + BN - 1 < m0) return;
   const int z = blockIdx.z, z2 = z % a.nb2, zq = z / a.nb2, z1 = zq % a.nb1, z0 = zq / a.nb1;
 
-  f32x16 acc[4][2];
+  f32x16 acc[2][2];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < 2; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
@@ -64,11 +67,11 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
   // per-thread chunk coordinates (same for every stage)
   const int crow = tid >> 3, ckc = (tid & 7) * 8;
   // Two register stages (sets r and q) are in flight besides the two LDS stages: a stage's global
-  // loads are issued two compute phases (~0.9 us of MFMA work) before they are written to LDS.
+  // loads are issued two compute phases before they are written to LDS.
   // They are named scalars, not arrays: the arrays were left in scratch memory by the compiler.
-  static_assert(A_CH == 8 && B_CH == 4, "the staging macros below are written for 8 + 4 chunks per thread");
-  uint4 ra0, ra1, ra2, ra3, ra4, ra5, ra6, ra7, rb0, rb1, rb2, rb3;
-  uint4 qa0, qa1, qa2, qa3, qa4, qa5, qa6, qa7, qb0, qb1, qb2, qb3;
+  static_assert(A_CH == 4 && B_CH == 2, "the staging macros below are written for 4 + 2 chunks per thread");
+  uint4 ra0, ra1, ra2, ra3, rb0, rb1;
+  uint4 qa0, qa1, qa2, qa3, qb0, qb1;
   // Row pointers of the current K segment live in registers and advance by BK per stage, so a
   // stage's loads need no address arithmetic beyond one select: out-of-range chunks (rows past
   // M / N, k past the segment) read a zero word instead -- selecting the ADDRESS keeps every
@@ -77,9 +80,9 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
   const unsigned short* pb[B_CH];
   bool oka[A_CH], okb[B_CH];
 #pragma unroll
-  for (int i = 0; i < A_CH; ++i) oka[i] = m0 + crow + i * 32 < a.M;
+  for (int i = 0; i < A_CH; ++i) oka[i] = m0 + crow + i * 64 < a.M;
 #pragma unroll
-  for (int i = 0; i < B_CH; ++i) okb[i] = n0 + crow + i * 32 < a.N;
+  for (int i = 0; i < B_CH; ++i) okb[i] = n0 + crow + i * 64 < a.N;
   int seg = -1, k0 = 0, kend = 0, Kseg = 0;
 
   // (written out with macros rather than lambdas: arrays captured by reference ended up in scratch)
@@ -96,9 +99,9 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
       const unsigned short* A_ = sg.A + z0 * sg.a_bs0 + z1 * sg.a_bs1 + z2 * sg.a_bs2;                    \
       const unsigned short* B_ = sg.B + z0 * sg.b_bs0 + z1 * sg.b_bs1 + z2 * sg.b_bs2;                    \
       _Pragma("unroll") for (int i = 0; i < A_CH; ++i)                                                    \
-          pa[i] = A_ + (long long)(m0 + crow + i * 32) * sg.lda + k0 + ckc;                               \
+          pa[i] = A_ + (long long)(m0 + crow + i * 64) * sg.lda + k0 + ckc;                               \
       _Pragma("unroll") for (int i = 0; i < B_CH; ++i)                                                    \
-          pb[i] = B_ + (long long)(n0 + crow + i * 32) * sg.ldb + k0 + ckc;                               \
+          pb[i] = B_ + (long long)(n0 + crow + i * 64) * sg.ldb + k0 + ckc;                               \
     }                                                                                                     \
   } while (0)
 #define LDA_(S, i) S##a##i = *((kok && oka[i]) ? reinterpret_cast<const uint4*>(pa[i]) : zero16)
@@ -108,17 +111,15 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
 #define FETCH(S, valid)                                                                                   \
   do {                                                                                                    \
     const bool kok = (valid) && (k0 + ckc < Kseg);                                                        \
-    LDA_(S, 0); LDA_(S, 1); LDA_(S, 2); LDA_(S, 3); LDA_(S, 4); LDA_(S, 5); LDA_(S, 6); LDA_(S, 7);       \
-    LDB_(S, 0); LDB_(S, 1); LDB_(S, 2); LDB_(S, 3);                                                       \
+    LDA_(S, 0); LDA_(S, 1); LDA_(S, 2); LDA_(S, 3); LDB_(S, 0); LDB_(S, 1);                               \
   } while (0)
-#define STA_(S, i) *reinterpret_cast<uint4*>(sa_ + (crow + i * 32) * ROWB + ckc * 2) = S##a##i
-#define STB_(S, i) *reinterpret_cast<uint4*>(sb_ + (crow + i * 32) * ROWB + ckc * 2) = S##b##i
+#define STA_(S, i) *reinterpret_cast<uint4*>(sa_ + (crow + i * 64) * ROWB + ckc * 2) = S##a##i
+#define STB_(S, i) *reinterpret_cast<uint4*>(sb_ + (crow + i * 64) * ROWB + ckc * 2) = S##b##i
 #define STASH(S, buf_)                                                                                    \
   do {                                                                                                    \
     char* sa_ = smem + (buf_) * STAGE;                                                                    \
     char* sb_ = sa_ + A_STAGE;                                                                            \
-    STA_(S, 0); STA_(S, 1); STA_(S, 2); STA_(S, 3); STA_(S, 4); STA_(S, 5); STA_(S, 6); STA_(S, 7);       \
-    STB_(S, 0); STB_(S, 1); STB_(S, 2); STB_(S, 3);                                                       \
+    STA_(S, 0); STA_(S, 1); STA_(S, 2); STA_(S, 3); STB_(S, 0); STB_(S, 1);                               \
   } while (0)
 #define ADVANCE()                                                                                         \
   do {                                                                                                    \
@@ -133,15 +134,15 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
   } while (0)
 #define COMPUTE(buf_)                                                                                     \
   do {                                                                                                    \
-    const char* sa_ = smem + (buf_) * STAGE + (wm * 128 + (lane & 31)) * ROWB + (lane >> 5) * 16;         \
+    const char* sa_ = smem + (buf_) * STAGE + (wm * 64 + (lane & 31)) * ROWB + (lane >> 5) * 16;         \
     const char* sb_ = smem + (buf_) * STAGE + A_STAGE + (wn * 64 + (lane & 31)) * ROWB + (lane >> 5) * 16; \
     _Pragma("unroll") for (int sub = 0; sub < BK / 16; ++sub) {                                           \
-      uint4 fa[4], fb[2];                                                                                 \
-      _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                       \
+      uint4 fa[2], fb[2];                                                                                 \
+      _Pragma("unroll") for (int i = 0; i < 2; ++i)                                                       \
           fa[i] = *reinterpret_cast<const uint4*>(sa_ + i * 32 * ROWB + sub * 32);                        \
       _Pragma("unroll") for (int j = 0; j < 2; ++j)                                                       \
           fb[j] = *reinterpret_cast<const uint4*>(sb_ + j * 32 * ROWB + sub * 32);                        \
-      _Pragma("unroll") for (int i = 0; i < 4; ++i) _Pragma("unroll") for (int j = 0; j < 2; ++j)         \
+      _Pragma("unroll") for (int i = 0; i < 2; ++i) _Pragma("unroll") for (int j = 0; j < 2; ++j)         \
           acc[i][j] = HALF ? __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, fa[i]),     \
                                                                     __builtin_bit_cast(f16x8, fb[j]), acc[i][j], 0, 0, 0)  \
                            : __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[i]),   \
@@ -206,14 +207,14 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
   const float* Rs = a.res ? a.res + z0 * a.cf_bs0 + z1 * a.cf_bs1 + z2 * a.cf_bs2 : nullptr;
   unsigned short* Ct = a.Ct ? a.Ct + z0 * a.ct_bs0 + z1 * a.ct_bs1 + z2 * a.ct_bs2 : nullptr;
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < 2; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       const int n = n0 + wn * 64 + j * 32 + col_l;
       if (n >= a.N) continue;
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const int mb = m0 + wm * 128 + i * 32 + q * 8 + rgrp;
+        const int mb = m0 + wm * 64 + i * 32 + q * 8 + rgrp;
         float o[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
@@ -316,9 +317,9 @@ harli_status gemm_launch(const GemmArgs& a, int batches, hipStream_t st) {
     HARLI_HIP(hipEventRecord(rec.e0, st));
   }
   if (a.half)
-    hipLaunchKernelGGL(k_gemm<true>, dim3(chunk * 8, 1, batches), dim3(256), LDS_BYTES, st, a, tiles_n, total, chunk, GM, GN, zero16);
+    hipLaunchKernelGGL(k_gemm<true>, dim3(chunk * 8, 1, batches), dim3(NT), LDS_BYTES, st, a, tiles_n, total, chunk, GM, GN, zero16);
   else
-    hipLaunchKernelGGL(k_gemm<false>, dim3(chunk * 8, 1, batches), dim3(256), LDS_BYTES, st, a, tiles_n, total, chunk, GM, GN, zero16);
+    hipLaunchKernelGGL(k_gemm<false>, dim3(chunk * 8, 1, batches), dim3(NT), LDS_BYTES, st, a, tiles_n, total, chunk, GM, GN, zero16);
   if (g_prof_on) {
     HARLI_HIP(hipEventRecord(rec.e1, st));
     g_prof.push_back(rec);
