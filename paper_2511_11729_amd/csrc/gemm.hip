@@ -206,32 +206,98 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
   float* Cf = a.Cf ? a.Cf + z0 * a.cf_bs0 + z1 * a.cf_bs1 + z2 * a.cf_bs2 : nullptr;
   const float* Rs = a.res ? a.res + z0 * a.cf_bs0 + z1 * a.cf_bs1 + z2 * a.cf_bs2 : nullptr;
   unsigned short* Ct = a.Ct ? a.Ct + z0 * a.ct_bs0 + z1 * a.ct_bs1 + z2 * a.ct_bs2 : nullptr;
+  // Row-major outputs go through LDS (free after the K loop's last barrier; each wave uses a region of its own) so
+  // that every global access is 16 bytes per lane along a row: 64-column rows of fp32 are 256 contiguous bytes,
+  // the residual is read the same way, and all residual loads of a 32-row slab are in flight together.
+  constexpr int ER = 72 * 4;  // staged row: 64 fp32 + 8 pad (4 rows further = 32 banks further)
+  static_assert(8 * 32 * ER <= LDS_BYTES, "epilogue staging must fit the K-loop buffers");
+  char* ebuf = smem + wave * (32 * ER);
+  const bool vok = ((a.ldcf | a.ldcb) & 3) == 0 && ((reinterpret_cast<uintptr_t>(Cf) | reinterpret_cast<uintptr_t>(Rs)) & 15) == 0 &&
+                   (reinterpret_cast<uintptr_t>(Cb) & 7) == 0;
+  // whole rows of eight 16-bit columns: N and the row stride multiples of 8, 16-byte aligned base
+  const bool vok8 = ((a.ldcb | a.N) & 7) == 0 && (reinterpret_cast<uintptr_t>(Cb) & 15) == 0;
+  if (Cf || Cb) {
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < 2; ++i) {
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const int n = n0 + wn * 64 + j * 32 + col_l;
-      if (n >= a.N) continue;
+      for (int j = 0; j < 2; ++j)
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int mb = m0 + wm * 64 + i * 32 + q * 8 + rgrp;
-        float o[4];
+        for (int v = 0; v < 16; ++v)
+          *reinterpret_cast<float*>(ebuf + (8 * (v >> 2) + rgrp + (v & 3)) * ER + (j * 32 + col_l) * 4) = acc[i][j][v] * a.alpha;
+      __builtin_amdgcn_wave_barrier();
+      if (!Cf && vok8) {  // 16-bit output only: eight columns (16 bytes) per lane, eight rows per pass
+        const int c8 = (lane & 7) * 8, n8 = n0 + wn * 64 + c8;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          o[e] = acc[i][j][q * 4 + e] * a.alpha;
-          const int m = mb + e;
-          if (m < a.M) {
-            if (Cf) {
-              const float r = Rs ? Rs[(long long)m * a.ldcf + n] : 0.f;
-              o[e] += r;
-              Cf[(long long)m * a.ldcf + n] = o[e];
-            }
-            if (Cb) Cb[(long long)m * a.ldcb + n] = HALF ? f2h(o[e]) : f2bf(o[e]);
-          }
+        for (int it = 0; it < 4; ++it) {
+          const int row = it * 8 + (lane >> 3);
+          const int m = m0 + wm * 64 + i * 32 + row;
+          const float4 lo = *reinterpret_cast<const float4*>(ebuf + row * ER + c8 * 4);
+          const float4 hi = *reinterpret_cast<const float4*>(ebuf + row * ER + c8 * 4 + 16);
+          if (m < a.M && n8 < a.N)
+            *reinterpret_cast<uint4*>(Cb + (long long)m * a.ldcb + n8) =
+                HALF ? make_uint4(pack_h2(lo.x, lo.y), pack_h2(lo.z, lo.w), pack_h2(hi.x, hi.y), pack_h2(hi.z, hi.w))
+                     : make_uint4(pack_bf2(lo.x, lo.y), pack_bf2(lo.z, lo.w), pack_bf2(hi.x, hi.y), pack_bf2(hi.z, hi.w));
         }
-        if (Ct) {
+        __builtin_amdgcn_wave_barrier();
+        continue;
+      }
+      const int c4 = (lane & 15) * 4, n = n0 + wn * 64 + c4;
+      const bool nvec = vok && n + 3 < a.N;
+      float4 rv[8];
+#pragma unroll
+      for (int it = 0; it < 8; ++it) {
+        const int m = m0 + wm * 64 + i * 32 + it * 4 + (lane >> 4);
+        rv[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (Rs && nvec && m < a.M) rv[it] = *reinterpret_cast<const float4*>(Rs + (long long)m * a.ldcf + n);
+      }
+#pragma unroll
+      for (int it = 0; it < 8; ++it) {
+        const int row = it * 4 + (lane >> 4);
+        const int m = m0 + wm * 64 + i * 32 + row;
+        float4 o = *reinterpret_cast<const float4*>(ebuf + row * ER + c4 * 4);
+        if (m >= a.M || n >= a.N) continue;
+        if (nvec) {
+          o.x += rv[it].x, o.y += rv[it].y, o.z += rv[it].z, o.w += rv[it].w;
+          if (Cf) *reinterpret_cast<float4*>(Cf + (long long)m * a.ldcf + n) = o;
+          if (Cb)
+            *reinterpret_cast<uint2*>(Cb + (long long)m * a.ldcb + n) =
+                HALF ? make_uint2(pack_h2(o.x, o.y), pack_h2(o.z, o.w)) : make_uint2(pack_bf2(o.x, o.y), pack_bf2(o.z, o.w));
+        } else {
+          const float ov[4] = {o.x, o.y, o.z, o.w};
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (n + e < a.N) {
+              float x = ov[e];
+              if (Cf) {
+                if (Rs) x += Rs[(long long)m * a.ldcf + n + e];
+                Cf[(long long)m * a.ldcf + n + e] = x;
+              }
+              if (Cb) Cb[(long long)m * a.ldcb + n + e] = HALF ? f2h(x) : f2bf(x);
+            }
+        }
+      }
+      __builtin_amdgcn_wave_barrier();
+    }
+  }
+  // transposed 16-bit output straight from the accumulators (a lane holds runs of four rows of one column)
+  if (Ct) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int n = n0 + wn * 64 + j * 32 + col_l;
+        if (n >= a.N) continue;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int mb = m0 + wm * 64 + i * 32 + q * 8 + rgrp;
+          float o[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            o[e] = acc[i][j][q * 4 + e] * a.alpha;
+            if (Cf && Rs && mb + e < a.M) o[e] += Rs[(long long)(mb + e) * a.ldcf + n];
+          }
           unsigned short* p = Ct + (long long)n * a.ldct + mb;
-          if (mb + 3 < a.M && ((a.ldct & 3) == 0)) {
+          if (mb + 3 < a.M && ((a.ldct & 3) == 0) && (reinterpret_cast<uintptr_t>(Ct) & 7) == 0) {
             *reinterpret_cast<uint2*>(p) = HALF ? make_uint2(pack_h2(o[0], o[1]), pack_h2(o[2], o[3]))
                                                 : make_uint2(pack_bf2(o[0], o[1]), pack_bf2(o[2], o[3]));
           } else {
@@ -241,7 +307,7 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
           }
         }
       }
-    }
+  }
 }
 
 }  // namespace
