@@ -45,9 +45,9 @@ struct FtWs {
   char* base = nullptr;
   float *scores = nullptr, *dP = nullptr, *ST = nullptr, *dPT = nullptr, *delta = nullptr, *dm = nullptr, *dh2 = nullptr,
         *dx1 = nullptr, *dh = nullptr, *gpart = nullptr;
-  bf *vT = nullptr, *At = nullptr, *Bt = nullptr, *dyb = nullptr, *da = nullptr, *du = nullptr, *dx1b = nullptr, *dob = nullptr,
+  bf *vT = nullptr, *At[kTargets] = {}, *Bt[kTargets] = {}, *dyb = nullptr, *da = nullptr, *du = nullptr, *dx1b = nullptr, *dob = nullptr,
      *doT = nullptr, *dS = nullptr, *PT = nullptr, *dST = nullptr, *qT = nullptr, *kT = nullptr, *dq = nullptr, *dkq = nullptr,
-     *dvq = nullptr, *dk = nullptr, *dv = nullptr, *gs[3] = {}, *An[3] = {}, *Bn = nullptr;
+     *dvq = nullptr, *dk = nullptr, *dv = nullptr, *gs[3] = {}, *An[kTargets] = {}, *Bn[kTargets] = {};
   float* scale = nullptr;  // [0] sigma, [1] 1/sigma, [2] scratch: gradient scaling of the backward pass
   int Bf = 0, S = 0;
 };
@@ -96,8 +96,9 @@ harli_status ensure_ws(harli_ctx* c, int Bf, int S) {
   const size_t o_delta = take((size_t)D.Z * S * 4);
   const size_t o_dm = take(T * D.F * 4), o_dh2 = take(T * D.H * 4), o_dx1 = take(T * D.H * 4), o_dh = take(T * D.H * 4);
   const size_t o_vT = take(T * D.KVD * 2), o_kT = take(T * D.KVD * 2), o_qT = take(T * D.QD * 2), o_doT = take(T * D.QD * 2);
-  const size_t o_At = take(maxdim * D.r * 2), o_Bt = take(maxdim * D.r * 2);
-  const size_t o_An = take(3 * al(maxdim * D.r * 2)), o_Bn = take(maxdim * D.r * 2), o_scale = take(64);
+  const size_t ad = al(maxdim * D.r * 2);  // one adapter matrix in the compute element
+  const size_t o_At = take(kTargets * ad), o_Bt = take(kTargets * ad);
+  const size_t o_An = take(kTargets * ad), o_Bn = take(kTargets * ad), o_scale = take(64);
   const size_t o_dyb = take(T * D.H * 2), o_da = take(T * D.F * 2), o_du = take(T * D.F * 2), o_dx1b = take(T * D.H * 2);
   const size_t o_dob = take(T * D.QD * 2), o_dq = take(T * D.QD * 2), o_dkq = take(T * D.QD * 2), o_dvq = take(T * D.QD * 2);
   const size_t o_dk = take(T * D.KVD * 2), o_dv = take(T * D.KVD * 2), o_gs = take(3 * al(T * D.r * 2));
@@ -114,13 +115,16 @@ harli_status ensure_ws(harli_ctx* c, int Bf, int S) {
   w.dS = (bf*)(b + o_dS); w.PT = (bf*)(b + o_PT); w.dST = (bf*)(b + o_dST); w.delta = (float*)(b + o_delta);
   w.dm = (float*)(b + o_dm); w.dh2 = (float*)(b + o_dh2); w.dx1 = (float*)(b + o_dx1); w.dh = (float*)(b + o_dh);
   w.vT = (bf*)(b + o_vT); w.kT = (bf*)(b + o_kT); w.qT = (bf*)(b + o_qT); w.doT = (bf*)(b + o_doT);
-  w.At = (bf*)(b + o_At); w.Bt = (bf*)(b + o_Bt); w.dyb = (bf*)(b + o_dyb); w.da = (bf*)(b + o_da); w.du = (bf*)(b + o_du);
+  w.dyb = (bf*)(b + o_dyb); w.da = (bf*)(b + o_da); w.du = (bf*)(b + o_du);
   w.dx1b = (bf*)(b + o_dx1b); w.dob = (bf*)(b + o_dob); w.dq = (bf*)(b + o_dq); w.dkq = (bf*)(b + o_dkq);
   w.dvq = (bf*)(b + o_dvq); w.dk = (bf*)(b + o_dk); w.dv = (bf*)(b + o_dv); 
   for (int i = 0; i < 3; ++i) w.gs[i] = (bf*)(b + o_gs + i * al(T * D.r * 2));
   w.gpart = (float*)(b + o_gpart);
-  for (int i = 0; i < 3; ++i) w.An[i] = (bf*)(b + o_An + i * al(maxdim * D.r * 2));
-  w.Bn = (bf*)(b + o_Bn); w.scale = (float*)(b + o_scale);
+  for (int i = 0; i < kTargets; ++i) {
+    w.At[i] = (bf*)(b + o_At + i * ad); w.Bt[i] = (bf*)(b + o_Bt + i * ad);
+    w.An[i] = (bf*)(b + o_An + i * ad); w.Bn[i] = (bf*)(b + o_Bn + i * ad);
+  }
+  w.scale = (float*)(b + o_scale);
   w.Bf = Bf;
   w.S = S;
   return HARLI_OK;
@@ -149,6 +153,22 @@ void add_seg(GemmArgs& g, const bf* A, long long lda, const bf* B, long long ldb
   s.ldb = ldb;
 }
 
+// Every adapted projection's A and B (bf16 storage, contents may change between calls) converted to the compute
+// element in ONE launch: transposed copies for the forward pass, natural ones for the backward pass.
+void convert_adapters(harli_ctx* c, const LayerDev& L, bool transposed, hipStream_t st) {
+  FtWs& w = state(c)->ws;
+  FtConvJobs jobs{};
+  for (int t = 0; t < kTargets; ++t) {
+    if (!adapted(c, t)) continue;
+    int out, in;
+    proj_shape(c->cfg, t, &out, &in);
+    const int r = c->lora.rank;
+    jobs.j[jobs.n++] = FtConvJob{static_cast<const bf*>(L.A[t]), transposed ? w.At[t] : w.An[t], in, r, transposed ? 1 : 0};
+    jobs.j[jobs.n++] = FtConvJob{static_cast<const bf*>(L.B[t]), transposed ? w.Bt[t] : w.Bn[t], r, out, transposed ? 1 : 0};
+  }
+  if (jobs.n) ft_convert_jobs(jobs, st);
+}
+
 // forward of one projection: out = xin . W^T (+ us . Bt^T), us = s * xin . A kept for backward
 harli_status proj_fwd(harli_ctx* c, const LayerDev& L, int t, const bf* xin, int T, harli_saved* sv, GemmArgs& g, hipStream_t st) {
   int out, in;
@@ -157,16 +177,15 @@ harli_status proj_fwd(harli_ctx* c, const LayerDev& L, int t, const bf* xin, int
   add_seg(g, xin, in, static_cast<const bf*>(L.w16[t]), in, in);
   if (adapted(c, t)) {
     const int r = c->lora.rank;
-    ft_transpose_from_bf16(static_cast<const bf*>(L.A[t]), w.At, in, r, st);   // A [in, r] -> [r, in]
-    ft_skinny_nt(xin, in, w.At, in, sv->us[t], r, T, r, in, lscale(c), st);     // us = s * x . A
-    ft_transpose_from_bf16(static_cast<const bf*>(L.B[t]), w.Bt, r, out, st);  // B [r, out] -> [out, r]
-    add_seg(g, sv->us[t], r, w.Bt, r, r);
+    // ws.At[t] = A^T [r, in] and ws.Bt[t] = B^T [out, r] were made by convert_adapters at the top of the call
+    ft_skinny_nt(xin, in, w.At[t], in, sv->us[t], r, T, r, in, lscale(c), st);  // us = s * x . A
+    add_seg(g, sv->us[t], r, w.Bt[t], r, r);
   }
   return gemm_launch(g, 1, st);
 }
 
 // adapter gradients of one projection given dy (bf16 [T, out]) and its input xin (bf16 [T, in]);
-// leaves gs = s * dy . B^T in ws.gs[slot] and A (compute element, [in, r]) in ws.An[slot]: the caller adds them
+// leaves gs = s * dy . B^T in ws.gs[slot]: the caller adds (gs, ws.An[t])
 // to its dx GEMM as one more K segment (dx += gs . A^T)
 harli_status proj_grads(harli_ctx* c, const LayerDev& L, int t, int slot, const bf* dy, const bf* xin, int T,
                         const harli_saved* sv, float* const* dA, float* const* dB, hipStream_t st) {
@@ -174,9 +193,8 @@ harli_status proj_grads(harli_ctx* c, const LayerDev& L, int t, int slot, const 
   proj_shape(c->cfg, t, &out, &in);
   FtWs& w = state(c)->ws;
   const int r = c->lora.rank;
-  ft_from_bf16(static_cast<const bf*>(L.B[t]), w.Bn, (long long)r * out, st);
-  ft_from_bf16(static_cast<const bf*>(L.A[t]), w.An[slot], (long long)in * r, st);
-  ft_skinny_nt(dy, out, w.Bn, out, w.gs[slot], r, T, r, out, lscale(c), st);        // gs = s * dy . B^T   (carries sigma)
+  // ws.An[t] = A [in, r] and ws.Bn[t] = B [r, out] in the compute element were made by convert_adapters
+  ft_skinny_nt(dy, out, w.Bn[t], out, w.gs[slot], r, T, r, out, lscale(c), st);     // gs = s * dy . B^T   (carries sigma)
   ft_lora_grad(xin, in, w.gs[slot], r, dA[t], r, 1, T, in, r, w.scale + 1, w.gpart, st);     // dA += x^T gs / sigma
   ft_lora_grad(dy, out, sv->us[t], r, dB[t], 1, out, T, out, r, w.scale + 1, w.gpart, st);  // dB += us^T dy / sigma
   return HARLI_OK;
@@ -366,6 +384,7 @@ extern "C" harli_status harli_lora_fwd(harli_ctx* c, int32_t layer, const float*
   } while (0)
 
   const int T = D.T;
+  convert_adapters(c, L, true, st);
   ft_rmsnorm_fwd(X, L.g1, sv->h, sv->rho1, T, D.H, m.rms_eps, st);
   {
     GemmArgs g = plain_gemm(T, D.QD);
@@ -473,6 +492,7 @@ extern "C" harli_status harli_lora_bwd(harli_ctx* c, int32_t layer, const float*
   } while (0)
 
   // ---- FFN ----
+  convert_adapters(c, L, false, st);
   ft_make_scale(dY, (long long)T * D.H, w.scale, st);
   ft_f32_to_e(dY, w.dyb, (long long)T * D.H, w.scale, st);  // every gradient below carries the factor sigma
   {
@@ -480,7 +500,7 @@ extern "C" harli_status harli_lora_bwd(harli_ctx* c, int32_t layer, const float*
     add_seg(g, w.dyb, D.H, static_cast<const bf*>(L.wt[6]), D.H, D.H);
     if (adapted(c, 6)) {
       RUNB(proj_grads(c, L, 6, 0, w.dyb, sv->m, T, sv, dA, dB, st));
-      add_seg(g, w.gs[0], D.r, w.An[0], D.r, D.r);
+      add_seg(g, w.gs[0], D.r, w.An[6], D.r, D.r);
     }
     g.Cf = w.dm; g.ldcf = D.F;
     RUNB(gemm_launch(g, 1, st));
@@ -493,7 +513,7 @@ extern "C" harli_status harli_lora_bwd(harli_ctx* c, int32_t layer, const float*
     for (int t = 4; t <= 5; ++t)
       if (adapted(c, t)) {  // dh2 += gs_t A_t^T as one more K segment
         RUNB(proj_grads(c, L, t, t - 4, t == 4 ? w.da : w.du, sv->h2, T, sv, dA, dB, st));
-        add_seg(g, w.gs[t - 4], D.r, w.An[t - 4], D.r, D.r);
+        add_seg(g, w.gs[t - 4], D.r, w.An[t], D.r, D.r);
       }
     g.Cf = w.dh2; g.ldcf = D.H;
     RUNB(gemm_launch(g, 1, st));
@@ -506,7 +526,7 @@ extern "C" harli_status harli_lora_bwd(harli_ctx* c, int32_t layer, const float*
     add_seg(g, w.dx1b, D.H, static_cast<const bf*>(L.wt[3]), D.H, D.H);
     if (adapted(c, 3)) {
       RUNB(proj_grads(c, L, 3, 0, w.dx1b, sv->o, T, sv, dA, dB, st));
-      add_seg(g, w.gs[0], D.r, w.An[0], D.r, D.r);
+      add_seg(g, w.gs[0], D.r, w.An[3], D.r, D.r);
     }
     g.Cb = w.dob; g.ldcb = D.QD;
     RUNB(gemm_launch(g, 1, st));

@@ -29,6 +29,18 @@ void ft_make_scale(const float* x, long long n, float* scale, hipStream_t st);
 // bf16 storage -> compute element: plain copy and [R][C] -> [C][R] transpose
 void ft_from_bf16(const bf* in, bf* out, long long n, hipStream_t st);
 void ft_transpose_from_bf16(const bf* in, bf* out, int R, int C, hipStream_t st);
+// Several small bf16 -> compute-element conversions in one launch: src [R][C] -> dst [R][C], or dst [C][R] when
+// transpose is set (meant for adapter matrices: the strided side is not tuned)
+struct FtConvJob {
+  const bf* src;
+  bf* dst;
+  int R, C, transpose;
+};
+struct FtConvJobs {
+  FtConvJob j[16];
+  int n;
+};
+void ft_convert_jobs(const FtConvJobs& jobs, hipStream_t st);
 // batched transpose: in [Z][R][C] (row stride ldi, batch stride bsi) -> out [Z][C][R]
 void ft_transpose(const bf* in, bf* out, int Z, int R, int C, long long ldi, long long bsi, long long ldo, long long bso,
                   hipStream_t st);

@@ -74,10 +74,36 @@ __global__ void __launch_bounds__(256) k_rmsnorm_bwd(const float* dh, const floa
 }
 
 // ---------------------------------------------------------------- rotary embedding, pairs (i, i + d/2)
+// one thread rotates eight adjacent pairs with two 16-byte loads and stores when d/2 is a multiple of 8 (rows are
+// 16-byte aligned then: heads*d is a multiple of 8); other head sizes take the pair-at-a-time loop
 __global__ void __launch_bounds__(256) k_rope(bf* x, int S, int heads, int d, const double* inv_freq, float sign) {
   const int t = blockIdx.x, half = d >> 1;
   const double pos = (double)(t % S);
   bf* row = x + (size_t)t * heads * d;
+  if ((half & 7) == 0) {
+    const int per_head = half >> 3;
+    for (int idx = threadIdx.x; idx < heads * per_head; idx += 256) {
+      const int hh = idx / per_head, i0 = (idx - hh * per_head) * 8;
+      bf* p = row + hh * d + i0;
+      const uint4 lo4 = *reinterpret_cast<const uint4*>(p), hi4 = *reinterpret_cast<const uint4*>(p + half);
+      float lo[8], hi[8], ol[8], oh[8];
+      UNPACK8(lo4, lo);
+      UNPACK8(hi4, hi);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const double ang = pos * inv_freq[i0 + e];
+        const double red = ang - 6.283185307179586476925 * rint(ang * 0.15915494309189533577);
+        float sn, cs;
+        sincosf((float)red, &sn, &cs);
+        sn *= sign;
+        ol[e] = lo[e] * cs - hi[e] * sn;
+        oh[e] = hi[e] * cs + lo[e] * sn;
+      }
+      *reinterpret_cast<uint4*>(p) = make_uint4(PACK2(ol[0], ol[1]), PACK2(ol[2], ol[3]), PACK2(ol[4], ol[5]), PACK2(ol[6], ol[7]));
+      *reinterpret_cast<uint4*>(p + half) = make_uint4(PACK2(oh[0], oh[1]), PACK2(oh[2], oh[3]), PACK2(oh[4], oh[5]), PACK2(oh[6], oh[7]));
+    }
+    return;
+  }
   for (int idx = threadIdx.x; idx < heads * half; idx += 256) {
     const int hh = idx / half, i = idx - hh * half;
     const double ang = pos * inv_freq[i];
@@ -393,6 +419,20 @@ __global__ void __launch_bounds__(256) k_sum_groups(const bf* in, bf* out, long 
   out[i] = F2E(s);
 }
 
+__global__ void __launch_bounds__(256) k_convert_jobs(FtConvJobs jobs) {
+  const FtConvJob jb = jobs.j[blockIdx.y];
+  const long long n = (long long)jb.R * jb.C;
+  for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n; i += (long long)gridDim.x * 256) {
+    const unsigned short v = F2E(bf2f(jb.src[i]));
+    if (jb.transpose) {
+      const int r = (int)(i / jb.C), c = (int)(i - (long long)r * jb.C);
+      jb.dst[(long long)c * jb.R + r] = v;
+    } else {
+      jb.dst[i] = v;
+    }
+  }
+}
+
 inline unsigned nblk(long long n, int per) { return (unsigned)((n + per - 1) / per); }
 
 }  // namespace
@@ -427,6 +467,9 @@ void ft_transpose(const bf* in, bf* out, int Z, int R, int C, long long ldi, lon
 void ft_transpose_from_bf16(const bf* in, bf* out, int R, int C, hipStream_t st) {
   hipLaunchKernelGGL(k_transpose<true>, dim3((C + 63) / 64, (R + 63) / 64, 1), dim3(256), 0, st, in, out, R, C,
                      (long long)C, 0LL, (long long)R, 0LL);
+}
+void ft_convert_jobs(const FtConvJobs& jobs, hipStream_t st) {
+  hipLaunchKernelGGL(k_convert_jobs, dim3(64, jobs.n), dim3(256), 0, st, jobs);
 }
 void ft_from_bf16(const bf* in, bf* out, long long n, hipStream_t st) {
   hipLaunchKernelGGL(k_from_bf16, dim3(nblk(n, 256)), dim3(256), 0, st, in, out, n);
