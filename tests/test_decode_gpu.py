@@ -183,3 +183,49 @@ def test_fp32_three_layer_model_with_embedding_and_logits():
     srt = np.sort(ref_logits, axis=-1)
     clear = (srt[:, -1] - srt[:, -2]) > 2e-4 * np.max(np.abs(ref_logits))
     assert np.array_equal(nxt[clear], ref_next[clear])
+
+
+# ---- the other workloads at their real layer width (depth cut to what the oracle finishes in seconds) ----
+
+def test_config2_width_two_layers_batch16_with_logits():
+    """7B-class model, batch 16 at 1024 cached tokens, embedding + 2 of the 32 layers + output layer (V = 32000)."""
+    w, m = variant(2, n_layers=2)
+    lengths = wl.draw_lengths(w)
+    assert len(lengths) == 16 and int(lengths[0]) == 1024
+    case = DecodeCase(w, m, lengths, full_model=True)
+    tok = wl.make_token_ids(dataclasses.replace(w, model=m), (16,))
+    hid = case.run_gpu(token_ids=tok)
+    ref_hid, ref_logits, ref_next = case.run_oracle(token_ids=tok)
+    assert_close(hid, ref_hid, "hidden state")
+    logits = case.logits_dev.cpu().numpy()
+    assert_close(logits, ref_logits, "logits")
+    case.check_cache()
+    nxt = case.next_dev.cpu().numpy()
+    assert np.array_equal(nxt, np.argmax(logits, axis=-1))
+    srt = np.sort(ref_logits, axis=-1)
+    clear = (srt[:, -1] - srt[:, -2]) > 4e-2 * np.max(np.abs(ref_logits))
+    assert np.array_equal(nxt[clear], ref_next[clear])
+
+
+def test_config2_width_batch256():
+    """The largest decode batch of the sweep (four passes of 64 rows) on one 7B-class layer."""
+    w, m = variant(2, n_layers=1)
+    run_case(w, m, [100 + (i * 37) % 400 for i in range(256)])
+
+
+def test_config3_width_layer_lognormal_lengths():
+    """13B-class layer (hidden 5120, 40 heads, ffn 13824): 160 KiB pages do not divide the 2 MiB block (12 + slack),
+    batch 32 with log-normal lengths capped at 4096."""
+    w, m = variant(3, n_layers=1)
+    lengths = wl.draw_lengths(w)
+    case, stats = run_case(w, m, lengths)
+    assert case.geom.pages_per_block == 12
+    print("config 3 layer decode parity: max-abs ratio %.2e, rel-Fro %.2e, lengths %d..%d" % (stats + (lengths.min(), lengths.max())))
+
+
+def test_config4_width_layer_gqa_long_context():
+    """8B-class GQA layer (32 query / 8 KV heads, ffn 14336), batch 8, log-normal lengths capped at 8192."""
+    w, m = variant(4, n_layers=1)
+    lengths = wl.draw_lengths(w)
+    case, stats = run_case(w, m, lengths)
+    print("config 4 layer decode parity: max-abs ratio %.2e, rel-Fro %.2e, lengths %d..%d" % (stats + (lengths.min(), lengths.max())))

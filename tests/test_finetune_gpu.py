@@ -114,3 +114,20 @@ def test_config1_full_size_layer():
     case = FinetuneCase(w, w.model, w.lora, w.finetune)
     r = check(case)
     print({k: "%.1e/%.1e" % v for k, v in r.items()})
+
+
+def test_config3_width_layer_rank64_all_targets():
+    """13B-class layer (hidden 5120, 40 x 128 heads, ffn 13824), r 64 on all seven projections, 2 x 1024 tokens
+    (half of the workload's micro-batch of 4: the oracle's time is linear in it)."""
+    w = wl.workload(3)
+    m = dataclasses.replace(w.model, n_layers=1)
+    case = FinetuneCase(w, m, w.lora, wl.FinetuneCfg(2, 1024))
+    check(case, "config 3 layer")
+
+
+def test_config4_width_layer_gqa_rank32():
+    """8B-class GQA layer (32 query / 8 KV heads, ffn 14336), r 32 on q,k,v,o, 4 x 512 tokens."""
+    w = wl.workload(4)
+    m = dataclasses.replace(w.model, n_layers=1)
+    case = FinetuneCase(w, m, w.lora, wl.FinetuneCfg(4, 512))
+    check(case, "config 4 layer")
