@@ -37,6 +37,10 @@ sys.path.insert(0, ROOT)
 SLO_MS_FULL_MODEL = 40.0          # paper Sec. 8.1: TPOT QoS target
 PEAK_MFMA_TFLOPS = 2500.0         # MI355X dense fp16/bf16
 PEAK_HBM_GBS = 8000.0
+# HBM traffic per launch / per step from the rocprofv3 FETCH_SIZE and WRITE_SIZE counter runs summarised in
+# profiles/bench_config1_hbm_traffic.md (each scaled by what the same counter reads for a 256 MiB device copy)
+TRAFFIC_GEMM_BYTES_PER_LAUNCH = 377.1e6      # k_gemm, average over the 11 launches of a finetune unit
+TRAFFIC_DECODE_BYTES_PER_STEP = 559.5e6      # all kernels of one decode step
 
 
 def log(*a):
@@ -321,6 +325,13 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
 
+    # measured ceilings of this GPU (plain read kernels of the library's debug ABI): what HBM and the L2 caches deliver
+    probe = torch.empty(6 << 30, dtype=torch.uint8, device=dev)
+    peaks = {"hbm_stream_read_GBs": hb.dbg_read_bandwidth(probe, 0), "l2_to_cu_read_GBs": hb.dbg_read_bandwidth(probe, 1),
+             "note": "the GEMM's workgroups pull (256+128) x K x 2 bytes of operand panels per 256x128 tile through L2: at "
+                     "the L2 rate above that bounds it below the MFMA peak"}
+    del probe
+
     ach_tf = gemm_flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else float("nan")
     out = {
         "metric": "LoRA finetune tokens/s under decode TPOT SLO",
@@ -336,11 +347,11 @@ def main():
                 "decode_step_latency_ms_p50": float(np.percentile(closed["steplat"], 50)),
                 "decode_step_latency_ms_p99": float(np.percentile(closed["steplat"], 99))},
         "roofline": {"bound": "mfma", "achieved": ach_tf, "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s",
-                     "frac": ach_tf / PEAK_MFMA_TFLOPS, "traffic": None, "kernel": "k_gemm<half>",
+                     "frac": ach_tf / PEAK_MFMA_TFLOPS, "traffic": TRAFFIC_GEMM_BYTES_PER_LAUNCH, "kernel": "k_gemm<half>",
                      "launches": int(gemm_n), "avg_launch_us": gemm_ms * 1e3 / max(gemm_n, 1),
                      "note": "co-located with decode; flops = 2MNK per launch (causal launches count half)"},
         "roofline_decode": {"bound": "hbm", "achieved": dec_bytes / (tpot_mean * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
-                            "unit": "GB/s", "frac": dec_bytes / (tpot_mean * 1e-3) / 1e9 / PEAK_HBM_GBS, "traffic": None,
+                            "unit": "GB/s", "frac": dec_bytes / (tpot_mean * 1e-3) / 1e9 / PEAK_HBM_GBS, "traffic": TRAFFIC_DECODE_BYTES_PER_STEP,
                             "bytes_per_step": dec_bytes, "solo_achieved": dec_bytes / (dec_solo_ms * 1e-3) / 1e9,
                             "solo_frac": dec_bytes / (dec_solo_ms * 1e-3) / 1e9 / PEAK_HBM_GBS},
         "slo_paced": {"decode_interval_ms": pace_ms, "value": paced["tokens_per_s"], "unit": "tokens/s",
@@ -352,6 +363,7 @@ def main():
                       "note": "same co-location with decode steps issued every 0.6 x SLO instead of back to back"},
         "solo": {"decode_ms_per_step": dec_solo_ms, "finetune_ms_per_step": ft_solo_ms,
                  "finetune_tokens_per_s": T / ft_solo_ms * 1e3},
+        "measured_peaks": peaks,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))

@@ -29,6 +29,14 @@ harli_status harli_dbg_gemm(const void* A1, const void* B1, int32_t K1, const vo
 harli_status harli_prof_enable(int32_t on);
 harli_status harli_prof_collect(double* gemm_flops, double* gemm_ms, int64_t* gemm_launches);
 
+/* Measured memory ceilings of this GPU, for reading the roofline fractions.  Runs a plain read kernel on
+ * `buf` (device, `bytes` long, contents irrelevant, at least 64 MiB) and writes the achieved GB/s to *gbs
+ * (host).  mode 0: every workgroup streams a region of its own once per pass (HBM rate; use a buffer much
+ * larger than the 256 MiB memory-side cache).  mode 1: workgroups re-read 32 shared 3 MiB regions the way the
+ * MFMA GEMM's workgroups re-read operand panels (the rate at which the per-XCD L2 caches feed the CUs).
+ * Synchronises the stream.  Returns HARLI_ERR_INVALID for a null pointer, a small buffer or an unknown mode. */
+harli_status harli_dbg_read_bandwidth(const void* buf, size_t bytes, int32_t mode, double* gbs, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

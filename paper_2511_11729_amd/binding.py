@@ -97,6 +97,7 @@ _SIGS = {
     "harli_saved_bytes": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_size_t)]),
     "harli_prof_enable": (C.c_int, [C.c_int32]),
     "harli_prof_collect": (C.c_int, [C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
+    "harli_dbg_read_bandwidth": (C.c_int, [C.c_void_p, C.c_size_t, C.c_int32, C.POINTER(C.c_double), C.c_void_p]),
     "harli_dbg_gemm": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
                                  C.c_float, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
 }
@@ -286,6 +287,14 @@ def dbg_gemm(A1, B1, *, A2=None, B2=None, alpha=1.0, causal=0, half=False, Cb=No
     K2 = A2.shape[1] if A2 is not None else 0
     _check(lib().harli_dbg_gemm(_ptr(A1), _ptr(B1), K1, _ptr(A2), _ptr(B2), K2, M, N, alpha, causal, int(half), _ptr(Cb), _ptr(Cf),
                                 _ptr(res), _ptr(Ct), _stream(stream)))
+
+
+def dbg_read_bandwidth(buf, mode: int, stream=None) -> float:
+    """Measured read rate in GB/s over the uint8 device tensor `buf`: mode 0 streams it (HBM), mode 1 re-reads
+    shared regions the way GEMM workgroups do (L2)."""
+    g = C.c_double()
+    _check(lib().harli_dbg_read_bandwidth(_ptr(buf), buf.numel() * buf.element_size(), mode, C.byref(g), _stream(stream)))
+    return g.value
 
 
 def prof_enable(on: bool) -> None:

@@ -49,3 +49,50 @@ extern "C" harli_status harli_prof_collect(double* gemm_flops, double* gemm_ms, 
   *gemm_launches = n;
   return s;
 }
+
+// ---- read-bandwidth probe ----
+namespace {
+// 12 independent 16-byte loads per thread and step (12 KiB per workgroup and step), 256 steps: 3 MiB per workgroup
+constexpr int kProbeU = 12, kProbeSteps = 256;
+__global__ void __launch_bounds__(256) k_probe_read(const uint4* __restrict__ base, long long wg_stride16, int wg_mod, unsigned* sink) {
+  const uint4* p = base + (long long)(blockIdx.x % wg_mod) * wg_stride16 + threadIdx.x;
+  unsigned acc = 0;
+  for (int s = 0; s < kProbeSteps; ++s) {
+    uint4 v[kProbeU];
+#pragma unroll
+    for (int i = 0; i < kProbeU; ++i) v[i] = p[i * 256];
+#pragma unroll
+    for (int i = 0; i < kProbeU; ++i) acc ^= v[i].x ^ v[i].w;
+    p += kProbeU * 256;
+  }
+  if (acc == 0x9e3779b9u) *sink = acc;  // keeps the loads alive; practically never true
+}
+}  // namespace
+
+extern "C" harli_status harli_dbg_read_bandwidth(const void* buf, size_t bytes, int32_t mode, double* gbs, void* hip_stream) {
+  const size_t per_wg = (size_t)kProbeU * 256 * 16 * kProbeSteps;  // 3 MiB
+  if (!buf || !gbs || (mode != 0 && mode != 1) || bytes < (64u << 20) + 256) return fail(HARLI_ERR_INVALID, "read_bandwidth: bad argument");
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  unsigned* sink = nullptr;
+  HARLI_HIP(hipMalloc(reinterpret_cast<void**>(&sink), 256));
+  const int regions = (int)((bytes - 256) / per_wg);
+  const int wg_mod = mode == 0 ? regions : (regions < 32 ? regions : 32);
+  const int wgs = mode == 0 ? regions : 4096;
+  hipEvent_t e0, e1;
+  HARLI_HIP(hipEventCreate(&e0));
+  HARLI_HIP(hipEventCreate(&e1));
+  const int reps = 5;
+  hipLaunchKernelGGL(k_probe_read, dim3(wgs), dim3(256), 0, st, static_cast<const uint4*>(buf), (long long)(per_wg / 16), wg_mod, sink);
+  HARLI_HIP(hipEventRecord(e0, st));
+  for (int i = 0; i < reps; ++i)
+    hipLaunchKernelGGL(k_probe_read, dim3(wgs), dim3(256), 0, st, static_cast<const uint4*>(buf), (long long)(per_wg / 16), wg_mod, sink);
+  HARLI_HIP(hipEventRecord(e1, st));
+  HARLI_HIP(hipEventSynchronize(e1));
+  float ms = 0.f;
+  HARLI_HIP(hipEventElapsedTime(&ms, e0, e1));
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  (void)hipFree(sink);
+  *gbs = (double)wgs * per_wg * reps / (ms * 1e-3) / 1e9;
+  return HARLI_OK;
+}

@@ -87,3 +87,15 @@ def test_bad_arguments_are_rejected():
     A, B = rnd((16, 16), 1), rnd((16, 16), 2)
     with pytest.raises(hb.HarliError):
         hb.dbg_gemm(A, B)                                  # no output
+
+
+def test_read_bandwidth_probe_reports_sane_rates():
+    """The ceilings the benchmark quotes: HBM streaming and L2-resident re-reads, both between 0.5 and 40 TB/s."""
+    buf = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0")
+    hbm = hb.dbg_read_bandwidth(buf, 0)
+    l2 = hb.dbg_read_bandwidth(buf, 1)
+    print("probe: HBM stream %.0f GB/s, L2 re-read %.0f GB/s" % (hbm, l2))
+    assert 500 < hbm < 40000 and 500 < l2 < 40000 and l2 > hbm
+    small = torch.empty(1 << 20, dtype=torch.uint8, device="cuda:0")
+    with pytest.raises(hb.HarliError):
+        hb.dbg_read_bandwidth(small, 0)
