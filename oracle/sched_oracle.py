@@ -1,0 +1,69 @@
+"""CPU oracle of the latency predictor and the allocation choice (Harli Sec. 5 and Sec. 6.2).
+
+TEST INFRASTRUCTURE ONLY: plain NumPy float64, written from the paper's equations; the product path never
+imports it.  It is the definition the library's host-side predictor (`harli_pred_*`, `harli_sched_pick`) is
+compared with.
+
+* Eq. 1 (solo decode latency, one model per compute-unit ratio):
+      latency = bs*b0 + c0 + bs*k0*seqlen
+  fitted by ordinary least squares over profiled (bs, seqlen, latency) samples.
+* Eq. 2 (co-located decode latency):
+      latency_colo = (SM_infer*b1 + SM_ft*k1) * latency_solo(SM_infer)
+  fitted by ordinary least squares of latency_colo on the two regressors SM_infer*latency_solo and
+  SM_ft*latency_solo (the paper says only that b1, k1 come from profiling; this is the reading taken).
+* Allocation (Sec. 5.2 "Perceive the Finetune Performance", Sec. 6.2): with ratios in steps of 1/n_levels the
+  candidate plans are the pairs (SM_infer, SM_ft) with SM_infer + SM_ft <= 1, both at least one step (45 pairs
+  for ten levels).  The plan chosen is the one whose predicted co-located latency is closest to the QoS target
+  without exceeding it; ties go to the larger finetune share, then to the smaller inference share.  When no
+  pair meets the target the finetune task is paused and inference gets every compute unit.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+
+def fit_solo(samples):
+    """samples: iterable of (bs, seqlen, latency).  Returns (b0, c0, k0) of Eq. 1."""
+    s = np.asarray(list(samples), np.float64)
+    X = np.stack([s[:, 0], np.ones(len(s)), s[:, 0] * s[:, 1]], axis=1)
+    beta, *_ = np.linalg.lstsq(X, s[:, 2], rcond=None)
+    return tuple(float(b) for b in beta)
+
+
+def predict_solo(coef, bs, seqlen):
+    b0, c0, k0 = coef
+    return bs * b0 + c0 + bs * k0 * seqlen
+
+
+def fit_colo(samples):
+    """samples: iterable of (sm_infer, sm_ft, latency_colo, latency_solo_at_sm_infer).  Returns (b1, k1) of Eq. 2."""
+    s = np.asarray(list(samples), np.float64)
+    X = np.stack([s[:, 0] * s[:, 3], s[:, 1] * s[:, 3]], axis=1)
+    beta, *_ = np.linalg.lstsq(X, s[:, 2], rcond=None)
+    return float(beta[0]), float(beta[1])
+
+
+def predict_colo(colo_coef, sm_infer, sm_ft, latency_solo):
+    b1, k1 = colo_coef
+    return (sm_infer * b1 + sm_ft * k1) * latency_solo
+
+
+def pairs(n_levels=10):
+    """Index pairs (i, f), 1-based numbers of steps, with i + f <= n_levels."""
+    return [(i, f) for i in range(1, n_levels) for f in range(1, n_levels - i + 1)]
+
+
+def pick(solo_coefs, colo_coef, bs, seqlen, slo, n_levels=10):
+    """solo_coefs[i-1] = Eq. 1 coefficients at ratio i/n_levels.  Returns (i, f, predicted latency); f = 0 means
+    the finetune task is paused and inference runs alone on all compute units (i = n_levels)."""
+    best = None
+    for i, f in pairs(n_levels):
+        lat = predict_colo(colo_coef, i / n_levels, f / n_levels, predict_solo(solo_coefs[i - 1], bs, seqlen))
+        if lat > slo:
+            continue
+        key = (lat, f, -i)
+        if best is None or key > best[0]:
+            best = (key, (i, f, lat))
+    if best is None:
+        return n_levels, 0, predict_solo(solo_coefs[n_levels - 1], bs, seqlen)
+    return best[1]

@@ -1,0 +1,109 @@
+"""Pins of the predictor / allocation oracle (CPU only): closed forms, planted coefficients, the normal
+equations, the paper's 45 plans, hand-worked choices."""
+import itertools
+
+import numpy as np
+
+from oracle import sched_oracle as S
+
+
+def test_eq1_three_points_equal_the_hand_solution():
+    # exactly determined: solve the 3x3 system by Cramer's rule, no library routine
+    pts = [(4, 100, 1.30), (16, 100, 2.50), (16, 400, 4.90)]
+    def det(m):
+        return (m[0][0] * (m[1][1] * m[2][2] - m[1][2] * m[2][1]) - m[0][1] * (m[1][0] * m[2][2] - m[1][2] * m[2][0])
+                + m[0][2] * (m[1][0] * m[2][1] - m[1][1] * m[2][0]))
+    A = [[bs, 1.0, bs * n] for bs, n, _ in pts]
+    y = [p[2] for p in pts]
+    D = det(A)
+    sol = []
+    for c in range(3):
+        M = [row[:] for row in A]
+        for r in range(3):
+            M[r][c] = y[r]
+        sol.append(det(M) / D)
+    got = S.fit_solo(pts)
+    assert np.allclose(got, sol, rtol=1e-10, atol=1e-12)
+    # and the model reproduces the points
+    for bs, n, lat in pts:
+        assert abs(S.predict_solo(got, bs, n) - lat) < 1e-10
+
+
+def test_eq1_recovers_planted_coefficients_and_is_linear_in_seqlen():
+    b0, c0, k0 = 0.0125, 0.9, 3.1e-5
+    pts = [(bs, n, bs * b0 + c0 + bs * k0 * n) for bs in (4, 16, 64) for n in (64, 128, 256, 512)]
+    got = S.fit_solo(pts)
+    assert np.allclose(got, (b0, c0, k0), rtol=1e-9)
+    # slope in seqlen at fixed batch is bs*k0; the intercept at bs -> 0 is c0
+    assert abs((S.predict_solo(got, 16, 301) - S.predict_solo(got, 16, 300)) - 16 * k0) < 1e-12
+    assert abs(S.predict_solo(got, 0, 12345) - c0) < 1e-9
+
+
+def test_least_squares_satisfies_the_normal_equations():
+    rng = np.random.default_rng(7)
+    pts = [(bs, n, 0.02 * bs + 1.0 + 2e-5 * bs * n + 0.05 * rng.standard_normal()) for bs in (4, 8, 16, 32, 64) for n in (32, 100, 300, 500)]
+    b0, c0, k0 = S.fit_solo(pts)
+    s = np.asarray(pts)
+    X = np.stack([s[:, 0], np.ones(len(s)), s[:, 0] * s[:, 1]], axis=1)
+    r = s[:, 2] - X @ np.array([b0, c0, k0])
+    assert np.max(np.abs(X.T @ r)) < 1e-6 * np.max(np.abs(X.T @ s[:, 2]))
+    # any perturbation of the coefficients increases the squared error
+    base = float(r @ r)
+    for d in itertools.product((-1, 0, 1), repeat=3):
+        if d == (0, 0, 0):
+            continue
+        pert = np.array([b0, c0, k0]) * (1 + 1e-3 * np.array(d))
+        rr = s[:, 2] - X @ pert
+        assert float(rr @ rr) >= base
+
+
+def test_eq2_recovers_the_bandwidth_sharing_model():
+    # Sec. 5.2 theoretical analysis: slowdown = (f_infer + f_ft) / B with each demand proportional to its share
+    cin, cft, B = 5.0, 3.0, 8.0
+    pts = []
+    for i, f in S.pairs(10):
+        solo = 2.0 / (i / 10) ** 0.5
+        pts.append((i / 10, f / 10, (cin * i / 10 + cft * f / 10) / B * solo, solo))
+    b1, k1 = S.fit_colo(pts)
+    assert abs(b1 - cin / B) < 1e-9 and abs(k1 - cft / B) < 1e-9
+    assert abs(S.predict_colo((b1, k1), 0.4, 0.3, 3.0) - (0.4 * cin + 0.3 * cft) / B * 3.0) < 1e-9
+
+
+def test_ten_levels_give_the_papers_45_plans():
+    p = S.pairs(10)
+    assert len(p) == 45 and len(set(p)) == 45
+    assert all(1 <= i and 1 <= f and i + f <= 10 for i, f in p)
+    assert (9, 1) in p and (1, 9) in p and (5, 5) in p and (9, 2) not in p
+
+
+def _flat_solo(levels, lat_by_level):
+    # Eq. 1 models with b0 = k0 = 0: latency depends on the ratio only
+    return [(0.0, lat_by_level[i], 0.0) for i in range(levels)]
+
+
+def test_pick_takes_the_plan_closest_below_the_target():
+    solo = _flat_solo(10, [10.0, 6.0, 4.5, 3.8, 3.3, 3.0, 2.8, 2.6, 2.5, 2.4])
+    colo = (1.0, 1.0)           # factor = SM_infer + SM_ft
+    # brute force by hand
+    cands = [(i, f, (i + f) / 10 * solo[i - 1][1]) for i, f in S.pairs(10)]
+    ok = [c for c in cands if c[2] <= 2.0]
+    want = max(ok, key=lambda c: (c[2], c[1], -c[0]))
+    got = S.pick(solo, colo, 8, 512, 2.0)
+    assert got[:2] == want[:2] and abs(got[2] - want[2]) < 1e-12
+    assert got[2] <= 2.0
+    # nothing else that fits is closer to the target
+    assert all(c[2] <= got[2] + 1e-12 for c in ok)
+
+
+def test_pick_ties_go_to_the_larger_finetune_share():
+    solo = _flat_solo(4, [4.0, 2.0, 4.0 / 3.0, 1.0])      # latency * ratio constant -> (i + f)/i * const
+    colo = (1.0, 1.0)
+    # pairs with the same predicted latency: (1,1): 2/4*4 = 2.0 ; (2,2): 4/4*2 = 2.0 -> f = 2 wins
+    i, f, lat = S.pick(solo, colo, 1, 1, 2.0, n_levels=4)
+    assert (i, f) == (2, 2) and abs(lat - 2.0) < 1e-12
+
+
+def test_pick_pauses_finetune_when_no_plan_meets_the_target():
+    solo = _flat_solo(10, [50.0] * 10)
+    i, f, lat = S.pick(solo, (1.0, 1.0), 8, 512, 1.0)
+    assert (i, f) == (10, 0) and lat == 50.0
