@@ -1,0 +1,67 @@
+/*
+ * harli_sched.h -- latency predictor, allocation choice and compute-unit partitions of the
+ * co-location scheduler (Harli Sec. 5 and Sec. 6.2).  Host-side arithmetic in double precision, plus two
+ * calls that create / destroy HIP streams restricted to a range of compute units (the MI355X counterpart of
+ * the paper's per-stream SM partitions, Sec. 7).
+ */
+#ifndef HARLI_SCHED_H
+#define HARLI_SCHED_H
+
+#include "harli.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct harli_predictor harli_predictor;
+
+/* A predictor over n_levels compute-unit ratios 1/n_levels, 2/n_levels, ..., 1 (the paper uses ten, Sec. 5.1).
+ * n_levels in 2..64.  Level indices below are 1-based: level i means ratio i / n_levels. */
+harli_status harli_pred_create(int32_t n_levels, harli_predictor** out);
+void harli_pred_destroy(harli_predictor* p);
+
+/* One profiled solo decode step at compute-unit level `level`: batch size, sequence length, measured latency
+ * (any unit, used consistently).  Samples accumulate until harli_pred_fit. */
+harli_status harli_pred_add_solo(harli_predictor* p, int32_t level, int32_t bs, int32_t seqlen, double latency);
+/* One profiled co-located decode step: inference at `infer_level`, finetune at `ft_level`
+ * (infer_level + ft_level <= n_levels), measured co-located latency and the solo latency of the same
+ * (bs, seqlen) at infer_level. */
+harli_status harli_pred_add_colo(harli_predictor* p, int32_t infer_level, int32_t ft_level, double latency_colo,
+                                 double latency_solo);
+
+/* Ordinary least squares (Householder QR) of
+ *   Eq. 1 per level:  latency = bs*b0 + c0 + bs*k0*seqlen           (needs >= 3 samples at that level)
+ *   Eq. 2 overall:    latency_colo = (SM_infer*b1 + SM_ft*k1) * latency_solo   (needs >= 2 samples; optional)
+ * Levels without samples stay unfitted; HARLI_ERR_STATE if a sampled level has fewer than 3 samples or a
+ * rank-deficient design (e.g. one batch size only). */
+harli_status harli_pred_fit(harli_predictor* p);
+
+/* Coefficients after a fit (host out-pointers): solo[3] = b0, c0, k0 of `level`; colo[2] = b1, k1.
+ * HARLI_ERR_STATE when that model has not been fitted. */
+harli_status harli_pred_solo_coef(const harli_predictor* p, int32_t level, double* solo);
+harli_status harli_pred_colo_coef(const harli_predictor* p, double* colo);
+
+/* Predictions (host out-pointer). */
+harli_status harli_pred_solo(const harli_predictor* p, int32_t level, int32_t bs, int32_t seqlen, double* latency);
+harli_status harli_pred_colo(const harli_predictor* p, int32_t infer_level, int32_t ft_level, int32_t bs, int32_t seqlen,
+                             double* latency);
+
+/* Allocation for the next decode phase (Sec. 5.2, 6.2): over all pairs (infer_level, ft_level) with
+ * infer_level + ft_level <= n_levels, both >= 1, whose predicted co-located latency is <= slo, the pair with the
+ * largest predicted latency (closest to the target without exceeding it); ties go to the larger ft_level, then
+ * to the smaller infer_level.  When no pair qualifies: infer_level = n_levels, ft_level = 0 (finetune paused,
+ * every compute unit to inference) and the solo prediction at the full level.  Every level must be fitted. */
+harli_status harli_sched_pick(const harli_predictor* p, int32_t bs, int32_t seqlen, double slo, int32_t* infer_level,
+                              int32_t* ft_level, double* predicted);
+
+/* A HIP stream (default priority) whose kernels run only on compute units [cu_first, cu_first + cu_count) of the
+ * current device's compute-unit mask order; the runtime spreads consecutive mask bits round-robin over the XCDs,
+ * so a contiguous range is an equal share of every XCD.  *hip_stream receives a hipStream_t.  Ranges outside
+ * 0..multiProcessorCount or empty ranges give HARLI_ERR_INVALID.  Only contiguous ranges are offered. */
+harli_status harli_cu_stream_create(int32_t cu_first, int32_t cu_count, void** hip_stream);
+harli_status harli_cu_stream_destroy(void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HARLI_SCHED_H */

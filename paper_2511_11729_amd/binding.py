@@ -97,6 +97,19 @@ _SIGS = {
     "harli_saved_bytes": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_size_t)]),
     "harli_prof_enable": (C.c_int, [C.c_int32]),
     "harli_prof_collect": (C.c_int, [C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
+    "harli_pred_create": (C.c_int, [C.c_int32, C.POINTER(C.c_void_p)]),
+    "harli_pred_destroy": (None, [C.c_void_p]),
+    "harli_pred_add_solo": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_double]),
+    "harli_pred_add_colo": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_double, C.c_double]),
+    "harli_pred_fit": (C.c_int, [C.c_void_p]),
+    "harli_pred_solo_coef": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_double)]),
+    "harli_pred_colo_coef": (C.c_int, [C.c_void_p, C.POINTER(C.c_double)]),
+    "harli_pred_solo": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_double)]),
+    "harli_pred_colo": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_double)]),
+    "harli_sched_pick": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_double, C.POINTER(C.c_int32), C.POINTER(C.c_int32),
+                                   C.POINTER(C.c_double)]),
+    "harli_cu_stream_create": (C.c_int, [C.c_int32, C.c_int32, C.POINTER(C.c_void_p)]),
+    "harli_cu_stream_destroy": (C.c_int, [C.c_void_p]),
     "harli_dbg_read_bandwidth": (C.c_int, [C.c_void_p, C.c_size_t, C.c_int32, C.POINTER(C.c_double), C.c_void_p]),
     "harli_dbg_gemm": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
                                  C.c_float, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
@@ -277,6 +290,73 @@ class Context:
         n = C.c_size_t()
         _check(lib().harli_saved_bytes(self.handle, B_f, S, C.byref(n)))
         return n.value
+
+
+# ----------------------------------------------------------------------------- predictor / scheduler (harli_sched.h)
+class Predictor:
+    """harli_pred_* / harli_sched_pick: Eq. 1 per compute-unit level, Eq. 2 overall, closest-below-target choice."""
+
+    def __init__(self, n_levels: int = 10):
+        self.n_levels = n_levels
+        self.handle = C.c_void_p()
+        _check(lib().harli_pred_create(n_levels, C.byref(self.handle)))
+
+    def close(self):
+        if self.handle:
+            lib().harli_pred_destroy(self.handle)
+            self.handle = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def add_solo(self, level: int, bs: int, seqlen: int, latency: float) -> None:
+        _check(lib().harli_pred_add_solo(self.handle, level, bs, seqlen, latency))
+
+    def add_colo(self, infer_level: int, ft_level: int, latency_colo: float, latency_solo: float) -> None:
+        _check(lib().harli_pred_add_colo(self.handle, infer_level, ft_level, latency_colo, latency_solo))
+
+    def fit(self) -> None:
+        _check(lib().harli_pred_fit(self.handle))
+
+    def solo_coef(self, level: int):
+        c = (C.c_double * 3)()
+        _check(lib().harli_pred_solo_coef(self.handle, level, c))
+        return tuple(c)
+
+    def colo_coef(self):
+        c = (C.c_double * 2)()
+        _check(lib().harli_pred_colo_coef(self.handle, c))
+        return tuple(c)
+
+    def solo(self, level: int, bs: int, seqlen: int) -> float:
+        v = C.c_double()
+        _check(lib().harli_pred_solo(self.handle, level, bs, seqlen, C.byref(v)))
+        return v.value
+
+    def colo(self, infer_level: int, ft_level: int, bs: int, seqlen: int) -> float:
+        v = C.c_double()
+        _check(lib().harli_pred_colo(self.handle, infer_level, ft_level, bs, seqlen, C.byref(v)))
+        return v.value
+
+    def pick(self, bs: int, seqlen: int, slo: float):
+        """(infer_level, ft_level, predicted latency); ft_level 0 = finetune paused, inference on every compute unit."""
+        i, f, v = C.c_int32(), C.c_int32(), C.c_double()
+        _check(lib().harli_sched_pick(self.handle, bs, seqlen, slo, C.byref(i), C.byref(f), C.byref(v)))
+        return i.value, f.value, v.value
+
+
+def cu_stream_create(cu_first: int, cu_count: int) -> int:
+    """hipStream_t (as an integer) restricted to compute units [cu_first, cu_first + cu_count)."""
+    h = C.c_void_p()
+    _check(lib().harli_cu_stream_create(cu_first, cu_count, C.byref(h)))
+    return h.value
+
+
+def cu_stream_destroy(stream: int) -> None:
+    _check(lib().harli_cu_stream_destroy(stream))
 
 
 def dbg_gemm(A1, B1, *, A2=None, B2=None, alpha=1.0, causal=0, half=False, Cb=None, Cf=None, res=None, Ct=None,

@@ -1,0 +1,234 @@
+// Latency predictor, allocation choice and compute-unit partitions (Harli Sec. 5, Sec. 6.2, Sec. 7).
+// Host code only.  The two regressions are ordinary least squares solved by Householder QR in double precision.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <vector>
+
+#include "common.h"
+#include "harli_sched.h"
+
+using namespace harli;
+
+namespace {
+
+struct SoloSample {
+  double bs, seqlen, lat;
+};
+struct ColoSample {
+  double sm_i, sm_f, colo, solo;
+};
+
+// min ||X beta - y||_2 for an n x m design (row-major), m <= 3; false when rank deficient
+bool lstsq(std::vector<double> X, std::vector<double> y, int n, int m, double* beta) {
+  double col_scale = 0.0;
+  for (double v : X) col_scale = std::fmax(col_scale, std::fabs(v));
+  for (int k = 0; k < m; ++k) {
+    double norm = 0.0;
+    for (int i = k; i < n; ++i) norm += X[i * m + k] * X[i * m + k];
+    norm = std::sqrt(norm);
+    if (!(norm > 1e-13 * col_scale * std::sqrt((double)n))) return false;
+    const double alpha = X[k * m + k] > 0 ? -norm : norm;
+    std::vector<double> v(n - k);
+    for (int i = k; i < n; ++i) v[i - k] = X[i * m + k];
+    v[0] -= alpha;
+    double vv = 0.0;
+    for (double t : v) vv += t * t;
+    if (vv > 0.0) {
+      for (int j = k; j < m; ++j) {
+        double dot = 0.0;
+        for (int i = k; i < n; ++i) dot += v[i - k] * X[i * m + j];
+        const double f = 2.0 * dot / vv;
+        for (int i = k; i < n; ++i) X[i * m + j] -= f * v[i - k];
+      }
+      double dot = 0.0;
+      for (int i = k; i < n; ++i) dot += v[i - k] * y[i];
+      const double f = 2.0 * dot / vv;
+      for (int i = k; i < n; ++i) y[i] -= f * v[i - k];
+    }
+  }
+  for (int k = m - 1; k >= 0; --k) {
+    double s = y[k];
+    for (int j = k + 1; j < m; ++j) s -= X[k * m + j] * beta[j];
+    beta[k] = s / X[k * m + k];
+  }
+  return true;
+}
+
+}  // namespace
+
+struct harli_predictor {
+  int n_levels = 0;
+  std::vector<std::vector<SoloSample>> solo;  // per level (index level-1)
+  std::vector<ColoSample> colo;
+  std::vector<double> coef;       // 3 per level
+  std::vector<char> fitted;       // per level
+  double b1 = 0, k1 = 0;
+  bool colo_fitted = false;
+};
+
+namespace {
+bool level_ok(const harli_predictor* p, int level) { return level >= 1 && level <= p->n_levels; }
+double eval_solo(const harli_predictor* p, int level, double bs, double seqlen) {
+  const double* c = &p->coef[(size_t)(level - 1) * 3];
+  return bs * c[0] + c[1] + bs * c[2] * seqlen;
+}
+double eval_colo(const harli_predictor* p, int il, int fl, double solo) {
+  return ((double)il / p->n_levels * p->b1 + (double)fl / p->n_levels * p->k1) * solo;
+}
+}  // namespace
+
+extern "C" harli_status harli_pred_create(int32_t n_levels, harli_predictor** out) {
+  if (!out || n_levels < 2 || n_levels > 64) return fail(HARLI_ERR_INVALID, "pred_create: n_levels %d outside 2..64", n_levels);
+  harli_predictor* p = new harli_predictor;
+  p->n_levels = n_levels;
+  p->solo.resize(n_levels);
+  p->coef.assign((size_t)n_levels * 3, 0.0);
+  p->fitted.assign(n_levels, 0);
+  *out = p;
+  return HARLI_OK;
+}
+
+extern "C" void harli_pred_destroy(harli_predictor* p) { delete p; }
+
+extern "C" harli_status harli_pred_add_solo(harli_predictor* p, int32_t level, int32_t bs, int32_t seqlen, double latency) {
+  if (!p || !level_ok(p, level) || bs < 1 || seqlen < 0 || !(latency > 0.0) || !std::isfinite(latency))
+    return fail(HARLI_ERR_INVALID, "pred_add_solo: bad sample (level %d bs %d seqlen %d)", level, bs, seqlen);
+  p->solo[level - 1].push_back(SoloSample{(double)bs, (double)seqlen, latency});
+  return HARLI_OK;
+}
+
+extern "C" harli_status harli_pred_add_colo(harli_predictor* p, int32_t infer_level, int32_t ft_level, double latency_colo,
+                                            double latency_solo) {
+  if (!p || !level_ok(p, infer_level) || ft_level < 1 || infer_level + ft_level > p->n_levels || !(latency_colo > 0.0) ||
+      !(latency_solo > 0.0) || !std::isfinite(latency_colo) || !std::isfinite(latency_solo))
+    return fail(HARLI_ERR_INVALID, "pred_add_colo: bad sample (levels %d + %d)", infer_level, ft_level);
+  p->colo.push_back(ColoSample{(double)infer_level / p->n_levels, (double)ft_level / p->n_levels, latency_colo, latency_solo});
+  return HARLI_OK;
+}
+
+extern "C" harli_status harli_pred_fit(harli_predictor* p) {
+  if (!p) return fail(HARLI_ERR_INVALID, "pred_fit: null predictor");
+  for (int l = 0; l < p->n_levels; ++l) {
+    const std::vector<SoloSample>& s = p->solo[l];
+    if (s.empty()) continue;
+    const int n = (int)s.size();
+    if (n < 3) return fail(HARLI_ERR_STATE, "pred_fit: level %d has %d samples, Eq. 1 needs 3", l + 1, n);
+    std::vector<double> X((size_t)n * 3), y(n);
+    for (int i = 0; i < n; ++i) {
+      X[i * 3 + 0] = s[i].bs;
+      X[i * 3 + 1] = 1.0;
+      X[i * 3 + 2] = s[i].bs * s[i].seqlen;
+      y[i] = s[i].lat;
+    }
+    if (!lstsq(X, y, n, 3, &p->coef[(size_t)l * 3]))
+      return fail(HARLI_ERR_STATE, "pred_fit: level %d samples do not determine Eq. 1 (vary batch size and sequence length)", l + 1);
+    p->fitted[l] = 1;
+  }
+  if (!p->colo.empty()) {
+    const int n = (int)p->colo.size();
+    if (n < 2) return fail(HARLI_ERR_STATE, "pred_fit: Eq. 2 needs at least 2 co-located samples");
+    std::vector<double> X((size_t)n * 2), y(n);
+    for (int i = 0; i < n; ++i) {
+      X[i * 2 + 0] = p->colo[i].sm_i * p->colo[i].solo;
+      X[i * 2 + 1] = p->colo[i].sm_f * p->colo[i].solo;
+      y[i] = p->colo[i].colo;
+    }
+    double b[2];
+    if (!lstsq(X, y, n, 2, b)) return fail(HARLI_ERR_STATE, "pred_fit: co-located samples do not determine Eq. 2");
+    p->b1 = b[0];
+    p->k1 = b[1];
+    p->colo_fitted = true;
+  }
+  return HARLI_OK;
+}
+
+extern "C" harli_status harli_pred_solo_coef(const harli_predictor* p, int32_t level, double* solo) {
+  if (!p || !solo || !level_ok(p, level)) return fail(HARLI_ERR_INVALID, "pred_solo_coef: bad argument");
+  if (!p->fitted[level - 1]) return fail(HARLI_ERR_STATE, "pred_solo_coef: level %d is not fitted", level);
+  for (int i = 0; i < 3; ++i) solo[i] = p->coef[(size_t)(level - 1) * 3 + i];
+  return HARLI_OK;
+}
+
+extern "C" harli_status harli_pred_colo_coef(const harli_predictor* p, double* colo) {
+  if (!p || !colo) return fail(HARLI_ERR_INVALID, "pred_colo_coef: bad argument");
+  if (!p->colo_fitted) return fail(HARLI_ERR_STATE, "pred_colo_coef: Eq. 2 is not fitted");
+  colo[0] = p->b1;
+  colo[1] = p->k1;
+  return HARLI_OK;
+}
+
+extern "C" harli_status harli_pred_solo(const harli_predictor* p, int32_t level, int32_t bs, int32_t seqlen, double* latency) {
+  if (!p || !latency || !level_ok(p, level) || bs < 1 || seqlen < 0) return fail(HARLI_ERR_INVALID, "pred_solo: bad argument");
+  if (!p->fitted[level - 1]) return fail(HARLI_ERR_STATE, "pred_solo: level %d is not fitted", level);
+  *latency = eval_solo(p, level, bs, seqlen);
+  return HARLI_OK;
+}
+
+extern "C" harli_status harli_pred_colo(const harli_predictor* p, int32_t infer_level, int32_t ft_level, int32_t bs,
+                                        int32_t seqlen, double* latency) {
+  if (!p || !latency || !level_ok(p, infer_level) || ft_level < 1 || infer_level + ft_level > p->n_levels || bs < 1 || seqlen < 0)
+    return fail(HARLI_ERR_INVALID, "pred_colo: bad argument");
+  if (!p->fitted[infer_level - 1] || !p->colo_fitted) return fail(HARLI_ERR_STATE, "pred_colo: models are not fitted");
+  *latency = eval_colo(p, infer_level, ft_level, eval_solo(p, infer_level, bs, seqlen));
+  return HARLI_OK;
+}
+
+extern "C" harli_status harli_sched_pick(const harli_predictor* p, int32_t bs, int32_t seqlen, double slo, int32_t* infer_level,
+                                         int32_t* ft_level, double* predicted) {
+  if (!p || !infer_level || !ft_level || !predicted || bs < 1 || seqlen < 0 || !(slo > 0.0))
+    return fail(HARLI_ERR_INVALID, "sched_pick: bad argument");
+  if (!p->colo_fitted) return fail(HARLI_ERR_STATE, "sched_pick: Eq. 2 is not fitted");
+  for (int l = 0; l < p->n_levels; ++l)
+    if (!p->fitted[l]) return fail(HARLI_ERR_STATE, "sched_pick: level %d is not fitted", l + 1);
+  bool have = false;
+  int bi = 0, bf = 0;
+  double bl = 0.0;
+  for (int i = 1; i < p->n_levels; ++i)
+    for (int f = 1; i + f <= p->n_levels; ++f) {
+      const double lat = eval_colo(p, i, f, eval_solo(p, i, bs, seqlen));
+      if (!(lat <= slo)) continue;
+      const bool better = !have || lat > bl || (lat == bl && (f > bf || (f == bf && i < bi)));
+      if (better) {
+        have = true;
+        bi = i;
+        bf = f;
+        bl = lat;
+      }
+    }
+  if (!have) {
+    bi = p->n_levels;
+    bf = 0;
+    bl = eval_solo(p, p->n_levels, bs, seqlen);
+  }
+  *infer_level = bi;
+  *ft_level = bf;
+  *predicted = bl;
+  return HARLI_OK;
+}
+
+extern "C" harli_status harli_cu_stream_create(int32_t cu_first, int32_t cu_count, void** hip_stream) {
+  if (!hip_stream) return fail(HARLI_ERR_INVALID, "cu_stream_create: null out pointer");
+  int dev = 0;
+  hipDeviceProp_t prop;
+  if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess)
+    return fail(HARLI_ERR_HIP, "cu_stream_create: no HIP device available");
+  const int n_cu = prop.multiProcessorCount;
+  if (cu_first < 0 || cu_count < 1 || cu_first + cu_count > n_cu)
+    return fail(HARLI_ERR_INVALID, "cu_stream_create: range [%d, %d) outside the device's %d compute units", cu_first,
+                cu_first + cu_count, n_cu);
+  std::vector<uint32_t> mask((n_cu + 31) / 32, 0u);
+  for (int c = cu_first; c < cu_first + cu_count; ++c) mask[c >> 5] |= 1u << (c & 31);
+  hipStream_t st = nullptr;
+  hipError_t e = hipExtStreamCreateWithCUMask(&st, (uint32_t)mask.size(), mask.data());
+  if (e != hipSuccess) return fail(HARLI_ERR_HIP, "cu_stream_create: %s", hipGetErrorString(e));
+  *hip_stream = st;
+  return HARLI_OK;
+}
+
+extern "C" harli_status harli_cu_stream_destroy(void* hip_stream) {
+  if (!hip_stream) return fail(HARLI_ERR_INVALID, "cu_stream_destroy: null stream");
+  hipError_t e = hipStreamDestroy(static_cast<hipStream_t>(hip_stream));
+  if (e != hipSuccess) return fail(HARLI_ERR_HIP, "cu_stream_destroy: %s", hipGetErrorString(e));
+  return HARLI_OK;
+}

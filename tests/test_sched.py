@@ -1,0 +1,110 @@
+"""The library's host-side predictor and allocation choice against the oracle (CPU only: no GPU call is made).
+
+Coefficients and predictions: both sides solve the same least-squares problems in double precision (QR in the
+library, LAPACK in the oracle); they must agree to 1e-8 relative.  Chosen plans are integers and must be equal.
+"""
+import numpy as np
+import pytest
+
+from oracle import sched_oracle as S
+from paper_2511_11729_amd import binding as hb
+
+
+def synth_profile(seed, n_levels=10, noise=0.02):
+    """Latencies shaped like a decode step on a fraction of the chip: a weight-streaming floor that shrinks
+    sublinearly with the compute-unit ratio plus per-sequence and per-token terms, with multiplicative noise."""
+    rng = np.random.default_rng(seed)
+    solo = {}
+    for lv in range(1, n_levels + 1):
+        r = lv / n_levels
+        c0 = 0.09 / r ** 0.7 + 0.03
+        b0 = 0.0015 / r ** 0.5
+        k0 = 2.0e-6 / r ** 0.8
+        solo[lv] = [(bs, n, (bs * b0 + c0 + bs * k0 * n) * (1 + noise * rng.standard_normal()))
+                    for bs in (4, 16, 64) for n in (64, 128, 256, 512)]
+    colo = []
+    for i, f in S.pairs(n_levels):
+        base = solo[i][5][2]
+        colo.append((i, f, base * (0.55 * i / n_levels + 0.9 + 0.8 * f / n_levels) * (1 + noise * rng.standard_normal()), base))
+    return solo, colo
+
+
+def build_both(seed, n_levels=10, noise=0.02):
+    solo, colo = synth_profile(seed, n_levels, noise)
+    p = hb.Predictor(n_levels)
+    for lv, pts in solo.items():
+        for bs, n, lat in pts:
+            p.add_solo(lv, bs, n, lat)
+    for i, f, lc, ls in colo:
+        p.add_colo(i, f, lc, ls)
+    p.fit()
+    o_solo = [S.fit_solo(solo[lv]) for lv in range(1, n_levels + 1)]
+    o_colo = S.fit_colo([(i / n_levels, f / n_levels, lc, ls) for i, f, lc, ls in colo])
+    return p, o_solo, o_colo
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_fits_and_predictions_match_the_oracle(seed):
+    p, o_solo, o_colo = build_both(seed)
+    for lv in range(1, 11):
+        got = p.solo_coef(lv)
+        assert np.allclose(got, o_solo[lv - 1], rtol=1e-8, atol=1e-14), (lv, got, o_solo[lv - 1])
+    assert np.allclose(p.colo_coef(), o_colo, rtol=1e-8)
+    for lv, bs, n in [(1, 1, 0), (3, 8, 77), (10, 256, 4096), (7, 33, 1000)]:
+        assert abs(p.solo(lv, bs, n) - S.predict_solo(o_solo[lv - 1], bs, n)) <= 1e-8 * abs(S.predict_solo(o_solo[lv - 1], bs, n))
+    for i, f in S.pairs(10):
+        want = S.predict_colo(o_colo, i / 10, f / 10, S.predict_solo(o_solo[i - 1], 8, 1153))
+        assert abs(p.colo(i, f, 8, 1153) - want) <= 1e-8 * abs(want)
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2, 3])
+def test_chosen_plans_equal_the_oracles(seed):
+    p, o_solo, o_colo = build_both(seed)
+    rng = np.random.default_rng(100 + seed)
+    n_paused = 0
+    for _ in range(300):
+        bs = int(rng.integers(1, 257))
+        n = int(rng.integers(0, 4097))
+        slo = float(rng.uniform(0.05, 3.0))
+        gi, gf, gl = p.pick(bs, n, slo)
+        wi, wf, wl_ = S.pick(o_solo, o_colo, bs, n, slo)
+        assert (gi, gf) == (wi, wf), (bs, n, slo, (gi, gf, gl), (wi, wf, wl_))
+        assert abs(gl - wl_) <= 1e-8 * abs(wl_)
+        n_paused += gf == 0
+        if gf:
+            assert gl <= slo and gi + gf <= 10
+    assert 0 < n_paused < 300          # both branches were exercised
+
+
+def test_exact_data_gives_exact_coefficients():
+    p = hb.Predictor(4)
+    for lv in range(1, 5):
+        for bs in (2, 8, 32):
+            for n in (10, 100, 1000):
+                p.add_solo(lv, bs, n, bs * 0.01 * lv + 0.5 / lv + bs * 1e-5 * n)
+    p.fit()
+    for lv in range(1, 5):
+        assert np.allclose(p.solo_coef(lv), (0.01 * lv, 0.5 / lv, 1e-5), rtol=1e-9)
+
+
+def test_errors():
+    p = hb.Predictor(10)
+    with pytest.raises(hb.HarliError):
+        p.add_solo(0, 4, 100, 1.0)                # level out of range
+    with pytest.raises(hb.HarliError):
+        p.add_colo(6, 5, 1.0, 1.0)                # 6 + 5 > 10
+    with pytest.raises(hb.HarliError):
+        p.add_solo(1, 4, 100, float("nan"))
+    p.add_solo(1, 4, 100, 1.0)
+    p.add_solo(1, 4, 200, 1.1)
+    with pytest.raises(hb.HarliError) as e:
+        p.fit()                                   # two samples
+    assert e.value.status == hb.HARLI_ERR_STATE
+    p.add_solo(1, 4, 300, 1.2)
+    with pytest.raises(hb.HarliError) as e:
+        p.fit()                                   # one batch size only: rank deficient
+    assert e.value.status == hb.HARLI_ERR_STATE
+    with pytest.raises(hb.HarliError):
+        p.pick(8, 100, 1.0)                       # nothing fitted
+    with pytest.raises(hb.HarliError):
+        hb.Predictor(1)
