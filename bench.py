@@ -54,6 +54,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--solo", action="store_true", help="also report each task running alone (default on)")
+    ap.add_argument("--no-sched", action="store_true", help="skip the predictor profiling and the scheduled run")
     ap.add_argument("--calib-copy", action="store_true",
                     help="after the timed region run three plain 256 MiB device copies: the known-size kernel that the "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
@@ -66,7 +67,7 @@ def main():
     import torch
     import workloads as wl
     from paper_2511_11729_amd import binding as hb
-    from tests.gpu_util import to_dev, f32_dev        # device upload helpers only (no arithmetic)
+    from paper_2511_11729_amd.harness import LayerHarness
 
     hb.lib()                                          # fails loudly when libharli.so is not built
     dev = "cuda:0"
@@ -77,91 +78,19 @@ def main():
     T = ft.tokens
     slo_ms = SLO_MS_FULL_MODEL / 32.0
 
-    # ------------------------------------------------------------------ inputs (seeded, synthetic)
+    # inputs (seeded, synthetic), one unified pool for KV pages and activations, context, adapters
     log("[bench] generating config-1 weights and inputs")
-    W_np = wl.make_layer_weights(w, 0)
-    lora_np = wl.make_lora(w, 0)
-    x_np, kv_len, kv_np = wl.make_decode_inputs(w)
-    X_np, _ = wl.make_finetune_inputs(w)
-    B = len(kv_len)
-    P = 16
-    n_pages = [(int(n) + 1 + P - 1) // P for n in kv_len]
-    total_pages = sum(n_pages)
-
-    # ------------------------------------------------------------------ one unified pool for KV pages and activations
-    block = 2 << 20
-    chunk = m.n_layers * 2 * block
-    ppb = block // (P * m.kv_row_bytes)
-    act_bytes_est = (T * m.hidden * 12 + T * m.n_q * m.head_dim * 4 + T * m.n_kv * m.head_dim * 4 + T * m.ffn * 6
-                     + ft.micro_batch * m.n_q * ft.seq_len * ft.seq_len * 2)
-    in_flight = 8                                      # finetune micro-batches whose release events may be pending
-    n_chunks = -(-total_pages // ppb) + in_flight * (act_bytes_est // chunk + 2) + 4
-    small = 64 << 20
-    slab_bytes = small + n_chunks * chunk
-    slab = torch.zeros(slab_bytes, dtype=torch.uint8, device=dev)
-    pool = hb.Pool(slab, slab_bytes, block_bytes=block, n_layers=m.n_layers, kv_row_bytes=m.kv_row_bytes,
-                   small_pool_bytes=small, kv_reserve_chunks=2)
-    ids = np.array(pool.alloc_pages(total_pages), np.int64)[wl.page_order(w, total_pages)]
-    max_pages = max(n_pages) + 1
-    table = np.full((B, max_pages), -1, np.int32)
-    k = 0
-    for b in range(B):
-        table[b, :n_pages[b]] = ids[k:k + n_pages[b]]
-        k += n_pages[b]
-    # KV contents: the values do not change the traffic; fill the pages with the seeded draws
-    img = np.zeros(slab_bytes // 2, np.uint16)
-    d = m.head_dim
-    for b in range(B):
-        Kc, Vc = kv_np[0][b]
-        for which, Tn in ((0, Kc), (1, Vc)):
-            enc = wl.bf16_bits(Tn).reshape(Tn.shape)
-            n = Tn.shape[0]
-            for lp in range((n + P - 1) // P):
-                t0, t1 = lp * P, min(n, lp * P + P)
-                base = pool.kv_addr(int(table[b, lp]), 0, which) // 2
-                for c in range(m.n_kv):
-                    off = base + c * P * d
-                    img[off: off + (t1 - t0) * d] = enc[t0:t1, c, :].reshape(-1)
-    slab.copy_(torch.from_numpy(img.view(np.uint8)))
-    del img
-
-    layer_dev = {n: to_dev(W_np[n], "bf16") for n in ("wq", "wk", "wv", "wo", "wg", "wu", "wd")}
-    layer_dev["g1"], layer_dev["g2"] = f32_dev(W_np["g1"]), f32_dev(W_np["g2"])
-    ctx = hb.Context(pool, n_layers=1, hidden=m.hidden, n_q_heads=m.n_q, n_kv_heads=m.n_kv, head_dim=m.head_dim,
-                     ffn=m.ffn, rms_eps=m.rms_eps, rope_base=m.rope_base, dtype=hb.HARLI_BF16, max_batch=B,
-                     max_seq_len=int(kv_len.max()) + 8, max_ft_tokens=T, layers=[layer_dev])
-    A_dev = {p: to_dev(a, "bf16") for p, (a, b) in lora_np.items()}
-    B_dev = {p: to_dev(b, "bf16") for p, (a, b) in lora_np.items()}
-    ctx.lora_attach(lora.rank, lora.alpha, lora.targets, [A_dev], [B_dev])
-
-    kv_len_dev = torch.from_numpy(kv_len.astype(np.int32)).to(dev)
-    table_dev = torch.from_numpy(table).to(dev)
-    x_dev = f32_dev(x_np)
-    y_dev = torch.empty(B, m.hidden, dtype=torch.float32, device=dev)
-    X_dev = f32_dev(X_np.reshape(T, m.hidden))
-    Y_dev = torch.empty(T, m.hidden, dtype=torch.float32, device=dev)
-    dY_dev = torch.randn(T, m.hidden, dtype=torch.float32, device=dev, generator=torch.Generator(dev).manual_seed(1003)) / (T * m.hidden)
-    dX_dev = torch.empty(T, m.hidden, dtype=torch.float32, device=dev)
-    dA = {p: torch.zeros(a.shape, dtype=torch.float32, device=dev) for p, (a, b) in lora_np.items()}
-    dB = {p: torch.zeros(b.shape, dtype=torch.float32, device=dev) for p, (a, b) in lora_np.items()}
-    max_kv = int(kv_len.max()) + 1
+    hz = LayerHarness(w, in_flight=8, decode_capacity=(64, 2048))
+    ctx, pool, B, kv_len = hz.ctx, hz.pool, hz.B, hz.kv_len
+    W_np, lora_np, X_np = hz.W_np, hz.lora_np, hz.X_np
 
     sD, sF = torch.cuda.Stream(), torch.cuda.Stream()   # default priority on both
 
     def decode_launch():
-        ctx.decode_step(batch=B, kv_len=kv_len_dev, page_table=table_dev, max_pages=max_pages, max_kv_len=max_kv,
-                        x_in=x_dev, x_out=y_dev, stream=sD)
-
-    ft_done = []                                       # one event per finished unit: bounds the units in flight
+        hz.decode_launch(sD)
 
     def finetune_unit():
-        if len(ft_done) >= in_flight - 2:
-            ft_done[-(in_flight - 2)].synchronize()    # their pool memory is released by events, keep <= 6 pending
-        sv = ctx.lora_fwd(0, X_dev, Y_dev, ft.micro_batch, ft.seq_len, stream=sF)
-        ctx.lora_bwd(0, dY_dev, dX_dev, sv, dA, dB, stream=sF)
-        ev = torch.cuda.Event()
-        ev.record(sF)
-        ft_done.append(ev)
+        hz.finetune_unit(sF)
 
     # decode step as one graph launch (no memset nodes inside); falls back to direct launches
     graph = None
@@ -185,8 +114,7 @@ def main():
         else:
             decode_launch()
 
-    kv_bytes = int(sum(int(n) + 1 for n in kv_len)) * 2 * m.kv_row_bytes
-    dec_bytes = 2 * m.layer_params + kv_bytes
+    dec_bytes = hz.decode_bytes()
 
     # ------------------------------------------------------------------ solo references
     def time_decode_solo(n=300):
@@ -219,67 +147,18 @@ def main():
     pool.stats()                                       # polls release events
 
     # ------------------------------------------------------------------ co-located, timed
+    from paper_2511_11729_amd import colocate
+
     def run_colocated(pace_ms):
         """K timed finetune units with decode beside them.  pace_ms None: decode steps back to back (closed loop);
         otherwise one decode step is issued every pace_ms (a request stream that only needs the SLO)."""
-        stop = threading.Event()
-        started = threading.Event()
-        dec_start, dec_end = [], []
-
-        def decode_thread():
-            torch.cuda.set_device(0)
-            i = 0
-            t_next = time.perf_counter()
-            while not stop.is_set():
-                if pace_ms is not None:
-                    while True:
-                        now = time.perf_counter()
-                        if now >= t_next or stop.is_set():
-                            break
-                        time.sleep(min(2e-4, t_next - now))
-                    t_next = max(t_next + pace_ms * 1e-3, time.perf_counter() - 5 * pace_ms * 1e-3)
-                if i >= 256:
-                    dec_end[i - 256].synchronize()     # bound the run-ahead of the host thread
-                e0 = torch.cuda.Event(enable_timing=True)
-                e0.record(sD)
-                decode_once()
-                e1 = torch.cuda.Event(enable_timing=True)
-                e1.record(sD)
-                dec_start.append(e0)
-                dec_end.append(e1)
-                i += 1
-                if i == 8:
-                    started.set()
-
-        th = threading.Thread(target=decode_thread, daemon=True)
-        th.start()
-        started.wait()
-        for _ in range(W):
-            finetune_unit()
-        sF.synchronize()
-        torch.cuda.synchronize()
         hb.prof_enable(True)
-        i0 = len(dec_end)
-        t0 = time.perf_counter()
-        for _ in range(K):
-            finetune_unit()
-        sF.synchronize()
-        t1 = time.perf_counter()
-        i1 = len(dec_end)
-        stop.set()
-        th.join()
-        torch.cuda.synchronize()
+        hb.prof_collect()                              # drop earlier records; the run's own warm-up units are included (the figure is a ratio)
+        r = colocate.run_colocated(hz, sD, sF, decode_once, K, W, pace_ms)
         hb.prof_enable(False)
-        gemm_flops, gemm_ms, gemm_n = hb.prof_collect()
+        r["gemm"] = hb.prof_collect()
         ctx.check(sD)
-        elapsed = t1 - t0
-        # time per output token: completion-to-completion interval of consecutive decode steps inside the window;
-        # step latency: first kernel start to last kernel end of one step
-        lo, hi = max(i0, 1) - 1, i1
-        tpot = np.array([dec_end[j].elapsed_time(dec_end[j + 1]) for j in range(lo, hi - 1)]) if hi - lo > 2 else np.array([float("nan")])
-        steplat = np.array([dec_start[j].elapsed_time(dec_end[j]) for j in range(lo, hi)]) if hi > lo else np.array([float("nan")])
-        return {"elapsed": elapsed, "tokens_per_s": K * T / elapsed, "ms_per_step": elapsed * 1e3 / K,
-                "tpot": tpot, "steplat": steplat, "gemm": (gemm_flops, gemm_ms, gemm_n)}
+        return r
 
     log("[bench] co-located, decode in a closed loop: %d warmup + %d timed finetune units" % (W, K))
     closed = run_colocated(None)
@@ -290,6 +169,39 @@ def main():
     gemm_flops, gemm_ms, gemm_n = closed["gemm"]
     lat = closed["tpot"]
     tpot_p50, tpot_p99, tpot_mean = float(np.percentile(lat, 50)), float(np.percentile(lat, 99)), float(lat.mean())
+
+    # ------------------------------------------------------------------ the paper's policy: predictor + compute-unit partitions
+    sched = None
+    if not args.no_sched:
+        log("[bench] profiling the latency predictor on compute-unit partitions")
+        pred, rep = colocate.profile(hz, log=log)
+        seqlen = int(round(float(kv_len.mean())))
+        il, fl, plat = pred.pick(B, seqlen, slo_ms)
+        log("[bench] scheduler: inference level %d/10, finetune level %d/10, predicted TPOT %.3f ms" % (il, fl, plat))
+        cs = colocate.CuStreams()
+        sDm = cs.low(il)
+        cs.low(il)                                     # spacer: keeps the two streams two dispatch pipes apart
+        if fl > 0:
+            sFm = cs.high(fl)
+            res = colocate.run_colocated(hz, sDm, sFm, lambda: hz.decode_launch(sDm), K, W, None)
+        else:
+            res = colocate.run_colocated(hz, sDm, sF, lambda: hz.decode_launch(sDm), K, W, None, finetune=False)
+        ctx.check(sDm)
+        # the same inference partition with the finetune task on EVERY compute unit (overlapping masks): outside the
+        # paper's 45 disjoint plans, but a 256-tile GEMM needs all 256 compute units to finish in one round
+        res_o = colocate.run_colocated(hz, sDm, sF, lambda: hz.decode_launch(sDm), K, W, None) if fl > 0 else None
+        ctx.check(sDm)
+        cs.close()
+        sched = {"infer_level": il, "ft_level": fl, "predicted_tpot_ms": plat, "value": res["tokens_per_s"], "unit": "tokens/s",
+                 "ms_per_step": res["ms_per_step"], "tpot_ms_p50": float(np.percentile(res["tpot"], 50)),
+                 "tpot_ms_p99": float(np.percentile(res["tpot"], 99)), "met": bool(np.percentile(res["tpot"], 99) <= slo_ms),
+                 "seqlen_used": seqlen, "predictor": rep,
+                 "finetune_on_all_cus": None if res_o is None else {
+                     "value": res_o["tokens_per_s"], "ms_per_step": res_o["ms_per_step"],
+                     "tpot_ms_p50": float(np.percentile(res_o["tpot"], 50)), "tpot_ms_p99": float(np.percentile(res_o["tpot"], 99)),
+                     "met": bool(np.percentile(res_o["tpot"], 99) <= slo_ms)},
+                 "note": "decode and finetune on disjoint compute-unit ranges chosen by harli_sched_pick (closest "
+                         "predicted TPOT below the SLO over the 45 partitions), decode in a closed loop, direct launches"}
 
     # ------------------------------------------------------------------ CPU baseline: the oracle on a bounded sample
     cpu = None
@@ -361,6 +273,7 @@ def main():
                       "decode_step_latency_ms_p99": float(np.percentile(paced["steplat"], 99)),
                       "met": bool(np.percentile(paced["tpot"], 99) <= slo_ms),
                       "note": "same co-location with decode steps issued every 0.6 x SLO instead of back to back"},
+        "scheduled": sched,
         "solo": {"decode_ms_per_step": dec_solo_ms, "finetune_ms_per_step": ft_solo_ms,
                  "finetune_tokens_per_s": T / ft_solo_ms * 1e3},
         "measured_peaks": peaks,

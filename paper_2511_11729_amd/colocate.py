@@ -1,0 +1,215 @@
+"""Profiling and scheduling of the co-location on compute-unit partitions (Harli Sec. 5, Sec. 6.2).
+
+`profile(hz)` measures one layer's decode latency on the device at ten compute-unit levels (streams restricted to
+a contiguous range of compute units, an equal share of every XCD), fits Eq. 1 per level and Eq. 2 over the 45
+disjoint (inference, finetune) partitions with the library's predictor, and reports the prediction errors on
+held-out points.  `run_colocated(hz, ...)` runs decode and finetune side by side on given streams and returns
+throughput and latency statistics.  Host orchestration only: timing uses HIP events on the streams involved.
+"""
+from __future__ import annotations
+
+import threading
+import time
+
+import numpy as np
+import torch
+
+from . import binding as hb
+
+N_LEVELS = 10
+PROFILE_BATCHES = (4, 16, 64)              # three representative batch sizes (Sec. 5.1)
+PROFILE_SEQLENS = (64, 128, 256, 512)
+HELDOUT = ((8, 96), (8, 384), (32, 192), (32, 448), (48, 320))
+
+
+class CuStreams:
+    """Streams restricted to compute-unit ranges, wrapped for torch; destroyed on close()."""
+
+    def __init__(self):
+        self.n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+        self._raw = []
+
+    def make(self, first: int, count: int):
+        raw = hb.cu_stream_create(first, count)
+        self._raw.append(raw)
+        return torch.cuda.ExternalStream(raw)
+
+    def low(self, level: int):
+        """The first level/N_LEVELS of the compute units (inference side)."""
+        return self.make(0, max(1, self.n_cu * level // N_LEVELS))
+
+    def high(self, level: int):
+        """The last level/N_LEVELS of the compute units (finetune side): disjoint from low(i) when i + level <= N."""
+        c = max(1, self.n_cu * level // N_LEVELS)
+        return self.make(self.n_cu - c, c)
+
+    def close(self):
+        torch.cuda.synchronize()
+        for r in self._raw:
+            hb.cu_stream_destroy(r)
+        self._raw = []
+
+
+def time_decode(hz, stream, batch, kv_len_dev, max_kv, steps):
+    """Median latency in ms of `steps` decode steps issued back to back on `stream` (completion to completion;
+    the median keeps one-off stalls of the host threads out of the profile)."""
+    for _ in range(2):
+        hz.decode_launch(stream, batch, kv_len_dev, max_kv)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    ev[0].record(stream)
+    for k in range(steps):
+        hz.decode_launch(stream, batch, kv_len_dev, max_kv)
+        ev[k + 1].record(stream)
+    stream.synchronize()
+    return float(np.median([ev[k].elapsed_time(ev[k + 1]) for k in range(steps)]))
+
+
+class FinetuneLoop:
+    """Keeps finetune units enqueued on a stream from a host thread until stopped (the neighbour in profiling)."""
+
+    def __init__(self, hz, stream):
+        self.hz, self.stream = hz, stream
+        self.stop_flag = threading.Event()
+        self.units = 0
+        self.th = threading.Thread(target=self._run, daemon=True)
+
+    def _run(self):
+        torch.cuda.set_device(0)
+        while not self.stop_flag.is_set():
+            self.hz.finetune_unit(self.stream)
+            self.units += 1
+
+    def __enter__(self):
+        self.th.start()
+        while self.units < 2:
+            time.sleep(1e-3)
+        return self
+
+    def __exit__(self, *a):
+        self.stop_flag.set()
+        self.th.join()
+        self.stream.synchronize()
+
+
+def profile(hz, steps=12, log=lambda *a: None):
+    """Returns (predictor, report).  hz must have decode capacity for batch 64 at 512 cached tokens."""
+    cs = CuStreams()
+    pred = hb.Predictor(N_LEVELS)
+    dev = hz.x_dev.device
+
+    def lens(bs, n):
+        return torch.full((bs,), n, dtype=torch.int32, device=dev)
+
+    # Streams are handed to the device's dispatch pipes round-robin in creation order (four pipes here), and two
+    # streams on one pipe dispatch their kernels one after the other: measured, a decode stream sharing a pipe with
+    # the finetune stream sees about twice the latency of one that does not.  Create the streams so that inference
+    # streams always sit two pipes away from finetune streams: L L H H L L H H ...
+    low, high = {}, {}
+    for g in range(0, N_LEVELS, 2):
+        for lv in (g + 1, g + 2):
+            low[lv] = cs.low(lv)
+        for lv in (g + 1, g + 2):
+            high[lv] = cs.high(lv)
+    solo_meas = {}
+    t0 = time.perf_counter()
+    for lv in range(1, N_LEVELS + 1):
+        for bs in PROFILE_BATCHES:
+            for n in PROFILE_SEQLENS:
+                ms = time_decode(hz, low[lv], bs, lens(bs, n), n + 1, steps)
+                pred.add_solo(lv, bs, n, ms)
+                solo_meas[(lv, bs, n)] = ms
+    held = {}
+    for lv in range(1, N_LEVELS + 1):
+        for bs, n in HELDOUT:
+            held[(lv, bs, n)] = time_decode(hz, low[lv], bs, lens(bs, n), n + 1, steps)
+    # the workload's own batch (mixed lengths) solo at every level: the base of the co-located samples
+    base = {lv: time_decode(hz, low[lv], None, None, None, steps) for lv in range(1, N_LEVELS + 1)}
+    log("[sched] solo profile: %d + %d points in %.1f s" % (len(solo_meas), len(held), time.perf_counter() - t0))
+    t0 = time.perf_counter()
+    colo_meas = {}
+    for f in range(1, N_LEVELS):
+        with FinetuneLoop(hz, high[f]):
+            for i in range(1, N_LEVELS - f + 1):
+                colo_meas[(i, f)] = time_decode(hz, low[i], None, None, None, steps)
+        for i in range(1, N_LEVELS - f + 1):
+            pred.add_colo(i, f, colo_meas[(i, f)], base[i])
+    log("[sched] co-located profile: %d partitions in %.1f s" % (len(colo_meas), time.perf_counter() - t0))
+    pred.fit()
+    err_fit = [abs(pred.solo(lv, bs, n) - ms) / ms for (lv, bs, n), ms in solo_meas.items()]
+    err_held = [abs(pred.solo(lv, bs, n) - ms) / ms for (lv, bs, n), ms in held.items()]
+    b1, k1 = pred.colo_coef()
+    err_colo = [abs((i / N_LEVELS * b1 + f / N_LEVELS * k1) * base[i] - ms) / ms for (i, f), ms in colo_meas.items()]
+    report = {
+        "levels": N_LEVELS, "compute_units": cs.n_cu,
+        "eq1_mean_abs_err_fitted_points": float(np.mean(err_fit)), "eq1_mean_abs_err_heldout": float(np.mean(err_held)),
+        "eq1_max_abs_err_heldout": float(np.max(err_held)),
+        "eq1_coef_full_chip_b0_c0_k0_ms": list(pred.solo_coef(N_LEVELS)),
+        "eq2_b1_k1": [b1, k1], "eq2_mean_abs_err": float(np.mean(err_colo)), "eq2_max_abs_err": float(np.max(err_colo)),
+        "solo_ms_by_level_workload_batch": [base[lv] for lv in range(1, N_LEVELS + 1)],
+        "colo_ms": {"%d+%d" % k: v for k, v in sorted(colo_meas.items())},
+    }
+    cs.close()
+    return pred, report
+
+
+def run_colocated(hz, sD, sF, decode_once, K, W, pace_ms=None, finetune=True):
+    """K timed finetune units on sF with decode on sD beside them (decode_once() issues one step on sD).
+    pace_ms None: decode steps back to back; otherwise one step every pace_ms.  With finetune False only decode
+    runs, for K * 3 ms.  Returns tokens/s, ms per unit, decode completion-to-completion intervals and step
+    latencies (ms) inside the timed window."""
+    stop = threading.Event()
+    started = threading.Event()
+    dec_start, dec_end = [], []
+
+    def decode_thread():
+        torch.cuda.set_device(0)
+        i = 0
+        t_next = time.perf_counter()
+        while not stop.is_set():
+            if pace_ms is not None:
+                while True:
+                    now = time.perf_counter()
+                    if now >= t_next or stop.is_set():
+                        break
+                    time.sleep(min(2e-4, t_next - now))
+                t_next = max(t_next + pace_ms * 1e-3, time.perf_counter() - 5 * pace_ms * 1e-3)
+            if i >= 256:
+                dec_end[i - 256].synchronize()         # bound the run-ahead of the host thread
+            e0 = torch.cuda.Event(enable_timing=True)
+            e0.record(sD)
+            decode_once()
+            e1 = torch.cuda.Event(enable_timing=True)
+            e1.record(sD)
+            dec_start.append(e0)
+            dec_end.append(e1)
+            i += 1
+            if i == 8:
+                started.set()
+
+    th = threading.Thread(target=decode_thread, daemon=True)
+    th.start()
+    started.wait()
+    if finetune:
+        for _ in range(W):
+            hz.finetune_unit(sF)
+        sF.synchronize()
+    torch.cuda.synchronize()
+    i0 = len(dec_end)
+    t0 = time.perf_counter()
+    if finetune:
+        for _ in range(K):
+            hz.finetune_unit(sF)
+        sF.synchronize()
+    else:
+        time.sleep(K * 3e-3)
+    t1 = time.perf_counter()
+    i1 = len(dec_end)
+    stop.set()
+    th.join()
+    torch.cuda.synchronize()
+    elapsed = t1 - t0
+    lo, hi = max(i0, 1) - 1, i1
+    tpot = np.array([dec_end[j].elapsed_time(dec_end[j + 1]) for j in range(lo, hi - 1)]) if hi - lo > 2 else np.array([float("nan")])
+    steplat = np.array([dec_start[j].elapsed_time(dec_end[j]) for j in range(lo, hi)]) if hi > lo else np.array([float("nan")])
+    return {"elapsed": elapsed, "tokens_per_s": K * hz.T / elapsed if finetune else 0.0, "ms_per_step": elapsed * 1e3 / K,
+            "tpot": tpot, "steplat": steplat}

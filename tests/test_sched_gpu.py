@@ -1,0 +1,72 @@
+"""Compute-unit partitions and the predictor on the device: a decode step on a CU-range stream gives the same
+result as on an ordinary stream, profiling yields a usable Eq. 1 / Eq. 2 fit, and the chosen partition keeps
+the decode time per output token inside the SLO while finetune units run beside it."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from paper_2511_11729_amd import binding as hb
+from paper_2511_11729_amd import colocate
+from paper_2511_11729_amd.harness import LayerHarness
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def hz():
+    return LayerHarness(wl.workload(1), in_flight=8, decode_capacity=(64, 2048))
+
+
+def test_cu_range_stream_validates_its_range():
+    n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+    for first, count in [(-1, 4), (0, 0), (n_cu, 1), (8, n_cu)]:
+        with pytest.raises(hb.HarliError) as e:
+            hb.cu_stream_create(first, count)
+        assert e.value.status == hb.HARLI_ERR_INVALID
+    s = hb.cu_stream_create(n_cu - 8, 8)
+    hb.cu_stream_destroy(s)
+
+
+def test_decode_on_a_quarter_of_the_chip_matches_the_full_chip(hz):
+    cs = colocate.CuStreams()
+    full = torch.cuda.Stream()
+    part = cs.low(3)                                   # 30 % of the compute units
+    hz.decode_launch(full)
+    full.synchronize()
+    want = hz.y_dev[: hz.B].clone()
+    hz.y_dev.zero_()
+    hz.decode_launch(part)
+    part.synchronize()
+    hz.ctx.check(part)
+    got = hz.y_dev[: hz.B]
+    # same kernels, same inputs; only the order of a few fp32 atomic sums may differ
+    assert torch.allclose(got, want, rtol=1e-4, atol=1e-5 * float(want.abs().max()))
+    t_full = colocate.time_decode(hz, full, None, None, None, 10)
+    t_part = colocate.time_decode(hz, part, None, None, None, 10)
+    assert t_part > 1.3 * t_full                       # the restriction is real
+    cs.close()
+
+
+def test_profile_fit_and_scheduled_colocation(hz):
+    pred, rep = colocate.profile(hz, steps=6)
+    solo = rep["solo_ms_by_level_workload_batch"]
+    assert solo[0] > 2.0 * solo[-1]                    # a tenth of the chip is much slower than all of it
+    assert all(solo[i + 1] <= 1.15 * solo[i] for i in range(9))
+    assert rep["eq1_mean_abs_err_heldout"] < 0.20      # Eq. 1 describes decode latency on every partition
+    b0, c0, k0 = rep["eq1_coef_full_chip_b0_c0_k0_ms"]
+    assert c0 > 0 and k0 > 0                           # a weight-streaming floor and a per-token cost
+    slo = 40.0 / 32.0
+    il, fl, plat = pred.pick(hz.B, int(hz.kv_len.mean()), slo)
+    assert 1 <= il <= 10 and 0 <= fl <= 10 - il and (fl == 0 or plat <= slo)
+    cs = colocate.CuStreams()
+    sD = cs.low(il)
+    cs.low(il)                                         # spacer (dispatch pipes, see colocate.profile)
+    sF = cs.high(max(fl, 1))
+    res = colocate.run_colocated(hz, sD, sF, lambda: hz.decode_launch(sD), 4, 1, None)
+    hz.ctx.check(sD)
+    cs.close()
+    assert res["tokens_per_s"] > 0
+    assert float(np.percentile(res["tpot"], 99)) <= slo
+    st = hz.pool.stats()
+    assert st.pending_frees == 0 or st.pending_frees <= 16
