@@ -287,6 +287,7 @@ extern "C" harli_status harli_lora_attach(harli_ctx* c, const harli_lora_cfg* cf
     return fail(HARLI_ERR_INVALID, "lora_attach: rank must be 8, 16, 32 or 64, got %d", cfg->rank);
   if (cfg->targets == 0 || cfg->targets >= (1u << kTargets)) return fail(HARLI_ERR_INVALID, "lora_attach: bad target mask");
   if (c->cfg.max_ft_tokens < 1) return fail(HARLI_ERR_STATE, "lora_attach: the context was created with max_ft_tokens = 0");
+  if (c->cfg.head_dim > 512) return fail(HARLI_ERR_INVALID, "lora_attach: head_dim %d above 512 is not supported", c->cfg.head_dim);
   for (int l = 0; l < c->cfg.n_layers; ++l)
     for (int t = 0; t < kTargets; ++t)
       if (((cfg->targets >> t) & 1u) && (!A[l * kTargets + t] || !B[l * kTargets + t]))

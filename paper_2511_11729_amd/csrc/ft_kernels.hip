@@ -74,11 +74,24 @@ __global__ void __launch_bounds__(256) k_rmsnorm_bwd(const float* dh, const floa
 }
 
 // ---------------------------------------------------------------- rotary embedding, pairs (i, i + d/2)
-// one thread rotates eight adjacent pairs with two 16-byte loads and stores when d/2 is a multiple of 8 (rows are
-// 16-byte aligned then: heads*d is a multiple of 8); other head sizes take the pair-at-a-time loop
+// One workgroup per token.  The d/2 (cos, sin) pairs of the token's position are computed once into LDS (angle
+// reduced in double, as the oracle's positions are exact) and shared by every head.  One thread rotates eight
+// adjacent pairs with two 16-byte loads and stores when d/2 is a multiple of 8 (rows are 16-byte aligned then:
+// heads*d is a multiple of 8); other head sizes take the pair-at-a-time loop.
+constexpr int kRopeMaxHalf = 256;
 __global__ void __launch_bounds__(256) k_rope(bf* x, int S, int heads, int d, const double* inv_freq, float sign) {
+  __shared__ float cs_[kRopeMaxHalf], sn_[kRopeMaxHalf];
   const int t = blockIdx.x, half = d >> 1;
   const double pos = (double)(t % S);
+  for (int i = threadIdx.x; i < half; i += 256) {
+    const double ang = pos * inv_freq[i];
+    const double red = ang - 6.283185307179586476925 * rint(ang * 0.15915494309189533577);
+    float sn, cs;
+    sincosf((float)red, &sn, &cs);
+    cs_[i] = cs;
+    sn_[i] = sn * sign;
+  }
+  __syncthreads();
   bf* row = x + (size_t)t * heads * d;
   if ((half & 7) == 0) {
     const int per_head = half >> 3;
@@ -91,11 +104,7 @@ __global__ void __launch_bounds__(256) k_rope(bf* x, int S, int heads, int d, co
       UNPACK8(hi4, hi);
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        const double ang = pos * inv_freq[i0 + e];
-        const double red = ang - 6.283185307179586476925 * rint(ang * 0.15915494309189533577);
-        float sn, cs;
-        sincosf((float)red, &sn, &cs);
-        sn *= sign;
+        const float cs = cs_[i0 + e], sn = sn_[i0 + e];
         ol[e] = lo[e] * cs - hi[e] * sn;
         oh[e] = hi[e] * cs + lo[e] * sn;
       }
@@ -106,11 +115,7 @@ __global__ void __launch_bounds__(256) k_rope(bf* x, int S, int heads, int d, co
   }
   for (int idx = threadIdx.x; idx < heads * half; idx += 256) {
     const int hh = idx / half, i = idx - hh * half;
-    const double ang = pos * inv_freq[i];
-    const double red = ang - 6.283185307179586476925 * rint(ang * 0.15915494309189533577);
-    float sn, cs;
-    sincosf((float)red, &sn, &cs);
-    sn *= sign;
+    const float cs = cs_[i], sn = sn_[i];
     bf* p = row + hh * d + i;
     const float lo = E2F(p[0]), hi = E2F(p[half]);
     p[0] = F2E(lo * cs - hi * sn);
@@ -289,10 +294,20 @@ __global__ void __launch_bounds__(256) k_attn_ds_t(const float* ST, const float*
 }
 
 // ---------------------------------------------------------------- skinny NT GEMM (LoRA down-projection x.A and dy.B^T)
-// Workgroup = 16 rows of X, 4 waves split K, one 16x16x32 MFMA column tile per 16 outputs.
+// Workgroup = 16 rows of X, 8 waves split K, one 16x16x32 MFMA column tile per 16 outputs.  Full 32-wide K steps are
+// loaded four at a time, unconditionally; only a last partial step (K % 32) masks its operands.
+typedef unsigned __attribute__((ext_vector_type(4))) u32x4;  // native vector: arrays of it stay in registers
+__device__ __forceinline__ f32x4 mma16(const u32x4& a, const u32x4& b, f32x4 c) {
+#if HARLI_FT_HALF
+  return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+#else
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+#endif
+}
 template <int NT>
-__global__ void __launch_bounds__(256) k_skinny_nt(const bf* X, long long ldx, const bf* Bm, long long ldb, bf* C,
+__global__ void __launch_bounds__(512) k_skinny_nt(const bf* X, long long ldx, const bf* Bm, long long ldb, bf* C,
                                                    long long ldc, int M, int N, int K, float alpha) {
+  constexpr int NW = 8, U = 4;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, i16 = lane & 15, g = lane >> 4;
   const int m0 = blockIdx.x * 16;
   const int mr = min(m0 + i16, M - 1);
@@ -303,40 +318,52 @@ __global__ void __launch_bounds__(256) k_skinny_nt(const bf* X, long long ldx, c
   f32x4 acc[NT];
 #pragma unroll
   for (int t = 0; t < NT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-  const int steps = (K + 31) >> 5;
-  const int s0 = steps * wave / 4, s1 = steps * (wave + 1) / 4;
-  for (int s = s0; s < s1; ++s) {
-    const int k = s << 5;
+  const int full = K >> 5;  // whole 32-wide steps
+  const int s0 = full * wave / NW, s1 = full * (wave + 1) / NW;
+  int s = s0;
+  for (; s + U <= s1; s += U) {
+    u32x4 xf[U], bfr[NT][U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      xf[u] = *reinterpret_cast<const u32x4*>(xr + ((s + u) << 5));
+#pragma unroll
+      for (int t = 0; t < NT; ++t) bfr[t][u] = *reinterpret_cast<const u32x4*>(br[t] + ((s + u) << 5));
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int t = 0; t < NT; ++t) acc[t] = mma16(xf[u], bfr[t][u], acc[t]);  // rows of X = MFMA rows, rows of Bm = columns
+  }
+  for (; s < s1; ++s) {
+    const u32x4 xf = *reinterpret_cast<const u32x4*>(xr + (s << 5));
+#pragma unroll
+    for (int t = 0; t < NT; ++t) acc[t] = mma16(xf, *reinterpret_cast<const u32x4*>(br[t] + (s << 5)), acc[t]);
+  }
+  if (wave == NW - 1 && (K & 31)) {  // partial last step: lanes whose 8 k lie past K contribute zeros
+    const int k = full << 5;
     const bool ok = k + g * 8 < K;
     const int kc = ok ? k : 0;
-    uint4 xf = *reinterpret_cast<const uint4*>(xr + kc);
-    if (!ok) xf = make_uint4(0, 0, 0, 0);
+    u32x4 xf = *reinterpret_cast<const u32x4*>(xr + kc);
+    if (!ok) xf = u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
-    for (int t = 0; t < NT; ++t) {
-      const uint4 bfr = *reinterpret_cast<const uint4*>(br[t] + kc);
-      // rows of X are the MFMA "row" operand, rows of Bm the "column" operand: D[m][n]
-#if HARLI_FT_HALF
-      acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, xf), __builtin_bit_cast(f16x8, bfr), acc[t], 0, 0, 0);
-#else
-      acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, xf), __builtin_bit_cast(bf16x8, bfr), acc[t], 0, 0, 0);
-#endif
-    }
+    for (int t = 0; t < NT; ++t) acc[t] = mma16(xf, *reinterpret_cast<const u32x4*>(br[t] + kc), acc[t]);
   }
-  __shared__ float4 red[4][NT][64];
+  __shared__ float4 red[NW][NT][64];
 #pragma unroll
   for (int t = 0; t < NT; ++t) red[wave][t][lane] = make_float4(acc[t][0], acc[t][1], acc[t][2], acc[t][3]);
   __syncthreads();
   if (wave == 0) {
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
-      float4 s = red[0][t][lane];
-      for (int w = 1; w < 4; ++w) {
+      float4 sm = red[0][t][lane];
+#pragma unroll
+      for (int w = 1; w < NW; ++w) {
         const float4 o = red[w][t][lane];
-        s.x += o.x; s.y += o.y; s.z += o.z; s.w += o.w;
+        sm.x += o.x; sm.y += o.y; sm.z += o.z; sm.w += o.w;
       }
       // lane holds D[m = 4g + e][n = i16]
       const int n = t * 16 + i16;
-      const float v[4] = {s.x, s.y, s.z, s.w};
+      const float v[4] = {sm.x, sm.y, sm.z, sm.w};
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         const int m = m0 + 4 * g + e;
@@ -352,6 +379,61 @@ __global__ void __launch_bounds__(256) k_skinny_nt(const bf* X, long long ldx, c
 // read as one 32-bit word per lane and token, eight tokens in flight (rows past the chunk reuse its last row against
 // zero U rows).  The chunk's sums go to part[chunk][r][j].  Pass 2 adds the chunks and accumulates into G.
 constexpr int kLgT = 64, kLgMaxChunks = 32;
+#if HARLI_FT_HALF
+// Half operands: two tokens per v_dot2_f32_f16 (exact products, fp32 accumulation).  U is staged in LDS as packed
+// pairs (U[t][r], U[t+1][r]); the matching pairs of X are assembled from the two tokens' 32-bit words.
+typedef _Float16 h16x2 __attribute__((ext_vector_type(2)));
+template <int R>
+__global__ void __launch_bounds__(256) k_lora_grad_part(const bf* X, long long ldx, const bf* U, long long ldu, float* part,
+                                                        int T, int J, int tpc) {
+  __shared__ __align__(16) unsigned us2[kLgT / 2][R];
+  const int tid = threadIdx.x;
+  const int j0 = (blockIdx.x * 256 + tid) * 2;
+  const int c0 = blockIdx.y * tpc, c1 = min(T, c0 + tpc);
+  float a0[R], a1[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) a0[r] = a1[r] = 0.f;
+  for (int t0 = c0; t0 < c1; t0 += kLgT) {
+    const int nt = min(kLgT, c1 - t0);
+    __syncthreads();
+    for (int i = tid; i < (kLgT / 2) * R; i += 256) {
+      const int tp = i / R, r = i - tp * R;
+      const unsigned lo = 2 * tp < nt ? U[(long long)(t0 + 2 * tp) * ldu + r] : 0u;
+      const unsigned hi = 2 * tp + 1 < nt ? U[(long long)(t0 + 2 * tp + 1) * ldu + r] : 0u;
+      us2[tp][r] = lo | (hi << 16);
+    }
+    __syncthreads();
+    const bf* xp = X + (long long)t0 * ldx + min(j0, J - 2);
+    for (int tp = 0; tp < kLgT / 2; tp += 4) {
+      unsigned xv[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) xv[u] = *reinterpret_cast<const unsigned*>(xp + (long long)min(2 * tp + u, nt - 1) * ldx);
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const unsigned w0 = xv[2 * u], w1 = xv[2 * u + 1];
+        const h16x2 p0 = __builtin_bit_cast(h16x2, (w0 & 0xffffu) | (w1 << 16));        // (X[t][j0],   X[t+1][j0])
+        const h16x2 p1 = __builtin_bit_cast(h16x2, (w0 >> 16) | (w1 & 0xffff0000u));   // (X[t][j0+1], X[t+1][j0+1])
+#pragma unroll
+        for (int r = 0; r < R; r += 4) {
+          const uint4 uu = *reinterpret_cast<const uint4*>(&us2[tp + u][r]);
+          const unsigned uw[4] = {uu.x, uu.y, uu.z, uu.w};
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const h16x2 up = __builtin_bit_cast(h16x2, uw[e]);
+            a0[r + e] = __builtin_amdgcn_fdot2(p0, up, a0[r + e], false);
+            a1[r + e] = __builtin_amdgcn_fdot2(p1, up, a1[r + e], false);
+          }
+        }
+      }
+    }
+  }
+  if (j0 < J) {
+    float* p = part + (long long)blockIdx.y * R * J + j0;
+#pragma unroll
+    for (int r = 0; r < R; ++r) *reinterpret_cast<float2*>(p + (long long)r * J) = make_float2(a0[r], a1[r]);
+  }
+}
+#else
 template <int R>
 __global__ void __launch_bounds__(256) k_lora_grad_part(const bf* X, long long ldx, const bf* U, long long ldu, float* part,
                                                         int T, int J, int tpc) {
@@ -393,6 +475,8 @@ __global__ void __launch_bounds__(256) k_lora_grad_part(const bf* X, long long l
     for (int r = 0; r < R; ++r) *reinterpret_cast<float2*>(p + (long long)r * J) = make_float2(a0[r], a1[r]);
   }
 }
+
+#endif
 
 // G[j*sj + r*sr] += out_mul * sum_c part[c][r][j]: one thread per (r, j), lanes along j (the reads of part, 2 x
 // nchunk times the volume of G, are the contiguous side)
@@ -500,7 +584,7 @@ void ft_attn_ds_t(const float* ST, const float* dPT, const float* lse, const flo
 void ft_skinny_nt(const bf* X, long long ldx, const bf* Bm, long long ldb, bf* C, long long ldc, int M, int N, int K,
                   float alpha, hipStream_t st) {
   const int nt = (N + 15) / 16;
-  const dim3 grid((M + 15) / 16), blk(256);
+  const dim3 grid((M + 15) / 16), blk(512);
   if (nt == 1) hipLaunchKernelGGL(k_skinny_nt<1>, grid, blk, 0, st, X, ldx, Bm, ldb, C, ldc, M, N, K, alpha);
   else if (nt == 2) hipLaunchKernelGGL(k_skinny_nt<2>, grid, blk, 0, st, X, ldx, Bm, ldb, C, ldc, M, N, K, alpha);
   else hipLaunchKernelGGL(k_skinny_nt<4>, grid, blk, 0, st, X, ldx, Bm, ldb, C, ldc, M, N, K, alpha);
