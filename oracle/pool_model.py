@@ -50,6 +50,7 @@ class PoolModel:
         assert order * small_granule == block_bytes and order & (order - 1) == 0
         self.block_bytes, self.n_layers = block_bytes, n_layers
         self.page_bytes = page_tokens * kv_row_bytes
+        self._kv_row_bytes = kv_row_bytes
         self.ppb = block_bytes // self.page_bytes
         assert self.ppb >= 1
         self.bpc = 2 * n_layers
@@ -203,6 +204,30 @@ class PoolModel:
             self._free_small(off, nbytes)
         else:
             self._free_tensor(off, nbytes)
+
+    # -- inter-task coordination (Sec. 4.4) -------------------------------------------
+    def reserve_chunks_for(self, release_time: float, slo: float, max_bs: int) -> int:
+        """Chunks that hold Memory_reserved = (T / SLO) * max_bs * Mem_kv: while the finetune task takes
+        `release_time` to give memory back, decode runs release_time / slo steps and each appends one token to at
+        most max_bs sequences.  A token's KV (every layer's K and V) is one slot of a chunk, so the reserve is
+        ceil(ceil(release_time / slo * max_bs) / tokens_per_chunk) chunks."""
+        import math
+        tokens = math.ceil(release_time / slo * max_bs - 1e-12)
+        per_chunk = self.ppb * (self.page_bytes // self.kv_row_bytes_())
+        return -(-tokens // per_chunk)
+
+    def kv_row_bytes_(self) -> int:
+        return self._kv_row_bytes
+
+    def set_reserve(self, chunks: int) -> None:
+        assert chunks >= 0
+        self.reserve = chunks
+
+    def pressure(self) -> int:
+        """Chunks the finetune task should relinquish now: the shortfall of FREE chunks against the reserve, but
+        no more than the TENSOR chunks that exist."""
+        short = max(0, self.reserve - self.free_chunks())
+        return min(short, sum(1 for c in self.cls if c == TENSOR))
 
     # -- invariants -----------------------------------------------------------------
     def is_pristine(self) -> bool:

@@ -250,3 +250,45 @@ def test_random_trace_never_overlaps_and_returns_to_pristine(seed):
     for off in list(live):
         p.free(off)
     assert p.is_pristine()
+
+
+# ---- inter-task memory coordination (Sec. 4.4): the reserve formula and the back-pressure count ----
+
+def _coord_model(n_chunks=12, n_layers=2, reserve=0):
+    from oracle.pool_model import PoolModel
+    block = 64 << 10
+    return PoolModel(n_chunks * n_layers * 2 * block, block, n_layers, 16, 512, 0, 2048, reserve)
+
+
+def test_reserve_formula_hand_values():
+    """Memory_reserved = (T/SLO) * max_bs * Mem_kv, in whole chunks.  Geometry: 64 KiB blocks, 512 B rows,
+    16-token pages -> 8 pages = 128 tokens per chunk."""
+    m = _coord_model()
+    assert m.ppb == 8
+    # release 100 ms, SLO 50 ms: two decode steps; 64 sequences -> 128 tokens -> exactly one chunk
+    assert m.reserve_chunks_for(100.0, 50.0, 64) == 1
+    assert m.reserve_chunks_for(100.0, 50.0, 65) == 2          # 130 tokens
+    assert m.reserve_chunks_for(25.0, 50.0, 1) == 1            # half a step still needs the token's slot
+    assert m.reserve_chunks_for(0.0, 50.0, 256) == 0
+    # the paper's own example scale: T = 80 ms, SLO 50 ms, 256 sequences -> 410 tokens -> 4 chunks of 128
+    assert m.reserve_chunks_for(80.0, 50.0, 256) == 4
+
+
+def test_pressure_counts_the_shortfall_against_the_reserve():
+    m = _coord_model(n_chunks=6, reserve=2)
+    t = [m.alloc_tensor(m.chunk_bytes) for _ in range(4)]      # four TENSOR chunks, two FREE left = the reserve
+    assert m.free_chunks() == 2 and m.pressure() == 0
+    import pytest
+    from oracle.pool_model import PoolOOM
+    with pytest.raises(PoolOOM):
+        m.alloc_tensor(m.chunk_bytes)                          # would eat the reserve
+    pages = [m.alloc_page() for _ in range(m.ppb + 1)]         # decode grows into the reserve: two KV chunks
+    assert m.free_chunks() == 0 and m.pressure() == 2
+    m.free(t[0][0])
+    assert m.pressure() == 1
+    m.set_reserve(5)
+    assert m.pressure() == 3                                   # never more than the TENSOR chunks that exist
+    for pg in pages:
+        m.free_page(pg)
+    m.set_reserve(2)
+    assert m.pressure() == 0
