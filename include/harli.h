@@ -130,6 +130,20 @@ harli_status harli_pool_free_pages(harli_pool* p, int32_t n_pages, const int32_t
 harli_status harli_pool_kv_addr(const harli_pool* p, int32_t page, int32_t layer, int32_t kv, size_t* byte_off);
 harli_status harli_pool_stats(harli_pool* p, harli_pool_stats_t* out);
 
+/* Inter-task memory coordination (Sec. 4.4, Principle 3).
+ * reserve_chunks_for: the number of chunks that hold Memory_reserved = (T / SLO) * max_bs * Mem_kv at page
+ *   granularity, where release_time (T) is how long the finetune task needs to give memory back and slo the decode
+ *   QoS target (same unit) and max_bs the largest decode batch: in ceil(T / SLO) decode steps each sequence appends
+ *   that many tokens and may need ceil(steps / page_tokens) new pages, so the reserve is
+ *   ceil(max_bs * ceil(ceil(T / SLO) / page_tokens) / pages_per_block) chunks.  Pure arithmetic on the geometry.
+ * set_reserve: replaces kv_reserve_chunks (it only gates FUTURE tensor-chunk conversions; nothing is evicted).
+ * pressure: how many chunks the finetune task should relinquish now = min(max(0, reserve - FREE chunks),
+ *   TENSOR chunks); polls pending event-deferred frees first.  The caller answers by releasing saved
+ *   activations / skipping finetune units until it reads 0. */
+harli_status harli_pool_reserve_chunks_for(const harli_pool* p, double release_time, double slo, int32_t max_bs, int32_t* chunks);
+harli_status harli_pool_set_reserve(harli_pool* p, int32_t chunks);
+harli_status harli_pool_pressure(harli_pool* p, int32_t* chunks_to_release);
+
 /* ======================================================================== *
  * Model context: shapes plus BORROWED device pointers to the frozen weights.
  * ======================================================================== */

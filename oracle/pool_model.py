@@ -207,14 +207,16 @@ class PoolModel:
 
     # -- inter-task coordination (Sec. 4.4) -------------------------------------------
     def reserve_chunks_for(self, release_time: float, slo: float, max_bs: int) -> int:
-        """Chunks that hold Memory_reserved = (T / SLO) * max_bs * Mem_kv: while the finetune task takes
-        `release_time` to give memory back, decode runs release_time / slo steps and each appends one token to at
-        most max_bs sequences.  A token's KV (every layer's K and V) is one slot of a chunk, so the reserve is
-        ceil(ceil(release_time / slo * max_bs) / tokens_per_chunk) chunks."""
+        """Chunks that hold Memory_reserved = (T / SLO) * max_bs * Mem_kv at page granularity: while the finetune
+        task takes `release_time` to give memory back, decode runs ceil(release_time / slo) steps and each of at
+        most max_bs sequences appends one token per step.  KV memory is handed out in pages of page_tokens tokens,
+        so a sequence may need ceil(steps / page_tokens) new pages in that window (a sequence that has just started
+        needs its first page for its first token): the reserve is max_bs times that many pages, in whole chunks."""
         import math
-        tokens = math.ceil(release_time / slo * max_bs - 1e-12)
-        per_chunk = self.ppb * (self.page_bytes // self.kv_row_bytes_())
-        return -(-tokens // per_chunk)
+        steps = math.ceil(release_time / slo - 1e-12)
+        page_tokens = self.page_bytes // self._kv_row_bytes
+        pages = max_bs * (-(-steps // page_tokens))
+        return -(-pages // self.ppb)
 
     def kv_row_bytes_(self) -> int:
         return self._kv_row_bytes

@@ -97,6 +97,9 @@ _SIGS = {
     "harli_saved_bytes": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_size_t)]),
     "harli_prof_enable": (C.c_int, [C.c_int32]),
     "harli_prof_collect": (C.c_int, [C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
+    "harli_pool_reserve_chunks_for": (C.c_int, [C.c_void_p, C.c_double, C.c_double, C.c_int32, C.POINTER(C.c_int32)]),
+    "harli_pool_set_reserve": (C.c_int, [C.c_void_p, C.c_int32]),
+    "harli_pool_pressure": (C.c_int, [C.c_void_p, C.POINTER(C.c_int32)]),
     "harli_pred_create": (C.c_int, [C.c_int32, C.POINTER(C.c_void_p)]),
     "harli_pred_destroy": (None, [C.c_void_p]),
     "harli_pred_add_solo": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_double]),
@@ -202,6 +205,21 @@ class Pool:
         s = PoolStats()
         _check(lib().harli_pool_stats(self.handle, C.byref(s)))
         return s
+
+    def reserve_chunks_for(self, release_time: float, slo: float, max_bs: int) -> int:
+        """Chunks holding Memory_reserved = (T / SLO) * max_bs * Mem_kv (Sec. 4.4)."""
+        n = C.c_int32()
+        _check(lib().harli_pool_reserve_chunks_for(self.handle, release_time, slo, max_bs, C.byref(n)))
+        return n.value
+
+    def set_reserve(self, chunks: int) -> None:
+        _check(lib().harli_pool_set_reserve(self.handle, chunks))
+
+    def pressure(self) -> int:
+        """Chunks the finetune task should relinquish now."""
+        n = C.c_int32()
+        _check(lib().harli_pool_pressure(self.handle, C.byref(n)))
+        return n.value
 
 
 def _event(e) -> Optional[int]:

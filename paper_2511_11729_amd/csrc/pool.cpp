@@ -7,6 +7,7 @@
 #include <cstdio>
 #include <cstring>
 #include <map>
+#include <cmath>
 #include <mutex>
 #include <set>
 #include <string>
@@ -483,6 +484,36 @@ harli_status harli_pool_stats(harli_pool* p, harli_pool_stats_t* out) {
   s.small_fallbacks = p->small_fallbacks;
   s.pending_frees = int64_t(p->pending.size());
   *out = s;
+  return HARLI_OK;
+}
+
+// ---- inter-task memory coordination (Sec. 4.4) ----
+harli_status harli_pool_reserve_chunks_for(const harli_pool* p, double release_time, double slo, int32_t max_bs, int32_t* chunks) {
+  if (!p || !chunks || !(release_time >= 0.0) || !(slo > 0.0) || max_bs < 1 || !std::isfinite(release_time) || !std::isfinite(slo))
+    return fail(HARLI_ERR_INVALID, "pool_reserve_chunks_for: bad argument");
+  // decode steps that pass while the finetune task is still releasing; each of max_bs sequences appends a token
+  // per step and may need ceil(steps / page_tokens) new pages in that window
+  const double st = std::ceil(release_time / slo - 1e-12);
+  if (st > 1e9) return fail(HARLI_ERR_INVALID, "pool_reserve_chunks_for: %.3g decode steps is out of range", st);
+  const long long steps = (long long)st;
+  const long long pages = (long long)max_bs * ((steps + p->cfg.page_tokens - 1) / p->cfg.page_tokens);
+  *chunks = (int32_t)((pages + p->ppb - 1) / p->ppb);
+  return HARLI_OK;
+}
+
+harli_status harli_pool_set_reserve(harli_pool* p, int32_t chunks) {
+  if (!p || chunks < 0) return fail(HARLI_ERR_INVALID, "pool_set_reserve: bad argument");
+  std::lock_guard<std::mutex> lk(p->mu);
+  p->cfg.kv_reserve_chunks = chunks;
+  return HARLI_OK;
+}
+
+harli_status harli_pool_pressure(harli_pool* p, int32_t* chunks_to_release) {
+  if (!p || !chunks_to_release) return fail(HARLI_ERR_INVALID, "pool_pressure: null argument");
+  std::lock_guard<std::mutex> lk(p->mu);
+  p->poll();
+  const int shortfall = std::max(0, p->cfg.kv_reserve_chunks - int(p->free_chunks.size()));
+  *chunks_to_release = std::min(shortfall, int(p->tensor_chunks.size()));
   return HARLI_OK;
 }
 

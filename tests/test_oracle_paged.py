@@ -261,17 +261,19 @@ def _coord_model(n_chunks=12, n_layers=2, reserve=0):
 
 
 def test_reserve_formula_hand_values():
-    """Memory_reserved = (T/SLO) * max_bs * Mem_kv, in whole chunks.  Geometry: 64 KiB blocks, 512 B rows,
-    16-token pages -> 8 pages = 128 tokens per chunk."""
+    """Memory_reserved = (T/SLO) * max_bs * Mem_kv at page granularity, in whole chunks.  Geometry: 64 KiB blocks,
+    512 B rows, 16-token pages -> 8 pages per chunk."""
     m = _coord_model()
     assert m.ppb == 8
-    # release 100 ms, SLO 50 ms: two decode steps; 64 sequences -> 128 tokens -> exactly one chunk
-    assert m.reserve_chunks_for(100.0, 50.0, 64) == 1
-    assert m.reserve_chunks_for(100.0, 50.0, 65) == 2          # 130 tokens
-    assert m.reserve_chunks_for(25.0, 50.0, 1) == 1            # half a step still needs the token's slot
+    # release 100 ms, SLO 50 ms: two decode steps, at most one new page per sequence; 64 sequences -> 64 pages
+    assert m.reserve_chunks_for(100.0, 50.0, 64) == 8
+    assert m.reserve_chunks_for(100.0, 50.0, 65) == 9
+    assert m.reserve_chunks_for(25.0, 50.0, 1) == 1            # half a step still needs the token's page
     assert m.reserve_chunks_for(0.0, 50.0, 256) == 0
-    # the paper's own example scale: T = 80 ms, SLO 50 ms, 256 sequences -> 410 tokens -> 4 chunks of 128
-    assert m.reserve_chunks_for(80.0, 50.0, 256) == 4
+    assert m.reserve_chunks_for(80.0, 50.0, 256) == 32
+    # a release lasting 20 steps can cross two page boundaries per sequence: 8 sequences -> 16 pages -> 2 chunks
+    assert m.reserve_chunks_for(1000.0, 50.0, 8) == 2
+    assert m.reserve_chunks_for(800.0, 50.0, 8) == 1           # 16 steps: one page each
 
 
 def test_pressure_counts_the_shortfall_against_the_reserve():
