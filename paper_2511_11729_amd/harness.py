@@ -56,6 +56,9 @@ class LayerHarness:
         self.slab = torch.zeros(self.slab_bytes, dtype=torch.uint8, device=DEV)
         self.pool = hb.Pool(self.slab, self.slab_bytes, block_bytes=block, n_layers=m.n_layers, kv_row_bytes=m.kv_row_bytes,
                             small_pool_bytes=small, kv_reserve_chunks=2)
+        # KV reserve from the coordination formula (Sec. 4.4): a finetune unit gives its activations back within about
+        # two unit times (6 ms); the decode QoS target of this single layer is 40 ms / 32
+        self.pool.set_reserve(self.pool.reserve_chunks_for(6.0, 40.0 / 32.0, cap_b))
         ids = np.array(self.pool.alloc_pages(total_pages), np.int64)[wl.page_order(w, total_pages)]
         self.max_pages = pages_per_seq
         table = ids.reshape(cap_b, pages_per_seq).astype(np.int32)
