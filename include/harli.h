@@ -248,6 +248,24 @@ harli_status harli_saved_release(harli_ctx* c, harli_saved* saved, void* hip_str
 /* Pool bytes a forward call of (B_f, S) reserves for its saved activations. */
 harli_status harli_saved_bytes(const harli_ctx* c, int32_t B_f, int32_t S, size_t* bytes);
 
+/* ======================================================================== *
+ * Adapter update (Sec. 2.1: finetuning = forward, backward, update).  The paper names no optimizer; this is
+ * AdamW with decoupled weight decay over n elements, all arithmetic in fp32:
+ *   g = grad[i] * grad_scale;  m = beta1*m + (1-beta1)*g;  v = beta2*v + (1-beta2)*g*g;
+ *   master -= lr * ( (m / (1 - beta1^step)) / (sqrt(v / (1 - beta2^step)) + eps) + weight_decay * master )
+ * master, m, v: device fp32 [n], updated in place (m, v start at zero).  grad: device fp32 [n] (the dA / dB that
+ * harli_lora_bwd accumulated); cleared afterwards when zero_grad != 0.  param_bf16: device bfloat16 [n], rewritten
+ * from master with round-to-nearest-even -- the A / B buffer given to harli_lora_attach -- or NULL.  step >= 1.
+ * Asynchronous on the stream.  HARLI_ERR_INVALID for null pointers, step < 1 or betas outside [0, 1).
+ * ======================================================================== */
+typedef struct {
+  float lr, beta1, beta2, eps, weight_decay, grad_scale;
+  int32_t step;      /* 1-based count of updates, for the bias corrections */
+  int32_t zero_grad; /* clear grad after the update */
+} harli_adamw_cfg;
+harli_status harli_adamw_step(float* master, float* m, float* v, float* grad, void* param_bf16, size_t n,
+                              const harli_adamw_cfg* cfg, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

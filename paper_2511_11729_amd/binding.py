@@ -64,6 +64,11 @@ class LoraCfg(C.Structure):
     _fields_ = [("rank", C.c_int32), ("alpha", C.c_float), ("targets", C.c_uint32)]
 
 
+class AdamWCfg(C.Structure):
+    _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float), ("weight_decay", C.c_float),
+                ("grad_scale", C.c_float), ("step", C.c_int32), ("zero_grad", C.c_int32)]
+
+
 class DecodeBatch(C.Structure):
     _fields_ = [("batch", C.c_int32), ("token_ids", C.c_void_p), ("x_in", C.c_void_p), ("x_out", C.c_void_p),
                 ("logits", C.c_void_p), ("next_token", C.c_void_p), ("kv_len", C.c_void_p), ("page_table", C.c_void_p),
@@ -97,6 +102,8 @@ _SIGS = {
     "harli_saved_bytes": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_size_t)]),
     "harli_prof_enable": (C.c_int, [C.c_int32]),
     "harli_prof_collect": (C.c_int, [C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
+    "harli_adamw_step": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.POINTER(AdamWCfg),
+                                   C.c_void_p]),
     "harli_pool_reserve_chunks_for": (C.c_int, [C.c_void_p, C.c_double, C.c_double, C.c_int32, C.POINTER(C.c_int32)]),
     "harli_pool_set_reserve": (C.c_int, [C.c_void_p, C.c_int32]),
     "harli_pool_pressure": (C.c_int, [C.c_void_p, C.POINTER(C.c_int32)]),
@@ -308,6 +315,14 @@ class Context:
         n = C.c_size_t()
         _check(lib().harli_saved_bytes(self.handle, B_f, S, C.byref(n)))
         return n.value
+
+
+def adamw_step(master, m, v, grad, param_bf16, *, step: int, lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0,
+               grad_scale=1.0, zero_grad=False, stream=None) -> None:
+    """AdamW on device tensors: fp32 master / moments / gradient, optional bf16 copy rewritten from the master."""
+    cfg = AdamWCfg(lr, beta1, beta2, eps, weight_decay, grad_scale, step, int(zero_grad))
+    _check(lib().harli_adamw_step(_ptr(master), _ptr(m), _ptr(v), _ptr(grad), _ptr(param_bf16), master.numel(), C.byref(cfg),
+                                  _stream(stream)))
 
 
 # ----------------------------------------------------------------------------- predictor / scheduler (harli_sched.h)
