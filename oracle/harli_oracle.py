@@ -449,3 +449,26 @@ def ce_loss(logits: np.ndarray, targets: np.ndarray):
     d = softmax(z)
     d[np.arange(N), targets] -= 1.0
     return loss, d / N
+
+
+def head_forward_backward(x: np.ndarray, g_final: np.ndarray, w_lm: np.ndarray, targets: np.ndarray, eps: float):
+    """Output layer of the finetune task (Sec. 2.1: "output layer" after the stack of transformer layers) with the
+    next-token cross entropy of the workloads that carry a vocabulary.
+
+    x [N, H]: hidden states after the last layer; h = RMSNorm(x; g_final); logits = h W_lm^T  ([N, V]).
+    targets [N]: class index per position, or -1 for a position that is not counted (the last token of a sequence).
+    loss = mean over counted positions of -log softmax(logits)[target]; returns (loss, d loss / d x, logits).
+    W_lm and g_final are frozen (no gradient)."""
+    x = np.asarray(x, F)
+    W = np.asarray(w_lm, F)
+    t = np.asarray(targets)
+    h = rmsnorm(x, g_final, eps)
+    logits = h @ W.T
+    valid = t >= 0
+    n = int(valid.sum())
+    loss, dl = ce_loss(logits[valid], t[valid])          # dl = (softmax - onehot) / n over the counted rows
+    dlogits = np.zeros_like(logits)
+    dlogits[valid] = dl
+    dh = dlogits @ W
+    dx = _rmsnorm_bwd(dh, x, g_final, eps)
+    return loss, dx, logits

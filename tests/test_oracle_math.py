@@ -397,3 +397,70 @@ def test_ce_loss_and_gradient():
         zp[idx] += eps
         zm[idx] -= eps
         assert np.isclose(d[idx], (O.ce_loss(zp, tg)[0] - O.ce_loss(zm, tg)[0]) / (2 * eps), atol=1e-8)
+
+
+# ---- output layer with cross entropy (head_forward_backward) ----
+
+def _head_case(seed=5, N=7, H=12, V=9):
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((N, H))
+    g = 1.0 + 0.1 * rng.standard_normal(H)
+    W = 0.3 * rng.standard_normal((V, H))
+    t = rng.integers(0, V, size=N)
+    t[2] = -1
+    t[N - 1] = -1
+    return x, g, W, t
+
+
+def test_head_loss_is_the_mean_nll_over_counted_positions():
+    from oracle import harli_oracle as O
+    x, g, W, t = _head_case()
+    loss, dx, logits = O.head_forward_backward(x, g, W, t, 1e-6)
+    # brute force, position by position
+    tot, n = 0.0, 0
+    for i in range(len(t)):
+        if t[i] < 0:
+            continue
+        xi = x[i]
+        h = xi * g / np.sqrt(np.mean(xi * xi) + 1e-6)
+        z = W @ h
+        tot += np.log(np.sum(np.exp(z - z.max()))) + z.max() - z[t[i]]
+        n += 1
+        assert np.allclose(z, logits[i])
+    assert n == 5 and abs(loss - tot / n) < 1e-12
+
+
+def test_head_dx_matches_finite_differences_and_ignores_uncounted_rows():
+    from oracle import harli_oracle as O
+    x, g, W, t = _head_case()
+    loss, dx, _ = O.head_forward_backward(x, g, W, t, 1e-6)
+    assert not dx[2].any() and not dx[-1].any()            # uncounted positions get no gradient
+    num = np.zeros_like(x)
+    e = 1e-6
+    for i in range(x.shape[0]):
+        for j in range(x.shape[1]):
+            xp, xm = x.copy(), x.copy()
+            xp[i, j] += e
+            xm[i, j] -= e
+            num[i, j] = (O.head_forward_backward(xp, g, W, t, 1e-6)[0] - O.head_forward_backward(xm, g, W, t, 1e-6)[0]) / (2 * e)
+    assert np.max(np.abs(num - dx)) < 1e-8
+
+
+def test_head_matches_torch_autograd():
+    import torch
+    from oracle import harli_oracle as O
+    x, g, W, t = _head_case(seed=9, N=11, H=16, V=23)
+    loss, dx, _ = O.head_forward_backward(x, g, W, t, 1e-6)
+    tx = torch.tensor(x, dtype=torch.float64, requires_grad=True)
+    h = tx * torch.tensor(g) / torch.sqrt((tx * tx).mean(-1, keepdim=True) + 1e-6)
+    z = h @ torch.tensor(W).T
+    l = torch.nn.functional.cross_entropy(z, torch.tensor(t), ignore_index=-1, reduction="mean")
+    l.backward()
+    assert abs(float(l) - loss) < 1e-12 and np.allclose(tx.grad.numpy(), dx, rtol=1e-10, atol=1e-14)
+
+
+def test_head_uniform_logits_give_log_vocab():
+    from oracle import harli_oracle as O
+    x = np.ones((3, 8))
+    loss, dx, _ = O.head_forward_backward(x, np.ones(8), np.zeros((50, 8)), np.array([1, 7, 49]), 1e-6)
+    assert abs(loss - np.log(50)) < 1e-12 and not dx.any()
