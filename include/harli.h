@@ -249,6 +249,22 @@ harli_status harli_saved_release(harli_ctx* c, harli_saved* saved, void* hip_str
 harli_status harli_saved_bytes(const harli_ctx* c, int32_t B_f, int32_t S, size_t* bytes);
 
 /* ======================================================================== *
+ * Output layer of the finetune task with next-token cross entropy (Sec. 2.1: "output layer" after the stack of
+ * transformer layers; the loss of the workloads that carry a vocabulary).  Needs g_final and w_lm in the context
+ * (bf16 storage) and harli_lora_attach.
+ *   h = RMSNorm(x; g_final);  logits = h W_lm^T;
+ *   loss = mean over the positions with targets[i] >= 0 of  -log softmax(logits[i])[targets[i]];
+ *   dx = d loss / d x   (W_lm and g_final are frozen).
+ * x: device fp32 [T, hidden], the last layer's output.  targets: device int32 [T], a class index below vocab or a
+ * negative value for a position that is not counted (the last token of each sequence); an index >= vocab sets the
+ * context's error flag (harli_ctx_check) and the position is skipped.  loss: device fp32 scalar.  dx: device fp32
+ * [T, hidden].  1 <= T <= cfg.max_ft_tokens.  Asynchronous on the stream; the library keeps half-precision copies of
+ * W_lm and W_lm^T and a workspace (logits are produced in row chunks and never returned).
+ * ======================================================================== */
+harli_status harli_head_fwd_bwd(harli_ctx* c, const float* x, const int32_t* targets, int32_t T, float* loss, float* dx,
+                                void* hip_stream);
+
+/* ======================================================================== *
  * Adapter update (Sec. 2.1: finetuning = forward, backward, update).  The paper names no optimizer; this is
  * AdamW with decoupled weight decay over n elements, all arithmetic in fp32:
  *   g = grad[i] * grad_scale;  m = beta1*m + (1-beta1)*g;  v = beta2*v + (1-beta2)*g*g;

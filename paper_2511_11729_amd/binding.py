@@ -102,6 +102,7 @@ _SIGS = {
     "harli_saved_bytes": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_size_t)]),
     "harli_prof_enable": (C.c_int, [C.c_int32]),
     "harli_prof_collect": (C.c_int, [C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
+    "harli_head_fwd_bwd": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]),
     "harli_adamw_step": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.POINTER(AdamWCfg),
                                    C.c_void_p]),
     "harli_pool_reserve_chunks_for": (C.c_int, [C.c_void_p, C.c_double, C.c_double, C.c_int32, C.POINTER(C.c_int32)]),
@@ -307,6 +308,11 @@ class Context:
                 pa[i] = _ptr(dA[t])
                 pb[i] = _ptr(dB[t])
         _check(lib().harli_lora_bwd(self.handle, layer, _ptr(dY), _ptr(dX), saved, pa, pb, _stream(stream)))
+
+    def head_fwd_bwd(self, x, targets, loss, dx, stream=None) -> None:
+        """Output layer + next-token cross entropy: x fp32 [T, hidden], targets int32 [T] (-1 = not counted), loss fp32
+        scalar tensor, dx fp32 [T, hidden]."""
+        _check(lib().harli_head_fwd_bwd(self.handle, _ptr(x), _ptr(targets), x.shape[0], _ptr(loss), _ptr(dx), _stream(stream)))
 
     def saved_release(self, saved: int, stream=None) -> None:
         _check(lib().harli_saved_release(self.handle, saved, _stream(stream)))

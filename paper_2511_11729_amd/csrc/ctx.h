@@ -61,6 +61,7 @@ struct harli_ctx {
   harli_lora_cfg lora{};
   void* ft_ws = nullptr;     // finetune workspace (library-owned)
   size_t ft_ws_bytes = 0;
+  void* head_ws = nullptr;   // output-layer workspace of the finetune task (library-owned)
   int n_cu = 0;
 };
 

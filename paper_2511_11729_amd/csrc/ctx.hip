@@ -25,6 +25,7 @@ static harli_status dev_alloc(T** p, size_t bytes, bool zero) {
 }
 
 void free_finetune_state(harli_ctx* c);  // finetune.hip
+void free_head_state(harli_ctx* c);      // head.hip
 
 }  // namespace harli
 
@@ -179,6 +180,7 @@ extern "C" void harli_ctx_destroy(harli_ctx* c) {
       if (ld.wp[t]) (void)hipFree(ld.wp[t]);
   if (c->wlm_p) (void)hipFree(c->wlm_p);
   free_finetune_state(c);
+  free_head_state(c);
   delete c;
 }
 

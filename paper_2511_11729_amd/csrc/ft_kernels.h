@@ -12,7 +12,7 @@ typedef unsigned short bf;
 // h = bf16(x * rho * g), rho = rsqrt(mean x^2 + eps) (also stored)
 void ft_rmsnorm_fwd(const float* x, const float* g, bf* h, float* rho, int T, int H, float eps, hipStream_t st);
 // dx = dres + rho * (dh*g - xhat * mean(dh*g*xhat)), xhat = x*rho;  dh is fp32
-// res_mul / out_mul: optional device scalars: dx = out_mul * (dres * res_mul + ...)
+// res_mul / out_mul: optional device scalars: dx = out_mul * (dres * res_mul + ...); dres may be NULL (taken as zero)
 void ft_rmsnorm_bwd(const float* dh, const float* x, const float* rho, const float* g, const float* dres, float* dx, int T,
                     int H, const float* res_mul, const float* out_mul, hipStream_t st);
 // rotary embedding in place on [T, heads*d] bf16, position = t % S; inverse rotates by the negative angle

@@ -63,7 +63,7 @@ __global__ void __launch_bounds__(256) k_rmsnorm_bwd(const float* dh, const floa
     const float4 v = *reinterpret_cast<const float4*>(xr + k);
     const float4 d = *reinterpret_cast<const float4*>(dr + k);
     const float4 gg = *reinterpret_cast<const float4*>(g + k);
-    const float4 rs = *reinterpret_cast<const float4*>(dres + (size_t)t * H + k);
+    const float4 rs = dres ? *reinterpret_cast<const float4*>(dres + (size_t)t * H + k) : make_float4(0.f, 0.f, 0.f, 0.f);
     float4 o;
     o.x = om * (rs.x * rm + r * (d.x * gg.x - v.x * c));
     o.y = om * (rs.y * rm + r * (d.y * gg.y - v.y * c));

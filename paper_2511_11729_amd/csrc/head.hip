@@ -1,0 +1,194 @@
+// Output layer of the finetune task with next-token cross entropy (Harli Sec. 2.1: the model is an embedding, a
+// stack of transformer layers and an output layer; the frozen output layer only passes the gradient down).
+//   h = RMSNorm(x; g_final), logits = h W_lm^T, loss = mean NLL over counted positions, dx = dloss/dx.
+// Logits exist only as a row chunk in the workspace: per chunk one MFMA GEMM makes them (fp32), one kernel turns a
+// row into (softmax - onehot) in half precision and adds the row's loss, and a second GEMM multiplies by W_lm.
+// The 1 / count of the mean is applied at the very end (RMSNorm backward), so the half-precision gradient of the
+// logits stays in [-1, 1].
+#include <algorithm>
+
+#include "ctx.h"
+#include "ft_elem.h"
+#include "ft_kernels.h"
+#include "gemm.h"
+
+namespace harli {
+namespace {
+
+struct HeadWs {
+  char* base = nullptr;
+  size_t bytes = 0;
+  bf *w16 = nullptr, *wT = nullptr;  // [V][H] and [H][Vp] in the compute element (made once)
+  bf *h = nullptr, *dlog = nullptr;
+  float *rho = nullptr, *logits = nullptr, *dh = nullptr, *acc = nullptr;  // acc: [0] loss sum, [1] count, [2] 1/count
+  int T = 0, TC = 0, Vp = 0;
+  bool weights_ready = false;
+};
+
+inline size_t al(size_t n) { return (n + 255) & ~size_t(255); }
+
+__global__ void k_head_reset(float* acc) {
+  if (threadIdx.x < 4) acc[threadIdx.x] = 0.f;
+}
+
+// one workgroup per row: max, log-sum-exp, loss, and dlog = softmax - onehot (zero row when the position is not counted)
+__global__ void __launch_bounds__(256) k_ce_row(const float* __restrict__ logits, const int* __restrict__ targets, bf* __restrict__ dlog,
+                                                int V, int Vp, float* acc, int* err_flag) {
+  __shared__ float red[4];
+  __shared__ float bc;
+  const int row = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const float* z = logits + (size_t)row * Vp;
+  bf* d = dlog + (size_t)row * Vp;
+  int tg = targets[row];
+  if (tg >= V) {
+    if (tid == 0) atomicOr(err_flag, 2);
+    tg = -1;
+  }
+  if (tg < 0) {
+    for (int j = tid; j < Vp; j += 256) d[j] = 0;
+    return;
+  }
+  float mx = -INFINITY;
+  for (int j = tid; j < V; j += 256) mx = fmaxf(mx, z[j]);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+  if (lane == 0) red[wave] = mx;
+  __syncthreads();
+  mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+  __syncthreads();
+  float sum = 0.f;
+  for (int j = tid; j < V; j += 256) sum += expf(z[j] - mx);
+  sum = wave_sum(sum);
+  if (lane == 0) red[wave] = sum;
+  __syncthreads();
+  if (tid == 0) {
+    const float tot = red[0] + red[1] + red[2] + red[3];
+    bc = 1.f / tot;
+    atomicAdd(acc, logf(tot) + mx - z[tg]);
+    atomicAdd(acc + 1, 1.f);
+  }
+  __syncthreads();
+  const float inv = bc;
+  for (int j = tid; j < Vp; j += 256) {
+    float p = j < V ? expf(z[j] - mx) * inv : 0.f;
+    if (j == tg) p -= 1.f;
+    d[j] = F2E(p);
+  }
+}
+
+__global__ void k_head_finish(float* acc, float* loss) {
+  const float n = fmaxf(acc[1], 1.f);
+  acc[2] = 1.f / n;
+  *loss = acc[0] / n;
+}
+
+// [V][H] bf16 -> [H][Vp] compute element, zero in the pad columns
+__global__ void __launch_bounds__(256) k_head_wt(const bf* __restrict__ w, bf* __restrict__ wT, int V, int H, int Vp) {
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= (long long)H * Vp) return;
+  const int hh = (int)(i / Vp), v = (int)(i - (long long)hh * Vp);
+  wT[i] = v < V ? F2E(bf2f(w[(long long)v * H + hh])) : 0;
+}
+
+HeadWs* ws_of(harli_ctx* c) { return static_cast<HeadWs*>(c->head_ws); }
+
+harli_status ensure(harli_ctx* c, int T, hipStream_t st) {
+  if (!c->head_ws) c->head_ws = new HeadWs;
+  HeadWs& w = *ws_of(c);
+  const int V = c->cfg.vocab, H = c->cfg.hidden;
+  const int Vp = (V + 7) & ~7;
+  if (!w.weights_ready) {
+    HARLI_HIP(hipMalloc(reinterpret_cast<void**>(&w.w16), (size_t)V * H * 2));
+    HARLI_HIP(hipMalloc(reinterpret_cast<void**>(&w.wT), (size_t)H * Vp * 2));
+    ft_from_bf16(static_cast<const bf*>(c->w_lm), w.w16, (long long)V * H, st);
+    const long long n = (long long)H * Vp;
+    hipLaunchKernelGGL(k_head_wt, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, static_cast<const bf*>(c->w_lm), w.wT, V, H, Vp);
+    w.Vp = Vp;
+    w.weights_ready = true;
+  }
+  if (T > w.T) {
+    // row chunk: at most 2048 rows and about 512 MiB of fp32 logits
+    const int TC = (int)std::max<long long>(64, std::min<long long>(2048, ((512ll << 20) / ((long long)Vp * 4)) / 64 * 64));
+    size_t off = 0;
+    auto take = [&](size_t n) {
+      size_t o = off;
+      off += al(n);
+      return o;
+    };
+    const size_t o_h = take((size_t)T * H * 2), o_rho = take((size_t)T * 4), o_log = take((size_t)TC * Vp * 4);
+    const size_t o_dlog = take((size_t)TC * Vp * 2), o_dh = take((size_t)T * H * 4), o_acc = take(64);
+    if (w.base) {
+      HARLI_HIP(hipStreamSynchronize(st));
+      HARLI_HIP(hipFree(w.base));
+      w.base = nullptr;
+    }
+    HARLI_HIP(hipMalloc(reinterpret_cast<void**>(&w.base), off));
+    w.bytes = off;
+    char* b = w.base;
+    w.h = (bf*)(b + o_h); w.rho = (float*)(b + o_rho); w.logits = (float*)(b + o_log); w.dlog = (bf*)(b + o_dlog);
+    w.dh = (float*)(b + o_dh); w.acc = (float*)(b + o_acc);
+    w.T = T;
+    w.TC = TC;
+  }
+  return HARLI_OK;
+}
+
+}  // namespace
+
+void free_head_state(harli_ctx* c) {
+  if (!c->head_ws) return;
+  HeadWs* w = ws_of(c);
+  if (w->base) (void)hipFree(w->base);
+  if (w->w16) (void)hipFree(w->w16);
+  if (w->wT) (void)hipFree(w->wT);
+  delete w;
+  c->head_ws = nullptr;
+}
+
+}  // namespace harli
+
+extern "C" harli_status harli_head_fwd_bwd(harli_ctx* c, const float* x, const int32_t* targets, int32_t T, float* loss, float* dx,
+                                           void* hip_stream) {
+  using namespace harli;
+  if (!c || !x || !targets || !loss || !dx) return fail(HARLI_ERR_INVALID, "head_fwd_bwd: null argument");
+  if (c->cfg.dtype != HARLI_BF16) return fail(HARLI_ERR_INVALID, "head_fwd_bwd: the finetune unit is built for bf16 storage");
+  if (!c->lora_attached) return fail(HARLI_ERR_STATE, "head_fwd_bwd: call harli_lora_attach first");
+  if (!c->w_lm || !c->g_final || c->cfg.vocab < 1) return fail(HARLI_ERR_STATE, "head_fwd_bwd: the context has no output layer (g_final, w_lm, vocab)");
+  if (T < 1 || T > c->cfg.max_ft_tokens) return fail(HARLI_ERR_INVALID, "head_fwd_bwd: %d tokens outside 1..max_ft_tokens %d", T, c->cfg.max_ft_tokens);
+  if (c->cfg.hidden % 8) return fail(HARLI_ERR_INVALID, "head_fwd_bwd: hidden must be a multiple of 8");
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  harli_status s = ensure(c, T, st);
+  if (s != HARLI_OK) return s;
+  HeadWs& w = *ws_of(c);
+  const int V = c->cfg.vocab, H = c->cfg.hidden, Vp = w.Vp;
+  ft_rmsnorm_fwd(x, c->g_final, w.h, w.rho, T, H, c->cfg.rms_eps, st);
+  hipLaunchKernelGGL(k_head_reset, dim3(1), dim3(64), 0, st, w.acc);
+  for (int t0 = 0; t0 < T; t0 += w.TC) {
+    const int rows = std::min(w.TC, T - t0);
+    {  // logits = h W^T
+      GemmArgs g{};
+      g.M = rows; g.N = V; g.nb1 = g.nb2 = 1; g.alpha = 1.f; g.causal = GEMM_FULL; g.half = kFtHalf ? 1 : 0;
+      g.nseg = 1;
+      g.seg[0] = GemmSeg{};
+      g.seg[0].A = w.h + (size_t)t0 * H; g.seg[0].B = w.w16; g.seg[0].K = H; g.seg[0].lda = H; g.seg[0].ldb = H;
+      g.Cf = w.logits; g.ldcf = Vp;
+      s = gemm_launch(g, 1, st);
+      if (s != HARLI_OK) return s;
+    }
+    hipLaunchKernelGGL(k_ce_row, dim3(rows), dim3(256), 0, st, w.logits, targets + t0, w.dlog, V, Vp, w.acc, c->dw.err_flag);
+    {  // dh = dlog W   (contraction over the padded vocabulary: pad columns are zero on both sides)
+      GemmArgs g{};
+      g.M = rows; g.N = H; g.nb1 = g.nb2 = 1; g.alpha = 1.f; g.causal = GEMM_FULL; g.half = kFtHalf ? 1 : 0;
+      g.nseg = 1;
+      g.seg[0] = GemmSeg{};
+      g.seg[0].A = w.dlog; g.seg[0].B = w.wT; g.seg[0].K = Vp; g.seg[0].lda = Vp; g.seg[0].ldb = Vp;
+      g.Cf = w.dh + (size_t)t0 * H; g.ldcf = H;
+      s = gemm_launch(g, 1, st);
+      if (s != HARLI_OK) return s;
+    }
+  }
+  hipLaunchKernelGGL(k_head_finish, dim3(1), dim3(1), 0, st, w.acc, loss);
+  ft_rmsnorm_bwd(w.dh, x, w.rho, c->g_final, nullptr, dx, T, H, nullptr, w.acc + 2, st);
+  HARLI_HIP(hipGetLastError());
+  return HARLI_OK;
+}
