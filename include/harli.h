@@ -237,7 +237,8 @@ harli_status harli_lora_fwd(harli_ctx* c, int32_t layer, const float* X, float* 
 
 /* dX = d loss / dX given dY = d loss / dY (device [B_f*S, hidden] fp32).
  * dA, dB: host arrays of 7 device pointers (q,k,v,o,gate,up,down; fp32, shapes
- * of A and B); the adapter gradients are ACCUMULATED into them.  Frozen weights
+ * of A and B); the adapter gradients are ACCUMULATED into them (read and written
+ * without atomics: nothing else may update them while the call runs).  Frozen weights
  * get no gradient.  Consumes `saved`: its pool memory is released with an event
  * recorded on `hip_stream` after the last kernel. */
 harli_status harli_lora_bwd(harli_ctx* c, int32_t layer, const float* dY, float* dX, harli_saved* saved,

@@ -11,10 +11,11 @@
 extern "C" {
 #endif
 
-/* C = alpha * (A1 . B1^T + A2 . B2^T) (+ res), the finetune unit's bf16 MFMA GEMM.
- * A1 [M, K1], B1 [N, K1], optional A2 [M, K2], B2 [N, K2] (K2 = 0: absent): device 16-bit
- * (half = 1: IEEE half, 0: bfloat16; the 16-bit outputs use the same type), row-major, contraction index contiguous.  Any of the outputs may be NULL: Cb bf16 [M, N],
- * Cf fp32 [M, N] (with optional fp32 residual res [M, N]), Ct bf16 [N, M].
+/* C = alpha * (A1 . B1^T + A2 . B2^T) (+ res), the finetune unit's 16-bit MFMA GEMM (fp32 accumulation).
+ * A1 [M, K1], B1 [N, K1], optional A2 [M, K2], B2 [N, K2] (K2 = 0: absent): device 16-bit elements, IEEE half when
+ * half = 1 and bfloat16 when half = 0, row-major, contraction index contiguous, K a multiple of 8.  Any of the
+ * outputs may be NULL: Cb 16-bit [M, N] (same element type as the inputs), Cf fp32 [M, N] (with optional fp32
+ * residual res [M, N]), Ct 16-bit [N, M].
  * causal: 0 full, 1 lower output tiles only, 2 upper output tiles only, 3 K loop up to the
  * tile's last row, 4 K loop from the tile's first row (see the kernel for the exact meaning). */
 harli_status harli_dbg_gemm(const void* A1, const void* B1, int32_t K1, const void* A2, const void* B2, int32_t K2,

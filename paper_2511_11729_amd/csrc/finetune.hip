@@ -6,8 +6,10 @@
 // segment [s x A | B^T] of the base GEMM.  Backward needs no weight gradients for the frozen
 // base: dx = dy W + (s dy B^T) A^T is again one multi-segment GEMM against a library-owned
 // transposed copy of W, and dA = x^T (s dy B^T), dB = (s x A)^T dy are skinny reductions over
-// the tokens.  Attention runs as batched GEMMs with causal tile skipping around element-wise
-// softmax / dS kernels.
+// the tokens (the adapters' contributions to dx ride on the backward GEMMs as further K
+// segments).  Attention is the fused forward / dQ / dK-dV kernels of ft_attention.hip for head
+// sizes 64 and 128; other head sizes run it as batched GEMMs with causal tile skipping around
+// element-wise softmax / dS kernels.
 #include <algorithm>
 #include <cmath>
 #include <vector>
