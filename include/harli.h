@@ -18,7 +18,9 @@
  *    in one process, each on its own stream); two decode steps, or two finetune
  *    calls, of the same context must not overlap.
  *  - Storage type: HARLI_BF16 (weights, KV cache and saved activations are
- *    bfloat16, accumulation is fp32) or HARLI_F32 (everything fp32).  Hidden
+ *    bfloat16, accumulation is fp32) or HARLI_F32 (weights, adapters and KV cache are
+ *    fp32; decode computes in fp32 throughout, the finetune unit rounds weights and
+ *    adapters to its 16-bit compute element and keeps fp32 accumulation).  Hidden
  *    states crossing the ABI (x, y, dY, dX), RMSNorm gains, logits and adapter
  *    gradients are always fp32.
  *  - Linear weights are [out, in] row-major (y = x W^T), no biases.  LoRA A is
@@ -252,7 +254,7 @@ harli_status harli_saved_bytes(const harli_ctx* c, int32_t B_f, int32_t S, size_
 /* ======================================================================== *
  * Output layer of the finetune task with next-token cross entropy (Sec. 2.1: "output layer" after the stack of
  * transformer layers; the loss of the workloads that carry a vocabulary).  Needs g_final and w_lm in the context
- * (bf16 storage) and harli_lora_attach.
+ * and harli_lora_attach.
  *   h = RMSNorm(x; g_final);  logits = h W_lm^T;
  *   loss = mean over the positions with targets[i] >= 0 of  -log softmax(logits[i])[targets[i]];
  *   dx = d loss / d x   (W_lm and g_final are frozen).
@@ -272,7 +274,8 @@ harli_status harli_head_fwd_bwd(harli_ctx* c, const float* x, const int32_t* tar
  *   master -= lr * ( (m / (1 - beta1^step)) / (sqrt(v / (1 - beta2^step)) + eps) + weight_decay * master )
  * master, m, v: device fp32 [n], updated in place (m, v start at zero).  grad: device fp32 [n] (the dA / dB that
  * harli_lora_bwd accumulated); cleared afterwards when zero_grad != 0.  param_bf16: device bfloat16 [n], rewritten
- * from master with round-to-nearest-even -- the A / B buffer given to harli_lora_attach -- or NULL.  step >= 1.
+ * from master with round-to-nearest-even -- the A / B buffer given to harli_lora_attach -- or NULL (with fp32
+ * storage the master itself can be the attached buffer).  step >= 1.
  * Asynchronous on the stream.  HARLI_ERR_INVALID for null pointers, step < 1 or betas outside [0, 1).
  * ======================================================================== */
 typedef struct {

@@ -165,8 +165,9 @@ void convert_adapters(harli_ctx* c, const LayerDev& L, bool transposed, hipStrea
     int out, in;
     proj_shape(c->cfg, t, &out, &in);
     const int r = c->lora.rank;
-    jobs.j[jobs.n++] = FtConvJob{static_cast<const bf*>(L.A[t]), transposed ? w.At[t] : w.An[t], in, r, transposed ? 1 : 0};
-    jobs.j[jobs.n++] = FtConvJob{static_cast<const bf*>(L.B[t]), transposed ? w.Bt[t] : w.Bn[t], r, out, transposed ? 1 : 0};
+    const int f32 = c->cfg.dtype == HARLI_F32 ? 1 : 0;
+    jobs.j[jobs.n++] = FtConvJob{L.A[t], transposed ? w.At[t] : w.An[t], in, r, transposed ? 1 : 0, f32};
+    jobs.j[jobs.n++] = FtConvJob{L.B[t], transposed ? w.Bt[t] : w.Bn[t], r, out, transposed ? 1 : 0, f32};
   }
   if (jobs.n) ft_convert_jobs(jobs, st);
 }
@@ -204,7 +205,6 @@ harli_status proj_grads(harli_ctx* c, const LayerDev& L, int t, int slot, const 
 
 harli_status check_call(harli_ctx* c, int layer, int Bf, int S, const char* who) {
   if (!c) return fail(HARLI_ERR_INVALID, "%s: null context", who);
-  if (c->cfg.dtype != HARLI_BF16) return fail(HARLI_ERR_INVALID, "%s: the finetune unit is built for bf16 storage", who);
   if (!c->lora_attached) return fail(HARLI_ERR_STATE, "%s: call harli_lora_attach first", who);
   if (layer < 0 || layer >= c->cfg.n_layers) return fail(HARLI_ERR_INVALID, "%s: layer %d out of range", who, layer);
   if (Bf < 1 || S < 1 || (long long)Bf * S > c->cfg.max_ft_tokens)
@@ -284,7 +284,6 @@ void free_finetune_state(harli_ctx* c) {
 
 extern "C" harli_status harli_lora_attach(harli_ctx* c, const harli_lora_cfg* cfg, void* const* A, void* const* B) {
   if (!c || !cfg || !A || !B) return fail(HARLI_ERR_INVALID, "lora_attach: null argument");
-  if (c->cfg.dtype != HARLI_BF16) return fail(HARLI_ERR_INVALID, "lora_attach: the finetune unit is built for bf16 storage");
   if (cfg->rank != 8 && cfg->rank != 16 && cfg->rank != 32 && cfg->rank != 64)
     return fail(HARLI_ERR_INVALID, "lora_attach: rank must be 8, 16, 32 or 64, got %d", cfg->rank);
   if (cfg->targets == 0 || cfg->targets >= (1u << kTargets)) return fail(HARLI_ERR_INVALID, "lora_attach: bad target mask");
@@ -305,9 +304,16 @@ extern "C" harli_status harli_lora_attach(harli_ctx* c, const harli_lora_cfg* cf
         int out, in;   // W [out, in] for the forward pass and WT [in, out] for dx = dy W
         proj_shape(c->cfg, t, &out, &in);
         HARLI_HIP(hipMalloc(&L.wt[t], (size_t)out * in * 2));
-        ft_transpose_from_bf16(static_cast<const bf*>(L.w[t]), static_cast<bf*>(L.wt[t]), out, in, nullptr);
         HARLI_HIP(hipMalloc(&L.w16[t], (size_t)out * in * 2));
-        ft_from_bf16(static_cast<const bf*>(L.w[t]), static_cast<bf*>(L.w16[t]), (long long)out * in, nullptr);
+        if (c->cfg.dtype == HARLI_BF16) {
+          ft_transpose_from_bf16(static_cast<const bf*>(L.w[t]), static_cast<bf*>(L.wt[t]), out, in, nullptr);
+          ft_from_bf16(static_cast<const bf*>(L.w[t]), static_cast<bf*>(L.w16[t]), (long long)out * in, nullptr);
+        } else {  // fp32 storage: rounded once to the compute element
+          FtConvJobs jobs{};
+          jobs.j[jobs.n++] = FtConvJob{L.w[t], static_cast<bf*>(L.wt[t]), out, in, 1, 1};
+          jobs.j[jobs.n++] = FtConvJob{L.w[t], static_cast<bf*>(L.w16[t]), out, in, 0, 1};
+          ft_convert_jobs(jobs, nullptr);
+        }
       }
     }
   }

@@ -29,12 +29,13 @@ void ft_make_scale(const float* x, long long n, float* scale, hipStream_t st);
 // bf16 storage -> compute element: plain copy and [R][C] -> [C][R] transpose
 void ft_from_bf16(const bf* in, bf* out, long long n, hipStream_t st);
 void ft_transpose_from_bf16(const bf* in, bf* out, int R, int C, hipStream_t st);
-// Several small bf16 -> compute-element conversions in one launch: src [R][C] -> dst [R][C], or dst [C][R] when
-// transpose is set (meant for adapter matrices: the strided side is not tuned)
+// Several storage -> compute-element conversions in one launch: src [R][C] (bf16, or fp32 when src_f32 is set) ->
+// dst [R][C], or dst [C][R] when transpose is set (meant for adapter matrices and one-time weight copies: the
+// strided side is not tuned)
 struct FtConvJob {
-  const bf* src;
+  const void* src;
   bf* dst;
-  int R, C, transpose;
+  int R, C, transpose, src_f32;
 };
 struct FtConvJobs {
   FtConvJob j[16];

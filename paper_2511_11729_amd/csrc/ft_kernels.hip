@@ -507,7 +507,7 @@ __global__ void __launch_bounds__(256) k_convert_jobs(FtConvJobs jobs) {
   const FtConvJob jb = jobs.j[blockIdx.y];
   const long long n = (long long)jb.R * jb.C;
   for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n; i += (long long)gridDim.x * 256) {
-    const unsigned short v = F2E(bf2f(jb.src[i]));
+    const unsigned short v = jb.src_f32 ? F2E(static_cast<const float*>(jb.src)[i]) : F2E(bf2f(static_cast<const bf*>(jb.src)[i]));
     if (jb.transpose) {
       const int r = (int)(i / jb.C), c = (int)(i - (long long)r * jb.C);
       jb.dst[(long long)c * jb.R + r] = v;

@@ -82,12 +82,13 @@ __global__ void k_head_finish(float* acc, float* loss) {
   *loss = acc[0] / n;
 }
 
-// [V][H] bf16 -> [H][Vp] compute element, zero in the pad columns
-__global__ void __launch_bounds__(256) k_head_wt(const bf* __restrict__ w, bf* __restrict__ wT, int V, int H, int Vp) {
+// [V][H] storage (bf16 or fp32) -> [H][Vp] compute element, zero in the pad columns
+__global__ void __launch_bounds__(256) k_head_wt(const void* __restrict__ w, int f32, bf* __restrict__ wT, int V, int H, int Vp) {
   const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
   if (i >= (long long)H * Vp) return;
   const int hh = (int)(i / Vp), v = (int)(i - (long long)hh * Vp);
-  wT[i] = v < V ? F2E(bf2f(w[(long long)v * H + hh])) : 0;
+  const long long src = (long long)v * H + hh;
+  wT[i] = v >= V ? 0 : F2E(f32 ? static_cast<const float*>(w)[src] : bf2f(static_cast<const bf*>(w)[src]));
 }
 
 HeadWs* ws_of(harli_ctx* c) { return static_cast<HeadWs*>(c->head_ws); }
@@ -100,9 +101,12 @@ harli_status ensure(harli_ctx* c, int T, hipStream_t st) {
   if (!w.weights_ready) {
     HARLI_HIP(hipMalloc(reinterpret_cast<void**>(&w.w16), (size_t)V * H * 2));
     HARLI_HIP(hipMalloc(reinterpret_cast<void**>(&w.wT), (size_t)H * Vp * 2));
-    ft_from_bf16(static_cast<const bf*>(c->w_lm), w.w16, (long long)V * H, st);
+    const int f32 = c->cfg.dtype == HARLI_F32 ? 1 : 0;
+    FtConvJobs jobs{};
+    jobs.j[jobs.n++] = FtConvJob{c->w_lm, w.w16, V, H, 0, f32};
+    ft_convert_jobs(jobs, st);
     const long long n = (long long)H * Vp;
-    hipLaunchKernelGGL(k_head_wt, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, static_cast<const bf*>(c->w_lm), w.wT, V, H, Vp);
+    hipLaunchKernelGGL(k_head_wt, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, c->w_lm, f32, w.wT, V, H, Vp);
     w.Vp = Vp;
     w.weights_ready = true;
   }
@@ -151,7 +155,6 @@ extern "C" harli_status harli_head_fwd_bwd(harli_ctx* c, const float* x, const i
                                            void* hip_stream) {
   using namespace harli;
   if (!c || !x || !targets || !loss || !dx) return fail(HARLI_ERR_INVALID, "head_fwd_bwd: null argument");
-  if (c->cfg.dtype != HARLI_BF16) return fail(HARLI_ERR_INVALID, "head_fwd_bwd: the finetune unit is built for bf16 storage");
   if (!c->lora_attached) return fail(HARLI_ERR_STATE, "head_fwd_bwd: call harli_lora_attach first");
   if (!c->w_lm || !c->g_final || c->cfg.vocab < 1) return fail(HARLI_ERR_STATE, "head_fwd_bwd: the context has no output layer (g_final, w_lm, vocab)");
   if (T < 1 || T > c->cfg.max_ft_tokens) return fail(HARLI_ERR_INVALID, "head_fwd_bwd: %d tokens outside 1..max_ft_tokens %d", T, c->cfg.max_ft_tokens);

@@ -196,7 +196,8 @@ class FinetuneCase:
         self.layer_dev["g1"], self.layer_dev["g2"] = f32_dev(self.W_np["g1"]), f32_dev(self.W_np["g2"])
         self.ctx = hb.Context(self.pool, n_layers=m.n_layers, hidden=m.hidden, n_q_heads=m.n_q, n_kv_heads=m.n_kv,
                               head_dim=m.head_dim, ffn=m.ffn, rms_eps=m.rms_eps, rope_base=m.rope_base,
-                              dtype=hb.HARLI_BF16, max_batch=1, max_seq_len=16, max_ft_tokens=T,
+                              dtype=hb.HARLI_BF16 if m.dtype == "bf16" else hb.HARLI_F32, max_batch=1, max_seq_len=16,
+                              max_ft_tokens=T,
                               layers=[self.layer_dev])
         self.A_dev = {p: to_dev(a, m.dtype) for p, (a, b) in self.lora_np.items()}
         self.B_dev = {p: to_dev(b, m.dtype) for p, (a, b) in self.lora_np.items()}

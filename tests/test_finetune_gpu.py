@@ -50,6 +50,14 @@ def test_config0_shapes_bf16():
     check(build(0))
 
 
+def test_config0_as_written_fp32_storage():
+    """Config 0 with its own storage type: fp32 weights and adapters at the ABI, rounded once to the unit's 16-bit
+    compute element (the oracle uses the fp32 values), same bar."""
+    w = wl.workload(0)
+    assert w.model.dtype == "f32"
+    check(FinetuneCase(w, w.model, w.lora, w.finetune), "config 0 fp32 storage")
+
+
 def test_all_seven_targets_and_ragged_sequence():
     w = wl.workload(0)
     check(build(0, lora=wl.LoraCfg(16, 32.0, wl.LORA_TARGETS), ft=wl.FinetuneCfg(3, 72)))
