@@ -45,7 +45,7 @@ inline size_t al(size_t n) { return (n + 255) & ~size_t(255); }
 struct FtWs {
   size_t bytes = 0;
   char* base = nullptr;
-  float *scores = nullptr, *dP = nullptr, *ST = nullptr, *dPT = nullptr, *delta = nullptr, *dm = nullptr, *dh2 = nullptr,
+  float *scores = nullptr, *dP = nullptr, *ST = nullptr, *dPT = nullptr, *delta = nullptr, *dh2 = nullptr,
         *dx1 = nullptr, *dh = nullptr, *gpart = nullptr;
   bf *vT = nullptr, *At[kTargets] = {}, *Bt[kTargets] = {}, *dyb = nullptr, *da = nullptr, *du = nullptr, *dx1b = nullptr, *dob = nullptr,
      *doT = nullptr, *dS = nullptr, *PT = nullptr, *dST = nullptr, *qT = nullptr, *kT = nullptr, *dq = nullptr, *dkq = nullptr,
@@ -96,7 +96,7 @@ harli_status ensure_ws(harli_ctx* c, int Bf, int S) {
   const size_t o_scores = take(ZSS * 4), o_dP = take(ZSS * 4), o_ST = take(ZSS * 4), o_dPT = take(ZSS * 4);
   const size_t o_dS = take(ZSS * 2), o_PT = take(ZSS * 2), o_dST = take(ZSS * 2);
   const size_t o_delta = take((size_t)D.Z * S * 4);
-  const size_t o_dm = take(T * D.F * 4), o_dh2 = take(T * D.H * 4), o_dx1 = take(T * D.H * 4), o_dh = take(T * D.H * 4);
+  const size_t o_dh2 = take(T * D.H * 4), o_dx1 = take(T * D.H * 4), o_dh = take(T * D.H * 4);
   const size_t o_vT = take(T * D.KVD * 2), o_kT = take(T * D.KVD * 2), o_qT = take(T * D.QD * 2), o_doT = take(T * D.QD * 2);
   const size_t ad = al(maxdim * D.r * 2);  // one adapter matrix in the compute element
   const size_t o_At = take(kTargets * ad), o_Bt = take(kTargets * ad);
@@ -115,7 +115,7 @@ harli_status ensure_ws(harli_ctx* c, int Bf, int S) {
   char* b = w.base;
   w.scores = (float*)(b + o_scores); w.dP = (float*)(b + o_dP); w.ST = (float*)(b + o_ST); w.dPT = (float*)(b + o_dPT);
   w.dS = (bf*)(b + o_dS); w.PT = (bf*)(b + o_PT); w.dST = (bf*)(b + o_dST); w.delta = (float*)(b + o_delta);
-  w.dm = (float*)(b + o_dm); w.dh2 = (float*)(b + o_dh2); w.dx1 = (float*)(b + o_dx1); w.dh = (float*)(b + o_dh);
+  w.dh2 = (float*)(b + o_dh2); w.dx1 = (float*)(b + o_dx1); w.dh = (float*)(b + o_dh);
   w.vT = (bf*)(b + o_vT); w.kT = (bf*)(b + o_kT); w.qT = (bf*)(b + o_qT); w.doT = (bf*)(b + o_doT);
   w.dyb = (bf*)(b + o_dyb); w.da = (bf*)(b + o_da); w.du = (bf*)(b + o_du);
   w.dx1b = (bf*)(b + o_dx1b); w.dob = (bf*)(b + o_dob); w.dq = (bf*)(b + o_dq); w.dkq = (bf*)(b + o_dkq);
@@ -454,12 +454,12 @@ extern "C" harli_status harli_lora_fwd(harli_ctx* c, int32_t layer, const float*
     g.Cb = sv->a; g.ldcb = D.F;
     RUN(proj_fwd(c, L, 4, sv->h2, T, sv, g, st));
   }
-  {
+  {  // u = up projection; its epilogue also writes m = silu(a) * u
     GemmArgs g = plain_gemm(T, D.F);
     g.Cb = sv->u; g.ldcb = D.F;
+    g.epi = GEMM_EPI_SILU_MUL; g.e0 = sv->a; g.o0 = sv->m; g.lde = D.F;
     RUN(proj_fwd(c, L, 5, sv->h2, T, sv, g, st));
   }
-  ft_silu_mul(sv->a, sv->u, sv->m, (long long)T * D.F, st);
   {  // Y = x1 + m Wd^T
     GemmArgs g = plain_gemm(T, D.H);
     g.Cf = Y; g.ldcf = D.H; g.res = sv->x1;
@@ -505,16 +505,16 @@ extern "C" harli_status harli_lora_bwd(harli_ctx* c, int32_t layer, const float*
   ft_make_scale(dY, (long long)T * D.H, w.scale, st);
   ft_f32_to_e(dY, w.dyb, (long long)T * D.H, w.scale, st);  // every gradient below carries the factor sigma
   {
-    GemmArgs g = plain_gemm(T, D.F);  // dm = dy Wd (+ gs A_d^T)
+    GemmArgs g = plain_gemm(T, D.F);  // dm = dy Wd (+ gs A_d^T) -> da, du
     add_seg(g, w.dyb, D.H, static_cast<const bf*>(L.wt[6]), D.H, D.H);
     if (adapted(c, 6)) {
       RUNB(proj_grads(c, L, 6, 0, w.dyb, sv->m, T, sv, dA, dB, st));
       add_seg(g, w.gs[0], D.r, w.An[6], D.r, D.r);
     }
-    g.Cf = w.dm; g.ldcf = D.F;
+    // the epilogue turns dm straight into da and du (SwiGLU backward); dm itself is never stored
+    g.epi = GEMM_EPI_SWIGLU_BWD; g.e0 = sv->a; g.e1 = sv->u; g.o0 = w.da; g.o1 = w.du; g.lde = D.F;
     RUNB(gemm_launch(g, 1, st));
   }
-  ft_swiglu_bwd(w.dm, sv->a, sv->u, w.da, w.du, (long long)T * D.F, st);
   {
     GemmArgs g = plain_gemm(T, D.H);  // dh2 = da Wg + du Wu
     add_seg(g, w.da, D.F, static_cast<const bf*>(L.wt[4]), D.F, D.F);

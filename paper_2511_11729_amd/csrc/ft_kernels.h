@@ -19,9 +19,6 @@ void ft_rmsnorm_bwd(const float* dh, const float* x, const float* rho, const flo
 void ft_rope(bf* t, int T, int S, int heads, int d, const double* inv_freq, bool inverse, hipStream_t st);
 // causal softmax of fp32 scores [Z][S][S] (already scaled) -> P bf16 (zeros above the diagonal), lse [Z][S] (natural log)
 void ft_softmax_causal(const float* sc, bf* P, float* lse, int Z, int S, hipStream_t st);
-void ft_silu_mul(const bf* a, const bf* u, bf* m, long long n, hipStream_t st);
-// da = dm*u*sig(a)*(1 + a(1-sig(a))), du = dm*a*sig(a);  dm fp32
-void ft_swiglu_bwd(const float* dm, const bf* a, const bf* u, bf* da, bf* du, long long n, hipStream_t st);
 // y = 16-bit(x * *scale)   (scale: optional device scalar)
 void ft_f32_to_e(const float* x, bf* y, long long n, const float* scale, hipStream_t st);
 // scale[0] = sigma = power of two bringing max|x| to 2^8, scale[1] = 1/sigma (scale[2] is scratch)

@@ -143,38 +143,6 @@ __global__ void __launch_bounds__(256) k_softmax_causal(const float* sc, bf* P, 
   if (lane == 0) lse[row] = mx + __logf(sum);
 }
 
-// ---------------------------------------------------------------- SwiGLU
-__global__ void __launch_bounds__(256) k_silu_mul(const bf* a, const bf* u, bf* m, long long n8) {
-  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
-  if (i >= n8) return;
-  const uint4 av = reinterpret_cast<const uint4*>(a)[i], uv = reinterpret_cast<const uint4*>(u)[i];
-  float af[8], uf[8], o[8];
-  UNPACK8(av, af);
-  UNPACK8(uv, uf);
-#pragma unroll
-  for (int e = 0; e < 8; ++e) o[e] = af[e] / (1.f + __expf(-af[e])) * uf[e];
-  reinterpret_cast<uint4*>(m)[i] = make_uint4(PACK2(o[0], o[1]), PACK2(o[2], o[3]), PACK2(o[4], o[5]), PACK2(o[6], o[7]));
-}
-
-__global__ void __launch_bounds__(256) k_swiglu_bwd(const float* dm, const bf* a, const bf* u, bf* da, bf* du, long long n8) {
-  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
-  if (i >= n8) return;
-  const uint4 av = reinterpret_cast<const uint4*>(a)[i], uv = reinterpret_cast<const uint4*>(u)[i];
-  const float4 d0 = reinterpret_cast<const float4*>(dm)[2 * i], d1 = reinterpret_cast<const float4*>(dm)[2 * i + 1];
-  const float d[8] = {d0.x, d0.y, d0.z, d0.w, d1.x, d1.y, d1.z, d1.w};
-  float af[8], uf[8], oa[8], ou[8];
-  UNPACK8(av, af);
-  UNPACK8(uv, uf);
-#pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    const float sg = 1.f / (1.f + __expf(-af[e]));
-    oa[e] = d[e] * uf[e] * sg * (1.f + af[e] * (1.f - sg));
-    ou[e] = d[e] * af[e] * sg;
-  }
-  reinterpret_cast<uint4*>(da)[i] = make_uint4(PACK2(oa[0], oa[1]), PACK2(oa[2], oa[3]), PACK2(oa[4], oa[5]), PACK2(oa[6], oa[7]));
-  reinterpret_cast<uint4*>(du)[i] = make_uint4(PACK2(ou[0], ou[1]), PACK2(ou[2], ou[3]), PACK2(ou[4], ou[5]), PACK2(ou[6], ou[7]));
-}
-
 // ---------------------------------------------------------------- transposes (64 x 64 tiles through LDS)
 template <bool FROM_BF16>
 __global__ void __launch_bounds__(256) k_transpose(const bf* in, bf* out, int R, int C, long long ldi, long long bsi,
@@ -534,12 +502,6 @@ void ft_rope(bf* t, int T, int S, int heads, int d, const double* inv_freq, bool
 void ft_softmax_causal(const float* sc, bf* P, float* lse, int Z, int S, hipStream_t st) {
   const long long rows = (long long)Z * S;
   hipLaunchKernelGGL(k_softmax_causal, dim3(nblk(rows, 4)), dim3(256), 0, st, sc, P, lse, S, rows);
-}
-void ft_silu_mul(const bf* a, const bf* u, bf* m, long long n, hipStream_t st) {
-  hipLaunchKernelGGL(k_silu_mul, dim3(nblk(n / 8, 256)), dim3(256), 0, st, a, u, m, n / 8);
-}
-void ft_swiglu_bwd(const float* dm, const bf* a, const bf* u, bf* da, bf* du, long long n, hipStream_t st) {
-  hipLaunchKernelGGL(k_swiglu_bwd, dim3(nblk(n / 8, 256)), dim3(256), 0, st, dm, a, u, da, du, n / 8);
 }
 void ft_f32_to_e(const float* x, bf* y, long long n, const float* scale, hipStream_t st) {
   hipLaunchKernelGGL(k_f32_to_e_scaled, dim3(nblk(n / 4, 256)), dim3(256), 0, st, x, y, n / 4, scale);

@@ -43,7 +43,16 @@ struct GemmArgs {
   long long ldcf, cf_bs0, cf_bs1, cf_bs2;
   unsigned short* Ct;
   long long ldct, ct_bs0, ct_bs1, ct_bs2;
+  // fused SwiGLU epilogues (not batched; N and lde multiples of 8, 16-byte aligned pointers, row stride lde):
+  //   GEMM_EPI_SILU_MUL   C = the up projection u:  Cb = u (16-bit), o0 = silu(e0) * u   with e0 = the gate output a
+  //   GEMM_EPI_SWIGLU_BWD C = dm:  o0 = da = dm * u * sig(a) * (1 + a (1 - sig(a))),  o1 = du = dm * a * sig(a),
+  //                       e0 = a, e1 = u; no other output is written
+  int epi;
+  const unsigned short *e0, *e1;
+  unsigned short *o0, *o1;
+  long long lde;
 };
+enum GemmEpi { GEMM_EPI_NONE = 0, GEMM_EPI_SILU_MUL = 1, GEMM_EPI_SWIGLU_BWD = 2 };
 
 // Launches on `st`; batches = grid.z.  Shapes are validated (K % 8, pointers, strides % 8).
 harli_status gemm_launch(const GemmArgs& a, int batches, hipStream_t st);

@@ -35,7 +35,7 @@ __device__ __forceinline__ void seg_range(const GemmArgs& a, int s, int m0, int*
 // One workgroup of 8 waves per CU, two waves per SIMD (256 registers each): while one wave of a SIMD waits on its
 // staging loads, LDS writes or the barrier, the other one issues MFMAs.  (Four waves with twice the tile each and
 // the whole register file were 27 % slower: nothing covered those waits.)
-template <bool HALF>
+template <bool HALF, int EPI>
 __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) k_gemm(GemmArgs a, int tiles_n, int tiles_total, int chunk, int GM, int GN, const uint4* zero16) {
   extern __shared__ __align__(16) char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -216,7 +216,7 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
                    (reinterpret_cast<uintptr_t>(Cb) & 7) == 0;
   // whole rows of eight 16-bit columns: N and the row stride multiples of 8, 16-byte aligned base
   const bool vok8 = ((a.ldcb | a.N) & 7) == 0 && (reinterpret_cast<uintptr_t>(Cb) & 15) == 0;
-  if (Cf || Cb) {
+  if (Cf || Cb || EPI != GEMM_EPI_NONE) {
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
 #pragma unroll
@@ -225,7 +225,7 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
         for (int v = 0; v < 16; ++v)
           *reinterpret_cast<float*>(ebuf + (8 * (v >> 2) + rgrp + (v & 3)) * ER + (j * 32 + col_l) * 4) = acc[i][j][v] * a.alpha;
       __builtin_amdgcn_wave_barrier();
-      if (!Cf && vok8) {  // 16-bit output only: eight columns (16 bytes) per lane, eight rows per pass
+      if (EPI != GEMM_EPI_NONE || (!Cf && vok8)) {  // 16-bit outputs only: eight columns (16 bytes) per lane, eight rows per pass
         const int c8 = (lane & 7) * 8, n8 = n0 + wn * 64 + c8;
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
@@ -233,10 +233,40 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
           const int m = m0 + wm * 64 + i * 32 + row;
           const float4 lo = *reinterpret_cast<const float4*>(ebuf + row * ER + c8 * 4);
           const float4 hi = *reinterpret_cast<const float4*>(ebuf + row * ER + c8 * 4 + 16);
-          if (m < a.M && n8 < a.N)
-            *reinterpret_cast<uint4*>(Cb + (long long)m * a.ldcb + n8) =
-                HALF ? make_uint4(pack_h2(lo.x, lo.y), pack_h2(lo.z, lo.w), pack_h2(hi.x, hi.y), pack_h2(hi.z, hi.w))
-                     : make_uint4(pack_bf2(lo.x, lo.y), pack_bf2(lo.z, lo.w), pack_bf2(hi.x, hi.y), pack_bf2(hi.z, hi.w));
+          if (m >= a.M || n8 >= a.N) continue;
+          float x[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+          auto pack = [](const float* v) {
+            return HALF ? make_uint4(pack_h2(v[0], v[1]), pack_h2(v[2], v[3]), pack_h2(v[4], v[5]), pack_h2(v[6], v[7]))
+                        : make_uint4(pack_bf2(v[0], v[1]), pack_bf2(v[2], v[3]), pack_bf2(v[4], v[5]), pack_bf2(v[6], v[7]));
+          };
+          auto unpack = [](const uint4& w, float* v) {
+            if (HALF) unpack8h(w, v);
+            else unpack8(w, v);
+          };
+          if (EPI == GEMM_EPI_SILU_MUL) {
+            float av[8], uv[8], mv[8];
+            unpack(*reinterpret_cast<const uint4*>(a.e0 + (long long)m * a.lde + n8), av);
+            const uint4 up = pack(x);
+            unpack(up, uv);  // the rounded u, as the backward pass will read it
+#pragma unroll
+            for (int e = 0; e < 8; ++e) mv[e] = av[e] / (1.f + __expf(-av[e])) * uv[e];
+            *reinterpret_cast<uint4*>(Cb + (long long)m * a.ldcb + n8) = up;
+            *reinterpret_cast<uint4*>(a.o0 + (long long)m * a.lde + n8) = pack(mv);
+          } else if (EPI == GEMM_EPI_SWIGLU_BWD) {
+            float av[8], uv[8], oa[8], ou[8];
+            unpack(*reinterpret_cast<const uint4*>(a.e0 + (long long)m * a.lde + n8), av);
+            unpack(*reinterpret_cast<const uint4*>(a.e1 + (long long)m * a.lde + n8), uv);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+              const float sg = 1.f / (1.f + __expf(-av[e]));
+              oa[e] = x[e] * uv[e] * sg * (1.f + av[e] * (1.f - sg));
+              ou[e] = x[e] * av[e] * sg;
+            }
+            *reinterpret_cast<uint4*>(a.o0 + (long long)m * a.lde + n8) = pack(oa);
+            *reinterpret_cast<uint4*>(a.o1 + (long long)m * a.lde + n8) = pack(ou);
+          } else {
+            *reinterpret_cast<uint4*>(Cb + (long long)m * a.ldcb + n8) = pack(x);
+          }
         }
         __builtin_amdgcn_wave_barrier();
         continue;
@@ -360,15 +390,25 @@ harli_status gemm_launch(const GemmArgs& a, int batches, hipStream_t st) {
       return fail(HARLI_ERR_INVALID, "gemm: segment %d needs K %% 8 == 0 and 16-byte aligned rows (K %d lda %lld ldb %lld)", s,
                   g.K, g.lda, g.ldb);
   }
-  if (!a.Cb && !a.Cf && !a.Ct) return fail(HARLI_ERR_INVALID, "gemm: no output");
+  if (a.epi == GEMM_EPI_NONE && !a.Cb && !a.Cf && !a.Ct) return fail(HARLI_ERR_INVALID, "gemm: no output");
+  if (a.epi != GEMM_EPI_NONE) {
+    const bool silu = a.epi == GEMM_EPI_SILU_MUL;
+    if ((a.epi != GEMM_EPI_SILU_MUL && a.epi != GEMM_EPI_SWIGLU_BWD) || batches != 1 || a.Cf || a.Ct || a.res || (a.N & 7) || (a.lde & 7) ||
+        !a.e0 || !a.o0 || (silu ? (!a.Cb || (a.ldcb & 7) || ((uintptr_t)a.Cb & 15)) : (!a.e1 || !a.o1 || a.Cb)) ||
+        (((uintptr_t)a.e0 | (uintptr_t)a.e1 | (uintptr_t)a.o0 | (uintptr_t)a.o1) & 15))
+      return fail(HARLI_ERR_INVALID, "gemm: fused SwiGLU epilogue %d needs N, lde %% 8 == 0, aligned operands and its own outputs only", a.epi);
+  }
   if (a.res && !a.Cf) return fail(HARLI_ERR_INVALID, "gemm: a residual needs the fp32 output");
   static bool attr_set = false;
   static uint4* zero16 = nullptr;  // 256 zero bytes in device memory, kept for the life of the process
   if (!attr_set) {
     HARLI_HIP(hipMalloc(reinterpret_cast<void**>(&zero16), 256));
     HARLI_HIP(hipMemset(zero16, 0, 256));
-    HARLI_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<true>), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES));
-    HARLI_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<false>), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES));
+#define HARLI_GEMM_ATTR(H_, E_) \
+  HARLI_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<H_, E_>), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES))
+    HARLI_GEMM_ATTR(true, GEMM_EPI_NONE); HARLI_GEMM_ATTR(true, GEMM_EPI_SILU_MUL); HARLI_GEMM_ATTR(true, GEMM_EPI_SWIGLU_BWD);
+    HARLI_GEMM_ATTR(false, GEMM_EPI_NONE); HARLI_GEMM_ATTR(false, GEMM_EPI_SILU_MUL); HARLI_GEMM_ATTR(false, GEMM_EPI_SWIGLU_BWD);
+#undef HARLI_GEMM_ATTR
     attr_set = true;
   }
   const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
@@ -382,10 +422,18 @@ harli_status gemm_launch(const GemmArgs& a, int batches, hipStream_t st) {
     rec.flops = gemm_flops(a, batches);
     HARLI_HIP(hipEventRecord(rec.e0, st));
   }
-  if (a.half)
-    hipLaunchKernelGGL(k_gemm<true>, dim3(chunk * 8, 1, batches), dim3(NT), LDS_BYTES, st, a, tiles_n, total, chunk, GM, GN, zero16);
-  else
-    hipLaunchKernelGGL(k_gemm<false>, dim3(chunk * 8, 1, batches), dim3(NT), LDS_BYTES, st, a, tiles_n, total, chunk, GM, GN, zero16);
+#define HARLI_GEMM_LAUNCH(H_, E_) \
+  hipLaunchKernelGGL((k_gemm<H_, E_>), dim3(chunk * 8, 1, batches), dim3(NT), LDS_BYTES, st, a, tiles_n, total, chunk, GM, GN, zero16)
+  if (a.half) {
+    if (a.epi == GEMM_EPI_SILU_MUL) HARLI_GEMM_LAUNCH(true, GEMM_EPI_SILU_MUL);
+    else if (a.epi == GEMM_EPI_SWIGLU_BWD) HARLI_GEMM_LAUNCH(true, GEMM_EPI_SWIGLU_BWD);
+    else HARLI_GEMM_LAUNCH(true, GEMM_EPI_NONE);
+  } else {
+    if (a.epi == GEMM_EPI_SILU_MUL) HARLI_GEMM_LAUNCH(false, GEMM_EPI_SILU_MUL);
+    else if (a.epi == GEMM_EPI_SWIGLU_BWD) HARLI_GEMM_LAUNCH(false, GEMM_EPI_SWIGLU_BWD);
+    else HARLI_GEMM_LAUNCH(false, GEMM_EPI_NONE);
+  }
+#undef HARLI_GEMM_LAUNCH
   if (g_prof_on) {
     HARLI_HIP(hipEventRecord(rec.e1, st));
     g_prof.push_back(rec);
