@@ -527,9 +527,8 @@ extern "C" harli_status harli_lora_bwd(harli_ctx* c, int32_t layer, const float*
     g.Cf = w.dh2; g.ldcf = D.H;
     RUNB(gemm_launch(g, 1, st));
   }
-  ft_rmsnorm_bwd(w.dh2, sv->x1, sv->rho2, L.g2, dY, w.dx1, T, D.H, w.scale, nullptr, st);
+  ft_rmsnorm_bwd(w.dh2, sv->x1, sv->rho2, L.g2, dY, w.dx1, w.dx1b, T, D.H, w.scale, nullptr, st);
   // ---- attention output projection ----
-  ft_f32_to_e(w.dx1, w.dx1b, (long long)T * D.H, nullptr, st);
   {
     GemmArgs g = plain_gemm(T, D.QD);  // do = dx1 Wo
     add_seg(g, w.dx1b, D.H, static_cast<const bf*>(L.wt[3]), D.H, D.H);
@@ -541,7 +540,7 @@ extern "C" harli_status harli_lora_bwd(harli_ctx* c, int32_t layer, const float*
     RUNB(gemm_launch(g, 1, st));
   }
   // ---- attention ----
-  ft_attn_delta(w.dob, sv->o, w.delta, B_f, S, D.nq, D.d, st);
+  if (!ft_attn_supported(D.d)) ft_attn_delta(w.dob, sv->o, w.delta, B_f, S, D.nq, D.d, st);  // the fused dQ kernel makes its own
   auto qlike = [&](GemmSeg& sg, bool is_a) {  // operand laid out like q: [T, n_q*d], batch (b, c, g)
     (is_a ? sg.a_bs0 : sg.b_bs0) = (long long)S * D.QD;
     (is_a ? sg.a_bs1 : sg.b_bs1) = (long long)D.G * D.d;
@@ -570,8 +569,8 @@ extern "C" harli_status harli_lora_bwd(harli_ctx* c, int32_t layer, const float*
   ft_transpose_heads(sv->q, w.qT, B_f, S, D.nq, D.d, st);
   ft_transpose_heads(sv->k, w.kT, B_f, S, D.nkv, D.d, st);
   if (ft_attn_supported(D.d)) {
-    RUNB(ft_attn_bwd(sv->q, sv->k, sv->v, w.qT, w.kT, w.dob, w.doT, sv->lse, w.delta, w.dq, w.dkq, w.dvq, B_f, S, D.nq, D.nkv,
-                     D.d, st));
+    RUNB(ft_attn_bwd(sv->q, sv->k, sv->v, sv->o, w.qT, w.kT, w.dob, w.doT, sv->lse, w.delta, w.dq, w.dkq, w.dvq, B_f, S, D.nq,
+                     D.nkv, D.d, st));
   } else {
     {  // dP = dO V^T (lower)
       GemmArgs g = plain_gemm(S, S);
@@ -649,7 +648,7 @@ extern "C" harli_status harli_lora_bwd(harli_ctx* c, int32_t layer, const float*
     g.Cf = w.dh; g.ldcf = D.H;
     RUNB(gemm_launch(g, 1, st));
   }
-  ft_rmsnorm_bwd(w.dh, sv->X, sv->rho1, L.g1, w.dx1, dX, T, D.H, nullptr, w.scale + 1, st);
+  ft_rmsnorm_bwd(w.dh, sv->X, sv->rho1, L.g1, w.dx1, dX, nullptr, T, D.H, nullptr, w.scale + 1, st);
   HARLI_HIP(hipGetLastError());
   release_saved(c, sv, st, true);
   return HARLI_OK;

@@ -16,10 +16,11 @@ inline bool ft_attn_supported(int d) { return d == 64 || d == 128; }
 harli_status ft_attn_fwd(const bf* q, const bf* k, const bf* vT, bf* o, float* lse, int Bf, int S, int n_q, int n_kv, int d,
                          hipStream_t st);
 
-// Given dO and delta[z][s] = sum_e dO[s][e] o[s][e]:
+// Given dO and the forward output o:  delta[z][s] = sum_e dO[s][e] o[s][e] (written to `delta`, a workspace of
+// Bf*n_q*S floats),
 //   dq  = dS k / sqrt(d),  dkq = dS^T q / sqrt(d),  dvq = P^T dO   with P = exp(score - lse), dS = P (dP - delta),
 //   dP = dO v^T.  dkq and dvq are per QUERY head ([Bf*S, n_q*d]); the caller sums them over the heads of a group.
-harli_status ft_attn_bwd(const bf* q, const bf* k, const bf* v, const bf* qT, const bf* kT, const bf* dO, const bf* dOT,
-                         const float* lse, const float* delta, bf* dq, bf* dkq, bf* dvq, int Bf, int S, int n_q, int n_kv,
-                         int d, hipStream_t st);
+harli_status ft_attn_bwd(const bf* q, const bf* k, const bf* v, const bf* o, const bf* qT, const bf* kT, const bf* dO,
+                         const bf* dOT, const float* lse, float* delta, bf* dq, bf* dkq, bf* dvq, int Bf, int S, int n_q,
+                         int n_kv, int d, hipStream_t st);
 }  // namespace harli

@@ -172,12 +172,13 @@ __global__ void __launch_bounds__(256, 2) k_attn_fwd(const bf* __restrict__ q, c
 
 // -------------------------------------------------------------------------------------------- backward: dQ
 // grid (ceil(S/128), Bf*n_q); same ownership as the forward kernel.  dQ^T[e][q] += K^T[e][k] dS^T[k][q].
+// Also computes delta[q] = sum_e dO[q][e] O[q][e] and stores it.
 template <int D>
 __global__ void __launch_bounds__(256, 2) k_attn_bwd_dq(const bf* __restrict__ q, const bf* __restrict__ k, const bf* __restrict__ v,
                                                      const bf* __restrict__ kT, const bf* __restrict__ dO,
-                                                     const float* __restrict__ lse, const float* __restrict__ delta,
-                                                     bf* __restrict__ dq, int S, int nq, int nkv, float scale,
-                                                     float scale_log2) {
+                                                     const bf* __restrict__ o, const float* __restrict__ lse,
+                                                     float* __restrict__ delta, bf* __restrict__ dq, int S, int nq, int nkv,
+                                                     float scale, float scale_log2) {
   constexpr int RS = D * 2 + 16, NJ = D / 16, NE = D / 32, CPT = D / 32;
   extern __shared__ __align__(16) char smem[];
   char* sK = smem;                  // [KB][D]
@@ -198,7 +199,24 @@ __global__ void __launch_bounds__(256, 2) k_attn_bwd_dq(const bf* __restrict__ q
       Gf[j] = *reinterpret_cast<const u32x4*>(dO + ro + 16 * j);
     }
   }
-  const float lse2 = lse[(long long)z * S + qc] * kLog2e, dl = delta[(long long)z * S + qc];
+  const float lse2 = lse[(long long)z * S + qc] * kLog2e;
+  // delta = rowsum(dO * O) of this lane's query: the lane holds half of the row's dO (8 of every 16 elements), its
+  // partner lane the other half.  Stored for the dK / dV kernel, which runs after this one.
+  float dl = 0.f;
+  {
+    const bf* op = o + ((long long)b * S + qc) * QD + head * D + 8 * h;
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      const u32x4 ov = *reinterpret_cast<const u32x4*>(op + 16 * j);
+      float gf[8], of[8];
+      UNPACK8(uint4{Gf[j].x, Gf[j].y, Gf[j].z, Gf[j].w}, gf);
+      UNPACK8(uint4{ov.x, ov.y, ov.z, ov.w}, of);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) dl += gf[e] * of[e];
+    }
+    dl += __shfl_xor(dl, 32, 64);
+    if (h == 0 && qrow < S) delta[(long long)z * S + qrow] = dl;
+  }
   f32x16 dQ[NE];
 #pragma unroll
   for (int e = 0; e < NE; ++e) dQ[e] = zero16f();
@@ -439,23 +457,23 @@ harli_status ft_attn_fwd(const bf* q, const bf* k, const bf* vT, bf* o, float* l
   return HARLI_OK;
 }
 
-harli_status ft_attn_bwd(const bf* q, const bf* k, const bf* v, const bf* qT, const bf* kT, const bf* dO, const bf* dOT,
-                         const float* lse, const float* delta, bf* dq, bf* dkq, bf* dvq, int Bf, int S, int n_q, int n_kv,
-                         int d, hipStream_t st) {
+harli_status ft_attn_bwd(const bf* q, const bf* k, const bf* v, const bf* o, const bf* qT, const bf* kT, const bf* dO,
+                         const bf* dOT, const float* lse, float* delta, bf* dq, bf* dkq, bf* dvq, int Bf, int S, int n_q,
+                         int n_kv, int d, hipStream_t st) {
   harli_status s = check_shape(Bf, S, n_q, n_kv, d);
   if (s != HARLI_OK) return s;
   const dim3 grid((S + 127) / 128, Bf * n_q), blk(256);
   const float sc = 1.f / sqrtf((float)d), sl2 = kLog2e * sc;
   if (d == 128) {
     if ((s = set_attrs<128>()) != HARLI_OK) return s;
+    hipLaunchKernelGGL(k_attn_bwd_dq<128>, grid, blk, dq_lds<128>(), st, q, k, v, kT, dO, o, lse, delta, dq, S, n_q, n_kv, sc, sl2);
     hipLaunchKernelGGL(k_attn_bwd_dkv<128>, grid, blk, dkv_lds<128>(), st, q, k, v, qT, dO, dOT, lse, delta, dkq, dvq, S, n_q,
                        n_kv, sc, sl2);
-    hipLaunchKernelGGL(k_attn_bwd_dq<128>, grid, blk, dq_lds<128>(), st, q, k, v, kT, dO, lse, delta, dq, S, n_q, n_kv, sc, sl2);
   } else {
     if ((s = set_attrs<64>()) != HARLI_OK) return s;
+    hipLaunchKernelGGL(k_attn_bwd_dq<64>, grid, blk, dq_lds<64>(), st, q, k, v, kT, dO, o, lse, delta, dq, S, n_q, n_kv, sc, sl2);
     hipLaunchKernelGGL(k_attn_bwd_dkv<64>, grid, blk, dkv_lds<64>(), st, q, k, v, qT, dO, dOT, lse, delta, dkq, dvq, S, n_q,
                        n_kv, sc, sl2);
-    hipLaunchKernelGGL(k_attn_bwd_dq<64>, grid, blk, dq_lds<64>(), st, q, k, v, kT, dO, lse, delta, dq, S, n_q, n_kv, sc, sl2);
   }
   return HARLI_OK;
 }

@@ -13,8 +13,9 @@ typedef unsigned short bf;
 void ft_rmsnorm_fwd(const float* x, const float* g, bf* h, float* rho, int T, int H, float eps, hipStream_t st);
 // dx = dres + rho * (dh*g - xhat * mean(dh*g*xhat)), xhat = x*rho;  dh is fp32
 // res_mul / out_mul: optional device scalars: dx = out_mul * (dres * res_mul + ...); dres may be NULL (taken as zero)
-void ft_rmsnorm_bwd(const float* dh, const float* x, const float* rho, const float* g, const float* dres, float* dx, int T,
-                    int H, const float* res_mul, const float* out_mul, hipStream_t st);
+// dx16: optional 16-bit copy of dx (the next GEMM's operand)
+void ft_rmsnorm_bwd(const float* dh, const float* x, const float* rho, const float* g, const float* dres, float* dx, bf* dx16,
+                    int T, int H, const float* res_mul, const float* out_mul, hipStream_t st);
 // rotary embedding in place on [T, heads*d] bf16, position = t % S; inverse rotates by the negative angle
 void ft_rope(bf* t, int T, int S, int heads, int d, const double* inv_freq, bool inverse, hipStream_t st);
 // causal softmax of fp32 scores [Z][S][S] (already scaled) -> P bf16 (zeros above the diagonal), lse [Z][S] (natural log)

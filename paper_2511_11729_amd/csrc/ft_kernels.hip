@@ -42,7 +42,7 @@ __global__ void __launch_bounds__(256) k_rmsnorm_fwd(const float* x, const float
 }
 
 __global__ void __launch_bounds__(256) k_rmsnorm_bwd(const float* dh, const float* x, const float* rho, const float* g,
-                                                     const float* dres, float* dx, int H, const float* res_mul,
+                                                     const float* dres, float* dx, bf* dx16, int H, const float* res_mul,
                                                      const float* out_mul) {
   __shared__ float sh[4];
   const int t = blockIdx.x, tid = threadIdx.x;
@@ -70,6 +70,7 @@ __global__ void __launch_bounds__(256) k_rmsnorm_bwd(const float* dh, const floa
     o.z = om * (rs.z * rm + r * (d.z * gg.z - v.z * c));
     o.w = om * (rs.w * rm + r * (d.w * gg.w - v.w * c));
     *reinterpret_cast<float4*>(dx + (size_t)t * H + k) = o;
+    if (dx16) *reinterpret_cast<uint2*>(dx16 + (size_t)t * H + k) = make_uint2(PACK2(o.x, o.y), PACK2(o.z, o.w));
   }
 }
 
@@ -492,9 +493,9 @@ inline unsigned nblk(long long n, int per) { return (unsigned)((n + per - 1) / p
 void ft_rmsnorm_fwd(const float* x, const float* g, bf* h, float* rho, int T, int H, float eps, hipStream_t st) {
   hipLaunchKernelGGL(k_rmsnorm_fwd, dim3(T), dim3(256), 0, st, x, g, h, rho, H, eps);
 }
-void ft_rmsnorm_bwd(const float* dh, const float* x, const float* rho, const float* g, const float* dres, float* dx, int T,
-                    int H, const float* res_mul, const float* out_mul, hipStream_t st) {
-  hipLaunchKernelGGL(k_rmsnorm_bwd, dim3(T), dim3(256), 0, st, dh, x, rho, g, dres, dx, H, res_mul, out_mul);
+void ft_rmsnorm_bwd(const float* dh, const float* x, const float* rho, const float* g, const float* dres, float* dx, bf* dx16,
+                    int T, int H, const float* res_mul, const float* out_mul, hipStream_t st) {
+  hipLaunchKernelGGL(k_rmsnorm_bwd, dim3(T), dim3(256), 0, st, dh, x, rho, g, dres, dx, dx16, H, res_mul, out_mul);
 }
 void ft_rope(bf* t, int T, int S, int heads, int d, const double* inv_freq, bool inverse, hipStream_t st) {
   hipLaunchKernelGGL(k_rope, dim3(T), dim3(256), 0, st, t, S, heads, d, inv_freq, inverse ? -1.f : 1.f);

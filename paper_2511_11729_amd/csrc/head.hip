@@ -191,7 +191,7 @@ extern "C" harli_status harli_head_fwd_bwd(harli_ctx* c, const float* x, const i
     }
   }
   hipLaunchKernelGGL(k_head_finish, dim3(1), dim3(1), 0, st, w.acc, loss);
-  ft_rmsnorm_bwd(w.dh, x, w.rho, c->g_final, nullptr, dx, T, H, nullptr, w.acc + 2, st);
+  ft_rmsnorm_bwd(w.dh, x, w.rho, c->g_final, nullptr, dx, nullptr, T, H, nullptr, w.acc + 2, st);
   HARLI_HIP(hipGetLastError());
   return HARLI_OK;
 }
