@@ -39,8 +39,8 @@ PEAK_MFMA_TFLOPS = 2500.0         # MI355X dense fp16/bf16
 PEAK_HBM_GBS = 8000.0
 # HBM traffic per launch / per step from the rocprofv3 FETCH_SIZE and WRITE_SIZE counter runs summarised in
 # profiles/bench_config1_hbm_traffic.md (each scaled by what the same counter reads for a 256 MiB device copy)
-TRAFFIC_GEMM_BYTES_PER_LAUNCH = 377.1e6      # k_gemm, average over the 11 launches of a finetune unit
-TRAFFIC_DECODE_BYTES_PER_STEP = 559.5e6      # all kernels of one decode step
+TRAFFIC_GEMM_BYTES_PER_LAUNCH = 393.4e6      # k_gemm (all epilogue variants), average over the 11 launches of a finetune unit
+TRAFFIC_DECODE_BYTES_PER_STEP = 559.6e6      # all kernels of one decode step
 
 
 def log(*a):
