@@ -22,6 +22,15 @@ harli_status harli_dbg_gemm(const void* A1, const void* B1, int32_t K1, const vo
                             int32_t M, int32_t N, float alpha, int32_t causal, int32_t half, void* Cb, float* Cf,
                             const float* res, void* Ct, void* hip_stream);
 
+/* At which clock does the chip run the MFMA GEMM?  Launches Cb[M, N] = A[M, K] . B[N, K]^T (all device, 16-bit, as for
+ * harli_dbg_gemm) once to warm up and then `reps` times back to back, and writes to host pointers the achieved
+ * TFLOP/s (2*M*N*K per launch over HIP-event time) and the shader clock in MHz that workgroup 0 of the last launch
+ * saw inside its K loop (shader-clock cycles over ticks of the constant 100 MHz counter).  Under this kernel the
+ * clock settles well below the nominal 2.4 GHz, which bounds what fraction of the nominal MFMA peak can be reached.
+ * Allocates 16 bytes for the duration of the call and synchronises the stream. */
+harli_status harli_dbg_gemm_clock(const void* A, const void* B, int32_t M, int32_t N, int32_t K, int32_t half, void* Cb,
+                                  int32_t reps, double* tflops, double* shader_mhz, void* hip_stream);
+
 /* Kernel timing for the benchmark.  While enabled, every launch of the finetune unit's MFMA GEMM
  * is bracketed by two HIP events on the stream it is launched on.  harli_prof_collect waits for
  * them (it SYNCHRONISES on those events), returns the summed algorithmic flops (2*M*N*K per

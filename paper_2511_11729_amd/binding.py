@@ -122,6 +122,8 @@ _SIGS = {
     "harli_cu_stream_create": (C.c_int, [C.c_int32, C.c_int32, C.POINTER(C.c_void_p)]),
     "harli_cu_stream_destroy": (C.c_int, [C.c_void_p]),
     "harli_dbg_read_bandwidth": (C.c_int, [C.c_void_p, C.c_size_t, C.c_int32, C.POINTER(C.c_double), C.c_void_p]),
+    "harli_dbg_gemm_clock": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_int32,
+                                       C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_void_p]),
     "harli_dbg_gemm": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
                                  C.c_float, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
 }
@@ -406,6 +408,15 @@ def dbg_gemm(A1, B1, *, A2=None, B2=None, alpha=1.0, causal=0, half=False, Cb=No
     K2 = A2.shape[1] if A2 is not None else 0
     _check(lib().harli_dbg_gemm(_ptr(A1), _ptr(B1), K1, _ptr(A2), _ptr(B2), K2, M, N, alpha, causal, int(half), _ptr(Cb), _ptr(Cf),
                                 _ptr(res), _ptr(Ct), _stream(stream)))
+
+
+def dbg_gemm_clock(A, B, Cb, *, half=True, reps=20, stream=None):
+    """(TFLOP/s, shader MHz) of the MFMA GEMM Cb = A . B^T run `reps` times back to back."""
+    M, K = A.shape
+    N = B.shape[0]
+    t, f = C.c_double(0.0), C.c_double(0.0)
+    _check(lib().harli_dbg_gemm_clock(_ptr(A), _ptr(B), M, N, K, int(half), _ptr(Cb), reps, C.byref(t), C.byref(f), _stream(stream)))
+    return t.value, f.value
 
 
 def dbg_read_bandwidth(buf, mode: int, stream=None) -> float:

@@ -51,6 +51,9 @@ struct GemmArgs {
   const unsigned short *e0, *e1;
   unsigned short *o0, *o1;
   long long lde;
+  // Clock probe (null: off).  Workgroup 0 writes {shader-clock cycles, ticks of the constant 100 MHz counter} spent in
+  // its K loop, so that the host can see at which clock the chip ran the launch.
+  long long* clk;
 };
 enum GemmEpi { GEMM_EPI_NONE = 0, GEMM_EPI_SILU_MUL = 1, GEMM_EPI_SWIGLU_BWD = 2 };
 

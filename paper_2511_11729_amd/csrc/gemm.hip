@@ -160,6 +160,9 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
     seg_range(a, sgi, m0, &kb, &ke);
     if (ke > kb) n_stage += (ke - kb + BK - 1) / BK;
   }
+  const bool probe = a.clk != nullptr && blockIdx.x == 0 && blockIdx.z == 0;
+  long long c_start = 0, w_start = 0;
+  if (probe) c_start = clock64(), w_start = wall_clock64();
   if (n_stage > 0) {
     bool f0;
     OPEN_SEG(f0);
@@ -189,6 +192,7 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
       __syncthreads();
     }
   }
+  if (probe && tid == 0) a.clk[0] = clock64() - c_start, a.clk[1] = wall_clock64() - w_start;
 #undef OPEN_SEG
 #undef FETCH
 #undef LDA_

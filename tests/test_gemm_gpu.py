@@ -99,3 +99,19 @@ def test_read_bandwidth_probe_reports_sane_rates():
     small = torch.empty(1 << 20, dtype=torch.uint8, device="cuda:0")
     with pytest.raises(hb.HarliError):
         hb.dbg_read_bandwidth(small, 0)
+
+
+def test_clock_probe_reports_the_clock_and_leaves_the_product_intact():
+    """The in-kernel clock probe: a plausible shader clock (0.5 .. 2.6 GHz), a plausible rate, and the same product
+    as the fp64 reference."""
+    M, N, K = 512, 384, 256
+    g = torch.Generator().manual_seed(5)
+    A = ((torch.rand(M, K, generator=g) - 0.5)).half().to(DEV)
+    B = ((torch.rand(N, K, generator=g) - 0.5)).half().to(DEV)
+    Cb = torch.empty(M, N, dtype=torch.float16, device=DEV)
+    tf, mhz = hb.dbg_gemm_clock(A, B, Cb, half=True, reps=3)
+    assert 500.0 < mhz < 2600.0 and tf > 0.0
+    ref = A.double().cpu() @ B.double().cpu().T
+    assert float((Cb.double().cpu() - ref).abs().max()) <= 2e-3 * float(ref.abs().max())
+    with pytest.raises(hb.HarliError):
+        hb.dbg_gemm_clock(A, B, Cb, half=True, reps=0)
