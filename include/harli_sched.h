@@ -54,6 +54,37 @@ harli_status harli_pred_colo(const harli_predictor* p, int32_t infer_level, int3
 harli_status harli_sched_pick(const harli_predictor* p, int32_t bs, int32_t seqlen, double slo, int32_t* infer_level,
                               int32_t* ft_level, double* predicted);
 
+/* Runtime scheduling (Sec. 6.2): one decision at the beginning of every decode phase. */
+typedef struct harli_scheduler harli_scheduler;
+
+enum {
+  HARLI_SCHED_KEEP = 0,    /* the plan in force still meets the target: both tasks continue */
+  HARLI_SCHED_REPLAN = 1,  /* new plan: pause the finetune task (let its unit in flight finish) before switching */
+  HARLI_SCHED_PAUSED = 2,  /* no plan meets the target: finetune stays paused, inference gets every compute unit */
+  HARLI_SCHED_STARVED = 3  /* the finetune task has no ready work: inference gets every compute unit this phase */
+};
+
+typedef struct harli_sched_decision {
+  int32_t infer_level; /* 1..n_levels */
+  int32_t ft_level;    /* 0 = finetune does not run in this phase */
+  int32_t action;      /* HARLI_SCHED_* */
+  double predicted;    /* predicted decode latency of this phase under the decision */
+} harli_sched_decision;
+
+/* `p` must be fully fitted and outlive the scheduler.  slo > 0 in the predictor's latency unit.  refresh_phases >= 0:
+ * after that many consecutive phases under one plan the choice is recomputed even though the plan still meets the
+ * target (0 = never; the paper reports adjustments about every 100 ms, Sec. 8.6, without giving the rule). */
+harli_status harli_sched_create(const harli_predictor* p, double slo, int32_t refresh_phases, harli_scheduler** out);
+void harli_sched_destroy(harli_scheduler* s);
+
+/* Decision for the decode phase that is about to start: batch size bs >= 1, sequence length seqlen >= 0, ft_ready
+ * non-zero when the finetune task has a unit ready to run.  Rules, in this order: not ready -> STARVED (all compute
+ * units to inference, plan dropped); no plan in force -> harli_sched_pick (REPLAN, or PAUSED when no pair meets the
+ * target); plan in force and its predicted co-located latency above the target -> harli_sched_pick likewise;
+ * otherwise KEEP, except that a plan older than refresh_phases is recomputed (REPLAN only if the pair changes).
+ * *out is a host pointer. */
+harli_status harli_sched_step(harli_scheduler* s, int32_t bs, int32_t seqlen, int32_t ft_ready, harli_sched_decision* out);
+
 /* A HIP stream (default priority) whose kernels run only on compute units [cu_first, cu_first + cu_count) of the
  * current device's compute-unit mask order; the runtime spreads consecutive mask bits round-robin over the XCDs,
  * so a contiguous range is an equal share of every XCD.  *hip_stream receives a hipStream_t.  Ranges outside

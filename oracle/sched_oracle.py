@@ -67,3 +67,63 @@ def pick(solo_coefs, colo_coef, bs, seqlen, slo, n_levels=10):
     if best is None:
         return n_levels, 0, predict_solo(solo_coefs[n_levels - 1], bs, seqlen)
     return best[1]
+
+
+KEEP, REPLAN, PAUSED, STARVED = 0, 1, 2, 3
+
+
+class RuntimeScheduler:
+    """Per-decode-phase allocation decisions (Sec. 6.2 "Runtime Scheduling").
+
+    Called once at the beginning of every decode phase with the batch size, the sequence length and whether the
+    finetune task has ready work.  Returns (infer_level, ft_level, predicted latency, action):
+
+    * the finetune task has no ready work (it waits for data): inference takes every compute unit for this phase
+      (STARVED); the plan is recomputed when the finetune task is ready again;
+    * no plan in force (first phase, after a starved or paused phase): the closest-below-target plan is chosen
+      (REPLAN), or, when no plan meets the target, the finetune task stays paused and inference runs alone on the
+      whole chip (PAUSED);
+    * a plan is in force: its co-located latency is predicted for the new (bs, seqlen); above the target, the
+      finetune task is paused and a new plan is computed (REPLAN, or PAUSED when none qualifies); otherwise both
+      tasks continue (KEEP).
+    * Reading taken where the paper is silent: a plan that stays valid while the load falls would never be
+      revisited by the rules above, yet Sec. 8.6 reports adjustments about every 100 ms.  After `refresh_phases`
+      consecutive phases under one plan (0 = never) the choice is recomputed; REPLAN if it differs, KEEP if not.
+    """
+
+    def __init__(self, solo_coefs, colo_coef, slo, n_levels=10, refresh_phases=0):
+        self.solo_coefs, self.colo_coef, self.slo, self.n, self.refresh = solo_coefs, colo_coef, slo, n_levels, refresh_phases
+        self.cur = None
+        self.age = 0
+
+    def _solo_full(self, bs, seqlen):
+        return predict_solo(self.solo_coefs[self.n - 1], bs, seqlen)
+
+    def _replan(self, bs, seqlen):
+        i, f, lat = pick(self.solo_coefs, self.colo_coef, bs, seqlen, self.slo, self.n)
+        self.age = 0
+        if f == 0:
+            self.cur = None
+            return i, f, lat, PAUSED
+        self.cur = (i, f)
+        return i, f, lat, REPLAN
+
+    def step(self, bs, seqlen, ft_ready):
+        if not ft_ready:
+            self.cur = None
+            self.age = 0
+            return self.n, 0, self._solo_full(bs, seqlen), STARVED
+        if self.cur is None:
+            return self._replan(bs, seqlen)
+        i, f = self.cur
+        lat = predict_colo(self.colo_coef, i / self.n, f / self.n, predict_solo(self.solo_coefs[i - 1], bs, seqlen))
+        if lat > self.slo:
+            return self._replan(bs, seqlen)
+        self.age += 1
+        if self.refresh > 0 and self.age >= self.refresh:
+            old = self.cur
+            r = self._replan(bs, seqlen)
+            if r[3] == REPLAN and self.cur == old:
+                return r[0], r[1], r[2], KEEP
+            return r
+        return i, f, lat, KEEP

@@ -117,6 +117,9 @@ _SIGS = {
     "harli_pred_colo_coef": (C.c_int, [C.c_void_p, C.POINTER(C.c_double)]),
     "harli_pred_solo": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_double)]),
     "harli_pred_colo": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_double)]),
+    "harli_sched_create": (C.c_int, [C.c_void_p, C.c_double, C.c_int32, C.POINTER(C.c_void_p)]),
+    "harli_sched_destroy": (None, [C.c_void_p]),
+    "harli_sched_step": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p]),
     "harli_sched_pick": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_double, C.POINTER(C.c_int32), C.POINTER(C.c_int32),
                                    C.POINTER(C.c_double)]),
     "harli_cu_stream_create": (C.c_int, [C.c_int32, C.c_int32, C.POINTER(C.c_void_p)]),
@@ -387,6 +390,40 @@ class Predictor:
         i, f, v = C.c_int32(), C.c_int32(), C.c_double()
         _check(lib().harli_sched_pick(self.handle, bs, seqlen, slo, C.byref(i), C.byref(f), C.byref(v)))
         return i.value, f.value, v.value
+
+
+SCHED_KEEP, SCHED_REPLAN, SCHED_PAUSED, SCHED_STARVED = 0, 1, 2, 3
+
+
+class SchedDecision(C.Structure):
+    _fields_ = [("infer_level", C.c_int32), ("ft_level", C.c_int32), ("action", C.c_int32), ("predicted", C.c_double)]
+
+
+class Scheduler:
+    """harli_sched_create / step: one allocation decision per decode phase.  Keeps the predictor alive."""
+
+    def __init__(self, pred: Predictor, slo: float, refresh_phases: int = 0):
+        self.pred = pred
+        h = C.c_void_p()
+        _check(lib().harli_sched_create(pred.handle, slo, refresh_phases, C.byref(h)))
+        self.handle = h
+
+    def close(self):
+        if self.handle:
+            lib().harli_sched_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def step(self, bs: int, seqlen: int, ft_ready: bool = True):
+        """(infer_level, ft_level, predicted latency, action)."""
+        d = SchedDecision()
+        _check(lib().harli_sched_step(self.handle, bs, seqlen, int(bool(ft_ready)), C.byref(d)))
+        return d.infer_level, d.ft_level, d.predicted, d.action
 
 
 def cu_stream_create(cu_first: int, cu_count: int) -> int:

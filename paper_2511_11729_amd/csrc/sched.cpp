@@ -207,6 +207,61 @@ extern "C" harli_status harli_sched_pick(const harli_predictor* p, int32_t bs, i
   return HARLI_OK;
 }
 
+struct harli_scheduler {
+  const harli_predictor* p;
+  double slo;
+  int refresh;
+  bool have;  // a plan is in force
+  int i, f, age;
+};
+
+extern "C" harli_status harli_sched_create(const harli_predictor* p, double slo, int32_t refresh_phases, harli_scheduler** out) {
+  if (!p || !out || !(slo > 0.0) || refresh_phases < 0) return fail(HARLI_ERR_INVALID, "sched_create: bad argument");
+  if (!p->colo_fitted) return fail(HARLI_ERR_STATE, "sched_create: Eq. 2 is not fitted");
+  for (int l = 0; l < p->n_levels; ++l)
+    if (!p->fitted[l]) return fail(HARLI_ERR_STATE, "sched_create: level %d is not fitted", l + 1);
+  *out = new harli_scheduler{p, slo, refresh_phases, false, 0, 0, 0};
+  return HARLI_OK;
+}
+
+extern "C" void harli_sched_destroy(harli_scheduler* s) { delete s; }
+
+static harli_status sched_replan(harli_scheduler* s, int bs, int seqlen, harli_sched_decision* out) {
+  int32_t i = 0, f = 0;
+  double lat = 0.0;
+  harli_status rc = harli_sched_pick(s->p, bs, seqlen, s->slo, &i, &f, &lat);
+  if (rc != HARLI_OK) return rc;
+  s->age = 0;
+  s->have = f > 0;
+  s->i = i;
+  s->f = f;
+  *out = harli_sched_decision{i, f, f > 0 ? HARLI_SCHED_REPLAN : HARLI_SCHED_PAUSED, lat};
+  return HARLI_OK;
+}
+
+extern "C" harli_status harli_sched_step(harli_scheduler* s, int32_t bs, int32_t seqlen, int32_t ft_ready, harli_sched_decision* out) {
+  if (!s || !out || bs < 1 || seqlen < 0) return fail(HARLI_ERR_INVALID, "sched_step: bad argument");
+  const harli_predictor* p = s->p;
+  if (!ft_ready) {
+    s->have = false;
+    s->age = 0;
+    *out = harli_sched_decision{p->n_levels, 0, HARLI_SCHED_STARVED, eval_solo(p, p->n_levels, bs, seqlen)};
+    return HARLI_OK;
+  }
+  if (!s->have) return sched_replan(s, bs, seqlen, out);
+  const double lat = eval_colo(p, s->i, s->f, eval_solo(p, s->i, bs, seqlen));
+  if (lat > s->slo) return sched_replan(s, bs, seqlen, out);
+  s->age += 1;
+  if (s->refresh > 0 && s->age >= s->refresh) {
+    const int oi = s->i, of = s->f;
+    harli_status rc = sched_replan(s, bs, seqlen, out);
+    if (rc == HARLI_OK && out->action == HARLI_SCHED_REPLAN && out->infer_level == oi && out->ft_level == of) out->action = HARLI_SCHED_KEEP;
+    return rc;
+  }
+  *out = harli_sched_decision{s->i, s->f, HARLI_SCHED_KEEP, lat};
+  return HARLI_OK;
+}
+
 extern "C" harli_status harli_cu_stream_create(int32_t cu_first, int32_t cu_count, void** hip_stream) {
   if (!hip_stream) return fail(HARLI_ERR_INVALID, "cu_stream_create: null out pointer");
   int dev = 0;

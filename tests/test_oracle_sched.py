@@ -107,3 +107,39 @@ def test_pick_pauses_finetune_when_no_plan_meets_the_target():
     solo = _flat_solo(10, [50.0] * 10)
     i, f, lat = S.pick(solo, (1.0, 1.0), 8, 512, 1.0)
     assert (i, f) == (10, 0) and lat == 50.0
+
+
+# ---- runtime scheduling (Sec. 6.2): hand-worked traces on a model whose predictions can be done in the head ----
+def _toy():
+    """Solo latency = bs at every level (b0 = 1, c0 = k0 = 0); Eq. 2 with b1 = 0, k1 = 1: the co-located latency is
+    (f / 10) * bs, independent of the inference share.  With a target of 4.0 the largest admissible finetune share
+    is f = floor(40 / bs); ties (every i gives the same latency) go to the smallest inference share i = 1."""
+    return [(1.0, 0.0, 0.0)] * 10, (0.0, 1.0)
+
+
+def test_runtime_scheduler_follows_the_rules_of_sec_6_2():
+    solo, colo = _toy()
+    s = S.RuntimeScheduler(solo, colo, slo=4.0)
+    assert s.step(8, 100, True) == (1, 5, 4.0, S.REPLAN)           # first phase: 0.8 f <= 4 -> f = 5
+    assert s.step(8, 999, True) == (1, 5, 4.0, S.KEEP)             # still valid: both continue
+    i, f, lat, act = s.step(10, 100, True)                         # 0.5 * 10 = 5 > 4: pause finetune, re-plan
+    assert (i, f, act) == (1, 4, S.REPLAN) and abs(lat - 4.0) < 1e-12
+    assert s.step(50, 100, True) == (10, 0, 50.0, S.PAUSED)        # 5 f <= 4 has no solution: inference alone
+    assert s.step(50, 100, True) == (10, 0, 50.0, S.PAUSED)        # retried every phase
+    assert s.step(8, 100, True) == (1, 5, 4.0, S.REPLAN)           # load fell: finetune resumes under a new plan
+    assert s.step(8, 100, False) == (10, 0, 8.0, S.STARVED)        # no ready finetune work: all CUs to inference
+    assert s.step(8, 100, True) == (1, 5, 4.0, S.REPLAN)           # work is back: redistribute
+
+
+def test_runtime_scheduler_refresh_revisits_a_plan_that_stays_valid():
+    solo, colo = _toy()
+    s = S.RuntimeScheduler(solo, colo, slo=4.0, refresh_phases=3)
+    assert s.step(20, 0, True)[:2] == (1, 2)                       # 2 f <= 4 -> f = 2
+    assert s.step(5, 0, True) == (1, 2, 1.0, S.KEEP)               # valid, far below the target, age 1
+    assert s.step(5, 0, True) == (1, 2, 1.0, S.KEEP)               # age 2
+    assert s.step(5, 0, True) == (1, 8, 4.0, S.REPLAN)             # age 3: recomputed, 0.5 f <= 4 -> f = 8
+    assert s.step(5, 0, True)[3] == S.KEEP and s.step(5, 0, True)[3] == S.KEEP
+    assert s.step(5, 0, True) == (1, 8, 4.0, S.KEEP)               # age 3 again: same pair, nothing to do
+    never = S.RuntimeScheduler(solo, colo, slo=4.0)
+    never.step(20, 0, True)
+    assert all(never.step(5, 0, True) == (1, 2, 1.0, S.KEEP) for _ in range(10))

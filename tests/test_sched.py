@@ -108,3 +108,43 @@ def test_errors():
         p.pick(8, 100, 1.0)                       # nothing fitted
     with pytest.raises(hb.HarliError):
         hb.Predictor(1)
+
+
+@pytest.mark.parametrize("seed,refresh", [(0, 0), (1, 4), (2, 1), (3, 16)])
+def test_runtime_scheduler_matches_the_oracle_on_random_traces(seed, refresh):
+    """400 decode phases of a random walk in batch size and sequence length with starvation episodes: the
+    library's decisions (levels and action bit-exact, prediction to 1e-8) equal the oracle's at every phase."""
+    p, o_solo, o_colo = build_both(seed)
+    rng = np.random.default_rng(100 + seed)
+    slo = float(rng.uniform(0.15, 0.6))
+    lib_s = hb.Scheduler(p, slo, refresh)
+    ora_s = S.RuntimeScheduler(o_solo, o_colo, slo, 10, refresh)
+    bs, n = 8, 300
+    seen = set()
+    for _ in range(400):
+        bs = int(np.clip(bs + rng.integers(-6, 7), 1, 96))
+        n = int(np.clip(n + rng.integers(-200, 260), 0, 4096))
+        ready = rng.random() > 0.1
+        gi, gf, gl, ga = lib_s.step(bs, n, ready)
+        wi, wf, wl_, wa = ora_s.step(bs, n, ready)
+        assert (gi, gf, ga) == (wi, wf, wa), (bs, n, ready)
+        assert abs(gl - wl_) <= 1e-8 * abs(wl_)
+        seen.add(ga)
+    assert {hb.SCHED_KEEP, hb.SCHED_REPLAN, hb.SCHED_STARVED} <= seen
+    lib_s.close()
+
+
+def test_runtime_scheduler_rejects_bad_arguments():
+    p, _, _ = build_both(0)
+    for slo, refresh in [(0.0, 0), (-1.0, 0), (1.0, -1)]:
+        with pytest.raises(hb.HarliError) as e:
+            hb.Scheduler(p, slo, refresh)
+        assert e.value.status == hb.HARLI_ERR_INVALID
+    unfitted = hb.Predictor(10)
+    with pytest.raises(hb.HarliError) as e:
+        hb.Scheduler(unfitted, 1.0, 0)
+    assert e.value.status == hb.HARLI_ERR_STATE
+    s = hb.Scheduler(p, 1.0, 0)
+    for bs, n in [(0, 10), (4, -1)]:
+        with pytest.raises(hb.HarliError):
+            s.step(bs, n, True)
