@@ -41,7 +41,9 @@ harli_status harli_pred_fit(harli_predictor* p);
 harli_status harli_pred_solo_coef(const harli_predictor* p, int32_t level, double* solo);
 harli_status harli_pred_colo_coef(const harli_predictor* p, double* colo);
 
-/* Predictions (host out-pointer). */
+/* Predictions (host out-pointer).  Co-located: max(1, SM_infer*b1 + SM_ft*k1) * solo(infer_level): Eq. 2's slowdown
+ * factor is derived (Sec. 5.2.2) for the contended case only, where it is at least 1; below that the two tasks do not
+ * contend and the prediction is the solo latency. */
 harli_status harli_pred_solo(const harli_predictor* p, int32_t level, int32_t bs, int32_t seqlen, double* latency);
 harli_status harli_pred_colo(const harli_predictor* p, int32_t infer_level, int32_t ft_level, int32_t bs, int32_t seqlen,
                              double* latency);

@@ -11,6 +11,10 @@ compared with.
       latency_colo = (SM_infer*b1 + SM_ft*k1) * latency_solo(SM_infer)
   fitted by ordinary least squares of latency_colo on the two regressors SM_infer*latency_solo and
   SM_ft*latency_solo (the paper says only that b1, k1 come from profiling; this is the reading taken).
+  Prediction floors the factor at 1: the theoretical analysis of Sec. 5.2 derives it as
+  (f_infer + f_ft) / B under contention, f_infer + f_ft > B, where it is at least 1; with less combined demand
+  than bandwidth the tasks do not slow each other and the co-located latency is the solo latency (a factor
+  below 1 would predict that a neighbour makes decode faster).
 * Allocation (Sec. 5.2 "Perceive the Finetune Performance", Sec. 6.2): with ratios in steps of 1/n_levels the
   candidate plans are the pairs (SM_infer, SM_ft) with SM_infer + SM_ft <= 1, both at least one step (45 pairs
   for ten levels).  The plan chosen is the one whose predicted co-located latency is closest to the QoS target
@@ -44,8 +48,9 @@ def fit_colo(samples):
 
 
 def predict_colo(colo_coef, sm_infer, sm_ft, latency_solo):
+    """Eq. 2 with the slowdown factor floored at 1 (see the module header)."""
     b1, k1 = colo_coef
-    return (sm_infer * b1 + sm_ft * k1) * latency_solo
+    return max(1.0, sm_infer * b1 + sm_ft * k1) * latency_solo
 
 
 def pairs(n_levels=10):

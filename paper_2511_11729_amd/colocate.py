@@ -138,7 +138,7 @@ def profile(hz, steps=12, log=lambda *a: None):
     err_fit = [abs(pred.solo(lv, bs, n) - ms) / ms for (lv, bs, n), ms in solo_meas.items()]
     err_held = [abs(pred.solo(lv, bs, n) - ms) / ms for (lv, bs, n), ms in held.items()]
     b1, k1 = pred.colo_coef()
-    err_colo = [abs((i / N_LEVELS * b1 + f / N_LEVELS * k1) * base[i] - ms) / ms for (i, f), ms in colo_meas.items()]
+    err_colo = [abs(max(1.0, i / N_LEVELS * b1 + f / N_LEVELS * k1) * base[i] - ms) / ms for (i, f), ms in colo_meas.items()]
     report = {
         "levels": N_LEVELS, "compute_units": cs.n_cu,
         "eq1_mean_abs_err_fitted_points": float(np.mean(err_fit)), "eq1_mean_abs_err_heldout": float(np.mean(err_held)),
@@ -213,3 +213,113 @@ def run_colocated(hz, sD, sF, decode_once, K, W, pace_ms=None, finetune=True):
     steplat = np.array([dec_start[j].elapsed_time(dec_end[j]) for j in range(lo, hi)]) if hi > lo else np.array([float("nan")])
     return {"elapsed": elapsed, "tokens_per_s": K * hz.T / elapsed if finetune else 0.0, "ms_per_step": elapsed * 1e3 / K,
             "tpot": tpot, "steplat": steplat}
+
+
+class FinetuneFeeder:
+    """Host thread that keeps the finetune task running on whatever stream the scheduler last assigned
+    (`target`; None = paused).  At most two units are in flight, so a pause or a move to another partition takes
+    effect after the unit that is running; a unit on a new stream waits for the last unit on the old one (the
+    units share the task's workspace)."""
+
+    def __init__(self, hz):
+        self.hz = hz
+        self.target = None
+        self.units = 0
+        self._stop = threading.Event()
+        self._evs = []
+        self._last_stream = None
+        self.th = threading.Thread(target=self._run, daemon=True)
+
+    def _run(self):
+        torch.cuda.set_device(0)
+        while not self._stop.is_set():
+            st = self.target
+            if st is None:
+                time.sleep(5e-5)
+                continue
+            if len(self._evs) >= 2:
+                self._evs[-2].synchronize()
+            if self._last_stream is not None and st is not self._last_stream and self._evs:
+                st.wait_event(self._evs[-1])
+            self.hz.finetune_unit(st)
+            ev = torch.cuda.Event()
+            ev.record(st)
+            self._evs.append(ev)
+            if len(self._evs) > 8:
+                del self._evs[:4]
+            self._last_stream = st
+            self.units += 1
+
+    def completed(self):
+        """Units whose work has finished on the device."""
+        pending = sum(0 if e.query() else 1 for e in self._evs[-2:])
+        return self.units - pending
+
+    def __enter__(self):
+        self.th.start()
+        return self
+
+    def __exit__(self, *a):
+        self._stop.set()
+        self.th.join()
+        torch.cuda.synchronize()
+
+
+def run_trace(hz, pred, slo_ms, segments, seqlen, refresh_phases=32, starve=(), log=lambda *a: None):
+    """Replays a decode load trace under the runtime scheduler (Sec. 6.2) on compute-unit partitions.
+
+    segments: [(phases, batch), ...]; every sequence has `seqlen` cached tokens.  At the beginning of each decode
+    phase the library's scheduler decides the partition; decode runs on the first infer_level tenths of the compute
+    units, the finetune task on the last ft_level tenths (or not at all).  `starve`: phase indices at which the
+    finetune task reports no ready work.  The host waits for each decode step before deciding the next phase.
+    Returns per-phase records and a per-segment summary (latency percentiles, share of phases within the target,
+    finetune units completed)."""
+    cs = CuStreams()
+    low, high = {}, {}
+    for g in range(0, N_LEVELS, 2):                      # inference and finetune streams two dispatch pipes apart
+        for lv in (g + 1, g + 2):
+            low[lv] = cs.low(lv)
+        for lv in (g + 1, g + 2):
+            high[lv] = cs.high(lv)
+    sched = hb.Scheduler(pred, slo_ms, refresh_phases)
+    dev = hz.x_dev.device
+    starve = set(starve)
+    rec = []
+    summary = []
+    g = 0
+    last_stream, last_ev = None, None
+    with FinetuneFeeder(hz) as feeder:
+        for n_ph, bs in segments:
+            lens = torch.full((bs,), seqlen, dtype=torch.int32, device=dev)
+            u0, t0 = feeder.completed(), time.perf_counter()
+            first = len(rec)
+            for _ in range(n_ph):
+                ready = g not in starve
+                i, f, pred_ms, act = sched.step(bs, seqlen, ready)
+                feeder.target = high[f] if f > 0 else None
+                st = low[i]
+                if last_stream is not None and st is not last_stream:
+                    st.wait_event(last_ev)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(st)
+                hz.decode_launch(st, bs, lens, seqlen + 1)
+                e1.record(st)
+                e1.synchronize()
+                last_stream, last_ev = st, e1
+                rec.append({"phase": g, "batch": bs, "infer_level": i, "ft_level": f, "action": act, "predicted_ms": pred_ms,
+                            "latency_ms": e0.elapsed_time(e1)})
+                g += 1
+            dt = time.perf_counter() - t0
+            lat = np.array([r["latency_ms"] for r in rec[first:]])
+            units = feeder.completed() - u0
+            summary.append({"batch": bs, "phases": n_ph, "latency_ms_p50": float(np.percentile(lat, 50)),
+                            "latency_ms_p99": float(np.percentile(lat, 99)), "within_slo": float(np.mean(lat <= slo_ms)),
+                            "finetune_units": int(units), "finetune_tokens_per_s": units * hz.T / dt,
+                            "plans": sorted({(r["infer_level"], r["ft_level"]) for r in rec[first:]}),
+                            "replans": int(sum(r["action"] == hb.SCHED_REPLAN for r in rec[first:]))})
+            log("[trace] batch %d: %s" % (bs, summary[-1]))
+        feeder.target = None
+    sched.close()
+    cs.close()
+    hz.ctx.check(torch.cuda.current_stream())
+    return {"phases": rec, "segments": summary}

@@ -73,8 +73,11 @@ double eval_solo(const harli_predictor* p, int level, double bs, double seqlen) 
   const double* c = &p->coef[(size_t)(level - 1) * 3];
   return bs * c[0] + c[1] + bs * c[2] * seqlen;
 }
+// Eq. 2, with the slowdown factor floored at 1: the paper derives the factor as (f_infer + f_ft) / B for the
+// contended case f_infer + f_ft > B only; without contention the co-located latency is the solo latency.
 double eval_colo(const harli_predictor* p, int il, int fl, double solo) {
-  return ((double)il / p->n_levels * p->b1 + (double)fl / p->n_levels * p->k1) * solo;
+  const double factor = (double)il / p->n_levels * p->b1 + (double)fl / p->n_levels * p->k1;
+  return (factor > 1.0 ? factor : 1.0) * solo;
 }
 }  // namespace
 

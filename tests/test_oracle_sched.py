@@ -59,7 +59,7 @@ def test_least_squares_satisfies_the_normal_equations():
 
 def test_eq2_recovers_the_bandwidth_sharing_model():
     # Sec. 5.2 theoretical analysis: slowdown = (f_infer + f_ft) / B with each demand proportional to its share
-    cin, cft, B = 5.0, 3.0, 8.0
+    cin, cft, B = 50.0, 30.0, 8.0      # demands large enough that every pair is in the contended regime
     pts = []
     for i, f in S.pairs(10):
         solo = 2.0 / (i / 10) ** 0.5
@@ -83,24 +83,37 @@ def _flat_solo(levels, lat_by_level):
 
 def test_pick_takes_the_plan_closest_below_the_target():
     solo = _flat_solo(10, [10.0, 6.0, 4.5, 3.8, 3.3, 3.0, 2.8, 2.6, 2.5, 2.4])
-    colo = (1.0, 1.0)           # factor = SM_infer + SM_ft
+    colo = (10.0, 10.0)         # factor = i + f >= 2: contended everywhere
     # brute force by hand
-    cands = [(i, f, (i + f) / 10 * solo[i - 1][1]) for i, f in S.pairs(10)]
-    ok = [c for c in cands if c[2] <= 2.0]
+    cands = [(i, f, (i + f) * solo[i - 1][1]) for i, f in S.pairs(10)]
+    ok = [c for c in cands if c[2] <= 20.0]
     want = max(ok, key=lambda c: (c[2], c[1], -c[0]))
-    got = S.pick(solo, colo, 8, 512, 2.0)
+    got = S.pick(solo, colo, 8, 512, 20.0)
     assert got[:2] == want[:2] and abs(got[2] - want[2]) < 1e-12
-    assert got[2] <= 2.0
+    assert got[2] <= 20.0
     # nothing else that fits is closer to the target
     assert all(c[2] <= got[2] + 1e-12 for c in ok)
 
 
 def test_pick_ties_go_to_the_larger_finetune_share():
     solo = _flat_solo(4, [4.0, 2.0, 4.0 / 3.0, 1.0])      # latency * ratio constant -> (i + f)/i * const
-    colo = (1.0, 1.0)
-    # pairs with the same predicted latency: (1,1): 2/4*4 = 2.0 ; (2,2): 4/4*2 = 2.0 -> f = 2 wins
-    i, f, lat = S.pick(solo, colo, 1, 1, 2.0, n_levels=4)
-    assert (i, f) == (2, 2) and abs(lat - 2.0) < 1e-12
+    colo = (4.0, 4.0)           # factor = i + f
+    # pairs with the same predicted latency: (1,1): 2*4 = 8.0 ; (2,2): 4*2 = 8.0 -> f = 2 wins
+    i, f, lat = S.pick(solo, colo, 1, 1, 8.0, n_levels=4)
+    assert (i, f) == (2, 2) and abs(lat - 8.0) < 1e-12
+
+
+def test_without_contention_the_colocated_latency_is_the_solo_latency():
+    # factor 0.3*0.5 + 0.2*1.0 = 0.35 < 1: no contention (combined demand below the bandwidth) -> solo latency;
+    # factor 0.8*0.5 + 0.2*4.0 = 1.2 -> 1.2 x solo
+    assert S.predict_colo((0.5, 1.0), 0.3, 0.2, 3.0) == 3.0
+    assert abs(S.predict_colo((0.5, 4.0), 0.8, 0.2, 3.0) - 3.6) < 1e-12
+    # a neighbour never makes the predicted decode step faster, whatever the coefficients
+    rng = np.random.default_rng(3)
+    for _ in range(200):
+        c = tuple(rng.uniform(0, 3, 2))
+        i, f = S.pairs(10)[rng.integers(45)]
+        assert S.predict_colo(c, i / 10, f / 10, 2.5) >= 2.5
 
 
 def test_pick_pauses_finetune_when_no_plan_meets_the_target():
@@ -111,35 +124,36 @@ def test_pick_pauses_finetune_when_no_plan_meets_the_target():
 
 # ---- runtime scheduling (Sec. 6.2): hand-worked traces on a model whose predictions can be done in the head ----
 def _toy():
-    """Solo latency = bs at every level (b0 = 1, c0 = k0 = 0); Eq. 2 with b1 = 0, k1 = 1: the co-located latency is
-    (f / 10) * bs, independent of the inference share.  With a target of 4.0 the largest admissible finetune share
-    is f = floor(40 / bs); ties (every i gives the same latency) go to the smallest inference share i = 1."""
-    return [(1.0, 0.0, 0.0)] * 10, (0.0, 1.0)
+    """Solo latency = bs at every level (b0 = 1, c0 = k0 = 0); Eq. 2 with b1 = 0, k1 = 10: the slowdown factor is f
+    (>= 1: contended), the co-located latency f * bs, independent of the inference share.  With a target of 40 the
+    largest admissible finetune share is f = floor(40 / bs); ties (every i gives the same latency) go to the
+    smallest inference share i = 1."""
+    return [(1.0, 0.0, 0.0)] * 10, (0.0, 10.0)
 
 
 def test_runtime_scheduler_follows_the_rules_of_sec_6_2():
     solo, colo = _toy()
-    s = S.RuntimeScheduler(solo, colo, slo=4.0)
-    assert s.step(8, 100, True) == (1, 5, 4.0, S.REPLAN)           # first phase: 0.8 f <= 4 -> f = 5
-    assert s.step(8, 999, True) == (1, 5, 4.0, S.KEEP)             # still valid: both continue
-    i, f, lat, act = s.step(10, 100, True)                         # 0.5 * 10 = 5 > 4: pause finetune, re-plan
-    assert (i, f, act) == (1, 4, S.REPLAN) and abs(lat - 4.0) < 1e-12
-    assert s.step(50, 100, True) == (10, 0, 50.0, S.PAUSED)        # 5 f <= 4 has no solution: inference alone
+    s = S.RuntimeScheduler(solo, colo, slo=40.0)
+    assert s.step(8, 100, True) == (1, 5, 40.0, S.REPLAN)           # first phase: 8 f <= 40 -> f = 5
+    assert s.step(8, 999, True) == (1, 5, 40.0, S.KEEP)             # still valid: both continue
+    i, f, lat, act = s.step(10, 100, True)                         # 5 * 10 = 50 > 40: pause finetune, re-plan
+    assert (i, f, act) == (1, 4, S.REPLAN) and abs(lat - 40.0) < 1e-12
+    assert s.step(50, 100, True) == (10, 0, 50.0, S.PAUSED)        # 50 f <= 40 has no solution: inference alone
     assert s.step(50, 100, True) == (10, 0, 50.0, S.PAUSED)        # retried every phase
-    assert s.step(8, 100, True) == (1, 5, 4.0, S.REPLAN)           # load fell: finetune resumes under a new plan
+    assert s.step(8, 100, True) == (1, 5, 40.0, S.REPLAN)           # load fell: finetune resumes under a new plan
     assert s.step(8, 100, False) == (10, 0, 8.0, S.STARVED)        # no ready finetune work: all CUs to inference
-    assert s.step(8, 100, True) == (1, 5, 4.0, S.REPLAN)           # work is back: redistribute
+    assert s.step(8, 100, True) == (1, 5, 40.0, S.REPLAN)           # work is back: redistribute
 
 
 def test_runtime_scheduler_refresh_revisits_a_plan_that_stays_valid():
     solo, colo = _toy()
-    s = S.RuntimeScheduler(solo, colo, slo=4.0, refresh_phases=3)
-    assert s.step(20, 0, True)[:2] == (1, 2)                       # 2 f <= 4 -> f = 2
-    assert s.step(5, 0, True) == (1, 2, 1.0, S.KEEP)               # valid, far below the target, age 1
-    assert s.step(5, 0, True) == (1, 2, 1.0, S.KEEP)               # age 2
-    assert s.step(5, 0, True) == (1, 8, 4.0, S.REPLAN)             # age 3: recomputed, 0.5 f <= 4 -> f = 8
+    s = S.RuntimeScheduler(solo, colo, slo=40.0, refresh_phases=3)
+    assert s.step(20, 0, True)[:2] == (1, 2)                       # 20 f <= 40 -> f = 2
+    assert s.step(5, 0, True) == (1, 2, 10.0, S.KEEP)               # valid, far below the target, age 1
+    assert s.step(5, 0, True) == (1, 2, 10.0, S.KEEP)               # age 2
+    assert s.step(5, 0, True) == (1, 8, 40.0, S.REPLAN)             # age 3: recomputed, 5 f <= 40 -> f = 8
     assert s.step(5, 0, True)[3] == S.KEEP and s.step(5, 0, True)[3] == S.KEEP
-    assert s.step(5, 0, True) == (1, 8, 4.0, S.KEEP)               # age 3 again: same pair, nothing to do
-    never = S.RuntimeScheduler(solo, colo, slo=4.0)
+    assert s.step(5, 0, True) == (1, 8, 40.0, S.KEEP)               # age 3 again: same pair, nothing to do
+    never = S.RuntimeScheduler(solo, colo, slo=40.0)
     never.step(20, 0, True)
-    assert all(never.step(5, 0, True) == (1, 2, 1.0, S.KEEP) for _ in range(10))
+    assert all(never.step(5, 0, True) == (1, 2, 10.0, S.KEEP) for _ in range(10))

@@ -71,3 +71,32 @@ def test_profile_fit_and_scheduled_colocation(hz):
     assert float(np.percentile(res["tpot"], 99)) <= slo
     st = hz.pool.stats()
     assert st.pending_frees == 0 or st.pending_frees <= 16
+
+
+def test_runtime_scheduler_replays_a_load_trace(hz):
+    """Light -> heavy -> medium decode load (the shape of the paper's memory/SM-ratio traces, Sec. 8.5-8.6) with two
+    starvation episodes: the decode step stays inside the target in nearly every phase, the finetune task makes
+    progress in every segment, starved phases give inference the whole chip, and a heavier load never gets a
+    smaller inference share."""
+    pred, _ = colocate.profile(hz, steps=6)
+    slo = 40.0 / 32.0
+    segs = [(40, 8), (40, 42), (40, 24)]
+    starve = set(range(20, 24)) | set(range(100, 103))
+    out = colocate.run_trace(hz, pred, slo, segs, seqlen=1024, refresh_phases=16, starve=starve)
+    ph, sg = out["phases"], out["segments"]
+    assert len(ph) == 120
+    for r in ph:
+        if r["phase"] in starve:
+            assert (r["infer_level"], r["ft_level"], r["action"]) == (10, 0, hb.SCHED_STARVED)
+        else:
+            assert r["infer_level"] + r["ft_level"] <= 10 and r["infer_level"] >= 1
+            assert r["ft_level"] == 0 or r["predicted_ms"] <= slo
+    for s in sg:
+        assert s["within_slo"] >= 0.9, s
+        assert s["finetune_units"] >= 1, s
+    light = min(i for i, f in sg[0]["plans"] if f > 0)
+    heavy = min(i for i, f in sg[1]["plans"] if f > 0)
+    assert heavy >= light
+    # the phase after a starvation episode re-plans
+    assert ph[24]["action"] == hb.SCHED_REPLAN and ph[103]["action"] == hb.SCHED_REPLAN
+    assert hz.pool.stats().pending_frees <= 16
