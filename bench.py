@@ -191,7 +191,16 @@ def main():
         # paper's 45 disjoint plans, but a 256-tile GEMM needs all 256 compute units to finish in one round
         res_o = colocate.run_colocated(hz, sDm, sF, lambda: hz.decode_launch(sDm), K, W, None) if fl > 0 else None
         ctx.check(sDm)
+        # StaticMode-style comparator (Sec. 8.1): 60 % of the compute units to inference, 40 % to finetune, fixed
+        sDs = cs.low(6)
+        cs.low(6)
+        sFs = cs.high(4)
+        res_s = colocate.run_colocated(hz, sDs, sFs, lambda: hz.decode_launch(sDs), K, W, None)
+        ctx.check(sDs)
         cs.close()
+        # runtime scheduling over a load trace (Sec. 6.2): light -> heavy -> medium decode batches, one starvation episode
+        trace = colocate.run_trace(hz, pred, slo_ms, [(150, 8), (150, 42), (150, 24)], seqlen=1024, refresh_phases=32,
+                                   starve=range(60, 70), log=log)
         sched = {"infer_level": il, "ft_level": fl, "predicted_tpot_ms": plat, "value": res["tokens_per_s"], "unit": "tokens/s",
                  "ms_per_step": res["ms_per_step"], "tpot_ms_p50": float(np.percentile(res["tpot"], 50)),
                  "tpot_ms_p99": float(np.percentile(res["tpot"], 99)), "met": bool(np.percentile(res["tpot"], 99) <= slo_ms),
@@ -200,6 +209,12 @@ def main():
                      "value": res_o["tokens_per_s"], "ms_per_step": res_o["ms_per_step"],
                      "tpot_ms_p50": float(np.percentile(res_o["tpot"], 50)), "tpot_ms_p99": float(np.percentile(res_o["tpot"], 99)),
                      "met": bool(np.percentile(res_o["tpot"], 99) <= slo_ms)},
+                 "static_60_40": {"value": res_s["tokens_per_s"], "ms_per_step": res_s["ms_per_step"],
+                                  "tpot_ms_p50": float(np.percentile(res_s["tpot"], 50)),
+                                  "tpot_ms_p99": float(np.percentile(res_s["tpot"], 99)),
+                                  "met": bool(np.percentile(res_s["tpot"], 99) <= slo_ms)},
+                 "trace": {"segments": trace["segments"], "seqlen": 1024, "starved_phases": [60, 69],
+                           "note": "decision per decode phase by harli_sched_step; host waits for each decode step"},
                  "note": "decode and finetune on disjoint compute-unit ranges chosen by harli_sched_pick (closest "
                          "predicted TPOT below the SLO over the 45 partitions), decode in a closed loop, direct launches"}
 
