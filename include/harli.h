@@ -251,6 +251,38 @@ harli_status harli_saved_release(harli_ctx* c, harli_saved* saved, void* hip_str
 /* Pool bytes a forward call of (B_f, S) reserves for its saved activations. */
 harli_status harli_saved_bytes(const harli_ctx* c, int32_t B_f, int32_t S, size_t* bytes);
 
+/* ---- Window over the finetune task's frozen weights (Sec. 4.3; shrinking under memory pressure: Sec. 4.4) ----
+ * After harli_lora_attach the library holds finetune-private copies of every layer's frozen weights (W for the forward
+ * pass, W^T for the backward pass).  harli_ft_window_enable moves them to pinned host memory and keeps only n_slots of
+ * them on the device, in TENSOR allocations of the unified pool (one slot = one layer's seven matrices in one
+ * orientation; n_slots is capped at 2 * n_layers, which is everything).  A training step uses the copies in a fixed
+ * cyclic order -- W of layers 0..L-1, then W^T of layers L-1..0 -- and harli_lora_fwd / harli_lora_bwd make their
+ * stream wait for the copy they need, then, once the layer is enqueued, refill its slot over a library-owned copy
+ * stream with the nearest copy ahead in that order that is not on the device (the first layer outside the window).
+ * A copy requested while absent (another order of calls, a window just resized) is loaded on demand.  Frozen weights
+ * never change, so eviction writes nothing back.  Results are bit-identical with and without a window.
+ * enable: HARLI_ERR_STATE before lora_attach or when a window exists; HARLI_ERR_OOM when the pool cannot hold n_slots
+ *   slots or the host cannot pin the copies (nothing is moved then).  Synchronises the device.
+ * resize: grows (pool permitting: on HARLI_ERR_OOM the window keeps the slots it got) or shrinks the window, keeping
+ *   the copies needed soonest; waits for the copy stream and for the layers that last used the slots.
+ * disable: brings every copy back to device memory of its own and releases slots and host memory.
+ * ready: *ready (host) = 1 when the copy that harli_lora_fwd (backward = 0) or harli_lora_bwd (backward = 1) of `layer`
+ *   needs is on the device now (always 1 without a window): what a scheduler asks before it calls the finetune task
+ *   "ready" (Sec. 6.2).  Never blocks.
+ * None of these may run concurrently with harli_lora_fwd / harli_lora_bwd on the same context. */
+typedef struct harli_window_stats {
+  int32_t slots;      /* 0 = no window */
+  size_t slot_bytes;  /* one layer's frozen weights in one orientation */
+  size_t host_bytes;  /* pinned host memory held */
+  int64_t h2d_bytes;  /* host-to-device bytes copied so far */
+  int64_t hits, misses, refills; /* acquisitions found on the device / loaded on demand; slots refilled after use */
+} harli_window_stats;
+harli_status harli_ft_window_enable(harli_ctx* c, int32_t n_slots);
+harli_status harli_ft_window_resize(harli_ctx* c, int32_t n_slots);
+harli_status harli_ft_window_disable(harli_ctx* c);
+harli_status harli_ft_window_ready(harli_ctx* c, int32_t layer, int32_t backward, int32_t* ready);
+harli_status harli_ft_window_stats(harli_ctx* c, harli_window_stats* out);
+
 /* ======================================================================== *
  * Output layer of the finetune task with next-token cross entropy (Sec. 2.1: "output layer" after the stack of
  * transformer layers; the loss of the workloads that carry a vocabulary).  Needs g_final and w_lm in the context

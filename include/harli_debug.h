@@ -31,6 +31,13 @@ harli_status harli_dbg_gemm(const void* A1, const void* B1, int32_t K1, const vo
 harli_status harli_dbg_gemm_clock(const void* A, const void* B, int32_t M, int32_t N, int32_t K, int32_t half, void* Cb,
                                   int32_t reps, double* tflops, double* shader_mhz, void* hip_stream);
 
+/* The residency plan of harli_ft_window_* on its own (host logic only, no device needed): a window of n_slots over the
+ * 2 * n_layers cyclic items, prefilled with items 0..n_slots-1, is driven through `items[0..n_access)`; for every
+ * access the slot that served it, the item loaded on demand (-1 on a hit) and the item loaded into the slot
+ * afterwards (-1 = none) are written to the three host arrays. */
+harli_status harli_dbg_window_plan(int32_t n_layers, int32_t n_slots, const int32_t* items, int32_t n_access, int32_t* slot,
+                                   int32_t* miss, int32_t* refill);
+
 /* Kernel timing for the benchmark.  While enabled, every launch of the finetune unit's MFMA GEMM
  * is bracketed by two HIP events on the stream it is launched on.  harli_prof_collect waits for
  * them (it SYNCHRONISES on those events), returns the summed algorithmic flops (2*M*N*K per

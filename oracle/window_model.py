@@ -1,0 +1,58 @@
+"""CPU model of the window over the finetune task's frozen weights (Harli Sec. 4.3).
+
+TEST INFRASTRUCTURE ONLY: the product path never imports it.  It states the residency policy the library's host
+logic (`harli_dbg_window_plan`, and through it `harli_ft_window_*`) is compared with.
+
+The frozen weights of an L-layer model are used, step after step, in the cyclic order
+    forward copy of layer 0, 1, ..., L-1, then backward (transposed) copy of layer L-1, ..., 0,
+2L "items" numbered in that order.  A window of n slots keeps the next items on the device (the paper: when a layer
+has been computed its frozen weights are evicted and those of the first layer outside the window are prefetched):
+
+* access of an item that is resident: hit;
+* access of an absent item: it is loaded at once into an empty slot, else into the slot whose item comes latest
+  in the cyclic order counted from the accessed item;
+* after every access the slot just used is refilled with the nearest item ahead (1..n steps) that is absent; if all
+  of them are present (n >= 2L covers the whole cycle) nothing is loaded.
+"""
+from __future__ import annotations
+
+
+def item_of(layer: int, backward: bool, n_layers: int) -> int:
+    return 2 * n_layers - 1 - layer if backward else layer
+
+
+class Window:
+    def __init__(self, n_layers: int, n_slots: int, prefill: bool = True):
+        self.items = 2 * n_layers
+        self.n = n_slots
+        self.slots = [-1] * n_slots
+        if prefill:
+            for s in range(min(n_slots, self.items)):
+                self.slots[s] = s
+
+    def _ahead(self, frm: int, to: int) -> int:
+        return (to - frm) % self.items
+
+    def access(self, item: int):
+        """Returns (slot, item loaded on a miss or -1, item loaded into the slot afterwards or -1)."""
+        miss = -1
+        if item in self.slots:
+            s = self.slots.index(item)
+        else:
+            if -1 in self.slots:
+                s = self.slots.index(-1)
+            else:
+                s = max(range(self.n), key=lambda q: (self._ahead(item, self.slots[q]), -q))
+            self.slots[s] = item
+            miss = item
+        refill = -1
+        for d in range(1, self.n + 1):
+            cand = (item + d) % self.items
+            if cand == item:
+                break
+            if cand not in self.slots:
+                refill = cand
+                break
+        if refill >= 0:
+            self.slots[s] = refill
+        return s, miss, refill

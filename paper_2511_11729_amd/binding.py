@@ -7,6 +7,7 @@ library has not been built (`python -m paper_2511_11729_amd.build`).
 from __future__ import annotations
 
 import ctypes as C
+import sys
 import os
 from typing import List, Optional, Sequence
 
@@ -125,6 +126,13 @@ _SIGS = {
     "harli_cu_stream_create": (C.c_int, [C.c_int32, C.c_int32, C.POINTER(C.c_void_p)]),
     "harli_cu_stream_destroy": (C.c_int, [C.c_void_p]),
     "harli_dbg_read_bandwidth": (C.c_int, [C.c_void_p, C.c_size_t, C.c_int32, C.POINTER(C.c_double), C.c_void_p]),
+    "harli_ft_window_enable": (C.c_int, [C.c_void_p, C.c_int32]),
+    "harli_ft_window_resize": (C.c_int, [C.c_void_p, C.c_int32]),
+    "harli_ft_window_disable": (C.c_int, [C.c_void_p]),
+    "harli_ft_window_ready": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_int32)]),
+    "harli_ft_window_stats": (C.c_int, [C.c_void_p, C.c_void_p]),
+    "harli_dbg_window_plan": (C.c_int, [C.c_int32, C.c_int32, C.POINTER(C.c_int32), C.c_int32, C.POINTER(C.c_int32),
+                                        C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
     "harli_dbg_gemm_clock": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_int32,
                                        C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_void_p]),
     "harli_dbg_gemm": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
@@ -187,6 +195,8 @@ class Pool:
             self.handle = C.c_void_p()
 
     def __del__(self):
+        if sys.is_finalizing():       # the HIP runtime may already be gone: let the process exit reclaim everything
+            return
         try:
             self.close()
         except Exception:
@@ -268,6 +278,8 @@ class Context:
             self.handle = C.c_void_p()
 
     def __del__(self):
+        if sys.is_finalizing():       # the HIP runtime may already be gone: let the process exit reclaim everything
+            return
         try:
             self.close()
         except Exception:
@@ -275,6 +287,26 @@ class Context:
 
     def check(self, stream=None) -> None:
         _check(lib().harli_ctx_check(self.handle, _stream(stream)))
+
+    # ---- window over the finetune task's frozen weights (harli_ft_window_*)
+    def ft_window_enable(self, n_slots: int) -> None:
+        _check(lib().harli_ft_window_enable(self.handle, n_slots))
+
+    def ft_window_resize(self, n_slots: int) -> None:
+        _check(lib().harli_ft_window_resize(self.handle, n_slots))
+
+    def ft_window_disable(self) -> None:
+        _check(lib().harli_ft_window_disable(self.handle))
+
+    def ft_window_ready(self, layer: int, backward: bool) -> bool:
+        r = C.c_int32(0)
+        _check(lib().harli_ft_window_ready(self.handle, layer, int(bool(backward)), C.byref(r)))
+        return bool(r.value)
+
+    def ft_window_stats(self) -> "WindowStats":
+        st = WindowStats()
+        _check(lib().harli_ft_window_stats(self.handle, C.byref(st)))
+        return st
 
     def lora_attach(self, rank: int, alpha: float, targets: Sequence[str], A, B) -> None:
         """A, B: per layer a dict target -> torch tensor."""
@@ -351,6 +383,8 @@ class Predictor:
             self.handle = C.c_void_p()
 
     def __del__(self):
+        if sys.is_finalizing():       # the HIP runtime may already be gone: let the process exit reclaim everything
+            return
         try:
             self.close()
         except Exception:
@@ -414,6 +448,8 @@ class Scheduler:
             self.handle = None
 
     def __del__(self):
+        if sys.is_finalizing():       # the HIP runtime may already be gone: let the process exit reclaim everything
+            return
         try:
             self.close()
         except Exception:
@@ -445,6 +481,20 @@ def dbg_gemm(A1, B1, *, A2=None, B2=None, alpha=1.0, causal=0, half=False, Cb=No
     K2 = A2.shape[1] if A2 is not None else 0
     _check(lib().harli_dbg_gemm(_ptr(A1), _ptr(B1), K1, _ptr(A2), _ptr(B2), K2, M, N, alpha, causal, int(half), _ptr(Cb), _ptr(Cf),
                                 _ptr(res), _ptr(Ct), _stream(stream)))
+
+
+class WindowStats(C.Structure):
+    _fields_ = [("slots", C.c_int32), ("slot_bytes", C.c_size_t), ("host_bytes", C.c_size_t), ("h2d_bytes", C.c_int64),
+                ("hits", C.c_int64), ("misses", C.c_int64), ("refills", C.c_int64)]
+
+
+def dbg_window_plan(n_layers: int, n_slots: int, items):
+    """(slot, miss, refill) lists of the library's window residency plan driven through `items`."""
+    n = len(items)
+    arr = (C.c_int32 * max(n, 1))(*items)
+    slot, miss, refill = (C.c_int32 * max(n, 1))(), (C.c_int32 * max(n, 1))(), (C.c_int32 * max(n, 1))()
+    _check(lib().harli_dbg_window_plan(n_layers, n_slots, arr, n, slot, miss, refill))
+    return list(slot[:n]), list(miss[:n]), list(refill[:n])
 
 
 def dbg_gemm_clock(A, B, Cb, *, half=True, reps=20, stream=None):

@@ -62,6 +62,7 @@ struct harli_ctx {
   void* ft_ws = nullptr;     // finetune workspace (library-owned)
   size_t ft_ws_bytes = 0;
   void* head_ws = nullptr;   // output-layer workspace of the finetune task (library-owned)
+  void* window = nullptr;    // window over the finetune task's frozen weights (library-owned), or null
   int n_cu = 0;
 };
 

@@ -26,6 +26,8 @@ static harli_status dev_alloc(T** p, size_t bytes, bool zero) {
 
 void free_finetune_state(harli_ctx* c);  // finetune.hip
 void free_head_state(harli_ctx* c);      // head.hip
+void free_window_state(harli_ctx* c);    // window.hip
+void detach_layers(harli_ctx* c);        // window.hip
 
 }  // namespace harli
 
@@ -179,6 +181,8 @@ extern "C" void harli_ctx_destroy(harli_ctx* c) {
     for (int t = 0; t < kTargets; ++t)
       if (ld.wp[t]) (void)hipFree(ld.wp[t]);
   if (c->wlm_p) (void)hipFree(c->wlm_p);
+  if (c->window) detach_layers(c);  // the weight tables point into window slots
+  free_window_state(c);
   free_finetune_state(c);
   free_head_state(c);
   delete c;

@@ -19,6 +19,7 @@
 #include "ft_attention.h"
 #include "ft_kernels.h"
 #include "gemm.h"
+#include "window.h"
 
 using namespace harli;
 
@@ -289,6 +290,7 @@ extern "C" harli_status harli_lora_attach(harli_ctx* c, const harli_lora_cfg* cf
   if (cfg->targets == 0 || cfg->targets >= (1u << kTargets)) return fail(HARLI_ERR_INVALID, "lora_attach: bad target mask");
   if (c->cfg.max_ft_tokens < 1) return fail(HARLI_ERR_STATE, "lora_attach: the context was created with max_ft_tokens = 0");
   if (c->cfg.head_dim > 512) return fail(HARLI_ERR_INVALID, "lora_attach: head_dim %d above 512 is not supported", c->cfg.head_dim);
+  if (c->window) return fail(HARLI_ERR_STATE, "lora_attach: disable the weight window first");
   for (int l = 0; l < c->cfg.n_layers; ++l)
     for (int t = 0; t < kTargets; ++t)
       if (((cfg->targets >> t) & 1u) && (!A[l * kTargets + t] || !B[l * kTargets + t]))
@@ -347,6 +349,8 @@ extern "C" harli_status harli_lora_fwd(harli_ctx* c, int32_t layer, const float*
   s = ensure_ws(c, B_f, S);
   if (s != HARLI_OK) return s;
   FtWs& w = state(c)->ws;
+  s = window_acquire(c, layer, false, st);
+  if (s != HARLI_OK) return s;
 
   // ---- activations kept for backward come from the unified pool ----
   harli_saved* sv = new harli_saved;
@@ -469,6 +473,11 @@ extern "C" harli_status harli_lora_fwd(harli_ctx* c, int32_t layer, const float*
     release_saved(c, sv, st, true);
     return fail(HARLI_ERR_HIP, "lora_fwd: a kernel launch failed");
   }
+  s = window_release(c, layer, false, st);
+  if (s != HARLI_OK) {
+    release_saved(c, sv, st, true);
+    return s;
+  }
   *saved = sv;
   return HARLI_OK;
 }
@@ -489,6 +498,8 @@ extern "C" harli_status harli_lora_bwd(harli_ctx* c, int32_t layer, const float*
   s = ensure_ws(c, B_f, S);
   if (s != HARLI_OK) return s;
   FtWs& w = state(c)->ws;
+  s = window_acquire(c, layer, true, st);
+  if (s != HARLI_OK) return s;
   const int T = D.T;
   const long long SS = (long long)S * S;
   const int batches = B_f * D.nq;
@@ -650,8 +661,9 @@ extern "C" harli_status harli_lora_bwd(harli_ctx* c, int32_t layer, const float*
   }
   ft_rmsnorm_bwd(w.dh, sv->X, sv->rho1, L.g1, w.dx1, dX, nullptr, T, D.H, nullptr, w.scale + 1, st);
   HARLI_HIP(hipGetLastError());
+  s = window_release(c, layer, true, st);
   release_saved(c, sv, st, true);
-  return HARLI_OK;
+  return s;
 }
 
 extern "C" harli_status harli_saved_release(harli_ctx* c, harli_saved* saved, void* hip_stream) {

@@ -1,0 +1,51 @@
+// Residency plan of the window over the finetune task's frozen weights (Harli Sec. 4.3): pure host logic, no HIP.
+//
+// One training step touches the frozen weights in a fixed cyclic order: the forward copies W of layers 0..L-1, then the
+// transposed copies W^T of layers L-1..0 (the backward pass), then the next step's forward again.  Numbering these
+// 2L "items" 0..2L-1 in that order, a window of n device slots holds the items about to be used.  After an item has
+// been used its slot receives the nearest item ahead that no slot holds (in steady state: the item n steps ahead, "the
+// first layer outside the window"); an item requested while absent (out-of-order use, or a window that was just
+// resized) is loaded on demand into an empty slot or, failing that, the slot whose item is needed farthest in the future.
+#pragma once
+#include <vector>
+
+namespace harli {
+
+struct WindowPlan {
+  int L = 0, n = 0;
+  std::vector<int> slot_item;  // item resident (or being loaded) per slot, -1 = empty
+
+  void init(int layers, int slots) {
+    L = layers;
+    n = slots;
+    slot_item.assign(n, -1);
+  }
+  int items() const { return 2 * L; }
+  static int item_of(int layer, bool backward, int layers) { return backward ? 2 * layers - 1 - layer : layer; }
+  int find(int item) const {
+    for (int s = 0; s < n; ++s)
+      if (slot_item[s] == item) return s;
+    return -1;
+  }
+  // how many uses ahead of `from` the item `to` comes (0 = itself)
+  int ahead(int from, int to) const { return ((to - from) % items() + items()) % items(); }
+  int victim(int item) const {
+    int best = -1, far = -1;
+    for (int s = 0; s < n; ++s) {
+      if (slot_item[s] < 0) return s;
+      const int d = ahead(item, slot_item[s]);
+      if (d > far) far = d, best = s;
+    }
+    return best;
+  }
+  int refill_after(int item) const {
+    for (int d = 1; d <= n; ++d) {
+      const int cand = (item + d) % items();
+      if (cand == item) return -1;
+      if (find(cand) < 0) return cand;
+    }
+    return -1;
+  }
+};
+
+}  // namespace harli
