@@ -5,7 +5,9 @@ layer's backward (the paper's per-layer units, Sec. 6.1, chained through explici
 update of every adapter.  Seeded random weights; every layer shares ONE set of host-generated frozen weights (the
 library still keeps its own half-precision copies per layer), adapters are per layer.  Prints one JSON line with
 tokens/s and the achieved rate on the algorithmic flops (4 T P_layer per layer for the base GEMMs, 4 T V H for the
-output layer, causal attention and LoRA terms added).
+output layer, causal attention and LoRA terms added).  --window n runs the step under a window of n device slots over
+the frozen weights (the rest stays in pinned host memory and is copied in ahead of use) and reports the host-to-device
+rate the step sustained.
 """
 from __future__ import annotations
 
@@ -24,6 +26,8 @@ def main():
     ap.add_argument("--config", type=int, default=2)
     ap.add_argument("--layers", type=int, default=None, help="depth override")
     ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--window", type=int, default=0,
+                    help="keep only this many layer copies of the frozen weights on the device (0: all resident)")
     args = ap.parse_args()
 
     import dataclasses
@@ -54,6 +58,8 @@ def main():
     chunk = L * 2 * block
     per_layer = T * H * 12 + T * m.n_q * m.head_dim * 4 + T * m.n_kv * m.head_dim * 4 + T * m.ffn * 6
     n_chunks = (L + 1) * (per_layer // chunk + 2) + 4       # a unit's activations take whole adjacent chunks
+    slot_chunks = -(-2 * m.layer_params // chunk) + 1        # one window slot: a layer's weights in one orientation
+    n_chunks += min(args.window, 2 * L) * slot_chunks
     small = 256 << 20
     slab_bytes = small + n_chunks * chunk
     slab = torch.zeros(slab_bytes, dtype=torch.uint8, device=dev)
@@ -63,6 +69,8 @@ def main():
                      vocab=m.vocab, rms_eps=m.rms_eps, rope_base=m.rope_base, dtype=hb.HARLI_BF16, max_batch=1, max_seq_len=16,
                      max_ft_tokens=T, layers=[layer] * L, emb=emb, g_final=gf, w_lm=wlm)
     ctx.lora_attach(lora.rank, lora.alpha, lora.targets, A, B)
+    if args.window > 0:
+        ctx.ft_window_enable(args.window)
 
     tok = wl.make_token_ids(w, (ft.micro_batch, ft.seq_len))
     tg = np.full(tok.shape, -1, np.int32)
@@ -109,6 +117,13 @@ def main():
     st.synchronize()
     ctx.check(st)
     ms = e0.elapsed_time(e1) / args.steps
+    ws = ctx.ft_window_stats()
+    window = None
+    if ws.slots > 0:
+        per_step = 2 * L * ws.slot_bytes if ws.slots < 2 * L else 0
+        window = {"slots": ws.slots, "slot_MB": ws.slot_bytes / 1e6, "host_pinned_GB": ws.host_bytes / 1e9,
+                  "h2d_GB_per_step": per_step / 1e9, "h2d_GBs": per_step / ms / 1e6, "hits": ws.hits, "misses": ws.misses,
+                  "refills": ws.refills}
     r = lora.rank
     lora_flops = 0
     for p in lora.targets:
@@ -120,7 +135,7 @@ def main():
                                   (args.config, L, ft.micro_batch, ft.seq_len, r, ",".join(lora.targets)),
                       "ms_per_step": ms, "tokens_per_s": T / ms * 1e3, "algorithmic_TFLOP_per_step": flops / 1e12,
                       "achieved_TFLOPs": flops / ms / 1e9, "frac_of_2.5PF": flops / ms / 1e9 / 2500.0,
-                      "loss_first": l0, "loss_last": float(loss), "steps": args.steps}))
+                      "loss_first": l0, "loss_last": float(loss), "steps": args.steps, "window": window}))
 
 
 if __name__ == "__main__":
