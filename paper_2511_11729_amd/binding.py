@@ -195,9 +195,9 @@ class Pool:
             self.handle = C.c_void_p()
 
     def __del__(self):
-        if sys.is_finalizing():       # the HIP runtime may already be gone: let the process exit reclaim everything
-            return
         try:
+            if sys.is_finalizing():   # the HIP runtime may already be gone: let the process exit reclaim everything
+                return
             self.close()
         except Exception:
             pass
@@ -278,9 +278,9 @@ class Context:
             self.handle = C.c_void_p()
 
     def __del__(self):
-        if sys.is_finalizing():       # the HIP runtime may already be gone: let the process exit reclaim everything
-            return
         try:
+            if sys.is_finalizing():   # the HIP runtime may already be gone: let the process exit reclaim everything
+                return
             self.close()
         except Exception:
             pass
@@ -383,9 +383,9 @@ class Predictor:
             self.handle = C.c_void_p()
 
     def __del__(self):
-        if sys.is_finalizing():       # the HIP runtime may already be gone: let the process exit reclaim everything
-            return
         try:
+            if sys.is_finalizing():   # the HIP runtime may already be gone: let the process exit reclaim everything
+                return
             self.close()
         except Exception:
             pass
@@ -448,9 +448,9 @@ class Scheduler:
             self.handle = None
 
     def __del__(self):
-        if sys.is_finalizing():       # the HIP runtime may already be gone: let the process exit reclaim everything
-            return
         try:
+            if sys.is_finalizing():   # the HIP runtime may already be gone: let the process exit reclaim everything
+                return
             self.close()
         except Exception:
             pass
