@@ -33,7 +33,8 @@ norm-preserving relative rotation; RMSNorm output has unit RMS.  The full
 multi-layer model is pinned only as "a stack of the pinned layer" -- parity
 with a real checkpoint is unpinned (no weights are available).
 
-Conventions: linear weights are [out, in] (y = x W^T), no biases; A is [in, r],
+Conventions: linear weights are [out, in] (y = x W^T); no biases except optional frozen ones on q, k, v ("bq", "bk",
+"bv" in the weight dict: the Qwen2.5 family the paper also evaluates, Sec. 8.1); A is [in, r],
 B is [r, out]; `kv_len` counts tokens cached BEFORE the step (the step appends
 one and attends over kv_len + 1).
 """
@@ -248,13 +249,20 @@ class Shapes:
     rope_base: float = 10000.0
 
 
+def _bias(W, name):
+    """Frozen additive bias of a projection (q, k, v of models that carry them), or 0.  It is added before the
+    rotary embedding; being constant it receives no gradient and changes no other gradient formula."""
+    b = W.get(name)
+    return F(0.0) if b is None else np.asarray(b, F)
+
+
 def _qkv_new_token(x, W, sh: Shapes, pos):
     """Steps 1-3 of the decode layer for one batch of single tokens."""
     h = rmsnorm(x, W["g1"], sh.rms_eps)
     B = h.shape[0]
-    q = (h @ np.asarray(W["wq"], F).T).reshape(B, sh.n_q, sh.head_dim)
-    k = (h @ np.asarray(W["wk"], F).T).reshape(B, sh.n_kv, sh.head_dim)
-    v = (h @ np.asarray(W["wv"], F).T).reshape(B, sh.n_kv, sh.head_dim)
+    q = (h @ np.asarray(W["wq"], F).T + _bias(W, "bq")).reshape(B, sh.n_q, sh.head_dim)
+    k = (h @ np.asarray(W["wk"], F).T + _bias(W, "bk")).reshape(B, sh.n_kv, sh.head_dim)
+    v = (h @ np.asarray(W["wv"], F).T + _bias(W, "bv")).reshape(B, sh.n_kv, sh.head_dim)
     q = rope(q, pos, sh.rope_base)
     k = rope(k, pos, sh.rope_base)
     return q, k, v
@@ -339,9 +347,9 @@ def layer_forward(X: np.ndarray, W: Dict[str, np.ndarray], lora: Dict[str, Tuple
     Bf, S, H = X.shape
     pos = np.broadcast_to(np.arange(S), (Bf, S))
     h = rmsnorm(X, W["g1"], sh.rms_eps)
-    q0 = lora_linear(h, W["wq"], lora.get("q"), scale).reshape(Bf, S, sh.n_q, sh.head_dim)
-    k0 = lora_linear(h, W["wk"], lora.get("k"), scale).reshape(Bf, S, sh.n_kv, sh.head_dim)
-    v = lora_linear(h, W["wv"], lora.get("v"), scale).reshape(Bf, S, sh.n_kv, sh.head_dim)
+    q0 = (lora_linear(h, W["wq"], lora.get("q"), scale) + _bias(W, "bq")).reshape(Bf, S, sh.n_q, sh.head_dim)
+    k0 = (lora_linear(h, W["wk"], lora.get("k"), scale) + _bias(W, "bk")).reshape(Bf, S, sh.n_kv, sh.head_dim)
+    v = (lora_linear(h, W["wv"], lora.get("v"), scale) + _bias(W, "bv")).reshape(Bf, S, sh.n_kv, sh.head_dim)
     q, k = rope(q0, pos, sh.rope_base), rope(k0, pos, sh.rope_base)
     o = np.empty((Bf, S, sh.n_q, sh.head_dim), F)
     P = []

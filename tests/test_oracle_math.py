@@ -464,3 +464,93 @@ def test_head_uniform_logits_give_log_vocab():
     x = np.ones((3, 8))
     loss, dx, _ = O.head_forward_backward(x, np.ones(8), np.zeros((50, 8)), np.array([1, 7, 49]), 1e-6)
     assert abs(loss - np.log(50)) < 1e-12 and not dx.any()
+
+
+# ----------------------------------------------------------------------------- frozen biases on q, k, v
+def with_biases(rng, W, sh, std=0.7):
+    W = dict(W)
+    W["bq"] = rng.standard_normal(sh.n_q * sh.head_dim) * std
+    W["bk"] = rng.standard_normal(sh.n_kv * sh.head_dim) * std
+    W["bv"] = rng.standard_normal(sh.n_kv * sh.head_dim) * std
+    return W
+
+
+def test_biases_zero_projections_put_the_biases_where_they_belong():
+    """With Wq = Wk = Wv = 0 the projections ARE the biases: the cached key of the new token is rope(bk) at its
+    position, the cached value is bv, and with an empty cache attention returns bv repeated over each group."""
+    rng = np.random.default_rng(31)
+    sh = tiny_shapes(n_q=4, n_kv=2, d=4)
+    W = with_biases(rng, rand_weights(rng, sh), sh)
+    for n in ("wq", "wk", "wv"):
+        W[n] = np.zeros_like(W[n])
+    x = rng.standard_normal((1, sh.hidden))
+    pos = 5
+    cache = [(rng.standard_normal((pos, sh.n_kv, sh.head_dim)), rng.standard_normal((pos, sh.n_kv, sh.head_dim)))]
+    _, new = O.decode_layer_contiguous(x, W, sh, cache)
+    bk = W["bk"].reshape(1, sh.n_kv, sh.head_dim)
+    assert np.allclose(new[0][0][-1], O.rope(bk, np.array([pos]), sh.rope_base)[0], atol=1e-13)
+    assert np.allclose(new[0][1][-1], W["bv"].reshape(sh.n_kv, sh.head_dim), atol=1e-13)
+    empty = [(np.zeros((0, sh.n_kv, sh.head_dim)), np.zeros((0, sh.n_kv, sh.head_dim)))]
+    y, _ = O.decode_layer_contiguous(x, W, sh, empty)
+    o = np.repeat(W["bv"].reshape(1, sh.n_kv, sh.head_dim), sh.n_q // sh.n_kv, axis=1).reshape(1, -1)
+    x1 = x + o @ W["wo"].T
+    h2 = O.rmsnorm(x1, W["g2"], sh.rms_eps)
+    a = h2 @ W["wg"].T
+    assert np.allclose(y, x1 + ((a / (1 + np.exp(-a))) * (h2 @ W["wu"].T)) @ W["wd"].T, atol=1e-12)
+
+
+def test_biases_are_a_constant_input_column():
+    """x W^T + b = [x, 1] [W, b]^T: folding each bias into one more input column of its projection (fed with ones
+    after the normalisation) must give the same layer.  Done by hand here on the attention inputs: the scores of a
+    biased layer equal those computed from the augmented products."""
+    rng = np.random.default_rng(32)
+    sh = tiny_shapes(n_q=4, n_kv=2, d=4)
+    W = with_biases(rng, rand_weights(rng, sh), sh)
+    X = rng.standard_normal((1, 6, sh.hidden))
+    _, saved = O.layer_forward(X, W, {}, 0.0, sh)
+    h1 = np.concatenate([O.rmsnorm(X, W["g1"], sh.rms_eps), np.ones((1, 6, 1))], axis=-1)
+    pos = np.arange(6)[None]
+    for name, bias, heads, key in (("wq", "bq", sh.n_q, "q"), ("wk", "bk", sh.n_kv, "k")):
+        aug = np.concatenate([W[name], W[bias][:, None]], axis=1)
+        want = O.rope((h1 @ aug.T).reshape(1, 6, heads, sh.head_dim), pos, sh.rope_base)
+        assert np.allclose(saved[key], want, atol=1e-12), name
+    aug = np.concatenate([W["wv"], W["bv"][:, None]], axis=1)
+    assert np.allclose(saved["v"], (h1 @ aug.T).reshape(1, 6, sh.n_kv, sh.head_dim), atol=1e-12)
+    # and a zero bias is no bias, bit for bit
+    W0 = dict(W, bq=np.zeros_like(W["bq"]), bk=np.zeros_like(W["bk"]), bv=np.zeros_like(W["bv"]))
+    Wn = {k: v for k, v in W.items() if k not in ("bq", "bk", "bv")}
+    assert np.array_equal(O.layer_forward(X, W0, {}, 0.0, sh)[0], O.layer_forward(X, Wn, {}, 0.0, sh)[0])
+
+
+def test_biased_layer_decode_equals_last_row_and_gradients_match_finite_differences():
+    rng = np.random.default_rng(33)
+    sh = tiny_shapes(n_q=4, n_kv=2, d=4)
+    W = with_biases(rng, rand_weights(rng, sh), sh)
+    S = 7
+    X = rng.standard_normal((1, S, sh.hidden))
+    Y, saved = O.layer_forward(X, W, {}, 0.0, sh)
+    y, _ = O.decode_layer_contiguous(X[0, S - 1:], W, sh, [(saved["k"][0, : S - 1], saved["v"][0, : S - 1])])
+    assert np.allclose(y[0], Y[0, S - 1], atol=1e-12)
+    # the biases are constants of the layer: the gradient formulas are unchanged and still exact
+    lora = rand_lora(rng, sh, 2, ("q", "k", "v", "o"))
+    s = 2.0
+    T = rng.standard_normal(X.shape)
+    Y, saved = O.layer_forward(X, W, lora, s, sh)
+    _, dY = O.mse_loss(Y, T)
+    dX, grads = O.layer_backward(dY, saved, W, lora, s, sh)
+    eps = 1e-6
+
+    def fd(arr, idx):
+        old = arr[idx]
+        arr[idx] = old + eps
+        lp = _loss(X, W, lora, s, sh, T)
+        arr[idx] = old - eps
+        lm = _loss(X, W, lora, s, sh, T)
+        arr[idx] = old
+        return (lp - lm) / (2 * eps)
+
+    for idx in [(0, 0, 0), (0, 3, 7), (0, 6, 15)]:
+        assert np.isclose(dX[idx], fd(X, idx), rtol=2e-5, atol=1e-9), idx
+    for p in ("q", "k", "v", "o"):
+        assert np.isclose(grads[p][0][1, 1], fd(lora[p][0], (1, 1)), rtol=2e-5, atol=1e-9), p
+        assert np.isclose(grads[p][1][1, 2], fd(lora[p][1], (1, 2)), rtol=2e-5, atol=1e-9), p

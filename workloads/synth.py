@@ -39,6 +39,7 @@ class ModelCfg:
     rms_eps: float = 1e-6
     rope_base: float = 10000.0
     dtype: str = "bf16"          # storage type of weights, KV cache and saved activations
+    qkv_bias: bool = False       # frozen additive biases on the q, k, v projections (the Qwen2.5 family)
 
     @property
     def elem_bytes(self) -> int:
@@ -116,6 +117,12 @@ CONFIGS: Dict[int, Workload] = {
     4: Workload(4, ModelCfg("8b-gqa-32l", 32, 4096, 32, 8, 128, 14336, 128256),
                 LoraCfg(32, 64.0, ("q", "k", "v", "o")),
                 DecodeCfg(8, ("lognormal", 800, 0.6, 8192)), FinetuneCfg(8, 512, "ce")),
+    # the second model family of the paper's evaluation (Sec. 8.1): a Qwen2.5-7B-class decoder -- 28 layers, hidden
+    # 3584, 28 query heads over 4 KV heads (groups of 7), head_dim 128, ffn 18944, vocabulary 152064, RoPE base 1e6,
+    # biases on q, k, v
+    5: Workload(5, ModelCfg("qwen7b-class-28l", 28, 3584, 28, 4, 128, 18944, 152064, rope_base=1.0e6, qkv_bias=True),
+                LoraCfg(16, 32.0, ("q", "k", "v", "o")),
+                DecodeCfg(8, ("lognormal", 800, 0.6, 8192)), FinetuneCfg(8, 512, "ce")),
 }
 
 
@@ -160,7 +167,8 @@ def _normal(rng: np.random.Generator, shape, std: float) -> np.ndarray:
 # --------------------------------------------------------------------------- tensors
 def make_layer_weights(w: Workload, layer: int = 0, model: ModelCfg | None = None) -> Dict[str, np.ndarray]:
     """Frozen weights of one decoder layer: projections ~N(0, 0.02) stored as
-    ``model.dtype``; RMSNorm gains 1 + 0.02*N(0,1) kept in float32."""
+    ``model.dtype``; RMSNorm gains 1 + 0.02*N(0,1) kept in float32; with ``qkv_bias`` the
+    biases bq, bk, bv ~N(0, 0.5) in float32 (the same order of magnitude as the projections' outputs)."""
     m = model or w.model
     rng = rng_for(w.idx, S_WEIGHTS, layer)
     out = {}
@@ -168,6 +176,9 @@ def make_layer_weights(w: Workload, layer: int = 0, model: ModelCfg | None = Non
         out[WEIGHT_NAME[p]] = _store(_normal(rng, m.proj_shape(p), 0.02), m.dtype)
     out["g1"] = (1.0 + _normal(rng, (m.hidden,), 0.02)).astype(np.float32)
     out["g2"] = (1.0 + _normal(rng, (m.hidden,), 0.02)).astype(np.float32)
+    if m.qkv_bias:                       # drawn last, so that models without biases keep their weights
+        for p in ("q", "k", "v"):
+            out["b" + p] = _normal(rng, (m.proj_shape(p)[0],), 0.5).astype(np.float32)
     return out
 
 
