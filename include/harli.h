@@ -164,6 +164,8 @@ typedef struct {
 typedef struct {
   const void *wq, *wk, *wv, *wo, *wg, *wu, *wd; /* device, [out,in], cfg.dtype */
   const float *g1, *g2;                         /* device, [hidden] RMSNorm gains */
+  const float *bq, *bk, *bv; /* device fp32 [n_q*head_dim], [n_kv*head_dim], [n_kv*head_dim]: frozen biases added to the
+                              * q, k, v projections before the rotary embedding (the Qwen2.5 family, Sec. 8.1), or NULL */
 } harli_layer_weights;
 
 typedef struct {

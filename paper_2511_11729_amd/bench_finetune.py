@@ -49,6 +49,9 @@ def main():
     ex = wl.make_model_extras(w, m)
     layer = {n: dev_bf16(W_np[n]) for n in ("wq", "wk", "wv", "wo", "wg", "wu", "wd")}
     layer["g1"], layer["g2"] = dev_f32(W_np["g1"]), dev_f32(W_np["g2"])
+    for bn in ("bq", "bk", "bv"):
+        if bn in W_np:
+            layer[bn] = dev_f32(W_np[bn])
     emb, gf, wlm = dev_bf16(ex["emb"]), dev_f32(ex["gf"]), dev_bf16(ex["wlm"])
     lora_np = wl.make_lora(w, 0, m, lora)
     A = [{p: dev_bf16(a) for p, (a, b) in lora_np.items()} for _ in range(L)]

@@ -54,7 +54,7 @@ class ModelCfg(C.Structure):
 
 
 class LayerWeights(C.Structure):
-    _fields_ = [(n, C.c_void_p) for n in ("wq", "wk", "wv", "wo", "wg", "wu", "wd", "g1", "g2")]
+    _fields_ = [(n, C.c_void_p) for n in ("wq", "wk", "wv", "wo", "wg", "wu", "wd", "g1", "g2", "bq", "bk", "bv")]
 
 
 class Weights(C.Structure):
@@ -268,6 +268,8 @@ class Context:
         for i, lw in enumerate(layers):
             for n in ("wq", "wk", "wv", "wo", "wg", "wu", "wd", "g1", "g2"):
                 setattr(arr[i], n, _ptr(lw[n]))
+            for n in ("bq", "bk", "bv"):                      # optional frozen biases (fp32)
+                setattr(arr[i], n, _ptr(lw.get(n)))
         w = Weights(arr, _ptr(emb), _ptr(g_final), _ptr(w_lm))
         self.handle = C.c_void_p()
         _check(lib().harli_ctx_create(C.byref(self.cfg), C.byref(w), pool.handle, C.byref(self.handle)))

@@ -23,6 +23,8 @@ struct LayerDev {
   void* w16[kTargets];       // library-owned [out,in] copies in the finetune compute element (after lora_attach)
   void* wp[kTargets];        // decode-private pre-shuffled copies: [0] = q,k,v stacked, [3] o, [4] gate, [5] up, [6] down
   const float *g1, *g2;
+  const float* bias[3];      // borrowed q, k, v biases (fp32) or null
+  void* b16[3];              // library-owned [out, 8] copies in the finetune compute element, bias in column 0 (after lora_attach)
   void* A[kTargets];         // borrowed adapter pointers (NULL when not adapted)
   void* B[kTargets];
 };
@@ -62,6 +64,7 @@ struct harli_ctx {
   void* ft_ws = nullptr;     // finetune workspace (library-owned)
   size_t ft_ws_bytes = 0;
   void* head_ws = nullptr;   // output-layer workspace of the finetune task (library-owned)
+  void* ones16 = nullptr;    // [max_ft_tokens, 8] ones in the finetune compute element: the input column of the biases
   void* window = nullptr;    // window over the finetune task's frozen weights (library-owned), or null
   int n_cu = 0;
 };

@@ -59,8 +59,8 @@ extern "C" harli_status harli_ctx_create(const harli_model_cfg* cfg, const harli
     if (m.hidden % 8 || m.ffn % 8 || QD % 8)
       return fail(HARLI_ERR_INVALID, "ctx_create: bf16 kernels need hidden, ffn and n_q*head_dim to be multiples of 8");
     const int G = m.n_q_heads / m.n_kv_heads;
-    if (G != 1 && G != 2 && G != 4 && G != 8)
-      return fail(HARLI_ERR_INVALID, "ctx_create: query/KV head ratio %d is not supported", G);
+    if (G < 1 || G > 8 || (m.head_dim == 64 && G != 1 && G != 2 && G != 4))
+      return fail(HARLI_ERR_INVALID, "ctx_create: query/KV head ratio %d is not supported at head_dim %d", G, m.head_dim);
   }
   KvGeom geom;
   harli_pool_geom(pool, &geom);
@@ -96,6 +96,10 @@ extern "C" harli_status harli_ctx_create(const harli_model_cfg* cfg, const harli
     }
     d.g1 = lw.g1;
     d.g2 = lw.g2;
+    d.bias[0] = lw.bq;
+    d.bias[1] = lw.bk;
+    d.bias[2] = lw.bv;
+    d.b16[0] = d.b16[1] = d.b16[2] = nullptr;
   }
   c->emb = w->emb;
   c->g_final = w->g_final;

@@ -56,6 +56,7 @@ struct SkinnyArgs {
   char* slab;
   KvGeom geom;
   int* err_flag;
+  const float* bias[3];  // q, k, v biases (fp32, indexed by output row of that projection) or null
   // RESID
   const float* res;
   float* out;
@@ -126,11 +127,17 @@ __global__ void __launch_bounds__(TW * KW * 64) k_skinny(SkinnyArgs a) {
   float2 pre_cs[4];
   float4 pre_res = make_float4(0.f, 0.f, 0.f, 0.f), pre_g = make_float4(0.f, 0.f, 0.f, 0.f);
   int pre_page = -1, pre_slot = 0;
+  float4 pre_b0 = make_float4(0.f, 0.f, 0.f, 0.f), pre_b1 = make_float4(0.f, 0.f, 0.f, 0.f);  // biases of the two half tiles
 #pragma unroll
   for (int e = 0; e < 4; ++e) pre_cs[e] = make_float2(1.f, 0.f);
   if (active) {
     if (MODE != MODE_RESID) pre_ssq = a.ssq_in[jb];
     if (MODE == MODE_QKV) {
+      if (a.bias[which]) {  // rows hl*d + pidx*16 + 4g + e and the same + d/2; d % 32 == 0 keeps them 16-byte aligned
+        const float* bp = a.bias[which] + hl * a.d + pidx * 16 + 4 * g;
+        pre_b0 = *reinterpret_cast<const float4*>(bp);
+        pre_b1 = *reinterpret_cast<const float4*>(bp + (a.d >> 1));
+      }
       if (which != 2) {
         const float* cs = a.rope + ((size_t)jb * (a.d >> 1) + pidx * 16 + 4 * g) * 2;
 #pragma unroll
@@ -211,9 +218,10 @@ __global__ void __launch_bounds__(TW * KW * 64) k_skinny(SkinnyArgs a) {
       const int half = a.d >> 1;
       const int idx0 = pidx * 16 + 4 * g;  // rotation index of v[.][0]
       float r0[4], r1[4];
+      const float b0[4] = {pre_b0.x, pre_b0.y, pre_b0.z, pre_b0.w}, b1[4] = {pre_b1.x, pre_b1.y, pre_b1.z, pre_b1.w};
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        const float a0 = v[0][e] * rho, a1 = v[TW - 1][e] * rho;
+        const float a0 = v[0][e] * rho + b0[e], a1 = v[TW - 1][e] * rho + b1[e];
         if (which != 2) {
           const float2 cs = pre_cs[e];
           r0[e] = a0 * cs.x - a1 * cs.y;
@@ -700,12 +708,17 @@ extern "C" harli_status harli_decode_step(harli_ctx* c, const harli_decode_batch
     a.d = d;
     a.slab = c->slab;
     a.geom = c->geom;
+    for (int t = 0; t < 3; ++t) a.bias[t] = lw.bias[t];
     dispatch_skinny<MODE_QKV, 2, 2>(a, (m.n_q_heads + 2 * m.n_kv_heads) * (d / 32), st);
     // --- attention
     if (d == 128 && G == 1) launch_attn<128, 1, 256>(c, b, l, st);
     else if (d == 128 && G == 2) launch_attn<128, 2, 256>(c, b, l, st);
     else if (d == 128 && G == 4) launch_attn<128, 4, 128>(c, b, l, st);
     else if (d == 128 && G == 8) launch_attn<128, 8, 128>(c, b, l, st);
+    else if (d == 128 && G == 3) launch_attn<128, 3, 128>(c, b, l, st);
+    else if (d == 128 && G == 5) launch_attn<128, 5, 128>(c, b, l, st);
+    else if (d == 128 && G == 6) launch_attn<128, 6, 128>(c, b, l, st);
+    else if (d == 128 && G == 7) launch_attn<128, 7, 128>(c, b, l, st);
     else if (d == 64 && G == 1) launch_attn<64, 1, 256>(c, b, l, st);
     else if (d == 64 && G == 2) launch_attn<64, 2, 256>(c, b, l, st);
     else if (d == 64 && G == 4) launch_attn<64, 4, 256>(c, b, l, st);

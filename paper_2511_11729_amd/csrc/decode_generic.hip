@@ -74,7 +74,8 @@ __global__ void __launch_bounds__(256) g_linear(const float* h, const float* W, 
 
 // rotary embedding of q (in place) and k at position kv_len[b]; k and v appended to the page of that position.
 // One workgroup per sequence; pair (i, i + d/2) of every head, angle pos * base^(-2i/d) evaluated in double.
-__global__ void __launch_bounds__(256) g_rope_append(float* q, const float* k, const float* v, const int* kv_len,
+__global__ void __launch_bounds__(256) g_rope_append(float* q, const float* k, const float* v, const float* bq, const float* bk,
+                                                     const float* bv, const int* kv_len,
                                                      const int* page_table, int max_pages, int layer, int n_q, int n_kv,
                                                      int d, const double* inv_freq, char* slab, KvGeom geom, int* err_flag) {
   const int b = blockIdx.x, tid = threadIdx.x, half = d / 2;
@@ -88,7 +89,8 @@ __global__ void __launch_bounds__(256) g_rope_append(float* q, const float* k, c
     const double ang = (double)pos * inv_freq[i];
     const float cs = (float)cos(ang), sn = (float)sin(ang);
     float* p = q + ((size_t)b * n_q + hd) * d;
-    const float a = p[i], c = p[i + half];
+    float a = p[i], c = p[i + half];
+    if (bq) a += bq[hd * d + i], c += bq[hd * d + i + half];  // the bias precedes the rotation
     p[i] = a * cs - c * sn;
     p[i + half] = c * cs + a * sn;
   }
@@ -101,13 +103,14 @@ __global__ void __launch_bounds__(256) g_rope_append(float* q, const float* k, c
     const double ang = (double)pos * inv_freq[i];
     const float cs = (float)cos(ang), sn = (float)sin(ang);
     const float* p = k + ((size_t)b * n_kv + hd) * d;
-    const float a = p[i], c = p[i + half];
+    float a = p[i], c = p[i + half];
+    if (bk) a += bk[hd * d + i], c += bk[hd * d + i + half];
     const size_t o = ((size_t)hd * geom.page_tokens + slot) * d;
     kp[o + i] = a * cs - c * sn;
     kp[o + i + half] = c * cs + a * sn;
     const float* pv = v + ((size_t)b * n_kv + hd) * d;
-    vp[o + i] = pv[i];
-    vp[o + i + half] = pv[i + half];
+    vp[o + i] = pv[i] + (bv ? bv[hd * d + i] : 0.f);
+    vp[o + i + half] = pv[i + half] + (bv ? bv[hd * d + i + half] : 0.f);
   }
 }
 
@@ -229,7 +232,7 @@ harli_status decode_step_f32(harli_ctx* c, const harli_decode_batch* b, hipStrea
     linear(h, lw.w[0], nullptr, q, B, QD, H, st);
     linear(h, lw.w[1], nullptr, w.fk, B, KVD, H, st);
     linear(h, lw.w[2], nullptr, w.fv, B, KVD, H, st);
-    hipLaunchKernelGGL(g_rope_append, dim3(B), dim3(256), 0, st, q, w.fk, w.fv, b->kv_len, b->page_table, b->max_pages, l,
+    hipLaunchKernelGGL(g_rope_append, dim3(B), dim3(256), 0, st, q, w.fk, w.fv, lw.bias[0], lw.bias[1], lw.bias[2], b->kv_len, b->page_table, b->max_pages, l,
                        m.n_q_heads, m.n_kv_heads, d, w.inv_freq, c->slab, c->geom, w.err_flag);
     hipLaunchKernelGGL(g_attention, dim3(m.n_q_heads, B), dim3(256), 0, st, q, b->kv_len, b->page_table, b->max_pages, l,
                        m.n_q_heads, m.n_kv_heads, d, c->slab, c->geom, w.scores, m.max_seq_len, o, w.err_flag);

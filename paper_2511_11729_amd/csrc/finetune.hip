@@ -179,6 +179,8 @@ harli_status proj_fwd(harli_ctx* c, const LayerDev& L, int t, const bf* xin, int
   proj_shape(c->cfg, t, &out, &in);
   FtWs& w = state(c)->ws;
   add_seg(g, xin, in, static_cast<const bf*>(L.w16[t]), in, in);
+  // a frozen bias rides as eight more contraction columns: ones on the input side, (b, 0, ..., 0) on the weight side
+  if (t < 3 && L.b16[t]) add_seg(g, static_cast<const bf*>(c->ones16), 8, static_cast<const bf*>(L.b16[t]), 8, 8);
   if (adapted(c, t)) {
     const int r = c->lora.rank;
     // ws.At[t] = A^T [r, in] and ws.Bt[t] = B^T [out, r] were made by convert_adapters at the top of the call
@@ -267,6 +269,16 @@ void release_saved(harli_ctx* c, harli_saved* sv, hipStream_t st, bool with_even
 namespace harli {
 void free_finetune_state(harli_ctx* c) {
   for (LayerDev& L : c->layers)
+    for (int t = 0; t < 3; ++t)
+      if (L.b16[t]) {
+        (void)hipFree(L.b16[t]);
+        L.b16[t] = nullptr;
+      }
+  if (c->ones16) {
+    (void)hipFree(c->ones16);
+    c->ones16 = nullptr;
+  }
+  for (LayerDev& L : c->layers)
     for (int t = 0; t < kTargets; ++t)
       if (L.wt[t]) {
         (void)hipFree(L.wt[t]);
@@ -318,6 +330,28 @@ extern "C" harli_status harli_lora_attach(harli_ctx* c, const harli_lora_cfg* cf
         }
       }
     }
+  }
+  // biases of q, k, v in the compute element ([out, 8], bias in column 0) and the column of ones they multiply
+  bool any_bias = false;
+  for (int l = 0; l < c->cfg.n_layers; ++l) {
+    LayerDev& L = c->layers[l];
+    for (int t = 0; t < 3; ++t) {
+      if (!L.bias[t] || L.b16[t]) continue;
+      any_bias = true;
+      int out, in;
+      proj_shape(c->cfg, t, &out, &in);
+      std::vector<float> hb(out);
+      HARLI_HIP(hipMemcpy(hb.data(), L.bias[t], (size_t)out * 4, hipMemcpyDeviceToHost));
+      std::vector<unsigned short> h16((size_t)out * 8, 0);
+      for (int n = 0; n < out; ++n) h16[(size_t)n * 8] = host_to_elem(hb[n]);
+      HARLI_HIP(hipMalloc(&L.b16[t], h16.size() * 2));
+      HARLI_HIP(hipMemcpy(L.b16[t], h16.data(), h16.size() * 2, hipMemcpyHostToDevice));
+    }
+  }
+  if (any_bias && !c->ones16) {
+    std::vector<unsigned short> ones((size_t)c->cfg.max_ft_tokens * 8, host_to_elem(1.0f));
+    HARLI_HIP(hipMalloc(&c->ones16, ones.size() * 2));
+    HARLI_HIP(hipMemcpy(c->ones16, ones.data(), ones.size() * 2, hipMemcpyHostToDevice));
   }
   HARLI_HIP(hipDeviceSynchronize());
   if (!c->ft_ws) c->ft_ws = new FtState;

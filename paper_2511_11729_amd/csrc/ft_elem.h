@@ -21,4 +21,19 @@ __device__ __forceinline__ unsigned PACK2(float lo, float hi) { return pack_bf2(
 __device__ __forceinline__ void UNPACK8(const uint4& u, float* f) { unpack8(u, f); }
 #endif
 constexpr bool kFtHalf = HARLI_FT_HALF != 0;
+
+// host-side rounding of a float to the compute element (round to nearest even), for small tables built at set-up
+inline unsigned short host_to_elem(float f) {
+#if HARLI_FT_HALF
+  const _Float16 h = static_cast<_Float16>(f);
+  unsigned short u;
+  __builtin_memcpy(&u, &h, 2);
+  return u;
+#else
+  unsigned u;
+  __builtin_memcpy(&u, &f, 4);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return static_cast<unsigned short>(u >> 16);
+#endif
+}
 }  // namespace harli

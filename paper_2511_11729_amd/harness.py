@@ -81,6 +81,9 @@ class LayerHarness:
             del img
         layer = {n: dev_bf16(self.W_np[n]) for n in ("wq", "wk", "wv", "wo", "wg", "wu", "wd")}
         layer["g1"], layer["g2"] = dev_f32(self.W_np["g1"]), dev_f32(self.W_np["g2"])
+        for bn in ("bq", "bk", "bv"):
+            if bn in self.W_np:
+                layer[bn] = dev_f32(self.W_np[bn])
         self.layer = layer
         self.ctx = hb.Context(self.pool, n_layers=1, hidden=m.hidden, n_q_heads=m.n_q, n_kv_heads=m.n_kv, head_dim=m.head_dim,
                               ffn=m.ffn, rms_eps=m.rms_eps, rope_base=m.rope_base, dtype=hb.HARLI_BF16, max_batch=cap_b,

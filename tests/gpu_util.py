@@ -105,6 +105,9 @@ class DecodeCase:
         for L in self.layers_np:
             dl = {n: to_dev(L[n], m.dtype) for n in ("wq", "wk", "wv", "wo", "wg", "wu", "wd")}
             dl["g1"], dl["g2"] = f32_dev(L["g1"]), f32_dev(L["g2"])
+            for bn in ("bq", "bk", "bv"):
+                if bn in L:
+                    dl[bn] = f32_dev(L[bn])
             self.layers_dev.append(dl)
         kw = {}
         if full_model:
@@ -194,6 +197,9 @@ class FinetuneCase:
                             kv_row_bytes=m.kv_row_bytes, small_pool_bytes=small_pool_bytes, kv_reserve_chunks=1)
         self.layer_dev = {n: to_dev(self.W_np[n], m.dtype) for n in ("wq", "wk", "wv", "wo", "wg", "wu", "wd")}
         self.layer_dev["g1"], self.layer_dev["g2"] = f32_dev(self.W_np["g1"]), f32_dev(self.W_np["g2"])
+        for bn in ("bq", "bk", "bv"):
+            if bn in self.W_np:
+                self.layer_dev[bn] = f32_dev(self.W_np[bn])
         self.ctx = hb.Context(self.pool, n_layers=m.n_layers, hidden=m.hidden, n_q_heads=m.n_q, n_kv_heads=m.n_kv,
                               head_dim=m.head_dim, ffn=m.ffn, rms_eps=m.rms_eps, rope_base=m.rope_base,
                               dtype=hb.HARLI_BF16 if m.dtype == "bf16" else hb.HARLI_F32, max_batch=1, max_seq_len=16,

@@ -59,7 +59,8 @@ def test_batch_above_64_runs_in_passes():
     run_case(w, m, [7 + (i * 5) % 90 for i in range(100)], block_bytes=64 << 10)
 
 
-@pytest.mark.parametrize("n_q,n_kv,d", [(8, 2, 64), (8, 8, 128), (8, 4, 128), (8, 2, 128), (8, 1, 128)])
+@pytest.mark.parametrize("n_q,n_kv,d", [(8, 2, 64), (8, 8, 128), (8, 4, 128), (8, 2, 128), (8, 1, 128), (6, 2, 128), (5, 1, 128),
+                                        (6, 1, 128), (7, 1, 128)])
 def test_head_layouts(n_q, n_kv, d):
     """GQA ratios 1, 2, 4, 8 and both head sizes."""
     w, m = variant(0, dtype="bf16", hidden=n_q * d // 2, n_q=n_q, n_kv=n_kv, head_dim=d, ffn=320)
@@ -229,3 +230,21 @@ def test_config4_width_layer_gqa_long_context():
     lengths = wl.draw_lengths(w)
     case, stats = run_case(w, m, lengths)
     print("config 4 layer decode parity: max-abs ratio %.2e, rel-Fro %.2e, lengths %d..%d" % (stats + (lengths.min(), lengths.max())))
+
+
+def test_config5_width_layer_biases_and_groups_of_seven():
+    """Qwen2.5-7B-class layer (hidden 3584, 28 query / 4 KV heads, ffn 18944, RoPE base 1e6, biases on q, k, v), batch 8,
+    log-normal lengths."""
+    w, m = variant(5, n_layers=1)
+    assert m.qkv_bias
+    lengths = wl.draw_lengths(w)
+    case, stats = run_case(w, m, lengths)
+    assert "bq" in case.layers_np[0]
+    print("config 5 layer decode parity: max-abs ratio %.2e, rel-Fro %.2e, lengths %d..%d" % (stats + (lengths.min(), lengths.max())))
+
+
+def test_biases_small_shapes_bf16_and_fp32():
+    """Biases with two layers, ragged lengths, both storage types (the fp32 path adds them in its rotary kernel)."""
+    for dtype in ("bf16", "f32"):
+        w, m = variant(0, dtype=dtype, n_layers=2, qkv_bias=True)
+        run_case(w, m, [0, 5, 16, 31, 77])

@@ -139,3 +139,21 @@ def test_config4_width_layer_gqa_rank32():
     m = dataclasses.replace(w.model, n_layers=1)
     case = FinetuneCase(w, m, w.lora, wl.FinetuneCfg(4, 512))
     check(case, "config 4 layer")
+
+
+def test_config5_width_layer_biases_and_groups_of_seven():
+    """Qwen2.5-7B-class layer (hidden 3584, 28 query / 4 KV heads, ffn 18944, biases on q, k, v), r 16 on q,k,v,o,
+    2 x 512 tokens."""
+    w = wl.workload(5)
+    m = dataclasses.replace(w.model, n_layers=1)
+    case = FinetuneCase(w, m, w.lora, wl.FinetuneCfg(2, 512))
+    assert "bq" in case.W_np
+    check(case, "config 5 layer")
+
+
+def test_biases_small_shape_fp32_storage_and_bf16():
+    for dtype in ("bf16", "f32"):
+        w = wl.workload(0)
+        m = dataclasses.replace(w.model, dtype=dtype, qkv_bias=True)
+        case = FinetuneCase(w, m, wl.LoraCfg(8, 16.0, ("q", "k", "v", "o")), wl.FinetuneCfg(2, 128))
+        check(case, "tiny layer with biases, %s storage" % dtype)

@@ -44,6 +44,9 @@ class ModelCase:
         for L in self.layers_np:
             dl = {n: to_dev(L[n], "bf16") for n in ("wq", "wk", "wv", "wo", "wg", "wu", "wd")}
             dl["g1"], dl["g2"] = f32_dev(L["g1"]), f32_dev(L["g2"])
+            for bn in ("bq", "bk", "bv"):
+                if bn in L:
+                    dl[bn] = f32_dev(L[bn])
             self.layers_dev.append(dl)
         self.emb_dev, self.gf_dev, self.wlm_dev = to_dev(self.ex["emb"], "bf16"), f32_dev(self.ex["gf"]), to_dev(self.ex["wlm"], "bf16")
         self.ctx = hb.Context(self.pool, n_layers=n_layers, hidden=m.hidden, n_q_heads=m.n_q, n_kv_heads=m.n_kv,
