@@ -193,17 +193,28 @@ harli_status proj_fwd(harli_ctx* c, const LayerDev& L, int t, const bf* xin, int
 // adapter gradients of one projection given dy (bf16 [T, out]) and its input xin (bf16 [T, in]);
 // leaves gs = s * dy . B^T in ws.gs[slot]: the caller adds (gs, ws.An[t])
 // to its dx GEMM as one more K segment (dx += gs . A^T)
-harli_status proj_grads(harli_ctx* c, const LayerDev& L, int t, int slot, const bf* dy, const bf* xin, int T,
-                        const harli_saved* sv, float* const* dA, float* const* dB, hipStream_t st) {
-  int out, in;
-  proj_shape(c->cfg, t, &out, &in);
+// One or more projections that read the same input xin: their 2 n gradient products go out as one pair of launches.
+harli_status proj_grads_group(harli_ctx* c, int n, const int* ts, const int* slots, const bf* const* dys, const bf* xin, int T,
+                              const harli_saved* sv, float* const* dA, float* const* dB, hipStream_t st) {
   FtWs& w = state(c)->ws;
   const int r = c->lora.rank;
-  // ws.An[t] = A [in, r] and ws.Bn[t] = B [r, out] in the compute element were made by convert_adapters
-  ft_skinny_nt(dy, out, w.Bn[t], out, w.gs[slot], r, T, r, out, lscale(c), st);     // gs = s * dy . B^T   (carries sigma)
-  ft_lora_grad(xin, in, w.gs[slot], r, dA[t], r, 1, T, in, r, w.scale + 1, w.gpart, st);     // dA += x^T gs / sigma
-  ft_lora_grad(dy, out, sv->us[t], r, dB[t], 1, out, T, out, r, w.scale + 1, w.gpart, st);  // dB += us^T dy / sigma
+  LoraGradJobs jobs{};
+  for (int i = 0; i < n; ++i) {
+    const int t = ts[i];
+    int out, in;
+    proj_shape(c->cfg, t, &out, &in);
+    // ws.An[t] = A [in, r] and ws.Bn[t] = B [r, out] in the compute element were made by convert_adapters
+    ft_skinny_nt(dys[i], out, w.Bn[t], out, w.gs[slots[i]], r, T, r, out, lscale(c), st);  // gs = s * dy . B^T   (carries sigma)
+    jobs.j[jobs.n++] = LoraGradJob{xin, in, w.gs[slots[i]], r, dA[t], r, 1, in, 0, 0, 0, 0};      // dA += x^T gs / sigma
+    jobs.j[jobs.n++] = LoraGradJob{dys[i], out, sv->us[t], r, dB[t], 1, out, out, 0, 0, 0, 0};    // dB += us^T dy / sigma
+  }
+  ft_lora_grad_multi(jobs, T, r, w.scale + 1, w.gpart, st);
   return HARLI_OK;
+}
+harli_status proj_grads(harli_ctx* c, const LayerDev& L, int t, int slot, const bf* dy, const bf* xin, int T,
+                        const harli_saved* sv, float* const* dA, float* const* dB, hipStream_t st) {
+  (void)L;
+  return proj_grads_group(c, 1, &t, &slot, &dy, xin, T, sv, dA, dB, st);
 }
 
 harli_status check_call(harli_ctx* c, int layer, int Bf, int S, const char* who) {
@@ -564,11 +575,14 @@ extern "C" harli_status harli_lora_bwd(harli_ctx* c, int32_t layer, const float*
     GemmArgs g = plain_gemm(T, D.H);  // dh2 = da Wg + du Wu
     add_seg(g, w.da, D.F, static_cast<const bf*>(L.wt[4]), D.F, D.F);
     add_seg(g, w.du, D.F, static_cast<const bf*>(L.wt[5]), D.F, D.F);
-    for (int t = 4; t <= 5; ++t)
-      if (adapted(c, t)) {  // dh2 += gs_t A_t^T as one more K segment
-        RUNB(proj_grads(c, L, t, t - 4, t == 4 ? w.da : w.du, sv->h2, T, sv, dA, dB, st));
-        add_seg(g, w.gs[t - 4], D.r, w.An[t], D.r, D.r);
-      }
+    {
+      int ts[2], slots[2], n = 0;
+      const bf* dys[2];
+      for (int t = 4; t <= 5; ++t)
+        if (adapted(c, t)) ts[n] = t, slots[n] = t - 4, dys[n] = t == 4 ? w.da : w.du, ++n;
+      if (n) RUNB(proj_grads_group(c, n, ts, slots, dys, sv->h2, T, sv, dA, dB, st));
+      for (int i = 0; i < n; ++i) add_seg(g, w.gs[slots[i]], D.r, w.An[ts[i]], D.r, D.r);  // dh2 += gs_t A_t^T as one more K segment
+    }
     g.Cf = w.dh2; g.ldcf = D.H;
     RUNB(gemm_launch(g, 1, st));
   }
@@ -684,12 +698,15 @@ extern "C" harli_status harli_lora_bwd(harli_ctx* c, int32_t layer, const float*
     add_seg(g, w.dq, D.QD, static_cast<const bf*>(L.wt[0]), D.QD, D.QD);
     add_seg(g, dk, D.KVD, static_cast<const bf*>(L.wt[1]), D.KVD, D.KVD);
     add_seg(g, dv, D.KVD, static_cast<const bf*>(L.wt[2]), D.KVD, D.KVD);
-    const bf* dys[3] = {w.dq, dk, dv};
-    for (int t = 0; t < 3; ++t)
-      if (adapted(c, t)) {  // dh += gs_t A_t^T as one more K segment
-        RUNB(proj_grads(c, L, t, t, dys[t], sv->h, T, sv, dA, dB, st));
-        add_seg(g, w.gs[t], D.r, w.An[t], D.r, D.r);
-      }
+    const bf* all[3] = {w.dq, dk, dv};
+    {
+      int ts[3], slots[3], n = 0;
+      const bf* dys[3];
+      for (int t = 0; t < 3; ++t)
+        if (adapted(c, t)) ts[n] = t, slots[n] = t, dys[n] = all[t], ++n;
+      if (n) RUNB(proj_grads_group(c, n, ts, slots, dys, sv->h, T, sv, dA, dB, st));
+      for (int i = 0; i < n; ++i) add_seg(g, w.gs[slots[i]], D.r, w.An[ts[i]], D.r, D.r);  // dh += gs_t A_t^T as one more K segment
+    }
     g.Cf = w.dh; g.ldcf = D.H;
     RUNB(gemm_launch(g, 1, st));
   }

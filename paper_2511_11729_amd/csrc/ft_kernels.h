@@ -59,6 +59,26 @@ void ft_skinny_nt(const bf* X, long long ldx, const bf* Bm, long long ldb, bf* C
 // one of sj, sr equal to 1.  `part` is scratch of ft_lora_grad_ws_floats(J, R) floats; G is read and written
 // without atomics, so no other work may update it concurrently.
 size_t ft_lora_grad_ws_floats(int J, int R);
+// Several such products in one pair of launches (their workgroups run side by side instead of one short kernel after
+// the other): job i is G_i[j*sj + r*sr] += out_mul * sum_t X_i[t][j] * U_i[t][r] with its own J; same T and R for all.
+// The host fills X, ldx, U, ldu, G, sj, sr, J; the remaining fields are set by ft_lora_grad_multi.
+constexpr int kLoraGradMaxJobs = 8;
+struct LoraGradJob {
+  const bf* X;
+  long long ldx;
+  const bf* U;
+  long long ldu;
+  float* G;
+  long long sj, sr;
+  int J;
+  int jt, nch, tpm;    // column tiles, token chunks, tokens per chunk
+  long long part_off;  // this job's partial sums inside the scratch
+};
+struct LoraGradJobs {
+  int n;
+  LoraGradJob j[kLoraGradMaxJobs];
+};
+void ft_lora_grad_multi(LoraGradJobs& jobs, int T, int R, const float* out_mul, float* part, hipStream_t st);
 void ft_lora_grad(const bf* X, long long ldx, const bf* U, long long ldu, float* G, long long sj, long long sr, int T, int J,
                   int R, const float* out_mul, float* part, hipStream_t st);
 // sum GQA query-head groups: dk[T][n_kv*d] = sum_g dkq[T][(c*G+g)*d + e]

@@ -447,6 +447,113 @@ __global__ void __launch_bounds__(256) k_lora_grad_part(const bf* X, long long l
 
 #endif
 
+
+// MFMA version of pass 1 for 16-byte aligned operands (J, ldx, ldu multiples of 8).  The product contracts over the
+// ROW index of both operands (part[r][j] = sum_t X[t][j] U[t][r]), the layout MFMA operands do not come in: a lane must
+// hold eight consecutive t of one column.  gfx950's transposing LDS read does that turn on the way out of LDS: with
+// the tiles stored as they are in memory ([t][j], [t][r]) and lane q of every 16-lane group pointing at row q / 4,
+// columns 4 (q % 4) .. + 3 of a 4 x 16 block, ds_read_b64_tr_b16 leaves lane i of the group with column i of the four
+// rows -- two such reads give a lane its eight t of v_mfma_f32_16x16x32.  Workgroup: 256 columns j (64 per wave, four
+// 16-column tiles) x all R ranks x one token chunk, 32 tokens per step through LDS.
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned lg_u32x4 __attribute__((ext_vector_type(4)));  // native vector: arrays of HIP's uint4 struct were left in scratch memory
+constexpr int kLmJ = 256, kLmT = 32, kLmPF = 4, kLmXS = kLmJ + 8;  // tile sizes, steps in flight; padded row of the X tile (halves)
+
+template <int R>
+__global__ void __launch_bounds__(256) k_lora_grad_mfma(LoraGradJobs jobs, float* part_all, int T) {
+  const LoraGradJob& jb = jobs.j[blockIdx.z];
+  if ((int)blockIdx.x >= jb.jt || (int)blockIdx.y >= jb.nch) return;  // the grid is sized for the largest job
+  const bf* X = jb.X;
+  const bf* U = jb.U;
+  const long long ldx = jb.ldx, ldu = jb.ldu;
+  const int J = jb.J, tpc = jb.tpm;
+  float* part = part_all + jb.part_off;
+  constexpr int RP = R < 16 ? 16 : R;  // rank padded to an MFMA tile (the padding columns of the U tile stay zero)
+  constexpr int NT = RP / 16;          // 16-rank tiles
+  constexpr int US = RP + 8;           // padded row of the U tile (halves)
+  __shared__ __align__(16) unsigned short xs[kLmT][kLmXS];
+  __shared__ __align__(16) unsigned short us[kLmT][US];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int j0 = blockIdx.x * kLmJ;
+  const int c0 = blockIdx.y * tpc, c1 = min(T, c0 + tpc);
+  f32x4 acc[4][NT];
+#pragma unroll
+  for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int i = tid; i < kLmT * US; i += 256) (&us[0][0])[i] = 0;  // zero once: rows and columns never written stay zero
+
+  // staging coordinates: X tile = 32 rows x 32 chunks of 16 bytes, four per thread; U tile = 32 rows x R / 8 chunks
+  const int xc = tid & 31, xr = tid >> 5;
+  const int xcol = min(j0 + xc * 8, J - 8);  // columns past J are loaded from a valid place and never stored
+  constexpr int UCH = R / 8;
+  const int uc = tid % UCH, ur = tid / UCH;  // threads with ur >= 32 stage nothing
+  // fragment coordinates: 16-lane group g covers t = 8g .. 8g+7; lane q of it points at row q / 4, columns 4 (q % 4)
+  const int g = lane >> 4, q = lane & 15;
+  const int frow = 8 * g + (q >> 2), fcol = 4 * (q & 3);
+
+  // kLmPF steps of loads are issued together (the MFMAs of a step take a fraction of a load's latency, so one step
+  // of prefetch would leave every step waiting for memory)
+  for (int tb = c0; tb < c1; tb += kLmT * kLmPF) {
+    lg_u32x4 xv[kLmPF][4], uv[kLmPF];
+#pragma unroll
+    for (int p = 0; p < kLmPF; ++p) {
+      const int t0 = tb + p * kLmT;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        xv[p][i] = *reinterpret_cast<const lg_u32x4*>(X + (long long)min(t0 + xr + 8 * i, T - 1) * ldx + xcol);
+      // rows past the chunk are fetched from a valid row and zeroed below: they add nothing
+      uv[p] = *reinterpret_cast<const lg_u32x4*>(U + (long long)min(t0 + min(ur, kLmT - 1), T - 1) * ldu + uc * 8);
+    }
+#pragma unroll
+    for (int p = 0; p < kLmPF; ++p) {
+      const int t0 = tb + p * kLmT;
+      if (t0 >= c1) break;  // uniform
+      __syncthreads();      // the previous step's fragments have been read
+#pragma unroll
+      for (int i = 0; i < 4; ++i) *reinterpret_cast<lg_u32x4*>(&xs[xr + 8 * i][xc * 8]) = xv[p][i];
+      if (ur < kLmT) *reinterpret_cast<lg_u32x4*>(&us[ur][uc * 8]) = t0 + ur < c1 ? uv[p] : lg_u32x4{0u, 0u, 0u, 0u};
+      __syncthreads();
+      s16x8 bfr[NT];
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(&us[frow][nt * 16 + fcol]));
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(&us[frow + 4][nt * 16 + fcol]));
+        bfr[nt] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+      }
+#pragma unroll
+      for (int mt = 0; mt < 4; ++mt) {
+        const int col = wave * 64 + mt * 16 + fcol;
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(&xs[frow][col]));
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(&xs[frow + 4][col]));
+        const s16x8 afr = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+#if HARLI_FT_HALF
+          acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, afr), __builtin_bit_cast(f16x8, bfr[nt]), acc[mt][nt], 0, 0, 0);
+#else
+          acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, afr), __builtin_bit_cast(bf16x8, bfr[nt]), acc[mt][nt], 0, 0, 0);
+#endif
+        }
+      }
+    }
+  }
+  // lane holds out[j = tile + 4 (lane / 16) + v][r = tile + lane % 16], v = 0..3: four consecutive j of one rank
+#pragma unroll
+  for (int mt = 0; mt < 4; ++mt) {
+    const int j = j0 + wave * 64 + mt * 16 + 4 * g;
+    if (j >= J) continue;  // J % 8 == 0: the four columns are in or out together
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      const int r = nt * 16 + q;
+      if (r < R)
+        *reinterpret_cast<float4*>(part + (long long)blockIdx.y * R * J + (long long)r * J + j) =
+            make_float4(acc[mt][nt][0], acc[mt][nt][1], acc[mt][nt][2], acc[mt][nt][3]);
+    }
+  }
+}
+
 // G[j*sj + r*sr] += out_mul * sum_c part[c][r][j]: one thread per (r, j), lanes along j (the reads of part, 2 x
 // nchunk times the volume of G, are the contiguous side)
 __global__ void __launch_bounds__(256) k_lora_grad_reduce(const float* part, int nchunk, float* G, long long sj, long long sr,
@@ -458,6 +565,19 @@ __global__ void __launch_bounds__(256) k_lora_grad_reduce(const float* part, int
 #pragma unroll 8
   for (int c = 0; c < nchunk; ++c) sum += part[c * RJ + i];
   float* g = G + (long long)j * sj + (long long)r * sr;
+  *g += sum * (out_mul ? *out_mul : 1.f);
+}
+
+__global__ void __launch_bounds__(256) k_lora_grad_reduce_multi(LoraGradJobs jobs, const float* part_all, int R, const float* out_mul) {
+  const LoraGradJob& jb = jobs.j[blockIdx.y];
+  const long long RJ = (long long)R * jb.J;
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= RJ) return;
+  const int r = (int)(i / jb.J), j = (int)(i - (long long)r * jb.J);
+  const float* part = part_all + jb.part_off;
+  float sum = 0.f;
+  for (int c = 0; c < jb.nch; ++c) sum += part[c * RJ + i];
+  float* g = jb.G + (long long)j * jb.sj + (long long)r * jb.sr;
   *g += sum * (out_mul ? *out_mul : 1.f);
 }
 
@@ -552,7 +672,11 @@ void ft_skinny_nt(const bf* X, long long ldx, const bf* Bm, long long ldb, bf* C
   else if (nt == 2) hipLaunchKernelGGL(k_skinny_nt<2>, grid, blk, 0, st, X, ldx, Bm, ldb, C, ldc, M, N, K, alpha);
   else hipLaunchKernelGGL(k_skinny_nt<4>, grid, blk, 0, st, X, ldx, Bm, ldb, C, ldc, M, N, K, alpha);
 }
-size_t ft_lora_grad_ws_floats(int J, int R) { return (size_t)kLgMaxChunks * J * R; }
+// floats of partial sums one job of the MFMA path can need: nch * J with nch <= max(1, 512 / column tiles)
+static size_t lora_grad_job_floats(int J, int R) { return (size_t)std::max(512 * kLmJ, (J + kLmJ - 1) / kLmJ * kLmJ) * R; }
+size_t ft_lora_grad_ws_floats(int J, int R) {
+  return std::max((size_t)kLgMaxChunks * J * R, (size_t)kLoraGradMaxJobs * lora_grad_job_floats(J, R));
+}
 template <int R>
 static void lora_grad_launch(const bf* X, long long ldx, const bf* U, long long ldu, float* G, long long sj, long long sr, int T,
                              int J, const float* out_mul, float* part, hipStream_t st) {
@@ -562,12 +686,53 @@ static void lora_grad_launch(const bf* X, long long ldx, const bf* U, long long 
   hipLaunchKernelGGL(k_lora_grad_reduce, dim3(nblk((long long)R * J, 256)), dim3(256), 0, st, part, nchunk, G, sj, sr, J, (long long)R * J,
                      out_mul);
 }
+static void lora_grad_vector(const LoraGradJob& b, int T, int R, const float* out_mul, float* part, hipStream_t st) {
+  if (R == 8) lora_grad_launch<8>(b.X, b.ldx, b.U, b.ldu, b.G, b.sj, b.sr, T, b.J, out_mul, part, st);
+  else if (R == 16) lora_grad_launch<16>(b.X, b.ldx, b.U, b.ldu, b.G, b.sj, b.sr, T, b.J, out_mul, part, st);
+  else if (R == 32) lora_grad_launch<32>(b.X, b.ldx, b.U, b.ldu, b.G, b.sj, b.sr, T, b.J, out_mul, part, st);
+  else lora_grad_launch<64>(b.X, b.ldx, b.U, b.ldu, b.G, b.sj, b.sr, T, b.J, out_mul, part, st);
+}
+void ft_lora_grad_multi(LoraGradJobs& jobs, int T, int R, const float* out_mul, float* part, hipStream_t st) {
+  if (jobs.n < 1) return;
+  bool aligned = (reinterpret_cast<uintptr_t>(part) & 15) == 0;
+  for (int i = 0; i < jobs.n; ++i) {
+    const LoraGradJob& b = jobs.j[i];
+    aligned = aligned && b.J % 8 == 0 && b.ldx % 8 == 0 && b.ldu % 8 == 0 &&
+              ((reinterpret_cast<uintptr_t>(b.X) | reinterpret_cast<uintptr_t>(b.U)) & 15) == 0;
+  }
+  if (!aligned) {  // the vector kernels, one job after the other (each uses the whole scratch)
+    for (int i = 0; i < jobs.n; ++i) lora_grad_vector(jobs.j[i], T, R, out_mul, part, st);
+    return;
+  }
+  // about two workgroups per compute unit per job and whole groups of steps in flight
+  int max_jt = 0, max_nch = 0, max_j = 0;
+  long long off = 0;
+  const int unit = kLmT * kLmPF;
+  for (int i = 0; i < jobs.n; ++i) {
+    LoraGradJob& b = jobs.j[i];
+    b.jt = (b.J + kLmJ - 1) / kLmJ;
+    const int want = std::min(kLgMaxChunks, std::max(1, 512 / b.jt));
+    b.tpm = std::max(unit, ((T + want - 1) / want + unit - 1) / unit * unit);
+    b.nch = (T + b.tpm - 1) / b.tpm;
+    b.part_off = off;
+    off += (long long)lora_grad_job_floats(b.J, R);
+    max_jt = std::max(max_jt, b.jt);
+    max_nch = std::max(max_nch, b.nch);
+    max_j = std::max(max_j, b.J);
+  }
+  const dim3 grid(max_jt, max_nch, jobs.n);
+  if (R == 8) hipLaunchKernelGGL(k_lora_grad_mfma<8>, grid, dim3(256), 0, st, jobs, part, T);
+  else if (R == 16) hipLaunchKernelGGL(k_lora_grad_mfma<16>, grid, dim3(256), 0, st, jobs, part, T);
+  else if (R == 32) hipLaunchKernelGGL(k_lora_grad_mfma<32>, grid, dim3(256), 0, st, jobs, part, T);
+  else hipLaunchKernelGGL(k_lora_grad_mfma<64>, grid, dim3(256), 0, st, jobs, part, T);
+  hipLaunchKernelGGL(k_lora_grad_reduce_multi, dim3(nblk((long long)R * max_j, 256), jobs.n), dim3(256), 0, st, jobs, part, R, out_mul);
+}
 void ft_lora_grad(const bf* X, long long ldx, const bf* U, long long ldu, float* G, long long sj, long long sr, int T, int J,
                   int R, const float* out_mul, float* part, hipStream_t st) {
-  if (R == 8) lora_grad_launch<8>(X, ldx, U, ldu, G, sj, sr, T, J, out_mul, part, st);
-  else if (R == 16) lora_grad_launch<16>(X, ldx, U, ldu, G, sj, sr, T, J, out_mul, part, st);
-  else if (R == 32) lora_grad_launch<32>(X, ldx, U, ldu, G, sj, sr, T, J, out_mul, part, st);
-  else lora_grad_launch<64>(X, ldx, U, ldu, G, sj, sr, T, J, out_mul, part, st);
+  LoraGradJobs jobs{};
+  jobs.n = 1;
+  jobs.j[0] = LoraGradJob{X, ldx, U, ldu, G, sj, sr, J, 0, 0, 0, 0};
+  ft_lora_grad_multi(jobs, T, R, out_mul, part, st);
 }
 void ft_sum_groups(const bf* in, bf* out, int T, int n_kv, int G, int d, hipStream_t st) {
   const long long total = (long long)T * n_kv * d;
