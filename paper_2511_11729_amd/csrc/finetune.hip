@@ -174,6 +174,22 @@ void convert_adapters(harli_ctx* c, const LayerDev& L, bool transposed, hipStrea
 }
 
 // forward of one projection: out = xin . W^T (+ us . Bt^T), us = s * xin . A kept for backward
+// us_t = s * xin . A_t for every adapted projection t of a group that reads the same input, in one launch
+void proj_us_group(harli_ctx* c, int t_first, int t_last, const bf* xin, int T, harli_saved* sv, hipStream_t st) {
+  FtWs& w = state(c)->ws;
+  const int r = c->lora.rank;
+  SkinnyNtJobs jobs{};
+  for (int t = t_first; t <= t_last; ++t) {
+    if (!adapted(c, t)) continue;
+    int out, in;
+    proj_shape(c->cfg, t, &out, &in);
+    // ws.At[t] = A^T [r, in] was made by convert_adapters at the top of the call
+    jobs.j[jobs.n++] = SkinnyNtJob{xin, in, w.At[t], in, sv->us[t], r, r, in};
+  }
+  ft_skinny_nt_multi(jobs, T, lscale(c), st);
+}
+
+// (us_t must have been made by proj_us_group)
 harli_status proj_fwd(harli_ctx* c, const LayerDev& L, int t, const bf* xin, int T, harli_saved* sv, GemmArgs& g, hipStream_t st) {
   int out, in;
   proj_shape(c->cfg, t, &out, &in);
@@ -183,8 +199,7 @@ harli_status proj_fwd(harli_ctx* c, const LayerDev& L, int t, const bf* xin, int
   if (t < 3 && L.b16[t]) add_seg(g, static_cast<const bf*>(c->ones16), 8, static_cast<const bf*>(L.b16[t]), 8, 8);
   if (adapted(c, t)) {
     const int r = c->lora.rank;
-    // ws.At[t] = A^T [r, in] and ws.Bt[t] = B^T [out, r] were made by convert_adapters at the top of the call
-    ft_skinny_nt(xin, in, w.At[t], in, sv->us[t], r, T, r, in, lscale(c), st);  // us = s * x . A
+    // ws.Bt[t] = B^T [out, r] was made by convert_adapters at the top of the call
     add_seg(g, sv->us[t], r, w.Bt[t], r, r);
   }
   return gemm_launch(g, 1, st);
@@ -199,15 +214,17 @@ harli_status proj_grads_group(harli_ctx* c, int n, const int* ts, const int* slo
   FtWs& w = state(c)->ws;
   const int r = c->lora.rank;
   LoraGradJobs jobs{};
+  SkinnyNtJobs sk{};
   for (int i = 0; i < n; ++i) {
     const int t = ts[i];
     int out, in;
     proj_shape(c->cfg, t, &out, &in);
     // ws.An[t] = A [in, r] and ws.Bn[t] = B [r, out] in the compute element were made by convert_adapters
-    ft_skinny_nt(dys[i], out, w.Bn[t], out, w.gs[slots[i]], r, T, r, out, lscale(c), st);  // gs = s * dy . B^T   (carries sigma)
+    sk.j[sk.n++] = SkinnyNtJob{dys[i], out, w.Bn[t], out, w.gs[slots[i]], r, r, out};  // gs = s * dy . B^T   (carries sigma)
     jobs.j[jobs.n++] = LoraGradJob{xin, in, w.gs[slots[i]], r, dA[t], r, 1, in, 0, 0, 0, 0};      // dA += x^T gs / sigma
     jobs.j[jobs.n++] = LoraGradJob{dys[i], out, sv->us[t], r, dB[t], 1, out, out, 0, 0, 0, 0};    // dB += us^T dy / sigma
   }
+  ft_skinny_nt_multi(sk, T, lscale(c), st);
   ft_lora_grad_multi(jobs, T, r, w.scale + 1, w.gpart, st);
   return HARLI_OK;
 }
@@ -444,6 +461,7 @@ extern "C" harli_status harli_lora_fwd(harli_ctx* c, int32_t layer, const float*
   const int T = D.T;
   convert_adapters(c, L, true, st);
   ft_rmsnorm_fwd(X, L.g1, sv->h, sv->rho1, T, D.H, m.rms_eps, st);
+  proj_us_group(c, 0, 2, sv->h, T, sv, st);
   {
     GemmArgs g = plain_gemm(T, D.QD);
     g.Cb = sv->q; g.ldcb = D.QD;
@@ -495,9 +513,11 @@ extern "C" harli_status harli_lora_fwd(harli_ctx* c, int32_t layer, const float*
   {  // x1 = X + o Wo^T
     GemmArgs g = plain_gemm(T, D.H);
     g.Cf = sv->x1; g.ldcf = D.H; g.res = X;
+    proj_us_group(c, 3, 3, sv->o, T, sv, st);
     RUN(proj_fwd(c, L, 3, sv->o, T, sv, g, st));
   }
   ft_rmsnorm_fwd(sv->x1, L.g2, sv->h2, sv->rho2, T, D.H, m.rms_eps, st);
+  proj_us_group(c, 4, 5, sv->h2, T, sv, st);
   {
     GemmArgs g = plain_gemm(T, D.F);
     g.Cb = sv->a; g.ldcb = D.F;
@@ -512,6 +532,7 @@ extern "C" harli_status harli_lora_fwd(harli_ctx* c, int32_t layer, const float*
   {  // Y = x1 + m Wd^T
     GemmArgs g = plain_gemm(T, D.H);
     g.Cf = Y; g.ldcf = D.H; g.res = sv->x1;
+    proj_us_group(c, 6, 6, sv->m, T, sv, st);
     RUN(proj_fwd(c, L, 6, sv->m, T, sv, g, st));
   }
   if (hipGetLastError() != hipSuccess) {

@@ -55,6 +55,22 @@ void ft_attn_ds_t(const float* ST, const float* dPT, const float* lse, const flo
 // skinny NT GEMM: C[M, N] = alpha * X[M, K] . Bm[N, K]^T, N <= 64 and N % 16 == 0 after padding by the caller's layout
 void ft_skinny_nt(const bf* X, long long ldx, const bf* Bm, long long ldb, bf* C, long long ldc, int M, int N, int K,
                   float alpha, hipStream_t st);
+// Several such products with the same M and alpha in one launch (job = blockIdx.y).
+constexpr int kSkinnyMaxJobs = 4;
+struct SkinnyNtJob {
+  const bf* X;
+  long long ldx;
+  const bf* Bm;
+  long long ldb;
+  bf* C;
+  long long ldc;
+  int N, K;
+};
+struct SkinnyNtJobs {
+  int n;
+  SkinnyNtJob j[kSkinnyMaxJobs];
+};
+void ft_skinny_nt_multi(const SkinnyNtJobs& jobs, int M, float alpha, hipStream_t st);
 // G[j*sj + r*sr] += out_mul * sum_t X[t][j] * U[t][r];  X [T, J] and U [T, R] 16-bit, R in {8, 16, 32, 64}, J even,
 // one of sj, sr equal to 1.  `part` is scratch of ft_lora_grad_ws_floats(J, R) floats; G is read and written
 // without atomics, so no other work may update it concurrently.

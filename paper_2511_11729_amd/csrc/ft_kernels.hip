@@ -274,8 +274,13 @@ __device__ __forceinline__ f32x4 mma16(const u32x4& a, const u32x4& b, f32x4 c) 
 #endif
 }
 template <int NT>
-__global__ void __launch_bounds__(512) k_skinny_nt(const bf* X, long long ldx, const bf* Bm, long long ldb, bf* C,
-                                                   long long ldc, int M, int N, int K, float alpha) {
+__global__ void __launch_bounds__(512) k_skinny_nt(SkinnyNtJobs jobs, int M, float alpha) {
+  const SkinnyNtJob& jb = jobs.j[blockIdx.y];
+  const bf* X = jb.X;
+  const bf* Bm = jb.Bm;
+  bf* C = jb.C;
+  const long long ldx = jb.ldx, ldb = jb.ldb, ldc = jb.ldc;
+  const int N = jb.N, K = jb.K;
   constexpr int NW = 8, U = 4;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, i16 = lane & 15, g = lane >> 4;
   const int m0 = blockIdx.x * 16;
@@ -664,13 +669,22 @@ void ft_attn_ds_t(const float* ST, const float* dPT, const float* lse, const flo
   const long long rows = (long long)Z * S;
   hipLaunchKernelGGL(k_attn_ds_t, dim3(nblk(rows, 4)), dim3(256), 0, st, ST, dPT, lse, delta, PT, dST, S, rows);
 }
+void ft_skinny_nt_multi(const SkinnyNtJobs& jobs, int M, float alpha, hipStream_t st) {
+  if (jobs.n < 1) return;
+  int nmax = 0;
+  for (int i = 0; i < jobs.n; ++i) nmax = std::max(nmax, jobs.j[i].N);
+  const int nt = (nmax + 15) / 16;  // jobs with fewer columns mask their stores
+  const dim3 grid((M + 15) / 16, jobs.n), blk(512);
+  if (nt == 1) hipLaunchKernelGGL(k_skinny_nt<1>, grid, blk, 0, st, jobs, M, alpha);
+  else if (nt == 2) hipLaunchKernelGGL(k_skinny_nt<2>, grid, blk, 0, st, jobs, M, alpha);
+  else hipLaunchKernelGGL(k_skinny_nt<4>, grid, blk, 0, st, jobs, M, alpha);
+}
 void ft_skinny_nt(const bf* X, long long ldx, const bf* Bm, long long ldb, bf* C, long long ldc, int M, int N, int K,
                   float alpha, hipStream_t st) {
-  const int nt = (N + 15) / 16;
-  const dim3 grid((M + 15) / 16), blk(512);
-  if (nt == 1) hipLaunchKernelGGL(k_skinny_nt<1>, grid, blk, 0, st, X, ldx, Bm, ldb, C, ldc, M, N, K, alpha);
-  else if (nt == 2) hipLaunchKernelGGL(k_skinny_nt<2>, grid, blk, 0, st, X, ldx, Bm, ldb, C, ldc, M, N, K, alpha);
-  else hipLaunchKernelGGL(k_skinny_nt<4>, grid, blk, 0, st, X, ldx, Bm, ldb, C, ldc, M, N, K, alpha);
+  SkinnyNtJobs jobs{};
+  jobs.n = 1;
+  jobs.j[0] = SkinnyNtJob{X, ldx, Bm, ldb, C, ldc, N, K};
+  ft_skinny_nt_multi(jobs, M, alpha, st);
 }
 // floats of partial sums one job of the MFMA path can need: nch * J with nch <= max(1, 512 / column tiles)
 static size_t lora_grad_job_floats(int J, int R) { return (size_t)std::max(512 * kLmJ, (J + kLmJ - 1) / kLmJ * kLmJ) * R; }
