@@ -55,6 +55,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--solo", action="store_true", help="also report each task running alone (default on)")
     ap.add_argument("--no-sched", action="store_true", help="skip the predictor profiling and the scheduled run")
+    ap.add_argument("--no-peaks", action="store_true",
+                    help="skip the read-bandwidth and GEMM-clock probes (profiling runs: keeps their kernels out of the trace)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="after the timed region run three plain 256 MiB device copies: the known-size kernel that the "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
@@ -253,19 +255,21 @@ def main():
         torch.cuda.synchronize()
 
     # measured ceilings of this GPU (plain read kernels of the library's debug ABI): what HBM and the L2 caches deliver
-    probe = torch.empty(6 << 30, dtype=torch.uint8, device=dev)
-    peaks = {"hbm_stream_read_GBs": hb.dbg_read_bandwidth(probe, 0), "l2_to_cu_read_GBs": hb.dbg_read_bandwidth(probe, 1),
-             "note": "the GEMM's workgroups pull (256+128) x K x 2 bytes of operand panels per 256x128 tile through L2: at "
-                     "the L2 rate above that bounds it below the MFMA peak"}
-    del probe
-    # the clock the chip sustains under the GEMM itself (seen from inside the kernel), on random half operands
-    ga = (torch.rand(2048, 4096, device=dev) - 0.5).half()
-    gb = (torch.rand(4096, 4096, device=dev) - 0.5).half()
-    gc = torch.empty(2048, 4096, dtype=torch.float16, device=dev)
-    tf, mhz = hb.dbg_gemm_clock(ga, gb, gc, half=True, reps=50)
-    peaks["gemm_2048x4096x4096_back_to_back"] = {"TFLOPs": tf, "shader_clock_MHz": mhz, "nominal_clock_MHz": 2400,
-                                                 "note": "the published 2.5 PFLOP/s is at the nominal clock"}
-    del ga, gb, gc
+    peaks = None
+    if not args.no_peaks:
+        probe = torch.empty(6 << 30, dtype=torch.uint8, device=dev)
+        peaks = {"hbm_stream_read_GBs": hb.dbg_read_bandwidth(probe, 0), "l2_to_cu_read_GBs": hb.dbg_read_bandwidth(probe, 1),
+                 "note": "the GEMM's workgroups pull (256+128) x K x 2 bytes of operand panels per 256x128 tile through L2: at "
+                         "the L2 rate above that bounds it below the MFMA peak"}
+        del probe
+        # the clock the chip sustains under the GEMM itself (seen from inside the kernel), on random half operands
+        ga = (torch.rand(2048, 4096, device=dev) - 0.5).half()
+        gb = (torch.rand(4096, 4096, device=dev) - 0.5).half()
+        gc = torch.empty(2048, 4096, dtype=torch.float16, device=dev)
+        tf, mhz = hb.dbg_gemm_clock(ga, gb, gc, half=True, reps=50)
+        peaks["gemm_2048x4096x4096_back_to_back"] = {"TFLOPs": tf, "shader_clock_MHz": mhz, "nominal_clock_MHz": 2400,
+                                                     "note": "the published 2.5 PFLOP/s is at the nominal clock"}
+        del ga, gb, gc
 
     ach_tf = gemm_flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else float("nan")
     out = {
