@@ -1,0 +1,233 @@
+"""A decode service with continuous batching next to a finetune task, both on one unified pool (Harli Sec. 3-4, the
+setting of the evaluation's request trace, Sec. 8.1 / 8.5).  Host orchestration only: every device step runs in
+libharli's kernels; this module keeps the request queue, the page tables and the calls in order.
+
+Requests arrive with a prompt whose KV cache is taken as given (the paper serves decode in a prefill/decode
+disaggregated deployment: prefill happens elsewhere) and a number of tokens to produce.  Admission allocates the
+prompt's KV pages from the pool; every decode step appends one token per running sequence, allocates a page when a
+sequence crosses a page boundary and frees the pages of sequences that finish (the pool reuses them once the step
+that last read them has completed).  The finetune task allocates its saved activations from the same pool and backs
+off when the pool reports pressure or cannot serve it (Sec. 4.4: inference has priority).
+"""
+from __future__ import annotations
+
+import collections
+import threading
+import time
+
+import numpy as np
+import torch
+
+from . import binding as hb
+
+P = 16  # tokens per KV page
+
+
+class DecodeServer:
+    """Continuous batching over `harli_decode_step`.  Not thread-safe: one thread drives it."""
+
+    def __init__(self, ctx, pool, m, *, max_batch: int, max_len: int, stream, slab=None):
+        """slab: the pool's slab as a torch uint8 tensor; when given, the KV pages of an admitted prompt are cleared on
+        the decode stream (standing in for the arrival of the prompt's cache from the prefill instance: the same
+        bytes are written once).  Without it the pages keep whatever the pool last held there."""
+        self.ctx, self.pool, self.m, self.stream = ctx, pool, m, stream
+        self.kv_view = None
+        if slab is not None:
+            cfg, st = pool.cfg, pool.stats()
+            page_bytes = P * cfg.kv_row_bytes
+            chunk_bytes = 2 * cfg.n_layers * cfg.block_bytes
+            self.ppb = st.pages_per_block
+            self.kv_view = torch.as_strided(slab, (st.n_chunks, 2 * cfg.n_layers, self.ppb, page_bytes),
+                                            (chunk_bytes, cfg.block_bytes, page_bytes, 1), cfg.small_pool_bytes)
+        self.max_batch, self.max_len = max_batch, max_len
+        self.max_pages = (max_len + P - 1) // P + 1
+        dev = "cuda:0"
+        self.table = np.full((max_batch, self.max_pages), -1, np.int32)   # host truth, updated incrementally
+        self.kv = np.zeros(max_batch, np.int32)
+        self.ring = [(torch.empty(max_batch, self.max_pages, dtype=torch.int32, pin_memory=True),
+                      torch.empty(max_batch, dtype=torch.int32, pin_memory=True), None) for _ in range(4)]
+        self.table_dev = torch.empty(max_batch, self.max_pages, dtype=torch.int32, device=dev)
+        self.kv_dev = torch.empty(max_batch, dtype=torch.int32, device=dev)
+        self.tok = torch.zeros(max_batch, dtype=torch.int32, device=dev)
+        self.nxt = torch.zeros(max_batch, dtype=torch.int32, device=dev)
+        self.logits = torch.empty(max_batch, m.vocab, dtype=torch.float32, device=dev)
+        self.x_out = torch.empty(max_batch, m.hidden, dtype=torch.float32, device=dev)
+        self.running = []          # per slot: [pages (list), cached tokens, tokens left]
+        self.queue = collections.deque()
+        self.step_no = 0
+        self.admitted = self.finished = self.kv_stalls = self.preempted = self.tokens_out = 0
+
+    def submit(self, reqs):
+        self.queue.extend(reqs)
+
+    def _admit(self):
+        while self.queue and len(self.running) < self.max_batch:
+            prompt, out = self.queue[0]
+            prompt = min(prompt, self.max_len - 2)
+            out = max(1, min(out, self.max_len - 1 - prompt))
+            need = (prompt + 1 + P - 1) // P
+            try:
+                ids = self.pool.alloc_pages(need)
+            except hb.HarliError as e:
+                if e.status != hb.HARLI_ERR_OOM:
+                    raise
+                self.kv_stalls += 1            # no room for this prompt now: it stays queued
+                break
+            self.queue.popleft()
+            if self.kv_view is not None:       # the prompt's cache "arrives": its pages are written once
+                idx = torch.tensor(ids, dtype=torch.int64, device=self.kv_view.device)
+                with torch.cuda.stream(self.stream):
+                    self.kv_view[idx // self.ppb, :, idx % self.ppb, :] = 0
+            b = len(self.running)
+            self.table[b, :] = -1
+            self.table[b, :need] = ids
+            self.kv[b] = prompt
+            self.running.append([list(ids), prompt, out])
+            self.admitted += 1
+
+    def _drop(self, b, event):
+        """Frees slot b's pages (reusable once `event` has completed) and moves the last slot into its place."""
+        self.pool.free_pages(self.running[b][0], event)
+        last = len(self.running) - 1
+        if b != last:
+            self.running[b] = self.running[last]
+            self.table[b] = self.table[last]
+            self.kv[b] = self.kv[last]
+        self.running.pop()
+
+    def step(self):
+        """Admits what fits, launches one decode step for every running sequence and advances the host state.
+        Returns (event recorded after the step, batch size) or None when nothing is running."""
+        self._admit()
+        B = len(self.running)
+        if B == 0:
+            return None
+        tb, kb, ev = self.ring[self.step_no % len(self.ring)]
+        if ev is not None:
+            ev.synchronize()                   # the copy that last used this staging buffer is done
+        tb[:B].copy_(torch.from_numpy(self.table[:B]))
+        kb[:B].copy_(torch.from_numpy(self.kv[:B]))
+        with torch.cuda.stream(self.stream):
+            self.table_dev[:B].copy_(tb[:B], non_blocking=True)
+            self.kv_dev[:B].copy_(kb[:B], non_blocking=True)
+        max_kv = int(self.kv[:B].max()) + 1
+        self.ctx.decode_step(batch=B, kv_len=self.kv_dev, page_table=self.table_dev, max_pages=self.max_pages, max_kv_len=max_kv,
+                             token_ids=self.tok, x_out=self.x_out, logits=self.logits, next_token=self.nxt, stream=self.stream)
+        done = torch.cuda.Event(enable_timing=True)
+        done.record(self.stream)
+        self.ring[self.step_no % len(self.ring)] = (tb, kb, done)
+        self.tok, self.nxt = self.nxt, self.tok   # the tokens just produced feed the next step
+        self.step_no += 1
+        self.tokens_out += B
+        # host state after the step: every sequence holds one more token
+        b = 0
+        while b < len(self.running):
+            seq = self.running[b]
+            seq[1] += 1
+            seq[2] -= 1
+            self.kv[b] = seq[1]
+            if seq[2] == 0:
+                self._drop(b, done)
+                self.finished += 1
+                continue                        # slot b now holds another sequence
+            if seq[1] + 1 > len(seq[0]) * P:    # the next token starts a new page
+                try:
+                    pid = self.pool.alloc_pages(1)[0]
+                    self.table[b, len(seq[0])] = pid
+                    seq[0].append(pid)
+                except hb.HarliError as e:
+                    if e.status != hb.HARLI_ERR_OOM:
+                        raise
+                    # the reserve is there to prevent this; if it happens the sequence goes back to the queue
+                    self.preempted += 1
+                    self.queue.appendleft((seq[1], seq[2]))
+                    self._drop(b, done)
+                    continue
+            b += 1
+        return done, B
+
+    def drain(self):
+        """Frees every running sequence (end of a run)."""
+        self.stream.synchronize()
+        while self.running:
+            self._drop(len(self.running) - 1, None)
+
+
+class FinetuneWorker:
+    """Host thread stepping a whole-model finetune task on its own stream.  `step_fn(stream)` enqueues one training step
+    and returns the saved-activation handles it still holds if it had to stop early (pool exhausted), else None."""
+
+    def __init__(self, pool, step_fn, stream, tokens_per_step):
+        self.pool, self.step_fn, self.stream, self.T = pool, step_fn, stream, tokens_per_step
+        self.steps = self.oom = self.backoff = 0
+        self._stop = threading.Event()
+        self.th = threading.Thread(target=self._run, daemon=True)
+
+    def _run(self):
+        torch.cuda.set_device(0)
+        while not self._stop.is_set():
+            if self.pool.pressure() > 0:       # inference needs the memory (Sec. 4.4): do not start a step now
+                self.backoff += 1
+                time.sleep(2e-3)
+                continue
+            ok = self.step_fn(self.stream)
+            if ok:
+                self.steps += 1
+            else:
+                self.oom += 1
+                time.sleep(2e-3)
+
+    def __enter__(self):
+        self.th.start()
+        return self
+
+    def __exit__(self, *a):
+        self._stop.set()
+        self.th.join()
+        self.stream.synchronize()
+
+
+def replay(server: DecodeServer, arrivals, worker_factory=None, slo_ms=40.0, sample_every=25, log=lambda *a: None):
+    """Drives `server` through `arrivals` (one list of requests per decode step) with, optionally, a finetune worker
+    beside it.  Returns per-step batch sizes and times per output token, pool snapshots and counters."""
+    pool = server.pool
+    recs, snaps = [], []
+    t_start = time.perf_counter()
+
+    def run():
+        pending = collections.deque()
+        for t, reqs in enumerate(arrivals):
+            server.submit(reqs)
+            r = server.step()
+            if r is not None:
+                pending.append(r)
+                recs.append(r)
+            if len(pending) > 2:
+                pending.popleft()[0].synchronize()     # the host runs at most two steps ahead of the device
+            if t % sample_every == 0:
+                st = pool.stats()
+                snaps.append({"step": t, "batch": len(server.running), "queued": len(server.queue), "free_chunks": st.free_chunks,
+                              "kv_chunks": st.kv_chunks, "tensor_chunks": st.tensor_chunks,
+                              "pressure": pool.pressure()})
+        server.stream.synchronize()
+
+    if worker_factory is not None:
+        with worker_factory() as worker:
+            run()
+        ft = {"steps": worker.steps, "oom_retries": worker.oom, "pressure_backoffs": worker.backoff, "tokens": worker.steps * worker.T}
+    else:
+        run()
+        ft = None
+    elapsed = time.perf_counter() - t_start
+    tpot = np.array([recs[i][0].elapsed_time(recs[i + 1][0]) for i in range(len(recs) - 1)]) if len(recs) > 1 else np.array([0.0])
+    batches = np.array([r[1] for r in recs])
+    out = {"steps": len(arrivals), "decode_steps": len(recs), "elapsed_s": elapsed, "tokens_out": server.tokens_out,
+           "decode_tokens_per_s": server.tokens_out / elapsed, "tpot_ms_p50": float(np.percentile(tpot, 50)),
+           "tpot_ms_p99": float(np.percentile(tpot, 99)), "tpot_ms_max": float(tpot.max()), "within_slo": float(np.mean(tpot <= slo_ms)),
+           "batch_mean": float(batches.mean()) if len(batches) else 0.0, "batch_max": int(batches.max()) if len(batches) else 0,
+           "admitted": server.admitted, "finished": server.finished, "kv_admission_stalls": server.kv_stalls,
+           "preempted": server.preempted, "queued_at_end": len(server.queue), "snapshots": snaps}
+    if ft is not None:
+        ft["tokens_per_s"] = ft["tokens"] / elapsed
+        out["finetune"] = ft
+    return out

@@ -7,5 +7,5 @@ from .synth import (  # noqa: F401
     ModelCfg, LoraCfg, DecodeCfg, FinetuneCfg, Workload, CONFIGS, workload,
     rng_for, bf16_round, bf16_bits, bf16_from_bits,
     make_layer_weights, make_lora, make_decode_inputs, make_finetune_inputs,
-    make_model_extras, draw_lengths, page_order, make_token_ids, LORA_TARGETS,
+    make_model_extras, draw_lengths, page_order, make_token_ids, make_arrivals, LORA_TARGETS,
 )

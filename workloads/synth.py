@@ -266,3 +266,31 @@ def make_finetune_inputs(w: Workload, model: ModelCfg | None = None, ft: Finetun
 def make_token_ids(w: Workload, shape) -> np.ndarray:
     m = w.model
     return rng_for(w.idx, S_INPUTS, 2).integers(0, m.vocab, size=shape).astype(np.int32)
+
+
+def make_arrivals(w: Workload, steps: int, targets=(1, 8, 42, 24, 128, 256), mean_out: int = 256, phase_steps: int | None = None,
+                  prompt=("lognormal", 800, 0.6, 8192)):
+    """Request arrivals of a decode service, one list per decode step: [(prompt tokens, output tokens), ...].
+
+    Piecewise-constant Poisson rate lambda(t) = target_batch / mean_out requests per step (Little's law: with a mean
+    output length of `mean_out` steps that load settles at `target_batch` running sequences), the targets taken in
+    turn for `phase_steps` steps each (default: steps / len(targets)); 8 / 42 / 24 are the light / heavy / medium loads
+    of the paper's controlled experiment (Sec. 8.5).  Prompt lengths follow `prompt` (as `DecodeCfg.len_dist`), output
+    lengths are geometric with mean `mean_out` on {1, 2, ...}.  Seeded by the workload index."""
+    rng = rng_for(w.idx, S_ARRIVALS)
+    ph = phase_steps or max(1, steps // len(targets))
+    out = []
+    for t in range(steps):
+        lam = targets[(t // ph) % len(targets)] / float(mean_out)
+        n = int(rng.poisson(lam))
+        reqs = []
+        for _ in range(n):
+            if prompt[0] == "lognormal":
+                pl = int(min(prompt[3], max(1, round(float(np.exp(np.log(prompt[1]) + prompt[2] * rng.standard_normal()))))))
+            elif prompt[0] == "uniform":
+                pl = int(rng.integers(prompt[1], prompt[2] + 1))
+            else:
+                pl = int(prompt[1])
+            reqs.append((pl, int(rng.geometric(1.0 / mean_out))))
+        out.append(reqs)
+    return out
