@@ -32,6 +32,10 @@ harli_status harli_pred_add_colo(harli_predictor* p, int32_t infer_level, int32_
 /* Ordinary least squares (Householder QR) of
  *   Eq. 1 per level:  latency = bs*b0 + c0 + bs*k0*seqlen           (needs >= 3 samples at that level)
  *   Eq. 2 overall:    latency_colo = (SM_infer*b1 + SM_ft*k1) * latency_solo   (needs >= 2 samples; optional)
+ *                     Predictions floor the factor at 1 (see harli_pred_colo), and a sample whose fitted factor is
+ *                     below 1 is then predicted by the floor whatever b1 and k1 are: after the pass over all samples
+ *                     the fit is repeated over the samples whose current factor is at least 1 until that set is
+ *                     stable.  With every sample in the contended regime this is the plain least-squares fit.
  * Levels without samples stay unfitted; HARLI_ERR_STATE if a sampled level has fewer than 3 samples or a
  * rank-deficient design (e.g. one batch size only). */
 harli_status harli_pred_fit(harli_predictor* p);

@@ -14,7 +14,11 @@ compared with.
   Prediction floors the factor at 1: the theoretical analysis of Sec. 5.2 derives it as
   (f_infer + f_ft) / B under contention, f_infer + f_ft > B, where it is at least 1; with less combined demand
   than bandwidth the tasks do not slow each other and the co-located latency is the solo latency (a factor
-  below 1 would predict that a neighbour makes decode faster).
+  below 1 would predict that a neighbour makes decode faster).  The fit follows the same reading: a sample whose
+  fitted factor is below 1 is predicted by the floor, whatever b1 and k1 are, so it says nothing about them;
+  after the first least-squares pass over all samples the pass is repeated over the samples whose current
+  factor is at least 1, until that set no longer changes (a stationary point of the squared error of the
+  floored prediction).  With every sample in the contended regime this is the plain least-squares fit.
 * Allocation (Sec. 5.2 "Perceive the Finetune Performance", Sec. 6.2): with ratios in steps of 1/n_levels the
   candidate plans are the pairs (SM_infer, SM_ft) with SM_infer + SM_ft <= 1, both at least one step (45 pairs
   for ten levels).  The plan chosen is the one whose predicted co-located latency is closest to the QoS target
@@ -39,11 +43,21 @@ def predict_solo(coef, bs, seqlen):
     return bs * b0 + c0 + bs * k0 * seqlen
 
 
+COLO_FIT_ROUNDS = 32
+
+
 def fit_colo(samples):
     """samples: iterable of (sm_infer, sm_ft, latency_colo, latency_solo_at_sm_infer).  Returns (b1, k1) of Eq. 2."""
     s = np.asarray(list(samples), np.float64)
     X = np.stack([s[:, 0] * s[:, 3], s[:, 1] * s[:, 3]], axis=1)
     beta, *_ = np.linalg.lstsq(X, s[:, 2], rcond=None)
+    active = np.ones(len(s), bool)
+    for _ in range(COLO_FIT_ROUNDS):
+        now = s[:, 0] * beta[0] + s[:, 1] * beta[1] >= 1.0      # samples the floor does not cover
+        if (now == active).all() or now.sum() < 2 or np.linalg.matrix_rank(X[now]) < 2:
+            break
+        active = now
+        beta, *_ = np.linalg.lstsq(X[active], s[active, 2], rcond=None)
     return float(beta[0]), float(beta[1])
 
 

@@ -139,6 +139,31 @@ extern "C" harli_status harli_pred_fit(harli_predictor* p) {
     }
     double b[2];
     if (!lstsq(X, y, n, 2, b)) return fail(HARLI_ERR_STATE, "pred_fit: co-located samples do not determine Eq. 2");
+    // Prediction floors the factor at 1, so a sample whose fitted factor is below 1 says nothing about b1, k1:
+    // repeat the fit over the samples the floor does not cover until that set is stable.
+    std::vector<char> active(n, 1), now(n);
+    for (int round = 0; round < 32; ++round) {
+      int cnt = 0;
+      bool same = true;
+      for (int i = 0; i < n; ++i) {
+        now[i] = p->colo[i].sm_i * b[0] + p->colo[i].sm_f * b[1] >= 1.0;
+        cnt += now[i];
+        same = same && now[i] == active[i];
+      }
+      if (same || cnt < 2) break;
+      std::vector<double> Xa, ya;
+      for (int i = 0; i < n; ++i)
+        if (now[i]) {
+          Xa.push_back(X[i * 2 + 0]);
+          Xa.push_back(X[i * 2 + 1]);
+          ya.push_back(y[i]);
+        }
+      double nb[2];
+      if (!lstsq(Xa, ya, cnt, 2, nb)) break;
+      active = now;
+      b[0] = nb[0];
+      b[1] = nb[1];
+    }
     p->b1 = b[0];
     p->k1 = b[1];
     p->colo_fitted = true;
