@@ -181,10 +181,10 @@ def main():
         il, fl, plat = pred.pick(B, seqlen, slo_ms)
         log("[bench] scheduler: inference level %d/10, finetune level %d/10, predicted TPOT %.3f ms" % (il, fl, plat))
         cs = colocate.CuStreams()
-        sDm = cs.low(il)
-        cs.low(il)                                     # spacer: keeps the two streams two dispatch pipes apart
+        low, high = cs.pairs()                         # inference and finetune streams on different dispatch pipes
+        sDm = low[il]
         if fl > 0:
-            sFm = cs.high(fl)
+            sFm = high[fl]
             res = colocate.run_colocated(hz, sDm, sFm, lambda: hz.decode_launch(sDm), K, W, None)
         else:
             res = colocate.run_colocated(hz, sDm, sF, lambda: hz.decode_launch(sDm), K, W, None, finetune=False)
@@ -194,11 +194,10 @@ def main():
         res_o = colocate.run_colocated(hz, sDm, sF, lambda: hz.decode_launch(sDm), K, W, None) if fl > 0 else None
         ctx.check(sDm)
         # StaticMode-style comparator (Sec. 8.1): 60 % of the compute units to inference, 40 % to finetune, fixed
-        sDs = cs.low(6)
-        cs.low(6)
-        sFs = cs.high(4)
+        sDs, sFs = low[6], high[4]
         res_s = colocate.run_colocated(hz, sDs, sFs, lambda: hz.decode_launch(sDs), K, W, None)
         ctx.check(sDs)
+        hz.drain()                                     # no event of the harness outlives the streams
         cs.close()
         # runtime scheduling over a load trace (Sec. 6.2): light -> heavy -> medium decode batches, one starvation episode
         trace = colocate.run_trace(hz, pred, slo_ms, [(150, 8), (150, 42), (150, 24)], seqlen=1024, refresh_phases=32,

@@ -40,6 +40,13 @@ harli_status harli_pred_add_colo(harli_predictor* p, int32_t infer_level, int32_
  * rank-deficient design (e.g. one batch size only). */
 harli_status harli_pred_fit(harli_predictor* p);
 
+/* Calibration (an addition to the paper's predictor): every prediction at `level` -- alone, co-located, in
+ * harli_sched_pick and in the runtime scheduler -- is Eq. 1's value times `scale` (> 0; 1 after create).  A caller that
+ * times its decode steps at run time folds the ratio measured / predicted back in here; the fitted coefficients
+ * (harli_pred_solo_coef) are not changed.  HARLI_ERR_INVALID for a level outside 1..n_levels or a scale that is not a
+ * positive finite number. */
+harli_status harli_pred_set_scale(harli_predictor* p, int32_t level, double scale);
+
 /* Coefficients after a fit (host out-pointers): solo[3] = b0, c0, k0 of `level`; colo[2] = b1, k1.
  * HARLI_ERR_STATE when that model has not been fitted. */
 harli_status harli_pred_solo_coef(const harli_predictor* p, int32_t level, double* solo);

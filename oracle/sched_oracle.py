@@ -43,6 +43,12 @@ def predict_solo(coef, bs, seqlen):
     return bs * b0 + c0 + bs * k0 * seqlen
 
 
+def calibrated(coef, scale):
+    """Eq. 1 coefficients whose prediction is `scale` times that of `coef` (the library's per-level calibration
+    factor, an addition to the paper's predictor: measured / predicted, folded back in at run time)."""
+    return tuple(scale * c for c in coef)
+
+
 COLO_FIT_ROUNDS = 32
 
 

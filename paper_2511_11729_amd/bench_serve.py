@@ -96,14 +96,19 @@ def build(args, model=None):
     embf = emb.float()
     state = {"t": 0}
 
-    def ft_step(st):
-        """One training step; False when the pool could not hold the step's activations (everything taken is returned)."""
+    def ft_step(wk):
+        """One training step, unit by unit: before each unit `wk.next_stream()` names the stream (compute-unit partition) it
+        goes to.  False when the pool could not hold the step's activations (everything taken is returned)."""
+        st = wk.next_stream()
         with torch.cuda.stream(st):
             torch.index_select(embf, 0, tok_dev, out=acts[0])
+        wk.unit_done(st)
         saved = []
         try:
             for l in range(L):
+                st = wk.next_stream()
                 saved.append(ctx.lora_fwd(l, acts[l], acts[l + 1], ft.micro_batch, ft.seq_len, stream=st))
+                wk.unit_done(st)
         except hb.HarliError as e:
             if e.status != hb.HARLI_ERR_OOM:
                 raise
@@ -112,22 +117,130 @@ def build(args, model=None):
             st.synchronize()
             return False
         state["t"] += 1
+        st = wk.next_stream()
         ctx.head_fwd_bwd(acts[L], tg_dev, loss, d0, stream=st)
+        wk.unit_done(st)
         d, dn = d0, d1
         for l in range(L - 1, -1, -1):
+            st = wk.next_stream()
             ctx.lora_bwd(l, d, dn, saved[l], dA[l], dB[l], stream=st)
+            wk.unit_done(st)
             d, dn = dn, d
+        st = wk.next_stream()
         for l in range(L):
             for p in A[l]:
                 hb.adamw_step(masters[l][p][0], moms[l][p][0], moms[l][p][1], dA[l][p], A[l][p], step=state["t"], lr=1e-4,
                               zero_grad=True, stream=st)
                 hb.adamw_step(masters[l][p][1], moms[l][p][2], moms[l][p][3], dB[l][p], Bm[l][p], step=state["t"], lr=1e-4,
                               zero_grad=True, stream=st)
+        wk.unit_done(st)
         st.synchronize()
         return True
 
     keep = (slab, layer, emb, gf, wlm, A, Bm, acts, masters, moms, dA, dB, embf, tok_dev, tg_dev, d0, d1, loss)
     return w, m, ft, pool, ctx, ft_step, (n_chunks, chunk, slab_bytes, reserve), keep
+
+
+def make_plan(args, m, ft, pool, ctx, ft_step, server, log):
+    """Profiles whole-model decode on compute-unit partitions (alone, then with training steps beside it), fits the
+    predictor and returns the per-phase planning hook for serve.replay."""
+    import torch
+    from paper_2511_11729_amd import binding as hb
+    from paper_2511_11729_amd import colocate, serve
+
+    dev = "cuda:0"
+    PB, PN = min(160, args.max_batch), min(1536, args.max_len - 8)
+    pages_per = (PN + 1 + serve.P - 1) // serve.P
+    ids = pool.alloc_pages(PB * pages_per)
+    table = torch.full((PB, server.max_pages), -1, dtype=torch.int32, device=dev)
+    table[:, :pages_per] = torch.tensor(ids, dtype=torch.int32).reshape(PB, pages_per).to(dev)
+    tok = torch.zeros(PB, dtype=torch.int32, device=dev)
+    rep_b, rep_n = min(32, PB), min(1024, PN)       # the representative batch of the co-located samples
+    rep_kv = torch.full((rep_b,), rep_n, dtype=torch.int32, device=dev)
+    torch.cuda.synchronize()
+
+    class Fixed:                                    # a training step pinned to one stream
+        def __init__(self, st):
+            self.st = st
+
+        def next_stream(self):
+            return self.st
+
+        def unit_done(self, st):
+            pass
+
+    class Hz:
+        x_dev = tok
+        T = ft.tokens
+
+        def decode_launch(self, stream, batch, kv_len_dev, max_kv):
+            if batch is None:                       # nothing here may touch the default stream (it would wait for the
+                batch, max_kv, kv_len_dev = rep_b, rep_n + 1, rep_kv       # finetune stream's queue)
+            ctx.decode_step(batch=batch, kv_len=kv_len_dev, page_table=table, max_pages=server.max_pages, max_kv_len=max_kv,
+                            token_ids=tok, x_out=server.x_out, logits=server.logits, next_token=server.nxt, stream=stream)
+
+        def finetune_unit(self, stream):
+            ft_step(Fixed(stream))
+
+    grid_b = tuple(b for b in (4, 16, 64, 160) if b <= PB)
+    grid_n = tuple(n for n in (128, 512, 1024, 1536) if n <= PN)
+    held = tuple((b, n) for b, n in ((8, 256), (32, 768), (96, 1280)) if b <= PB and n <= PN)
+    pred, rep = colocate.profile(Hz(), steps=3, log=log, batches=grid_b, seqlens=grid_n, heldout=held)
+    pool.free_pages(ids)
+    log("[sched] decode alone by level (ms): " + " ".join("%.1f" % v for v in rep["solo_ms_by_level_workload_batch"]))
+    log("[sched] decode beside finetune (ms): " + " ".join("%s=%.1f" % kv for kv in rep["colo_ms"].items()))
+    rep = {k: rep[k] for k in ("eq1_mean_abs_err_fitted_points", "eq1_mean_abs_err_heldout", "eq2_b1_k1", "eq2_mean_abs_err")}
+    cs = colocate.CuStreams()
+    low, high = cs.pairs(log)
+    sched = hb.Scheduler(pred, args.slo_ms * args.sched_margin, 64)
+
+    scale = [1.0] * (colocate.N_LEVELS + 1)         # per level: measured / predicted decode step, smoothed
+    seen = set()
+
+    def calibrate(srv):
+        """Sec. 6.2 plans with the predictor alone; here the steps that have finished are timed and the ratio
+        measured / predicted is folded back into the predictor per level (--no-feedback: off).  It absorbs what Eq. 1
+        cannot hold: latency that is a staircase in the batch size, batches of mixed lengths."""
+        changed = set()
+        for tag, ms in srv.completed_steps():
+            if tag is None or tag[1] <= 0.0:
+                continue
+            i, raw = tag
+            r = min(2.5, max(0.6, ms / raw))
+            scale[i] += 0.15 * (r - scale[i]) if i in seen else r - scale[i]
+            seen.add(i)
+            changed.add(i)
+            for j in range(1, colocate.N_LEVELS + 1):   # a level not seen yet borrows from the last one measured
+                if j not in seen:
+                    scale[j] = scale[i]
+                    changed.add(j)
+        for j in changed:
+            pred.set_scale(j, scale[j])
+
+    def plan(srv, worker):
+        if not args.no_feedback:
+            calibrate(srv)
+        B = min(args.max_batch, len(srv.running) + len(srv.queue))
+        if B == 0:
+            srv.tag = None
+            return (colocate.N_LEVELS, 0, -1, 0.0, 0)
+        n = int(srv.kv[: max(1, len(srv.running))].mean()) if srv.running else 800
+        ready = worker is not None and not worker.waiting
+        if args.static is not None:                 # StaticMode-style comparator (Sec. 8.1): one partition throughout
+            i, f = args.static
+            pred_ms, act = pred.colo(i, f, B, n) if f > 0 else pred.solo(i, B, n), 0
+        else:
+            i, f, pred_ms, act = sched.step(B, n, ready)
+        srv.use_stream(low[i])
+        srv.tag = (i, pred_ms / scale[i])           # the prediction before calibration
+        if worker is not None:
+            worker.target = high[f] if f > 0 else None
+        return (i, f, act, pred_ms, n)
+
+    rep["planned_for_ms"] = args.slo_ms * args.sched_margin
+    rep["feedback"] = not args.no_feedback
+    rep["calibration_by_level"] = scale              # filled in as the run goes (read after it)
+    return plan, rep, cs
 
 
 def main():
@@ -145,22 +258,68 @@ def main():
     ap.add_argument("--slo-ms", type=float, default=40.0)
     ap.add_argument("--release-ms", type=float, default=12.0, help="time the finetune task needs to give memory back")
     ap.add_argument("--no-finetune", action="store_true")
+    ap.add_argument("--sched", action="store_true",
+                    help="profile the latency predictor on compute-unit partitions first, then let the runtime scheduler "
+                         "place both tasks at the beginning of every decode phase (Sec. 5, Sec. 6.2)")
+    ap.add_argument("--static", type=int, nargs=2, default=None, metavar=("I", "F"),
+                    help="with --sched: no runtime scheduling, inference on the first I tenths of the compute units and the "
+                         "finetune task on the last F tenths (0: paused) throughout")
+    ap.add_argument("--no-feedback", action="store_true",
+                    help="with --sched: plan with the profiled predictor alone, without folding measured step times back in")
+    ap.add_argument("--dump", default=None, help="with --sched: per-step records (batch, plan, predicted and measured times) as CSV")
+    ap.add_argument("--sched-margin", type=float, default=0.9, help="the scheduler plans for this fraction of the target")
     args = ap.parse_args()
 
+    import faulthandler
     import torch
     import workloads as wl
     from paper_2511_11729_amd import serve
 
+    faulthandler.enable()                           # a crash in native code names the Python line it came from
     w, m, ft, pool, ctx, ft_step, (n_chunks, chunk, slab_bytes, reserve), keep = build(args)
-    sD, sF = torch.cuda.Stream(), torch.cuda.Stream()
+    scheduled = args.sched and not args.no_finetune
+    sD = torch.cuda.Stream()
+    sF = None if scheduled else torch.cuda.Stream()          # scheduled: the plan names the finetune stream, phase by phase
+    with torch.cuda.stream(sD):
+        keep[-1].zero_()                             # first use of the stream now (its hardware queue is set up here)
+    sD.synchronize()
     server = serve.DecodeServer(ctx, pool, m, max_batch=args.max_batch, max_len=args.max_len, stream=sD, slab=keep[0])
     arrivals = wl.make_arrivals(w, args.steps, tuple(args.targets), args.mean_out,
                                 prompt=w.decode.len_dist if w.decode.len_dist[0] == "lognormal" else ("lognormal", 800, 0.6, 8192))
     arrivals = [[(min(p, args.max_len - 2), o) for p, o in reqs] for reqs in arrivals]
     factory = None if args.no_finetune else (lambda: serve.FinetuneWorker(pool, ft_step, sF, ft.tokens))
-    res = serve.replay(server, arrivals, factory, slo_ms=args.slo_ms, log=lambda *a: print(*a, file=sys.stderr, flush=True))
+    log = lambda *a: print(*a, file=sys.stderr, flush=True)
+    plan, sched_report, cs = None, None, None
+    if scheduled:
+        plan, sched_report, cs = make_plan(args, m, ft, pool, ctx, ft_step, server, log)
+    res = serve.replay(server, arrivals, factory, slo_ms=args.slo_ms, log=log, plan=plan)
     server.drain()
+    server.use_stream(sD)
     ctx.check(sD)
+    if cs is not None:
+        cs.close()                                  # only now: no event and no task refers to the restricted streams any more
+    plans, tpot, batches, busy = res.pop("plans"), res.pop("tpot_ms"), res.pop("batches"), res.pop("step_ms")
+    res["step_ms_p50"], res["step_ms_p99"] = float(np.percentile(busy, 50)), float(np.percentile(busy, 99))
+    if plans and args.dump:
+        with open(args.dump, "w") as fh:
+            fh.write("step,batch,mean_len,infer_level,ft_level,predicted_ms,tpot_ms,step_ms\n")
+            for k in range(1, len(plans)):
+                fh.write("%d,%d,%d,%d,%d,%.3f,%.3f,%.3f\n" % (k, batches[k], plans[k][4], plans[k][0], plans[k][1], plans[k][3],
+                                                          tpot[k - 1], busy[k]))
+    if plans:
+        by = {}
+        for k in range(1, len(plans)):              # tpot[k - 1] is the duration of decode step k
+            i, f, act, pred_ms = plans[k][:4]
+            by.setdefault((i, f), []).append((tpot[k - 1], pred_ms, batches[k], busy[k]))
+        rows = []
+        for (i, f), v in sorted(by.items(), key=lambda kv: -len(kv[1]))[:10]:
+            v = np.array(v)
+            rows.append({"infer_level": i, "ft_level": f, "phases": len(v), "batch_mean": float(v[:, 2].mean()),
+                         "tpot_ms_mean": float(v[:, 0].mean()), "tpot_ms_p10_p50_p90": [float(x) for x in np.percentile(v[:, 0], (10, 50, 90))],
+                         "step_ms_mean": float(v[:, 3].mean()), "predicted_ms_mean": float(v[:, 1].mean()),
+                         "within_slo": float(np.mean(v[:, 0] <= args.slo_ms))})
+        res["scheduler"] = dict(sched_report, plans_used=rows, replans=sum(p[2] == 1 for p in plans),
+                                starved_phases=sum(p[2] == 3 for p in plans), paused_phases=sum(p[2] == 2 for p in plans))
     st = pool.stats()
     res["workload"] = ("config %d, %d layers + output layer: arrival trace with steady-state batches %s over %d decode steps, mean "
                        "output %d tokens; finetune %d x %d tokens per step" % (args.config, m.n_layers, args.targets, args.steps,

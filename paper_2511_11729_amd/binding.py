@@ -113,6 +113,7 @@ _SIGS = {
     "harli_pred_destroy": (None, [C.c_void_p]),
     "harli_pred_add_solo": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_double]),
     "harli_pred_add_colo": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_double, C.c_double]),
+    "harli_pred_set_scale": (C.c_int, [C.c_void_p, C.c_int32, C.c_double]),
     "harli_pred_fit": (C.c_int, [C.c_void_p]),
     "harli_pred_solo_coef": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_double)]),
     "harli_pred_colo_coef": (C.c_int, [C.c_void_p, C.POINTER(C.c_double)]),
@@ -400,6 +401,10 @@ class Predictor:
 
     def fit(self) -> None:
         _check(lib().harli_pred_fit(self.handle))
+
+    def set_scale(self, level: int, scale: float) -> None:
+        """Calibration factor on every prediction at `level` (1 by default)."""
+        _check(lib().harli_pred_set_scale(self.handle, level, C.c_double(scale)))
 
     def solo_coef(self, level: int):
         c = (C.c_double * 3)()

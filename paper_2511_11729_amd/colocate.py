@@ -8,6 +8,7 @@ throughput and latency statistics.  Host orchestration only: timing uses HIP eve
 """
 from __future__ import annotations
 
+import gc
 import threading
 import time
 
@@ -28,11 +29,19 @@ class CuStreams:
     def __init__(self):
         self.n_cu = torch.cuda.get_device_properties(0).multi_processor_count
         self._raw = []
+        self._big = self._small = None
+        self.shared_pipe = []                      # partitions whose two streams ended up on one pipe (see pairs)
 
     def make(self, first: int, count: int):
         raw = hb.cu_stream_create(first, count)
         self._raw.append(raw)
-        return torch.cuda.ExternalStream(raw)
+        st = torch.cuda.ExternalStream(raw)
+        if self._small is None:
+            self._small = torch.zeros(64, dtype=torch.float32, device="cuda:0")
+        with torch.cuda.stream(st):                # the hardware queue behind a stream is set up at its first use:
+            self._small.add_(1.0)                  # do that here, not inside somebody's timed region
+        st.synchronize()
+        return st
 
     def low(self, level: int):
         """The first level/N_LEVELS of the compute units (inference side)."""
@@ -43,7 +52,92 @@ class CuStreams:
         c = max(1, self.n_cu * level // N_LEVELS)
         return self.make(self.n_cu - c, c)
 
+    def _drop(self, streams):
+        """Destroys streams made by make() (idle ones: candidates that were only probed)."""
+        torch.cuda.synchronize()
+        for st in streams:
+            raw = st.cuda_stream
+            if raw in self._raw:
+                self._raw.remove(raw)
+                hb.cu_stream_destroy(raw)
+
+    def _conflict(self, a, b):
+        """True when work on stream `a` queues behind work on stream `b` although their compute units are disjoint:
+        the two sit on the same dispatch pipe.  A long element-wise kernel goes to `b`, a tiny one to `a` right after;
+        on one pipe the tiny one ends only when the long one is nearly through.  Both ends are timed from the start
+        of the long kernel (an event on `a` itself would queue behind the long kernel as well); asked twice, so that
+        a one-off stall of the device is not taken for queueing."""
+        if self._big is None:
+            self._big = torch.zeros(96 << 20, dtype=torch.float32, device="cuda:0")
+        for _ in range(2):
+            torch.cuda.synchronize()
+            eb0, eb1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            ea1 = torch.cuda.Event(enable_timing=True)
+            with torch.cuda.stream(b):
+                eb0.record()
+                self._big.add_(1.0)
+                eb1.record()
+            with torch.cuda.stream(a):
+                self._small.add_(1.0)
+                ea1.record()
+            a.synchronize()
+            b.synchronize()
+            if eb0.elapsed_time(ea1) <= 0.5 * eb0.elapsed_time(eb1):
+                return False
+        return True
+
+    def conflicts(self, low, high):
+        """The (i, f) with i + f <= N whose streams low[i] and high[f] share a dispatch pipe."""
+        return [(i, f) for i in sorted(low) for f in sorted(high) if i + f <= N_LEVELS and self._conflict(high[f], low[i])]
+
+    def pairs(self, log=lambda *a: None):
+        """(low, high): for every level an inference stream on the first level/N of the compute units and a finetune
+        stream on the last level/N, such that no inference stream shares a dispatch pipe with a finetune stream it can
+        run beside.  Two streams on one pipe dispatch their kernels one after the other: measured, a decode stream
+        sharing a pipe with the finetune stream sees about twice the latency of one that does not.  Which pipe (of
+        four) a stream's hardware queue sits on follows from its position among ALL hardware queues of the process,
+        and the positions are dealt again whenever a queue is created or destroyed; so all eighteen restricted
+        streams are created first, in an alternating order that usually keeps the two sides apart, and the result is
+        then checked by measurement (`conflicts`); on a conflict everything is destroyed and another arrangement
+        tried.  Level N (every compute unit; the finetune task is paused then) is an ordinary stream.
+        Call this after every other stream of the process exists AND has run something (the hardware queue behind
+        an ordinary stream comes into being at its first use), and create none while the result is in use.
+        Only the streams returned (and up to three idle spacers) stay alive: every restricted stream is a hardware
+        queue of its own, ordinary streams share up to four, and measured, a process with 24 queues or more
+        oversubscribes the queue slots of the device: every stream of the process then sees stalls of 10-30 ms."""
+        full = torch.cuda.Stream()                 # level N: every compute unit, an ordinary stream
+        if self._small is None:
+            self._small = torch.zeros(64, dtype=torch.float32, device="cuda:0")
+        with torch.cuda.stream(full):
+            self._small.add_(1.0)
+        torch.cuda.synchronize()
+        best = None
+        for spacers in (0, 1, 2, 3):
+            made = [self.low(1) for _ in range(spacers)]
+            low, high = {N_LEVELS: full}, {}
+            for lv in range(1, N_LEVELS):
+                low[lv] = self.low(lv)
+                high[lv] = self.high(lv)
+            bad = self.conflicts(low, high)
+            log("[streams] %d spacer(s): %d of 45 partitions share a pipe %s" % (spacers, len(bad), bad[:6]))
+            if not bad:
+                self.shared_pipe = []
+                return low, high
+            if best is None or len(bad) < best[0]:
+                best = (len(bad), spacers)
+            self._drop(made + [low[lv] for lv in range(1, N_LEVELS)] + list(high.values()))
+        made = [self.low(1) for _ in range(best[1])]       # none was clean: the arrangement with the fewest conflicts
+        low, high = {N_LEVELS: full}, {}
+        for lv in range(1, N_LEVELS):
+            low[lv] = self.low(lv)
+            high[lv] = self.high(lv)
+        self.shared_pipe = self.conflicts(low, high)
+        return low, high
+
     def close(self):
+        """Destroys the streams.  Call it once nothing refers to them any more: no task still issues work on them and
+        the events recorded on them have been let go (collected here before the streams go)."""
+        gc.collect()
         torch.cuda.synchronize()
         for r in self._raw:
             hb.cu_stream_destroy(r)
@@ -65,23 +159,31 @@ def time_decode(hz, stream, batch, kv_len_dev, max_kv, steps):
 
 
 class FinetuneLoop:
-    """Keeps finetune units enqueued on a stream from a host thread until stopped (the neighbour in profiling)."""
+    """Keeps finetune units enqueued on a stream from a host thread until stopped (the neighbour in profiling).
+    An exception in the thread ends it and is raised again in the thread that waits for it."""
 
     def __init__(self, hz, stream):
         self.hz, self.stream = hz, stream
         self.stop_flag = threading.Event()
         self.units = 0
+        self.error = None
         self.th = threading.Thread(target=self._run, daemon=True)
 
     def _run(self):
-        torch.cuda.set_device(0)
-        while not self.stop_flag.is_set():
-            self.hz.finetune_unit(self.stream)
-            self.units += 1
+        try:
+            torch.cuda.set_device(0)
+            while not self.stop_flag.is_set():
+                self.hz.finetune_unit(self.stream)
+                self.units += 1
+        except BaseException as e:                 # noqa: BLE001 -- handed to the waiting thread
+            self.error = e
 
     def __enter__(self):
         self.th.start()
         while self.units < 2:
+            if self.error is not None:
+                self.th.join()
+                raise RuntimeError("the finetune thread failed") from self.error
             time.sleep(1e-3)
         return self
 
@@ -89,10 +191,22 @@ class FinetuneLoop:
         self.stop_flag.set()
         self.th.join()
         self.stream.synchronize()
+        if self.error is not None and a[0] is None:
+            raise RuntimeError("the finetune thread failed") from self.error
 
 
-def profile(hz, steps=12, log=lambda *a: None):
-    """Returns (predictor, report).  hz must have decode capacity for batch 64 at 512 cached tokens."""
+def _quiesce(hz):
+    """Before restricted streams are destroyed the harness lets go of the events it recorded on them."""
+    drain = getattr(hz, "drain", None)
+    if drain is not None:
+        drain()
+
+
+def profile(hz, steps=12, log=lambda *a: None, batches=None, seqlens=None, heldout=None):
+    """Returns (predictor, report).  hz must have decode capacity for the largest profiled batch and length (default:
+    the paper's grid, batch 4 / 16 / 64 at up to 512 cached tokens); `decode_launch(stream, None, None, None)` runs the
+    workload's own batch, the base of the co-located samples."""
+    PROFILE_BATCHES_, PROFILE_SEQLENS_, HELDOUT_ = batches or PROFILE_BATCHES, seqlens or PROFILE_SEQLENS, heldout or HELDOUT
     cs = CuStreams()
     pred = hb.Predictor(N_LEVELS)
     dev = hz.x_dev.device
@@ -100,27 +214,18 @@ def profile(hz, steps=12, log=lambda *a: None):
     def lens(bs, n):
         return torch.full((bs,), n, dtype=torch.int32, device=dev)
 
-    # Streams are handed to the device's dispatch pipes round-robin in creation order (four pipes here), and two
-    # streams on one pipe dispatch their kernels one after the other: measured, a decode stream sharing a pipe with
-    # the finetune stream sees about twice the latency of one that does not.  Create the streams so that inference
-    # streams always sit two pipes away from finetune streams: L L H H L L H H ...
-    low, high = {}, {}
-    for g in range(0, N_LEVELS, 2):
-        for lv in (g + 1, g + 2):
-            low[lv] = cs.low(lv)
-        for lv in (g + 1, g + 2):
-            high[lv] = cs.high(lv)
+    low, high = cs.pairs()
     solo_meas = {}
     t0 = time.perf_counter()
     for lv in range(1, N_LEVELS + 1):
-        for bs in PROFILE_BATCHES:
-            for n in PROFILE_SEQLENS:
+        for bs in PROFILE_BATCHES_:
+            for n in PROFILE_SEQLENS_:
                 ms = time_decode(hz, low[lv], bs, lens(bs, n), n + 1, steps)
                 pred.add_solo(lv, bs, n, ms)
                 solo_meas[(lv, bs, n)] = ms
     held = {}
     for lv in range(1, N_LEVELS + 1):
-        for bs, n in HELDOUT:
+        for bs, n in HELDOUT_:
             held[(lv, bs, n)] = time_decode(hz, low[lv], bs, lens(bs, n), n + 1, steps)
     # the workload's own batch (mixed lengths) solo at every level: the base of the co-located samples
     base = {lv: time_decode(hz, low[lv], None, None, None, steps) for lv in range(1, N_LEVELS + 1)}
@@ -148,6 +253,7 @@ def profile(hz, steps=12, log=lambda *a: None):
         "solo_ms_by_level_workload_batch": [base[lv] for lv in range(1, N_LEVELS + 1)],
         "colo_ms": {"%d+%d" % k: v for k, v in sorted(colo_meas.items())},
     }
+    _quiesce(hz)
     cs.close()
     return pred, report
 
@@ -228,27 +334,31 @@ class FinetuneFeeder:
         self._stop = threading.Event()
         self._evs = []
         self._last_stream = None
+        self.error = None
         self.th = threading.Thread(target=self._run, daemon=True)
 
     def _run(self):
-        torch.cuda.set_device(0)
-        while not self._stop.is_set():
-            st = self.target
-            if st is None:
-                time.sleep(5e-5)
-                continue
-            if len(self._evs) >= 2:
-                self._evs[-2].synchronize()
-            if self._last_stream is not None and st is not self._last_stream and self._evs:
-                st.wait_event(self._evs[-1])
-            self.hz.finetune_unit(st)
-            ev = torch.cuda.Event()
-            ev.record(st)
-            self._evs.append(ev)
-            if len(self._evs) > 8:
-                del self._evs[:4]
-            self._last_stream = st
-            self.units += 1
+        try:
+            torch.cuda.set_device(0)
+            while not self._stop.is_set():
+                st = self.target
+                if st is None:
+                    time.sleep(5e-5)
+                    continue
+                if len(self._evs) >= 2:
+                    self._evs[-2].synchronize()
+                if self._last_stream is not None and st is not self._last_stream and self._evs:
+                    st.wait_event(self._evs[-1])
+                self.hz.finetune_unit(st)
+                ev = torch.cuda.Event()
+                ev.record(st)
+                self._evs.append(ev)
+                if len(self._evs) > 8:
+                    del self._evs[:4]
+                self._last_stream = st
+                self.units += 1
+        except BaseException as e:                 # noqa: BLE001 -- raised again by __exit__
+            self.error = e
 
     def completed(self):
         """Units whose work has finished on the device."""
@@ -263,6 +373,9 @@ class FinetuneFeeder:
         self._stop.set()
         self.th.join()
         torch.cuda.synchronize()
+        self._evs, self._last_stream = [], None    # nothing of this task refers to its streams any more
+        if self.error is not None and a[0] is None:
+            raise RuntimeError("the finetune thread failed") from self.error
 
 
 def run_trace(hz, pred, slo_ms, segments, seqlen, refresh_phases=32, starve=(), log=lambda *a: None):
@@ -275,12 +388,7 @@ def run_trace(hz, pred, slo_ms, segments, seqlen, refresh_phases=32, starve=(), 
     Returns per-phase records and a per-segment summary (latency percentiles, share of phases within the target,
     finetune units completed)."""
     cs = CuStreams()
-    low, high = {}, {}
-    for g in range(0, N_LEVELS, 2):                      # inference and finetune streams two dispatch pipes apart
-        for lv in (g + 1, g + 2):
-            low[lv] = cs.low(lv)
-        for lv in (g + 1, g + 2):
-            high[lv] = cs.high(lv)
+    low, high = cs.pairs()
     sched = hb.Scheduler(pred, slo_ms, refresh_phases)
     dev = hz.x_dev.device
     starve = set(starve)
@@ -288,9 +396,12 @@ def run_trace(hz, pred, slo_ms, segments, seqlen, refresh_phases=32, starve=(), 
     summary = []
     g = 0
     last_stream, last_ev = None, None
+    # made before the finetune task starts: work on the default stream waits for every restricted stream's queue
+    lens_of = {bs: torch.full((bs,), seqlen, dtype=torch.int32, device=dev) for _, bs in segments}
+    torch.cuda.synchronize()
     with FinetuneFeeder(hz) as feeder:
         for n_ph, bs in segments:
-            lens = torch.full((bs,), seqlen, dtype=torch.int32, device=dev)
+            lens = lens_of[bs]
             u0, t0 = feeder.completed(), time.perf_counter()
             first = len(rec)
             for _ in range(n_ph):
@@ -320,6 +431,7 @@ def run_trace(hz, pred, slo_ms, segments, seqlen, refresh_phases=32, starve=(), 
             log("[trace] batch %d: %s" % (bs, summary[-1]))
         feeder.target = None
     sched.close()
+    _quiesce(hz)
     cs.close()
     hz.ctx.check(torch.cuda.current_stream())
     return {"phases": rec, "segments": summary}

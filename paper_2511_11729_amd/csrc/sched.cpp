@@ -63,6 +63,7 @@ struct harli_predictor {
   std::vector<ColoSample> colo;
   std::vector<double> coef;       // 3 per level
   std::vector<char> fitted;       // per level
+  std::vector<double> scale;      // per level: calibration factor on Eq. 1's prediction (1 unless the caller sets it)
   double b1 = 0, k1 = 0;
   bool colo_fitted = false;
 };
@@ -71,7 +72,7 @@ namespace {
 bool level_ok(const harli_predictor* p, int level) { return level >= 1 && level <= p->n_levels; }
 double eval_solo(const harli_predictor* p, int level, double bs, double seqlen) {
   const double* c = &p->coef[(size_t)(level - 1) * 3];
-  return bs * c[0] + c[1] + bs * c[2] * seqlen;
+  return p->scale[level - 1] * (bs * c[0] + c[1] + bs * c[2] * seqlen);
 }
 // Eq. 2, with the slowdown factor floored at 1: the paper derives the factor as (f_infer + f_ft) / B for the
 // contended case f_infer + f_ft > B only; without contention the co-located latency is the solo latency.
@@ -88,6 +89,7 @@ extern "C" harli_status harli_pred_create(int32_t n_levels, harli_predictor** ou
   p->solo.resize(n_levels);
   p->coef.assign((size_t)n_levels * 3, 0.0);
   p->fitted.assign(n_levels, 0);
+  p->scale.assign(n_levels, 1.0);
   *out = p;
   return HARLI_OK;
 }
@@ -168,6 +170,13 @@ extern "C" harli_status harli_pred_fit(harli_predictor* p) {
     p->k1 = b[1];
     p->colo_fitted = true;
   }
+  return HARLI_OK;
+}
+
+extern "C" harli_status harli_pred_set_scale(harli_predictor* p, int32_t level, double scale) {
+  if (!p || !level_ok(p, level) || !(scale > 0.0) || !std::isfinite(scale))
+    return fail(HARLI_ERR_INVALID, "pred_set_scale: bad argument (level %d, scale %g)", level, scale);
+  p->scale[level - 1] = scale;
   return HARLI_OK;
 }
 

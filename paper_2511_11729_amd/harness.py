@@ -130,6 +130,13 @@ class LayerHarness:
         if len(self._ft_done) > 64:
             del self._ft_done[:32]
 
+    def drain(self):
+        """Waits for the finetune units issued so far and lets go of their events (call before destroying a stream
+        they ran on: an event must not be asked about after its stream is gone)."""
+        for ev in self._ft_done:
+            ev.synchronize()
+        self._ft_done = []
+
     def decode_bytes(self, batch=None, kv_len=None):
         kv = self.kv_len if kv_len is None else kv_len
         return 2 * self.m.layer_params + int(sum(int(n) + 1 for n in kv[: batch or self.B])) * 2 * self.m.kv_row_bytes

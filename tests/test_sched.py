@@ -45,6 +45,40 @@ def build_both(seed, n_levels=10, noise=0.02, weak=False):
     return p, o_solo, o_colo
 
 
+@pytest.mark.parametrize("seed", [0, 1])
+def test_calibration_scales_every_prediction_of_its_level(seed):
+    p, o_solo, o_colo = build_both(seed)
+    rng = np.random.default_rng(100 + seed)
+    scales = rng.uniform(0.7, 1.8, 10)
+    for lv in range(1, 11):
+        p.set_scale(lv, float(scales[lv - 1]))
+    cal = [S.calibrated(o_solo[lv], scales[lv]) for lv in range(10)]
+    for lv in range(1, 11):
+        assert np.allclose(p.solo_coef(lv), o_solo[lv - 1], rtol=1e-8, atol=1e-14)       # the fit itself is untouched
+        want = S.predict_solo(cal[lv - 1], 24, 900)
+        assert abs(p.solo(lv, 24, 900) - want) <= 1e-9 * abs(want)
+    for i, f in S.pairs(10):
+        want = S.predict_colo(o_colo, i / 10, f / 10, S.predict_solo(cal[i - 1], 8, 1153))
+        assert abs(p.colo(i, f, 8, 1153) - want) <= 1e-8 * abs(want)
+    for bs, n, slo in [(8, 512, 0.4), (42, 1024, 0.9), (24, 300, 0.25), (64, 2048, 3.0)]:
+        wi, wf, wl_ = S.pick(cal, o_colo, bs, n, slo)
+        gi, gf, gl = p.pick(bs, n, slo)
+        assert (gi, gf) == (wi, wf) and abs(gl - wl_) <= 1e-8 * abs(wl_)
+    ora = S.RuntimeScheduler(cal, o_colo, 0.6, 10, 8)
+    sch = hb.Scheduler(p, 0.6, 8)
+    for k in range(60):
+        bs, n, ready = int(rng.integers(1, 80)), int(rng.integers(16, 2000)), bool(rng.random() > 0.1)
+        assert sch.step(bs, n, ready)[:2] == ora.step(bs, n, ready)[:2]
+    # one factor on every level is the same as dividing the target by it
+    for lv in range(1, 11):
+        p.set_scale(lv, 1.25)
+    assert p.pick(24, 700, 0.5)[:2] == S.pick(o_solo, o_colo, 24, 700, 0.5 / 1.25)[:2]
+    with pytest.raises(hb.HarliError):
+        p.set_scale(11, 1.0)
+    with pytest.raises(hb.HarliError):
+        p.set_scale(3, 0.0)
+
+
 @pytest.mark.parametrize("seed", [0, 1, 2])
 @pytest.mark.parametrize("weak", [False, True])
 def test_fits_and_predictions_match_the_oracle(seed, weak):

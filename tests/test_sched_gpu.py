@@ -46,6 +46,7 @@ def test_decode_on_a_quarter_of_the_chip_matches_the_full_chip(hz):
     t_full = colocate.time_decode(hz, full, None, None, None, 10)
     t_part = colocate.time_decode(hz, part, None, None, None, 10)
     assert t_part > 1.3 * t_full                       # the restriction is real
+    hz.drain()
     cs.close()
 
 
@@ -61,11 +62,11 @@ def test_profile_fit_and_scheduled_colocation(hz):
     il, fl, plat = pred.pick(hz.B, int(hz.kv_len.mean()), slo)
     assert 1 <= il <= 10 and 0 <= fl <= 10 - il and (fl == 0 or plat <= slo)
     cs = colocate.CuStreams()
-    sD = cs.low(il)
-    cs.low(il)                                         # spacer (dispatch pipes, see colocate.profile)
-    sF = cs.high(max(fl, 1))
+    low, high = cs.pairs()                             # streams on different dispatch pipes
+    sD, sF = low[il], high[max(fl, 1)]
     res = colocate.run_colocated(hz, sD, sF, lambda: hz.decode_launch(sD), 4, 1, None)
     hz.ctx.check(sD)
+    hz.drain()                                         # no event of the harness outlives the streams
     cs.close()
     assert res["tokens_per_s"] > 0
     assert float(np.percentile(res["tpot"], 99)) <= slo
