@@ -149,8 +149,17 @@ def make_plan(args, m, ft, pool, ctx, ft_step, server, log):
     from paper_2511_11729_amd import colocate, serve
 
     dev = "cuda:0"
-    PB, PN = min(160, args.max_batch), min(1536, args.max_len - 8)
+    PN = min(1536, args.max_len - 8)
     pages_per = (PN + 1 + serve.P - 1) // serve.P
+    # the largest profiled batch whose KV cache fits beside a training step's activations (a tight pool profiles less)
+    st = pool.stats()
+    L, T = m.n_layers, ft.tokens
+    per_layer = T * m.hidden * 12 + T * m.n_q * m.head_dim * 4 + T * m.n_kv * m.head_dim * 4 + T * m.ffn * 6
+    chunk = 2 * L * pool.cfg.block_bytes
+    room = st.free_chunks - ((L + 1) * (per_layer // chunk + 2) + 8)
+    PB = next((b for b in (160, 128, 96, 64, 32, 16) if b <= args.max_batch and -(-b * pages_per // st.pages_per_block) <= room), None)
+    if PB is None:
+        raise SystemExit("bench_serve: the pool is too small to profile the predictor beside a training step")
     ids = pool.alloc_pages(PB * pages_per)
     table = torch.full((PB, server.max_pages), -1, dtype=torch.int32, device=dev)
     table[:, :pages_per] = torch.tensor(ids, dtype=torch.int32).reshape(PB, pages_per).to(dev)

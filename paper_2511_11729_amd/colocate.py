@@ -99,26 +99,36 @@ class CuStreams:
         and the positions are dealt again whenever a queue is created or destroyed; so all eighteen restricted
         streams are created first, in an alternating order that usually keeps the two sides apart, and the result is
         then checked by measurement (`conflicts`); on a conflict everything is destroyed and another arrangement
-        tried.  Level N (every compute unit; the finetune task is paused then) is an ordinary stream.
+        tried.  Level N (every compute unit; the finetune task is paused then, but units already in flight finish on
+        their partition) is an ordinary stream, chosen among four so that it shares a pipe with no finetune stream.
         Call this after every other stream of the process exists AND has run something (the hardware queue behind
         an ordinary stream comes into being at its first use), and create none while the result is in use.
         Only the streams returned (and up to three idle spacers) stay alive: every restricted stream is a hardware
         queue of its own, ordinary streams share up to four, and measured, a process with 24 queues or more
         oversubscribes the queue slots of the device: every stream of the process then sees stalls of 10-30 ms."""
-        full = torch.cuda.Stream()                 # level N: every compute unit, an ordinary stream
         if self._small is None:
             self._small = torch.zeros(64, dtype=torch.float32, device="cuda:0")
-        with torch.cuda.stream(full):
-            self._small.add_(1.0)
+        cands = [torch.cuda.Stream() for _ in range(4)]    # level N (every compute unit) is an ordinary stream: one of
+        for c in cands:                                    # these, chosen below; all used once now, so that the
+            with torch.cuda.stream(c):                     # hardware queues behind them exist before the positions
+                self._small.add_(1.0)                      # are measured
         torch.cuda.synchronize()
-        best = None
-        for spacers in (0, 1, 2, 3):
+
+        def arrange(spacers):
             made = [self.low(1) for _ in range(spacers)]
-            low, high = {N_LEVELS: full}, {}
+            low, high = {}, {}
             for lv in range(1, N_LEVELS):
                 low[lv] = self.low(lv)
                 high[lv] = self.high(lv)
-            bad = self.conflicts(low, high)
+            # the full-chip stream runs beside finetune units still in flight on their partition after a pause
+            clean = [c for c in cands if not any(self._conflict(c, high[f]) for f in high)]
+            low[N_LEVELS] = clean[0] if clean else cands[0]
+            bad = self.conflicts(low, high) + ([] if clean else [(N_LEVELS, 0)])
+            return made, low, high, bad
+
+        best = None
+        for spacers in (0, 1, 2, 3):
+            made, low, high, bad = arrange(spacers)
             log("[streams] %d spacer(s): %d of 45 partitions share a pipe %s" % (spacers, len(bad), bad[:6]))
             if not bad:
                 self.shared_pipe = []
@@ -126,12 +136,7 @@ class CuStreams:
             if best is None or len(bad) < best[0]:
                 best = (len(bad), spacers)
             self._drop(made + [low[lv] for lv in range(1, N_LEVELS)] + list(high.values()))
-        made = [self.low(1) for _ in range(best[1])]       # none was clean: the arrangement with the fewest conflicts
-        low, high = {N_LEVELS: full}, {}
-        for lv in range(1, N_LEVELS):
-            low[lv] = self.low(lv)
-            high[lv] = self.high(lv)
-        self.shared_pipe = self.conflicts(low, high)
+        made, low, high, self.shared_pipe = arrange(best[1])   # none was clean: the arrangement with the fewest conflicts
         return low, high
 
     def close(self):
