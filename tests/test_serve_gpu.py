@@ -104,3 +104,40 @@ def test_moving_page_tables_give_the_same_tokens_as_a_static_run():
         tok, nxt = nxt, tok
     pool.free_pages(ids)
     assert got == want
+
+
+def test_scheduled_trace_places_both_tasks_on_partitions_and_calibrates():
+    """The request trace under the runtime scheduler: predictor profiled on the whole (small) model, one decision per
+    decode phase, decode and finetune units moved between compute-unit partitions, measured step times folded back
+    into the predictor.  Checks the plumbing end to end: valid plans, finetune progress, factors inside their clip,
+    a clean pool, and no stream or event left behind (the process goes on to run other tests)."""
+    args, w, m, ft, pool, ctx, ft_step, info, keep = small(max_batch=32, max_len=600, ft_tokens=(4, 128))
+    args.sched_margin, args.static, args.no_feedback = 0.9, None, False
+    args.slo_ms = 5.0
+    sD = torch.cuda.Stream()
+    with torch.cuda.stream(sD):
+        keep[-1].zero_()
+    sD.synchronize()
+    server = serve.DecodeServer(ctx, pool, m, max_batch=args.max_batch, max_len=args.max_len, stream=sD, slab=keep[0])
+    plan, rep, cs = bench_serve.make_plan(args, m, ft, pool, ctx, ft_step, server, lambda *a: None)
+    assert cs.shared_pipe == []
+    assert rep["eq1_mean_abs_err_fitted_points"] < 0.5 and rep["eq2_b1_k1"][0] > 0
+    arrivals = wl.make_arrivals(w, 300, targets=(2, 8, 24, 6), mean_out=24, prompt=("uniform", 5, 400))
+    res = serve.replay(server, arrivals, lambda: serve.FinetuneWorker(pool, ft_step, None, ft.tokens), slo_ms=args.slo_ms, plan=plan)
+    server.drain()
+    server.use_stream(sD)
+    ctx.check(sD)
+    cs.close()
+    plans = res["plans"]
+    assert len(plans) == res["decode_steps"] > 100
+    for i, f, act, pred_ms, n in plans:
+        assert 1 <= i <= 10 and 0 <= f <= 10 - i
+        assert f > 0 or i == 10                                    # paused or starved: inference has the whole chip
+    assert res["finetune"]["steps"] >= 1 and res["preempted"] == 0
+    assert res["within_slo"] >= 0.9, res["tpot_ms_p99"]
+    assert all(0.6 <= s_ <= 2.5 for s_ in rep["calibration_by_level"][1:])
+    assert any(abs(s_ - 1.0) > 1e-6 for s_ in rep["calibration_by_level"][1:])        # steps were timed and folded back
+    torch.cuda.synchronize()
+    pool.alloc_pages(0)
+    st = pool.stats()
+    assert st.kv_pages_live == 0 and st.tensor_blocks_live == 0
