@@ -39,6 +39,8 @@ struct DecodeWs {
   double* inv_freq = nullptr; // [d/2] base^(-2i/d)
   float* att_part = nullptr;  // [bpad][n_q][max_chunks][d+2]
   int* att_cnt = nullptr;     // [bpad][n_kv]
+  float* amax_v = nullptr;    // [bpad][64] per-slice maxima of the logits (full-model mode)
+  int* amax_i = nullptr;      // [bpad][64] and their indices
   float* scores = nullptr;    // fp32 path only: [bpad][n_q][max_seq_len]
   float *fk = nullptr, *fv = nullptr, *fa = nullptr, *fu = nullptr;  // fp32 path only: k, v [bpad, n_kv*d]; gate, up [bpad, ffn]
   int* err_flag = nullptr;    // device int set when a kernel sees an out-of-range page id

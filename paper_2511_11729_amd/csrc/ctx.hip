@@ -126,6 +126,10 @@ extern "C" harli_status harli_ctx_create(const harli_model_cfg* cfg, const harli
   TRY(dev_alloc(&d.xb, bp * m.hidden * 4, true));
   TRY(dev_alloc(&d.ssq, bp * (2 * m.n_layers + 1) * 4, true));
   TRY(dev_alloc(&d.rope, bp * m.head_dim * 4, true));
+  if (m.vocab > 0) {
+    TRY(dev_alloc(&d.amax_v, bp * 64 * 4, true));
+    TRY(dev_alloc(&d.amax_i, bp * 64 * 4, true));
+  }
   {
     TRY(dev_alloc(&d.inv_freq, (m.head_dim / 2) * sizeof(double), false));
     std::vector<double> f(m.head_dim / 2);
@@ -178,7 +182,7 @@ extern "C" harli_status harli_ctx_create(const harli_model_cfg* cfg, const harli
 extern "C" void harli_ctx_destroy(harli_ctx* c) {
   if (!c) return;
   DecodeWs& d = c->dw;
-  void* bufs[] = {d.hx1, d.obuf, d.hx2, d.mbuf, d.qbuf, d.x1, d.xa, d.xb, d.ssq, d.rope, d.att_part, d.att_cnt, d.err_flag, d.scores, d.inv_freq, d.fk, d.fv, d.fa, d.fu};
+  void* bufs[] = {d.hx1, d.obuf, d.hx2, d.mbuf, d.qbuf, d.x1, d.xa, d.xb, d.ssq, d.rope, d.att_part, d.att_cnt, d.amax_v, d.amax_i, d.err_flag, d.scores, d.inv_freq, d.fk, d.fv, d.fa, d.fu};
   for (void* p : bufs)
     if (p) (void)hipFree(p);
   for (LayerDev& ld : c->layers)

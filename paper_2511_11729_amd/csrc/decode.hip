@@ -572,32 +572,67 @@ __global__ void __launch_bounds__(D) k_attn_merge(const float* part, const int* 
   obuf[xfrag_off(b, head * D + e, (n_q * D + 31) >> 5)] = f2bf(o / L);
 }
 
-__global__ void __launch_bounds__(256) k_argmax(const float* logits, int V, int* next_token) {
-  const int b = blockIdx.x, tid = threadIdx.x;
+// argmax over the vocabulary in two launches: kArgSeg workgroups per sequence each find the first maximum of
+// their slice, one wave per sequence then picks among the slices (a single workgroup per sequence took 0.2 ms on
+// a 128k vocabulary whatever the batch).  Ties go to the smaller index at both levels: the first maximum, as in the
+// plain definition.
+constexpr int kArgSeg = 64;
+
+__device__ __forceinline__ bool arg_better(float v, int i, float bv, int bi) { return v > bv || (v == bv && i < bi); }
+
+__global__ void __launch_bounds__(256) k_argmax_part(const float* logits, int V, float* part_v, int* part_i) {
+  const int seg = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+  const int len = (V + kArgSeg - 1) / kArgSeg;
+  const int lo = seg * len, hi = min(V, lo + len);
   float best = -INFINITY;
   int bi = 0x7fffffff;
-  for (int i = tid; i < V; i += 256) {
-    float v = logits[(size_t)b * V + i];
-    if (v > best) {  // strided scan visits indices in increasing order per thread: first maximum is kept
+  for (int i = lo + tid; i < hi; i += 256) {
+    const float v = logits[(size_t)b * V + i];
+    if (v > best) {  // indices increase per thread: the first maximum is kept
       best = v;
       bi = i;
     }
   }
-  __shared__ float sv[256];
-  __shared__ int si[256];
-  sv[tid] = best;
-  si[tid] = bi;
-  __syncthreads();
-  for (int s = 128; s > 0; s >>= 1) {
-    if (tid < s) {
-      if (sv[tid + s] > sv[tid] || (sv[tid + s] == sv[tid] && si[tid + s] < si[tid])) {
-        sv[tid] = sv[tid + s];
-        si[tid] = si[tid + s];
-      }
+  for (int o = 1; o < 64; o <<= 1) {
+    const float ov = __shfl_xor(best, o, 64);
+    const int oi = __shfl_xor(bi, o, 64);
+    if (arg_better(ov, oi, best, bi)) {
+      best = ov;
+      bi = oi;
     }
-    __syncthreads();
   }
-  if (tid == 0) next_token[b] = si[0];
+  __shared__ float sv[4];
+  __shared__ int si[4];
+  if ((tid & 63) == 0) {
+    sv[tid >> 6] = best;
+    si[tid >> 6] = bi;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    for (int w = 1; w < 4; ++w)
+      if (arg_better(sv[w], si[w], best, bi)) {
+        best = sv[w];
+        bi = si[w];
+      }
+    part_v[b * kArgSeg + seg] = best;
+    part_i[b * kArgSeg + seg] = bi;
+  }
+}
+
+__global__ void __launch_bounds__(64) k_argmax_final(const float* part_v, const int* part_i, int* next_token) {
+  const int b = blockIdx.x, lane = threadIdx.x;
+  static_assert(kArgSeg == 64, "one lane per slice");
+  float best = part_v[b * kArgSeg + lane];
+  int bi = part_i[b * kArgSeg + lane];
+  for (int o = 1; o < 64; o <<= 1) {
+    const float ov = __shfl_xor(best, o, 64);
+    const int oi = __shfl_xor(bi, o, 64);
+    if (arg_better(ov, oi, best, bi)) {
+      best = ov;
+      bi = oi;
+    }
+  }
+  if (lane == 0) next_token[b] = bi;
 }
 
 template <int MODE, int NB, int TW, int KW, int U>
@@ -770,7 +805,10 @@ extern "C" harli_status harli_decode_step(harli_ctx* c, const harli_decode_batch
     a.ssq_in = w.ssq + (size_t)(2 * L) * w.bpad;
     a.logits = b->logits;
     dispatch_skinny<MODE_LM, 2, 4>(a, (m.vocab + 31) / 32, st);
-    if (b->next_token) hipLaunchKernelGGL(k_argmax, dim3(B), dim3(256), 0, st, b->logits, m.vocab, b->next_token);
+    if (b->next_token) {
+      hipLaunchKernelGGL(k_argmax_part, dim3(kArgSeg, B), dim3(256), 0, st, b->logits, m.vocab, w.amax_v, w.amax_i);
+      hipLaunchKernelGGL(k_argmax_final, dim3(B), dim3(64), 0, st, w.amax_v, w.amax_i, b->next_token);
+    }
   }
   HARLI_HIP(hipGetLastError());
   return HARLI_OK;
