@@ -640,18 +640,28 @@ void launch_skinny(const SkinnyArgs& a, int n_wg, hipStream_t st) {
   hipLaunchKernelGGL((k_skinny<MODE, NB, TW, KW, U>), dim3(n_wg), dim3(TW * KW * 64), 0, st, a);
 }
 
-// passes of at most 64 batch rows; NB = 16-row batch tiles per pass
+// passes of at most 64 batch rows (128 where the workgroup has eight waves to finish eight batch tiles and more than
+// 64 rows are left: every pass streams the whole weight matrix again); NB = 16-row batch tiles per pass
 template <int MODE, int TW, int KW>
 void dispatch_skinny(SkinnyArgs a, int n_wg, hipStream_t st) {
-  for (int b0 = 0; b0 < a.B; b0 += 64) {
+  for (int b0 = 0; b0 < a.B;) {
     a.b0 = b0;
-    const int nb = (min(a.B - b0, 64) + 15) / 16;
+    const int left = a.B - b0;
+    if constexpr (TW * KW >= 8) {
+      if (left > 64) {
+        launch_skinny<MODE, 8, TW, KW, 1>(a, n_wg, st);
+        b0 += 128;
+        continue;
+      }
+    }
+    const int nb = (min(left, 64) + 15) / 16;
     if (nb == 1)
       launch_skinny<MODE, 1, TW, KW, 8>(a, n_wg, st);
     else if (nb == 2)
       launch_skinny<MODE, 2, TW, KW, 4>(a, n_wg, st);
     else
       launch_skinny<MODE, 4, TW, KW, 2>(a, n_wg, st);
+    b0 += 64;
   }
 }
 

@@ -209,9 +209,17 @@ def test_config2_width_two_layers_batch16_with_logits():
 
 
 def test_config2_width_batch256():
-    """The largest decode batch of the sweep (four passes of 64 rows) on one 7B-class layer."""
+    """The largest decode batch of the sweep (passes of 64 or 128 rows) on one 7B-class layer."""
     w, m = variant(2, n_layers=1)
     run_case(w, m, [100 + (i * 37) % 400 for i in range(256)])
+
+
+@pytest.mark.parametrize("batch", [70, 150, 200])
+def test_config4_width_batches_that_split_into_uneven_passes(batch):
+    """Batches above 64 rows on the GQA layer: the eight-wave GEMMs take 128 rows per pass (70: one pass with three idle
+    batch tiles; 150: 128 + 22; 200: 128 + 72), the q,k,v GEMM 64."""
+    w, m = variant(4, n_layers=1)
+    run_case(w, m, [60 + (i * 53) % 300 for i in range(batch)])
 
 
 def test_config3_width_layer_lognormal_lengths():
