@@ -38,11 +38,13 @@ harli_status harli_dbg_gemm_clock(const void* A, const void* B, int32_t M, int32
 harli_status harli_dbg_window_plan(int32_t n_layers, int32_t n_slots, const int32_t* items, int32_t n_access, int32_t* slot,
                                    int32_t* miss, int32_t* refill);
 
-/* Kernel timing for the benchmark.  While enabled, every launch of the finetune unit's MFMA GEMM
- * is bracketed by two HIP events on the stream it is launched on.  harli_prof_collect waits for
- * them (it SYNCHRONISES on those events), returns the summed algorithmic flops (2*M*N*K per
- * launch, half of that for causal launches), the summed event-to-event milliseconds and the
- * launch count (all host pointers), and clears the record.  Not thread-safe. */
+/* Kernel timing for the benchmark.  harli_prof_enable(n), n > 0: from now on every n-th launch of the
+ * finetune unit's MFMA GEMM (the first, the (n+1)-th, ...) is bracketed by two HIP events on the stream it is
+ * launched on; n <= 0 switches it off.  (An event pair costs the stream about 10 us of overlap between
+ * neighbouring kernels: timing every launch slows a finetune unit by more than a tenth, so a benchmark samples.)
+ * harli_prof_collect waits for the recorded events (it SYNCHRONISES on them), returns the summed algorithmic
+ * flops (2*M*N*K per launch, half of that for causal launches) and the summed event-to-event milliseconds of the
+ * timed launches and their number (all host pointers), and clears the record.  Not thread-safe. */
 harli_status harli_prof_enable(int32_t on);
 harli_status harli_prof_collect(double* gemm_flops, double* gemm_ms, int64_t* gemm_launches);
 

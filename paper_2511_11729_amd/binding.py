@@ -521,8 +521,9 @@ def dbg_read_bandwidth(buf, mode: int, stream=None) -> float:
     return g.value
 
 
-def prof_enable(on: bool) -> None:
-    _check(lib().harli_prof_enable(int(on)))
+def prof_enable(every: int) -> None:
+    """Time every `every`-th launch of the finetune GEMM from now on (1 or True: all; 0 or False: off)."""
+    _check(lib().harli_prof_enable(int(every)))
 
 
 def prof_collect():

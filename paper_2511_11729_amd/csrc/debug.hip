@@ -82,7 +82,7 @@ extern "C" harli_status harli_dbg_gemm_clock(const void* A, const void* B, int32
 }
 
 extern "C" harli_status harli_prof_enable(int32_t on) {
-  gemm_prof_enable(on != 0);
+  gemm_prof_enable(on);
   return HARLI_OK;
 }
 

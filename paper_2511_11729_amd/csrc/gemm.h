@@ -62,7 +62,7 @@ harli_status gemm_launch(const GemmArgs& a, int batches, hipStream_t st);
 
 // Per-launch timing for the benchmark: when enabled every gemm_launch is bracketed by two events on
 // its stream; collect() waits for them and returns the summed flops, milliseconds and launch count.
-void gemm_prof_enable(bool on);
+void gemm_prof_enable(int every);
 harli_status gemm_prof_collect(double* flops, double* ms, long long* launches);
 
 }  // namespace harli

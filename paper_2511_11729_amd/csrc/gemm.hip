@@ -346,17 +346,21 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
 
 }  // namespace
 
-// ---- optional per-launch timing (harli_prof_*): two events around every GEMM launch ----
+// ---- optional per-launch timing (harli_prof_*): two events around every n-th GEMM launch ----
 namespace {
 struct ProfRec {
   hipEvent_t e0, e1;
   double flops;
 };
-bool g_prof_on = false;
+int g_prof_every = 0;       // 0: off; n: the launches whose running number is a multiple of n are timed
+long long g_prof_seen = 0;  // launches since enabling
 std::vector<ProfRec> g_prof;
 }  // namespace
 
-void gemm_prof_enable(bool on) { g_prof_on = on; }
+void gemm_prof_enable(int every) {
+  g_prof_every = every > 0 ? every : 0;
+  g_prof_seen = 0;
+}
 
 harli_status gemm_prof_collect(double* flops, double* ms, long long* launches) {
   double f = 0.0, t = 0.0;
@@ -420,7 +424,8 @@ harli_status gemm_launch(const GemmArgs& a, int batches, hipStream_t st) {
   const int GM = std::min(kGM, tiles_m), GN = std::min(kGN, tiles_n);
   const int total = ((tiles_m + GM - 1) / GM) * ((tiles_n + GN - 1) / GN) * GM * GN, chunk = (total + 7) / 8;
   ProfRec rec{};
-  if (g_prof_on) {
+  const bool timed = g_prof_every > 0 && (g_prof_seen++ % g_prof_every) == 0;
+  if (timed) {
     HARLI_HIP(hipEventCreate(&rec.e0));
     HARLI_HIP(hipEventCreate(&rec.e1));
     rec.flops = gemm_flops(a, batches);
@@ -438,7 +443,7 @@ harli_status gemm_launch(const GemmArgs& a, int batches, hipStream_t st) {
     else HARLI_GEMM_LAUNCH(false, GEMM_EPI_NONE);
   }
 #undef HARLI_GEMM_LAUNCH
-  if (g_prof_on) {
+  if (timed) {
     HARLI_HIP(hipEventRecord(rec.e1, st));
     g_prof.push_back(rec);
   }
