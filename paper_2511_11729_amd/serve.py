@@ -85,6 +85,14 @@ class DecodeServer:
             prompt = min(prompt, self.max_len - 2)
             out = max(1, min(out, self.max_len - 1 - prompt))
             need = (prompt + 1 + P - 1) // P
+            # headroom: besides the prompt, one more page for every sequence that is running (each reaches a page
+            # boundary within 16 steps); without it a pool smaller than the KV demand admits, runs out, sends a
+            # sequence back to the queue and admits it again, over and over
+            st = self.pool.stats()
+            free_pages = (st.kv_chunks + st.free_chunks) * st.pages_per_block - st.kv_pages_live
+            if self.running and need + len(self.running) > free_pages:
+                self.kv_stalls += 1
+                break
             try:
                 ids = self.pool.alloc_pages(need)
             except hb.HarliError as e:
