@@ -102,10 +102,19 @@ class DecodeServer:
                 break
             self.queue.popleft()
             if self.kv_view is not None:       # the prompt's cache "arrives": its pages are written once
-                idx = torch.tensor(ids, dtype=torch.int64)
-                with torch.cuda.stream(self.stream):   # everything on the decode stream: work on the default stream
-                    idx = idx.to(self.kv_view.device)  # would wait for, and hold up, every restricted stream
-                    self.kv_view[idx // self.ppb, :, idx % self.ppb, :] = 0
+                # One fill per run of neighbouring pages, on the decode stream, and no index tensor: copying one to the
+                # device would make the host wait for every step it has queued, and anything on the default stream
+                # would wait for, and hold up, every restricted stream.
+                with torch.cuda.stream(self.stream):
+                    srt = sorted(ids)
+                    k = 0
+                    while k < len(srt):
+                        c, s0 = divmod(srt[k], self.ppb)
+                        j = k + 1
+                        while j < len(srt) and srt[j] == srt[j - 1] + 1 and srt[j] // self.ppb == c:
+                            j += 1
+                        self.kv_view[c, :, s0:s0 + (j - k), :].zero_()
+                        k = j
             b = len(self.running)
             self.table[b, :] = -1
             self.table[b, :need] = ids
