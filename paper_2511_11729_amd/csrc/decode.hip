@@ -31,6 +31,7 @@ using namespace harli;
 namespace {
 
 constexpr int kPageTokens = 16;
+constexpr int kComputeUnits = 256;  // MI355X; only steers a tiling choice
 
 enum { MODE_QKV = 0, MODE_RESID = 1, MODE_GATEUP = 2, MODE_LM = 3 };
 
@@ -71,7 +72,10 @@ struct SkinnyArgs {
 
 __device__ __forceinline__ uint4 ld16(const unsigned short* p) { return *reinterpret_cast<const uint4*>(p); }
 
-template <int MODE, int NB, int TW, int KW, int U>
+// RT = 16-row weight tiles per wave: a wave holds RT x NB accumulator tiles, so that a batch fragment fetched for a
+// k-step serves RT weight fragments (at 64 batch rows every wave otherwise pulls four batch fragments through the
+// vector cache for each weight fragment it streams).  RT = 1 for small batches, where the weights are the traffic.
+template <int MODE, int NB, int TW, int KW, int U, int RT>
 __global__ void __launch_bounds__(TW * KW * 64) k_skinny(SkinnyArgs a) {
   constexpr int WAVES = TW * KW;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -79,15 +83,15 @@ __global__ void __launch_bounds__(TW * KW * 64) k_skinny(SkinnyArgs a) {
   const int t_w = wave / KW, ks = wave - t_w * KW;
   const int wg = blockIdx.x;
   const int steps = (a.K + 31) >> 5;
+  const int n_tiles = (a.n_rows + 15) >> 4;  // 16-row tiles of the (unpacked) output
 
-  // ---- which 16-row weight tile this wave streams -----------------------------------
-  int which = 0, hl = 0, pidx = 0;  // QKV bookkeeping (uniform over the workgroup)
-  int row0[TW];                     // first output row of each tile of the workgroup
-  const unsigned short* wt;
+  // ---- which 16-row weight tiles this workgroup covers: tile_row0(t, r), t < TW, r < RT ----------
+  int which = 0, hl = 0, pg = 0;  // QKV bookkeeping (uniform over the workgroup)
+  const int half = a.d >> 1;
   if (MODE == MODE_QKV) {
-    const int half = a.d >> 1, pph = half >> 4;
-    const int head = wg / pph;
-    pidx = wg - head * pph;
+    const int ppg = (half >> 4) / RT;  // workgroups per head: the d/2 rotation indices in groups of 16 * RT
+    const int head = wg / ppg;
+    pg = wg - head * ppg;
     if (head < a.n_q) {
       which = 0; hl = head;
     } else if (head < a.n_q + a.n_kv) {
@@ -95,53 +99,73 @@ __global__ void __launch_bounds__(TW * KW * 64) k_skinny(SkinnyArgs a) {
     } else {
       which = 2; hl = head - a.n_q - a.n_kv;
     }
-#pragma unroll
-    for (int t = 0; t < TW; ++t) row0[t] = hl * a.d + t * half + pidx * 16;
-    // q, k and v are packed as one matrix with heads in the order q.., k.., v..
-    const int rt = (head * a.d + t_w * half + pidx * 16) >> 4;
-    wt = a.w0 + ((size_t)rt * steps * 64 + lane) * 8;
-  } else if (MODE == MODE_GATEUP) {
-#pragma unroll
-    for (int t = 0; t < TW; ++t) row0[t] = wg * 16;
-    wt = (t_w == 0 ? a.w0 : a.w1) + ((size_t)wg * steps * 64 + lane) * 8;
-  } else {
-#pragma unroll
-    for (int t = 0; t < TW; ++t) row0[t] = (wg * TW + t) * 16;
-    wt = a.w0 + ((size_t)(wg * TW + t_w) * steps * 64 + lane) * 8;
   }
-  const bool tile_ok = row0[t_w < TW ? t_w : 0] < a.n_rows || MODE == MODE_QKV;
+  // first output row (within its projection) of tile (t, r)
+  auto tile_row0 = [&](int t, int r) -> int {
+    if (MODE == MODE_QKV) return hl * a.d + t * half + (pg * RT + r) * 16;
+    if (MODE == MODE_GATEUP) return (wg * RT + r) * 16;
+    return ((wg * TW + t) * RT + r) * 16;
+  };
+  const unsigned short* wt[RT];
+  bool tile_ok[RT];
+#pragma unroll
+  for (int r = 0; r < RT; ++r) {
+    int tile;  // index of the 16-row tile in the packed matrix this wave reads
+    if (MODE == MODE_QKV) {
+      // q, k and v are packed as one matrix with heads in the order q.., k.., v..
+      const int head = which == 0 ? hl : which == 1 ? a.n_q + hl : a.n_q + a.n_kv + hl;
+      tile = (head * a.d + t_w * half + (pg * RT + r) * 16) >> 4;
+      tile_ok[r] = true;
+    } else {
+      tile = MODE == MODE_GATEUP ? wg * RT + r : (wg * TW + t_w) * RT + r;
+      tile_ok[r] = tile < n_tiles;
+      if (!tile_ok[r]) tile = 0;  // past the last tile: read tile 0 (in bounds), the result is never stored
+    }
+    const unsigned short* base = (MODE == MODE_GATEUP && t_w != 0) ? a.w1 : a.w0;
+    wt[r] = base + ((size_t)tile * steps * 64 + lane) * 8;
+  }
 
   const unsigned short* xf0[NB];
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) xf0[nb] = a.x + (((size_t)((a.b0 >> 4) + nb) * steps) * 64 + lane) * 8;
 
-  f32x4 acc[NB];
+  f32x4 acc[RT][NB];
 #pragma unroll
-  for (int nb = 0; nb < NB; ++nb) acc[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int r = 0; r < RT; ++r)
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) acc[r][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
   // ---- epilogue operands are fetched now, so that the epilogue issues no dependent load ----
   const bool epi = wave < NB;  // wave nb finishes batch tile nb
   const int jb = a.b0 + wave * 16 + i16;
   const bool active = epi && jb < a.B;
   float pre_ssq = 1.f;
-  float2 pre_cs[4];
-  float4 pre_res = make_float4(0.f, 0.f, 0.f, 0.f), pre_g = make_float4(0.f, 0.f, 0.f, 0.f);
+  float2 pre_cs[RT][4];
+  float4 pre_res[RT], pre_g[RT];
   int pre_page = -1, pre_slot = 0;
-  float4 pre_b0 = make_float4(0.f, 0.f, 0.f, 0.f), pre_b1 = make_float4(0.f, 0.f, 0.f, 0.f);  // biases of the two half tiles
+  float4 pre_b0[RT], pre_b1[RT];  // biases of the two half tiles
 #pragma unroll
-  for (int e = 0; e < 4; ++e) pre_cs[e] = make_float2(1.f, 0.f);
+  for (int r = 0; r < RT; ++r) {
+    pre_res[r] = pre_g[r] = pre_b0[r] = pre_b1[r] = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) pre_cs[r][e] = make_float2(1.f, 0.f);
+  }
   if (active) {
     if (MODE != MODE_RESID) pre_ssq = a.ssq_in[jb];
     if (MODE == MODE_QKV) {
-      if (a.bias[which]) {  // rows hl*d + pidx*16 + 4g + e and the same + d/2; d % 32 == 0 keeps them 16-byte aligned
-        const float* bp = a.bias[which] + hl * a.d + pidx * 16 + 4 * g;
-        pre_b0 = *reinterpret_cast<const float4*>(bp);
-        pre_b1 = *reinterpret_cast<const float4*>(bp + (a.d >> 1));
-      }
-      if (which != 2) {
-        const float* cs = a.rope + ((size_t)jb * (a.d >> 1) + pidx * 16 + 4 * g) * 2;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) pre_cs[e] = make_float2(cs[2 * e], cs[2 * e + 1]);
+      for (int r = 0; r < RT; ++r) {
+        const int idx0 = (pg * RT + r) * 16 + 4 * g;  // rotation index of this lane's first row in tile r
+        if (a.bias[which]) {  // rows hl*d + idx0 + e and the same + d/2; d % 32 == 0 keeps them 16-byte aligned
+          const float* bp = a.bias[which] + hl * a.d + idx0;
+          pre_b0[r] = *reinterpret_cast<const float4*>(bp);
+          pre_b1[r] = *reinterpret_cast<const float4*>(bp + half);
+        }
+        if (which != 2) {
+          const float* cs = a.rope + ((size_t)jb * half + idx0) * 2;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) pre_cs[r][e] = make_float2(cs[2 * e], cs[2 * e + 1]);
+        }
       }
       if (which != 0) {
         const int n = a.kv_len[jb];
@@ -153,50 +177,74 @@ __global__ void __launch_bounds__(TW * KW * 64) k_skinny(SkinnyArgs a) {
       }
     }
     if (MODE == MODE_RESID) {
-      const int n0 = row0[0] + 4 * g;
-      if (n0 < a.n_rows) {
-        pre_res = *reinterpret_cast<const float4*>(a.res + (size_t)jb * a.n_rows + n0);
-        if (a.hxn) pre_g = *reinterpret_cast<const float4*>(a.gnext + n0);
+#pragma unroll
+      for (int r = 0; r < RT; ++r) {
+        const int n0 = tile_row0(0, r) + 4 * g;
+        if (n0 < a.n_rows) {
+          pre_res[r] = *reinterpret_cast<const float4*>(a.res + (size_t)jb * a.n_rows + n0);
+          if (a.hxn) pre_g[r] = *reinterpret_cast<const float4*>(a.gnext + n0);
+        }
       }
     }
   }
 
   // ---- stream: each instruction below reads 1 KiB contiguous per wave ---------------------
   const int s_begin = (int)(((long long)steps * ks) / KW), s_end = (int)(((long long)steps * (ks + 1)) / KW);
-  if (tile_ok) {
+  bool any_ok = false;
+#pragma unroll
+  for (int r = 0; r < RT; ++r) any_ok = any_ok || tile_ok[r];
+  if (any_ok) {
     int s = s_begin;
     for (; s + U <= s_end; s += U) {
-      uint4 wf[U], xf[U][NB];
+      uint4 wf[U][RT], xf[U][NB];
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        wf[u] = ld16(wt + (size_t)(s + u) * 512);
+#pragma unroll
+        for (int r = 0; r < RT; ++r) wf[u][r] = ld16(wt[r] + (size_t)(s + u) * 512);
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) xf[u][nb] = ld16(xf0[nb] + (size_t)(s + u) * 512);
       }
 #pragma unroll
       for (int u = 0; u < U; ++u)
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
-          acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wf[u]),
-                                                            __builtin_bit_cast(bf16x8, xf[u][nb]), acc[nb], 0, 0, 0);
+        for (int r = 0; r < RT; ++r)
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb)
+            acc[r][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wf[u][r]),
+                                                                 __builtin_bit_cast(bf16x8, xf[u][nb]), acc[r][nb], 0, 0, 0);
     }
     for (; s < s_end; ++s) {
-      const uint4 wf = ld16(wt + (size_t)s * 512);
+      uint4 xf[NB];
 #pragma unroll
-      for (int nb = 0; nb < NB; ++nb)
-        acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-            __builtin_bit_cast(bf16x8, wf), __builtin_bit_cast(bf16x8, ld16(xf0[nb] + (size_t)s * 512)), acc[nb], 0, 0, 0);
+      for (int nb = 0; nb < NB; ++nb) xf[nb] = ld16(xf0[nb] + (size_t)s * 512);
+#pragma unroll
+      for (int r = 0; r < RT; ++r) {
+        const uint4 wf = ld16(wt[r] + (size_t)s * 512);
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+          acc[r][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wf),
+                                                               __builtin_bit_cast(bf16x8, xf[nb]), acc[r][nb], 0, 0, 0);
+      }
     }
   }
 
-  // ---- reduce the K split through LDS ---------------------------------------------------
+  // ---- per row-tile round r: reduce the K split through LDS, then the epilogue ------------------
   __shared__ float4 red[TW][KW][NB][64];
-#pragma unroll
-  for (int nb = 0; nb < NB; ++nb) red[t_w][ks][nb][lane] = make_float4(acc[nb][0], acc[nb][1], acc[nb][2], acc[nb][3]);
-  __syncthreads();
-
   static_assert(NB <= WAVES, "one epilogue wave per batch tile");
-  if (epi) {
+  float rho = 1.f;
+  if (MODE != MODE_RESID && active) rho = rsqrtf(pre_ssq * a.inv_dim + a.eps);
+  const int steps_n = (a.n_rows + 31) >> 5;
+  float s2 = 0.f;  // RESID: this lane's share of sum x1^2 over the rounds
+
+#pragma unroll
+  for (int r = 0; r < RT; ++r) {
+    if (r > 0) __syncthreads();  // the readers of the previous round are done with `red`
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+      red[t_w][ks][nb][lane] = make_float4(acc[r][nb][0], acc[r][nb][1], acc[r][nb][2], acc[r][nb][3]);
+    __syncthreads();
+    if (!epi) continue;
+
     const int nb = wave;
     float v[TW][4];
 #pragma unroll
@@ -209,84 +257,84 @@ __global__ void __launch_bounds__(TW * KW * 64) k_skinny(SkinnyArgs a) {
       }
       v[t][0] = sacc.x; v[t][1] = sacc.y; v[t][2] = sacc.z; v[t][3] = sacc.w;
     }
-    // this lane holds output rows row0 + 4g + {0..3} of batch entry jb
-    float rho = 1.f;
-    if (MODE != MODE_RESID && active) rho = rsqrtf(pre_ssq * a.inv_dim + a.eps);
+    // this lane holds output rows tile_row0(t, r) + 4g + {0..3} of batch entry jb
 
     if (MODE == MODE_QKV) {
-      if (!active) return;
-      const int half = a.d >> 1;
-      const int idx0 = pidx * 16 + 4 * g;  // rotation index of v[.][0]
-      float r0[4], r1[4];
-      const float b0[4] = {pre_b0.x, pre_b0.y, pre_b0.z, pre_b0.w}, b1[4] = {pre_b1.x, pre_b1.y, pre_b1.z, pre_b1.w};
+      if (active) {
+        const int idx0 = (pg * RT + r) * 16 + 4 * g;  // rotation index of v[.][0]
+        float r0[4], r1[4];
+        const float b0[4] = {pre_b0[r].x, pre_b0[r].y, pre_b0[r].z, pre_b0[r].w};
+        const float b1[4] = {pre_b1[r].x, pre_b1[r].y, pre_b1[r].z, pre_b1[r].w};
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const float a0 = v[0][e] * rho + b0[e], a1 = v[TW - 1][e] * rho + b1[e];
-        if (which != 2) {
-          const float2 cs = pre_cs[e];
-          r0[e] = a0 * cs.x - a1 * cs.y;
-          r1[e] = a1 * cs.x + a0 * cs.y;
+        for (int e = 0; e < 4; ++e) {
+          const float a0 = v[0][e] * rho + b0[e], a1 = v[TW - 1][e] * rho + b1[e];
+          if (which != 2) {
+            const float2 cs = pre_cs[r][e];
+            r0[e] = a0 * cs.x - a1 * cs.y;
+            r1[e] = a1 * cs.x + a0 * cs.y;
+          } else {
+            r0[e] = a0;
+            r1[e] = a1;
+          }
+        }
+        if (which == 0) {
+          float* q = a.qbuf + (size_t)jb * (a.n_q * a.d) + hl * a.d + idx0;
+          *reinterpret_cast<float4*>(q) = make_float4(r0[0], r0[1], r0[2], r0[3]);
+          *reinterpret_cast<float4*>(q + half) = make_float4(r1[0], r1[1], r1[2], r1[3]);
         } else {
-          r0[e] = a0;
-          r1[e] = a1;
+          const int page = pre_page, slot = pre_slot;
+          if (page < 0 || page >= a.geom.n_pages_total) {
+            if (g == 0 && r == 0) atomicOr(a.err_flag, 1);
+          } else {
+            // inside a page the order is [kv head][token slot][head_dim]
+            char* base = a.slab + kv_page_off(a.geom, page, a.layer, which - 1) +
+                         ((size_t)(hl * a.geom.page_tokens + slot) * a.d) * sizeof(unsigned short);
+            unsigned short* dst = reinterpret_cast<unsigned short*>(base) + idx0;
+            *reinterpret_cast<uint2*>(dst) = make_uint2(pack_bf2(r0[0], r0[1]), pack_bf2(r0[2], r0[3]));
+            *reinterpret_cast<uint2*>(dst + half) = make_uint2(pack_bf2(r1[0], r1[1]), pack_bf2(r1[2], r1[3]));
+          }
         }
-      }
-      if (which == 0) {
-        float* q = a.qbuf + (size_t)jb * (a.n_q * a.d) + hl * a.d + idx0;
-        *reinterpret_cast<float4*>(q) = make_float4(r0[0], r0[1], r0[2], r0[3]);
-        *reinterpret_cast<float4*>(q + half) = make_float4(r1[0], r1[1], r1[2], r1[3]);
-      } else {
-        const int page = pre_page, slot = pre_slot;
-        if (page < 0 || page >= a.geom.n_pages_total) {
-          if (g == 0) atomicOr(a.err_flag, 1);
-          return;
-        }
-        // inside a page the order is [kv head][token slot][head_dim]
-        char* base = a.slab + kv_page_off(a.geom, page, a.layer, which - 1) +
-                     ((size_t)(hl * a.geom.page_tokens + slot) * a.d) * sizeof(unsigned short);
-        unsigned short* dst = reinterpret_cast<unsigned short*>(base) + idx0;
-        *reinterpret_cast<uint2*>(dst) = make_uint2(pack_bf2(r0[0], r0[1]), pack_bf2(r0[2], r0[3]));
-        *reinterpret_cast<uint2*>(dst + half) = make_uint2(pack_bf2(r1[0], r1[1]), pack_bf2(r1[2], r1[3]));
       }
     } else if (MODE == MODE_RESID) {
-      const int n0 = row0[0] + 4 * g;
-      const int steps_n = (a.n_rows + 31) >> 5;
-      float s2 = 0.f;
+      const int n0 = tile_row0(0, r) + 4 * g;
       if (active && n0 < a.n_rows) {  // n_rows is a multiple of 8, so the four rows are all in or all out
-        const float4 r = pre_res;
-        const float o0 = r.x + v[0][0], o1 = r.y + v[0][1], o2 = r.z + v[0][2], o3 = r.w + v[0][3];
+        const float4 rs = pre_res[r];
+        const float o0 = rs.x + v[0][0], o1 = rs.y + v[0][1], o2 = rs.z + v[0][2], o3 = rs.w + v[0][3];
         *reinterpret_cast<float4*>(a.out + (size_t)jb * a.n_rows + n0) = make_float4(o0, o1, o2, o3);
         if (a.hxn) {
-          const float4 gn = pre_g;
+          const float4 gn = pre_g[r];
           *reinterpret_cast<uint2*>(a.hxn + xfrag_off(jb, n0, steps_n)) =
               make_uint2(pack_bf2(o0 * gn.x, o1 * gn.y), pack_bf2(o2 * gn.z, o3 * gn.w));
         }
-        s2 = o0 * o0 + o1 * o1 + o2 * o2 + o3 * o3;
+        s2 += o0 * o0 + o1 * o1 + o2 * o2 + o3 * o3;
       }
-      s2 += __shfl_xor(s2, 16, 64);
-      s2 += __shfl_xor(s2, 32, 64);
-      if (active && g == 0 && a.ssq_out) atomicAdd(a.ssq_out + jb, s2);
     } else if (MODE == MODE_GATEUP) {
-      const int n0 = row0[0] + 4 * g;
-      if (!active || n0 >= a.n_rows) return;
-      const int steps_n = (a.n_rows + 31) >> 5;
-      float m[4];
+      const int n0 = tile_row0(0, r) + 4 * g;
+      if (active && n0 < a.n_rows) {
+        float m[4];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const float ga = v[0][e] * rho, up = v[TW - 1][e] * rho;
-        m[e] = ga / (1.f + __expf(-ga)) * up;
+        for (int e = 0; e < 4; ++e) {
+          const float ga = v[0][e] * rho, up = v[TW - 1][e] * rho;
+          m[e] = ga / (1.f + __expf(-ga)) * up;
+        }
+        *reinterpret_cast<uint2*>(a.mbuf + xfrag_off(jb, n0, steps_n)) = make_uint2(pack_bf2(m[0], m[1]), pack_bf2(m[2], m[3]));
       }
-      *reinterpret_cast<uint2*>(a.mbuf + xfrag_off(jb, n0, steps_n)) = make_uint2(pack_bf2(m[0], m[1]), pack_bf2(m[2], m[3]));
     } else {  // MODE_LM
-      if (!active) return;
+      if (active) {
 #pragma unroll
-      for (int t = 0; t < TW; ++t) {
-        const int n0 = row0[t] + 4 * g;
+        for (int t = 0; t < TW; ++t) {
+          const int n0 = tile_row0(t, r) + 4 * g;
 #pragma unroll
-        for (int e = 0; e < 4; ++e)
-          if (n0 + e < a.n_rows) a.logits[(size_t)jb * a.n_rows + n0 + e] = v[t][e] * rho;
+          for (int e = 0; e < 4; ++e)
+            if (n0 + e < a.n_rows) a.logits[(size_t)jb * a.n_rows + n0 + e] = v[t][e] * rho;
+        }
       }
     }
+  }
+  if (MODE == MODE_RESID && epi) {
+    s2 += __shfl_xor(s2, 16, 64);
+    s2 += __shfl_xor(s2, 32, 64);
+    if (active && g == 0 && a.ssq_out) atomicAdd(a.ssq_out + jb, s2);
   }
 }
 
@@ -635,32 +683,44 @@ __global__ void __launch_bounds__(64) k_argmax_final(const float* part_v, const 
   if (lane == 0) next_token[b] = bi;
 }
 
-template <int MODE, int NB, int TW, int KW, int U>
+template <int MODE, int NB, int TW, int KW, int U, int RT>
 void launch_skinny(const SkinnyArgs& a, int n_wg, hipStream_t st) {
-  hipLaunchKernelGGL((k_skinny<MODE, NB, TW, KW, U>), dim3(n_wg), dim3(TW * KW * 64), 0, st, a);
+  hipLaunchKernelGGL((k_skinny<MODE, NB, TW, KW, U, RT>), dim3((n_wg + RT - 1) / RT), dim3(TW * KW * 64), 0, st, a);
 }
 
 // passes of at most 64 batch rows (128 where the workgroup has eight waves to finish eight batch tiles and more than
-// 64 rows are left: every pass streams the whole weight matrix again); NB = 16-row batch tiles per pass
+// 64 rows are left: every pass streams the whole weight matrix again); NB = 16-row batch tiles per pass.
+// n_wg: workgroups at one weight tile per wave.
 template <int MODE, int TW, int KW>
 void dispatch_skinny(SkinnyArgs a, int n_wg, hipStream_t st) {
+  // Two weight tiles per wave (RT = 2) halve the workgroups.  Measured on 256 compute units: with 64 rows per pass
+  // it pays only where two workgroups per compute unit remain (gate/up, output layer; the 256-tile projections lost
+  // more from running on half the chip than they gained); with 128 rows per pass it pays everywhere.  q,k,v: the
+  // rotation indices of a head (d/2) split into groups of 16 * RT; d = 32 has a single 16-row group.
+  const bool rt_ok = MODE != MODE_QKV || (a.d >> 5) % 2 == 0;
+  const bool rt2_64 = rt_ok && n_wg >= 2 * kComputeUnits;
   for (int b0 = 0; b0 < a.B;) {
     a.b0 = b0;
     const int left = a.B - b0;
     if constexpr (TW * KW >= 8) {
       if (left > 64) {
-        launch_skinny<MODE, 8, TW, KW, 1>(a, n_wg, st);
+        if (rt_ok)
+          launch_skinny<MODE, 8, TW, KW, 1, 2>(a, n_wg, st);
+        else
+          launch_skinny<MODE, 8, TW, KW, 1, 1>(a, n_wg, st);
         b0 += 128;
         continue;
       }
     }
     const int nb = (min(left, 64) + 15) / 16;
     if (nb == 1)
-      launch_skinny<MODE, 1, TW, KW, 8>(a, n_wg, st);
+      launch_skinny<MODE, 1, TW, KW, 8, 1>(a, n_wg, st);
     else if (nb == 2)
-      launch_skinny<MODE, 2, TW, KW, 4>(a, n_wg, st);
+      launch_skinny<MODE, 2, TW, KW, 4, 1>(a, n_wg, st);
+    else if (rt2_64)
+      launch_skinny<MODE, 4, TW, KW, 2, 2>(a, n_wg, st);
     else
-      launch_skinny<MODE, 4, TW, KW, 2>(a, n_wg, st);
+      launch_skinny<MODE, 4, TW, KW, 2, 1>(a, n_wg, st);
     b0 += 64;
   }
 }
