@@ -26,7 +26,6 @@ import argparse
 import json
 import os
 import sys
-import threading
 import time
 
 import numpy as np

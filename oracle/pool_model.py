@@ -32,7 +32,7 @@ Where the paper gives no rule, the policy is fixed as "lowest index first":
 """
 from __future__ import annotations
 
-from typing import Dict, List, Optional, Tuple
+from typing import Dict, List, Tuple
 
 FREE, KV, TENSOR = 0, 1, 2
 CLS_KV_PAGE, CLS_TENSOR, CLS_SMALL, CLS_AUTO = 0, 1, 2, 3

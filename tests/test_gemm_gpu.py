@@ -3,7 +3,6 @@
 Inputs are exactly representable, accumulation is fp32, so the fp32 output must agree to fp32
 round-off of a K-term sum; the bf16 outputs to one bf16 rounding.
 """
-import numpy as np
 import pytest
 import torch
 

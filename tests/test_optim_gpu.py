@@ -10,7 +10,7 @@ import workloads as wl
 from oracle import harli_oracle as O
 from oracle.optim_oracle import adamw_step
 from paper_2511_11729_amd import binding as hb
-from tests.gpu_util import FinetuneCase, f32_dev, shapes_of, to_dev
+from tests.gpu_util import FinetuneCase, f32_dev, shapes_of
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"

@@ -5,12 +5,10 @@ tests/test_decode_gpu.py; here the moving page tables are checked through a seco
 import argparse
 import dataclasses
 
-import numpy as np
 import pytest
 import torch
 
 import workloads as wl
-from paper_2511_11729_amd import binding as hb
 from paper_2511_11729_amd import bench_serve, serve
 
 pytestmark = pytest.mark.gpu
