@@ -201,6 +201,11 @@ def make_plan(args, m, ft, pool, ctx, ft_step, server, log):
     rep = {k: rep[k] for k in ("eq1_mean_abs_err_fitted_points", "eq1_mean_abs_err_heldout", "eq2_b1_k1", "eq2_mean_abs_err")}
     cs = colocate.CuStreams()
     low, high = cs.pairs(log)
+    ft_all = None
+    if args.ft_all_cus:                              # only inference is confined; the finetune task may use every compute unit
+        ft_all = cs.unrestricted
+        if ft_all is None:
+            raise SystemExit("bench_serve: no ordinary stream off the inference streams' dispatch pipes was found")
     sched = hb.Scheduler(pred, args.slo_ms * args.sched_margin, 64)
 
     scale = [1.0] * (colocate.N_LEVELS + 1)         # per level: measured / predicted decode step, smoothed
@@ -243,7 +248,7 @@ def make_plan(args, m, ft, pool, ctx, ft_step, server, log):
         srv.use_stream(low[i])
         srv.tag = (i, pred_ms / scale[i])           # the prediction before calibration
         if worker is not None:
-            worker.target = high[f] if f > 0 else None
+            worker.target = (ft_all if ft_all is not None else high[f]) if f > 0 else None
         return (i, f, act, pred_ms, n)
 
     rep["planned_for_ms"] = args.slo_ms * args.sched_margin
@@ -273,6 +278,10 @@ def main():
     ap.add_argument("--static", type=int, nargs=2, default=None, metavar=("I", "F"),
                     help="with --sched: no runtime scheduling, inference on the first I tenths of the compute units and the "
                          "finetune task on the last F tenths (0: paused) throughout")
+    ap.add_argument("--ft-all-cus", action="store_true",
+                    help="with --sched: only the inference partition is enforced; finetune units run on every compute unit "
+                         "(outside the paper's disjoint plans; the decode step is then slower than the profile says and "
+                         "the calibration takes that up)")
     ap.add_argument("--no-feedback", action="store_true",
                     help="with --sched: plan with the profiled predictor alone, without folding measured step times back in")
     ap.add_argument("--dump", default=None, help="with --sched: per-step records (batch, plan, predicted and measured times) as CSV")

@@ -31,6 +31,7 @@ class CuStreams:
         self._raw = []
         self._big = self._small = None
         self.shared_pipe = []                      # partitions whose two streams ended up on one pipe (see pairs)
+        self.unrestricted = None                   # after pairs(): an ordinary stream that shares a pipe with no inference stream
 
     def make(self, first: int, count: int):
         raw = hb.cu_stream_create(first, count)
@@ -123,6 +124,9 @@ class CuStreams:
             # the full-chip stream runs beside finetune units still in flight on their partition after a pause
             clean = [c for c in cands if not any(self._conflict(c, high[f]) for f in high)]
             low[N_LEVELS] = clean[0] if clean else cands[0]
+            # an ordinary stream (every compute unit) for a finetune task that is not restricted: on no inference pipe
+            free = [c for c in cands if c is not low[N_LEVELS] and not any(self._conflict(c, low[i]) for i in range(1, N_LEVELS))]
+            self.unrestricted = free[0] if free else None
             bad = self.conflicts(low, high) + ([] if clean else [(N_LEVELS, 0)])
             return made, low, high, bad
 

@@ -110,7 +110,7 @@ def test_scheduled_trace_places_both_tasks_on_partitions_and_calibrates():
     into the predictor.  Checks the plumbing end to end: valid plans, finetune progress, factors inside their clip,
     a clean pool, and no stream or event left behind (the process goes on to run other tests)."""
     args, w, m, ft, pool, ctx, ft_step, info, keep = small(max_batch=32, max_len=600, ft_tokens=(4, 128))
-    args.sched_margin, args.static, args.no_feedback = 0.9, None, False
+    args.sched_margin, args.static, args.no_feedback, args.ft_all_cus = 0.9, None, False, False
     args.slo_ms = 5.0
     sD = torch.cuda.Stream()
     with torch.cuda.stream(sD):
