@@ -9,6 +9,14 @@ AdamW) and takes its saved activations from the SAME pool, backing off when the 
 it.  Prints one JSON line: time per output token (p50 / p99 / max, share of steps inside the target), decode and
 finetune tokens/s, admission stalls, pre-emptions, finetune out-of-memory retries and the pool's chunk census over
 time.  --pool-gb sizes the slab: roomy by default, tight to exercise the coordination.
+
+--sched profiles the latency predictor on compute-unit partitions first (Sec. 5: Eq. 1 per level on the whole model,
+Eq. 2 beside whole training steps) and then lets the runtime scheduler (Sec. 6.2) place both tasks at the beginning of
+every decode phase: decode on the first tenths of the compute units, the finetune task's next layer unit on the last
+tenths, or paused.  The plan hook also times the finished steps and folds measured / predicted back into the predictor
+per level (--no-feedback: the profiled predictor alone).  Comparators: --static I F (one partition throughout, the
+shape of the paper's StaticMode), --ft-all-cus (only the inference partition enforced).  --dump writes one CSV row per
+decode step (batch, plan, predicted and measured times).
 """
 from __future__ import annotations
 
