@@ -387,7 +387,7 @@ class FinetuneFeeder:
             raise RuntimeError("the finetune thread failed") from self.error
 
 
-def run_trace(hz, pred, slo_ms, segments, seqlen, refresh_phases=32, starve=(), log=lambda *a: None):
+def run_trace(hz, pred, slo_ms, segments, seqlen, refresh_phases=32, starve=(), log=lambda *a: None, feedback=True):
     """Replays a decode load trace under the runtime scheduler (Sec. 6.2) on compute-unit partitions.
 
     segments: [(phases, batch), ...]; every sequence has `seqlen` cached tokens.  At the beginning of each decode
@@ -395,10 +395,14 @@ def run_trace(hz, pred, slo_ms, segments, seqlen, refresh_phases=32, starve=(), 
     units, the finetune task on the last ft_level tenths (or not at all).  `starve`: phase indices at which the
     finetune task reports no ready work.  The host waits for each decode step before deciding the next phase.
     Returns per-phase records and a per-segment summary (latency percentiles, share of phases within the target,
-    finetune units completed)."""
+    finetune units completed).  feedback: every measured step corrects the predictor at its level by the smoothed ratio
+    measured / predicted (`harli_pred_set_scale`, an addition to the paper's scheduler: Eq. 1 is a straight line in the
+    batch size and misses a step on a tenth of the chip by 10 %, enough to pick a plan just above the target); the
+    factors are set back to 1 before returning."""
     cs = CuStreams()
     low, high = cs.pairs()
     sched = hb.Scheduler(pred, slo_ms, refresh_phases)
+    scale = [1.0] * (N_LEVELS + 1)
     dev = hz.x_dev.device
     starve = set(starve)
     rec = []
@@ -426,8 +430,13 @@ def run_trace(hz, pred, slo_ms, segments, seqlen, refresh_phases=32, starve=(), 
                 e1.record(st)
                 e1.synchronize()
                 last_stream, last_ev = st, e1
+                ms = e0.elapsed_time(e1)
                 rec.append({"phase": g, "batch": bs, "infer_level": i, "ft_level": f, "action": act, "predicted_ms": pred_ms,
-                            "latency_ms": e0.elapsed_time(e1)})
+                            "latency_ms": ms})
+                if feedback and pred_ms > 0.0:
+                    r = min(2.5, max(0.6, ms / (pred_ms / scale[i])))
+                    scale[i] += 0.5 * (r - scale[i])
+                    pred.set_scale(i, scale[i])
                 g += 1
             dt = time.perf_counter() - t0
             lat = np.array([r["latency_ms"] for r in rec[first:]])
@@ -440,7 +449,9 @@ def run_trace(hz, pred, slo_ms, segments, seqlen, refresh_phases=32, starve=(), 
             log("[trace] batch %d: %s" % (bs, summary[-1]))
         feeder.target = None
     sched.close()
+    for lv in range(1, N_LEVELS + 1):
+        pred.set_scale(lv, 1.0)
     _quiesce(hz)
     cs.close()
     hz.ctx.check(torch.cuda.current_stream())
-    return {"phases": rec, "segments": summary}
+    return {"phases": rec, "segments": summary, "calibration_by_level": scale[1:]}

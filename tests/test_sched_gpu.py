@@ -83,7 +83,7 @@ def test_runtime_scheduler_replays_a_load_trace(hz):
     slo = 40.0 / 32.0
     segs = [(40, 8), (40, 42), (40, 24)]
     starve = set(range(20, 24)) | set(range(100, 103))
-    out = colocate.run_trace(hz, pred, slo, segs, seqlen=1024, refresh_phases=16, starve=starve)
+    out = colocate.run_trace(hz, pred, slo, segs, seqlen=1024, refresh_phases=16, starve=starve, log=print)
     ph, sg = out["phases"], out["segments"]
     assert len(ph) == 120
     for r in ph:
