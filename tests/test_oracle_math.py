@@ -456,7 +456,7 @@ def test_head_matches_torch_autograd():
     z = h @ torch.tensor(W).T
     l = torch.nn.functional.cross_entropy(z, torch.tensor(t), ignore_index=-1, reduction="mean")
     l.backward()
-    assert abs(float(l) - loss) < 1e-12 and np.allclose(tx.grad.numpy(), dx, rtol=1e-10, atol=1e-14)
+    assert abs(float(l.detach()) - loss) < 1e-12 and np.allclose(tx.grad.numpy(), dx, rtol=1e-10, atol=1e-14)
 
 
 def test_head_uniform_logits_give_log_vocab():
