@@ -23,6 +23,7 @@ oracle timed on a bounded sample of the same finetune workload on this machine's
 from __future__ import annotations
 
 import argparse
+import gc
 import json
 import os
 import sys
@@ -165,10 +166,14 @@ def main():
         ctx.check(sD)
         return r
 
-    # The first time the two tasks run side by side in a process, one finetune unit (measured: around the 13th) takes a
-    # single stall of about 23 ms that does not come back; every later unit takes its steady 3.2-3.3 ms.  Over 40 timed
-    # units that one stall is 15 % of the figure, so a short untimed co-located run goes first (set-up, as the solo
-    # runs above are); the W warm-up units requested on the command line still run inside run_colocated.
+    # A full garbage collection of this process takes about 20 ms (the set-up leaves many long-lived Python objects
+    # behind); when one falls into a timed window the thread that issues finetune units stops for that long, the six
+    # units it keeps queued run dry and one unit "takes" 23 ms -- 15 % of a 40-unit window (measured: the stall is gone
+    # with the collector off).  The set-up's objects are moved out of the collector's sight, and a short untimed
+    # co-located run goes first (set-up, as the solo runs above are); the W warm-up units requested on the command line
+    # still run inside run_colocated.
+    gc.collect()
+    gc.freeze()
     log("[bench] co-located settling run (untimed)")
     colocate.run_colocated(hz, sD, sF, decode_once, 24, 0, None)
     log("[bench] co-located, decode in a closed loop: %d warmup + %d timed finetune units" % (W, K))
@@ -273,11 +278,11 @@ def main():
         # the clock the chip sustains under the GEMM itself (seen from inside the kernel), on random half operands
         ga = (torch.rand(2048, 4096, device=dev) - 0.5).half()
         gb = (torch.rand(4096, 4096, device=dev) - 0.5).half()
-        gc = torch.empty(2048, 4096, dtype=torch.float16, device=dev)
-        tf, mhz = hb.dbg_gemm_clock(ga, gb, gc, half=True, reps=50)
+        gout = torch.empty(2048, 4096, dtype=torch.float16, device=dev)
+        tf, mhz = hb.dbg_gemm_clock(ga, gb, gout, half=True, reps=50)
         peaks["gemm_2048x4096x4096_back_to_back"] = {"TFLOPs": tf, "shader_clock_MHz": mhz, "nominal_clock_MHz": 2400,
                                                      "note": "the published 2.5 PFLOP/s is at the nominal clock"}
-        del ga, gb, gc
+        del ga, gb, gout
 
     ach_tf = gemm_flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else float("nan")
     out = {

@@ -183,6 +183,9 @@ def main():
                 "within_slo": float(np.mean(tp <= args.slo_ms)), "decode_steps": int(len(tp)),
                 "decode_tokens_per_s": B * len(tp) / r["elapsed"]}
 
+    import gc
+    gc.collect()
+    gc.freeze()                                     # a full collection over the set-up's objects stops the host for ~20 ms
     closed = colocate.run_colocated(hz, sD, sF, decode_once, args.steps, 1, None)
     ctx.check(sD)
     pace = args.pace_ms if args.pace_ms is not None else 0.6 * args.slo_ms

@@ -318,6 +318,9 @@ def main():
     plan, sched_report, cs = None, None, None
     if scheduled:
         plan, sched_report, cs = make_plan(args, m, ft, pool, ctx, ft_step, server, log)
+    import gc
+    gc.collect()
+    gc.freeze()                                     # a full collection over the set-up's objects stops the host for ~20 ms
     res = serve.replay(server, arrivals, factory, slo_ms=args.slo_ms, log=log, plan=plan)
     server.drain()
     server.use_stream(sD)
