@@ -260,7 +260,10 @@ harli_status harli_saved_bytes(const harli_ctx* c, int32_t B_f, int32_t S, size_
  * orientation; n_slots is capped at 2 * n_layers, which is everything).  A training step uses the copies in a fixed
  * cyclic order -- W of layers 0..L-1, then W^T of layers L-1..0 -- and harli_lora_fwd / harli_lora_bwd make their
  * stream wait for the copy they need, then, once the layer is enqueued, refill its slot over a library-owned copy
- * stream with the nearest copy ahead in that order that is not on the device (the first layer outside the window).
+ * stream with the nearest copy among the next min(n_slots, 4) in that order that is not on the device; when those are
+ * all there the layer's own copy stays.  Up to four slots that is the paper's sliding window (the first layer outside
+ * the window replaces the layer just computed: 2L copies per step); with more slots the others keep their copies and a
+ * step moves (2L - n_slots) * 2L / (2L - 4) copies on average, so the traffic falls as the window grows.
  * A copy requested while absent (another order of calls, a window just resized) is loaded on demand.  Frozen weights
  * never change, so eviction writes nothing back.  Results are bit-identical with and without a window.
  * enable: HARLI_ERR_STATE before lora_attach or when a window exists; HARLI_ERR_OOM when the pool cannot hold n_slots

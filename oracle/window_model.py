@@ -11,10 +11,18 @@ has been computed its frozen weights are evicted and those of the first layer ou
 * access of an item that is resident: hit;
 * access of an absent item: it is loaded at once into an empty slot, else into the slot whose item comes latest
   in the cyclic order counted from the accessed item;
-* after every access the slot just used is refilled with the nearest item ahead (1..n steps) that is absent; if all
-  of them are present (n >= 2L covers the whole cycle) nothing is loaded.
+* after every access the slot just used is refilled with the nearest absent item among the next min(n, LOOKAHEAD);
+  if all of them are present nothing is loaded and the used item stays.  Up to LOOKAHEAD slots this is the paper's
+  sliding window (one copy per use).  Reading taken for larger windows: the paper gives the window as the means to
+  trade memory for copy traffic (Sec. 4.3, 4.4) without stating a policy for windows much larger than the prefetch
+  distance; evicting on every use would copy all 2L items per step whatever the window size, so only the next
+  LOOKAHEAD items are prefetched and the remaining slots keep what they hold ((2L - n) * 2L / (2L - LOOKAHEAD) copies per
+  step on average).
 """
 from __future__ import annotations
+
+
+LOOKAHEAD = 4
 
 
 def item_of(layer: int, backward: bool, n_layers: int) -> int:
@@ -46,7 +54,7 @@ class Window:
             self.slots[s] = item
             miss = item
         refill = -1
-        for d in range(1, self.n + 1):
+        for d in range(1, min(self.n, LOOKAHEAD) + 1):
             cand = (item + d) % self.items
             if cand == item:
                 break

@@ -112,6 +112,7 @@ def main():
     ctx.check(st)
     l0 = float(loss)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    h2d0 = ctx.ft_window_stats().h2d_bytes
     e0.record(st)
     for t in range(args.steps):
         step(t + 2)
@@ -123,7 +124,7 @@ def main():
     ws = ctx.ft_window_stats()
     window = None
     if ws.slots > 0:
-        per_step = 2 * L * ws.slot_bytes if ws.slots < 2 * L else 0
+        per_step = (ws.h2d_bytes - h2d0) / args.steps       # what the timed steps copied from the host
         window = {"slots": ws.slots, "slot_MB": ws.slot_bytes / 1e6, "host_pinned_GB": ws.host_bytes / 1e9,
                   "h2d_GB_per_step": per_step / 1e9, "h2d_GBs": per_step / ms / 1e6, "hits": ws.hits, "misses": ws.misses,
                   "refills": ws.refills}

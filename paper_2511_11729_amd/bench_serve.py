@@ -76,6 +76,8 @@ def build(args, model=None):
     else:                                                 # roomy: the largest phase's KV cache plus a whole step's activations
         kv_tokens = args.max_batch * min(args.max_len, 1400)
         n_chunks = -(-kv_tokens * 2 * m.kv_row_bytes * L // chunk) + act_chunks + 8
+        if getattr(args, "window", None):             # the window's slots are pool memory too
+            n_chunks += min(args.window, 2 * L) * (-(-2 * m.layer_params // chunk) + 1)
     slab_bytes = small + n_chunks * chunk
     slab = torch.zeros(slab_bytes, dtype=torch.uint8, device=dev)
     pool = hb.Pool(slab, slab_bytes, block_bytes=block, n_layers=L, kv_row_bytes=m.kv_row_bytes, small_pool_bytes=small,
@@ -280,6 +282,10 @@ def main():
     ap.add_argument("--slo-ms", type=float, default=40.0)
     ap.add_argument("--release-ms", type=float, default=12.0, help="time the finetune task needs to give memory back")
     ap.add_argument("--no-finetune", action="store_true")
+    ap.add_argument("--window", type=int, default=None, metavar="SLOTS",
+                    help="keep the finetune task's frozen weights on the host and at most SLOTS of the 2 x layers copies in the "
+                         "pool (Sec. 4.3); between steps the window shrinks when inference needs memory and grows again when "
+                         "chunks are free (Sec. 4.4)")
     ap.add_argument("--sched", action="store_true",
                     help="profile the latency predictor on compute-unit partitions first, then let the runtime scheduler "
                          "place both tasks at the beginning of every decode phase (Sec. 5, Sec. 6.2)")
@@ -299,6 +305,7 @@ def main():
     import faulthandler
     import torch
     import workloads as wl
+    from paper_2511_11729_amd import binding as hb
     from paper_2511_11729_amd import serve
 
     faulthandler.enable()                           # a crash in native code names the Python line it came from
@@ -313,8 +320,48 @@ def main():
     arrivals = wl.make_arrivals(w, args.steps, tuple(args.targets), args.mean_out,
                                 prompt=w.decode.len_dist if w.decode.len_dist[0] == "lognormal" else ("lognormal", 800, 0.6, 8192))
     arrivals = [[(min(p, args.max_len - 2), o) for p, o in reqs] for reqs in arrivals]
-    factory = None if args.no_finetune else (lambda: serve.FinetuneWorker(pool, ft_step, sF, ft.tokens))
     log = lambda *a: print(*a, file=sys.stderr, flush=True)
+    step_fn, window_log = ft_step, []
+    if args.window is not None and not args.no_finetune:
+        # Sec. 4.3 / 4.4: the finetune task's frozen weights live on the host and only a window of them in the pool;
+        # between training steps the window gives slots back when inference needs the memory and takes slots again when
+        # chunks are free.  (No finetune unit is in flight between steps: ft_step ends with a wait for its stream.)
+        L2 = 2 * m.n_layers
+        ctx.ft_window_enable(min(args.window, L2))
+        ws0 = ctx.ft_window_stats()
+        slot_chunks = -(-ws0.slot_bytes // chunk)
+        log("[window] %d of %d slots of %.0f MB on the device" % (ws0.slots, L2, ws0.slot_bytes / 1e6))
+        state = {"oom": False, "calm": 0}
+        T_, H_ = ft.tokens, m.hidden
+        per_layer = T_ * H_ * 12 + T_ * m.n_q * m.head_dim * 4 + T_ * m.n_kv * m.head_dim * 4 + T_ * m.ffn * 6
+        need = (m.n_layers + 1) * (per_layer // chunk + 2) + reserve + 8     # a step's saved activations, the KV reserve, slack
+        top = min(args.window, L2)
+
+        def step_fn(wk):
+            ws, st = ctx.ft_window_stats(), pool.stats()
+            target = ws.slots
+            if pool.pressure() > 0 or state["oom"] or st.free_chunks < need:
+                short = max(need - st.free_chunks, slot_chunks)
+                target, state["calm"] = max(4, ws.slots - 4 * (-(-short // (4 * slot_chunks)))), 0
+            elif st.free_chunks > need + 8 * slot_chunks and ws.slots < top:
+                state["calm"] += 1
+                if state["calm"] >= 2:                  # room two steps in a row: take four slots back
+                    target = min(top, ws.slots + 4)
+            else:
+                state["calm"] = 0
+            if target != ws.slots:
+                try:
+                    ctx.ft_window_resize(target)
+                except hb.HarliError as e:
+                    if e.status != hb.HARLI_ERR_OOM:
+                        raise
+                window_log.append({"decode_step": server.step_no, "slots": ctx.ft_window_stats().slots,
+                                   "free_chunks": pool.stats().free_chunks})
+            ok = ft_step(wk)
+            state["oom"] = not ok
+            return ok
+
+    factory = None if args.no_finetune else (lambda: serve.FinetuneWorker(pool, step_fn, sF, ft.tokens))
     plan, sched_report, cs = None, None, None
     if scheduled:
         plan, sched_report, cs = make_plan(args, m, ft, pool, ctx, ft_step, server, log)
@@ -356,6 +403,11 @@ def main():
     res["pool"] = {"chunks": n_chunks, "chunk_MB": chunk / 1e6, "slab_GB": slab_bytes / 1e9, "reserve_chunks": reserve,
                    "kv_pages_live_at_end": st.kv_pages_live, "tensor_blocks_live_at_end": st.tensor_blocks_live}
     res["slo_tpot_ms"] = args.slo_ms
+    if args.window is not None and not args.no_finetune:
+        ws = ctx.ft_window_stats()
+        res["window"] = {"slots_at_start": ws0.slots, "slots_at_end": ws.slots, "slot_MB": ws.slot_bytes / 1e6,
+                         "host_GB": ws.host_bytes / 1e9, "h2d_GB": ws.h2d_bytes / 1e9, "hits": ws.hits, "misses": ws.misses,
+                         "refills": ws.refills, "resizes": window_log[:: max(1, len(window_log) // 40)]}
     snaps = res.pop("snapshots")
     res["pool_census"] = snaps[:: max(1, len(snaps) // 24)]
     print(json.dumps(res))

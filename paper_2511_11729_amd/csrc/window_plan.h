@@ -3,13 +3,20 @@
 // One training step touches the frozen weights in a fixed cyclic order: the forward copies W of layers 0..L-1, then the
 // transposed copies W^T of layers L-1..0 (the backward pass), then the next step's forward again.  Numbering these
 // 2L "items" 0..2L-1 in that order, a window of n device slots holds the items about to be used.  After an item has
-// been used its slot receives the nearest item ahead that no slot holds (in steady state: the item n steps ahead, "the
-// first layer outside the window"); an item requested while absent (out-of-order use, or a window that was just
-// resized) is loaded on demand into an empty slot or, failing that, the slot whose item is needed farthest in the future.
+// been used its slot receives the nearest item among the next min(n, kLookahead) that no slot holds; when all of them
+// are on the device the used item simply stays.  With n <= kLookahead this is the paper's sliding window (every use
+// evicts the layer just computed and prefetches "the first layer outside the window": 2L copies per step whatever n);
+// with more slots only the next kLookahead items are prefetched and the other n - kLookahead slots keep their items,
+// so a step copies (2L - n) * 2L / (2L - kLookahead) items on average instead of 2L -- the traffic falls as the window grows, which
+// is what makes shrinking and growing the window under memory pressure (Sec. 4.4) a smooth trade.  An item requested
+// while absent (out-of-order use, or a window that was just resized) is loaded on demand into an empty slot or,
+// failing that, the slot whose item is needed farthest in the future.
 #pragma once
 #include <vector>
 
 namespace harli {
+
+constexpr int kLookahead = 4;  // uses between the start of a copy and the use of the item (a copy takes 2-3 layer units)
 
 struct WindowPlan {
   int L = 0, n = 0;
@@ -39,7 +46,8 @@ struct WindowPlan {
     return best;
   }
   int refill_after(int item) const {
-    for (int d = 1; d <= n; ++d) {
+    const int k = n < kLookahead ? n : kLookahead;
+    for (int d = 1; d <= k; ++d) {
       const int cand = (item + d) % items();
       if (cand == item) return -1;
       if (find(cand) < 0) return cand;

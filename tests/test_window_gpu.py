@@ -6,6 +6,7 @@ import pytest
 import torch
 
 from oracle import harli_oracle as O
+from oracle import window_model as WM
 from paper_2511_11729_amd import binding as hb
 from tests.gpu_util import assert_close, f32_dev, shapes_of
 from tests.test_head_gpu import DEV, ModelCase
@@ -53,7 +54,7 @@ def test_training_step_is_bit_identical_under_every_window():
     base = run_step(case)
     assert case.ctx.ft_window_stats().slots == 0 and case.ctx.ft_window_ready(3, True)
     free0 = case.pool.stats().tensor_blocks_live
-    for n in (1, 2, 3, 5, 8, 50):
+    for n in (1, 2, 3, 5, 6, 7, 8, 50):
         case.ctx.ft_window_enable(n)
         st0 = case.ctx.ft_window_stats()
         n_eff = min(n, 2 * L)
@@ -66,7 +67,9 @@ def test_training_step_is_bit_identical_under_every_window():
             assert same(run_step(case), base), "window of %d slots, step %d" % (n, rep)
         st = case.ctx.ft_window_stats()
         assert st.hits == 4 * L and st.misses == 0
-        assert st.refills == (4 * L if n_eff < 2 * L else 0)
+        model = WM.Window(L, n_eff)                                          # the copies follow the model's plan
+        want_refills = sum(model.access(it)[2] >= 0 for it in list(range(2 * L)) * 2)
+        assert st.refills == want_refills and (want_refills == 4 * L) == (n_eff <= WM.LOOKAHEAD)
         assert st.h2d_bytes == (n_eff + st.refills) * st.slot_bytes
         with pytest.raises(hb.HarliError) as e:
             case.ctx.ft_window_enable(2)
