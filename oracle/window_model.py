@@ -29,14 +29,29 @@ def item_of(layer: int, backward: bool, n_layers: int) -> int:
     return 2 * n_layers - 1 - layer if backward else layer
 
 
+def wanted_items(n_layers: int, n_slots: int, first: int = 0):
+    """What a window of n_slots holds before `first` is used, in order of use: everything if it fits; the next n_slots
+    items up to LOOKAHEAD slots (the sliding window); otherwise the next LOOKAHEAD items and, of the rest, all but
+    2L - n_slots items spread evenly over the cycle (offset LOOKAHEAD + floor((2j + 1)(2L - LOOKAHEAD) / (2m)) for
+    the j-th of the m absent ones).  The refill rule moves an absent item LOOKAHEAD places back each time it comes up,
+    so the spread stays even and the copies of a step are never neighbours in the order of use."""
+    N = 2 * n_layers
+    if n_slots >= N:
+        return [(first + d) % N for d in range(N)]
+    if n_slots <= LOOKAHEAD:
+        return [(first + d) % N for d in range(n_slots)]
+    m = N - n_slots
+    absent = {LOOKAHEAD + ((2 * j + 1) * (N - LOOKAHEAD)) // (2 * m) for j in range(m)}
+    return [(first + d) % N for d in range(N) if d not in absent]
+
+
 class Window:
     def __init__(self, n_layers: int, n_slots: int, prefill: bool = True):
         self.items = 2 * n_layers
         self.n = n_slots
         self.slots = [-1] * n_slots
         if prefill:
-            for s in range(min(n_slots, self.items)):
-                self.slots[s] = s
+            self.slots = wanted_items(n_layers, min(n_slots, self.items))
 
     def _ahead(self, frm: int, to: int) -> int:
         return (to - frm) % self.items

@@ -75,12 +75,19 @@ harli_status drain(FtWindow* w) {
   return HARLI_OK;
 }
 
-// fills empty slots with the nearest absent items after the last one used
+// fills empty slots: first with the items the plan wants on the device from here on (in order of use), then, if slots
+// are still empty, with the nearest absent items after the last one used
 harli_status fill_empty(FtWindow* w) {
   const int base = w->last_item < 0 ? w->plan.items() - 1 : w->last_item;
+  const std::vector<int> want = w->plan.wanted_items((base + 1) % w->plan.items(), w->plan.n);
+  size_t k = 0;
   for (int s = 0; s < w->plan.n; ++s) {
     if (w->plan.slot_item[s] >= 0) continue;
     int cand = -1;
+    while (k < want.size() && cand < 0) {
+      if (w->plan.find(want[k]) < 0) cand = want[k];
+      ++k;
+    }
     for (int d = 1; d < w->plan.items() + 1 && cand < 0; ++d) {
       const int it = (base + d) % w->plan.items();
       if (w->plan.find(it) < 0) cand = it;
@@ -239,13 +246,18 @@ extern "C" harli_status harli_ft_window_resize(harli_ctx* c, int32_t n_slots) {
   harli_status r = drain(w);
   if (r != HARLI_OK) return r;
   if (want < w->plan.n) {
-    // keep the items needed soonest: drop empty slots first, then those whose item comes latest after the last use
+    // drop empty slots first, then items the smaller window does not want (see wanted_items), then wanted ones; within
+    // a class the item that comes latest after the last use goes first
     const int base = w->last_item < 0 ? w->plan.items() - 1 : w->last_item;
+    const int N = w->plan.items();
+    std::vector<char> wanted(N, 0);
+    for (int it : w->plan.wanted_items((base + 1) % N, want)) wanted[it] = 1;
     auto rank = [&](int s) {
       const int it = w->plan.slot_item[s];
-      if (it < 0) return w->plan.items() + 1;
+      if (it < 0) return 3 * N;
       const int d = w->plan.ahead(base, it);
-      return d == 0 ? w->plan.items() : d;  // the item just used is needed a whole cycle from now
+      const int far = d == 0 ? N : d;  // the item just used is needed a whole cycle from now
+      return wanted[it] ? far : N + far;
     };
     while (w->plan.n > want) {
       int far = -1, fs = -1;
@@ -303,7 +315,10 @@ extern "C" harli_status harli_dbg_window_plan(int32_t n_layers, int32_t n_slots,
     return fail(HARLI_ERR_INVALID, "dbg_window_plan: bad argument");
   WindowPlan p;
   p.init(n_layers, n_slots < 2 * n_layers ? n_slots : 2 * n_layers);
-  for (int s = 0; s < p.n; ++s) p.slot_item[s] = s;
+  {
+    const std::vector<int> start = p.wanted_items(0, p.n);  // what enable() puts on the device
+    for (int s = 0; s < p.n; ++s) p.slot_item[s] = start[s];
+  }
   for (int a = 0; a < n_access; ++a) {
     const int it = items[a];
     if (it < 0 || it >= p.items()) return fail(HARLI_ERR_INVALID, "dbg_window_plan: item %d out of range", it);

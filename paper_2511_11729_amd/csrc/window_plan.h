@@ -45,6 +45,28 @@ struct WindowPlan {
     }
     return best;
   }
+  // The items a window of `slots` slots should hold when `first` is the next item used, in order of use: the next
+  // kLookahead items, and of the others all but 2L - slots that are spread evenly over the cycle.  The refill rule
+  // moves every absent item kLookahead places back per visit, so an even spread stays even; copies then come one at a
+  // time with compute in between instead of in one burst that the host link cannot hide.
+  std::vector<int> wanted_items(int first, int slots) const {
+    const int N = items();
+    std::vector<int> out;
+    if (slots >= N) {
+      for (int d = 0; d < N; ++d) out.push_back((first + d) % N);
+      return out;
+    }
+    if (slots <= kLookahead) {
+      for (int d = 0; d < slots; ++d) out.push_back((first + d) % N);
+      return out;
+    }
+    const int m = N - slots;  // absent items: offsets kLookahead + ((2j + 1)(N - kLookahead)) / (2m), distinct since m <= N - kLookahead
+    std::vector<char> absent(N, 0);
+    for (int j = 0; j < m; ++j) absent[kLookahead + ((2 * j + 1) * (N - kLookahead)) / (2 * m)] = 1;
+    for (int d = 0; d < N; ++d)
+      if (!absent[d]) out.push_back((first + d) % N);
+    return out;
+  }
   int refill_after(int item) const {
     const int k = n < kLookahead ? n : kLookahead;
     for (int d = 1; d <= k; ++d) {

@@ -62,7 +62,7 @@ def test_training_step_is_bit_identical_under_every_window():
         assert case.pool.stats().tensor_blocks_live > free0                 # the slots come from the unified pool
         torch.cuda.synchronize()
         assert case.ctx.ft_window_ready(0, False)
-        assert case.ctx.ft_window_ready(L - 1, True) == (n_eff >= L + 1)    # item L is resident only in a window > L
+        assert case.ctx.ft_window_ready(L - 1, True) == (WM.item_of(L - 1, True, L) in WM.wanted_items(L, n_eff))   # as the model places them
         for rep in range(2):
             assert same(run_step(case), base), "window of %d slots, step %d" % (n, rep)
         st = case.ctx.ft_window_stats()

@@ -71,6 +71,14 @@ def test_large_windows_keep_what_is_not_needed_soon(L, n):
             assert len(set(w.slots)) == n
             loads += refill >= 0
         loads_by_cycle.append(loads)
+    if 2 * (N - n) <= N - K:                                     # the copies of a step are spread out, never back to back
+        w2, last, gaps = WM.Window(L, n), None, []
+        for t in range(6 * N):
+            if w2.access(t % N)[2] >= 0:
+                if last is not None:
+                    gaps.append(t - last)
+                last = t
+        assert min(gaps) >= (N - K) // (N - n) - 1 >= 1
     steady = loads_by_cycle[N - K:]                              # the pattern repeats every 2L - K steps
     assert sum(steady[: N - K]) == N * (N - n)
     assert sum(steady) * (N - K) == len(steady) * N * (N - n)
