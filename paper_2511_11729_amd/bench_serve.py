@@ -163,10 +163,10 @@ def make_plan(args, m, ft, pool, ctx, ft_step, server, log):
     pages_per = (PN + 1 + serve.P - 1) // serve.P
     # the largest profiled batch whose KV cache fits beside a training step's activations (a tight pool profiles less)
     st = pool.stats()
-    L, T = m.n_layers, ft.tokens
-    per_layer = T * m.hidden * 12 + T * m.n_q * m.head_dim * 4 + T * m.n_kv * m.head_dim * 4 + T * m.ffn * 6
+    L = m.n_layers
     chunk = 2 * L * pool.cfg.block_bytes
-    room = st.free_chunks - ((L + 1) * (per_layer // chunk + 2) + 8)
+    saved = ctx.saved_bytes(ft.micro_batch, ft.seq_len)                   # what one layer's forward keeps for its backward
+    room = st.free_chunks - (L * (-(-saved // chunk) + 1) + 8)
     PB = next((b for b in (160, 128, 96, 64, 32, 16) if b <= args.max_batch and -(-b * pages_per // st.pages_per_block) <= room), None)
     if PB is None:
         raise SystemExit("bench_serve: the pool is too small to profile the predictor beside a training step")
@@ -332,9 +332,8 @@ def main():
         slot_chunks = -(-ws0.slot_bytes // chunk)
         log("[window] %d of %d slots of %.0f MB on the device" % (ws0.slots, L2, ws0.slot_bytes / 1e6))
         state = {"oom": False, "calm": 0}
-        T_, H_ = ft.tokens, m.hidden
-        per_layer = T_ * H_ * 12 + T_ * m.n_q * m.head_dim * 4 + T_ * m.n_kv * m.head_dim * 4 + T_ * m.ffn * 6
-        need = (m.n_layers + 1) * (per_layer // chunk + 2) + reserve + 8     # a step's saved activations, the KV reserve, slack
+        saved = ctx.saved_bytes(ft.micro_batch, ft.seq_len)               # what one layer's forward keeps for its backward
+        need = m.n_layers * (-(-saved // chunk) + 1) + reserve + 8          # a step's saved activations, the KV reserve, slack
         top = min(args.window, L2)
 
         def step_fn(wk):
@@ -364,6 +363,10 @@ def main():
     factory = None if args.no_finetune else (lambda: serve.FinetuneWorker(pool, step_fn, sF, ft.tokens))
     plan, sched_report, cs = None, None, None
     if scheduled:
+        if args.window is not None:                 # the profile needs a training step's activations and a KV cache of its own
+            while pool.stats().free_chunks < need + 110 and ctx.ft_window_stats().slots > 4:
+                ctx.ft_window_resize(ctx.ft_window_stats().slots - 4)
+            log("[window] %d slots while the predictor is profiled" % ctx.ft_window_stats().slots)
         plan, sched_report, cs = make_plan(args, m, ft, pool, ctx, ft_step, server, log)
     import gc
     gc.collect()
