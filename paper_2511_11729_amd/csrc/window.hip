@@ -13,10 +13,15 @@ namespace {
 struct FtWindow {
   WindowPlan plan;
   size_t item_bytes = 0;
-  size_t off[kTargets] = {};
+  size_t off[kTargets] = {}, nb[kTargets] = {};  // offset of a matrix inside an item on the host, and its bytes
   char* host = nullptr;  // pinned, [2L][item_bytes] in item order
-  std::vector<harli_alloc> alloc;
-  std::vector<char*> ptr;
+  // One pool allocation per matrix, not per slot: every matrix is smaller than a chunk, so the pool packs them into
+  // tensor chunks block by block (a slot of 3.25 chunks taken as one tensor occupied four).
+  struct Slot {
+    harli_alloc alloc[kTargets];
+    char* ptr[kTargets];
+  };
+  std::vector<Slot> slot;
   std::vector<hipEvent_t> ready, used;
   std::vector<char> used_valid;
   hipStream_t copy = nullptr;
@@ -28,7 +33,8 @@ FtWindow* win(harli_ctx* c) { return static_cast<FtWindow*>(c->window); }
 
 harli_status load(FtWindow* w, int item, int s) {
   if (w->used_valid[s]) HARLI_HIP(hipStreamWaitEvent(w->copy, w->used[s], 0));
-  HARLI_HIP(hipMemcpyAsync(w->ptr[s], w->host + (size_t)item * w->item_bytes, w->item_bytes, hipMemcpyHostToDevice, w->copy));
+  for (int t = 0; t < kTargets; ++t)
+    HARLI_HIP(hipMemcpyAsync(w->slot[s].ptr[t], w->host + (size_t)item * w->item_bytes + w->off[t], w->nb[t], hipMemcpyHostToDevice, w->copy));
   HARLI_HIP(hipEventRecord(w->ready[s], w->copy));
   w->plan.slot_item[s] = item;
   w->h2d_bytes += (long long)w->item_bytes;
@@ -36,36 +42,40 @@ harli_status load(FtWindow* w, int item, int s) {
 }
 
 harli_status add_slot(harli_ctx* c, FtWindow* w) {
-  harli_alloc a{};
-  harli_status s = harli_pool_alloc(c->pool, HARLI_CLS_TENSOR, w->item_bytes, &a);
-  if (s != HARLI_OK) return s;
+  FtWindow::Slot sl{};
+  for (int t = 0; t < kTargets; ++t) {
+    harli_status s = harli_pool_alloc(c->pool, HARLI_CLS_TENSOR, w->nb[t], &sl.alloc[t]);
+    if (s != HARLI_OK) {
+      for (int u = 0; u < t; ++u) (void)harli_pool_free(c->pool, &sl.alloc[u], nullptr);
+      return s;
+    }
+    sl.ptr[t] = static_cast<char*>(sl.alloc[t].ptr);
+  }
   hipEvent_t r = nullptr, u = nullptr;
   if (hipEventCreateWithFlags(&r, hipEventDisableTiming) != hipSuccess || hipEventCreateWithFlags(&u, hipEventDisableTiming) != hipSuccess) {
     if (r) (void)hipEventDestroy(r);
-    (void)harli_pool_free(c->pool, &a, nullptr);
+    for (int t = 0; t < kTargets; ++t) (void)harli_pool_free(c->pool, &sl.alloc[t], nullptr);
     return fail(HARLI_ERR_HIP, "ft_window: cannot create an event");
   }
-  w->alloc.push_back(a);
-  w->ptr.push_back(static_cast<char*>(a.ptr));
+  w->slot.push_back(sl);
   w->ready.push_back(r);
   w->used.push_back(u);
   w->used_valid.push_back(0);
   w->plan.slot_item.push_back(-1);
-  w->plan.n = (int)w->ptr.size();
+  w->plan.n = (int)w->slot.size();
   return HARLI_OK;
 }
 
 void drop_slot(harli_ctx* c, FtWindow* w) {  // the last one; the caller has synchronised
-  (void)harli_pool_free(c->pool, &w->alloc.back(), nullptr);
+  for (int t = 0; t < kTargets; ++t) (void)harli_pool_free(c->pool, &w->slot.back().alloc[t], nullptr);
   (void)hipEventDestroy(w->ready.back());
   (void)hipEventDestroy(w->used.back());
-  w->alloc.pop_back();
-  w->ptr.pop_back();
+  w->slot.pop_back();
   w->ready.pop_back();
   w->used.pop_back();
   w->used_valid.pop_back();
   w->plan.slot_item.pop_back();
-  w->plan.n = (int)w->ptr.size();
+  w->plan.n = (int)w->slot.size();
 }
 
 harli_status drain(FtWindow* w) {
@@ -118,7 +128,7 @@ harli_status window_acquire(harli_ctx* c, int layer, bool backward, hipStream_t 
   }
   HARLI_HIP(hipStreamWaitEvent(st, w->ready[s], 0));
   LayerDev& L = c->layers[layer];
-  for (int t = 0; t < kTargets; ++t) (backward ? L.wt[t] : L.w16[t]) = w->ptr[s] + w->off[t];
+  for (int t = 0; t < kTargets; ++t) (backward ? L.wt[t] : L.w16[t]) = w->slot[s].ptr[t];
   return HARLI_OK;
 }
 
@@ -153,7 +163,7 @@ void free_window_state(harli_ctx* c) {
   // only wait when the runtime still answers (a context destroyed while the process is going down must not block)
   const hipError_t q = w->copy ? hipStreamQuery(w->copy) : hipSuccess;
   if (q == hipSuccess || q == hipErrorNotReady) (void)drain(w);
-  while (!w->ptr.empty()) drop_slot(c, w);
+  while (!w->slot.empty()) drop_slot(c, w);
   if (w->host) (void)hipHostFree(w->host);
   if (w->copy) (void)hipStreamDestroy(w->copy);
   delete w;
@@ -174,7 +184,8 @@ extern "C" harli_status harli_ft_window_enable(harli_ctx* c, int32_t n_slots) {
     int out, in;
     proj_shape(c->cfg, t, &out, &in);
     w->off[t] = o;
-    o += ((size_t)out * in * 2 + 255) / 256 * 256;
+    w->nb[t] = (size_t)out * in * 2;
+    o += (w->nb[t] + 255) / 256 * 256;
   }
   w->item_bytes = o;
   c->window = w;
@@ -265,8 +276,7 @@ extern "C" harli_status harli_ft_window_resize(harli_ctx* c, int32_t n_slots) {
         if (rank(s) > far) far = rank(s), fs = s;
       // swap slot fs with the last slot, then drop the last
       const int last = w->plan.n - 1;
-      std::swap(w->alloc[fs], w->alloc[last]);
-      std::swap(w->ptr[fs], w->ptr[last]);
+      std::swap(w->slot[fs], w->slot[last]);
       std::swap(w->ready[fs], w->ready[last]);
       std::swap(w->used[fs], w->used[last]);
       std::swap(w->used_valid[fs], w->used_valid[last]);
