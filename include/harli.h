@@ -257,7 +257,7 @@ harli_status harli_saved_bytes(const harli_ctx* c, int32_t B_f, int32_t S, size_
  * After harli_lora_attach the library holds finetune-private copies of every layer's frozen weights (W for the forward
  * pass, W^T for the backward pass).  harli_ft_window_enable moves them to pinned host memory and keeps only n_slots of
  * them on the device, in TENSOR allocations of the unified pool (one slot = one layer's seven matrices in one
- * orientation; n_slots is capped at 2 * n_layers, which is everything).  A training step uses the copies in a fixed
+ * orientation, one allocation per matrix; n_slots is capped at 2 * n_layers, which is everything).  A training step uses the copies in a fixed
  * cyclic order -- W of layers 0..L-1, then W^T of layers L-1..0 -- and harli_lora_fwd / harli_lora_bwd make their
  * stream wait for the copy they need, then, once the layer is enqueued, refill its slot over a library-owned copy
  * stream with the nearest copy among the next min(n_slots, 4) in that order that is not on the device; when those are
