@@ -287,6 +287,21 @@ harli_status harli_ft_window_resize(harli_ctx* c, int32_t n_slots);
 harli_status harli_ft_window_disable(harli_ctx* c);
 harli_status harli_ft_window_ready(harli_ctx* c, int32_t layer, int32_t backward, int32_t* ready);
 harli_status harli_ft_window_stats(harli_ctx* c, harli_window_stats* out);
+/* Window size for the next training step (Sec. 4.4: the finetune task hands memory to inference under pressure and takes
+ * it back when chunks are free; the paper gives the behaviour, the step sizes are this library's).  Pure host
+ * arithmetic, no context: call it between training steps and pass *target to harli_ft_window_resize when it differs
+ * from `slots`.
+ *   slots, max_slots: the window now (>= 1) and the most it may hold (>= slots).  slot_chunks: pool chunks one slot
+ *   takes (slot_bytes / chunk bytes, rounded up).  free_chunks: harli_pool_stats.free_chunks now.  need_chunks: chunks
+ *   the next step's saved activations and the KV reserve need free.  pressed: nonzero when inference was short of memory
+ *   since the last step (harli_pool_pressure > 0) or the last training step ran out of pool memory.
+ *   *calm (host, in/out, start at 0): roomy steps in a row, kept by the caller between calls.
+ * Rule: slots move in groups of four.  pressed or free < need: shrink at once by ceil(max(need - free, slot_chunks) /
+ * (4 slot_chunks)) groups, never under min(slots, 4), *calm = 0.  Otherwise, free > need + 8 slot_chunks and slots <
+ * max_slots: ++*calm, and from the second such step in a row grow by one group (at most to max_slots).  Otherwise keep,
+ * *calm = 0.  HARLI_ERR_INVALID for arguments outside these ranges. */
+harli_status harli_ft_window_advise(int32_t slots, int32_t max_slots, int64_t slot_chunks, int64_t free_chunks,
+                                    int64_t need_chunks, int32_t pressed, int32_t* calm, int32_t* target);
 
 /* ======================================================================== *
  * Output layer of the finetune task with next-token cross entropy (Sec. 2.1: "output layer" after the stack of

@@ -79,3 +79,29 @@ class Window:
         if refill >= 0:
             self.slots[s] = refill
         return s, miss, refill
+
+
+# ---- window size between training steps (Sec. 4.4) ----
+# The paper: when inference runs short of memory the finetune task shrinks its window and hands the chunks over; when
+# memory is free again the window grows back.  It gives no step sizes.  Reading taken here (the library states the same
+# rule in its header): slots move in groups of LOOKAHEAD; under pressure, or when fewer chunks are free than the next
+# step needs, the window shrinks at once by as many groups as cover the shortage (at least one slot's worth), but never
+# under one group and never upwards; with more than GROW_SLACK slots' worth of chunks free beyond the need, the second
+# such step in a row and every one after it adds one group, up to the largest window allowed.
+CALM_STEPS = 2
+GROW_SLACK = 8
+
+
+def advise_slots(slots: int, max_slots: int, slot_chunks: int, free_chunks: int, need_chunks: int, pressed: bool, calm: int):
+    """Returns (target slots, updated count of roomy steps in a row)."""
+    group = LOOKAHEAD * slot_chunks
+    if pressed or free_chunks < need_chunks:
+        shortage = max(need_chunks - free_chunks, slot_chunks)
+        groups = -(-shortage // group)
+        return max(min(slots, LOOKAHEAD), slots - LOOKAHEAD * groups), 0
+    if free_chunks > need_chunks + GROW_SLACK * slot_chunks and slots < max_slots:
+        calm += 1
+        if calm >= CALM_STEPS:
+            return min(max_slots, slots + LOOKAHEAD), calm
+        return slots, calm
+    return slots, 0

@@ -338,16 +338,8 @@ def main():
 
         def step_fn(wk):
             ws, st = ctx.ft_window_stats(), pool.stats()
-            target = ws.slots
-            if pool.pressure() > 0 or state["oom"] or st.free_chunks < need:
-                short = max(need - st.free_chunks, slot_chunks)
-                target, state["calm"] = max(4, ws.slots - 4 * (-(-short // (4 * slot_chunks)))), 0
-            elif st.free_chunks > need + 8 * slot_chunks and ws.slots < top:
-                state["calm"] += 1
-                if state["calm"] >= 2:                  # room two steps in a row: take four slots back
-                    target = min(top, ws.slots + 4)
-            else:
-                state["calm"] = 0
+            target, state["calm"] = hb.ft_window_advise(ws.slots, max(top, ws.slots), slot_chunks, st.free_chunks, need,
+                                                        pool.pressure() > 0 or state["oom"], state["calm"])
             if target != ws.slots:
                 try:
                     ctx.ft_window_resize(target)

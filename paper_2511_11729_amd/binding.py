@@ -132,6 +132,8 @@ _SIGS = {
     "harli_ft_window_disable": (C.c_int, [C.c_void_p]),
     "harli_ft_window_ready": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_int32)]),
     "harli_ft_window_stats": (C.c_int, [C.c_void_p, C.c_void_p]),
+    "harli_ft_window_advise": (C.c_int, [C.c_int32, C.c_int32, C.c_int64, C.c_int64, C.c_int64, C.c_int32,
+                                          C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
     "harli_dbg_window_plan": (C.c_int, [C.c_int32, C.c_int32, C.POINTER(C.c_int32), C.c_int32, C.POINTER(C.c_int32),
                                         C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
     "harli_dbg_gemm_clock": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_int32,
@@ -493,6 +495,15 @@ def dbg_gemm(A1, B1, *, A2=None, B2=None, alpha=1.0, causal=0, half=False, Cb=No
 class WindowStats(C.Structure):
     _fields_ = [("slots", C.c_int32), ("slot_bytes", C.c_size_t), ("host_bytes", C.c_size_t), ("h2d_bytes", C.c_int64),
                 ("hits", C.c_int64), ("misses", C.c_int64), ("refills", C.c_int64)]
+
+
+def ft_window_advise(slots: int, max_slots: int, slot_chunks: int, free_chunks: int, need_chunks: int, pressed: bool,
+                     calm: int):
+    """(target slots, updated calm count) of harli_ft_window_advise."""
+    c, t = C.c_int32(calm), C.c_int32(0)
+    _check(lib().harli_ft_window_advise(slots, max_slots, slot_chunks, free_chunks, need_chunks, int(bool(pressed)),
+                                        C.byref(c), C.byref(t)))
+    return t.value, c.value
 
 
 def dbg_window_plan(n_layers: int, n_slots: int, items):

@@ -345,3 +345,13 @@ extern "C" harli_status harli_dbg_window_plan(int32_t n_layers, int32_t n_slots,
   }
   return HARLI_OK;
 }
+
+extern "C" harli_status harli_ft_window_advise(int32_t slots, int32_t max_slots, int64_t slot_chunks, int64_t free_chunks,
+                                               int64_t need_chunks, int32_t pressed, int32_t* calm, int32_t* target) {
+  if (slots < 1 || max_slots < slots || slot_chunks < 1 || free_chunks < 0 || need_chunks < 0 || !calm || *calm < 0 || !target)
+    return fail(HARLI_ERR_INVALID, "ft_window_advise: bad argument");
+  const WindowAdvice a = advise_slots(slots, max_slots, slot_chunks, free_chunks, need_chunks, pressed != 0, *calm);
+  *target = a.target;
+  *calm = a.calm;
+  return HARLI_OK;
+}

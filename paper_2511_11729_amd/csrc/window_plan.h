@@ -78,4 +78,43 @@ struct WindowPlan {
   }
 };
 
+// ---- Window size between training steps (Sec. 4.4: the finetune task gives memory back when inference needs it
+// and takes it again when chunks are free).  The paper states the behaviour, not step sizes; these are this
+// library's: slots move in groups of kLookahead (what one refill round covers), the window shrinks at once by as
+// many groups as cover the shortage, and grows by one group per step after kCalmSteps steps in a row with more than
+// kGrowSlack slots' worth of chunks free beyond the step's own need.
+constexpr int kCalmSteps = 2;
+constexpr int kGrowSlack = 8;
+
+struct WindowAdvice {
+  int target;  // slots to ask harli_ft_window_resize for (== slots: leave the window alone)
+  int calm;    // updated count of roomy steps in a row
+};
+
+// slots / max_slots: the window now and the most it may hold.  slot_chunks: pool chunks one slot takes.
+// free_chunks: chunks free in the pool now.  need_chunks: chunks the next training step and the KV reserve need free.
+// pressed: inference asked for memory since the last step (back-pressure, or the last step ran out of memory).
+inline WindowAdvice advise_slots(int slots, int max_slots, long long slot_chunks, long long free_chunks, long long need_chunks,
+                                 bool pressed, int calm) {
+  const long long group = (long long)kLookahead * slot_chunks;
+  if (pressed || free_chunks < need_chunks) {
+    long long shortage = need_chunks - free_chunks;
+    if (shortage < slot_chunks) shortage = slot_chunks;
+    const long long groups = (shortage + group - 1) / group;
+    const int floor_slots = slots < kLookahead ? slots : kLookahead;  // a window never grows here, nor falls under one group
+    long long t = (long long)slots - kLookahead * groups;
+    if (t < floor_slots) t = floor_slots;
+    return {(int)t, 0};
+  }
+  if (free_chunks > need_chunks + (long long)kGrowSlack * slot_chunks && slots < max_slots) {
+    calm += 1;
+    if (calm >= kCalmSteps) {
+      const int t = slots + kLookahead < max_slots ? slots + kLookahead : max_slots;
+      return {t, calm};
+    }
+    return {slots, calm};
+  }
+  return {slots, 0};
+}
+
 }  // namespace harli

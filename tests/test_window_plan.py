@@ -129,3 +129,71 @@ def test_plan_rejects_bad_arguments():
     for L, n, seq in [(0, 1, [0]), (2, 0, [0]), (2, 1, [4]), (2, 1, [-1])]:
         with pytest.raises(hb.HarliError):
             hb.dbg_window_plan(L, n, seq)
+
+
+# ---- window size between training steps (Sec. 4.4; step sizes are the library's own, stated in its header) ----
+# hand-worked: one slot = 3 chunks, so a group of four slots = 12 chunks
+ADVISE_PINS = [
+    # slots, max, slot_chunks, free, need, pressed, calm -> target, calm
+    ((64, 64, 3, 100, 130, False, 1), (52, 0)),    # 30 chunks short: three groups go
+    ((64, 64, 3, 129, 130, False, 0), (60, 0)),    # one chunk short still costs a whole group
+    ((64, 64, 3, 500, 130, True, 5), (60, 0)),     # pressed with room: one group, and the calm count starts over
+    ((8, 64, 3, 0, 1000, True, 0), (4, 0)),        # never under one group
+    ((2, 64, 3, 0, 1000, True, 0), (2, 0)),        # a window under one group is left alone (never grows under pressure)
+    ((40, 64, 3, 200, 130, False, 0), (40, 1)),    # first roomy step: wait
+    ((40, 64, 3, 200, 130, False, 1), (44, 2)),    # second in a row: one group more
+    ((44, 64, 3, 200, 130, False, 2), (48, 3)),    # and one per step after that
+    ((62, 64, 3, 200, 130, False, 1), (64, 2)),    # clipped to the largest window
+    ((64, 64, 3, 900, 130, False, 7), (64, 0)),    # full: nothing to grow
+    ((40, 64, 3, 154, 130, False, 1), (40, 0)),    # exactly need + 8 slots free is not roomy
+    ((40, 64, 3, 155, 130, False, 1), (44, 2)),
+    ((40, 64, 3, 130, 130, False, 1), (40, 0)),    # just enough: keep
+]
+
+
+@pytest.mark.parametrize("args,want", ADVISE_PINS)
+def test_window_size_rule_hand_worked(args, want):
+    assert WM.advise_slots(*args) == want
+    assert hb.ft_window_advise(*args) == want
+
+
+def test_window_size_rule_library_equals_model_on_a_replayed_pool():
+    """A pool of `total` chunks shared by the window, a training step's activations and a KV cache that swells and
+    shrinks: both statements of the rule take the same decisions, the window stays inside its bounds, a shrink frees
+    enough for the step unless the window is already at one group, and a calm stretch restores the full window."""
+    rng = np.random.default_rng(11)
+    for trial in range(20):
+        slot_chunks = int(rng.integers(1, 6))
+        top = int(rng.choice([8, 24, 64]))
+        need = int(rng.integers(20, 120))
+        total = top * slot_chunks + need + int(rng.integers(0, 60))
+        slots, calm_l, calm_m = top, 0, 0
+        kv = 0
+        for step in range(300):
+            phase = (step // 60) % 3                       # light, heavy, light again
+            kv = max(0, min(total, kv + int(rng.integers(-6, 8)) + (10 if phase == 1 else -10)))
+            free = max(0, total - slots * slot_chunks - kv)
+            pressed = bool(free == 0 or rng.random() < (0.3 if phase == 1 else 0.0))
+            t_m, calm_m = WM.advise_slots(slots, top, slot_chunks, free, need, pressed, calm_m)
+            t_l, calm_l = hb.ft_window_advise(slots, top, slot_chunks, free, need, pressed, calm_l)
+            assert (t_l, calm_l) == (t_m, calm_m)
+            assert min(slots, 4) <= t_m <= top
+            assert (t_m - slots) % 4 == 0 or t_m in (top, min(slots, 4))        # whole groups, unless clipped
+            if t_m < slots and t_m > 4:
+                assert free + (slots - t_m) * slot_chunks >= need      # the groups given up cover the shortage
+            if t_m > slots:
+                assert not pressed and free > need + 8 * slot_chunks
+            slots = t_m
+        kv = 0
+        for step in range(2 + top // 4):                   # empty cache: back to the full window, a group per step
+            free = total - slots * slot_chunks
+            slots, calm_m = WM.advise_slots(slots, top, slot_chunks, free, need, False, calm_m)
+        assert slots == top or total - slots * slot_chunks <= need + 8 * slot_chunks
+
+
+def test_window_size_rule_rejects_bad_arguments():
+    for bad in [(0, 4, 1, 0, 0, False, 0), (8, 4, 1, 0, 0, False, 0), (4, 8, 0, 0, 0, False, 0), (4, 8, 1, -1, 0, False, 0),
+                (4, 8, 1, 0, -1, False, 0), (4, 8, 1, 0, 0, False, -1)]:
+        with pytest.raises(hb.HarliError) as e:
+            hb.ft_window_advise(*bad)
+        assert e.value.status == hb.HARLI_ERR_INVALID
