@@ -46,6 +46,16 @@ harli_status harli_pred_fit(harli_predictor* p);
  * (harli_pred_solo_coef) are not changed.  HARLI_ERR_INVALID for a level outside 1..n_levels or a scale that is not a
  * positive finite number. */
 harli_status harli_pred_set_scale(harli_predictor* p, int32_t level, double scale);
+harli_status harli_pred_get_scale(const harli_predictor* p, int32_t level, double* scale /* host out */);
+/* Run-time feedback into that factor: one finished decode step at `level` took measured_ms where Eq. 1 (and Eq. 2 when a
+ * finetune task ran beside it) WITHOUT the calibration factor gave predicted_ms -- a caller that planned with a calibrated
+ * prediction divides it by the factor harli_pred_get_scale returned at planning time.  With r = measured / predicted
+ * clipped to [0.6, 2.5]: the first observation of a level sets its factor to r, later ones move it by weight * (r -
+ * factor) (0 < weight <= 1); every level that has not been observed yet takes the observed level's new factor, so a plan
+ * that moves to a fresh partition starts from the latest evidence.  harli_pred_set_scale puts a level back to "not
+ * observed".  HARLI_ERR_INVALID for a level outside 1..n_levels, times that are not positive finite numbers, or a weight
+ * outside (0, 1]. */
+harli_status harli_pred_observe(harli_predictor* p, int32_t level, double predicted_ms, double measured_ms, double weight);
 
 /* Coefficients after a fit (host out-pointers): solo[3] = b0, c0, k0 of `level`; colo[2] = b1, k1.
  * HARLI_ERR_STATE when that model has not been fitted. */

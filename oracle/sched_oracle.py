@@ -49,6 +49,34 @@ def calibrated(coef, scale):
     return tuple(scale * c for c in coef)
 
 
+SCALE_MIN, SCALE_MAX = 0.6, 2.5
+
+
+class Calibration:
+    """Run-time feedback into the per-level calibration factors (an addition to the paper's scheduler, which plans with
+    the fitted predictor alone, Sec. 6.2).  One finished decode step at a level gives r = measured / predicted (the
+    prediction without the factor), clipped to [SCALE_MIN, SCALE_MAX]: the first step seen at a level sets its factor
+    to r, later ones move it by weight * (r - factor); levels with no step seen yet take the new factor of the level
+    just measured.  Setting a factor by hand makes the level unseen again."""
+
+    def __init__(self, n_levels: int):
+        self.scale = [1.0] * n_levels          # index level - 1
+        self.seen = [False] * n_levels
+
+    def set(self, level: int, scale: float):
+        self.scale[level - 1] = float(scale)
+        self.seen[level - 1] = False
+
+    def observe(self, level: int, predicted_ms: float, measured_ms: float, weight: float):
+        r = min(SCALE_MAX, max(SCALE_MIN, measured_ms / predicted_ms))
+        i = level - 1
+        self.scale[i] = self.scale[i] + weight * (r - self.scale[i]) if self.seen[i] else r
+        self.seen[i] = True
+        for j in range(len(self.scale)):
+            if not self.seen[j]:
+                self.scale[j] = self.scale[i]
+
+
 COLO_FIT_ROUNDS = 32
 
 

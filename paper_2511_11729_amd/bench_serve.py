@@ -218,28 +218,20 @@ def make_plan(args, m, ft, pool, ctx, ft_step, server, log):
             raise SystemExit("bench_serve: no ordinary stream off the inference streams' dispatch pipes was found")
     sched = hb.Scheduler(pred, args.slo_ms * args.sched_margin, 64)
 
-    scale = [1.0] * (colocate.N_LEVELS + 1)         # per level: measured / predicted decode step, smoothed
-    seen = set()
+    scale = [1.0] * (colocate.N_LEVELS + 1)         # per level (index 0 unused): the predictor's factors, for the report
 
     def calibrate(srv):
         """Sec. 6.2 plans with the predictor alone; here the steps that have finished are timed and the ratio
-        measured / predicted is folded back into the predictor per level (--no-feedback: off).  It absorbs what Eq. 1
-        cannot hold: latency that is a staircase in the batch size, batches of mixed lengths."""
-        changed = set()
+        measured / predicted is folded back into the predictor per level (harli_pred_observe; --no-feedback: off).  It
+        absorbs what Eq. 1 cannot hold: latency that is a staircase in the batch size, batches of mixed lengths."""
+        n = 0
         for tag, ms in srv.completed_steps():
             if tag is None or tag[1] <= 0.0:
                 continue
-            i, raw = tag
-            r = min(2.5, max(0.6, ms / raw))
-            scale[i] += 0.15 * (r - scale[i]) if i in seen else r - scale[i]
-            seen.add(i)
-            changed.add(i)
-            for j in range(1, colocate.N_LEVELS + 1):   # a level not seen yet borrows from the last one measured
-                if j not in seen:
-                    scale[j] = scale[i]
-                    changed.add(j)
-        for j in changed:
-            pred.set_scale(j, scale[j])
+            pred.observe(tag[0], tag[1], ms, 0.15)
+            n += 1
+        if n:
+            scale[1:] = [pred.get_scale(j) for j in range(1, colocate.N_LEVELS + 1)]
 
     def plan(srv, worker):
         if not args.no_feedback:
@@ -256,7 +248,7 @@ def make_plan(args, m, ft, pool, ctx, ft_step, server, log):
         else:
             i, f, pred_ms, act = sched.step(B, n, ready)
         srv.use_stream(low[i])
-        srv.tag = (i, pred_ms / scale[i])           # the prediction before calibration
+        srv.tag = (i, pred_ms / pred.get_scale(i))  # the prediction before calibration
         if worker is not None:
             worker.target = (ft_all if ft_all is not None else high[f]) if f > 0 else None
         return (i, f, act, pred_ms, n)

@@ -114,6 +114,8 @@ _SIGS = {
     "harli_pred_add_solo": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_double]),
     "harli_pred_add_colo": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_double, C.c_double]),
     "harli_pred_set_scale": (C.c_int, [C.c_void_p, C.c_int32, C.c_double]),
+    "harli_pred_get_scale": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_double)]),
+    "harli_pred_observe": (C.c_int, [C.c_void_p, C.c_int32, C.c_double, C.c_double, C.c_double]),
     "harli_pred_fit": (C.c_int, [C.c_void_p]),
     "harli_pred_solo_coef": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_double)]),
     "harli_pred_colo_coef": (C.c_int, [C.c_void_p, C.POINTER(C.c_double)]),
@@ -407,6 +409,16 @@ class Predictor:
     def set_scale(self, level: int, scale: float) -> None:
         """Calibration factor on every prediction at `level` (1 by default)."""
         _check(lib().harli_pred_set_scale(self.handle, level, C.c_double(scale)))
+
+    def get_scale(self, level: int) -> float:
+        v = C.c_double(0.0)
+        _check(lib().harli_pred_get_scale(self.handle, level, C.byref(v)))
+        return v.value
+
+    def observe(self, level: int, predicted_ms: float, measured_ms: float, weight: float) -> None:
+        """Folds one measured decode step into the calibration factor of `level` (predicted_ms: without the factor)."""
+        _check(lib().harli_pred_observe(self.handle, level, C.c_double(predicted_ms), C.c_double(measured_ms),
+                                        C.c_double(weight)))
 
     def solo_coef(self, level: int):
         c = (C.c_double * 3)()

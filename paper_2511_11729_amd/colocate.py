@@ -396,13 +396,12 @@ def run_trace(hz, pred, slo_ms, segments, seqlen, refresh_phases=32, starve=(), 
     finetune task reports no ready work.  The host waits for each decode step before deciding the next phase.
     Returns per-phase records and a per-segment summary (latency percentiles, share of phases within the target,
     finetune units completed).  feedback: every measured step corrects the predictor at its level by the smoothed ratio
-    measured / predicted (`harli_pred_set_scale`, an addition to the paper's scheduler: Eq. 1 is a straight line in the
+    measured / predicted (`harli_pred_observe`, an addition to the paper's scheduler: Eq. 1 is a straight line in the
     batch size and misses a step on a tenth of the chip by 10 %, enough to pick a plan just above the target); the
     factors are set back to 1 before returning."""
     cs = CuStreams()
     low, high = cs.pairs()
     sched = hb.Scheduler(pred, slo_ms, refresh_phases)
-    scale = [1.0] * (N_LEVELS + 1)
     dev = hz.x_dev.device
     starve = set(starve)
     rec = []
@@ -434,9 +433,7 @@ def run_trace(hz, pred, slo_ms, segments, seqlen, refresh_phases=32, starve=(), 
                 rec.append({"phase": g, "batch": bs, "infer_level": i, "ft_level": f, "action": act, "predicted_ms": pred_ms,
                             "latency_ms": ms})
                 if feedback and pred_ms > 0.0:
-                    r = min(2.5, max(0.6, ms / (pred_ms / scale[i])))
-                    scale[i] += 0.5 * (r - scale[i])
-                    pred.set_scale(i, scale[i])
+                    pred.observe(i, pred_ms / pred.get_scale(i), ms, 0.5)   # the factor has not moved since the plan was made
                 g += 1
             dt = time.perf_counter() - t0
             lat = np.array([r["latency_ms"] for r in rec[first:]])
@@ -449,9 +446,10 @@ def run_trace(hz, pred, slo_ms, segments, seqlen, refresh_phases=32, starve=(), 
             log("[trace] batch %d: %s" % (bs, summary[-1]))
         feeder.target = None
     sched.close()
+    scale = [pred.get_scale(lv) for lv in range(1, N_LEVELS + 1)]
     for lv in range(1, N_LEVELS + 1):
         pred.set_scale(lv, 1.0)
     _quiesce(hz)
     cs.close()
     hz.ctx.check(torch.cuda.current_stream())
-    return {"phases": rec, "segments": summary, "calibration_by_level": scale[1:]}
+    return {"phases": rec, "segments": summary, "calibration_by_level": scale}

@@ -64,11 +64,13 @@ struct harli_predictor {
   std::vector<double> coef;       // 3 per level
   std::vector<char> fitted;       // per level
   std::vector<double> scale;      // per level: calibration factor on Eq. 1's prediction (1 unless the caller sets it)
+  std::vector<char> observed;     // per level: a measured step has been folded into `scale` (harli_pred_observe)
   double b1 = 0, k1 = 0;
   bool colo_fitted = false;
 };
 
 namespace {
+constexpr double kScaleMin = 0.6, kScaleMax = 2.5;  // one measured step moves a prediction by no more than this
 bool level_ok(const harli_predictor* p, int level) { return level >= 1 && level <= p->n_levels; }
 double eval_solo(const harli_predictor* p, int level, double bs, double seqlen) {
   const double* c = &p->coef[(size_t)(level - 1) * 3];
@@ -90,6 +92,7 @@ extern "C" harli_status harli_pred_create(int32_t n_levels, harli_predictor** ou
   p->coef.assign((size_t)n_levels * 3, 0.0);
   p->fitted.assign(n_levels, 0);
   p->scale.assign(n_levels, 1.0);
+  p->observed.assign(n_levels, 0);
   *out = p;
   return HARLI_OK;
 }
@@ -177,6 +180,30 @@ extern "C" harli_status harli_pred_set_scale(harli_predictor* p, int32_t level, 
   if (!p || !level_ok(p, level) || !(scale > 0.0) || !std::isfinite(scale))
     return fail(HARLI_ERR_INVALID, "pred_set_scale: bad argument (level %d, scale %g)", level, scale);
   p->scale[level - 1] = scale;
+  p->observed[level - 1] = 0;  // a factor set by hand is a prior: the first measured step replaces it
+  return HARLI_OK;
+}
+
+extern "C" harli_status harli_pred_get_scale(const harli_predictor* p, int32_t level, double* scale) {
+  if (!p || !scale || !level_ok(p, level)) return fail(HARLI_ERR_INVALID, "pred_get_scale: bad argument");
+  *scale = p->scale[level - 1];
+  return HARLI_OK;
+}
+
+extern "C" harli_status harli_pred_observe(harli_predictor* p, int32_t level, double predicted_ms, double measured_ms,
+                                           double weight) {
+  if (!p || !level_ok(p, level) || !(predicted_ms > 0.0) || !std::isfinite(predicted_ms) || !(measured_ms > 0.0) ||
+      !std::isfinite(measured_ms) || !(weight > 0.0) || !(weight <= 1.0))
+    return fail(HARLI_ERR_INVALID, "pred_observe: bad argument (level %d, predicted %g, measured %g, weight %g)", level,
+                predicted_ms, measured_ms, weight);
+  double r = measured_ms / predicted_ms;
+  r = r < kScaleMin ? kScaleMin : r > kScaleMax ? kScaleMax : r;
+  double& s = p->scale[level - 1];
+  if (p->observed[level - 1]) s += weight * (r - s);
+  else s = r;  // the first measurement of a level is taken whole
+  p->observed[level - 1] = 1;
+  for (int l = 0; l < p->n_levels; ++l)  // levels never measured borrow from the one measured last
+    if (!p->observed[l]) p->scale[l] = s;
   return HARLI_OK;
 }
 

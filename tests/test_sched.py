@@ -187,3 +187,28 @@ def test_runtime_scheduler_rejects_bad_arguments():
     for bs, n in [(0, 10), (4, -1)]:
         with pytest.raises(hb.HarliError):
             s.step(bs, n, True)
+
+
+def test_run_time_feedback_equals_the_model_and_moves_the_predictions():
+    p, o_solo, o_colo = build_both(0)
+    rng = np.random.default_rng(77)
+    c = S.Calibration(10)
+    for k in range(300):
+        lv = int(rng.integers(1, 11))
+        pred, meas, wgt = float(rng.uniform(0.1, 40)), float(rng.uniform(0.05, 90)), float(rng.choice([0.15, 0.5, 1.0]))
+        if k % 50 == 49:
+            v = float(rng.uniform(0.7, 1.5))
+            c.set(lv, v)
+            p.set_scale(lv, v)
+        c.observe(lv, pred, meas, wgt)
+        p.observe(lv, pred, meas, wgt)
+        got = [p.get_scale(l) for l in range(1, 11)]
+        assert np.allclose(got, c.scale, rtol=1e-12, atol=0)
+    for lv in range(1, 11):                         # and the factor is what every prediction of the level carries
+        want = S.predict_solo(S.calibrated(o_solo[lv - 1], c.scale[lv - 1]), 24, 900)
+        assert abs(p.solo(lv, 24, 900) - want) <= 1e-9 * abs(want)
+    for bad in [(0, 1.0, 1.0, 0.5), (11, 1.0, 1.0, 0.5), (1, 0.0, 1.0, 0.5), (1, 1.0, -1.0, 0.5), (1, 1.0, 1.0, 0.0),
+                (1, 1.0, 1.0, 1.5), (1, float("nan"), 1.0, 0.5), (1, 1.0, float("inf"), 0.5)]:
+        with pytest.raises(hb.HarliError) as e:
+            p.observe(*bad)
+        assert e.value.status == hb.HARLI_ERR_INVALID
