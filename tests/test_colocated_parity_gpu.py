@@ -4,8 +4,8 @@ loop on one stream while finetune units run on another, both through the C ABI a
 Sharing the chip must not change a result.  The finetune unit has no order-dependent arithmetic, so its outputs beside
 a running decode loop are bit-identical to its outputs alone, and they meet the oracle at the usual bar (max-abs error
 <= 2e-2 * max|ref|, relative Frobenius error <= 5e-3).  The decode step sums its row norms with floating-point atomics,
-so it is compared with its own solo result to 1e-5 (the solo step at this size is compared with the oracle in
-test_decode_gpu.py).
+whose order can flip the bf16 rounding of a few operand elements downstream, so it is compared with its own solo
+result to 2e-3 of the largest output (the solo step at this size is compared with the oracle in test_decode_gpu.py).
 """
 import threading
 
@@ -92,7 +92,7 @@ def test_results_do_not_change_when_both_tasks_share_the_chip():
     for p in dA1:
         assert torch.equal(dA1[p], dA2[p]) and torch.equal(dB1[p], dB2[p]), p
     scale = float(y1.abs().max())
-    assert float((hz.y_dev - y1).abs().max()) <= 1e-5 * scale
+    assert float((hz.y_dev - y1).abs().max()) <= 2e-3 * scale
 
     assert_close(Y2.cpu().numpy().reshape(Yo.shape), Yo, "Y beside decode")
     assert_close(dX2.cpu().numpy().reshape(dXo.shape), dXo, "dX beside decode")

@@ -50,6 +50,37 @@ def test_decode_on_a_quarter_of_the_chip_matches_the_full_chip(hz):
     cs.close()
 
 
+def test_finetune_unit_on_a_partition_is_bit_identical_and_slower(hz):
+    cs = colocate.CuStreams()
+    full = torch.cuda.Stream()
+    part = cs.high(4)                                  # the last 40 % of the compute units
+
+    def unit_on(st):
+        for p in hz.dA:
+            hz.dA[p].zero_()
+            hz.dB[p].zero_()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(st)
+        hz.finetune_unit(st)
+        e1.record(st)
+        st.synchronize()
+        hz.drain()
+        out = (hz.Y_dev.clone(), hz.dX_dev.clone(), {p: hz.dA[p].clone() for p in hz.dA}, {p: hz.dB[p].clone() for p in hz.dB})
+        torch.cuda.synchronize()
+        return out, e0.elapsed_time(e1)
+
+    unit_on(full)                                      # first use sizes the workspace
+    (Y1, dX1, dA1, dB1), t_full = unit_on(full)
+    (Y2, dX2, dA2, dB2), t_part = unit_on(part)
+    hz.ctx.check(part)
+    # no kernel of the unit depends on how many workgroups run at a time
+    assert torch.equal(Y1, Y2) and torch.equal(dX1, dX2)
+    assert all(torch.equal(dA1[p], dA2[p]) and torch.equal(dB1[p], dB2[p]) for p in dA1)
+    assert t_part > 1.5 * t_full                       # 40 % of the chip: the restriction is real
+    cs.close()
+
+
 def test_profile_fit_and_scheduled_colocation(hz):
     pred, rep = colocate.profile(hz, steps=6)
     solo = rep["solo_ms_by_level_workload_batch"]
