@@ -40,6 +40,14 @@ harli_status harli_pred_add_colo(harli_predictor* p, int32_t infer_level, int32_
  * rank-deficient design (e.g. one batch size only). */
 harli_status harli_pred_fit(harli_predictor* p);
 
+/* Which reading of Eq. 2 (Sec. 5.2.1) the fit and the co-located predictions use.  enabled != 0 (the state after
+ * create): the factor SM_infer*b1 + SM_ft*k1 is floored at 1 and the fit leaves out the samples the floor covers, as
+ * described at harli_pred_fit.  enabled == 0: Eq. 2 exactly as printed -- one ordinary least-squares fit over every
+ * sample, predictions without a floor -- so that the paper's accuracy figure for this model (Sec. 8.4) can be
+ * evaluated as written.  Changing the reading discards the co-located fit (the samples stay): call harli_pred_fit
+ * again before the next co-located prediction. */
+harli_status harli_pred_set_colo_floor(harli_predictor* p, int32_t enabled);
+
 /* Calibration (an addition to the paper's predictor): every prediction at `level` -- alone, co-located, in
  * harli_sched_pick and in the runtime scheduler -- is Eq. 1's value times `scale` (> 0; 1 after create).  A caller that
  * times its decode steps at run time folds the ratio measured / predicted back in here; the fitted coefficients

@@ -80,13 +80,14 @@ class Calibration:
 COLO_FIT_ROUNDS = 32
 
 
-def fit_colo(samples):
-    """samples: iterable of (sm_infer, sm_ft, latency_colo, latency_solo_at_sm_infer).  Returns (b1, k1) of Eq. 2."""
+def fit_colo(samples, floor=True):
+    """samples: iterable of (sm_infer, sm_ft, latency_colo, latency_solo_at_sm_infer).  Returns (b1, k1) of Eq. 2.
+    floor=False is Eq. 2 as printed: one least-squares fit over every sample."""
     s = np.asarray(list(samples), np.float64)
     X = np.stack([s[:, 0] * s[:, 3], s[:, 1] * s[:, 3]], axis=1)
     beta, *_ = np.linalg.lstsq(X, s[:, 2], rcond=None)
     active = np.ones(len(s), bool)
-    for _ in range(COLO_FIT_ROUNDS):
+    for _ in range(COLO_FIT_ROUNDS if floor else 0):
         now = s[:, 0] * beta[0] + s[:, 1] * beta[1] >= 1.0      # samples the floor does not cover
         if (now == active).all() or now.sum() < 2 or np.linalg.matrix_rank(X[now]) < 2:
             break
@@ -95,10 +96,11 @@ def fit_colo(samples):
     return float(beta[0]), float(beta[1])
 
 
-def predict_colo(colo_coef, sm_infer, sm_ft, latency_solo):
-    """Eq. 2 with the slowdown factor floored at 1 (see the module header)."""
+def predict_colo(colo_coef, sm_infer, sm_ft, latency_solo, floor=True):
+    """Eq. 2 with the slowdown factor floored at 1 (see the module header); floor=False: Eq. 2 as printed."""
     b1, k1 = colo_coef
-    return max(1.0, sm_infer * b1 + sm_ft * k1) * latency_solo
+    factor = sm_infer * b1 + sm_ft * k1
+    return (max(1.0, factor) if floor else factor) * latency_solo
 
 
 def pairs(n_levels=10):

@@ -119,6 +119,7 @@ _SIGS = {
     "harli_pred_fit": (C.c_int, [C.c_void_p]),
     "harli_pred_solo_coef": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_double)]),
     "harli_pred_colo_coef": (C.c_int, [C.c_void_p, C.POINTER(C.c_double)]),
+    "harli_pred_set_colo_floor": (C.c_int, [C.c_void_p, C.c_int32]),
     "harli_pred_solo": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_double)]),
     "harli_pred_colo": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_double)]),
     "harli_sched_create": (C.c_int, [C.c_void_p, C.c_double, C.c_int32, C.POINTER(C.c_void_p)]),
@@ -424,6 +425,9 @@ class Predictor:
         c = (C.c_double * 3)()
         _check(lib().harli_pred_solo_coef(self.handle, level, c))
         return tuple(c)
+
+    def set_colo_floor(self, enabled: bool) -> None:
+        _check(lib().harli_pred_set_colo_floor(self.handle, 1 if enabled else 0))
 
     def colo_coef(self):
         c = (C.c_double * 2)()

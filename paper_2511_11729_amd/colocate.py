@@ -248,6 +248,13 @@ def profile(hz, steps=12, log=lambda *a: None, batches=None, seqlens=None, heldo
         for i in range(1, N_LEVELS - f + 1):
             pred.add_colo(i, f, colo_meas[(i, f)], base[i])
     log("[sched] co-located profile: %d partitions in %.1f s" % (len(colo_meas), time.perf_counter() - t0))
+    # Eq. 2 as printed first (one least-squares fit, no floor), for the paper's accuracy figure; then the floored
+    # reading the scheduler runs on
+    pred.set_colo_floor(False)
+    pred.fit()
+    b1p, k1p = pred.colo_coef()
+    err_printed = [abs((i / N_LEVELS * b1p + f / N_LEVELS * k1p) * base[i] - ms) / ms for (i, f), ms in colo_meas.items()]
+    pred.set_colo_floor(True)
     pred.fit()
     err_fit = [abs(pred.solo(lv, bs, n) - ms) / ms for (lv, bs, n), ms in solo_meas.items()]
     err_held = [abs(pred.solo(lv, bs, n) - ms) / ms for (lv, bs, n), ms in held.items()]
@@ -259,6 +266,8 @@ def profile(hz, steps=12, log=lambda *a: None, batches=None, seqlens=None, heldo
         "eq1_max_abs_err_heldout": float(np.max(err_held)),
         "eq1_coef_full_chip_b0_c0_k0_ms": list(pred.solo_coef(N_LEVELS)),
         "eq2_b1_k1": [b1, k1], "eq2_mean_abs_err": float(np.mean(err_colo)), "eq2_max_abs_err": float(np.max(err_colo)),
+        "eq2_as_printed_b1_k1": [b1p, k1p], "eq2_as_printed_mean_abs_err": float(np.mean(err_printed)),
+        "eq2_as_printed_max_abs_err": float(np.max(err_printed)),
         "solo_ms_by_level_workload_batch": [base[lv] for lv in range(1, N_LEVELS + 1)],
         "colo_ms": {"%d+%d" % k: v for k, v in sorted(colo_meas.items())},
     }

@@ -34,7 +34,7 @@ struct DecodeWs {
   int bpad = 0;
   void *hx1 = nullptr, *obuf = nullptr, *hx2 = nullptr, *mbuf = nullptr;  // GEMM operands in storage dtype
   float *qbuf = nullptr, *x1 = nullptr, *xa = nullptr, *xb = nullptr;    // fp32
-  float* ssq = nullptr;       // [2*L+1][bpad]
+  unsigned long long* ssq = nullptr;  // [2*L+1][bpad][2]: sums of squares as (hi, lo) integer pairs
   float* rope = nullptr;      // [bpad][d/2][2]
   double* inv_freq = nullptr; // [d/2] base^(-2i/d)
   float* att_part = nullptr;  // [bpad][n_q][max_chunks][d+2]

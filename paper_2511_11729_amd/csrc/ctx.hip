@@ -124,7 +124,7 @@ extern "C" harli_status harli_ctx_create(const harli_model_cfg* cfg, const harli
   TRY(dev_alloc(&d.x1, bp * m.hidden * 4, true));
   TRY(dev_alloc(&d.xa, bp * m.hidden * 4, true));
   TRY(dev_alloc(&d.xb, bp * m.hidden * 4, true));
-  TRY(dev_alloc(&d.ssq, bp * (2 * m.n_layers + 1) * 4, true));
+  TRY(dev_alloc(&d.ssq, bp * (2 * m.n_layers + 1) * 16, true));
   TRY(dev_alloc(&d.rope, bp * m.head_dim * 4, true));
   if (m.vocab > 0) {
     TRY(dev_alloc(&d.amax_v, bp * 64 * 4, true));
@@ -205,8 +205,10 @@ extern "C" harli_status harli_ctx_check(harli_ctx* c, void* hip_stream) {
   if (flag) {
     HARLI_HIP(hipMemsetAsync(c->dw.err_flag, 0, sizeof(int), st));
     HARLI_HIP(hipStreamSynchronize(st));
-    return fail(HARLI_ERR_INVALID, "a kernel saw %s%s", (flag & 1) ? "a page id outside the pool " : "",
-                (flag & 2) ? "a token id outside the vocabulary" : "");
+    return fail(HARLI_ERR_INVALID, "a kernel saw %s%s%s%s", (flag & 1) ? "a page id outside the pool; " : "",
+                (flag & 2) ? "a token or class id outside the vocabulary; " : "",
+                (flag & 4) ? "a sequence longer than max_kv_len or its page-table row; " : "",
+                (flag & 8) ? "a finetune activation beyond the range of the 16-bit compute element; " : "");
   }
   return HARLI_OK;
 }

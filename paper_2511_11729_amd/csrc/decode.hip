@@ -46,7 +46,7 @@ struct SkinnyArgs {
   int B, b0, K;             // batch size, first batch row of this pass, contraction length
   int n_rows;               // output rows (tail masking of stores)
   const unsigned short *w0, *w1;  // pre-shuffled weights
-  const float* ssq_in;      // sum of squares of the operand's source row (rho), or null
+  const unsigned long long* ssq_in;  // sum of squares of the operand's source row (rho) as a (hi, lo) pair, or null
   float eps, inv_dim;
   // QKV
   float* qbuf;
@@ -63,7 +63,7 @@ struct SkinnyArgs {
   float* out;
   const float* gnext;
   unsigned short* hxn;  // next operand (fragment order, K = n_rows) or null
-  float* ssq_out;
+  unsigned long long* ssq_out;  // (hi, lo) pairs, see ssq_add
   // GATEUP
   unsigned short* mbuf;  // next operand (fragment order, K = n_rows)
   // LM
@@ -71,6 +71,27 @@ struct SkinnyArgs {
 };
 
 __device__ __forceinline__ uint4 ld16(const unsigned short* p) { return *reinterpret_cast<const uint4*>(p); }
+
+// Sum of squares of a residual row, accumulated across workgroups.  The workgroups of a launch finish in any order,
+// and a float sum depends on that order in its last bit (which then flips bf16 roundings downstream), so the
+// partial sums are added as integers, where the order does not matter: a non-negative float v <= 2^60 is split
+// exactly into hi = floor(v / 2^8) and lo = floor((v - 2^8 hi) 2^40) < 2^48 (only bits below 2^-40 are dropped,
+// the same ones for a given partial in every run), and the two 64-bit counters take up to 2^11 such partials.
+__device__ __forceinline__ void ssq_split(float v, unsigned long long* hi, unsigned long long* lo) {
+  const double dv = (double)fminf(v, 0x1p60f);
+  *hi = (unsigned long long)(dv * 0x1p-8);
+  *lo = (unsigned long long)((dv - (double)*hi * 0x1p8) * 0x1p40);
+}
+__device__ __forceinline__ void ssq_add(unsigned long long* slot, float v) {
+  unsigned long long hi, lo;
+  ssq_split(v, &hi, &lo);
+  atomicAdd(slot, hi);
+  atomicAdd(slot + 1, lo);
+}
+__device__ __forceinline__ float ssq_value(const unsigned long long* slot) {
+  const ulonglong2 p = *reinterpret_cast<const ulonglong2*>(slot);
+  return (float)((double)p.x * 0x1p8 + (double)p.y * 0x1p-40);
+}
 
 // RT = 16-row weight tiles per wave: a wave holds RT x NB accumulator tiles, so that a batch fragment fetched for a
 // k-step serves RT weight fragments (at 64 batch rows every wave otherwise pulls four batch fragments through the
@@ -151,7 +172,7 @@ __global__ void __launch_bounds__(TW * KW * 64) k_skinny(SkinnyArgs a) {
     for (int e = 0; e < 4; ++e) pre_cs[r][e] = make_float2(1.f, 0.f);
   }
   if (active) {
-    if (MODE != MODE_RESID) pre_ssq = a.ssq_in[jb];
+    if (MODE != MODE_RESID) pre_ssq = ssq_value(a.ssq_in + 2 * (size_t)jb);
     if (MODE == MODE_QKV) {
 #pragma unroll
       for (int r = 0; r < RT; ++r) {
@@ -334,7 +355,7 @@ __global__ void __launch_bounds__(TW * KW * 64) k_skinny(SkinnyArgs a) {
   if (MODE == MODE_RESID && epi) {
     s2 += __shfl_xor(s2, 16, 64);
     s2 += __shfl_xor(s2, 32, 64);
-    if (active && g == 0 && a.ssq_out) atomicAdd(a.ssq_out + jb, s2);
+    if (active && g == 0 && a.ssq_out) ssq_add(a.ssq_out + 2 * (size_t)jb, s2);
   }
 }
 
@@ -362,7 +383,7 @@ __global__ void __launch_bounds__(256) k_pack_weight(const unsigned short* src, 
 // ---------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(256) k_decode_prep(int H, int d, int n_ssq, int bpad, const int* token_ids,
                                                      const unsigned short* emb, int vocab, const float* x_in, float* xa,
-                                                     const float* g1, unsigned short* hx1, float* ssq, float* rope,
+                                                     const float* g1, unsigned short* hx1, unsigned long long* ssq, float* rope,
                                                      const int* kv_len, const double* inv_freq, int* err_flag) {
   const int b = blockIdx.x, tid = threadIdx.x;
   const int steps = (H + 31) >> 5;
@@ -396,8 +417,11 @@ __global__ void __launch_bounds__(256) k_decode_prep(int H, int d, int n_ssq, in
   s2 = wave_sum(s2);
   if ((tid & 63) == 0) sh[tid >> 6] = s2;
   __syncthreads();
-  if (tid == 0) ssq[b] = sh[0] + sh[1] + sh[2] + sh[3];
-  for (int i = 1 + tid; i < n_ssq; i += 256) ssq[(size_t)i * bpad + b] = 0.f;
+  if (tid == 0) ssq_split(sh[0] + sh[1] + sh[2] + sh[3], ssq + 2 * (size_t)b, ssq + 2 * (size_t)b + 1);
+  for (int i = 1 + tid; i < n_ssq; i += 256) {
+    ssq[2 * ((size_t)i * bpad + b)] = 0ull;
+    ssq[2 * ((size_t)i * bpad + b) + 1] = 0ull;
+  }
   const int half = d >> 1;
   const double pos = (double)kv_len[b];
   for (int i = tid; i < half; i += 256) {
@@ -431,6 +455,9 @@ __global__ void __launch_bounds__(256) k_paged_attn(const float* qbuf, const int
   constexpr int PW = CH / kPageTokens / 4;  // pages per wave
   const int b = blockIdx.z, c = blockIdx.y, ch = blockIdx.x;
   const int n_tot = kv_len[b] + 1;
+  // the grid covers the caller's bound max_kv_len: a longer sequence would lose its newest tokens without a word
+  if (ch == 0 && c == 0 && threadIdx.x == 0 && (n_tot > (int)gridDim.x * CH || n_tot > max_pages * kPageTokens))
+    atomicOr(err_flag, 4);
   if (ch * CH >= n_tot) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int dg = lane % LPT, tl = lane / LPT;
@@ -726,8 +753,7 @@ void dispatch_skinny(SkinnyArgs a, int n_wg, hipStream_t st) {
 }
 
 template <int D, int G, int CH>
-void launch_attn(harli_ctx* c, const harli_decode_batch* b, int layer, hipStream_t st) {
-  DecodeWs& w = c->dw;
+void launch_attn(harli_ctx* c, const DecodeWs& w, const harli_decode_batch* b, int layer, hipStream_t st) {
   const harli_model_cfg& m = c->cfg;
   const int n_chunks = (b->max_kv_len + CH - 1) / CH;
   hipLaunchKernelGGL((k_paged_attn<D, G, CH>), dim3(n_chunks, m.n_kv_heads, b->batch), dim3(256), 0, st, w.qbuf,
@@ -759,7 +785,10 @@ harli_status pack_weight(const void* src, void* dst, int N, int K, int row_tile0
 
 }  // namespace harli
 
-extern "C" harli_status harli_decode_step(harli_ctx* c, const harli_decode_batch* b, void* hip_stream) {
+namespace {
+
+// Argument checks shared by the two entry points (host only; nothing is enqueued on failure).
+harli_status check_decode_args(harli_ctx* c, const harli_decode_batch* b) {
   if (!c || !b) return fail(HARLI_ERR_INVALID, "decode_step: null argument");
   const harli_model_cfg& m = c->cfg;
   if (b->batch < 1 || b->batch > m.max_batch)
@@ -775,10 +804,12 @@ extern "C" harli_status harli_decode_step(harli_ctx* c, const harli_decode_batch
   if ((long long)b->max_pages * c->geom.page_tokens < b->max_kv_len)
     return fail(HARLI_ERR_INVALID, "decode_step: page table rows of %d pages cannot hold %d tokens", b->max_pages,
                 b->max_kv_len);
-  hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  if (m.dtype == HARLI_F32) return decode_step_f32(c, b, st);
+  return HARLI_OK;
+}
 
-  DecodeWs& w = c->dw;
+// The step on bf16 storage; every intermediate buffer comes from `w`.
+harli_status decode_step_bf16(harli_ctx* c, const harli_decode_batch* b, hipStream_t st, const DecodeWs& w) {
+  const harli_model_cfg& m = c->cfg;
   const int B = b->batch, H = m.hidden, d = m.head_dim, QD = m.n_q_heads * d, F = m.ffn, L = m.n_layers;
   const int n_ssq = 2 * L + 1;
   hipLaunchKernelGGL(k_decode_prep, dim3(B), dim3(256), 0, st, H, d, n_ssq, w.bpad, b->token_ids,
@@ -801,7 +832,7 @@ extern "C" harli_status harli_decode_step(harli_ctx* c, const harli_decode_batch
     a.K = H;
     a.n_rows = QD;
     a.w0 = static_cast<const unsigned short*>(lw.wp[0]);
-    a.ssq_in = w.ssq + (size_t)(2 * l) * w.bpad;
+    a.ssq_in = w.ssq + 2 * (size_t)(2 * l) * w.bpad;
     a.qbuf = w.qbuf;
     a.rope = w.rope;
     a.kv_len = b->kv_len;
@@ -816,17 +847,17 @@ extern "C" harli_status harli_decode_step(harli_ctx* c, const harli_decode_batch
     for (int t = 0; t < 3; ++t) a.bias[t] = lw.bias[t];
     dispatch_skinny<MODE_QKV, 2, 2>(a, (m.n_q_heads + 2 * m.n_kv_heads) * (d / 32), st);
     // --- attention
-    if (d == 128 && G == 1) launch_attn<128, 1, 256>(c, b, l, st);
-    else if (d == 128 && G == 2) launch_attn<128, 2, 256>(c, b, l, st);
-    else if (d == 128 && G == 4) launch_attn<128, 4, 128>(c, b, l, st);
-    else if (d == 128 && G == 8) launch_attn<128, 8, 128>(c, b, l, st);
-    else if (d == 128 && G == 3) launch_attn<128, 3, 128>(c, b, l, st);
-    else if (d == 128 && G == 5) launch_attn<128, 5, 128>(c, b, l, st);
-    else if (d == 128 && G == 6) launch_attn<128, 6, 128>(c, b, l, st);
-    else if (d == 128 && G == 7) launch_attn<128, 7, 128>(c, b, l, st);
-    else if (d == 64 && G == 1) launch_attn<64, 1, 256>(c, b, l, st);
-    else if (d == 64 && G == 2) launch_attn<64, 2, 256>(c, b, l, st);
-    else if (d == 64 && G == 4) launch_attn<64, 4, 256>(c, b, l, st);
+    if (d == 128 && G == 1) launch_attn<128, 1, 256>(c, w, b, l, st);
+    else if (d == 128 && G == 2) launch_attn<128, 2, 256>(c, w, b, l, st);
+    else if (d == 128 && G == 4) launch_attn<128, 4, 128>(c, w, b, l, st);
+    else if (d == 128 && G == 8) launch_attn<128, 8, 128>(c, w, b, l, st);
+    else if (d == 128 && G == 3) launch_attn<128, 3, 128>(c, w, b, l, st);
+    else if (d == 128 && G == 5) launch_attn<128, 5, 128>(c, w, b, l, st);
+    else if (d == 128 && G == 6) launch_attn<128, 6, 128>(c, w, b, l, st);
+    else if (d == 128 && G == 7) launch_attn<128, 7, 128>(c, w, b, l, st);
+    else if (d == 64 && G == 1) launch_attn<64, 1, 256>(c, w, b, l, st);
+    else if (d == 64 && G == 2) launch_attn<64, 2, 256>(c, w, b, l, st);
+    else if (d == 64 && G == 4) launch_attn<64, 4, 256>(c, w, b, l, st);
     else return fail(HARLI_ERR_INVALID, "decode_step: head_dim %d with group %d is not supported", d, G);
     // --- output projection + residual, operand of the FFN
     a.x = static_cast<const unsigned short*>(w.obuf);
@@ -837,7 +868,7 @@ extern "C" harli_status harli_decode_step(harli_ctx* c, const harli_decode_batch
     a.out = w.x1;
     a.gnext = lw.g2;
     a.hxn = static_cast<unsigned short*>(w.hx2);
-    a.ssq_out = w.ssq + (size_t)(2 * l + 1) * w.bpad;
+    a.ssq_out = w.ssq + 2 * (size_t)(2 * l + 1) * w.bpad;
     dispatch_skinny<MODE_RESID, 1, 8>(a, (H + 15) / 16, st);
     // --- gate/up + SwiGLU
     a.x = static_cast<const unsigned short*>(w.hx2);
@@ -845,7 +876,7 @@ extern "C" harli_status harli_decode_step(harli_ctx* c, const harli_decode_batch
     a.n_rows = F;
     a.w0 = static_cast<const unsigned short*>(lw.wp[4]);
     a.w1 = static_cast<const unsigned short*>(lw.wp[5]);
-    a.ssq_in = w.ssq + (size_t)(2 * l + 1) * w.bpad;
+    a.ssq_in = w.ssq + 2 * (size_t)(2 * l + 1) * w.bpad;
     a.mbuf = static_cast<unsigned short*>(w.mbuf);
     dispatch_skinny<MODE_GATEUP, 2, 4>(a, (F + 15) / 16, st);
     // --- down projection + residual, operand of the next layer (or of the output layer)
@@ -859,7 +890,7 @@ extern "C" harli_status harli_decode_step(harli_ctx* c, const harli_decode_batch
     a.out = xnext;
     a.gnext = last ? c->g_final : c->layers[l + 1].g1;
     a.hxn = (last && !b->logits) ? nullptr : static_cast<unsigned short*>(w.hx1);
-    a.ssq_out = w.ssq + (size_t)(2 * l + 2) * w.bpad;
+    a.ssq_out = w.ssq + 2 * (size_t)(2 * l + 2) * w.bpad;
     dispatch_skinny<MODE_RESID, 1, 8>(a, (H + 15) / 16, st);
     xcur = xnext;
   }
@@ -872,7 +903,7 @@ extern "C" harli_status harli_decode_step(harli_ctx* c, const harli_decode_batch
     a.K = H;
     a.n_rows = m.vocab;
     a.w0 = static_cast<const unsigned short*>(c->wlm_p);
-    a.ssq_in = w.ssq + (size_t)(2 * L) * w.bpad;
+    a.ssq_in = w.ssq + 2 * (size_t)(2 * L) * w.bpad;
     a.logits = b->logits;
     dispatch_skinny<MODE_LM, 2, 4>(a, (m.vocab + 31) / 32, st);
     if (b->next_token) {
@@ -882,4 +913,14 @@ extern "C" harli_status harli_decode_step(harli_ctx* c, const harli_decode_batch
   }
   HARLI_HIP(hipGetLastError());
   return HARLI_OK;
+}
+
+}  // namespace
+
+extern "C" harli_status harli_decode_step(harli_ctx* c, const harli_decode_batch* b, void* hip_stream) {
+  harli_status s = check_decode_args(c, b);
+  if (s != HARLI_OK) return s;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  if (c->cfg.dtype == HARLI_F32) return decode_step_f32(c, b, st);
+  return decode_step_bf16(c, b, st, c->dw);
 }

@@ -123,6 +123,7 @@ __global__ void __launch_bounds__(256) g_attention(const float* q, const int* kv
   const int hq = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int hk = hq / (n_q / n_kv);
   const int n_tot = min(min(kv_len[b] + 1, max_seq_len), max_pages * geom.page_tokens);
+  if (n_tot != kv_len[b] + 1 && threadIdx.x == 0) atomicOr(err_flag, 4);  // the sequence is longer than the step was sized for
   const float* qv = q + ((size_t)b * n_q + hq) * d;
   float* sc = scores + ((size_t)b * n_q + hq) * max_seq_len;
   const float scale = rsqrtf((float)d);

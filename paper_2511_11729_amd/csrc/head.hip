@@ -21,19 +21,16 @@ struct HeadWs {
   bf *w16 = nullptr, *wT = nullptr;  // [V][H] and [H][Vp] in the compute element (made once)
   bf *h = nullptr, *dlog = nullptr;
   float *rho = nullptr, *logits = nullptr, *dh = nullptr, *acc = nullptr;  // acc: [0] loss sum, [1] count, [2] 1/count
+  float* rowloss = nullptr;  // [T] loss of a counted row, -1 for a row that is not counted
   int T = 0, TC = 0, Vp = 0;
   bool weights_ready = false;
 };
 
 inline size_t al(size_t n) { return (n + 255) & ~size_t(255); }
 
-__global__ void k_head_reset(float* acc) {
-  if (threadIdx.x < 4) acc[threadIdx.x] = 0.f;
-}
-
 // one workgroup per row: max, log-sum-exp, loss, and dlog = softmax - onehot (zero row when the position is not counted)
 __global__ void __launch_bounds__(256) k_ce_row(const float* __restrict__ logits, const int* __restrict__ targets, bf* __restrict__ dlog,
-                                                int V, int Vp, float* acc, int* err_flag) {
+                                                int V, int Vp, float* rowloss, int* err_flag) {
   __shared__ float red[4];
   __shared__ float bc;
   const int row = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -46,6 +43,7 @@ __global__ void __launch_bounds__(256) k_ce_row(const float* __restrict__ logits
   }
   if (tg < 0) {
     for (int j = tid; j < Vp; j += 256) d[j] = 0;
+    if (tid == 0) rowloss[row] = -1.f;
     return;
   }
   float mx = -INFINITY;
@@ -64,8 +62,7 @@ __global__ void __launch_bounds__(256) k_ce_row(const float* __restrict__ logits
   if (tid == 0) {
     const float tot = red[0] + red[1] + red[2] + red[3];
     bc = 1.f / tot;
-    atomicAdd(acc, logf(tot) + mx - z[tg]);
-    atomicAdd(acc + 1, 1.f);
+    rowloss[row] = fmaxf(logf(tot) + mx - z[tg], 0.f);  // a row's loss is >= 0; rounding may leave -0
   }
   __syncthreads();
   const float inv = bc;
@@ -76,10 +73,32 @@ __global__ void __launch_bounds__(256) k_ce_row(const float* __restrict__ logits
   }
 }
 
-__global__ void k_head_finish(float* acc, float* loss) {
-  const float n = fmaxf(acc[1], 1.f);
-  acc[2] = 1.f / n;
-  *loss = acc[0] / n;
+// Sum of the rows' losses in a fixed order (thread t takes rows t, t + 256, ..., then a tree over the threads), so
+// that the loss is the same number in every run; atomics would add the rows in the order they happen to finish.
+__global__ void __launch_bounds__(256) k_head_finish(const float* rowloss, int T, float* acc, float* loss) {
+  __shared__ float sl[256];
+  __shared__ int sn[256];
+  const int tid = threadIdx.x;
+  float l = 0.f;
+  int n = 0;
+  for (int r = tid; r < T; r += 256) {
+    const float v = rowloss[r];
+    if (v >= 0.f) l += v, ++n;
+  }
+  sl[tid] = l;
+  sn[tid] = n;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if (tid < o) sl[tid] += sl[tid + o], sn[tid] += sn[tid + o];
+    __syncthreads();
+  }
+  if (tid == 0) {
+    const float cnt = fmaxf((float)sn[0], 1.f);
+    acc[0] = sl[0];
+    acc[1] = (float)sn[0];
+    acc[2] = 1.f / cnt;
+    *loss = sl[0] / cnt;
+  }
 }
 
 // [V][H] storage (bf16 or fp32) -> [H][Vp] compute element, zero in the pad columns
@@ -120,7 +139,7 @@ harli_status ensure(harli_ctx* c, int T, hipStream_t st) {
       return o;
     };
     const size_t o_h = take((size_t)T * H * 2), o_rho = take((size_t)T * 4), o_log = take((size_t)TC * Vp * 4);
-    const size_t o_dlog = take((size_t)TC * Vp * 2), o_dh = take((size_t)T * H * 4), o_acc = take(64);
+    const size_t o_dlog = take((size_t)TC * Vp * 2), o_dh = take((size_t)T * H * 4), o_acc = take(64), o_rl = take((size_t)T * 4);
     if (w.base) {
       HARLI_HIP(hipStreamSynchronize(st));
       HARLI_HIP(hipFree(w.base));
@@ -130,7 +149,7 @@ harli_status ensure(harli_ctx* c, int T, hipStream_t st) {
     w.bytes = off;
     char* b = w.base;
     w.h = (bf*)(b + o_h); w.rho = (float*)(b + o_rho); w.logits = (float*)(b + o_log); w.dlog = (bf*)(b + o_dlog);
-    w.dh = (float*)(b + o_dh); w.acc = (float*)(b + o_acc);
+    w.dh = (float*)(b + o_dh); w.acc = (float*)(b + o_acc); w.rowloss = (float*)(b + o_rl);
     w.T = T;
     w.TC = TC;
   }
@@ -165,7 +184,6 @@ extern "C" harli_status harli_head_fwd_bwd(harli_ctx* c, const float* x, const i
   HeadWs& w = *ws_of(c);
   const int V = c->cfg.vocab, H = c->cfg.hidden, Vp = w.Vp;
   ft_rmsnorm_fwd(x, c->g_final, w.h, w.rho, T, H, c->cfg.rms_eps, st);
-  hipLaunchKernelGGL(k_head_reset, dim3(1), dim3(64), 0, st, w.acc);
   for (int t0 = 0; t0 < T; t0 += w.TC) {
     const int rows = std::min(w.TC, T - t0);
     {  // logits = h W^T
@@ -178,7 +196,7 @@ extern "C" harli_status harli_head_fwd_bwd(harli_ctx* c, const float* x, const i
       s = gemm_launch(g, 1, st);
       if (s != HARLI_OK) return s;
     }
-    hipLaunchKernelGGL(k_ce_row, dim3(rows), dim3(256), 0, st, w.logits, targets + t0, w.dlog, V, Vp, w.acc, c->dw.err_flag);
+    hipLaunchKernelGGL(k_ce_row, dim3(rows), dim3(256), 0, st, w.logits, targets + t0, w.dlog, V, Vp, w.rowloss + t0, c->dw.err_flag);
     {  // dh = dlog W   (contraction over the padded vocabulary: pad columns are zero on both sides)
       GemmArgs g{};
       g.M = rows; g.N = H; g.nb1 = g.nb2 = 1; g.alpha = 1.f; g.causal = GEMM_FULL; g.half = kFtHalf ? 1 : 0;
@@ -190,7 +208,7 @@ extern "C" harli_status harli_head_fwd_bwd(harli_ctx* c, const float* x, const i
       if (s != HARLI_OK) return s;
     }
   }
-  hipLaunchKernelGGL(k_head_finish, dim3(1), dim3(1), 0, st, w.acc, loss);
+  hipLaunchKernelGGL(k_head_finish, dim3(1), dim3(256), 0, st, w.rowloss, T, w.acc, loss);
   ft_rmsnorm_bwd(w.dh, x, w.rho, c->g_final, nullptr, dx, nullptr, T, H, nullptr, w.acc + 2, st);
   HARLI_HIP(hipGetLastError());
   return HARLI_OK;

@@ -283,10 +283,17 @@ struct harli_pool {
   // ---- deferred frees -----------------------------------------------------------------
   void poll() {
     size_t k = 0;
+    void* seen = nullptr;  // entries that share an event (the pages of one free call) sit next to each other
+    int seen_done = 0;
+    std::vector<void*> destroy;
     for (size_t i = 0; i < pending.size(); ++i) {
       Pending& p = pending[i];
-      if (event_done(p.event) != 0) {  // completed (or the query failed: do not leak)
-        if (p.own) event_destroy(p.event);
+      if (p.event != seen) seen = p.event, seen_done = event_done(p.event);
+      // Only a completed event releases memory.  A query that fails says nothing about the work that still reads
+      // the buffer, so the entry stays pending (the memory is held back until the pool is destroyed rather than
+      // handed to a second owner).
+      if (seen_done > 0) {
+        if (p.own) destroy.push_back(p.event);  // after the pass: later entries may share it
         if (p.is_page)
           release_page(p.page);
         else
@@ -296,6 +303,7 @@ struct harli_pool {
       }
     }
     pending.resize(k);
+    for (void* e : destroy) event_destroy(e);
   }
 };
 
@@ -419,9 +427,13 @@ harli_status harli_pool_alloc_pages(harli_pool* p, int32_t n_pages, int32_t* pag
   return HARLI_OK;
 }
 
-harli_status harli_pool_free(harli_pool* p, const harli_alloc* a, void* event) {
+// `own`: the pool destroys the event once it has completed.  The pending entry is made with that flag under the
+// lock that adds it: a poll from another thread may run as soon as the lock is dropped.
+static harli_status free_pages_impl(harli_pool* p, int32_t n_pages, const int32_t* page_ids, void* event, bool own);
+
+static harli_status free_impl(harli_pool* p, const harli_alloc* a, void* event, bool own) {
   if (!p || !a) return fail(HARLI_ERR_INVALID, "pool_free: null argument");
-  if (a->cls == HARLI_CLS_KV_PAGE) return harli_pool_free_pages(p, 1, &a->page, event);
+  if (a->cls == HARLI_CLS_KV_PAGE) return free_pages_impl(p, 1, &a->page, event, own);
   std::lock_guard<std::mutex> lk(p->mu);
   p->poll();
   auto it = p->live.find(a->offset);
@@ -429,13 +441,19 @@ harli_status harli_pool_free(harli_pool* p, const harli_alloc* a, void* event) {
   for (const Pending& q : p->pending)
     if (!q.is_page && q.offset == a->offset) return fail(HARLI_ERR_INVALID, "pool_free: offset %zu freed twice", a->offset);
   if (event)
-    p->pending.push_back(Pending{event, false, false, -1, a->offset});
+    p->pending.push_back(Pending{event, own, false, -1, a->offset});
   else
     p->release(a->offset);
   return HARLI_OK;
 }
 
+harli_status harli_pool_free(harli_pool* p, const harli_alloc* a, void* event) { return free_impl(p, a, event, false); }
+
 harli_status harli_pool_free_pages(harli_pool* p, int32_t n_pages, const int32_t* page_ids, void* event) {
+  return free_pages_impl(p, n_pages, page_ids, event, false);
+}
+
+static harli_status free_pages_impl(harli_pool* p, int32_t n_pages, const int32_t* page_ids, void* event, bool own) {
   if (!p || (n_pages > 0 && !page_ids) || n_pages < 0) return fail(HARLI_ERR_INVALID, "pool_free_pages: bad argument");
   std::lock_guard<std::mutex> lk(p->mu);
   p->poll();
@@ -449,7 +467,7 @@ harli_status harli_pool_free_pages(harli_pool* p, int32_t n_pages, const int32_t
   }
   for (int32_t i = 0; i < n_pages; ++i) {
     if (event)
-      p->pending.push_back(Pending{event, false, true, page_ids[i], 0});
+      p->pending.push_back(Pending{event, own && i == 0, true, page_ids[i], 0});  // one entry owns a shared event
     else
       p->release_page(page_ids[i]);
   }
@@ -538,14 +556,8 @@ namespace harli {
 // one event per released buffer and cannot know when the pool will have polled it).
 harli_status pool_free_owned(harli_pool* p, const harli_alloc* a, void* event) {
   if (!event) return harli_pool_free(p, a, nullptr);
-  harli_status st = harli_pool_free(p, a, event);
-  if (st != HARLI_OK) {
-    event_destroy(event);
-    return st;
-  }
-  std::lock_guard<std::mutex> lk(p->mu);
-  for (Pending& q : p->pending)
-    if (q.event == event) q.own = true;
-  return HARLI_OK;
+  harli_status st = free_impl(p, a, event, true);
+  if (st != HARLI_OK) event_destroy(event);
+  return st;
 }
 }  // namespace harli

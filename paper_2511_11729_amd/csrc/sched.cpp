@@ -67,6 +67,7 @@ struct harli_predictor {
   std::vector<char> observed;     // per level: a measured step has been folded into `scale` (harli_pred_observe)
   double b1 = 0, k1 = 0;
   bool colo_fitted = false;
+  bool colo_floor = true;         // Eq. 2's factor floored at 1 (this library's reading); false: Eq. 2 as printed
 };
 
 namespace {
@@ -80,7 +81,7 @@ double eval_solo(const harli_predictor* p, int level, double bs, double seqlen) 
 // contended case f_infer + f_ft > B only; without contention the co-located latency is the solo latency.
 double eval_colo(const harli_predictor* p, int il, int fl, double solo) {
   const double factor = (double)il / p->n_levels * p->b1 + (double)fl / p->n_levels * p->k1;
-  return (factor > 1.0 ? factor : 1.0) * solo;
+  return (p->colo_floor && factor < 1.0 ? 1.0 : factor) * solo;
 }
 }  // namespace
 
@@ -147,7 +148,7 @@ extern "C" harli_status harli_pred_fit(harli_predictor* p) {
     // Prediction floors the factor at 1, so a sample whose fitted factor is below 1 says nothing about b1, k1:
     // repeat the fit over the samples the floor does not cover until that set is stable.
     std::vector<char> active(n, 1), now(n);
-    for (int round = 0; round < 32; ++round) {
+    for (int round = 0; p->colo_floor && round < 32; ++round) {
       int cnt = 0;
       bool same = true;
       for (int i = 0; i < n; ++i) {
@@ -173,6 +174,13 @@ extern "C" harli_status harli_pred_fit(harli_predictor* p) {
     p->k1 = b[1];
     p->colo_fitted = true;
   }
+  return HARLI_OK;
+}
+
+extern "C" harli_status harli_pred_set_colo_floor(harli_predictor* p, int32_t enabled) {
+  if (!p) return fail(HARLI_ERR_INVALID, "pred_set_colo_floor: null predictor");
+  p->colo_floor = enabled != 0;
+  p->colo_fitted = false;  // the fit depends on the reading: fit again
   return HARLI_OK;
 }
 

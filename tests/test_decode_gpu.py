@@ -94,6 +94,28 @@ def test_three_layer_model_with_embedding_and_logits():
     assert np.array_equal(nxt[clear], ref_next[clear])
 
 
+def test_step_is_bit_reproducible():
+    """The same step gives the same bits every time, on any stream and whatever ran in between (the row norms are
+    summed across workgroups as integers, in which the order of arrival does not matter)."""
+    w, m = variant(0, dtype="bf16", n_layers=3, vocab=1000)
+    lengths = [12, 200, 0, 77, 300, 33, 5, 129, 64]
+    case = DecodeCase(w, m, np.asarray(lengths, np.int32), full_model=True, block_bytes=64 << 10)
+    tok = wl.make_token_ids(dataclasses.replace(w, model=m), (len(lengths),))
+    case.run_gpu(token_ids=tok)
+    first = (case.y_dev.clone(), case.logits_dev.clone(), case.next_dev.clone(), case.slab.clone())
+    side = torch.cuda.Stream()
+    busy = torch.randn(2048, 2048, device="cuda:0")
+    for rep in range(6):
+        case.slab.copy_(torch.from_numpy(case.img0.view(np.uint8)))
+        if rep % 2:                                   # unrelated work on another stream while the step runs
+            with torch.cuda.stream(side):
+                for _ in range(4):
+                    busy = busy @ busy * 1e-3
+        case.run_gpu(token_ids=tok, stream=side if rep >= 3 else None)
+        assert torch.equal(case.y_dev, first[0]) and torch.equal(case.logits_dev, first[1])
+        assert torch.equal(case.next_dev, first[2]) and torch.equal(case.slab, first[3])
+
+
 def test_argmax_ties_go_to_the_lowest_index():
     w, m = variant(0, dtype="bf16", n_layers=1, vocab=64)
     def same_rows(case):             # identical rows in the output layer give exactly equal logits

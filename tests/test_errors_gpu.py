@@ -52,6 +52,51 @@ def test_decode_step_rejects_what_its_header_says_and_enqueues_nothing():
     assert_close(case.run_gpu(), case.run_oracle(), "decode output after the rejected calls")
 
 
+def test_device_side_checks_report_through_ctx_check_and_every_kernel_exits_normally():
+    """What only the device can see -- a page id outside the pool, a token id outside the vocabulary, a sequence
+    longer than the bound the step was sized for -- sets a flag instead of being dereferenced; harli_ctx_check
+    reports and clears it, and the next valid step gives the oracle's result."""
+    w = wl.workload(0)
+    m = dataclasses.replace(w.model, dtype="bf16", n_layers=2, vocab=500)
+    lengths = np.asarray([300, 20, 33], np.int32)
+    case = DecodeCase(w, m, lengths, full_model=True, block_bytes=64 << 10)
+    B = case.B
+    tok = wl.make_token_ids(dataclasses.replace(w, model=m), (B,))
+    y = torch.empty(B, m.hidden, dtype=torch.float32, device=DEV)
+    logits = torch.empty(B, m.vocab, dtype=torch.float32, device=DEV)
+    tok_dev = torch.from_numpy(tok).to(DEV)
+    good = dict(batch=B, kv_len=case.kv_len_dev, page_table=case.table_dev, max_pages=case.max_pages,
+                max_kv_len=int(lengths.max()) + 1, token_ids=tok_dev, logits=logits, x_out=y)
+
+    def flagged(word, **kw):
+        case.slab.copy_(torch.from_numpy(case.img0.view(np.uint8)))
+        case.ctx.decode_step(**dict(good, **kw))
+        torch.cuda.synchronize()
+        with pytest.raises(hb.HarliError) as e:
+            case.ctx.check()
+        assert e.value.status == hb.HARLI_ERR_INVALID and word in str(e.value), str(e.value)
+        case.ctx.check()                                                     # reported once, then clear
+
+    n_pages = case.geom.n_chunks * case.geom.pages_per_block                 # ids run 0..n_pages-1
+    bad_table = case.table_dev.clone()
+    bad_table[1, 0] = n_pages + 7                                            # a page the attention of sequence 1 reads
+    flagged("page id", page_table=bad_table)
+    bad_table = case.table_dev.clone()
+    bad_table[2, int(lengths[2]) // 16] = -1                                 # the page the new token of sequence 2 goes to
+    flagged("page id", page_table=bad_table)
+    bad_tok = tok_dev.clone()
+    bad_tok[0] = m.vocab
+    flagged("token", token_ids=bad_tok)
+    flagged("longer than max_kv_len", max_kv_len=256)                        # sequence 0 holds 301 tokens
+    # nothing sticks: the valid step is the oracle's
+    case.slab.copy_(torch.from_numpy(case.img0.view(np.uint8)))
+    hid = case.run_gpu(token_ids=tok)
+    ref_hid, ref_logits, _ = case.run_oracle(token_ids=tok)
+    assert_close(hid, ref_hid, "hidden state after the flagged steps")
+    assert_close(case.logits_dev.cpu().numpy(), ref_logits, "logits after the flagged steps")
+    case.check_cache()
+
+
 def test_finetune_entry_points_reject_bad_arguments_and_keep_the_pool_clean():
     w = wl.workload(0)
     m = dataclasses.replace(w.model, dtype="bf16")

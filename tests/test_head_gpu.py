@@ -74,6 +74,12 @@ def test_head_loss_and_dx_match_the_oracle(vocab, T):
     ref_loss, ref_dx, _ = O.head_forward_backward(x, case.ex["gf"], case.ex["wlm"], tg, case.m.rms_eps)
     assert abs(float(loss) - ref_loss) <= 2e-3 * abs(ref_loss), (float(loss), ref_loss)
     assert_close(dx.cpu().numpy(), ref_dx, "head dx")
+    # the rows' losses are added in a fixed order: the same bits on every call
+    loss2, dx2 = torch.zeros(1, device=DEV), torch.empty_like(dx)
+    for _ in range(3):
+        case.ctx.head_fwd_bwd(f32_dev(x), torch.from_numpy(tg).to(DEV), loss2, dx2)
+        torch.cuda.synchronize()
+        assert torch.equal(loss, loss2) and torch.equal(dx, dx2)
     # an out-of-range class is reported, not dereferenced
     tg[0] = vocab + 5
     case.ctx.head_fwd_bwd(f32_dev(x), torch.from_numpy(tg).to(DEV), loss, dx)

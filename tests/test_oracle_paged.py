@@ -153,6 +153,48 @@ def test_multi_layer_model_is_a_stack_of_layers():
     assert np.allclose(logits, O.rmsnorm(hid, extras["gf"], sh.rms_eps) @ extras["wlm"].T)
 
 
+def test_full_model_embedding_gather_final_norm_and_output_layer():
+    """Pins the three steps around the layer stack (Sec. 2.1: embedding, layers, output layer) to values worked out by
+    hand: the row of the table a token id selects, the final norm with gains that are not one, the output product
+    written as explicit sums, and the lowest index on an argmax tie."""
+    sh = tiny_shapes(n_kv=2, d=4)
+    H = sh.hidden
+    geom = _geom(sh, 1, 2, block_bytes=2048)
+    kv = O.PagedKV(geom, 4, sh.n_kv, sh.head_dim)
+    V = 11
+    emb = np.arange(V, dtype=np.float64)[:, None] * np.ones((1, H))     # row i is the constant i
+    gf = 1.0 + 0.1 * np.arange(H)
+    wlm = np.zeros((V, H))
+    wlm[3, 0], wlm[7, 0], wlm[5, 1] = 2.0, 2.0, 1.0                     # rows 3 and 7 tie
+    tokens = np.array([4, 9])
+    # no layers: the hidden state is the gathered row itself
+    hid, logits, nxt = O.decode_model_paged(tokens, [], dict(emb=emb, gf=gf, wlm=wlm), sh, kv, np.array([0, 0]),
+                                            np.array([[0], [1]]))
+    assert np.array_equal(hid, np.stack([np.full(H, 4.0), np.full(H, 9.0)]))
+    for b, c in enumerate((4.0, 9.0)):
+        rho = 1.0 / np.sqrt(c * c + sh.rms_eps)                         # mean of squares of a constant row
+        want = np.zeros(V)
+        for v in range(V):
+            for j in range(H):
+                want[v] += c * rho * gf[j] * wlm[v, j]
+        assert np.allclose(logits[b], want, rtol=1e-13, atol=0)
+        assert logits[b, 3] == logits[b, 7] > logits[b, 5] and nxt[b] == 3
+    # with layers: token ids give what the gathered rows give when passed as hidden states
+    rng = np.random.default_rng(5)
+    layers = [rand_weights(rng, sh)]
+    emb2 = rng.standard_normal((V, H))
+    lens, table = np.array([0, 0]), np.array([[0], [1]])
+    kv_a = O.PagedKV(geom, 4, sh.n_kv, sh.head_dim)
+    kv_b = O.PagedKV(geom, 4, sh.n_kv, sh.head_dim)
+    hid_t, _, _ = O.decode_model_paged(tokens, layers, dict(emb=emb2, gf=gf, wlm=wlm), sh, kv_a, lens, table)
+    x_rows = np.stack([emb2[4], emb2[9]])
+    hid_x = O.decode_model_paged(x_rows, layers, None, sh, kv_b, lens, table)
+    assert np.array_equal(hid_t, hid_x) and np.array_equal(kv_a.slab, kv_b.slab)
+    swapped = O.decode_model_paged(np.stack([emb2[9], emb2[4]]), layers, None, sh,
+                                   O.PagedKV(geom, 4, sh.n_kv, sh.head_dim), lens, table)
+    assert not np.allclose(hid_t, swapped)
+
+
 # ----------------------------------------------------------------------------- pool model
 def mk_pool(n_chunks=6, n_layers=2, block=8192, small_blocks=2, reserve=1, row=256):
     small = small_blocks * block

@@ -96,6 +96,37 @@ def test_fits_and_predictions_match_the_oracle(seed, weak):
         assert abs(p.colo(i, f, 8, 1153) - want) <= 1e-8 * abs(want)
 
 
+@pytest.mark.parametrize("weak", [False, True])
+def test_eq2_as_printed_is_one_plain_fit_without_a_floor(weak):
+    """Sec. 5.2.1 Eq. 2 as the paper prints it: with the floor switched off the library's fit is the ordinary
+    least-squares solution over every sample and its predictions may fall below the solo latency."""
+    n_levels = 10
+    solo, colo = synth_profile(3, n_levels, 0.004 if weak else 0.02, weak)
+    p, o_solo, o_floor = build_both(3, noise=0.004 if weak else 0.02, weak=weak)
+    p.set_colo_floor(False)
+    with pytest.raises(hb.HarliError):             # the co-located fit was discarded with the reading
+        p.colo_coef()
+    p.fit()
+    samples = [(i / n_levels, f / n_levels, lc, ls) for i, f, lc, ls in colo]
+    o_plain = S.fit_colo(samples, floor=False)
+    X = np.array([[a * ls, b * ls] for a, b, _, ls in samples])
+    y = np.array([lc for _, _, lc, _ in samples])
+    normal = np.linalg.solve(X.T @ X, X.T @ y)     # the normal equations, written out
+    assert np.allclose(o_plain, normal, rtol=1e-9)
+    assert np.allclose(p.colo_coef(), o_plain, rtol=1e-8)
+    below = 0
+    for i, f in S.pairs(n_levels):
+        base = S.predict_solo(o_solo[i - 1], 8, 1153)
+        want = S.predict_colo(o_plain, i / 10, f / 10, base, floor=False)
+        assert abs(want - (i / 10 * o_plain[0] + f / 10 * o_plain[1]) * base) <= 1e-12 * abs(want)
+        assert abs(p.colo(i, f, 8, 1153) - want) <= 1e-8 * abs(want)
+        below += want < base
+    assert below > 0                               # e.g. 1/10 + 1/10: the printed form predicts a speed-up there
+    p.set_colo_floor(True)
+    p.fit()
+    assert np.allclose(p.colo_coef(), o_floor, rtol=1e-8)
+
+
 @pytest.mark.parametrize("seed", [0, 1, 2, 3])
 def test_chosen_plans_equal_the_oracles(seed):
     p, o_solo, o_colo = build_both(seed)

@@ -6,9 +6,11 @@ import pytest
 import torch
 
 import workloads as wl
+from oracle import harli_oracle as O
 from paper_2511_11729_amd import binding as hb
 from paper_2511_11729_amd import colocate
 from paper_2511_11729_amd.harness import LayerHarness
+from tests.gpu_util import assert_close, shapes_of
 
 pytestmark = pytest.mark.gpu
 
@@ -40,9 +42,12 @@ def test_decode_on_a_quarter_of_the_chip_matches_the_full_chip(hz):
     part.synchronize()
     hz.ctx.check(part)
     got = hz.y_dev[: hz.B]
-    # same kernels, same inputs; only the order of the fp32 atomic sums of squares may differ, which can flip the
-    # bf16 rounding of a few operand elements downstream
-    assert float((got - want).abs().max()) <= 2e-3 * float(want.abs().max())
+    # same kernels, same inputs, no arithmetic that depends on how many workgroups run at a time: the same bits,
+    # and the oracle's result at the bf16 bar in this launch configuration too
+    assert torch.equal(got, want)
+    x_np, _, kv_np = wl.make_decode_inputs(hz.w)
+    yo, _ = O.decode_layer_contiguous(x_np, hz.W_np, shapes_of(hz.m), kv_np[0])
+    assert_close(got.cpu().numpy(), yo, "decode on 3/10 of the compute units")
     t_full = colocate.time_decode(hz, full, None, None, None, 10)
     t_part = colocate.time_decode(hz, part, None, None, None, 10)
     assert t_part > 1.3 * t_full                       # the restriction is real
