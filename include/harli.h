@@ -223,6 +223,24 @@ typedef struct {
 
 harli_status harli_decode_step(harli_ctx* c, const harli_decode_batch* b, void* hip_stream);
 
+/* The same step for callers that cannot allocate device memory or rely on memory allocated for them: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and the
+ * same results as harli_decode_step, but every intermediate buffer of the step (GEMM operands, q, attention
+ * partials, row norms, rotary table, argmax partials) lives in one array of HARLI_STATIC_SCRATCH_BYTES that is part
+ * of the library's device image (each GPU the library runs on holds its copy until the process ends) instead of
+ * the workspace harli_ctx_create allocated.  The call itself allocates and frees nothing, on the host side of the
+ * device or through any library.  bf16 storage only.
+ *   - harli_decode_step_static_bytes(c, batch, max_kv_len) is what a step of that batch and length bound needs
+ *     (host arithmetic; 0 for bad arguments).  A step that needs more than HARLI_STATIC_SCRATCH_BYTES is refused
+ *     with HARLI_ERR_INVALID before anything is enqueued; every other check is harli_decode_step's.
+ *   - Every call on a GPU uses that GPU's one array and finds what the last call left in it; the step clears what
+ *     must start at zero with a kernel of its own (no memset node, so the call can be captured).  Two calls that
+ *     overlap in time on one GPU -- two streams, two contexts, two threads -- race on the array: keep them in
+ *     stream order.  harli_decode_step does not touch the array and may run beside it. */
+#define HARLI_STATIC_SCRATCH_BYTES (64u << 20)
+harli_status harli_decode_step_static(harli_ctx* c, const harli_decode_batch* b, void* hip_stream);
+size_t harli_decode_step_static_bytes(const harli_ctx* c, int32_t batch, int32_t max_kv_len);
+
 /* ======================================================================== *
  * Finetune unit (Sec. 6.1): one transformer layer x one micro-batch.
  * ======================================================================== */

@@ -95,6 +95,8 @@ _SIGS = {
     "harli_ctx_check": (C.c_int, [C.c_void_p, C.c_void_p]),
     "harli_lora_attach": (C.c_int, [C.c_void_p, C.POINTER(LoraCfg), C.POINTER(C.c_void_p), C.POINTER(C.c_void_p)]),
     "harli_decode_step": (C.c_int, [C.c_void_p, C.POINTER(DecodeBatch), C.c_void_p]),
+    "harli_decode_step_static": (C.c_int, [C.c_void_p, C.POINTER(DecodeBatch), C.c_void_p]),
+    "harli_decode_step_static_bytes": (C.c_size_t, [C.c_void_p, C.c_int32, C.c_int32]),
     "harli_lora_fwd": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
                                  C.POINTER(C.c_void_p), C.c_void_p]),
     "harli_lora_bwd": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -338,6 +340,16 @@ class Context:
         b = DecodeBatch(batch, _ptr(token_ids), _ptr(x_in), _ptr(x_out), _ptr(logits), _ptr(next_token), _ptr(kv_len),
                         _ptr(page_table), max_pages, max_kv_len)
         _check(lib().harli_decode_step(self.handle, C.byref(b), _stream(stream)))
+
+    def decode_step_static(self, *, batch, kv_len, page_table, max_pages, max_kv_len, token_ids=None, x_in=None, x_out=None,
+                           logits=None, next_token=None, stream=None) -> None:
+        """harli_decode_step on the library's static scratch array: the call allocates nothing."""
+        b = DecodeBatch(batch, _ptr(token_ids), _ptr(x_in), _ptr(x_out), _ptr(logits), _ptr(next_token), _ptr(kv_len),
+                        _ptr(page_table), max_pages, max_kv_len)
+        _check(lib().harli_decode_step_static(self.handle, C.byref(b), _stream(stream)))
+
+    def decode_step_static_bytes(self, batch: int, max_kv_len: int) -> int:
+        return int(lib().harli_decode_step_static_bytes(self.handle, batch, max_kv_len))
 
     def lora_fwd(self, layer: int, X, Y, B_f: int, S: int, stream=None) -> int:
         saved = C.c_void_p()

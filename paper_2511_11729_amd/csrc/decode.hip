@@ -23,6 +23,8 @@
 // instruction) were measured at 3.6 TB/s against 5.0 TB/s for this layout.
 // A workgroup is TW tiles x KW waves; the KW waves split K and reduce through
 // LDS, so epilogues see complete sums.
+#include <mutex>
+
 #include "ctx.h"
 #include "device_utils.h"
 
@@ -915,6 +917,40 @@ harli_status decode_step_bf16(harli_ctx* c, const harli_decode_batch* b, hipStre
   return HARLI_OK;
 }
 
+// ---------------------------------------------------------------------------------------------
+// Static scratch of harli_decode_step_static: the step's intermediate buffers for callers that may not allocate.
+// One copy of the array exists on every device the library is loaded on, at that device's own address; host code
+// never uses the array's name as an address, only the pointer hipGetSymbolAddress returned for the device.
+// ---------------------------------------------------------------------------------------------
+constexpr size_t kStaticScratchBytes = HARLI_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mu;
+
+// device address of `scratch` on the current device (looked up once per device)
+harli_status static_scratch(unsigned char** out) {
+  int dev = -1;
+  HARLI_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail(HARLI_ERR_INVALID, "decode_step_static: device ordinal %d outside 0..%d", dev, kMaxDevices - 1);
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    HARLI_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return fail(HARLI_ERR_HIP, "decode_step_static: the scratch symbol has no address on device %d", dev);
+    g_scratch_ptr[dev] = p;
+  }
+  *out = static_cast<unsigned char*>(g_scratch_ptr[dev]);
+  return HARLI_OK;
+}
+
+// 16-byte fill (a kernel rather than a memset call, so that the step stays capturable in a HIP graph)
+__global__ void __launch_bounds__(256) k_zero16(uint4* p, size_t n16) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n16) p[i] = make_uint4(0, 0, 0, 0);
+}
+
 }  // namespace
 
 extern "C" harli_status harli_decode_step(harli_ctx* c, const harli_decode_batch* b, void* hip_stream) {
@@ -923,4 +959,72 @@ extern "C" harli_status harli_decode_step(harli_ctx* c, const harli_decode_batch
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   if (c->cfg.dtype == HARLI_F32) return decode_step_f32(c, b, st);
   return decode_step_bf16(c, b, st, c->dw);
+}
+
+extern "C" size_t harli_decode_step_static_bytes(const harli_ctx* c, int32_t batch, int32_t max_kv_len) {
+  if (!c || batch < 1 || max_kv_len < 1) return 0;
+  const harli_model_cfg& m = c->cfg;
+  auto al = [](size_t n) { return (n + 255) & ~size_t(255); };
+  auto r32 = [](size_t n) { return (n + 31) & ~size_t(31); };
+  const size_t bp = (size_t)(batch + 15) / 16 * 16, H = m.hidden, QD = (size_t)m.n_q_heads * m.head_dim, F = m.ffn;
+  const size_t chunks = ((size_t)max_kv_len + 127) / 128;
+  size_t n = al(bp * r32(H) * 2) * 2 + al(bp * r32(QD) * 2) + al(bp * r32(F) * 2);       // GEMM operands
+  n += al(bp * QD * 4) + 3 * al(bp * H * 4);                                             // q, x1, xa, xb
+  n += al(bp * (2 * (size_t)m.n_layers + 1) * 16) + al(bp * m.head_dim * 4);             // row norms, rotary table
+  n += al(bp * m.n_q_heads * chunks * ((size_t)m.head_dim + 2) * 4);                     // attention partials
+  n += 2 * al(bp * 64 * 4);                                                              // argmax partials
+  return n;
+}
+
+extern "C" harli_status harli_decode_step_static(harli_ctx* c, const harli_decode_batch* b, void* hip_stream) {
+  harli_status s = check_decode_args(c, b);
+  if (s != HARLI_OK) return s;
+  const harli_model_cfg& m = c->cfg;
+  if (m.dtype != HARLI_BF16) return fail(HARLI_ERR_INVALID, "decode_step_static: bf16 storage only");
+  const size_t need = harli_decode_step_static_bytes(c, b->batch, b->max_kv_len);
+  if (need > kStaticScratchBytes)
+    return fail(HARLI_ERR_INVALID, "decode_step_static: batch %d with max_kv_len %d needs %zu bytes of scratch, the static buffer holds %zu",
+                b->batch, b->max_kv_len, need, kStaticScratchBytes);
+  unsigned char* base = nullptr;
+  s = static_scratch(&base);
+  if (s != HARLI_OK) return s;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  // the same layout harli_decode_step_static_bytes adds up, sized by this call's batch and length bound
+  auto al = [](size_t n) { return (n + 255) & ~size_t(255); };
+  auto r32 = [](size_t n) { return (n + 31) & ~size_t(31); };
+  const size_t bp = (size_t)(b->batch + 15) / 16 * 16, H = m.hidden, QD = (size_t)m.n_q_heads * m.head_dim, F = m.ffn;
+  const size_t chunks = ((size_t)b->max_kv_len + 127) / 128;
+  size_t off = 0;
+  auto take = [&](size_t n) {
+    unsigned char* p = base + off;
+    off += al(n);
+    return p;
+  };
+  DecodeWs w;
+  w.bpad = (int)bp;
+  w.max_chunks = (int)chunks;
+  w.hx1 = take(bp * r32(H) * 2);
+  w.hx2 = take(bp * r32(H) * 2);
+  w.obuf = take(bp * r32(QD) * 2);
+  w.mbuf = take(bp * r32(F) * 2);
+  const size_t operand_bytes = off;
+  w.qbuf = reinterpret_cast<float*>(take(bp * QD * 4));
+  w.x1 = reinterpret_cast<float*>(take(bp * H * 4));
+  w.xa = reinterpret_cast<float*>(take(bp * H * 4));
+  w.xb = reinterpret_cast<float*>(take(bp * H * 4));
+  w.ssq = reinterpret_cast<unsigned long long*>(take(bp * (2 * (size_t)m.n_layers + 1) * 16));
+  w.rope = reinterpret_cast<float*>(take(bp * m.head_dim * 4));
+  w.att_part = reinterpret_cast<float*>(take(bp * m.n_q_heads * chunks * ((size_t)m.head_dim + 2) * 4));
+  w.amax_v = reinterpret_cast<float*>(take(bp * 64 * 4));
+  w.amax_i = reinterpret_cast<int*>(take(bp * 64 * 4));
+  w.inv_freq = c->dw.inv_freq;  // constants and the error flag made in harli_ctx_create
+  w.err_flag = c->dw.err_flag;
+  if (off != need) return fail(HARLI_ERR_STATE, "decode_step_static: layout of %zu bytes against %zu counted", off, need);
+  // The array keeps what the last call (of any shape) left.  The GEMM operands must start at zero: contraction
+  // positions past K (up to the next multiple of 32) are multiplied with the zero padding of the weights, and stale
+  // bits there may read as NaN.  Everything else is written before it is read (the row-norm counters are cleared by
+  // the step's first kernel; batch rows past `batch` only reach output columns that are never stored).
+  const size_t n16 = operand_bytes / 16;
+  hipLaunchKernelGGL(k_zero16, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, st, reinterpret_cast<uint4*>(base), n16);
+  return decode_step_bf16(c, b, st, w);
 }
