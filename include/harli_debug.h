@@ -31,6 +31,44 @@ harli_status harli_dbg_gemm(const void* A1, const void* B1, int32_t K1, const vo
 harli_status harli_dbg_gemm_clock(const void* A, const void* B, int32_t M, int32_t N, int32_t K, int32_t half, void* Cb,
                                   int32_t reps, double* tflops, double* shader_mhz, void* hip_stream);
 
+/* The weight GEMM of the finetune unit (256-wide tiles, weight side in blocked order) on its own.  The descriptor
+ * mirrors the kernel's arguments; weight-side operands are given ROW-MAJOR here ([rows, K], the contraction index
+ * contiguous, 16-bit elements of the type `half` selects) and the hook makes their blocked copies itself (it allocates
+ * device memory for them, synchronises the stream and frees them before it returns).
+ *   C = alpha * sum_s A_s . B_s^T (+ res).  Segment s contributes to the output column tiles [tile0, tile1) (256
+ *   columns per tile; 128 + 128 interleaved in 32-column groups when `pair` is set: B_s and B2_s are then the two
+ *   matrices of the pair and either may be NULL) and its weight rows start at the first column of tile0.  Output block
+ *   o starts at tile out_tile0[o] and has out_n[o] valid columns; all blocks are 16-bit (cb) or all fp32 (cf, optional
+ *   res).  epi 0: plain; 2: SwiGLU backward (cf/cb unused: o0 = da, o1 = du from e0 = a, e1 = u); 3: gate/up pair
+ *   (cb[0] = a, o1 = u, o0 = silu(a) * u).  tile_rows 128 or 256 fixes the tile height, 0 leaves the choice to the
+ *   library.  reps > 1 repeats the launch and writes TFLOP/s over HIP events and the shader clock of the last launch
+ *   to the host pointers (either may be NULL). */
+typedef struct {
+  int32_t M, nseg, nout, tiles_n, half, epi, tile_rows, reps;
+  float alpha;
+  const void* A[12];
+  int64_t lda[12];
+  int32_t K[12];
+  const void* B[12];
+  int32_t b_rows[12];
+  const void* B2[12];
+  int32_t b2_rows[12];
+  int32_t tile0[12], tile1[12], pair[12];
+  int32_t out_tile0[3], out_n[3];
+  void* cb[3];
+  int64_t ldcb[3];
+  float* cf[3];
+  const float* res[3];
+  int64_t ldcf[3];
+  const void *e0, *e1;
+  void *o0, *o1;
+  int64_t lde;
+  int32_t* overflow_flag;
+  double* tflops;
+  double* shader_mhz;
+} harli_dbg_gemm2_desc;
+harli_status harli_dbg_gemm2(const harli_dbg_gemm2_desc* d, void* hip_stream);
+
 /* The residency plan of harli_ft_window_* on its own (host logic only, no device needed): a window of n_slots over the
  * 2 * n_layers cyclic items, prefilled with items 0..n_slots-1, is driven through `items[0..n_access)`; for every
  * access the slot that served it, the item loaded on demand (-1 on a hit) and the item loaded into the slot

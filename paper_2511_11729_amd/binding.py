@@ -143,6 +143,7 @@ _SIGS = {
                                         C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
     "harli_dbg_gemm_clock": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_int32,
                                        C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_void_p]),
+    "harli_dbg_gemm2": (C.c_int, [C.c_void_p, C.c_void_p]),
     "harli_dbg_gemm": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
                                  C.c_float, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
 }
@@ -518,6 +519,57 @@ def dbg_gemm(A1, B1, *, A2=None, B2=None, alpha=1.0, causal=0, half=False, Cb=No
     K2 = A2.shape[1] if A2 is not None else 0
     _check(lib().harli_dbg_gemm(_ptr(A1), _ptr(B1), K1, _ptr(A2), _ptr(B2), K2, M, N, alpha, causal, int(half), _ptr(Cb), _ptr(Cf),
                                 _ptr(res), _ptr(Ct), _stream(stream)))
+
+
+class DbgGemm2Desc(C.Structure):
+    _fields_ = [("M", C.c_int32), ("nseg", C.c_int32), ("nout", C.c_int32), ("tiles_n", C.c_int32), ("half", C.c_int32),
+                ("epi", C.c_int32), ("tile_rows", C.c_int32), ("reps", C.c_int32), ("alpha", C.c_float),
+                ("A", C.c_void_p * 12), ("lda", C.c_int64 * 12), ("K", C.c_int32 * 12), ("B", C.c_void_p * 12),
+                ("b_rows", C.c_int32 * 12), ("B2", C.c_void_p * 12), ("b2_rows", C.c_int32 * 12), ("tile0", C.c_int32 * 12),
+                ("tile1", C.c_int32 * 12), ("pair", C.c_int32 * 12), ("out_tile0", C.c_int32 * 3), ("out_n", C.c_int32 * 3),
+                ("cb", C.c_void_p * 3), ("ldcb", C.c_int64 * 3), ("cf", C.c_void_p * 3), ("res", C.c_void_p * 3),
+                ("ldcf", C.c_int64 * 3), ("e0", C.c_void_p), ("e1", C.c_void_p), ("o0", C.c_void_p), ("o1", C.c_void_p),
+                ("lde", C.c_int64), ("overflow_flag", C.c_void_p), ("tflops", C.POINTER(C.c_double)),
+                ("shader_mhz", C.POINTER(C.c_double))]
+
+
+def dbg_gemm2(M, segs, outs, *, half=True, epi=0, alpha=1.0, tile_rows=0, reps=0, e0=None, e1=None, o0=None, o1=None, lde=0,
+              overflow_flag=None, stream=None):
+    """Test hook for the finetune unit's weight GEMM.  segs: dicts with A (device [M, K], 16-bit), optional lda,
+    B (device [rows, K] row-major weight side; the hook blocks it), optional B2 and pair, optional tile0 / tile1.
+    outs: dicts with N, tile0 and cb (16-bit) or cf (+ res), optional ld.  Tiles are 256 columns (128 + 128 for
+    pairs).  Returns (TFLOP/s, shader MHz) when reps > 1."""
+    d = DbgGemm2Desc()
+    d.M, d.nseg, d.nout, d.half, d.epi, d.tile_rows, d.reps, d.alpha = M, len(segs), len(outs), int(half), epi, tile_rows, reps, alpha
+    width = 128 if epi == 3 else 256
+    tiles = 0
+    for o, q in enumerate(outs):
+        d.out_tile0[o] = q.get("tile0", tiles)
+        d.out_n[o] = q["N"]
+        tiles = d.out_tile0[o] + -(-q["N"] // width)
+        if q.get("cb") is not None:
+            d.cb[o], d.ldcb[o] = _ptr(q["cb"]), q.get("ld", q["cb"].shape[1])
+        if q.get("cf") is not None:
+            d.cf[o], d.ldcf[o] = _ptr(q["cf"]), q.get("ld", q["cf"].shape[1])
+        if q.get("res") is not None:
+            d.res[o] = _ptr(q["res"])
+    d.tiles_n = tiles
+    for s, q in enumerate(segs):
+        A = q["A"]
+        d.A[s], d.lda[s], d.K[s] = _ptr(A), q.get("lda", A.shape[1]), q.get("K", A.shape[1])
+        if q.get("B") is not None:
+            d.B[s], d.b_rows[s] = _ptr(q["B"]), q["B"].shape[0]
+        if q.get("B2") is not None:
+            d.B2[s], d.b2_rows[s] = _ptr(q["B2"]), q["B2"].shape[0]
+        d.pair[s] = int(q.get("pair", 0))
+        d.tile0[s], d.tile1[s] = q.get("tile0", 0), q.get("tile1", tiles)
+    d.e0, d.e1, d.o0, d.o1, d.lde = _ptr(e0), _ptr(e1), _ptr(o0), _ptr(o1), lde
+    d.overflow_flag = _ptr(overflow_flag)
+    t, f = C.c_double(0.0), C.c_double(0.0)
+    if reps > 1:
+        d.tflops, d.shader_mhz = C.pointer(t), C.pointer(f)
+    _check(lib().harli_dbg_gemm2(C.byref(d), _stream(stream)))
+    return t.value, f.value
 
 
 class WindowStats(C.Structure):

@@ -19,6 +19,7 @@
 #include "ft_attention.h"
 #include "ft_kernels.h"
 #include "gemm.h"
+#include "gemm2.h"
 #include "window.h"
 
 using namespace harli;
@@ -99,9 +100,10 @@ harli_status ensure_ws(harli_ctx* c, int Bf, int S) {
   const size_t o_delta = take((size_t)D.Z * S * 4);
   const size_t o_dh2 = take(T * D.H * 4), o_dx1 = take(T * D.H * 4), o_dh = take(T * D.H * 4);
   const size_t o_vT = take(T * D.KVD * 2), o_kT = take(T * D.KVD * 2), o_qT = take(T * D.QD * 2), o_doT = take(T * D.QD * 2);
-  const size_t ad = al(maxdim * D.r * 2);  // one adapter matrix in the compute element
-  const size_t o_At = take(kTargets * ad), o_Bt = take(kTargets * ad);
-  const size_t o_An = take(kTargets * ad), o_Bn = take(kTargets * ad), o_scale = take(64);
+  const size_t ad = al(maxdim * D.r * 2);  // one adapter matrix in the compute element, row-major (skinny products)
+  const size_t adb = al(blocked_elems((long long)maxdim, D.r) * 2);  // ... in the weight GEMM's blocked order
+  const size_t o_At = take(kTargets * ad), o_Bt = take(kTargets * adb);
+  const size_t o_An = take(kTargets * adb), o_Bn = take(kTargets * ad), o_scale = take(64);
   const size_t o_dyb = take(T * D.H * 2), o_da = take(T * D.F * 2), o_du = take(T * D.F * 2), o_dx1b = take(T * D.H * 2);
   const size_t o_dob = take(T * D.QD * 2), o_dq = take(T * D.QD * 2), o_dkq = take(T * D.QD * 2), o_dvq = take(T * D.QD * 2);
   const size_t o_dk = take(T * D.KVD * 2), o_dv = take(T * D.KVD * 2), o_gs = take(3 * al(T * D.r * 2));
@@ -124,8 +126,8 @@ harli_status ensure_ws(harli_ctx* c, int Bf, int S) {
   for (int i = 0; i < 3; ++i) w.gs[i] = (bf*)(b + o_gs + i * al(T * D.r * 2));
   w.gpart = (float*)(b + o_gpart);
   for (int i = 0; i < kTargets; ++i) {
-    w.At[i] = (bf*)(b + o_At + i * ad); w.Bt[i] = (bf*)(b + o_Bt + i * ad);
-    w.An[i] = (bf*)(b + o_An + i * ad); w.Bn[i] = (bf*)(b + o_Bn + i * ad);
+    w.At[i] = (bf*)(b + o_At + i * ad); w.Bt[i] = (bf*)(b + o_Bt + i * adb);
+    w.An[i] = (bf*)(b + o_An + i * adb); w.Bn[i] = (bf*)(b + o_Bn + i * ad);
   }
   w.scale = (float*)(b + o_scale);
   w.Bf = Bf;
@@ -156,21 +158,30 @@ void add_seg(GemmArgs& g, const bf* A, long long lda, const bf* B, long long ldb
   s.ldb = ldb;
 }
 
-// Every adapted projection's A and B (bf16 storage, contents may change between calls) converted to the compute
-// element in ONE launch: transposed copies for the forward pass, natural ones for the backward pass.
-void convert_adapters(harli_ctx* c, const LayerDev& L, bool transposed, hipStream_t st) {
+// Every adapted projection's A and B (storage type, contents may change between calls) converted to the compute
+// element in two launches.  Forward: A^T [r, in] row-major for the skinny product s x A, and B^T as the weight GEMM's
+// blocked operand [out rows, r].  Backward: B [r, out] row-major for s dy B^T, and A as the blocked operand [in rows, r].
+void convert_adapters(harli_ctx* c, const LayerDev& L, bool forward, hipStream_t st) {
   FtWs& w = state(c)->ws;
   FtConvJobs jobs{};
+  BlockJobs blk{};
+  blk.half = kFtHalf ? 1 : 0;
   for (int t = 0; t < kTargets; ++t) {
     if (!adapted(c, t)) continue;
     int out, in;
     proj_shape(c->cfg, t, &out, &in);
     const int r = c->lora.rank;
     const int f32 = c->cfg.dtype == HARLI_F32 ? 1 : 0;
-    jobs.j[jobs.n++] = FtConvJob{L.A[t], transposed ? w.At[t] : w.An[t], in, r, transposed ? 1 : 0, f32};
-    jobs.j[jobs.n++] = FtConvJob{L.B[t], transposed ? w.Bt[t] : w.Bn[t], r, out, transposed ? 1 : 0, f32};
+    if (forward) {
+      jobs.j[jobs.n++] = FtConvJob{L.A[t], w.At[t], in, r, 1, f32};
+      blk.j[blk.n++] = BlockJob{L.B[t], w.Bt[t], r, out, 1, f32};  // operand [n = out][k = r] = B[k][n]
+    } else {
+      blk.j[blk.n++] = BlockJob{L.A[t], w.An[t], in, r, 0, f32};   // operand [n = in][k = r] = A[n][k]
+      jobs.j[jobs.n++] = FtConvJob{L.B[t], w.Bn[t], r, out, 0, f32};
+    }
   }
   if (jobs.n) ft_convert_jobs(jobs, st);
+  gemm2_block_jobs(blk, st);
 }
 
 // forward of one projection: out = xin . W^T (+ us . Bt^T), us = s * xin . A kept for backward
@@ -189,20 +200,48 @@ void proj_us_group(harli_ctx* c, int t_first, int t_last, const bf* xin, int T, 
   ft_skinny_nt_multi(jobs, T, lscale(c), st);
 }
 
-// (us_t must have been made by proj_us_group)
-harli_status proj_fwd(harli_ctx* c, const LayerDev& L, int t, const bf* xin, int T, harli_saved* sv, GemmArgs& g, hipStream_t st) {
+// ---- the weight GEMMs (gemm2.h) ----
+inline int tiles256(int n) { return (n + kG2TileN - 1) / kG2TileN; }
+Gemm2Args wg_begin(const harli_ctx* c, int T) {
+  Gemm2Args g{};
+  g.M = T;
+  g.alpha = 1.f;
+  g.half = kFtHalf ? 1 : 0;
+  g.overflow_flag = c->dw.err_flag;
+  return g;
+}
+void wg_seg(Gemm2Args& g, const bf* A, long long lda, int K, const void* B, int rows, int t0, int t1, const void* B2 = nullptr, int pair = 0) {
+  Gemm2Seg& q = g.seg[g.nseg++];
+  q = Gemm2Seg{};
+  q.A = A;
+  q.lda = lda;
+  q.K = K;
+  q.B = static_cast<const unsigned short*>(B);
+  q.B2 = static_cast<const unsigned short*>(B2);
+  q.pair = pair;
+  q.rows = rows;
+  q.tile0 = t0;
+  q.tile1 = t1;
+}
+// one projection's segments over the output tiles [t0, t1): x W^T, the frozen bias (eight more contraction columns:
+// ones on the input side, (b, 0, ..., 0) on the weight side) and the adapter s (x A) B (us_t made by proj_us_group)
+void wg_proj(harli_ctx* c, Gemm2Args& g, const LayerDev& L, int t, const bf* xin, const harli_saved* sv, int t0, int t1) {
   int out, in;
   proj_shape(c->cfg, t, &out, &in);
   FtWs& w = state(c)->ws;
-  add_seg(g, xin, in, static_cast<const bf*>(L.w16[t]), in, in);
-  // a frozen bias rides as eight more contraction columns: ones on the input side, (b, 0, ..., 0) on the weight side
-  if (t < 3 && L.b16[t]) add_seg(g, static_cast<const bf*>(c->ones16), 8, static_cast<const bf*>(L.b16[t]), 8, 8);
-  if (adapted(c, t)) {
-    const int r = c->lora.rank;
-    // ws.Bt[t] = B^T [out, r] was made by convert_adapters at the top of the call
-    add_seg(g, sv->us[t], r, w.Bt[t], r, r);
-  }
-  return gemm_launch(g, 1, st);
+  wg_seg(g, xin, in, in, L.w16[t], out, t0, t1);
+  if (t < 3 && L.b16[t]) wg_seg(g, static_cast<const bf*>(c->ones16), 8, 8, L.b16[t], out, t0, t1);
+  if (adapted(c, t)) wg_seg(g, sv->us[t], c->lora.rank, c->lora.rank, w.Bt[t], out, t0, t1);
+}
+void wg_out_f32(Gemm2Args& g, float* Cf, const float* res, int N) {
+  g.nout = 1;
+  g.tiles_n = tiles256(N);
+  g.out[0] = Gemm2Out{0, N, nullptr, 0, Cf, res, N};
+}
+void wg_out_16(Gemm2Args& g, bf* Cb, int N) {
+  g.nout = 1;
+  g.tiles_n = tiles256(N);
+  g.out[0] = Gemm2Out{0, N, Cb, N, nullptr, nullptr, 0};
 }
 
 // adapter gradients of one projection given dy (bf16 [T, out]) and its input xin (bf16 [T, in]);
@@ -342,20 +381,18 @@ extern "C" harli_status harli_lora_attach(harli_ctx* c, const harli_lora_cfg* cf
       const bool on = (cfg->targets >> t) & 1u;
       L.A[t] = on ? A[l * kTargets + t] : nullptr;
       L.B[t] = on ? B[l * kTargets + t] : nullptr;
-      if (!L.wt[t]) {  // finetune-private copies of the frozen weights in the compute element:
-        int out, in;   // W [out, in] for the forward pass and WT [in, out] for dx = dy W
+      if (!L.wt[t]) {  // finetune-private copies of the frozen weights in the compute element, in the weight GEMM's
+        int out, in;   // blocked order: W as the operand [out rows, in] of the forward pass, W^T [in rows, out] for dx = dy W
         proj_shape(c->cfg, t, &out, &in);
-        HARLI_HIP(hipMalloc(&L.wt[t], (size_t)out * in * 2));
-        HARLI_HIP(hipMalloc(&L.w16[t], (size_t)out * in * 2));
-        if (c->cfg.dtype == HARLI_BF16) {
-          ft_transpose_from_bf16(static_cast<const bf*>(L.w[t]), static_cast<bf*>(L.wt[t]), out, in, nullptr);
-          ft_from_bf16(static_cast<const bf*>(L.w[t]), static_cast<bf*>(L.w16[t]), (long long)out * in, nullptr);
-        } else {  // fp32 storage: rounded once to the compute element
-          FtConvJobs jobs{};
-          jobs.j[jobs.n++] = FtConvJob{L.w[t], static_cast<bf*>(L.wt[t]), out, in, 1, 1};
-          jobs.j[jobs.n++] = FtConvJob{L.w[t], static_cast<bf*>(L.w16[t]), out, in, 0, 1};
-          ft_convert_jobs(jobs, nullptr);
-        }
+        const size_t nb = ft_weight_copy_bytes(out, in);
+        HARLI_HIP(hipMalloc(&L.wt[t], nb));
+        HARLI_HIP(hipMalloc(&L.w16[t], nb));
+        const int f32 = c->cfg.dtype == HARLI_F32 ? 1 : 0;
+        BlockJobs jobs{};
+        jobs.half = kFtHalf ? 1 : 0;
+        jobs.j[jobs.n++] = BlockJob{L.w[t], static_cast<bf*>(L.w16[t]), out, in, 0, f32};
+        jobs.j[jobs.n++] = BlockJob{L.w[t], static_cast<bf*>(L.wt[t]), out, in, 1, f32};
+        gemm2_block_jobs(jobs, nullptr);
       }
     }
   }
@@ -370,8 +407,9 @@ extern "C" harli_status harli_lora_attach(harli_ctx* c, const harli_lora_cfg* cf
       proj_shape(c->cfg, t, &out, &in);
       std::vector<float> hb(out);
       HARLI_HIP(hipMemcpy(hb.data(), L.bias[t], (size_t)out * 4, hipMemcpyDeviceToHost));
-      std::vector<unsigned short> h16((size_t)out * 8, 0);
-      for (int n = 0; n < out; ++n) h16[(size_t)n * 8] = host_to_elem(hb[n]);
+      // blocked operand [out rows, K = 8]: one K step per row tile, row n of a tile at 32 n, the bias in column 0
+      std::vector<unsigned short> h16(blocked_elems(out, 8), 0);
+      for (int n = 0; n < out; ++n) h16[(size_t)(n / kG2TileN) * (kG2TileN * kG2StepK) + (size_t)(n % kG2TileN) * kG2StepK] = host_to_elem(hb[n]);
       HARLI_HIP(hipMalloc(&L.b16[t], h16.size() * 2));
       HARLI_HIP(hipMemcpy(L.b16[t], h16.data(), h16.size() * 2, hipMemcpyHostToDevice));
     }
@@ -462,20 +500,19 @@ extern "C" harli_status harli_lora_fwd(harli_ctx* c, int32_t layer, const float*
   convert_adapters(c, L, true, st);
   ft_rmsnorm_fwd(X, L.g1, sv->h, sv->rho1, T, D.H, m.rms_eps, st);
   proj_us_group(c, 0, 2, sv->h, T, sv, st);
-  {
-    GemmArgs g = plain_gemm(T, D.QD);
-    g.Cb = sv->q; g.ldcb = D.QD;
-    RUN(proj_fwd(c, L, 0, sv->h, T, sv, g, st));
-  }
-  {
-    GemmArgs g = plain_gemm(T, D.KVD);
-    g.Cb = sv->k; g.ldcb = D.KVD;
-    RUN(proj_fwd(c, L, 1, sv->h, T, sv, g, st));
-  }
-  {
-    GemmArgs g = plain_gemm(T, D.KVD);
-    g.Cb = sv->v; g.ldcb = D.KVD;
-    RUN(proj_fwd(c, L, 2, sv->h, T, sv, g, st));
+  {  // q, k, v in one launch: three column blocks, each with its own weights, bias and adapter segments
+    Gemm2Args g = wg_begin(c, T);
+    const int tq = tiles256(D.QD), tk = tiles256(D.KVD);
+    const int t0[3] = {0, tq, tq + tk}, ns[3] = {D.QD, D.KVD, D.KVD};
+    bf* dst[3] = {sv->q, sv->k, sv->v};
+    for (int t = 0; t < 3; ++t) {
+      const int t1 = t0[t] + (t == 0 ? tq : tk);
+      wg_proj(c, g, L, t, sv->h, sv, t0[t], t1);
+      g.out[t] = Gemm2Out{t0[t], ns[t], dst[t], ns[t], nullptr, nullptr, 0};
+    }
+    g.nout = 3;
+    g.tiles_n = tq + 2 * tk;
+    RUN(gemm2_launch(g, st));
   }
   ft_rope(sv->q, T, S, D.nq, D.d, c->dw.inv_freq, false, st);
   ft_rope(sv->k, T, S, D.nkv, D.d, c->dw.inv_freq, false, st);
@@ -511,29 +548,36 @@ extern "C" harli_status harli_lora_fwd(harli_ctx* c, int32_t layer, const float*
     }
   }
   {  // x1 = X + o Wo^T
-    GemmArgs g = plain_gemm(T, D.H);
-    g.Cf = sv->x1; g.ldcf = D.H; g.res = X;
     proj_us_group(c, 3, 3, sv->o, T, sv, st);
-    RUN(proj_fwd(c, L, 3, sv->o, T, sv, g, st));
+    Gemm2Args g = wg_begin(c, T);
+    wg_proj(c, g, L, 3, sv->o, sv, 0, tiles256(D.H));
+    wg_out_f32(g, sv->x1, X, D.H);
+    RUN(gemm2_launch(g, st));
   }
   ft_rmsnorm_fwd(sv->x1, L.g2, sv->h2, sv->rho2, T, D.H, m.rms_eps, st);
   proj_us_group(c, 4, 5, sv->h2, T, sv, st);
-  {
-    GemmArgs g = plain_gemm(T, D.F);
-    g.Cb = sv->a; g.ldcb = D.F;
-    RUN(proj_fwd(c, L, 4, sv->h2, T, sv, g, st));
-  }
-  {  // u = up projection; its epilogue also writes m = silu(a) * u
-    GemmArgs g = plain_gemm(T, D.F);
-    g.Cb = sv->u; g.ldcb = D.F;
-    g.epi = GEMM_EPI_SILU_MUL; g.e0 = sv->a; g.o0 = sv->m; g.lde = D.F;
-    RUN(proj_fwd(c, L, 5, sv->h2, T, sv, g, st));
+  {  // gate and up as one launch of interleaved pairs; the epilogue writes a, u and m = silu(a) * u
+    Gemm2Args g = wg_begin(c, T);
+    const int tp = (D.F + 127) / 128;  // a tile holds 128 gate + 128 up columns
+    wg_seg(g, sv->h2, D.H, D.H, L.w16[4], D.F, 0, tp, L.w16[5], 1);
+    const int r = c->lora.rank;
+    if (adapted(c, 4)) wg_seg(g, sv->us[4], r, r, w.Bt[4], D.F, 0, tp, nullptr, 1);
+    if (adapted(c, 5)) wg_seg(g, sv->us[5], r, r, nullptr, D.F, 0, tp, w.Bt[5], 1);
+    g.epi = GEMM2_EPI_GATEUP;
+    g.nout = 1;
+    g.tiles_n = tp;
+    g.out[0] = Gemm2Out{0, D.F, sv->a, D.F, nullptr, nullptr, 0};
+    g.o1 = sv->u;
+    g.o0 = sv->m;
+    g.lde = D.F;
+    RUN(gemm2_launch(g, st));
   }
   {  // Y = x1 + m Wd^T
-    GemmArgs g = plain_gemm(T, D.H);
-    g.Cf = Y; g.ldcf = D.H; g.res = sv->x1;
     proj_us_group(c, 6, 6, sv->m, T, sv, st);
-    RUN(proj_fwd(c, L, 6, sv->m, T, sv, g, st));
+    Gemm2Args g = wg_begin(c, T);
+    wg_proj(c, g, L, 6, sv->m, sv, 0, tiles256(D.H));
+    wg_out_f32(g, Y, sv->x1, D.H);
+    RUN(gemm2_launch(g, st));
   }
   if (hipGetLastError() != hipSuccess) {
     release_saved(c, sv, st, true);
@@ -581,43 +625,51 @@ extern "C" harli_status harli_lora_bwd(harli_ctx* c, int32_t layer, const float*
   convert_adapters(c, L, false, st);
   ft_make_scale(dY, (long long)T * D.H, w.scale, st);
   ft_f32_to_e(dY, w.dyb, (long long)T * D.H, w.scale, st);  // every gradient below carries the factor sigma
-  {
-    GemmArgs g = plain_gemm(T, D.F);  // dm = dy Wd (+ gs A_d^T) -> da, du
-    add_seg(g, w.dyb, D.H, static_cast<const bf*>(L.wt[6]), D.H, D.H);
+  const int r = c->lora.rank;
+  {  // dm = dy Wd (+ gs A_d^T) -> da, du
+    Gemm2Args g = wg_begin(c, T);
+    const int tf = tiles256(D.F);
+    wg_seg(g, w.dyb, D.H, D.H, L.wt[6], D.F, 0, tf);
     if (adapted(c, 6)) {
       RUNB(proj_grads(c, L, 6, 0, w.dyb, sv->m, T, sv, dA, dB, st));
-      add_seg(g, w.gs[0], D.r, w.An[6], D.r, D.r);
+      wg_seg(g, w.gs[0], r, r, w.An[6], D.F, 0, tf);
     }
     // the epilogue turns dm straight into da and du (SwiGLU backward); dm itself is never stored
-    g.epi = GEMM_EPI_SWIGLU_BWD; g.e0 = sv->a; g.e1 = sv->u; g.o0 = w.da; g.o1 = w.du; g.lde = D.F;
-    RUNB(gemm_launch(g, 1, st));
+    g.epi = GEMM2_EPI_SWIGLU_BWD;
+    g.e0 = sv->a; g.e1 = sv->u; g.o0 = w.da; g.o1 = w.du; g.lde = D.F;
+    g.nout = 1;
+    g.tiles_n = tf;
+    g.out[0] = Gemm2Out{0, D.F, nullptr, 0, nullptr, nullptr, 0};
+    RUNB(gemm2_launch(g, st));
   }
-  {
-    GemmArgs g = plain_gemm(T, D.H);  // dh2 = da Wg + du Wu
-    add_seg(g, w.da, D.F, static_cast<const bf*>(L.wt[4]), D.F, D.F);
-    add_seg(g, w.du, D.F, static_cast<const bf*>(L.wt[5]), D.F, D.F);
+  {  // dh2 = da Wg + du Wu
+    Gemm2Args g = wg_begin(c, T);
+    const int th = tiles256(D.H);
+    wg_seg(g, w.da, D.F, D.F, L.wt[4], D.H, 0, th);
+    wg_seg(g, w.du, D.F, D.F, L.wt[5], D.H, 0, th);
     {
       int ts[2], slots[2], n = 0;
       const bf* dys[2];
       for (int t = 4; t <= 5; ++t)
         if (adapted(c, t)) ts[n] = t, slots[n] = t - 4, dys[n] = t == 4 ? w.da : w.du, ++n;
       if (n) RUNB(proj_grads_group(c, n, ts, slots, dys, sv->h2, T, sv, dA, dB, st));
-      for (int i = 0; i < n; ++i) add_seg(g, w.gs[slots[i]], D.r, w.An[ts[i]], D.r, D.r);  // dh2 += gs_t A_t^T as one more K segment
+      for (int i = 0; i < n; ++i) wg_seg(g, w.gs[slots[i]], r, r, w.An[ts[i]], D.H, 0, th);  // dh2 += gs_t A_t^T as one more K segment
     }
-    g.Cf = w.dh2; g.ldcf = D.H;
-    RUNB(gemm_launch(g, 1, st));
+    wg_out_f32(g, w.dh2, nullptr, D.H);
+    RUNB(gemm2_launch(g, st));
   }
   ft_rmsnorm_bwd(w.dh2, sv->x1, sv->rho2, L.g2, dY, w.dx1, w.dx1b, T, D.H, w.scale, nullptr, st);
   // ---- attention output projection ----
-  {
-    GemmArgs g = plain_gemm(T, D.QD);  // do = dx1 Wo
-    add_seg(g, w.dx1b, D.H, static_cast<const bf*>(L.wt[3]), D.H, D.H);
+  {  // do = dx1 Wo
+    Gemm2Args g = wg_begin(c, T);
+    const int tq = tiles256(D.QD);
+    wg_seg(g, w.dx1b, D.H, D.H, L.wt[3], D.QD, 0, tq);
     if (adapted(c, 3)) {
       RUNB(proj_grads(c, L, 3, 0, w.dx1b, sv->o, T, sv, dA, dB, st));
-      add_seg(g, w.gs[0], D.r, w.An[3], D.r, D.r);
+      wg_seg(g, w.gs[0], r, r, w.An[3], D.QD, 0, tq);
     }
-    g.Cb = w.dob; g.ldcb = D.QD;
-    RUNB(gemm_launch(g, 1, st));
+    wg_out_16(g, w.dob, D.QD);
+    RUNB(gemm2_launch(g, st));
   }
   // ---- attention ----
   if (!ft_attn_supported(D.d)) ft_attn_delta(w.dob, sv->o, w.delta, B_f, S, D.nq, D.d, st);  // the fused dQ kernel makes its own
@@ -714,11 +766,12 @@ extern "C" harli_status harli_lora_bwd(harli_ctx* c, int32_t layer, const float*
   ft_rope(w.dq, T, S, D.nq, D.d, c->dw.inv_freq, true, st);
   ft_rope(const_cast<bf*>(dk), T, S, D.nkv, D.d, c->dw.inv_freq, true, st);
   // ---- q, k, v projections ----
-  {
-    GemmArgs g = plain_gemm(T, D.H);  // dh = dq Wq + dk Wk + dv Wv
-    add_seg(g, w.dq, D.QD, static_cast<const bf*>(L.wt[0]), D.QD, D.QD);
-    add_seg(g, dk, D.KVD, static_cast<const bf*>(L.wt[1]), D.KVD, D.KVD);
-    add_seg(g, dv, D.KVD, static_cast<const bf*>(L.wt[2]), D.KVD, D.KVD);
+  {  // dh = dq Wq + dk Wk + dv Wv
+    Gemm2Args g = wg_begin(c, T);
+    const int th = tiles256(D.H);
+    wg_seg(g, w.dq, D.QD, D.QD, L.wt[0], D.H, 0, th);
+    wg_seg(g, dk, D.KVD, D.KVD, L.wt[1], D.H, 0, th);
+    wg_seg(g, dv, D.KVD, D.KVD, L.wt[2], D.H, 0, th);
     const bf* all[3] = {w.dq, dk, dv};
     {
       int ts[3], slots[3], n = 0;
@@ -726,10 +779,10 @@ extern "C" harli_status harli_lora_bwd(harli_ctx* c, int32_t layer, const float*
       for (int t = 0; t < 3; ++t)
         if (adapted(c, t)) ts[n] = t, slots[n] = t, dys[n] = all[t], ++n;
       if (n) RUNB(proj_grads_group(c, n, ts, slots, dys, sv->h, T, sv, dA, dB, st));
-      for (int i = 0; i < n; ++i) add_seg(g, w.gs[slots[i]], D.r, w.An[ts[i]], D.r, D.r);  // dh += gs_t A_t^T as one more K segment
+      for (int i = 0; i < n; ++i) wg_seg(g, w.gs[slots[i]], r, r, w.An[ts[i]], D.H, 0, th);  // dh += gs_t A_t^T as one more K segment
     }
-    g.Cf = w.dh; g.ldcf = D.H;
-    RUNB(gemm_launch(g, 1, st));
+    wg_out_f32(g, w.dh, nullptr, D.H);
+    RUNB(gemm2_launch(g, st));
   }
   ft_rmsnorm_bwd(w.dh, sv->X, sv->rho1, L.g1, w.dx1, dX, nullptr, T, D.H, nullptr, w.scale + 1, st);
   HARLI_HIP(hipGetLastError());

@@ -63,6 +63,14 @@ harli_status gemm_launch(const GemmArgs& a, int batches, hipStream_t st);
 // Per-launch timing for the benchmark: when enabled every gemm_launch is bracketed by two events on
 // its stream; collect() waits for them and returns the summed flops, milliseconds and launch count.
 void gemm_prof_enable(int every);
+// The same bracket for other GEMM kernels: begin() before the launch, end() after it; both do nothing for launches
+// that are not sampled.
+struct GemmTimer {
+  void *e0 = nullptr, *e1 = nullptr;
+  double flops = 0;
+  hipError_t begin(double flops_of_launch, hipStream_t st);
+  hipError_t end(hipStream_t st);
+};
 harli_status gemm_prof_collect(double* flops, double* ms, long long* launches);
 
 }  // namespace harli

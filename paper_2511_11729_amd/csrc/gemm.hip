@@ -383,6 +383,24 @@ harli_status gemm_prof_collect(double* flops, double* ms, long long* launches) {
   return HARLI_OK;
 }
 
+hipError_t GemmTimer::begin(double flops_of_launch, hipStream_t st) {
+  if (!(g_prof_every > 0 && (g_prof_seen++ % g_prof_every) == 0)) return hipSuccess;
+  hipEvent_t a, b;
+  hipError_t e = hipEventCreate(&a);
+  if (e != hipSuccess) return e;
+  e = hipEventCreate(&b);
+  if (e != hipSuccess) return e;
+  e0 = a, e1 = b, flops = flops_of_launch;
+  return hipEventRecord(a, st);
+}
+hipError_t GemmTimer::end(hipStream_t st) {
+  if (!e0) return hipSuccess;
+  hipError_t e = hipEventRecord(static_cast<hipEvent_t>(e1), st);
+  g_prof.push_back(ProfRec{static_cast<hipEvent_t>(e0), static_cast<hipEvent_t>(e1), flops});
+  e0 = e1 = nullptr;
+  return e;
+}
+
 // flops the launch is asked to perform: full products for GEMM_FULL, the causal half otherwise
 static double gemm_flops(const GemmArgs& a, int batches) {
   double k = 0;

@@ -11,6 +11,7 @@
 #include "ft_elem.h"
 #include "ft_kernels.h"
 #include "gemm.h"
+#include "gemm2.h"
 
 namespace harli {
 namespace {
@@ -18,7 +19,7 @@ namespace {
 struct HeadWs {
   char* base = nullptr;
   size_t bytes = 0;
-  bf *w16 = nullptr, *wT = nullptr;  // [V][H] and [H][Vp] in the compute element (made once)
+  bf *w16 = nullptr, *wT = nullptr;  // the output layer as the weight GEMM's blocked operands [V rows, H] and [H rows, V] (made once)
   bf *h = nullptr, *dlog = nullptr;
   float *rho = nullptr, *logits = nullptr, *dh = nullptr, *acc = nullptr;  // acc: [0] loss sum, [1] count, [2] 1/count
   float* rowloss = nullptr;  // [T] loss of a counted row, -1 for a row that is not counted
@@ -101,15 +102,6 @@ __global__ void __launch_bounds__(256) k_head_finish(const float* rowloss, int T
   }
 }
 
-// [V][H] storage (bf16 or fp32) -> [H][Vp] compute element, zero in the pad columns
-__global__ void __launch_bounds__(256) k_head_wt(const void* __restrict__ w, int f32, bf* __restrict__ wT, int V, int H, int Vp) {
-  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
-  if (i >= (long long)H * Vp) return;
-  const int hh = (int)(i / Vp), v = (int)(i - (long long)hh * Vp);
-  const long long src = (long long)v * H + hh;
-  wT[i] = v >= V ? 0 : F2E(f32 ? static_cast<const float*>(w)[src] : bf2f(static_cast<const bf*>(w)[src]));
-}
-
 HeadWs* ws_of(harli_ctx* c) { return static_cast<HeadWs*>(c->head_ws); }
 
 harli_status ensure(harli_ctx* c, int T, hipStream_t st) {
@@ -118,14 +110,14 @@ harli_status ensure(harli_ctx* c, int T, hipStream_t st) {
   const int V = c->cfg.vocab, H = c->cfg.hidden;
   const int Vp = (V + 7) & ~7;
   if (!w.weights_ready) {
-    HARLI_HIP(hipMalloc(reinterpret_cast<void**>(&w.w16), (size_t)V * H * 2));
-    HARLI_HIP(hipMalloc(reinterpret_cast<void**>(&w.wT), (size_t)H * Vp * 2));
+    HARLI_HIP(hipMalloc(reinterpret_cast<void**>(&w.w16), blocked_elems(V, H) * 2));
+    HARLI_HIP(hipMalloc(reinterpret_cast<void**>(&w.wT), blocked_elems(H, Vp) * 2));
     const int f32 = c->cfg.dtype == HARLI_F32 ? 1 : 0;
-    FtConvJobs jobs{};
-    jobs.j[jobs.n++] = FtConvJob{c->w_lm, w.w16, V, H, 0, f32};
-    ft_convert_jobs(jobs, st);
-    const long long n = (long long)H * Vp;
-    hipLaunchKernelGGL(k_head_wt, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, c->w_lm, f32, w.wT, V, H, Vp);
+    BlockJobs jobs{};
+    jobs.half = kFtHalf ? 1 : 0;
+    jobs.j[jobs.n++] = BlockJob{c->w_lm, w.w16, V, H, 0, f32};  // operand [n = class][k = hidden]
+    jobs.j[jobs.n++] = BlockJob{c->w_lm, w.wT, V, H, 1, f32};   // operand [n = hidden][k = class], zero past V
+    gemm2_block_jobs(jobs, st);
     w.Vp = Vp;
     w.weights_ready = true;
   }
@@ -187,24 +179,26 @@ extern "C" harli_status harli_head_fwd_bwd(harli_ctx* c, const float* x, const i
   for (int t0 = 0; t0 < T; t0 += w.TC) {
     const int rows = std::min(w.TC, T - t0);
     {  // logits = h W^T
-      GemmArgs g{};
-      g.M = rows; g.N = V; g.nb1 = g.nb2 = 1; g.alpha = 1.f; g.causal = GEMM_FULL; g.half = kFtHalf ? 1 : 0;
+      Gemm2Args g{};
+      g.M = rows; g.alpha = 1.f; g.half = kFtHalf ? 1 : 0; g.overflow_flag = c->dw.err_flag;
       g.nseg = 1;
-      g.seg[0] = GemmSeg{};
-      g.seg[0].A = w.h + (size_t)t0 * H; g.seg[0].B = w.w16; g.seg[0].K = H; g.seg[0].lda = H; g.seg[0].ldb = H;
-      g.Cf = w.logits; g.ldcf = Vp;
-      s = gemm_launch(g, 1, st);
+      g.seg[0] = Gemm2Seg{w.h + (size_t)t0 * H, H, H, w.w16, 0, (V + kG2TileN - 1) / kG2TileN, nullptr, 0, V};
+      g.nout = 1;
+      g.tiles_n = (V + kG2TileN - 1) / kG2TileN;
+      g.out[0] = Gemm2Out{0, V, nullptr, 0, w.logits, nullptr, Vp};
+      s = gemm2_launch(g, st);
       if (s != HARLI_OK) return s;
     }
     hipLaunchKernelGGL(k_ce_row, dim3(rows), dim3(256), 0, st, w.logits, targets + t0, w.dlog, V, Vp, w.rowloss + t0, c->dw.err_flag);
     {  // dh = dlog W   (contraction over the padded vocabulary: pad columns are zero on both sides)
-      GemmArgs g{};
-      g.M = rows; g.N = H; g.nb1 = g.nb2 = 1; g.alpha = 1.f; g.causal = GEMM_FULL; g.half = kFtHalf ? 1 : 0;
+      Gemm2Args g{};
+      g.M = rows; g.alpha = 1.f; g.half = kFtHalf ? 1 : 0; g.overflow_flag = c->dw.err_flag;
       g.nseg = 1;
-      g.seg[0] = GemmSeg{};
-      g.seg[0].A = w.dlog; g.seg[0].B = w.wT; g.seg[0].K = Vp; g.seg[0].lda = Vp; g.seg[0].ldb = Vp;
-      g.Cf = w.dh + (size_t)t0 * H; g.ldcf = H;
-      s = gemm_launch(g, 1, st);
+      g.seg[0] = Gemm2Seg{w.dlog, Vp, Vp, w.wT, 0, (H + kG2TileN - 1) / kG2TileN, nullptr, 0, H};
+      g.nout = 1;
+      g.tiles_n = (H + kG2TileN - 1) / kG2TileN;
+      g.out[0] = Gemm2Out{0, H, nullptr, 0, w.dh + (size_t)t0 * H, nullptr, H};
+      s = gemm2_launch(g, st);
       if (s != HARLI_OK) return s;
     }
   }

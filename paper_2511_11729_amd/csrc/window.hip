@@ -1,5 +1,6 @@
 // Window over the finetune task's frozen weights (Harli Sec. 4.3; Sec. 4.4 for the shrink under memory pressure).
 #include "window.h"
+#include "gemm2.h"
 
 #include <vector>
 
@@ -184,7 +185,7 @@ extern "C" harli_status harli_ft_window_enable(harli_ctx* c, int32_t n_slots) {
     int out, in;
     proj_shape(c->cfg, t, &out, &in);
     w->off[t] = o;
-    w->nb[t] = (size_t)out * in * 2;
+    w->nb[t] = ft_weight_copy_bytes(out, in);
     o += (w->nb[t] + 255) / 256 * 256;
   }
   w->item_bytes = o;
@@ -208,7 +209,7 @@ extern "C" harli_status harli_ft_window_enable(harli_ctx* c, int32_t n_slots) {
     for (int t = 0; t < kTargets; ++t) {
       int out, in;
       proj_shape(c->cfg, t, &out, &in);
-      const size_t nb = (size_t)out * in * 2;
+      const size_t nb = ft_weight_copy_bytes(out, in);
       if (hipMemcpy(w->host + (size_t)l * w->item_bytes + w->off[t], Ld.w16[t], nb, hipMemcpyDeviceToHost) != hipSuccess ||
           hipMemcpy(w->host + (size_t)(2 * L - 1 - l) * w->item_bytes + w->off[t], Ld.wt[t], nb, hipMemcpyDeviceToHost) != hipSuccess)
         return bail(fail(HARLI_ERR_HIP, "ft_window_enable: copy to the host failed"));
@@ -237,7 +238,7 @@ extern "C" harli_status harli_ft_window_disable(harli_ctx* c) {
     for (int t = 0; t < kTargets; ++t) {
       int out, in;
       proj_shape(c->cfg, t, &out, &in);
-      const size_t nb = (size_t)out * in * 2;
+      const size_t nb = ft_weight_copy_bytes(out, in);
       HARLI_HIP(hipMalloc(&Ld.w16[t], nb));
       HARLI_HIP(hipMalloc(&Ld.wt[t], nb));
       HARLI_HIP(hipMemcpy(Ld.w16[t], w->host + (size_t)l * w->item_bytes + w->off[t], nb, hipMemcpyHostToDevice));
