@@ -37,14 +37,27 @@ sys.path.insert(0, ROOT)
 SLO_MS_FULL_MODEL = 40.0          # paper Sec. 8.1: TPOT QoS target
 PEAK_MFMA_TFLOPS = 2500.0         # MI355X dense fp16/bf16
 PEAK_HBM_GBS = 8000.0
-# Live timing of the dominant kernel: every 4th launch of the finetune GEMM is bracketed by HIP events (a unit has 11
+# Live timing of the dominant kernel: every 3rd launch of the finetune GEMM is bracketed by HIP events (a unit has 8
 # launches, so the sample walks through all of them).  Bracketing every launch costs the finetune stream the overlap
 # between neighbouring kernels: measured, 3.25 -> 3.8 ms per unit, i.e. it would take 13 % off the number it is there to explain.
-GEMM_TIMED_EVERY = 4
-# HBM traffic per launch / per step from the rocprofv3 FETCH_SIZE and WRITE_SIZE counter runs summarised in
-# profiles/bench_config1_hbm_traffic.md (each scaled by what the same counter reads for a 256 MiB device copy)
-TRAFFIC_GEMM_BYTES_PER_LAUNCH = 393.4e6      # k_gemm (all epilogue variants), average over the 11 launches of a finetune unit
-TRAFFIC_DECODE_BYTES_PER_STEP = 559.6e6      # all kernels of one decode step
+GEMM_TIMED_EVERY = 3
+# HBM traffic per launch / per step comes from the rocprofv3 FETCH_SIZE and WRITE_SIZE counter runs summarised in this
+# file (each scaled by what the same counter reads for a 256 MiB device copy); the two figures are read from its lines
+# "gemm_bytes_per_launch: ..." and "decode_bytes_per_step: ...", so that they change with the profile and not by hand
+TRAFFIC_SUMMARY = os.path.join(ROOT, "profiles", "bench_config1_hbm_traffic.md")
+
+
+def measured_traffic():
+    """(finetune GEMM bytes per launch, decode bytes per step) from the counter summary, None where it has none."""
+    out = {"gemm_bytes_per_launch": None, "decode_bytes_per_step": None}
+    try:
+        for line in open(TRAFFIC_SUMMARY):
+            for key in out:
+                if line.strip().startswith(key + ":"):
+                    out[key] = float(line.split(":", 1)[1].split()[0])
+    except OSError:
+        pass
+    return out["gemm_bytes_per_launch"], out["decode_bytes_per_step"]
 
 
 def log(*a):
@@ -59,6 +72,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--solo", action="store_true", help="also report each task running alone (default on)")
     ap.add_argument("--no-sched", action="store_true", help="skip the predictor profiling and the scheduled run")
+    ap.add_argument("--no-full-depth", action="store_true",
+                    help="skip the full-depth leg (config 2: the whole 32-layer model decoded beside a whole-model finetune step)")
     ap.add_argument("--no-peaks", action="store_true",
                     help="skip the read-bandwidth and GEMM-clock probes (profiling runs: keeps their kernels out of the trace)")
     ap.add_argument("--calib-copy", action="store_true",
@@ -259,6 +274,19 @@ def main():
         cpu = {"value": reps * sb * ss / (c1 - c0), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
                "sample": "numpy fp64 layer forward+backward of the %d x %d micro-batch at full 7B-layer width, repeated "
                          "%d times (%.1f s), decode not running" % (sb, ss, reps, c1 - c0)}
+        try:                                           # the same oracle on one thread, one sequence of 256 tokens
+            from threadpoolctl import threadpool_limits
+            with threadpool_limits(limits=1):
+                Xs1 = X_np[:1, :256]
+                c0 = time.perf_counter()
+                Yo, sv = O.layer_forward(Xs1, W_np, lora_np, lora.scale, sh)
+                _, dYo = O.mse_loss(Yo, np.zeros_like(Yo))
+                O.layer_backward(dYo, sv, W_np, lora_np, lora.scale, sh)
+                c1 = time.perf_counter()
+            cpu["single_thread"] = {"value": 256 / (c1 - c0), "unit": "tokens/s", "cores": 1,
+                                    "sample": "one sequence of 256 tokens, forward+backward, once (%.1f s)" % (c1 - c0)}
+        except Exception as e:                         # pragma: no cover
+            cpu["single_thread"] = {"value": None, "note": "threadpoolctl unavailable: %s" % e}
 
     if args.calib_copy:
         src = torch.full((64 << 20,), 1.0, dtype=torch.float32, device=dev)     # 256 MiB
@@ -284,7 +312,19 @@ def main():
                                                      "note": "the published 2.5 PFLOP/s is at the nominal clock"}
         del ga, gb, gout
 
+    # ------------------------------------------------------------------ full depth: config 2, the paper's own setting
+    full = None
+    if not args.no_full_depth:
+        log("[bench] full-depth leg: config 2 (32 layers + output layer), decode batch 16 x 1024 beside 8 x 512 finetune")
+        del graph, hz, ctx, pool
+        gc.collect()
+        torch.cuda.empty_cache()
+        from paper_2511_11729_amd import bench_colocate
+        fa = argparse.Namespace(config=2, layers=None, batch=16, kv_len=1024, steps=3, slo_ms=SLO_MS_FULL_MODEL, pace_ms=None)
+        full = bench_colocate.run(fa)
+
     ach_tf = gemm_flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else float("nan")
+    traffic_gemm, traffic_decode = measured_traffic()
     out = {
         "metric": "LoRA finetune tokens/s under decode TPOT SLO",
         "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
@@ -299,12 +339,14 @@ def main():
                 "decode_step_latency_ms_p50": float(np.percentile(closed["steplat"], 50)),
                 "decode_step_latency_ms_p99": float(np.percentile(closed["steplat"], 99))},
         "roofline": {"bound": "mfma", "achieved": ach_tf, "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s",
-                     "frac": ach_tf / PEAK_MFMA_TFLOPS, "traffic": TRAFFIC_GEMM_BYTES_PER_LAUNCH, "kernel": "k_gemm<half>",
+                     "frac": ach_tf / PEAK_MFMA_TFLOPS, "traffic": traffic_gemm, "kernel": "k_gemm2 (all tile heights and epilogues)",
                      "launches": int(gemm_n), "avg_launch_us": gemm_ms * 1e3 / max(gemm_n, 1),
-                     "note": "co-located with decode; flops = 2MNK per launch (causal launches count half); every %d-th "
-                             "launch of the timed region is bracketed by HIP events, `launches` is the number bracketed" % GEMM_TIMED_EVERY},
+                     "solo_unit_frac": (4.0 * T * m.layer_params) / (ft_solo_ms * 1e-3) / 1e12 / PEAK_MFMA_TFLOPS,
+                     "note": "co-located with decode; flops = 2 M K per valid output column of every K segment; every %d-th "
+                             "launch of the timed region is bracketed by HIP events, `launches` is the number bracketed; "
+                             "solo_unit_frac = base-GEMM flops of a unit (4 T P_layer) over the whole solo unit time" % GEMM_TIMED_EVERY},
         "roofline_decode": {"bound": "hbm", "achieved": dec_bytes / (tpot_mean * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
-                            "unit": "GB/s", "frac": dec_bytes / (tpot_mean * 1e-3) / 1e9 / PEAK_HBM_GBS, "traffic": TRAFFIC_DECODE_BYTES_PER_STEP,
+                            "unit": "GB/s", "frac": dec_bytes / (tpot_mean * 1e-3) / 1e9 / PEAK_HBM_GBS, "traffic": traffic_decode,
                             "bytes_per_step": dec_bytes, "solo_achieved": dec_bytes / (dec_solo_ms * 1e-3) / 1e9,
                             "solo_frac": dec_bytes / (dec_solo_ms * 1e-3) / 1e9 / PEAK_HBM_GBS},
         "slo_paced": {"decode_interval_ms": pace_ms, "value": paced["tokens_per_s"], "unit": "tokens/s",
@@ -318,6 +360,10 @@ def main():
         "solo": {"decode_ms_per_step": dec_solo_ms, "finetune_ms_per_step": ft_solo_ms,
                  "finetune_tokens_per_s": T / ft_solo_ms * 1e3},
         "measured_peaks": peaks,
+        "full_depth": full,
+        "notes": {"finetune_unit": "a unit is one layer forward + backward on a fixed seeded dY (no loss between them: the loss "
+                                   "belongs to the whole-model step, which the full_depth leg times with its output layer, "
+                                   "cross entropy and AdamW)"},
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))

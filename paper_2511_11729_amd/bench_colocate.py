@@ -31,7 +31,12 @@ def main():
     ap.add_argument("--slo-ms", type=float, default=40.0, help="decode time-per-output-token target")
     ap.add_argument("--pace-ms", type=float, default=None, help="paced run: one decode step every this many ms (default 0.6 x target)")
     args = ap.parse_args()
+    print(json.dumps(run(args)))
 
+
+def run(args):
+    """The measurement itself; `args` carries config, layers, batch, kv_len, steps, slo_ms, pace_ms.  Returns the
+    result dictionary (bench.py calls this for its full-depth leg)."""
     import dataclasses
     import torch
     import workloads as wl
@@ -192,16 +197,42 @@ def main():
     paced = colocate.run_colocated(hz, sD, sF, decode_once, args.steps, 1, pace)
     ctx.check(sD)
     st = pool.stats()
+    # algorithmic work per step: decode reads every weight once plus the cached K/V; the finetune step multiplies by
+    # the frozen weights forward and backward (no weight gradients), plus attention (causal half), adapters, output layer
+    dec_bytes = 2 * (L * m.layer_params + m.vocab * H) + int(sum(int(n) + 1 for n in kv_len)) * 2 * m.kv_row_bytes * L
+    lora_flops = 0
+    dims = dict(q=(H, m.n_q * m.head_dim), k=(H, m.n_kv * m.head_dim), v=(H, m.n_kv * m.head_dim), o=(m.n_q * m.head_dim, H),
+                gate=(H, m.ffn), up=(H, m.ffn), down=(m.ffn, H))
+    for p in lora.targets:
+        lora_flops += 6 * T * lora.rank * sum(dims[p])
+    attn = ft.micro_batch * 7 * ft.seq_len * ft.seq_len * m.n_q * m.head_dim      # forward 2 S^2 H, backward 2.5 x that
+    ft_flops = L * (4 * T * m.layer_params + lora_flops + attn) + 4 * T * m.vocab * H
+
+    def roof(summary, dec_ms_mean):
+        return dict(summary,
+                    finetune_TFLOPs=ft_flops / (summary["finetune_ms_per_step"] * 1e-3) / 1e12,
+                    finetune_frac_of_2500_TFLOPs=ft_flops / (summary["finetune_ms_per_step"] * 1e-3) / 1e12 / 2500.0,
+                    decode_GBs=dec_bytes / (dec_ms_mean * 1e-3) / 1e9, decode_frac_of_8000_GBs=dec_bytes / (dec_ms_mean * 1e-3) / 1e9 / 8000.0)
+
     out = {"workload": "config %d, %d layers + output layer: decode batch %d (cached tokens %d..%d) beside a finetune step of %d x %d "
                        "tokens, LoRA r=%d on %s" % (args.config, L, B, kv_len.min(), kv_len.max(), ft.micro_batch, ft.seq_len,
                                                     lora.rank, ",".join(lora.targets)),
            "slo_tpot_ms": args.slo_ms,
-           "solo": {"decode_tpot_ms": dec_solo_ms, "finetune_ms_per_step": ft_solo_ms, "finetune_tokens_per_s": T / ft_solo_ms * 1e3},
-           "colocated_closed_loop": summarise(closed),
-           "colocated_paced": dict(summarise(paced), decode_interval_ms=pace),
+           "algorithmic": {"decode_GB_per_step": dec_bytes / 1e9, "finetune_TFLOP_per_step": ft_flops / 1e12},
+           "solo": {"decode_tpot_ms": dec_solo_ms, "decode_GBs": dec_bytes / (dec_solo_ms * 1e-3) / 1e9,
+                    "decode_frac_of_8000_GBs": dec_bytes / (dec_solo_ms * 1e-3) / 1e9 / 8000.0,
+                    "finetune_ms_per_step": ft_solo_ms, "finetune_tokens_per_s": T / ft_solo_ms * 1e3,
+                    "finetune_TFLOPs": ft_flops / (ft_solo_ms * 1e-3) / 1e12,
+                    "finetune_frac_of_2500_TFLOPs": ft_flops / (ft_solo_ms * 1e-3) / 1e12 / 2500.0},
+           "colocated_closed_loop": roof(summarise(closed), float(np.mean(closed["tpot"]))),
+           "colocated_paced": dict(summarise(paced), decode_interval_ms=pace,
+                                   finetune_TFLOPs=ft_flops / (paced["ms_per_step"] * 1e-3) / 1e12,
+                                   finetune_frac_of_2500_TFLOPs=ft_flops / (paced["ms_per_step"] * 1e-3) / 1e12 / 2500.0),
            "pool": {"chunks": st.n_chunks, "kv_chunks": st.kv_chunks, "chunk_MB": chunk / 1e6, "slab_GB": slab_bytes / 1e9},
            "loss_last": float(loss)}
-    print(json.dumps(out))
+    # let go of the device memory before the caller goes on
+    del graph
+    return out
 
 
 if __name__ == "__main__":

@@ -25,7 +25,11 @@
 namespace harli {
 namespace {
 
-constexpr int BN = kG2TileN, BK = kG2StepK, NT = 256, NS = 4;
+constexpr int BN = kG2TileN, BK = kG2StepK, NT = 256;
+// LDS stages: four (128 KiB at 256-row tiles).  Six stages at 128-row tiles (144 KiB) were measured and changed nothing:
+// those tiles are not short of loads in flight.
+template <int FM>
+constexpr int stages() { return 4; }
 constexpr int BSZ = BN * BK * 2;  // 16 KiB: one stage of the weight-side tile
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
@@ -160,7 +164,7 @@ __device__ __forceinline__ void g2_store_slab(const f32x16& c0, const f32x16& c1
 template <int FM, bool HALF, int EPI>
 __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1)))
 k_gemm2(Gemm2Args a, int tiles_total, int chunk, int GM, int GN, const uint4* zero16) {
-  constexpr int BM = 64 * FM, ASZ = BM * BK * 2, STG = ASZ + BSZ;
+  constexpr int BM = 64 * FM, ASZ = BM * BK * 2, STG = ASZ + BSZ, NS = stages<FM>();
   constexpr int LOADS = FM + 4;  // direct-to-LDS loads a wave issues per stage
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   const int tid = threadIdx.x, lane = tid & 63;
@@ -314,7 +318,7 @@ k_gemm2(Gemm2Args a, int tiles_total, int chunk, int GM, int GN, const uint4* ze
     G2_PIPE1();                                                                                                        \
     G2_SB0();                                                                                                          \
     G2_ADVANCE();                                                                                                      \
-    G2_WAITV(LOADS); /* all but the newest stage in flight has landed: this wave's part of stage `nxt` is in LDS */    \
+    G2_WAITV((NS - 3) * LOADS); /* all but the NS - 3 newest stages in flight have landed: stage `nxt` is in LDS */   \
     __builtin_amdgcn_s_barrier();                                                                                      \
     G2_SB0();                                                                                                          \
     G2_RD(fa0, fb0, nxt, 0);                                                                                           \
@@ -334,15 +338,30 @@ k_gemm2(Gemm2Args a, int tiles_total, int chunk, int GM, int GN, const uint4* ze
     G2_ISSUE(1);
     G2_ADVANCE();
     G2_ISSUE(2);
-    G2_WAITV(2 * LOADS);
+    if constexpr (NS == 6) {
+      G2_ADVANCE();
+      G2_ISSUE(3);
+      G2_ADVANCE();
+      G2_ISSUE(4);
+    }
+    G2_WAITV((NS - 2) * LOADS);
     __builtin_amdgcn_s_barrier();
     G2_RD(fa0, fb0, 0, 0);
     G2_SB0();
     for (int st = 0; st < n_step; st += NS) {
-      G2_STEP(0, 1, 3);
-      G2_STEP(1, 2, 0);
-      G2_STEP(2, 3, 1);
-      G2_STEP(3, 0, 2);
+      if constexpr (NS == 4) {
+        G2_STEP(0, 1, 3);
+        G2_STEP(1, 2, 0);
+        G2_STEP(2, 3, 1);
+        G2_STEP(3, 0, 2);
+      } else {
+        G2_STEP(0, 1, 5);
+        G2_STEP(1, 2, 0);
+        G2_STEP(2, 3, 1);
+        G2_STEP(3, 4, 2);
+        G2_STEP(4, 5, 3);
+        G2_STEP(5, 0, 4);
+      }
     }
     G2_WAITV(0);
   }
@@ -408,7 +427,7 @@ __global__ void __launch_bounds__(256) k_block_jobs(BlockJobs jobs) {
 }
 
 template <int FM>
-constexpr int lds_bytes() { return NS * (64 * FM * BK * 2 + BSZ); }
+constexpr int lds_bytes() { return stages<FM>() * (64 * FM * BK * 2 + BSZ); }
 
 int g_force_fm = 0;  // measurement hook: 2 or 4 fixes the tile height
 
