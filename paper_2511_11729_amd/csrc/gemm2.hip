@@ -510,7 +510,9 @@ harli_status gemm2_launch(const Gemm2Args& a, hipStream_t st) {
   if (g_force_fm == 2 || g_force_fm == 4) FM = g_force_fm;
   const int BM = 64 * FM;
   const int tiles_m = (a.M + BM - 1) / BM;
-  const int GM = std::min(4, tiles_m), GN = std::min(4, a.tiles_n);
+  // The 32 workgroups an XCD runs at a time form one GM x GN block of tiles about 1024 x 2048 outputs large, so that
+  // they share GM + GN operand panels in its L2.
+  const int GM = std::min(FM == 2 ? 8 : 4, tiles_m), GN = std::min(FM == 2 ? 4 : 8, a.tiles_n);
   const int total = ((tiles_m + GM - 1) / GM) * ((a.tiles_n + GN - 1) / GN) * GM * GN, chunk = (total + 7) / 8;
 #define G2_LAUNCH(F_, H_, E_) \
   hipLaunchKernelGGL((k_gemm2<F_, H_, E_>), dim3(chunk * 8), dim3(NT), lds_bytes<F_>(), st, a, total, chunk, GM, GN, zero16)
