@@ -111,6 +111,9 @@ typedef struct {
 
 /* slab: device base address (never dereferenced); slab_bytes >= small_pool_bytes + one chunk. */
 harli_status harli_pool_create(void* slab, size_t slab_bytes, const harli_pool_cfg* cfg, harli_pool** out);
+/* Gives up the creator's hold on the pool.  A context built on the pool (harli_ctx_create) holds it too and returns its
+ * pool memory when it is destroyed: the pool object is deleted when the last holder is gone, so the two may be destroyed
+ * in either order.  The caller must not use p after this call. */
 void harli_pool_destroy(harli_pool* p);
 
 /* One allocation.  cls = KV_PAGE: n is ignored, one page is returned in out->page.
@@ -179,6 +182,22 @@ typedef struct {
  * Allocates a device workspace proportional to max_batch and max_ft_tokens. */
 harli_status harli_ctx_create(const harli_model_cfg* cfg, const harli_weights* w, harli_pool* pool, harli_ctx** out);
 void harli_ctx_destroy(harli_ctx* c);
+/* Device memory the context holds beyond the caller's buffers (host out-pointer; host arithmetic only).  The decode
+ * instance keeps a private, pre-shuffled copy of the frozen weights and a small workspace (both made by
+ * harli_ctx_create); the finetune instance keeps private copies W and W^T of the frozen weights in its compute element
+ * (made by harli_lora_attach; the paper also keeps one model instance per task, Sec. 7) and the workspace described at
+ * harli_lora_cfg.  `in_pool` of these bytes are allocations of the unified pool, `outside_pool` are the library's own.
+ * After harli_ctx_create and harli_lora_attach the library no longer reads the seven projection matrices of a layer
+ * or w_lm on bf16 storage (everything runs on its copies): a caller short of memory may free them.  emb, the norm
+ * gains, biases and the adapters stay borrowed. */
+typedef struct {
+  size_t decode_weights, decode_workspace;
+  size_t finetune_weights, finetune_workspace;
+  size_t head_weights, head_workspace;
+  size_t in_pool, outside_pool;
+} harli_device_bytes;
+harli_status harli_ctx_device_bytes(const harli_ctx* c, harli_device_bytes* out);
+
 /* Diagnostic, SYNCHRONISES `hip_stream`: reports (and clears) whether any kernel of this
  * context met a page id outside the pool or a token id outside the vocabulary.  Such
  * entries are skipped by the kernels, never dereferenced. */
@@ -191,6 +210,13 @@ typedef struct {
   int32_t rank;
   float alpha;       /* scale = alpha / rank */
   uint32_t targets;  /* bit mask of HARLI_T_* */
+  /* Where the finetune task's workspace lives (backward temporaries of one unit and the output layer's logits chunk,
+   * sized once for max_ft_tokens in harli_lora_attach; no forward / backward call allocates afterwards).  0: the
+   * library allocates it.  1: it is taken from the unified pool as TENSOR allocations (Sec. 4.2: one pool for every
+   * tensor of both tasks), so harli_pool_stats and the inference-first coordination of Sec. 4.4 account for it; the
+   * caller sizes the slab for it (harli_ctx_device_bytes reports the size) and harli_lora_attach returns
+   * HARLI_ERR_OOM when the pool cannot hold it. */
+  int32_t workspace_in_pool;
 } harli_lora_cfg;
 
 /* A, B: host arrays of n_layers*7 device pointers indexed [layer*7 + t], t = 0..6

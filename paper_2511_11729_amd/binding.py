@@ -62,7 +62,12 @@ class Weights(C.Structure):
 
 
 class LoraCfg(C.Structure):
-    _fields_ = [("rank", C.c_int32), ("alpha", C.c_float), ("targets", C.c_uint32)]
+    _fields_ = [("rank", C.c_int32), ("alpha", C.c_float), ("targets", C.c_uint32), ("workspace_in_pool", C.c_int32)]
+
+
+class DeviceBytes(C.Structure):
+    _fields_ = [(n, C.c_size_t) for n in ("decode_weights", "decode_workspace", "finetune_weights", "finetune_workspace",
+                                           "head_weights", "head_workspace", "in_pool", "outside_pool")]
 
 
 class AdamWCfg(C.Structure):
@@ -94,6 +99,7 @@ _SIGS = {
     "harli_ctx_destroy": (None, [C.c_void_p]),
     "harli_ctx_check": (C.c_int, [C.c_void_p, C.c_void_p]),
     "harli_lora_attach": (C.c_int, [C.c_void_p, C.POINTER(LoraCfg), C.POINTER(C.c_void_p), C.POINTER(C.c_void_p)]),
+    "harli_ctx_device_bytes": (C.c_int, [C.c_void_p, C.c_void_p]),
     "harli_decode_step": (C.c_int, [C.c_void_p, C.POINTER(DecodeBatch), C.c_void_p]),
     "harli_decode_step_static": (C.c_int, [C.c_void_p, C.POINTER(DecodeBatch), C.c_void_p]),
     "harli_decode_step_static_bytes": (C.c_size_t, [C.c_void_p, C.c_int32, C.c_int32]),
@@ -200,6 +206,8 @@ class Pool:
 
     def close(self):
         if self.handle:
+            # contexts built on the pool hold it too (the library counts them): the garbage collector may finalise a
+            # pool before its contexts
             lib().harli_pool_destroy(self.handle)
             self.handle = C.c_void_p()
 
@@ -319,7 +327,12 @@ class Context:
         _check(lib().harli_ft_window_stats(self.handle, C.byref(st)))
         return st
 
-    def lora_attach(self, rank: int, alpha: float, targets: Sequence[str], A, B) -> None:
+    def device_bytes(self) -> "DeviceBytes":
+        b = DeviceBytes()
+        _check(lib().harli_ctx_device_bytes(self.handle, C.byref(b)))
+        return b
+
+    def lora_attach(self, rank: int, alpha: float, targets: Sequence[str], A, B, workspace_in_pool: bool = False) -> None:
         """A, B: per layer a dict target -> torch tensor."""
         n_layers = self.cfg.n_layers
         self._lora_keep = (A, B)
@@ -333,7 +346,7 @@ class Context:
                 if t in targets:
                     pa[l * 7 + i] = _ptr(A[l][t])
                     pb[l * 7 + i] = _ptr(B[l][t])
-        cfg = LoraCfg(rank, alpha, mask)
+        cfg = LoraCfg(rank, alpha, mask, int(bool(workspace_in_pool)))
         _check(lib().harli_lora_attach(self.handle, C.byref(cfg), pa, pb))
 
     def decode_step(self, *, batch, kv_len, page_table, max_pages, max_kv_len, token_ids=None, x_in=None, x_out=None,

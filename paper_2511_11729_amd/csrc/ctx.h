@@ -69,6 +69,7 @@ struct harli_ctx {
   void* ones16 = nullptr;    // [max_ft_tokens, 8] ones in the finetune compute element: the input column of the biases
   void* window = nullptr;    // window over the finetune task's frozen weights (library-owned), or null
   int n_cu = 0;
+  size_t decode_ws_bytes = 0, decode_weight_bytes = 0;  // device memory harli_ctx_create allocated
 };
 
 namespace harli {

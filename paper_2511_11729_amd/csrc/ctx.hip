@@ -17,16 +17,22 @@ int event_done(void* hip_event) {
 
 void event_destroy(void* hip_event) { (void)hipEventDestroy(static_cast<hipEvent_t>(hip_event)); }
 
+static size_t g_tally = 0;  // bytes handed out by dev_alloc since the caller last read it (harli_ctx_create is not re-entrant)
 template <typename T>
 static harli_status dev_alloc(T** p, size_t bytes, bool zero) {
   HARLI_HIP(hipMalloc(reinterpret_cast<void**>(p), bytes ? bytes : 16));
   if (zero) HARLI_HIP(hipMemset(*p, 0, bytes ? bytes : 16));
+  g_tally += bytes ? bytes : 16;
   return HARLI_OK;
 }
 
 void free_finetune_state(harli_ctx* c);  // finetune.hip
+void finetune_device_bytes(const harli_ctx* c, size_t* weights, size_t* workspace, int* in_pool);  // finetune.hip
+void head_device_bytes(const harli_ctx* c, size_t* weights, size_t* workspace, int* in_pool);      // head.hip
 void free_head_state(harli_ctx* c);      // head.hip
 void free_window_state(harli_ctx* c);    // window.hip
+void pool_retain(harli_pool* p);          // pool.cpp
+void pool_release(harli_pool* p);
 void detach_layers(harli_ctx* c);        // window.hip
 
 }  // namespace harli
@@ -80,6 +86,7 @@ extern "C" harli_status harli_ctx_create(const harli_model_cfg* cfg, const harli
   harli_ctx* c = new harli_ctx;
   c->cfg = m;
   c->pool = pool;
+  pool_retain(pool);
   c->geom = geom;
   c->slab = static_cast<char*>(harli_pool_slab(pool));
   c->layers.resize(m.n_layers);
@@ -113,6 +120,7 @@ extern "C" harli_status harli_ctx_create(const harli_model_cfg* cfg, const harli
   c->n_cu = prop.multiProcessorCount;
 
   DecodeWs& d = c->dw;
+  g_tally = 0;
   d.bpad = (m.max_batch + 15) / 16 * 16;
   d.max_chunks = (m.max_seq_len + 127) / 128;  // the smallest attention chunk is 128 tokens
   const size_t bp = d.bpad;
@@ -150,6 +158,8 @@ extern "C" harli_status harli_ctx_create(const harli_model_cfg* cfg, const harli
     TRY(dev_alloc(&d.fa, bp * m.ffn * 4, true));
     TRY(dev_alloc(&d.fu, bp * m.ffn * 4, true));
   }
+  c->decode_ws_bytes = g_tally;
+  g_tally = 0;
   // decode-private pre-shuffled weights (bf16 path): the inference instance keeps its own copy
   if (m.dtype == HARLI_BF16) {
     const int KVD = m.n_kv_heads * m.head_dim;
@@ -175,7 +185,23 @@ extern "C" harli_status harli_ctx_create(const harli_model_cfg* cfg, const harli
       return fail(HARLI_ERR_HIP, "ctx_create: pre-shuffling the weights failed");
     }
   }
+  c->decode_weight_bytes = g_tally;
   *out = c;
+  return HARLI_OK;
+}
+
+extern "C" harli_status harli_ctx_device_bytes(const harli_ctx* c, harli_device_bytes* out) {
+  if (!c || !out) return fail(HARLI_ERR_INVALID, "ctx_device_bytes: null argument");
+  harli_device_bytes b{};
+  b.decode_weights = c->decode_weight_bytes;
+  b.decode_workspace = c->decode_ws_bytes;
+  int ft_pool = 0, head_pool = 0;
+  finetune_device_bytes(c, &b.finetune_weights, &b.finetune_workspace, &ft_pool);
+  head_device_bytes(c, &b.head_weights, &b.head_workspace, &head_pool);
+  b.in_pool = (ft_pool ? b.finetune_workspace : 0) + (head_pool ? b.head_workspace : 0);
+  b.outside_pool = b.decode_weights + b.decode_workspace + b.finetune_weights + b.finetune_workspace + b.head_weights +
+                   b.head_workspace - b.in_pool;
+  *out = b;
   return HARLI_OK;
 }
 
@@ -193,6 +219,7 @@ extern "C" void harli_ctx_destroy(harli_ctx* c) {
   free_window_state(c);
   free_finetune_state(c);
   free_head_state(c);
+  pool_release(c->pool);
   delete c;
 }
 

@@ -26,6 +26,7 @@ using namespace harli;
 
 namespace harli {
 harli_status pool_free_owned(harli_pool* p, const harli_alloc* a, void* event);  // pool.cpp
+harli_status head_prepare(harli_ctx* c);                                          // head.hip
 }
 
 struct harli_saved {
@@ -53,14 +54,36 @@ struct FtWs {
      *doT = nullptr, *dS = nullptr, *PT = nullptr, *dST = nullptr, *qT = nullptr, *kT = nullptr, *dq = nullptr, *dkq = nullptr,
      *dvq = nullptr, *dk = nullptr, *dv = nullptr, *gs[3] = {}, *An[kTargets] = {}, *Bn[kTargets] = {};
   float* scale = nullptr;  // [0] sigma, [1] 1/sigma, [2] scratch: gradient scaling of the backward pass
+  char* sbase = nullptr;   // S x S score buffers of the unfused attention path (library allocation, grown on demand)
+  size_t sbytes = 0;
   int Bf = 0, S = 0;
 };
 
 struct FtState {
   FtWs ws;
+  bool ws_in_pool = false;   // ws.base is ws_alloc (a TENSOR allocation of the unified pool) rather than a library allocation
+  harli_alloc ws_alloc{};
+  size_t weight_bytes = 0;   // private copies of the frozen weights, biases and the ones column
 };
 
 FtState* state(harli_ctx* c) { return static_cast<FtState*>(c->ft_ws); }
+
+// gives the workspace back (waits for the device first: units in flight may still use it)
+harli_status free_ws(harli_ctx* c) {
+  FtState* fs = state(c);
+  if (!fs || !fs->ws.base) return HARLI_OK;
+  HARLI_HIP(hipDeviceSynchronize());
+  if (fs->ws_in_pool) {
+    harli_status r = harli_pool_free(c->pool, &fs->ws_alloc, nullptr);
+    if (r != HARLI_OK) return r;
+  } else {
+    HARLI_HIP(hipFree(fs->ws.base));
+  }
+  fs->ws.base = nullptr;
+  fs->ws.bytes = 0;
+  fs->ws_in_pool = false;
+  return HARLI_OK;
+}
 
 struct Dims {
   int T, H, QD, KVD, F, d, nq, nkv, G, r, Z;
@@ -83,11 +106,16 @@ Dims dims(const harli_ctx* c, int Bf, int S) {
   return D;
 }
 
-harli_status ensure_ws(harli_ctx* c, int Bf, int S) {
-  FtWs& w = state(c)->ws;
-  const Dims D = dims(c, Bf, S);
-  // the S x S score buffers exist only for head sizes the fused attention kernels do not cover
-  const size_t T = D.T, ZSS = ft_attn_supported(D.d) ? 0 : (size_t)D.Z * S * S;
+// The unit's workspace (backward temporaries, adapter copies, gradient scratch), sized once for max_ft_tokens when the
+// adapters are attached, so that no forward or backward call allocates or frees device memory (either would be a
+// device-wide synchronisation in the middle of serving).  With workspace_in_pool it is one TENSOR allocation of the
+// unified pool (Sec. 4.2: every byte a task uses comes from the one pool, so the pool's statistics and its
+// inference-first back-pressure, Sec. 4.4, see it); otherwise the library allocates it itself.
+harli_status make_ws(harli_ctx* c) {
+  FtState* fs = state(c);
+  FtWs& w = fs->ws;
+  const Dims D = dims(c, 1, c->cfg.max_ft_tokens);
+  const size_t T = D.T;
   const size_t maxdim = std::max(std::max((size_t)D.H, (size_t)D.QD), (size_t)D.F);
   size_t off = 0;
   auto take = [&](size_t n) {
@@ -95,9 +123,7 @@ harli_status ensure_ws(harli_ctx* c, int Bf, int S) {
     off += al(n);
     return o;
   };
-  const size_t o_scores = take(ZSS * 4), o_dP = take(ZSS * 4), o_ST = take(ZSS * 4), o_dPT = take(ZSS * 4);
-  const size_t o_dS = take(ZSS * 2), o_PT = take(ZSS * 2), o_dST = take(ZSS * 2);
-  const size_t o_delta = take((size_t)D.Z * S * 4);
+  const size_t o_delta = take(T * D.nq * 4);
   const size_t o_dh2 = take(T * D.H * 4), o_dx1 = take(T * D.H * 4), o_dh = take(T * D.H * 4);
   const size_t o_vT = take(T * D.KVD * 2), o_kT = take(T * D.KVD * 2), o_qT = take(T * D.QD * 2), o_doT = take(T * D.QD * 2);
   const size_t ad = al(maxdim * D.r * 2);  // one adapter matrix in the compute element, row-major (skinny products)
@@ -108,21 +134,27 @@ harli_status ensure_ws(harli_ctx* c, int Bf, int S) {
   const size_t o_dob = take(T * D.QD * 2), o_dq = take(T * D.QD * 2), o_dkq = take(T * D.QD * 2), o_dvq = take(T * D.QD * 2);
   const size_t o_dk = take(T * D.KVD * 2), o_dv = take(T * D.KVD * 2), o_gs = take(3 * al(T * D.r * 2));
   const size_t o_gpart = take(ft_lora_grad_ws_floats((int)maxdim, D.r) * 4);
-  if (off > w.bytes) {
-    if (w.base) HARLI_HIP(hipFree(w.base));
-    w.base = nullptr;
-    w.bytes = 0;
-    HARLI_HIP(hipMalloc(reinterpret_cast<void**>(&w.base), off));
+  const bool want_pool = c->lora.workspace_in_pool != 0;
+  if (off != w.bytes || want_pool != fs->ws_in_pool) {  // first attach, or another rank / placement than before
+    harli_status r = free_ws(c);
+    if (r != HARLI_OK) return r;
+    if (want_pool) {
+      r = harli_pool_alloc(c->pool, HARLI_CLS_TENSOR, off, &fs->ws_alloc);
+      if (r != HARLI_OK) return r;
+      w.base = static_cast<char*>(fs->ws_alloc.ptr);
+    } else {
+      HARLI_HIP(hipMalloc(reinterpret_cast<void**>(&w.base), off));
+    }
+    fs->ws_in_pool = want_pool;
     w.bytes = off;
   }
   char* b = w.base;
-  w.scores = (float*)(b + o_scores); w.dP = (float*)(b + o_dP); w.ST = (float*)(b + o_ST); w.dPT = (float*)(b + o_dPT);
-  w.dS = (bf*)(b + o_dS); w.PT = (bf*)(b + o_PT); w.dST = (bf*)(b + o_dST); w.delta = (float*)(b + o_delta);
+  w.delta = (float*)(b + o_delta);
   w.dh2 = (float*)(b + o_dh2); w.dx1 = (float*)(b + o_dx1); w.dh = (float*)(b + o_dh);
   w.vT = (bf*)(b + o_vT); w.kT = (bf*)(b + o_kT); w.qT = (bf*)(b + o_qT); w.doT = (bf*)(b + o_doT);
   w.dyb = (bf*)(b + o_dyb); w.da = (bf*)(b + o_da); w.du = (bf*)(b + o_du);
   w.dx1b = (bf*)(b + o_dx1b); w.dob = (bf*)(b + o_dob); w.dq = (bf*)(b + o_dq); w.dkq = (bf*)(b + o_dkq);
-  w.dvq = (bf*)(b + o_dvq); w.dk = (bf*)(b + o_dk); w.dv = (bf*)(b + o_dv); 
+  w.dvq = (bf*)(b + o_dvq); w.dk = (bf*)(b + o_dk); w.dv = (bf*)(b + o_dv);
   for (int i = 0; i < 3; ++i) w.gs[i] = (bf*)(b + o_gs + i * al(T * D.r * 2));
   w.gpart = (float*)(b + o_gpart);
   for (int i = 0; i < kTargets; ++i) {
@@ -130,8 +162,40 @@ harli_status ensure_ws(harli_ctx* c, int Bf, int S) {
     w.An[i] = (bf*)(b + o_An + i * adb); w.Bn[i] = (bf*)(b + o_Bn + i * ad);
   }
   w.scale = (float*)(b + o_scale);
+  return HARLI_OK;
+}
+
+// Per call: nothing to do for the head sizes the fused attention kernels cover.  Other head sizes run attention as
+// batched GEMMs around S x S score matrices, whose size depends on the sequence length of the call: that block is a
+// library allocation grown on demand (the one place left where a unit call may allocate).
+harli_status ensure_ws(harli_ctx* c, int Bf, int S) {
+  FtWs& w = state(c)->ws;
+  const Dims D = dims(c, Bf, S);
   w.Bf = Bf;
   w.S = S;
+  if (ft_attn_supported(D.d)) return HARLI_OK;
+  const size_t ZSS = (size_t)D.Z * S * S;
+  size_t off = 0;
+  auto take = [&](size_t n) {
+    size_t o = off;
+    off += al(n);
+    return o;
+  };
+  const size_t o_scores = take(ZSS * 4), o_dP = take(ZSS * 4), o_ST = take(ZSS * 4), o_dPT = take(ZSS * 4);
+  const size_t o_dS = take(ZSS * 2), o_PT = take(ZSS * 2), o_dST = take(ZSS * 2);
+  if (off > w.sbytes) {
+    if (w.sbase) {
+      HARLI_HIP(hipDeviceSynchronize());  // earlier units may still use the old block
+      HARLI_HIP(hipFree(w.sbase));
+    }
+    w.sbase = nullptr;
+    w.sbytes = 0;
+    HARLI_HIP(hipMalloc(reinterpret_cast<void**>(&w.sbase), off));
+    w.sbytes = off;
+  }
+  char* b = w.sbase;
+  w.scores = (float*)(b + o_scores); w.dP = (float*)(b + o_dP); w.ST = (float*)(b + o_ST); w.dPT = (float*)(b + o_dPT);
+  w.dS = (bf*)(b + o_dS); w.PT = (bf*)(b + o_PT); w.dST = (bf*)(b + o_dST);
   return HARLI_OK;
 }
 
@@ -355,7 +419,8 @@ void free_finetune_state(harli_ctx* c) {
       }
   if (c->ft_ws) {
     FtState* s = state(c);
-    if (s->ws.base) (void)hipFree(s->ws.base);
+    (void)free_ws(c);
+    if (s->ws.sbase) (void)hipFree(s->ws.sbase);
     delete s;
     c->ft_ws = nullptr;
   }
@@ -375,6 +440,7 @@ extern "C" harli_status harli_lora_attach(harli_ctx* c, const harli_lora_cfg* cf
       if (((cfg->targets >> t) & 1u) && (!A[l * kTargets + t] || !B[l * kTargets + t]))
         return fail(HARLI_ERR_INVALID, "lora_attach: layer %d target %d has a null adapter", l, t);
   c->lora = *cfg;
+  c->lora_attached = false;  // until everything below has succeeded
   for (int l = 0; l < c->cfg.n_layers; ++l) {
     LayerDev& L = c->layers[l];
     for (int t = 0; t < kTargets; ++t) {
@@ -421,9 +487,37 @@ extern "C" harli_status harli_lora_attach(harli_ctx* c, const harli_lora_cfg* cf
   }
   HARLI_HIP(hipDeviceSynchronize());
   if (!c->ft_ws) c->ft_ws = new FtState;
+  {
+    size_t nb = 0;
+    for (int l = 0; l < c->cfg.n_layers; ++l)
+      for (int t = 0; t < kTargets; ++t) {
+        int out, in;
+        proj_shape(c->cfg, t, &out, &in);
+        if (c->layers[l].wt[t]) nb += 2 * ft_weight_copy_bytes(out, in);
+        if (t < 3 && c->layers[l].b16[t]) nb += blocked_elems(out, 8) * 2;
+      }
+    if (c->ones16) nb += (size_t)c->cfg.max_ft_tokens * 16;
+    state(c)->weight_bytes = nb;
+  }
+  harli_status ws = make_ws(c);
+  if (ws == HARLI_OK) ws = head_prepare(c);
+  if (ws != HARLI_OK) return ws;
   c->lora_attached = true;
   return HARLI_OK;
 }
+
+namespace harli {
+// device memory the finetune side holds: (private weight copies, workspace, whether the workspace is in the pool)
+void finetune_device_bytes(const harli_ctx* c, size_t* weights, size_t* workspace, int* in_pool) {
+  *weights = *workspace = 0;
+  *in_pool = 0;
+  if (!c->ft_ws) return;
+  const FtState* fs = static_cast<const FtState*>(c->ft_ws);
+  *weights = fs->weight_bytes;
+  *workspace = fs->ws.bytes + fs->ws.sbytes;
+  *in_pool = fs->ws_in_pool ? 1 : 0;
+}
+}  // namespace harli
 
 extern "C" harli_status harli_saved_bytes(const harli_ctx* c, int32_t B_f, int32_t S, size_t* bytes) {
   if (!c || !bytes || B_f < 1 || S < 1) return fail(HARLI_ERR_INVALID, "saved_bytes: bad argument");

@@ -25,6 +25,9 @@ struct HeadWs {
   float* rowloss = nullptr;  // [T] loss of a counted row, -1 for a row that is not counted
   int T = 0, TC = 0, Vp = 0;
   bool weights_ready = false;
+  bool in_pool = false;      // base is `alloc` (a TENSOR allocation of the unified pool) rather than a library allocation
+  harli_alloc alloc{};
+  size_t weight_bytes = 0;
 };
 
 inline size_t al(size_t n) { return (n + 255) & ~size_t(255); }
@@ -104,10 +107,32 @@ __global__ void __launch_bounds__(256) k_head_finish(const float* rowloss, int T
 
 HeadWs* ws_of(harli_ctx* c) { return static_cast<HeadWs*>(c->head_ws); }
 
-harli_status ensure(harli_ctx* c, int T, hipStream_t st) {
+harli_status head_free_ws(harli_ctx* c) {
+  HeadWs* w = ws_of(c);
+  if (!w || !w->base) return HARLI_OK;
+  HARLI_HIP(hipDeviceSynchronize());
+  if (w->in_pool) {
+    harli_status r = harli_pool_free(c->pool, &w->alloc, nullptr);
+    if (r != HARLI_OK) return r;
+  } else {
+    HARLI_HIP(hipFree(w->base));
+  }
+  w->base = nullptr;
+  w->bytes = 0;
+  w->in_pool = false;
+  return HARLI_OK;
+}
+
+}  // namespace
+
+// Made once when the adapters are attached (the context has an output layer): the blocked copies of the output layer
+// and the workspace for max_ft_tokens rows -- from the unified pool when the adapters were attached with
+// workspace_in_pool, else a library allocation -- so that harli_head_fwd_bwd itself allocates nothing.
+harli_status head_prepare(harli_ctx* c) {
+  if (!c->w_lm || !c->g_final || c->cfg.vocab < 1) return HARLI_OK;
   if (!c->head_ws) c->head_ws = new HeadWs;
   HeadWs& w = *ws_of(c);
-  const int V = c->cfg.vocab, H = c->cfg.hidden;
+  const int V = c->cfg.vocab, H = c->cfg.hidden, T = c->cfg.max_ft_tokens;
   const int Vp = (V + 7) & ~7;
   if (!w.weights_ready) {
     HARLI_HIP(hipMalloc(reinterpret_cast<void**>(&w.w16), blocked_elems(V, H) * 2));
@@ -117,43 +142,58 @@ harli_status ensure(harli_ctx* c, int T, hipStream_t st) {
     jobs.half = kFtHalf ? 1 : 0;
     jobs.j[jobs.n++] = BlockJob{c->w_lm, w.w16, V, H, 0, f32};  // operand [n = class][k = hidden]
     jobs.j[jobs.n++] = BlockJob{c->w_lm, w.wT, V, H, 1, f32};   // operand [n = hidden][k = class], zero past V
-    gemm2_block_jobs(jobs, st);
+    gemm2_block_jobs(jobs, nullptr);
+    HARLI_HIP(hipDeviceSynchronize());
     w.Vp = Vp;
+    w.weight_bytes = (blocked_elems(V, H) + blocked_elems(H, Vp)) * 2;
     w.weights_ready = true;
   }
-  if (T > w.T) {
-    // row chunk: at most 2048 rows and about 512 MiB of fp32 logits
-    const int TC = (int)std::max<long long>(64, std::min<long long>(2048, ((512ll << 20) / ((long long)Vp * 4)) / 64 * 64));
-    size_t off = 0;
-    auto take = [&](size_t n) {
-      size_t o = off;
-      off += al(n);
-      return o;
-    };
-    const size_t o_h = take((size_t)T * H * 2), o_rho = take((size_t)T * 4), o_log = take((size_t)TC * Vp * 4);
-    const size_t o_dlog = take((size_t)TC * Vp * 2), o_dh = take((size_t)T * H * 4), o_acc = take(64), o_rl = take((size_t)T * 4);
-    if (w.base) {
-      HARLI_HIP(hipStreamSynchronize(st));
-      HARLI_HIP(hipFree(w.base));
-      w.base = nullptr;
+  // row chunk: at most 2048 rows and about 512 MiB of fp32 logits
+  const int TC = (int)std::max<long long>(64, std::min<long long>(2048, ((512ll << 20) / ((long long)Vp * 4)) / 64 * 64));
+  size_t off = 0;
+  auto take = [&](size_t n) {
+    size_t o = off;
+    off += al(n);
+    return o;
+  };
+  const size_t o_h = take((size_t)T * H * 2), o_rho = take((size_t)T * 4), o_log = take((size_t)TC * Vp * 4);
+  const size_t o_dlog = take((size_t)TC * Vp * 2), o_dh = take((size_t)T * H * 4), o_acc = take(64), o_rl = take((size_t)T * 4);
+  const bool want_pool = c->lora.workspace_in_pool != 0;
+  if (off != w.bytes || want_pool != w.in_pool) {
+    harli_status r = head_free_ws(c);
+    if (r != HARLI_OK) return r;
+    if (want_pool) {
+      r = harli_pool_alloc(c->pool, HARLI_CLS_TENSOR, off, &w.alloc);
+      if (r != HARLI_OK) return r;
+      w.base = static_cast<char*>(w.alloc.ptr);
+    } else {
+      HARLI_HIP(hipMalloc(reinterpret_cast<void**>(&w.base), off));
     }
-    HARLI_HIP(hipMalloc(reinterpret_cast<void**>(&w.base), off));
+    w.in_pool = want_pool;
     w.bytes = off;
-    char* b = w.base;
-    w.h = (bf*)(b + o_h); w.rho = (float*)(b + o_rho); w.logits = (float*)(b + o_log); w.dlog = (bf*)(b + o_dlog);
-    w.dh = (float*)(b + o_dh); w.acc = (float*)(b + o_acc); w.rowloss = (float*)(b + o_rl);
-    w.T = T;
-    w.TC = TC;
   }
+  char* b = w.base;
+  w.h = (bf*)(b + o_h); w.rho = (float*)(b + o_rho); w.logits = (float*)(b + o_log); w.dlog = (bf*)(b + o_dlog);
+  w.dh = (float*)(b + o_dh); w.acc = (float*)(b + o_acc); w.rowloss = (float*)(b + o_rl);
+  w.T = T;
+  w.TC = TC;
   return HARLI_OK;
 }
 
-}  // namespace
+void head_device_bytes(const harli_ctx* c, size_t* weights, size_t* workspace, int* in_pool) {
+  *weights = *workspace = 0;
+  *in_pool = 0;
+  if (!c->head_ws) return;
+  const HeadWs* w = static_cast<const HeadWs*>(c->head_ws);
+  *weights = w->weight_bytes;
+  *workspace = w->bytes;
+  *in_pool = w->in_pool ? 1 : 0;
+}
 
 void free_head_state(harli_ctx* c) {
   if (!c->head_ws) return;
   HeadWs* w = ws_of(c);
-  if (w->base) (void)hipFree(w->base);
+  (void)head_free_ws(c);
   if (w->w16) (void)hipFree(w->w16);
   if (w->wT) (void)hipFree(w->wT);
   delete w;
@@ -171,8 +211,8 @@ extern "C" harli_status harli_head_fwd_bwd(harli_ctx* c, const float* x, const i
   if (T < 1 || T > c->cfg.max_ft_tokens) return fail(HARLI_ERR_INVALID, "head_fwd_bwd: %d tokens outside 1..max_ft_tokens %d", T, c->cfg.max_ft_tokens);
   if (c->cfg.hidden % 8) return fail(HARLI_ERR_INVALID, "head_fwd_bwd: hidden must be a multiple of 8");
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  harli_status s = ensure(c, T, st);
-  if (s != HARLI_OK) return s;
+  if (!c->head_ws || !ws_of(c)->base) return fail(HARLI_ERR_STATE, "head_fwd_bwd: the output layer was not prepared by harli_lora_attach");
+  harli_status s = HARLI_OK;
   HeadWs& w = *ws_of(c);
   const int V = c->cfg.vocab, H = c->cfg.hidden, Vp = w.Vp;
   ft_rmsnorm_fwd(x, c->g_final, w.h, w.rho, T, H, c->cfg.rms_eps, st);

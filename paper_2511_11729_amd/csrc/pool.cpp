@@ -8,6 +8,7 @@
 #include <cstring>
 #include <map>
 #include <cmath>
+#include <atomic>
 #include <mutex>
 #include <set>
 #include <string>
@@ -89,6 +90,9 @@ using namespace harli;
 
 struct harli_pool {
   std::mutex mu;
+  // the creator's reference plus one per context built on the pool: a context gives pool memory back when it is
+  // destroyed, so the pool object has to live until the last of them is gone, whichever is destroyed first
+  std::atomic<int> refs{1};
   char* slab = nullptr;
   size_t slab_bytes = 0;
   harli_pool_cfg cfg{};
@@ -307,6 +311,18 @@ struct harli_pool {
   }
 };
 
+namespace harli {
+void pool_retain(harli_pool* p) {
+  if (p) p->refs.fetch_add(1, std::memory_order_relaxed);
+}
+void pool_release(harli_pool* p) {
+  if (!p || p->refs.fetch_sub(1, std::memory_order_acq_rel) != 1) return;
+  for (const Pending& q : p->pending)
+    if (q.own) event_destroy(q.event);
+  delete p;
+}
+}  // namespace harli
+
 extern "C" {
 
 const char* harli_status_str(harli_status s) {
@@ -365,12 +381,7 @@ harli_status harli_pool_create(void* slab, size_t slab_bytes, const harli_pool_c
   return HARLI_OK;
 }
 
-void harli_pool_destroy(harli_pool* p) {
-  if (!p) return;
-  for (const Pending& q : p->pending)
-    if (q.own) event_destroy(q.event);
-  delete p;
-}
+void harli_pool_destroy(harli_pool* p) { harli::pool_release(p); }
 
 harli_status harli_pool_alloc(harli_pool* p, harli_class cls, size_t n, harli_alloc* out) {
   if (!p || !out) return fail(HARLI_ERR_INVALID, "pool_alloc: null argument");
