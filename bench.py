@@ -300,14 +300,14 @@ def main():
     if not args.no_peaks:
         probe = torch.empty(6 << 30, dtype=torch.uint8, device=dev)
         peaks = {"hbm_stream_read_GBs": hb.dbg_read_bandwidth(probe, 0), "l2_to_cu_read_GBs": hb.dbg_read_bandwidth(probe, 1),
-                 "note": "the GEMM's workgroups pull (256+128) x K x 2 bytes of operand panels per 256x128 tile through L2: at "
-                         "the L2 rate above that bounds it below the MFMA peak"}
+                 "note": "the weight GEMM's workgroups pull (128+256) x K x 2 bytes of operand panels per 128x256 tile "
+                         "(256+256 per 256x256 tile) through L2: at the L2 rate above that bounds it below the MFMA peak"}
         del probe
         # the clock the chip sustains under the GEMM itself (seen from inside the kernel), on random half operands
         ga = (torch.rand(2048, 4096, device=dev) - 0.5).half()
         gb = (torch.rand(4096, 4096, device=dev) - 0.5).half()
         gout = torch.empty(2048, 4096, dtype=torch.float16, device=dev)
-        tf, mhz = hb.dbg_gemm_clock(ga, gb, gout, half=True, reps=50)
+        tf, mhz = hb.dbg_gemm2(2048, [{"A": ga, "B": gb}], [{"N": 4096, "cb": gout}], half=True, reps=50)
         peaks["gemm_2048x4096x4096_back_to_back"] = {"TFLOPs": tf, "shader_clock_MHz": mhz, "nominal_clock_MHz": 2400,
                                                      "note": "the published 2.5 PFLOP/s is at the nominal clock"}
         del ga, gb, gout

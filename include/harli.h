@@ -217,6 +217,12 @@ typedef struct {
    * caller sizes the slab for it (harli_ctx_device_bytes reports the size) and harli_lora_attach returns
    * HARLI_ERR_OOM when the pool cannot hold it. */
   int32_t workspace_in_pool;
+  /* The backward pass carries gradients in IEEE half, scaled by the power of two that brings max|dY| of the unit to
+   * 2^(8 - grad_headroom_log2): the default 0 keeps small gradients well above half's underflow; a model whose
+   * activations have outlier channels (gradients of the gated FFN are products with them) can overflow half at that
+   * scale, which harli_ctx_check reports; such a caller gives headroom here (0..24).  The results are unscaled
+   * before they are returned; the scale itself changes no bit of them while nothing under- or overflows. */
+  int32_t grad_headroom_log2;
 } harli_lora_cfg;
 
 /* A, B: host arrays of n_layers*7 device pointers indexed [layer*7 + t], t = 0..6

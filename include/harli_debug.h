@@ -11,26 +11,6 @@
 extern "C" {
 #endif
 
-/* C = alpha * (A1 . B1^T + A2 . B2^T) (+ res), the finetune unit's 16-bit MFMA GEMM (fp32 accumulation).
- * A1 [M, K1], B1 [N, K1], optional A2 [M, K2], B2 [N, K2] (K2 = 0: absent): device 16-bit elements, IEEE half when
- * half = 1 and bfloat16 when half = 0, row-major, contraction index contiguous, K a multiple of 8.  Any of the
- * outputs may be NULL: Cb 16-bit [M, N] (same element type as the inputs), Cf fp32 [M, N] (with optional fp32
- * residual res [M, N]), Ct 16-bit [N, M].
- * causal: 0 full, 1 lower output tiles only, 2 upper output tiles only, 3 K loop up to the
- * tile's last row, 4 K loop from the tile's first row (see the kernel for the exact meaning). */
-harli_status harli_dbg_gemm(const void* A1, const void* B1, int32_t K1, const void* A2, const void* B2, int32_t K2,
-                            int32_t M, int32_t N, float alpha, int32_t causal, int32_t half, void* Cb, float* Cf,
-                            const float* res, void* Ct, void* hip_stream);
-
-/* At which clock does the chip run the MFMA GEMM?  Launches Cb[M, N] = A[M, K] . B[N, K]^T (all device, 16-bit, as for
- * harli_dbg_gemm) once to warm up and then `reps` times back to back, and writes to host pointers the achieved
- * TFLOP/s (2*M*N*K per launch over HIP-event time) and the shader clock in MHz that workgroup 0 of the last launch
- * saw inside its K loop (shader-clock cycles over ticks of the constant 100 MHz counter).  Under this kernel the
- * clock settles well below the nominal 2.4 GHz, which bounds what fraction of the nominal MFMA peak can be reached.
- * Allocates 16 bytes for the duration of the call and synchronises the stream. */
-harli_status harli_dbg_gemm_clock(const void* A, const void* B, int32_t M, int32_t N, int32_t K, int32_t half, void* Cb,
-                                  int32_t reps, double* tflops, double* shader_mhz, void* hip_stream);
-
 /* The weight GEMM of the finetune unit (256-wide tiles, weight side in blocked order) on its own.  The descriptor
  * mirrors the kernel's arguments; weight-side operands are given ROW-MAJOR here ([rows, K], the contraction index
  * contiguous, 16-bit elements of the type `half` selects) and the hook makes their blocked copies itself (it allocates

@@ -62,7 +62,8 @@ class Weights(C.Structure):
 
 
 class LoraCfg(C.Structure):
-    _fields_ = [("rank", C.c_int32), ("alpha", C.c_float), ("targets", C.c_uint32), ("workspace_in_pool", C.c_int32)]
+    _fields_ = [("rank", C.c_int32), ("alpha", C.c_float), ("targets", C.c_uint32), ("workspace_in_pool", C.c_int32),
+                ("grad_headroom_log2", C.c_int32)]
 
 
 class DeviceBytes(C.Structure):
@@ -147,11 +148,7 @@ _SIGS = {
                                           C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
     "harli_dbg_window_plan": (C.c_int, [C.c_int32, C.c_int32, C.POINTER(C.c_int32), C.c_int32, C.POINTER(C.c_int32),
                                         C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
-    "harli_dbg_gemm_clock": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_int32,
-                                       C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_void_p]),
     "harli_dbg_gemm2": (C.c_int, [C.c_void_p, C.c_void_p]),
-    "harli_dbg_gemm": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
-                                 C.c_float, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
 }
 
 
@@ -332,7 +329,8 @@ class Context:
         _check(lib().harli_ctx_device_bytes(self.handle, C.byref(b)))
         return b
 
-    def lora_attach(self, rank: int, alpha: float, targets: Sequence[str], A, B, workspace_in_pool: bool = False) -> None:
+    def lora_attach(self, rank: int, alpha: float, targets: Sequence[str], A, B, workspace_in_pool: bool = False,
+                    grad_headroom_log2: int = 0) -> None:
         """A, B: per layer a dict target -> torch tensor."""
         n_layers = self.cfg.n_layers
         self._lora_keep = (A, B)
@@ -346,7 +344,7 @@ class Context:
                 if t in targets:
                     pa[l * 7 + i] = _ptr(A[l][t])
                     pb[l * 7 + i] = _ptr(B[l][t])
-        cfg = LoraCfg(rank, alpha, mask, int(bool(workspace_in_pool)))
+        cfg = LoraCfg(rank, alpha, mask, int(bool(workspace_in_pool)), grad_headroom_log2)
         _check(lib().harli_lora_attach(self.handle, C.byref(cfg), pa, pb))
 
     def decode_step(self, *, batch, kv_len, page_table, max_pages, max_kv_len, token_ids=None, x_in=None, x_out=None,
@@ -524,16 +522,6 @@ def cu_stream_destroy(stream: int) -> None:
     _check(lib().harli_cu_stream_destroy(stream))
 
 
-def dbg_gemm(A1, B1, *, A2=None, B2=None, alpha=1.0, causal=0, half=False, Cb=None, Cf=None, res=None, Ct=None,
-             stream=None) -> None:
-    """Test hook: C = alpha * (A1 B1^T + A2 B2^T) (+ res) on the finetune unit's bf16 MFMA GEMM."""
-    M, K1 = A1.shape
-    N = B1.shape[0]
-    K2 = A2.shape[1] if A2 is not None else 0
-    _check(lib().harli_dbg_gemm(_ptr(A1), _ptr(B1), K1, _ptr(A2), _ptr(B2), K2, M, N, alpha, causal, int(half), _ptr(Cb), _ptr(Cf),
-                                _ptr(res), _ptr(Ct), _stream(stream)))
-
-
 class DbgGemm2Desc(C.Structure):
     _fields_ = [("M", C.c_int32), ("nseg", C.c_int32), ("nout", C.c_int32), ("tiles_n", C.c_int32), ("half", C.c_int32),
                 ("epi", C.c_int32), ("tile_rows", C.c_int32), ("reps", C.c_int32), ("alpha", C.c_float),
@@ -606,15 +594,6 @@ def dbg_window_plan(n_layers: int, n_slots: int, items):
     slot, miss, refill = (C.c_int32 * max(n, 1))(), (C.c_int32 * max(n, 1))(), (C.c_int32 * max(n, 1))()
     _check(lib().harli_dbg_window_plan(n_layers, n_slots, arr, n, slot, miss, refill))
     return list(slot[:n]), list(miss[:n]), list(refill[:n])
-
-
-def dbg_gemm_clock(A, B, Cb, *, half=True, reps=20, stream=None):
-    """(TFLOP/s, shader MHz) of the MFMA GEMM Cb = A . B^T run `reps` times back to back."""
-    M, K = A.shape
-    N = B.shape[0]
-    t, f = C.c_double(0.0), C.c_double(0.0)
-    _check(lib().harli_dbg_gemm_clock(_ptr(A), _ptr(B), M, N, K, int(half), _ptr(Cb), reps, C.byref(t), C.byref(f), _stream(stream)))
-    return t.value, f.value
 
 
 def dbg_read_bandwidth(buf, mode: int, stream=None) -> float:

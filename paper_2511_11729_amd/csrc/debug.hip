@@ -2,87 +2,12 @@
 #include "harli_debug.h"
 
 #include "ctx.h"
-#include "gemm.h"
+#include "gemm_timer.h"
 #include "gemm2.h"
 
 #include <vector>
 
 using namespace harli;
-
-extern "C" harli_status harli_dbg_gemm(const void* A1, const void* B1, int32_t K1, const void* A2, const void* B2, int32_t K2,
-                                       int32_t M, int32_t N, float alpha, int32_t causal, int32_t half, void* Cb,
-                                       float* Cf, const float* res, void* Ct, void* hip_stream) {
-  GemmArgs g{};
-  g.M = M;
-  g.N = N;
-  g.nb1 = g.nb2 = 1;
-  g.alpha = alpha;
-  g.causal = causal;
-  g.half = half;
-  g.nseg = 0;
-  auto seg = [&](const void* A, const void* B, int K) {
-    GemmSeg& s = g.seg[g.nseg++];
-    s = GemmSeg{};
-    s.A = static_cast<const unsigned short*>(A);
-    s.B = static_cast<const unsigned short*>(B);
-    s.K = K;
-    s.lda = s.ldb = K;
-  };
-  seg(A1, B1, K1);
-  if (K2 > 0) seg(A2, B2, K2);
-  g.Cb = static_cast<unsigned short*>(Cb);
-  g.ldcb = N;
-  g.Cf = Cf;
-  g.res = res;
-  g.ldcf = N;
-  g.Ct = static_cast<unsigned short*>(Ct);
-  g.ldct = M;
-  return gemm_launch(g, 1, static_cast<hipStream_t>(hip_stream));
-}
-
-extern "C" harli_status harli_dbg_gemm_clock(const void* A, const void* B, int32_t M, int32_t N, int32_t K, int32_t half, void* Cb,
-                                             int32_t reps, double* tflops, double* shader_mhz, void* hip_stream) {
-  if (!A || !B || !Cb || !tflops || !shader_mhz || reps < 1) return fail(HARLI_ERR_INVALID, "dbg_gemm_clock: null argument or reps < 1");
-  hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  long long* clk = nullptr;
-  HARLI_HIP(hipMalloc(reinterpret_cast<void**>(&clk), 16));
-  GemmArgs g{};
-  g.M = M;
-  g.N = N;
-  g.nb1 = g.nb2 = 1;
-  g.alpha = 1.f;
-  g.half = half;
-  g.nseg = 1;
-  g.seg[0].A = static_cast<const unsigned short*>(A);
-  g.seg[0].B = static_cast<const unsigned short*>(B);
-  g.seg[0].K = K;
-  g.seg[0].lda = g.seg[0].ldb = K;
-  g.Cb = static_cast<unsigned short*>(Cb);
-  g.ldcb = N;
-  g.clk = clk;
-  hipEvent_t e0 = nullptr, e1 = nullptr;
-  harli_status rc = gemm_launch(g, 1, st);  // warm-up; validates the shape
-  if (rc == HARLI_OK) {
-    HARLI_HIP(hipEventCreate(&e0));
-    HARLI_HIP(hipEventCreate(&e1));
-    HARLI_HIP(hipEventRecord(e0, st));
-    for (int r = 0; r < reps && rc == HARLI_OK; ++r) rc = gemm_launch(g, 1, st);
-    HARLI_HIP(hipEventRecord(e1, st));
-    HARLI_HIP(hipEventSynchronize(e1));
-  }
-  if (rc == HARLI_OK) {
-    float ms = 0.f;
-    long long h[2] = {0, 0};
-    HARLI_HIP(hipEventElapsedTime(&ms, e0, e1));
-    HARLI_HIP(hipMemcpy(h, clk, 16, hipMemcpyDeviceToHost));
-    *tflops = 2.0 * M * (double)N * K * reps / (ms * 1e-3) / 1e12;
-    *shader_mhz = h[1] > 0 ? (double)h[0] / ((double)h[1] / 100.0) : 0.0;
-  }
-  if (e0) (void)hipEventDestroy(e0);
-  if (e1) (void)hipEventDestroy(e1);
-  (void)hipFree(clk);
-  return rc;
-}
 
 extern "C" harli_status harli_dbg_gemm2(const harli_dbg_gemm2_desc* d, void* hip_stream) {
   if (!d || d->nseg < 1 || d->nseg > kGemm2MaxSeg || d->nout < 1 || d->nout > kGemm2MaxOut)

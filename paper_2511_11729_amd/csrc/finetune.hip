@@ -7,9 +7,8 @@
 // base: dx = dy W + (s dy B^T) A^T is again one multi-segment GEMM against a library-owned
 // transposed copy of W, and dA = x^T (s dy B^T), dB = (s x A)^T dy are skinny reductions over
 // the tokens (the adapters' contributions to dx ride on the backward GEMMs as further K
-// segments).  Attention is the fused forward / dQ / dK-dV kernels of ft_attention.hip for head
-// sizes 64 and 128; other head sizes run it as batched GEMMs with causal tile skipping around
-// element-wise softmax / dS kernels.
+// segments).  Attention is the fused forward / dQ / dK-dV kernels of ft_attention.hip (head
+// sizes 64 and 128; harli_lora_attach refuses any other).
 #include <algorithm>
 #include <cmath>
 #include <vector>
@@ -18,7 +17,7 @@
 #include "ft_elem.h"
 #include "ft_attention.h"
 #include "ft_kernels.h"
-#include "gemm.h"
+#include "gemm_timer.h"
 #include "gemm2.h"
 #include "window.h"
 
@@ -35,7 +34,7 @@ struct harli_saved {
   harli_alloc big{};
   std::vector<harli_alloc> small;
   float *rho1 = nullptr, *rho2 = nullptr, *lse = nullptr, *x1 = nullptr;
-  bf *h = nullptr, *q = nullptr, *k = nullptr, *v = nullptr, *P = nullptr, *o = nullptr, *h2 = nullptr, *a = nullptr,
+  bf *h = nullptr, *q = nullptr, *k = nullptr, *v = nullptr, *o = nullptr, *h2 = nullptr, *a = nullptr,
      *u = nullptr, *m = nullptr;
   bf* us[kTargets] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
 };
@@ -48,14 +47,12 @@ inline size_t al(size_t n) { return (n + 255) & ~size_t(255); }
 struct FtWs {
   size_t bytes = 0;
   char* base = nullptr;
-  float *scores = nullptr, *dP = nullptr, *ST = nullptr, *dPT = nullptr, *delta = nullptr, *dh2 = nullptr,
+  float *delta = nullptr, *dh2 = nullptr,
         *dx1 = nullptr, *dh = nullptr, *gpart = nullptr;
   bf *vT = nullptr, *At[kTargets] = {}, *Bt[kTargets] = {}, *dyb = nullptr, *da = nullptr, *du = nullptr, *dx1b = nullptr, *dob = nullptr,
-     *doT = nullptr, *dS = nullptr, *PT = nullptr, *dST = nullptr, *qT = nullptr, *kT = nullptr, *dq = nullptr, *dkq = nullptr,
+     *doT = nullptr, *qT = nullptr, *kT = nullptr, *dq = nullptr, *dkq = nullptr,
      *dvq = nullptr, *dk = nullptr, *dv = nullptr, *gs[3] = {}, *An[kTargets] = {}, *Bn[kTargets] = {};
   float* scale = nullptr;  // [0] sigma, [1] 1/sigma, [2] scratch: gradient scaling of the backward pass
-  char* sbase = nullptr;   // S x S score buffers of the unfused attention path (library allocation, grown on demand)
-  size_t sbytes = 0;
   int Bf = 0, S = 0;
 };
 
@@ -165,62 +162,16 @@ harli_status make_ws(harli_ctx* c) {
   return HARLI_OK;
 }
 
-// Per call: nothing to do for the head sizes the fused attention kernels cover.  Other head sizes run attention as
-// batched GEMMs around S x S score matrices, whose size depends on the sequence length of the call: that block is a
-// library allocation grown on demand (the one place left where a unit call may allocate).
+// Per call: the workspace was sized at attach for max_ft_tokens; only the shape of the call is recorded.
 harli_status ensure_ws(harli_ctx* c, int Bf, int S) {
   FtWs& w = state(c)->ws;
-  const Dims D = dims(c, Bf, S);
   w.Bf = Bf;
   w.S = S;
-  if (ft_attn_supported(D.d)) return HARLI_OK;
-  const size_t ZSS = (size_t)D.Z * S * S;
-  size_t off = 0;
-  auto take = [&](size_t n) {
-    size_t o = off;
-    off += al(n);
-    return o;
-  };
-  const size_t o_scores = take(ZSS * 4), o_dP = take(ZSS * 4), o_ST = take(ZSS * 4), o_dPT = take(ZSS * 4);
-  const size_t o_dS = take(ZSS * 2), o_PT = take(ZSS * 2), o_dST = take(ZSS * 2);
-  if (off > w.sbytes) {
-    if (w.sbase) {
-      HARLI_HIP(hipDeviceSynchronize());  // earlier units may still use the old block
-      HARLI_HIP(hipFree(w.sbase));
-    }
-    w.sbase = nullptr;
-    w.sbytes = 0;
-    HARLI_HIP(hipMalloc(reinterpret_cast<void**>(&w.sbase), off));
-    w.sbytes = off;
-  }
-  char* b = w.sbase;
-  w.scores = (float*)(b + o_scores); w.dP = (float*)(b + o_dP); w.ST = (float*)(b + o_ST); w.dPT = (float*)(b + o_dPT);
-  w.dS = (bf*)(b + o_dS); w.PT = (bf*)(b + o_PT); w.dST = (bf*)(b + o_dST);
   return HARLI_OK;
 }
 
 inline bool adapted(const harli_ctx* c, int t) { return (c->lora.targets >> t) & 1u; }
 inline float lscale(const harli_ctx* c) { return c->lora.alpha / (float)c->lora.rank; }
-
-GemmArgs plain_gemm(int M, int N) {
-  GemmArgs g{};
-  g.M = M;
-  g.N = N;
-  g.nb1 = g.nb2 = 1;
-  g.alpha = 1.f;
-  g.causal = GEMM_FULL;
-  g.half = kFtHalf ? 1 : 0;
-  return g;
-}
-void add_seg(GemmArgs& g, const bf* A, long long lda, const bf* B, long long ldb, int K) {
-  GemmSeg& s = g.seg[g.nseg++];
-  s = GemmSeg{};
-  s.A = A;
-  s.B = B;
-  s.K = K;
-  s.lda = lda;
-  s.ldb = ldb;
-}
 
 // Every adapted projection's A and B (storage type, contents may change between calls) converted to the compute
 // element in two launches.  Forward: A^T [r, in] row-major for the skinny product s x A, and B^T as the weight GEMM's
@@ -229,7 +180,8 @@ void convert_adapters(harli_ctx* c, const LayerDev& L, bool forward, hipStream_t
   FtWs& w = state(c)->ws;
   FtConvJobs jobs{};
   BlockJobs blk{};
-  blk.half = kFtHalf ? 1 : 0;
+  blk.half = 1;
+  jobs.flag = blk.flag = c->dw.err_flag;
   for (int t = 0; t < kTargets; ++t) {
     if (!adapted(c, t)) continue;
     int out, in;
@@ -261,7 +213,7 @@ void proj_us_group(harli_ctx* c, int t_first, int t_last, const bf* xin, int T, 
     // ws.At[t] = A^T [r, in] was made by convert_adapters at the top of the call
     jobs.j[jobs.n++] = SkinnyNtJob{xin, in, w.At[t], in, sv->us[t], r, r, in};
   }
-  ft_skinny_nt_multi(jobs, T, lscale(c), st);
+  ft_skinny_nt_multi(jobs, T, lscale(c), c->dw.err_flag, st);
 }
 
 // ---- the weight GEMMs (gemm2.h) ----
@@ -270,7 +222,7 @@ Gemm2Args wg_begin(const harli_ctx* c, int T) {
   Gemm2Args g{};
   g.M = T;
   g.alpha = 1.f;
-  g.half = kFtHalf ? 1 : 0;
+  g.half = 1;
   g.overflow_flag = c->dw.err_flag;
   return g;
 }
@@ -327,7 +279,7 @@ harli_status proj_grads_group(harli_ctx* c, int n, const int* ts, const int* slo
     jobs.j[jobs.n++] = LoraGradJob{xin, in, w.gs[slots[i]], r, dA[t], r, 1, in, 0, 0, 0, 0};      // dA += x^T gs / sigma
     jobs.j[jobs.n++] = LoraGradJob{dys[i], out, sv->us[t], r, dB[t], 1, out, out, 0, 0, 0, 0};    // dB += us^T dy / sigma
   }
-  ft_skinny_nt_multi(sk, T, lscale(c), st);
+  ft_skinny_nt_multi(sk, T, lscale(c), c->dw.err_flag, st);
   ft_lora_grad_multi(jobs, T, r, w.scale + 1, w.gpart, st);
   return HARLI_OK;
 }
@@ -349,7 +301,7 @@ harli_status check_call(harli_ctx* c, int layer, int Bf, int S, const char* who)
 
 struct SavedPlan {
   size_t big_bytes;
-  size_t o_x1, o_h, o_q, o_k, o_v, o_P, o_o, o_h2, o_a, o_u, o_m;
+  size_t o_x1, o_h, o_q, o_k, o_v, o_o, o_h2, o_a, o_u, o_m;
 };
 
 SavedPlan plan_saved(const harli_ctx* c, const Dims& D, int S) {
@@ -366,7 +318,6 @@ SavedPlan plan_saved(const harli_ctx* c, const Dims& D, int S) {
   p.o_q = take(T * D.QD * 2);
   p.o_k = take(T * D.KVD * 2);
   p.o_v = take(T * D.KVD * 2);
-  p.o_P = take(ft_attn_supported(D.d) ? 0 : (size_t)D.Z * S * S * 2);
   p.o_o = take(T * D.QD * 2);
   p.o_h2 = take(T * D.H * 2);
   p.o_a = take(T * D.F * 2);
@@ -420,7 +371,6 @@ void free_finetune_state(harli_ctx* c) {
   if (c->ft_ws) {
     FtState* s = state(c);
     (void)free_ws(c);
-    if (s->ws.sbase) (void)hipFree(s->ws.sbase);
     delete s;
     c->ft_ws = nullptr;
   }
@@ -432,8 +382,11 @@ extern "C" harli_status harli_lora_attach(harli_ctx* c, const harli_lora_cfg* cf
   if (cfg->rank != 8 && cfg->rank != 16 && cfg->rank != 32 && cfg->rank != 64)
     return fail(HARLI_ERR_INVALID, "lora_attach: rank must be 8, 16, 32 or 64, got %d", cfg->rank);
   if (cfg->targets == 0 || cfg->targets >= (1u << kTargets)) return fail(HARLI_ERR_INVALID, "lora_attach: bad target mask");
+  if (cfg->grad_headroom_log2 < 0 || cfg->grad_headroom_log2 > 24)
+    return fail(HARLI_ERR_INVALID, "lora_attach: grad_headroom_log2 %d outside 0..24", cfg->grad_headroom_log2);
   if (c->cfg.max_ft_tokens < 1) return fail(HARLI_ERR_STATE, "lora_attach: the context was created with max_ft_tokens = 0");
-  if (c->cfg.head_dim > 512) return fail(HARLI_ERR_INVALID, "lora_attach: head_dim %d above 512 is not supported", c->cfg.head_dim);
+  if (!ft_attn_supported(c->cfg.head_dim))
+    return fail(HARLI_ERR_INVALID, "lora_attach: the finetune attention kernels cover head_dim 64 and 128, got %d", c->cfg.head_dim);
   if (c->window) return fail(HARLI_ERR_STATE, "lora_attach: disable the weight window first");
   for (int l = 0; l < c->cfg.n_layers; ++l)
     for (int t = 0; t < kTargets; ++t)
@@ -455,7 +408,8 @@ extern "C" harli_status harli_lora_attach(harli_ctx* c, const harli_lora_cfg* cf
         HARLI_HIP(hipMalloc(&L.w16[t], nb));
         const int f32 = c->cfg.dtype == HARLI_F32 ? 1 : 0;
         BlockJobs jobs{};
-        jobs.half = kFtHalf ? 1 : 0;
+        jobs.half = 1;
+        jobs.flag = c->dw.err_flag;
         jobs.j[jobs.n++] = BlockJob{L.w[t], static_cast<bf*>(L.w16[t]), out, in, 0, f32};
         jobs.j[jobs.n++] = BlockJob{L.w[t], static_cast<bf*>(L.wt[t]), out, in, 1, f32};
         gemm2_block_jobs(jobs, nullptr);
@@ -486,6 +440,21 @@ extern "C" harli_status harli_lora_attach(harli_ctx* c, const harli_lora_cfg* cf
     HARLI_HIP(hipMemcpy(c->ones16, ones.data(), ones.size() * 2, hipMemcpyHostToDevice));
   }
   HARLI_HIP(hipDeviceSynchronize());
+  {  // a frozen weight that half cannot hold would be clamped in the private copies: refuse it here, by name
+    int flag = 0;
+    HARLI_HIP(hipMemcpy(&flag, c->dw.err_flag, sizeof(int), hipMemcpyDeviceToHost));
+    if (flag & 8) {
+      flag &= ~8;
+      HARLI_HIP(hipMemcpy(c->dw.err_flag, &flag, sizeof(int), hipMemcpyHostToDevice));
+      for (LayerDev& L : c->layers)
+        for (int t = 0; t < kTargets; ++t) {
+          if (L.wt[t]) (void)hipFree(L.wt[t]);
+          if (L.w16[t]) (void)hipFree(L.w16[t]);
+          L.wt[t] = L.w16[t] = nullptr;
+        }
+      return fail(HARLI_ERR_INVALID, "lora_attach: a frozen weight lies beyond the range of the 16-bit compute element (|w| > 65504)");
+    }
+  }
   if (!c->ft_ws) c->ft_ws = new FtState;
   {
     size_t nb = 0;
@@ -514,7 +483,7 @@ void finetune_device_bytes(const harli_ctx* c, size_t* weights, size_t* workspac
   if (!c->ft_ws) return;
   const FtState* fs = static_cast<const FtState*>(c->ft_ws);
   *weights = fs->weight_bytes;
-  *workspace = fs->ws.bytes + fs->ws.sbytes;
+  *workspace = fs->ws.bytes;
   *in_pool = fs->ws_in_pool ? 1 : 0;
 }
 }  // namespace harli
@@ -578,7 +547,7 @@ extern "C" harli_status harli_lora_fwd(harli_ctx* c, int32_t layer, const float*
   }
   char* bb = static_cast<char*>(sv->big.ptr);
   sv->x1 = (float*)(bb + pl.o_x1); sv->h = (bf*)(bb + pl.o_h); sv->q = (bf*)(bb + pl.o_q); sv->k = (bf*)(bb + pl.o_k);
-  sv->v = (bf*)(bb + pl.o_v); sv->P = (bf*)(bb + pl.o_P); sv->o = (bf*)(bb + pl.o_o); sv->h2 = (bf*)(bb + pl.o_h2);
+  sv->v = (bf*)(bb + pl.o_v); sv->o = (bf*)(bb + pl.o_o); sv->h2 = (bf*)(bb + pl.o_h2);
   sv->a = (bf*)(bb + pl.o_a); sv->u = (bf*)(bb + pl.o_u); sv->m = (bf*)(bb + pl.o_m);
 
 #define RUN(x)                          \
@@ -592,7 +561,7 @@ extern "C" harli_status harli_lora_fwd(harli_ctx* c, int32_t layer, const float*
 
   const int T = D.T;
   convert_adapters(c, L, true, st);
-  ft_rmsnorm_fwd(X, L.g1, sv->h, sv->rho1, T, D.H, m.rms_eps, st);
+  ft_rmsnorm_fwd(X, L.g1, sv->h, sv->rho1, T, D.H, m.rms_eps, c->dw.err_flag, st);
   proj_us_group(c, 0, 2, sv->h, T, sv, st);
   {  // q, k, v in one launch: three column blocks, each with its own weights, bias and adapter segments
     Gemm2Args g = wg_begin(c, T);
@@ -608,39 +577,10 @@ extern "C" harli_status harli_lora_fwd(harli_ctx* c, int32_t layer, const float*
     g.tiles_n = tq + 2 * tk;
     RUN(gemm2_launch(g, st));
   }
-  ft_rope(sv->q, T, S, D.nq, D.d, c->dw.inv_freq, false, st);
-  ft_rope(sv->k, T, S, D.nkv, D.d, c->dw.inv_freq, false, st);
+  ft_rope(sv->q, T, S, D.nq, D.d, c->dw.inv_freq, false, c->dw.err_flag, st);
+  ft_rope(sv->k, T, S, D.nkv, D.d, c->dw.inv_freq, false, c->dw.err_flag, st);
   ft_transpose_heads(sv->v, w.vT, B_f, S, D.nkv, D.d, st);
-  const long long SS = (long long)S * S;
-  const int batches = B_f * D.nq;
-  if (ft_attn_supported(D.d)) {
-    RUN(ft_attn_fwd(sv->q, sv->k, w.vT, sv->o, sv->lse, B_f, S, D.nq, D.nkv, D.d, st));
-  } else {
-    {  // scores[z][q][k] = q . k / sqrt(d), lower triangle only
-      GemmArgs g = plain_gemm(S, S);
-      g.nb1 = D.nkv; g.nb2 = D.G;
-      g.alpha = 1.f / std::sqrt((float)D.d);
-      g.causal = GEMM_OUT_LOWER;
-      add_seg(g, sv->q, D.QD, sv->k, D.KVD, D.d);
-      g.seg[0].a_bs0 = (long long)S * D.QD; g.seg[0].a_bs1 = (long long)D.G * D.d; g.seg[0].a_bs2 = D.d;
-      g.seg[0].b_bs0 = (long long)S * D.KVD; g.seg[0].b_bs1 = D.d; g.seg[0].b_bs2 = 0;
-      g.Cf = w.scores; g.ldcf = S;
-      g.cf_bs0 = (long long)D.nq * SS; g.cf_bs1 = (long long)D.G * SS; g.cf_bs2 = SS;
-      RUN(gemm_launch(g, batches, st));
-    }
-    ft_softmax_causal(w.scores, sv->P, sv->lse, batches, S, st);
-    {  // o = P . V
-      GemmArgs g = plain_gemm(S, D.d);
-      g.nb1 = D.nkv; g.nb2 = D.G;
-      g.causal = GEMM_K_UPTO_M;
-      add_seg(g, sv->P, S, w.vT, S, S);
-      g.seg[0].a_bs0 = (long long)D.nq * SS; g.seg[0].a_bs1 = (long long)D.G * SS; g.seg[0].a_bs2 = SS;
-      g.seg[0].b_bs0 = (long long)D.KVD * S; g.seg[0].b_bs1 = (long long)D.d * S; g.seg[0].b_bs2 = 0;
-      g.Cb = sv->o; g.ldcb = D.QD;
-      g.cb_bs0 = (long long)S * D.QD; g.cb_bs1 = (long long)D.G * D.d; g.cb_bs2 = D.d;
-      RUN(gemm_launch(g, batches, st));
-    }
-  }
+  RUN(ft_attn_fwd(sv->q, sv->k, w.vT, sv->o, sv->lse, B_f, S, D.nq, D.nkv, D.d, st));
   {  // x1 = X + o Wo^T
     proj_us_group(c, 3, 3, sv->o, T, sv, st);
     Gemm2Args g = wg_begin(c, T);
@@ -648,7 +588,7 @@ extern "C" harli_status harli_lora_fwd(harli_ctx* c, int32_t layer, const float*
     wg_out_f32(g, sv->x1, X, D.H);
     RUN(gemm2_launch(g, st));
   }
-  ft_rmsnorm_fwd(sv->x1, L.g2, sv->h2, sv->rho2, T, D.H, m.rms_eps, st);
+  ft_rmsnorm_fwd(sv->x1, L.g2, sv->h2, sv->rho2, T, D.H, m.rms_eps, c->dw.err_flag, st);
   proj_us_group(c, 4, 5, sv->h2, T, sv, st);
   {  // gate and up as one launch of interleaved pairs; the epilogue writes a, u and m = silu(a) * u
     Gemm2Args g = wg_begin(c, T);
@@ -705,9 +645,6 @@ extern "C" harli_status harli_lora_bwd(harli_ctx* c, int32_t layer, const float*
   s = window_acquire(c, layer, true, st);
   if (s != HARLI_OK) return s;
   const int T = D.T;
-  const long long SS = (long long)S * S;
-  const int batches = B_f * D.nq;
-  const float scale = 1.f / std::sqrt((float)D.d);
 
 #define RUNB(x)                         \
   do {                                  \
@@ -717,7 +654,7 @@ extern "C" harli_status harli_lora_bwd(harli_ctx* c, int32_t layer, const float*
 
   // ---- FFN ----
   convert_adapters(c, L, false, st);
-  ft_make_scale(dY, (long long)T * D.H, w.scale, st);
+  ft_make_scale(dY, (long long)T * D.H, w.scale, 8 - c->lora.grad_headroom_log2, st);
   ft_f32_to_e(dY, w.dyb, (long long)T * D.H, w.scale, st);  // every gradient below carries the factor sigma
   const int r = c->lora.rank;
   {  // dm = dy Wd (+ gs A_d^T) -> da, du
@@ -752,7 +689,7 @@ extern "C" harli_status harli_lora_bwd(harli_ctx* c, int32_t layer, const float*
     wg_out_f32(g, w.dh2, nullptr, D.H);
     RUNB(gemm2_launch(g, st));
   }
-  ft_rmsnorm_bwd(w.dh2, sv->x1, sv->rho2, L.g2, dY, w.dx1, w.dx1b, T, D.H, w.scale, nullptr, st);
+  ft_rmsnorm_bwd(w.dh2, sv->x1, sv->rho2, L.g2, dY, w.dx1, w.dx1b, T, D.H, w.scale, nullptr, c->dw.err_flag, st);
   // ---- attention output projection ----
   {  // do = dx1 Wo
     Gemm2Args g = wg_begin(c, T);
@@ -766,99 +703,20 @@ extern "C" harli_status harli_lora_bwd(harli_ctx* c, int32_t layer, const float*
     RUNB(gemm2_launch(g, st));
   }
   // ---- attention ----
-  if (!ft_attn_supported(D.d)) ft_attn_delta(w.dob, sv->o, w.delta, B_f, S, D.nq, D.d, st);  // the fused dQ kernel makes its own
-  auto qlike = [&](GemmSeg& sg, bool is_a) {  // operand laid out like q: [T, n_q*d], batch (b, c, g)
-    (is_a ? sg.a_bs0 : sg.b_bs0) = (long long)S * D.QD;
-    (is_a ? sg.a_bs1 : sg.b_bs1) = (long long)D.G * D.d;
-    (is_a ? sg.a_bs2 : sg.b_bs2) = D.d;
-  };
-  auto klike = [&](GemmSeg& sg, bool is_a) {  // like k / v: [T, n_kv*d]
-    (is_a ? sg.a_bs0 : sg.b_bs0) = (long long)S * D.KVD;
-    (is_a ? sg.a_bs1 : sg.b_bs1) = D.d;
-    (is_a ? sg.a_bs2 : sg.b_bs2) = 0;
-  };
-  auto sslike = [&](GemmSeg& sg) {  // A operand [Z][S][S]
-    sg.a_bs0 = (long long)D.nq * SS; sg.a_bs1 = (long long)D.G * SS; sg.a_bs2 = SS;
-  };
-  auto qT_like = [&](GemmSeg& sg) {  // B operand [Bf][n_q*d][S]
-    sg.b_bs0 = (long long)D.QD * S; sg.b_bs1 = (long long)D.G * D.d * S; sg.b_bs2 = (long long)D.d * S;
-  };
-  auto ss_out = [&](GemmArgs& g, float* C) {
-    g.Cf = C; g.ldcf = S;
-    g.cf_bs0 = (long long)D.nq * SS; g.cf_bs1 = (long long)D.G * SS; g.cf_bs2 = SS;
-  };
-  auto q_out = [&](GemmArgs& g, bf* C) {
-    g.Cb = C; g.ldcb = D.QD;
-    g.cb_bs0 = (long long)S * D.QD; g.cb_bs1 = (long long)D.G * D.d; g.cb_bs2 = D.d;
-  };
   ft_transpose_heads(w.dob, w.doT, B_f, S, D.nq, D.d, st);
   ft_transpose_heads(sv->q, w.qT, B_f, S, D.nq, D.d, st);
   ft_transpose_heads(sv->k, w.kT, B_f, S, D.nkv, D.d, st);
-  if (ft_attn_supported(D.d)) {
-    RUNB(ft_attn_bwd(sv->q, sv->k, sv->v, sv->o, w.qT, w.kT, w.dob, w.doT, sv->lse, w.delta, w.dq, w.dkq, w.dvq, B_f, S, D.nq,
-                     D.nkv, D.d, st));
-  } else {
-    {  // dP = dO V^T (lower)
-      GemmArgs g = plain_gemm(S, S);
-      g.nb1 = D.nkv; g.nb2 = D.G; g.causal = GEMM_OUT_LOWER;
-      add_seg(g, w.dob, D.QD, sv->v, D.KVD, D.d);
-      qlike(g.seg[0], true); klike(g.seg[0], false);
-      ss_out(g, w.dP);
-      RUNB(gemm_launch(g, batches, st));
-    }
-    ft_attn_ds(sv->P, w.dP, w.delta, w.dS, batches, S, st);
-    {  // ST = K Q^T / sqrt(d) (upper, rows = keys)
-      GemmArgs g = plain_gemm(S, S);
-      g.nb1 = D.nkv; g.nb2 = D.G; g.causal = GEMM_OUT_UPPER; g.alpha = scale;
-      add_seg(g, sv->k, D.KVD, sv->q, D.QD, D.d);
-      klike(g.seg[0], true); qlike(g.seg[0], false);
-      ss_out(g, w.ST);
-      RUNB(gemm_launch(g, batches, st));
-    }
-    {  // dPT = V dO^T (upper)
-      GemmArgs g = plain_gemm(S, S);
-      g.nb1 = D.nkv; g.nb2 = D.G; g.causal = GEMM_OUT_UPPER;
-      add_seg(g, sv->v, D.KVD, w.dob, D.QD, D.d);
-      klike(g.seg[0], true); qlike(g.seg[0], false);
-      ss_out(g, w.dPT);
-      RUNB(gemm_launch(g, batches, st));
-    }
-    ft_attn_ds_t(w.ST, w.dPT, sv->lse, w.delta, w.PT, w.dST, batches, S, st);
-    {  // dV (per query head) = PT dO
-      GemmArgs g = plain_gemm(S, D.d);
-      g.nb1 = D.nkv; g.nb2 = D.G; g.causal = GEMM_K_FROM_M;
-      add_seg(g, w.PT, S, w.doT, S, S);
-      sslike(g.seg[0]); qT_like(g.seg[0]);
-      q_out(g, w.dvq);
-      RUNB(gemm_launch(g, batches, st));
-    }
-    {  // dK (per query head) = dST Q / sqrt(d)
-      GemmArgs g = plain_gemm(S, D.d);
-      g.nb1 = D.nkv; g.nb2 = D.G; g.causal = GEMM_K_FROM_M; g.alpha = scale;
-      add_seg(g, w.dST, S, w.qT, S, S);
-      sslike(g.seg[0]); qT_like(g.seg[0]);
-      q_out(g, w.dkq);
-      RUNB(gemm_launch(g, batches, st));
-    }
-    {  // dQ = dS K / sqrt(d)
-      GemmArgs g = plain_gemm(S, D.d);
-      g.nb1 = D.nkv; g.nb2 = D.G; g.causal = GEMM_K_UPTO_M; g.alpha = scale;
-      add_seg(g, w.dS, S, w.kT, S, S);
-      sslike(g.seg[0]);
-      g.seg[0].b_bs0 = (long long)D.KVD * S; g.seg[0].b_bs1 = (long long)D.d * S; g.seg[0].b_bs2 = 0;
-      q_out(g, w.dq);
-      RUNB(gemm_launch(g, batches, st));
-    }
-  }
+  RUNB(ft_attn_bwd(sv->q, sv->k, sv->v, sv->o, w.qT, w.kT, w.dob, w.doT, sv->lse, w.delta, w.dq, w.dkq, w.dvq, B_f, S, D.nq,
+                   D.nkv, D.d, c->dw.err_flag, st));
   const bf *dk = w.dkq, *dv = w.dvq;
   if (D.G > 1) {
-    ft_sum_groups(w.dkq, w.dk, T, D.nkv, D.G, D.d, st);
-    ft_sum_groups(w.dvq, w.dv, T, D.nkv, D.G, D.d, st);
+    ft_sum_groups(w.dkq, w.dk, T, D.nkv, D.G, D.d, c->dw.err_flag, st);
+    ft_sum_groups(w.dvq, w.dv, T, D.nkv, D.G, D.d, c->dw.err_flag, st);
     dk = w.dk;
     dv = w.dv;
   }
-  ft_rope(w.dq, T, S, D.nq, D.d, c->dw.inv_freq, true, st);
-  ft_rope(const_cast<bf*>(dk), T, S, D.nkv, D.d, c->dw.inv_freq, true, st);
+  ft_rope(w.dq, T, S, D.nq, D.d, c->dw.inv_freq, true, c->dw.err_flag, st);
+  ft_rope(const_cast<bf*>(dk), T, S, D.nkv, D.d, c->dw.inv_freq, true, c->dw.err_flag, st);
   // ---- q, k, v projections ----
   {  // dh = dq Wq + dk Wk + dv Wv
     Gemm2Args g = wg_begin(c, T);
@@ -878,7 +736,7 @@ extern "C" harli_status harli_lora_bwd(harli_ctx* c, int32_t layer, const float*
     wg_out_f32(g, w.dh, nullptr, D.H);
     RUNB(gemm2_launch(g, st));
   }
-  ft_rmsnorm_bwd(w.dh, sv->X, sv->rho1, L.g1, w.dx1, dX, nullptr, T, D.H, nullptr, w.scale + 1, st);
+  ft_rmsnorm_bwd(w.dh, sv->X, sv->rho1, L.g1, w.dx1, dX, nullptr, T, D.H, nullptr, w.scale + 1, c->dw.err_flag, st);
   HARLI_HIP(hipGetLastError());
   s = window_release(c, layer, true, st);
   release_saved(c, sv, st, true);

@@ -22,5 +22,5 @@ harli_status ft_attn_fwd(const bf* q, const bf* k, const bf* vT, bf* o, float* l
 //   dP = dO v^T.  dkq and dvq are per QUERY head ([Bf*S, n_q*d]); the caller sums them over the heads of a group.
 harli_status ft_attn_bwd(const bf* q, const bf* k, const bf* v, const bf* o, const bf* qT, const bf* kT, const bf* dO,
                          const bf* dOT, const float* lse, float* delta, bf* dq, bf* dkq, bf* dvq, int Bf, int S, int n_q,
-                         int n_kv, int d, hipStream_t st);
+                         int n_kv, int d, int* flag, hipStream_t st);
 }  // namespace harli

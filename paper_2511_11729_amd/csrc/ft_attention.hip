@@ -28,10 +28,7 @@ typedef unsigned __attribute__((ext_vector_type(2))) u32x2;
 constexpr float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
 
 __device__ __forceinline__ f32x16 mma32(const u32x4& a, const u32x4& b, f32x16 c) {
-  if constexpr (kFtHalf)
-    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
-  else
-    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+  return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
 }
 
 // A fragment of a row-major LDS tile (row stride RS bytes): rows sub*32 + lane%32, k = 16j + 8h .. +7
@@ -178,7 +175,7 @@ __global__ void __launch_bounds__(256, 2) k_attn_bwd_dq(const bf* __restrict__ q
                                                      const bf* __restrict__ kT, const bf* __restrict__ dO,
                                                      const bf* __restrict__ o, const float* __restrict__ lse,
                                                      float* __restrict__ delta, bf* __restrict__ dq, int S, int nq, int nkv,
-                                                     float scale, float scale_log2) {
+                                                     float scale, float scale_log2, int* flag) {
   constexpr int RS = D * 2 + 16, NJ = D / 16, NE = D / 32, CPT = D / 32;
   extern __shared__ __align__(16) char smem[];
   char* sK = smem;                  // [KB][D]
@@ -276,12 +273,14 @@ __global__ void __launch_bounds__(256, 2) k_attn_bwd_dq(const bf* __restrict__ q
 #undef DQ_FETCH
   if (qrow < S) {
     bf* op = dq + ((long long)b * S + qrow) * QD + head * D;
+    bool over = false;
 #pragma unroll
     for (int e = 0; e < NE; ++e)
 #pragma unroll
       for (int g = 0; g < 4; ++g)
-        *reinterpret_cast<u32x2*>(op + e * 32 + 8 * g + 4 * h) =
-            u32x2{PACK2(dQ[e][4 * g] * scale, dQ[e][4 * g + 1] * scale), PACK2(dQ[e][4 * g + 2] * scale, dQ[e][4 * g + 3] * scale)};
+        *reinterpret_cast<u32x2*>(op + e * 32 + 8 * g + 4 * h) = u32x2{PACK2G(dQ[e][4 * g] * scale, dQ[e][4 * g + 1] * scale, over),
+                                                                       PACK2G(dQ[e][4 * g + 2] * scale, dQ[e][4 * g + 3] * scale, over)};
+    elem_flag(over, flag);
   }
 }
 
@@ -295,7 +294,7 @@ __global__ void __launch_bounds__(256) k_attn_bwd_dkv(const bf* __restrict__ q, 
                                                       const bf* __restrict__ dOT, const float* __restrict__ lse,
                                                       const float* __restrict__ delta, bf* __restrict__ dkq,
                                                       bf* __restrict__ dvq, int S, int nq, int nkv, float scale,
-                                                      float scale_log2) {
+                                                      float scale_log2, int* flag) {
   constexpr int RS = D * 2 + 16, NJ = D / 16, NE = D / 32, CPT = D / 32;
   extern __shared__ __align__(16) char smem[];
   char* sQ = smem;                              // [KB][D] queries x head_dim
@@ -401,16 +400,18 @@ __global__ void __launch_bounds__(256) k_attn_bwd_dkv(const bf* __restrict__ q, 
 #undef KV_FETCH
   if (krow < S) {
     const long long ro = ((long long)b * S + krow) * QD + head * D;
+    bool over = false;
 #pragma unroll
     for (int e = 0; e < NE; ++e)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         const int eo = e * 32 + 8 * g + 4 * h;
         *reinterpret_cast<u32x2*>(dvq + ro + eo) =
-            u32x2{PACK2(dV[e][4 * g], dV[e][4 * g + 1]), PACK2(dV[e][4 * g + 2], dV[e][4 * g + 3])};
-        *reinterpret_cast<u32x2*>(dkq + ro + eo) =
-            u32x2{PACK2(dK[e][4 * g] * scale, dK[e][4 * g + 1] * scale), PACK2(dK[e][4 * g + 2] * scale, dK[e][4 * g + 3] * scale)};
+            u32x2{PACK2G(dV[e][4 * g], dV[e][4 * g + 1], over), PACK2G(dV[e][4 * g + 2], dV[e][4 * g + 3], over)};
+        *reinterpret_cast<u32x2*>(dkq + ro + eo) = u32x2{PACK2G(dK[e][4 * g] * scale, dK[e][4 * g + 1] * scale, over),
+                                                         PACK2G(dK[e][4 * g + 2] * scale, dK[e][4 * g + 3] * scale, over)};
       }
+    elem_flag(over, flag);
   }
 }
 
@@ -459,21 +460,21 @@ harli_status ft_attn_fwd(const bf* q, const bf* k, const bf* vT, bf* o, float* l
 
 harli_status ft_attn_bwd(const bf* q, const bf* k, const bf* v, const bf* o, const bf* qT, const bf* kT, const bf* dO,
                          const bf* dOT, const float* lse, float* delta, bf* dq, bf* dkq, bf* dvq, int Bf, int S, int n_q,
-                         int n_kv, int d, hipStream_t st) {
+                         int n_kv, int d, int* flag, hipStream_t st) {
   harli_status s = check_shape(Bf, S, n_q, n_kv, d);
   if (s != HARLI_OK) return s;
   const dim3 grid((S + 127) / 128, Bf * n_q), blk(256);
   const float sc = 1.f / sqrtf((float)d), sl2 = kLog2e * sc;
   if (d == 128) {
     if ((s = set_attrs<128>()) != HARLI_OK) return s;
-    hipLaunchKernelGGL(k_attn_bwd_dq<128>, grid, blk, dq_lds<128>(), st, q, k, v, kT, dO, o, lse, delta, dq, S, n_q, n_kv, sc, sl2);
+    hipLaunchKernelGGL(k_attn_bwd_dq<128>, grid, blk, dq_lds<128>(), st, q, k, v, kT, dO, o, lse, delta, dq, S, n_q, n_kv, sc, sl2, flag);
     hipLaunchKernelGGL(k_attn_bwd_dkv<128>, grid, blk, dkv_lds<128>(), st, q, k, v, qT, dO, dOT, lse, delta, dkq, dvq, S, n_q,
-                       n_kv, sc, sl2);
+                       n_kv, sc, sl2, flag);
   } else {
     if ((s = set_attrs<64>()) != HARLI_OK) return s;
-    hipLaunchKernelGGL(k_attn_bwd_dq<64>, grid, blk, dq_lds<64>(), st, q, k, v, kT, dO, o, lse, delta, dq, S, n_q, n_kv, sc, sl2);
+    hipLaunchKernelGGL(k_attn_bwd_dq<64>, grid, blk, dq_lds<64>(), st, q, k, v, kT, dO, o, lse, delta, dq, S, n_q, n_kv, sc, sl2, flag);
     hipLaunchKernelGGL(k_attn_bwd_dkv<64>, grid, blk, dkv_lds<64>(), st, q, k, v, qT, dO, dOT, lse, delta, dkq, dvq, S, n_q,
-                       n_kv, sc, sl2);
+                       n_kv, sc, sl2, flag);
   }
   return HARLI_OK;
 }

@@ -10,20 +10,18 @@ namespace harli {
 typedef unsigned short bf;
 
 // h = bf16(x * rho * g), rho = rsqrt(mean x^2 + eps) (also stored)
-void ft_rmsnorm_fwd(const float* x, const float* g, bf* h, float* rho, int T, int H, float eps, hipStream_t st);
+void ft_rmsnorm_fwd(const float* x, const float* g, bf* h, float* rho, int T, int H, float eps, int* flag, hipStream_t st);
 // dx = dres + rho * (dh*g - xhat * mean(dh*g*xhat)), xhat = x*rho;  dh is fp32
 // res_mul / out_mul: optional device scalars: dx = out_mul * (dres * res_mul + ...); dres may be NULL (taken as zero)
 // dx16: optional 16-bit copy of dx (the next GEMM's operand)
 void ft_rmsnorm_bwd(const float* dh, const float* x, const float* rho, const float* g, const float* dres, float* dx, bf* dx16,
-                    int T, int H, const float* res_mul, const float* out_mul, hipStream_t st);
+                    int T, int H, const float* res_mul, const float* out_mul, int* flag, hipStream_t st);
 // rotary embedding in place on [T, heads*d] bf16, position = t % S; inverse rotates by the negative angle
-void ft_rope(bf* t, int T, int S, int heads, int d, const double* inv_freq, bool inverse, hipStream_t st);
-// causal softmax of fp32 scores [Z][S][S] (already scaled) -> P bf16 (zeros above the diagonal), lse [Z][S] (natural log)
-void ft_softmax_causal(const float* sc, bf* P, float* lse, int Z, int S, hipStream_t st);
+void ft_rope(bf* t, int T, int S, int heads, int d, const double* inv_freq, bool inverse, int* flag, hipStream_t st);
 // y = 16-bit(x * *scale)   (scale: optional device scalar)
 void ft_f32_to_e(const float* x, bf* y, long long n, const float* scale, hipStream_t st);
-// scale[0] = sigma = power of two bringing max|x| to 2^8, scale[1] = 1/sigma (scale[2] is scratch)
-void ft_make_scale(const float* x, long long n, float* scale, hipStream_t st);
+// scale[0] = sigma = power of two bringing max|x| to 2^target_log2, scale[1] = 1/sigma (scale[2] is scratch)
+void ft_make_scale(const float* x, long long n, float* scale, int target_log2, hipStream_t st);
 // bf16 storage -> compute element: plain copy and [R][C] -> [C][R] transpose
 void ft_from_bf16(const bf* in, bf* out, long long n, hipStream_t st);
 void ft_transpose_from_bf16(const bf* in, bf* out, int R, int C, hipStream_t st);
@@ -38,6 +36,7 @@ struct FtConvJob {
 struct FtConvJobs {
   FtConvJob j[16];
   int n;
+  int* flag;  // device int or null: bit 8 is set when a value lay beyond the compute element's range
 };
 void ft_convert_jobs(const FtConvJobs& jobs, hipStream_t st);
 // batched transpose: in [Z][R][C] (row stride ldi, batch stride bsi) -> out [Z][C][R]
@@ -45,17 +44,8 @@ void ft_transpose(const bf* in, bf* out, int Z, int R, int C, long long ldi, lon
                   hipStream_t st);
 // head-wise transpose of a [T, heads*d] tensor into [Bf][heads][d][S]
 void ft_transpose_heads(const bf* in, bf* out, int Bf, int S, int heads, int d, hipStream_t st);
-// delta[z][q] = sum_e dO[b*S+q][h*d+e] * O[...], z = b*heads + h
-void ft_attn_delta(const bf* dO, const bf* O, float* delta, int Bf, int S, int heads, int d, hipStream_t st);
-// dS = P * (dP - delta[q]) for k <= q, else 0;  P bf16 [Z][S][S], dP fp32
-void ft_attn_ds(const bf* P, const float* dP, const float* delta, bf* dS, int Z, int S, hipStream_t st);
-// transposed orientation [Z][k][q]: PT = exp(ST - lse[q]), dST = PT * (dPT - delta[q]) for q >= k, else 0
-void ft_attn_ds_t(const float* ST, const float* dPT, const float* lse, const float* delta, bf* PT, bf* dST, int Z, int S,
-                  hipStream_t st);
-// skinny NT GEMM: C[M, N] = alpha * X[M, K] . Bm[N, K]^T, N <= 64 and N % 16 == 0 after padding by the caller's layout
-void ft_skinny_nt(const bf* X, long long ldx, const bf* Bm, long long ldb, bf* C, long long ldc, int M, int N, int K,
-                  float alpha, hipStream_t st);
-// Several such products with the same M and alpha in one launch (job = blockIdx.y).
+// skinny NT GEMMs: C[M, N] = alpha * X[M, K] . Bm[N, K]^T, N <= 64 and N % 16 == 0 after padding by the caller's layout;
+// several such products with the same M and alpha in one launch (job = blockIdx.y).
 constexpr int kSkinnyMaxJobs = 4;
 struct SkinnyNtJob {
   const bf* X;
@@ -70,7 +60,7 @@ struct SkinnyNtJobs {
   int n;
   SkinnyNtJob j[kSkinnyMaxJobs];
 };
-void ft_skinny_nt_multi(const SkinnyNtJobs& jobs, int M, float alpha, hipStream_t st);
+void ft_skinny_nt_multi(const SkinnyNtJobs& jobs, int M, float alpha, int* flag, hipStream_t st);
 // G[j*sj + r*sr] += out_mul * sum_t X[t][j] * U[t][r];  X [T, J] and U [T, R] 16-bit, R in {8, 16, 32, 64}, J even,
 // one of sj, sr equal to 1.  `part` is scratch of ft_lora_grad_ws_floats(J, R) floats; G is read and written
 // without atomics, so no other work may update it concurrently.
@@ -98,5 +88,5 @@ void ft_lora_grad_multi(LoraGradJobs& jobs, int T, int R, const float* out_mul, 
 void ft_lora_grad(const bf* X, long long ldx, const bf* U, long long ldu, float* G, long long sj, long long sr, int T, int J,
                   int R, const float* out_mul, float* part, hipStream_t st);
 // sum GQA query-head groups: dk[T][n_kv*d] = sum_g dkq[T][(c*G+g)*d + e]
-void ft_sum_groups(const bf* in, bf* out, int T, int n_kv, int G, int d, hipStream_t st);
+void ft_sum_groups(const bf* in, bf* out, int T, int n_kv, int G, int d, int* flag, hipStream_t st);
 }  // namespace harli

@@ -21,7 +21,7 @@ __device__ __forceinline__ float block_sum_256(float v, float* sh) {
 }
 
 // ---------------------------------------------------------------- RMSNorm
-__global__ void __launch_bounds__(256) k_rmsnorm_fwd(const float* x, const float* g, bf* h, float* rho, int H, float eps) {
+__global__ void __launch_bounds__(256) k_rmsnorm_fwd(const float* x, const float* g, bf* h, float* rho, int H, float eps, int* flag) {
   __shared__ float sh[4];
   const int t = blockIdx.x, tid = threadIdx.x;
   const float* xr = x + (size_t)t * H;
@@ -33,17 +33,19 @@ __global__ void __launch_bounds__(256) k_rmsnorm_fwd(const float* x, const float
   s2 = block_sum_256(s2, sh);
   const float r = rsqrtf(s2 / (float)H + eps);
   if (tid == 0) rho[t] = r;
+  bool over = false;
   for (int k = tid * 4; k < H; k += 1024) {
     const float4 v = *reinterpret_cast<const float4*>(xr + k);
     const float4 gg = *reinterpret_cast<const float4*>(g + k);
     *reinterpret_cast<uint2*>(h + (size_t)t * H + k) =
-        make_uint2(PACK2(v.x * r * gg.x, v.y * r * gg.y), PACK2(v.z * r * gg.z, v.w * r * gg.w));
+        make_uint2(PACK2G(v.x * r * gg.x, v.y * r * gg.y, over), PACK2G(v.z * r * gg.z, v.w * r * gg.w, over));
   }
+  elem_flag(over, flag);
 }
 
 __global__ void __launch_bounds__(256) k_rmsnorm_bwd(const float* dh, const float* x, const float* rho, const float* g,
                                                      const float* dres, float* dx, bf* dx16, int H, const float* res_mul,
-                                                     const float* out_mul) {
+                                                     const float* out_mul, int* flag) {
   __shared__ float sh[4];
   const int t = blockIdx.x, tid = threadIdx.x;
   const float r = rho[t];
@@ -59,6 +61,7 @@ __global__ void __launch_bounds__(256) k_rmsnorm_bwd(const float* dh, const floa
   }
   dot = block_sum_256(dot, sh);
   const float c = dot * r * r / (float)H;  // mean(dh*g*xhat) * rho, with xhat = x * rho
+  bool over = false;
   for (int k = tid * 4; k < H; k += 1024) {
     const float4 v = *reinterpret_cast<const float4*>(xr + k);
     const float4 d = *reinterpret_cast<const float4*>(dr + k);
@@ -70,8 +73,9 @@ __global__ void __launch_bounds__(256) k_rmsnorm_bwd(const float* dh, const floa
     o.z = om * (rs.z * rm + r * (d.z * gg.z - v.z * c));
     o.w = om * (rs.w * rm + r * (d.w * gg.w - v.w * c));
     *reinterpret_cast<float4*>(dx + (size_t)t * H + k) = o;
-    if (dx16) *reinterpret_cast<uint2*>(dx16 + (size_t)t * H + k) = make_uint2(PACK2(o.x, o.y), PACK2(o.z, o.w));
+    if (dx16) *reinterpret_cast<uint2*>(dx16 + (size_t)t * H + k) = make_uint2(PACK2G(o.x, o.y, over), PACK2G(o.z, o.w, over));
   }
+  elem_flag(over, flag);
 }
 
 // ---------------------------------------------------------------- rotary embedding, pairs (i, i + d/2)
@@ -80,7 +84,7 @@ __global__ void __launch_bounds__(256) k_rmsnorm_bwd(const float* dh, const floa
 // adjacent pairs with two 16-byte loads and stores when d/2 is a multiple of 8 (rows are 16-byte aligned then:
 // heads*d is a multiple of 8); other head sizes take the pair-at-a-time loop.
 constexpr int kRopeMaxHalf = 256;
-__global__ void __launch_bounds__(256) k_rope(bf* x, int S, int heads, int d, const double* inv_freq, float sign) {
+__global__ void __launch_bounds__(256) k_rope(bf* x, int S, int heads, int d, const double* inv_freq, float sign, int* flag) {
   __shared__ float cs_[kRopeMaxHalf], sn_[kRopeMaxHalf];
   const int t = blockIdx.x, half = d >> 1;
   const double pos = (double)(t % S);
@@ -94,6 +98,7 @@ __global__ void __launch_bounds__(256) k_rope(bf* x, int S, int heads, int d, co
   }
   __syncthreads();
   bf* row = x + (size_t)t * heads * d;
+  bool over = false;
   if ((half & 7) == 0) {
     const int per_head = half >> 3;
     for (int idx = threadIdx.x; idx < heads * per_head; idx += 256) {
@@ -109,9 +114,12 @@ __global__ void __launch_bounds__(256) k_rope(bf* x, int S, int heads, int d, co
         ol[e] = lo[e] * cs - hi[e] * sn;
         oh[e] = hi[e] * cs + lo[e] * sn;
       }
-      *reinterpret_cast<uint4*>(p) = make_uint4(PACK2(ol[0], ol[1]), PACK2(ol[2], ol[3]), PACK2(ol[4], ol[5]), PACK2(ol[6], ol[7]));
-      *reinterpret_cast<uint4*>(p + half) = make_uint4(PACK2(oh[0], oh[1]), PACK2(oh[2], oh[3]), PACK2(oh[4], oh[5]), PACK2(oh[6], oh[7]));
+      *reinterpret_cast<uint4*>(p) = make_uint4(PACK2G(ol[0], ol[1], over), PACK2G(ol[2], ol[3], over), PACK2G(ol[4], ol[5], over),
+                                                PACK2G(ol[6], ol[7], over));
+      *reinterpret_cast<uint4*>(p + half) = make_uint4(PACK2G(oh[0], oh[1], over), PACK2G(oh[2], oh[3], over),
+                                                       PACK2G(oh[4], oh[5], over), PACK2G(oh[6], oh[7], over));
     }
+    elem_flag(over, flag);
     return;
   }
   for (int idx = threadIdx.x; idx < heads * half; idx += 256) {
@@ -119,29 +127,10 @@ __global__ void __launch_bounds__(256) k_rope(bf* x, int S, int heads, int d, co
     const float cs = cs_[i], sn = sn_[i];
     bf* p = row + hh * d + i;
     const float lo = E2F(p[0]), hi = E2F(p[half]);
-    p[0] = F2E(lo * cs - hi * sn);
-    p[half] = F2E(hi * cs + lo * sn);
+    p[0] = F2EG(lo * cs - hi * sn, over);
+    p[half] = F2EG(hi * cs + lo * sn, over);
   }
-}
-
-// ---------------------------------------------------------------- causal softmax, one wave per row
-__global__ void __launch_bounds__(256) k_softmax_causal(const float* sc, bf* P, float* lse, int S, long long rows) {
-  const long long row = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (row >= rows) return;
-  const int lane = threadIdx.x & 63;
-  const int q = (int)(row % S);
-  const float* s = sc + row * S;
-  float mx = -INFINITY;
-  for (int k = lane; k <= q; k += 64) mx = fmaxf(mx, s[k]);
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
-  float sum = 0.f;
-  for (int k = lane; k <= q; k += 64) sum += __expf(s[k] - mx);
-  sum = wave_sum(sum);
-  const float inv = 1.f / sum;
-  bf* p = P + row * S;
-  for (int k = lane; k < S; k += 64) p[k] = (k <= q) ? F2E(__expf(s[k] - mx) * inv) : (bf)0;
-  if (lane == 0) lse[row] = mx + __logf(sum);
+  elem_flag(over, flag);
 }
 
 // ---------------------------------------------------------------- transposes (64 x 64 tiles through LDS)
@@ -191,13 +180,13 @@ __global__ void __launch_bounds__(256) k_amax(const float* x, long long n4, unsi
     atomicMax(amax_bits, __float_as_uint(fmaxf(fmaxf(wmax[0], wmax[1]), fmaxf(wmax[2], wmax[3]))));  // non-negative floats order like their bits
 }
 __global__ void k_scale_reset(unsigned* amax_bits) { *amax_bits = 0u; }
-__global__ void k_scale_make(const unsigned* amax_bits, float* scale) {
+__global__ void k_scale_make(const unsigned* amax_bits, float* scale, int target_log2) {
   const float a = __uint_as_float(*amax_bits);
   float sg = 1.f;
   if (a > 0.f && a < INFINITY) {
     int e;
     frexpf(a, &e);                       // a = f * 2^e, f in [0.5, 1)
-    sg = ldexpf(1.f, min(max(8 - e, -100), 100));
+    sg = ldexpf(1.f, min(max(target_log2 - e, -100), 100));
   }
   scale[0] = sg;
   scale[1] = 1.f / sg;
@@ -210,71 +199,15 @@ __global__ void __launch_bounds__(256) k_f32_to_e_scaled(const float* x, bf* y, 
   reinterpret_cast<uint2*>(y)[i] = make_uint2(PACK2(v.x * sg, v.y * sg), PACK2(v.z * sg, v.w * sg));
 }
 
-// ---------------------------------------------------------------- attention backward helpers
-__global__ void __launch_bounds__(256) k_attn_delta(const bf* dO, const bf* O, float* delta, int Bf, int S, int heads, int d) {
-  // one wave per (token, head)
-  const long long idx = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
-  const long long total = (long long)Bf * S * heads;
-  if (idx >= total) return;
-  const int lane = threadIdx.x & 63;
-  const long long t = idx / heads;
-  const int h = (int)(idx - t * heads);
-  const bf* a = dO + t * heads * d + h * d;
-  const bf* b = O + t * heads * d + h * d;
-  float s = 0.f;
-  for (int e = lane; e < d; e += 64) s += E2F(a[e]) * E2F(b[e]);
-  s = wave_sum(s);
-  if (lane == 0) {
-    const long long bb = t / S, q = t - bb * S;
-    delta[(bb * heads + h) * S + q] = s;
-  }
-}
-
-__global__ void __launch_bounds__(256) k_attn_ds(const bf* P, const float* dP, const float* delta, bf* dS, int S, long long rows) {
-  const long long row = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (row >= rows) return;
-  const int lane = threadIdx.x & 63;
-  const int q = (int)(row % S);
-  const float dl = delta[row];
-  for (int k = lane; k < S; k += 64)
-    dS[row * S + k] = (k <= q) ? F2E(E2F(P[row * S + k]) * (dP[row * S + k] - dl)) : (bf)0;
-}
-
-__global__ void __launch_bounds__(256) k_attn_ds_t(const float* ST, const float* dPT, const float* lse, const float* delta,
-                                                   bf* PT, bf* dST, int S, long long rows) {
-  // row = (z, key index); columns are query positions
-  const long long row = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (row >= rows) return;
-  const int lane = threadIdx.x & 63;
-  const long long z = row / S;
-  const int kk = (int)(row - z * S);
-  const float* l = lse + z * S;
-  const float* dl = delta + z * S;
-  for (int q = lane; q < S; q += 64) {
-    bf p = 0, ds = 0;
-    if (q >= kk) {
-      const float pf = __expf(ST[row * S + q] - l[q]);
-      p = F2E(pf);
-      ds = F2E(pf * (dPT[row * S + q] - dl[q]));
-    }
-    PT[row * S + q] = p;
-    dST[row * S + q] = ds;
-  }
-}
-
 // ---------------------------------------------------------------- skinny NT GEMM (LoRA down-projection x.A and dy.B^T)
 // Workgroup = 16 rows of X, 8 waves split K, one 16x16x32 MFMA column tile per 16 outputs.  Full 32-wide K steps are
 // loaded four at a time, unconditionally; only a last partial step (K % 32) masks its operands.
 typedef unsigned __attribute__((ext_vector_type(4))) u32x4;  // native vector: arrays of it stay in registers
 __device__ __forceinline__ f32x4 mma16(const u32x4& a, const u32x4& b, f32x4 c) {
-#if HARLI_FT_HALF
   return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
-#else
-  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
-#endif
 }
 template <int NT>
-__global__ void __launch_bounds__(512) k_skinny_nt(SkinnyNtJobs jobs, int M, float alpha) {
+__global__ void __launch_bounds__(512) k_skinny_nt(SkinnyNtJobs jobs, int M, float alpha, int* flag) {
   const SkinnyNtJob& jb = jobs.j[blockIdx.y];
   const bf* X = jb.X;
   const bf* Bm = jb.Bm;
@@ -327,6 +260,7 @@ __global__ void __launch_bounds__(512) k_skinny_nt(SkinnyNtJobs jobs, int M, flo
   for (int t = 0; t < NT; ++t) red[wave][t][lane] = make_float4(acc[t][0], acc[t][1], acc[t][2], acc[t][3]);
   __syncthreads();
   if (wave == 0) {
+    bool over = false;
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
       float4 sm = red[0][t][lane];
@@ -341,9 +275,10 @@ __global__ void __launch_bounds__(512) k_skinny_nt(SkinnyNtJobs jobs, int M, flo
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         const int m = m0 + 4 * g + e;
-        if (m < M && n < N) C[(long long)m * ldc + n] = F2E(v[e] * alpha);
+        if (m < M && n < N) C[(long long)m * ldc + n] = F2EG(v[e] * alpha, over);
       }
     }
+    elem_flag(over, flag);
   }
 }
 
@@ -353,7 +288,6 @@ __global__ void __launch_bounds__(512) k_skinny_nt(SkinnyNtJobs jobs, int M, flo
 // read as one 32-bit word per lane and token, eight tokens in flight (rows past the chunk reuse its last row against
 // zero U rows).  The chunk's sums go to part[chunk][r][j].  Pass 2 adds the chunks and accumulates into G.
 constexpr int kLgT = 64, kLgMaxChunks = 32;
-#if HARLI_FT_HALF
 // Half operands: two tokens per v_dot2_f32_f16 (exact products, fp32 accumulation).  U is staged in LDS as packed
 // pairs (U[t][r], U[t+1][r]); the matching pairs of X are assembled from the two tokens' 32-bit words.
 typedef _Float16 h16x2 __attribute__((ext_vector_type(2)));
@@ -407,50 +341,6 @@ __global__ void __launch_bounds__(256) k_lora_grad_part(const bf* X, long long l
     for (int r = 0; r < R; ++r) *reinterpret_cast<float2*>(p + (long long)r * J) = make_float2(a0[r], a1[r]);
   }
 }
-#else
-template <int R>
-__global__ void __launch_bounds__(256) k_lora_grad_part(const bf* X, long long ldx, const bf* U, long long ldu, float* part,
-                                                        int T, int J, int tpc) {
-  __shared__ __align__(16) float us[kLgT][R];
-  const int tid = threadIdx.x;
-  const int j0 = (blockIdx.x * 256 + tid) * 2;
-  const int c0 = blockIdx.y * tpc, c1 = min(T, c0 + tpc);
-  float a0[R], a1[R];
-#pragma unroll
-  for (int r = 0; r < R; ++r) a0[r] = a1[r] = 0.f;
-  for (int t0 = c0; t0 < c1; t0 += kLgT) {
-    const int nt = min(kLgT, c1 - t0);
-    __syncthreads();
-    for (int i = tid; i < kLgT * R; i += 256) {
-      const int t = i / R, r = i - t * R;
-      us[t][r] = t < nt ? E2F(U[(long long)(t0 + t) * ldu + r]) : 0.f;
-    }
-    __syncthreads();
-    const bf* xp = X + (long long)t0 * ldx + min(j0, J - 2);
-    for (int t = 0; t < kLgT; t += 8) {
-      unsigned xv[8];
-#pragma unroll
-      for (int u = 0; u < 8; ++u) xv[u] = *reinterpret_cast<const unsigned*>(xp + (long long)min(t + u, nt - 1) * ldx);
-#pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        const float x0 = E2F((unsigned short)(xv[u] & 0xffffu)), x1 = E2F((unsigned short)(xv[u] >> 16));
-#pragma unroll
-        for (int r = 0; r < R; r += 4) {
-          const float4 uv = *reinterpret_cast<const float4*>(&us[t + u][r]);
-          a0[r] += x0 * uv.x, a0[r + 1] += x0 * uv.y, a0[r + 2] += x0 * uv.z, a0[r + 3] += x0 * uv.w;
-          a1[r] += x1 * uv.x, a1[r + 1] += x1 * uv.y, a1[r + 2] += x1 * uv.z, a1[r + 3] += x1 * uv.w;
-        }
-      }
-    }
-  }
-  if (j0 < J) {
-    float* p = part + (long long)blockIdx.y * R * J + j0;
-#pragma unroll
-    for (int r = 0; r < R; ++r) *reinterpret_cast<float2*>(p + (long long)r * J) = make_float2(a0[r], a1[r]);
-  }
-}
-
-#endif
 
 
 // MFMA version of pass 1 for 16-byte aligned operands (J, ldx, ldu multiples of 8).  The product contracts over the
@@ -535,11 +425,7 @@ __global__ void __launch_bounds__(256) k_lora_grad_mfma(LoraGradJobs jobs, float
         const s16x8 afr = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
-#if HARLI_FT_HALF
           acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, afr), __builtin_bit_cast(f16x8, bfr[nt]), acc[mt][nt], 0, 0, 0);
-#else
-          acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, afr), __builtin_bit_cast(bf16x8, bfr[nt]), acc[mt][nt], 0, 0, 0);
-#endif
         }
       }
     }
@@ -586,7 +472,7 @@ __global__ void __launch_bounds__(256) k_lora_grad_reduce_multi(LoraGradJobs job
   *g += sum * (out_mul ? *out_mul : 1.f);
 }
 
-__global__ void __launch_bounds__(256) k_sum_groups(const bf* in, bf* out, long long total, int n_kv, int G, int d) {
+__global__ void __launch_bounds__(256) k_sum_groups(const bf* in, bf* out, long long total, int n_kv, int G, int d, int* flag) {
   const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
   if (i >= total) return;
   const int kvd = n_kv * d;
@@ -594,14 +480,17 @@ __global__ void __launch_bounds__(256) k_sum_groups(const bf* in, bf* out, long 
   const int rem = (int)(i - t * kvd), c = rem / d, e = rem - c * d;
   float s = 0.f;
   for (int g = 0; g < G; ++g) s += E2F(in[t * (long long)kvd * G + (c * G + g) * d + e]);
-  out[i] = F2E(s);
+  bool over = false;
+  out[i] = F2EG(s, over);
+  elem_flag(over, flag);
 }
 
 __global__ void __launch_bounds__(256) k_convert_jobs(FtConvJobs jobs) {
   const FtConvJob jb = jobs.j[blockIdx.y];
   const long long n = (long long)jb.R * jb.C;
+  bool over = false;
   for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n; i += (long long)gridDim.x * 256) {
-    const unsigned short v = jb.src_f32 ? F2E(static_cast<const float*>(jb.src)[i]) : F2E(bf2f(static_cast<const bf*>(jb.src)[i]));
+    const unsigned short v = F2EG(jb.src_f32 ? static_cast<const float*>(jb.src)[i] : bf2f(static_cast<const bf*>(jb.src)[i]), over);
     if (jb.transpose) {
       const int r = (int)(i / jb.C), c = (int)(i - (long long)r * jb.C);
       jb.dst[(long long)c * jb.R + r] = v;
@@ -609,25 +498,22 @@ __global__ void __launch_bounds__(256) k_convert_jobs(FtConvJobs jobs) {
       jb.dst[i] = v;
     }
   }
+  elem_flag(over, jobs.flag);
 }
 
 inline unsigned nblk(long long n, int per) { return (unsigned)((n + per - 1) / per); }
 
 }  // namespace
 
-void ft_rmsnorm_fwd(const float* x, const float* g, bf* h, float* rho, int T, int H, float eps, hipStream_t st) {
-  hipLaunchKernelGGL(k_rmsnorm_fwd, dim3(T), dim3(256), 0, st, x, g, h, rho, H, eps);
+void ft_rmsnorm_fwd(const float* x, const float* g, bf* h, float* rho, int T, int H, float eps, int* flag, hipStream_t st) {
+  hipLaunchKernelGGL(k_rmsnorm_fwd, dim3(T), dim3(256), 0, st, x, g, h, rho, H, eps, flag);
 }
 void ft_rmsnorm_bwd(const float* dh, const float* x, const float* rho, const float* g, const float* dres, float* dx, bf* dx16,
-                    int T, int H, const float* res_mul, const float* out_mul, hipStream_t st) {
-  hipLaunchKernelGGL(k_rmsnorm_bwd, dim3(T), dim3(256), 0, st, dh, x, rho, g, dres, dx, dx16, H, res_mul, out_mul);
+                    int T, int H, const float* res_mul, const float* out_mul, int* flag, hipStream_t st) {
+  hipLaunchKernelGGL(k_rmsnorm_bwd, dim3(T), dim3(256), 0, st, dh, x, rho, g, dres, dx, dx16, H, res_mul, out_mul, flag);
 }
-void ft_rope(bf* t, int T, int S, int heads, int d, const double* inv_freq, bool inverse, hipStream_t st) {
-  hipLaunchKernelGGL(k_rope, dim3(T), dim3(256), 0, st, t, S, heads, d, inv_freq, inverse ? -1.f : 1.f);
-}
-void ft_softmax_causal(const float* sc, bf* P, float* lse, int Z, int S, hipStream_t st) {
-  const long long rows = (long long)Z * S;
-  hipLaunchKernelGGL(k_softmax_causal, dim3(nblk(rows, 4)), dim3(256), 0, st, sc, P, lse, S, rows);
+void ft_rope(bf* t, int T, int S, int heads, int d, const double* inv_freq, bool inverse, int* flag, hipStream_t st) {
+  hipLaunchKernelGGL(k_rope, dim3(T), dim3(256), 0, st, t, S, heads, d, inv_freq, inverse ? -1.f : 1.f, flag);
 }
 void ft_f32_to_e(const float* x, bf* y, long long n, const float* scale, hipStream_t st) {
   hipLaunchKernelGGL(k_f32_to_e_scaled, dim3(nblk(n / 4, 256)), dim3(256), 0, st, x, y, n / 4, scale);
@@ -646,45 +532,25 @@ void ft_convert_jobs(const FtConvJobs& jobs, hipStream_t st) {
 void ft_from_bf16(const bf* in, bf* out, long long n, hipStream_t st) {
   hipLaunchKernelGGL(k_from_bf16, dim3(nblk(n, 256)), dim3(256), 0, st, in, out, n);
 }
-void ft_make_scale(const float* x, long long n, float* scale, hipStream_t st) {
+void ft_make_scale(const float* x, long long n, float* scale, int target_log2, hipStream_t st) {
   unsigned* bits = reinterpret_cast<unsigned*>(scale + 2);
   hipLaunchKernelGGL(k_scale_reset, dim3(1), dim3(1), 0, st, bits);
   hipLaunchKernelGGL(k_amax, dim3(std::min(nblk(n / 4, 1024), 1024u)), dim3(256), 0, st, x, n / 4, bits);
-  hipLaunchKernelGGL(k_scale_make, dim3(1), dim3(1), 0, st, bits, scale);
+  hipLaunchKernelGGL(k_scale_make, dim3(1), dim3(1), 0, st, bits, scale, target_log2);
 }
 void ft_transpose_heads(const bf* in, bf* out, int Bf, int S, int heads, int d, hipStream_t st) {
   // per sequence b: [S][heads*d] -> [heads*d][S] = [heads][d][S]
   ft_transpose(in, out, Bf, S, heads * d, (long long)heads * d, (long long)S * heads * d, S, (long long)S * heads * d, st);
 }
-void ft_attn_delta(const bf* dO, const bf* O, float* delta, int Bf, int S, int heads, int d, hipStream_t st) {
-  const long long total = (long long)Bf * S * heads;
-  hipLaunchKernelGGL(k_attn_delta, dim3(nblk(total, 4)), dim3(256), 0, st, dO, O, delta, Bf, S, heads, d);
-}
-void ft_attn_ds(const bf* P, const float* dP, const float* delta, bf* dS, int Z, int S, hipStream_t st) {
-  const long long rows = (long long)Z * S;
-  hipLaunchKernelGGL(k_attn_ds, dim3(nblk(rows, 4)), dim3(256), 0, st, P, dP, delta, dS, S, rows);
-}
-void ft_attn_ds_t(const float* ST, const float* dPT, const float* lse, const float* delta, bf* PT, bf* dST, int Z, int S,
-                  hipStream_t st) {
-  const long long rows = (long long)Z * S;
-  hipLaunchKernelGGL(k_attn_ds_t, dim3(nblk(rows, 4)), dim3(256), 0, st, ST, dPT, lse, delta, PT, dST, S, rows);
-}
-void ft_skinny_nt_multi(const SkinnyNtJobs& jobs, int M, float alpha, hipStream_t st) {
+void ft_skinny_nt_multi(const SkinnyNtJobs& jobs, int M, float alpha, int* flag, hipStream_t st) {
   if (jobs.n < 1) return;
   int nmax = 0;
   for (int i = 0; i < jobs.n; ++i) nmax = std::max(nmax, jobs.j[i].N);
   const int nt = (nmax + 15) / 16;  // jobs with fewer columns mask their stores
   const dim3 grid((M + 15) / 16, jobs.n), blk(512);
-  if (nt == 1) hipLaunchKernelGGL(k_skinny_nt<1>, grid, blk, 0, st, jobs, M, alpha);
-  else if (nt == 2) hipLaunchKernelGGL(k_skinny_nt<2>, grid, blk, 0, st, jobs, M, alpha);
-  else hipLaunchKernelGGL(k_skinny_nt<4>, grid, blk, 0, st, jobs, M, alpha);
-}
-void ft_skinny_nt(const bf* X, long long ldx, const bf* Bm, long long ldb, bf* C, long long ldc, int M, int N, int K,
-                  float alpha, hipStream_t st) {
-  SkinnyNtJobs jobs{};
-  jobs.n = 1;
-  jobs.j[0] = SkinnyNtJob{X, ldx, Bm, ldb, C, ldc, N, K};
-  ft_skinny_nt_multi(jobs, M, alpha, st);
+  if (nt == 1) hipLaunchKernelGGL(k_skinny_nt<1>, grid, blk, 0, st, jobs, M, alpha, flag);
+  else if (nt == 2) hipLaunchKernelGGL(k_skinny_nt<2>, grid, blk, 0, st, jobs, M, alpha, flag);
+  else hipLaunchKernelGGL(k_skinny_nt<4>, grid, blk, 0, st, jobs, M, alpha, flag);
 }
 // floats of partial sums one job of the MFMA path can need: nch * J with nch <= max(1, 512 / column tiles)
 static size_t lora_grad_job_floats(int J, int R) { return (size_t)std::max(512 * kLmJ, (J + kLmJ - 1) / kLmJ * kLmJ) * R; }
@@ -748,9 +614,9 @@ void ft_lora_grad(const bf* X, long long ldx, const bf* U, long long ldu, float*
   jobs.j[0] = LoraGradJob{X, ldx, U, ldu, G, sj, sr, J, 0, 0, 0, 0};
   ft_lora_grad_multi(jobs, T, R, out_mul, part, st);
 }
-void ft_sum_groups(const bf* in, bf* out, int T, int n_kv, int G, int d, hipStream_t st) {
+void ft_sum_groups(const bf* in, bf* out, int T, int n_kv, int G, int d, int* flag, hipStream_t st) {
   const long long total = (long long)T * n_kv * d;
-  hipLaunchKernelGGL(k_sum_groups, dim3(nblk(total, 256)), dim3(256), 0, st, in, out, total, n_kv, G, d);
+  hipLaunchKernelGGL(k_sum_groups, dim3(nblk(total, 256)), dim3(256), 0, st, in, out, total, n_kv, G, d, flag);
 }
 
 }  // namespace harli

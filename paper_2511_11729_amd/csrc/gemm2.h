@@ -1,6 +1,6 @@
 // Weight GEMM of the finetune unit for gfx950:  C = alpha * sum_s A_s . B_s^T  (+ res), 16-bit operands, fp32 accumulate
 // (Harli Sec. 2.1: PEFT is dominated by products with the frozen base weights; the LoRA path and frozen biases ride as
-// further K segments, as in gemm.h).
+// further K segments).
 //
 // A_s is an activation [M, K_s], row-major with row stride lda.  B_s is a weight-side operand [N, K_s] kept in the
 // BLOCKED layout this kernel streams: [row tile of 256][k step of 32][256 rows][32 k], rows past N and k past K_s
@@ -12,7 +12,7 @@
 #include <hip/hip_runtime.h>
 
 #include "common.h"
-#include "gemm.h"
+#include "gemm_timer.h"
 
 namespace harli {
 
@@ -93,7 +93,8 @@ struct BlockJob {
 struct BlockJobs {
   BlockJob j[16];
   int n;
-  int half;  // destination element: IEEE half (1) or bfloat16 (0)
+  int half;   // destination element: IEEE half (1) or bfloat16 (0)
+  int* flag;  // device int or null: bit 8 is set when a converted value lay beyond the destination element's range
 };
 void gemm2_block_jobs(const BlockJobs& jobs, hipStream_t st);
 // measurement hook: 128 or 256 fixes the tile height of every later launch, anything else gives the choice back

@@ -402,6 +402,7 @@ __global__ void __launch_bounds__(256) k_block_jobs(BlockJobs jobs) {
   const long long N = jb.transpose ? jb.C : jb.R, K = jb.transpose ? jb.R : jb.C;
   const long long ks_n = (K + BK - 1) / BK;
   const long long total = (long long)blocked_elems(N, K) / 8;  // 16-byte chunks of the destination
+  bool over = false;
   for (long long ci = (long long)blockIdx.x * 256 + threadIdx.x; ci < total; ci += (long long)gridDim.x * 256) {
     const long long e0 = ci * 8;  // first element of the chunk: ((tile * ks_n + ks) * 256 + row) * 32 + kk
     const int kk = (int)(e0 & 31), row = (int)((e0 >> 5) & 255);
@@ -418,12 +419,14 @@ __global__ void __launch_bounds__(256) k_block_jobs(BlockJobs jobs) {
         } else {
           const float f = jb.src_f32 ? static_cast<const float*>(jb.src)[si] : bf2f(static_cast<const unsigned short*>(jb.src)[si]);
           v[e] = jobs.half ? f2h(f) : f2bf(f);
+          over = over || (jobs.half && !(fabsf(f) <= 65504.f));
         }
       }
     }
     *reinterpret_cast<uint4*>(jb.dst + e0) = make_uint4(v[0] | (unsigned)v[1] << 16, v[2] | (unsigned)v[3] << 16, v[4] | (unsigned)v[5] << 16,
                                                         v[6] | (unsigned)v[7] << 16);
   }
+  if (over && jobs.flag) atomicOr(jobs.flag, 8);
 }
 
 template <int FM>

@@ -10,7 +10,7 @@
 #include "ctx.h"
 #include "ft_elem.h"
 #include "ft_kernels.h"
-#include "gemm.h"
+#include "gemm_timer.h"
 #include "gemm2.h"
 
 namespace harli {
@@ -139,7 +139,8 @@ harli_status head_prepare(harli_ctx* c) {
     HARLI_HIP(hipMalloc(reinterpret_cast<void**>(&w.wT), blocked_elems(H, Vp) * 2));
     const int f32 = c->cfg.dtype == HARLI_F32 ? 1 : 0;
     BlockJobs jobs{};
-    jobs.half = kFtHalf ? 1 : 0;
+    jobs.half = 1;
+    jobs.flag = c->dw.err_flag;  // an output-layer weight beyond the element's range shows in harli_ctx_check
     jobs.j[jobs.n++] = BlockJob{c->w_lm, w.w16, V, H, 0, f32};  // operand [n = class][k = hidden]
     jobs.j[jobs.n++] = BlockJob{c->w_lm, w.wT, V, H, 1, f32};   // operand [n = hidden][k = class], zero past V
     gemm2_block_jobs(jobs, nullptr);
@@ -215,12 +216,12 @@ extern "C" harli_status harli_head_fwd_bwd(harli_ctx* c, const float* x, const i
   harli_status s = HARLI_OK;
   HeadWs& w = *ws_of(c);
   const int V = c->cfg.vocab, H = c->cfg.hidden, Vp = w.Vp;
-  ft_rmsnorm_fwd(x, c->g_final, w.h, w.rho, T, H, c->cfg.rms_eps, st);
+  ft_rmsnorm_fwd(x, c->g_final, w.h, w.rho, T, H, c->cfg.rms_eps, c->dw.err_flag, st);
   for (int t0 = 0; t0 < T; t0 += w.TC) {
     const int rows = std::min(w.TC, T - t0);
     {  // logits = h W^T
       Gemm2Args g{};
-      g.M = rows; g.alpha = 1.f; g.half = kFtHalf ? 1 : 0; g.overflow_flag = c->dw.err_flag;
+      g.M = rows; g.alpha = 1.f; g.half = 1; g.overflow_flag = c->dw.err_flag;
       g.nseg = 1;
       g.seg[0] = Gemm2Seg{w.h + (size_t)t0 * H, H, H, w.w16, 0, (V + kG2TileN - 1) / kG2TileN, nullptr, 0, V};
       g.nout = 1;
@@ -232,7 +233,7 @@ extern "C" harli_status harli_head_fwd_bwd(harli_ctx* c, const float* x, const i
     hipLaunchKernelGGL(k_ce_row, dim3(rows), dim3(256), 0, st, w.logits, targets + t0, w.dlog, V, Vp, w.rowloss + t0, c->dw.err_flag);
     {  // dh = dlog W   (contraction over the padded vocabulary: pad columns are zero on both sides)
       Gemm2Args g{};
-      g.M = rows; g.alpha = 1.f; g.half = kFtHalf ? 1 : 0; g.overflow_flag = c->dw.err_flag;
+      g.M = rows; g.alpha = 1.f; g.half = 1; g.overflow_flag = c->dw.err_flag;
       g.nseg = 1;
       g.seg[0] = Gemm2Seg{w.dlog, Vp, Vp, w.wT, 0, (H + kG2TileN - 1) / kG2TileN, nullptr, 0, H};
       g.nout = 1;
@@ -243,7 +244,7 @@ extern "C" harli_status harli_head_fwd_bwd(harli_ctx* c, const float* x, const i
     }
   }
   hipLaunchKernelGGL(k_head_finish, dim3(1), dim3(256), 0, st, w.rowloss, T, w.acc, loss);
-  ft_rmsnorm_bwd(w.dh, x, w.rho, c->g_final, nullptr, dx, nullptr, T, H, nullptr, w.acc + 2, st);
+  ft_rmsnorm_bwd(w.dh, x, w.rho, c->g_final, nullptr, dx, nullptr, T, H, nullptr, w.acc + 2, c->dw.err_flag, st);
   HARLI_HIP(hipGetLastError());
   return HARLI_OK;
 }

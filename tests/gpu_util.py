@@ -178,12 +178,16 @@ class FinetuneCase:
     """One finetune unit (layer forward + backward) on both sides."""
 
     def __init__(self, w: wl.Workload, model: wl.ModelCfg, lora: wl.LoraCfg, ft: wl.FinetuneCfg, *,
-                 block_bytes=2 << 20, small_pool_bytes=8 << 20, zero_b=False, n_chunks=None, sets=1):
+                 block_bytes=2 << 20, small_pool_bytes=8 << 20, zero_b=False, n_chunks=None, sets=1, tweak=None,
+                 grad_headroom_log2=0, attach=True):
+        """tweak(case): edits W_np / lora_np / X_np (both sides then see the edited values)."""
         self.w, self.m, self.lora, self.ft = w, model, lora, ft
         m = model
         self.W_np = wl.make_layer_weights(w, 0, m)
         self.lora_np = wl.make_lora(w, 0, m, lora, zero_b=zero_b)
         self.X_np, self.T_np = wl.make_finetune_inputs(w, m, ft)
+        if tweak is not None:
+            tweak(self)
         T = ft.tokens
         # a first context-free estimate of the pool size: activations + slack
         Z = ft.micro_batch * m.n_q
@@ -207,7 +211,9 @@ class FinetuneCase:
                               layers=[self.layer_dev])
         self.A_dev = {p: to_dev(a, m.dtype) for p, (a, b) in self.lora_np.items()}
         self.B_dev = {p: to_dev(b, m.dtype) for p, (a, b) in self.lora_np.items()}
-        self.ctx.lora_attach(lora.rank, lora.alpha, lora.targets, [self.A_dev], [self.B_dev])
+        if attach:
+            self.ctx.lora_attach(lora.rank, lora.alpha, lora.targets, [self.A_dev], [self.B_dev],
+                                 grad_headroom_log2=grad_headroom_log2)
         self.X_dev = f32_dev(self.X_np.reshape(T, m.hidden))
 
     def forward_gpu(self, stream=None):
