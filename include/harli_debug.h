@@ -46,8 +46,19 @@ typedef struct {
   int32_t* overflow_flag;
   double* tflops;
   double* shader_mhz;
+  /* Compute units the tile height is chosen for: 0 = those of `hip_stream` (all of the device unless it is a
+   * harli_cu_stream), n > 0 = n. */
+  int32_t n_cu;
 } harli_dbg_gemm2_desc;
 harli_status harli_dbg_gemm2(const harli_dbg_gemm2_desc* d, void* hip_stream);
+
+/* The grid the weight GEMM would launch for M rows and tiles_n column tiles at tile height tile_rows (128 or 256), and
+ * its cost on n_cu compute units (host logic only, no device needed).  out[6] (host) receives GM, GN, total, chunk,
+ * grid and the rounds of tiles over the compute units.  Workgroup w computes the tile in slot (w % 8) * chunk + w / 8
+ * of the XCD-aware order: blocks of GM x GN tiles, row-major inside a block and over the blocks; slots past the matrix
+ * are idle.  The library launches the tile height with the smaller cost, a round of 128-row tiles counted as 0.55 of a
+ * round of 256-row tiles. */
+harli_status harli_dbg_gemm2_plan(int32_t M, int32_t tiles_n, int32_t tile_rows, int32_t n_cu, int32_t* out);
 
 /* The residency plan of harli_ft_window_* on its own (host logic only, no device needed): a window of n_slots over the
  * 2 * n_layers cyclic items, prefilled with items 0..n_slots-1, is driven through `items[0..n_access)`; for every

@@ -149,6 +149,7 @@ _SIGS = {
     "harli_dbg_window_plan": (C.c_int, [C.c_int32, C.c_int32, C.POINTER(C.c_int32), C.c_int32, C.POINTER(C.c_int32),
                                         C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
     "harli_dbg_gemm2": (C.c_int, [C.c_void_p, C.c_void_p]),
+    "harli_dbg_gemm2_plan": (C.c_int, [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int32)]),
 }
 
 
@@ -531,11 +532,18 @@ class DbgGemm2Desc(C.Structure):
                 ("cb", C.c_void_p * 3), ("ldcb", C.c_int64 * 3), ("cf", C.c_void_p * 3), ("res", C.c_void_p * 3),
                 ("ldcf", C.c_int64 * 3), ("e0", C.c_void_p), ("e1", C.c_void_p), ("o0", C.c_void_p), ("o1", C.c_void_p),
                 ("lde", C.c_int64), ("overflow_flag", C.c_void_p), ("tflops", C.POINTER(C.c_double)),
-                ("shader_mhz", C.POINTER(C.c_double))]
+                ("shader_mhz", C.POINTER(C.c_double)), ("n_cu", C.c_int32)]
+
+
+def dbg_gemm2_plan(M: int, tiles_n: int, tile_rows: int, n_cu: int) -> dict:
+    """The launch grid of the weight GEMM (host logic): GM, GN, total, chunk, grid, rounds."""
+    out = (C.c_int32 * 6)()
+    _check(lib().harli_dbg_gemm2_plan(M, tiles_n, tile_rows, n_cu, out))
+    return dict(zip(("GM", "GN", "total", "chunk", "grid", "rounds"), list(out)))
 
 
 def dbg_gemm2(M, segs, outs, *, half=True, epi=0, alpha=1.0, tile_rows=0, reps=0, e0=None, e1=None, o0=None, o1=None, lde=0,
-              overflow_flag=None, stream=None):
+              overflow_flag=None, stream=None, n_cu=0):
     """Test hook for the finetune unit's weight GEMM.  segs: dicts with A (device [M, K], 16-bit), optional lda,
     B (device [rows, K] row-major weight side; the hook blocks it), optional B2 and pair, optional tile0 / tile1.
     outs: dicts with N, tile0 and cb (16-bit) or cf (+ res), optional ld.  Tiles are 256 columns (128 + 128 for
@@ -566,6 +574,7 @@ def dbg_gemm2(M, segs, outs, *, half=True, epi=0, alpha=1.0, tile_rows=0, reps=0
         d.tile0[s], d.tile1[s] = q.get("tile0", 0), q.get("tile1", tiles)
     d.e0, d.e1, d.o0, d.o1, d.lde = _ptr(e0), _ptr(e1), _ptr(o0), _ptr(o1), lde
     d.overflow_flag = _ptr(overflow_flag)
+    d.n_cu = n_cu
     t, f = C.c_double(0.0), C.c_double(0.0)
     if reps > 1:
         d.tflops, d.shader_mhz = C.pointer(t), C.pointer(f)

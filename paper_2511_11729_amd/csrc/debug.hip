@@ -9,6 +9,15 @@
 
 using namespace harli;
 
+extern "C" harli_status harli_dbg_gemm2_plan(int32_t M, int32_t tiles_n, int32_t tile_rows, int32_t n_cu, int32_t* out) {
+  if (!out || M < 1 || tiles_n < 1 || n_cu < 1 || (tile_rows != 128 && tile_rows != 256))
+    return fail(HARLI_ERR_INVALID, "dbg_gemm2_plan: bad argument");
+  const Gemm2Plan p = gemm2_plan(M, tiles_n, tile_rows / 64, n_cu);
+  const int v[6] = {p.GM, p.GN, p.total, p.chunk, p.grid, p.rounds};
+  for (int i = 0; i < 6; ++i) out[i] = v[i];
+  return HARLI_OK;
+}
+
 extern "C" harli_status harli_dbg_gemm2(const harli_dbg_gemm2_desc* d, void* hip_stream) {
   if (!d || d->nseg < 1 || d->nseg > kGemm2MaxSeg || d->nout < 1 || d->nout > kGemm2MaxOut)
     return fail(HARLI_ERR_INVALID, "dbg_gemm2: bad descriptor");
@@ -95,6 +104,7 @@ extern "C" harli_status harli_dbg_gemm2(const harli_dbg_gemm2_desc* d, void* hip
     tmp.push_back(clk);
     g.clk = clk;
   }
+  g.n_cu = d->n_cu > 0 ? d->n_cu : 0;
   gemm2_force_tile_rows(d->tile_rows);
   harli_status rc = gemm2_launch(g, st);
   const int reps = d->reps > 1 ? d->reps : 0;

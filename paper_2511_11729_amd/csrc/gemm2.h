@@ -76,10 +76,21 @@ struct Gemm2Args {
   unsigned short *o0, *o1;
   long long lde;
   int* overflow_flag;  // device int: bit 8 is set when a 16-bit output had to be clamped to the element's range (or null)
-  long long* clk;      // clock probe as in GemmArgs (or null)
+  long long* clk;      // clock probe (or null): workgroup 0 writes {shader-clock cycles, 100 MHz ticks} of its K loop
+  // compute units the launch's stream may use (Harli Sec. 6.2: the finetune task runs on a share of them); 0: taken
+  // from the stream (harli_cu_stream_create), else the whole device.  The tile height is chosen for it.
+  int n_cu;
 };
 
+
 harli_status gemm2_launch(const Gemm2Args& a, hipStream_t st);
+
+// The grid gemm2_launch would use (exposed for the host-side tests of the tile order).
+struct Gemm2Plan {
+  int GM, GN, total, chunk, grid;  // block of tiles per XCD pass, padded tile slots, slots per XCD, workgroups launched
+  int rounds;                      // rounds of tiles over the compute units
+};
+Gemm2Plan gemm2_plan(int M, int tiles_n, int FM, int n_cu);
 
 // Blocked copies.  src is [R][C] row-major in the storage type (bf16; fp32 when src_f32 is 1; 16-bit elements that
 // are already in the compute element and are copied bit for bit when src_f32 is 2); the operand is B[n][k] =
@@ -99,5 +110,7 @@ struct BlockJobs {
 void gemm2_block_jobs(const BlockJobs& jobs, hipStream_t st);
 // measurement hook: 128 or 256 fixes the tile height of every later launch, anything else gives the choice back
 void gemm2_force_tile_rows(int rows);
+// compute units a stream made by harli_cu_stream_create may use; 0 for any other stream (sched.cpp)
+int cu_stream_count(void* hip_stream);
 
 }  // namespace harli

@@ -443,6 +443,21 @@ void gemm2_block_jobs(const BlockJobs& jobs, hipStream_t st) {
   hipLaunchKernelGGL(k_block_jobs, dim3(256, jobs.n), dim3(256), 0, st, jobs);
 }
 
+// Grid of a launch: the XCD-aware tile order of the kernel and its cost in rounds of tiles over n_cu compute units.
+Gemm2Plan gemm2_plan(int M, int tiles_n, int FM, int n_cu) {
+  Gemm2Plan p{};
+  const int BM = 64 * FM, tiles_m = (M + BM - 1) / BM;
+  // The 32 workgroups an XCD runs at a time form one GM x GN block of tiles about 1024 x 2048 outputs large, so that
+  // they share GM + GN operand panels in its L2.
+  p.GM = std::min(FM == 2 ? 8 : 4, tiles_m);
+  p.GN = std::min(FM == 2 ? 4 : 8, tiles_n);
+  p.total = ((tiles_m + p.GM - 1) / p.GM) * ((tiles_n + p.GN - 1) / p.GN) * p.GM * p.GN;  // whole blocks: slots past the matrix return at once
+  p.chunk = (p.total + 7) / 8;
+  p.grid = p.chunk * 8;
+  p.rounds = (tiles_m * tiles_n + n_cu - 1) / n_cu;
+  return p;
+}
+
 harli_status gemm2_launch(const Gemm2Args& a, hipStream_t st) {
   if (a.M < 1 || a.nseg < 1 || a.nseg > kGemm2MaxSeg || a.nout < 1 || a.nout > kGemm2MaxOut || a.tiles_n < 1)
     return fail(HARLI_ERR_INVALID, "gemm2: bad shape M %d nseg %d nout %d tiles %d", a.M, a.nseg, a.nout, a.tiles_n);
@@ -498,27 +513,22 @@ harli_status gemm2_launch(const Gemm2Args& a, hipStream_t st) {
 #undef G2_ATTR
     attr_set = true;
   }
-  // 256-row tiles unless they would leave compute units without a tile that 128-row tiles can feed
-  int n_cu = 256;
-  {
+  int n_cu = a.n_cu > 0 ? a.n_cu : cu_stream_count(st);
+  if (n_cu < 1) {
+    n_cu = 256;
     int dev = 0;
     hipDeviceProp_t prop;
     if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) n_cu = prop.multiProcessorCount;
   }
-  // Tile height: rounds of workgroups over the chip, a 128-row tile costed at 0.55 of a 256-row one (it moves 3/4 of the
-  // operand bytes for half the flops).
-  const int t256 = ((a.M + 255) / 256) * a.tiles_n, t128 = ((a.M + 127) / 128) * a.tiles_n;
-  const double cost4 = (double)((t256 + n_cu - 1) / n_cu), cost2 = 0.55 * (double)((t128 + n_cu - 1) / n_cu);
-  int FM = (a.M > 128 && cost4 <= cost2) ? 4 : 2;
+  const Gemm2Plan p4 = gemm2_plan(a.M, a.tiles_n, 4, n_cu), p2 = gemm2_plan(a.M, a.tiles_n, 2, n_cu);
+  // Tile height: rounds of workgroups over the compute units of the stream, a 128-row tile costed at 0.55 of a 256-row
+  // one (it moves 3/4 of the operand bytes for half the flops).
+  int FM = (a.M > 128 && p4.rounds <= 0.55 * p2.rounds) ? 4 : 2;
   if (g_force_fm == 2 || g_force_fm == 4) FM = g_force_fm;
-  const int BM = 64 * FM;
-  const int tiles_m = (a.M + BM - 1) / BM;
-  // The 32 workgroups an XCD runs at a time form one GM x GN block of tiles about 1024 x 2048 outputs large, so that
-  // they share GM + GN operand panels in its L2.
-  const int GM = std::min(FM == 2 ? 8 : 4, tiles_m), GN = std::min(FM == 2 ? 4 : 8, a.tiles_n);
-  const int total = ((tiles_m + GM - 1) / GM) * ((a.tiles_n + GN - 1) / GN) * GM * GN, chunk = (total + 7) / 8;
+  const Gemm2Plan& pl = FM == 4 ? p4 : p2;
+  const int GM = pl.GM, GN = pl.GN, total = pl.total, chunk = pl.chunk, grid = pl.grid;
 #define G2_LAUNCH(F_, H_, E_) \
-  hipLaunchKernelGGL((k_gemm2<F_, H_, E_>), dim3(chunk * 8), dim3(NT), lds_bytes<F_>(), st, a, total, chunk, GM, GN, zero16)
+  hipLaunchKernelGGL((k_gemm2<F_, H_, E_>), dim3(grid), dim3(NT), lds_bytes<F_>(), st, a, total, chunk, GM, GN, zero16)
 #define G2_PICK(F_)                                                                    \
   do {                                                                                 \
     if (a.half) {                                                                      \

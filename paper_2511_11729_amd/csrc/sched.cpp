@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 
 #include <cmath>
+#include <map>
+#include <mutex>
 #include <vector>
 
 #include "common.h"
@@ -334,6 +336,19 @@ extern "C" harli_status harli_sched_step(harli_scheduler* s, int32_t bs, int32_t
   return HARLI_OK;
 }
 
+// streams made here and the number of compute units each may use: the weight GEMM sizes its last round of tiles for it
+namespace {
+std::mutex g_cu_mu;
+std::map<void*, int> g_cu_streams;
+}  // namespace
+namespace harli {
+int cu_stream_count(void* hip_stream) {
+  std::lock_guard<std::mutex> lk(g_cu_mu);
+  auto it = g_cu_streams.find(hip_stream);
+  return it == g_cu_streams.end() ? 0 : it->second;
+}
+}  // namespace harli
+
 extern "C" harli_status harli_cu_stream_create(int32_t cu_first, int32_t cu_count, void** hip_stream) {
   if (!hip_stream) return fail(HARLI_ERR_INVALID, "cu_stream_create: null out pointer");
   int dev = 0;
@@ -349,12 +364,20 @@ extern "C" harli_status harli_cu_stream_create(int32_t cu_first, int32_t cu_coun
   hipStream_t st = nullptr;
   hipError_t e = hipExtStreamCreateWithCUMask(&st, (uint32_t)mask.size(), mask.data());
   if (e != hipSuccess) return fail(HARLI_ERR_HIP, "cu_stream_create: %s", hipGetErrorString(e));
+  {
+    std::lock_guard<std::mutex> lk(g_cu_mu);
+    g_cu_streams[st] = cu_count;
+  }
   *hip_stream = st;
   return HARLI_OK;
 }
 
 extern "C" harli_status harli_cu_stream_destroy(void* hip_stream) {
   if (!hip_stream) return fail(HARLI_ERR_INVALID, "cu_stream_destroy: null stream");
+  {
+    std::lock_guard<std::mutex> lk(g_cu_mu);
+    g_cu_streams.erase(hip_stream);
+  }
   hipError_t e = hipStreamDestroy(static_cast<hipStream_t>(hip_stream));
   if (e != hipSuccess) return fail(HARLI_ERR_HIP, "cu_stream_destroy: %s", hipGetErrorString(e));
   return HARLI_OK;

@@ -144,3 +144,26 @@ def test_full_size_shapes_on_sampled_outputs():
         ref = f64(A[rows]) @ f64(B).T
         close(f64(cb[rows]), ref, "%dx%dx%d" % (M, N, K))
         print("gemm2 %d x %d x %d: %.0f TFLOP/s at %.0f MHz" % (M, N, K, t, mhz))
+
+
+# ---- tile height chosen for the compute units of the stream ------------------------------------------------------------
+def test_full_size_shapes_on_a_nine_tenths_partition():
+    """2048 x 4096 x 4096 on a stream masked to 230 compute units: 256 tiles of 128 rows would run as one full round
+    and 26 stragglers, so the library takes 128 tiles of 256 rows there (one round); sampled rows against fp64,
+    timings of both tile heights on the partition for the record."""
+    M, N, K = 2048, 4096, 4096
+    assert hb.dbg_gemm2_plan(M, N // 256, 128, 230)["rounds"] == 2 and hb.dbg_gemm2_plan(M, N // 256, 256, 230)["rounds"] == 1
+    A, B = rnd((M, K), True, 60, 0.5), rnd((N, K), True, 61, 0.05)
+    rows = [0, 1, 255, 256, M // 2 + 7, M - 1]
+    ref = f64(A[rows]) @ f64(B).T
+    st = hb.cu_stream_create(0, 230)
+    try:
+        for name, kw in (("library's choice", {}), ("128-row tiles", dict(tile_rows=128)), ("256-row tiles", dict(tile_rows=256))):
+            cb = torch.zeros(M, N, dtype=torch.float16, device=DEV)
+            torch.cuda.synchronize()
+            t, _ = hb.dbg_gemm2(M, [dict(A=A, B=B)], [dict(N=N, cb=cb)], half=True, reps=10, stream=st, **kw)
+            torch.cuda.synchronize()
+            close(f64(cb[rows]), ref, name)
+            print("gemm2 2048 x 4096 x 4096 on 230 compute units, %s: %.0f TFLOP/s" % (name, t))
+    finally:
+        hb.cu_stream_destroy(st)
