@@ -52,7 +52,8 @@ struct FtWs {
   bf *vT = nullptr, *At[kTargets] = {}, *Bt[kTargets] = {}, *dyb = nullptr, *da = nullptr, *du = nullptr, *dx1b = nullptr, *dob = nullptr,
      *doT = nullptr, *qT = nullptr, *kT = nullptr, *dq = nullptr, *dkq = nullptr,
      *dvq = nullptr, *dk = nullptr, *dv = nullptr, *gs[3] = {}, *An[kTargets] = {}, *Bn[kTargets] = {};
-  float* scale = nullptr;  // [0] sigma, [1] 1/sigma, [2] scratch: gradient scaling of the backward pass
+  float* scale = nullptr;  // [0] sigma, [1] 1/sigma, [2], [3] maxima of this and the next call: gradient scaling of the backward pass
+  int scale_parity = 0;
   int Bf = 0, S = 0;
 };
 
@@ -159,6 +160,8 @@ harli_status make_ws(harli_ctx* c) {
     w.An[i] = (bf*)(b + o_An + i * adb); w.Bn[i] = (bf*)(b + o_Bn + i * ad);
   }
   w.scale = (float*)(b + o_scale);
+  HARLI_HIP(hipMemset(w.scale, 0, 64));  // the maxima start at zero; every backward call clears the slot of the next
+  w.scale_parity = 0;
   return HARLI_OK;
 }
 
@@ -579,7 +582,11 @@ extern "C" harli_status harli_lora_fwd(harli_ctx* c, int32_t layer, const float*
   }
   ft_rope(sv->q, T, S, D.nq, D.d, c->dw.inv_freq, false, c->dw.err_flag, st);
   ft_rope(sv->k, T, S, D.nkv, D.d, c->dw.inv_freq, false, c->dw.err_flag, st);
-  ft_transpose_heads(sv->v, w.vT, B_f, S, D.nkv, D.d, st);
+  {
+    TransposeJobs tj{};
+    tj.in[0] = sv->v, tj.out[0] = w.vT, tj.C[0] = D.KVD, tj.n = 1;
+    ft_transpose_heads(tj, B_f, S, st);
+  }
   RUN(ft_attn_fwd(sv->q, sv->k, w.vT, sv->o, sv->lse, B_f, S, D.nq, D.nkv, D.d, st));
   {  // x1 = X + o Wo^T
     proj_us_group(c, 3, 3, sv->o, T, sv, st);
@@ -654,8 +661,8 @@ extern "C" harli_status harli_lora_bwd(harli_ctx* c, int32_t layer, const float*
 
   // ---- FFN ----
   convert_adapters(c, L, false, st);
-  ft_make_scale(dY, (long long)T * D.H, w.scale, 8 - c->lora.grad_headroom_log2, st);
-  ft_f32_to_e(dY, w.dyb, (long long)T * D.H, w.scale, st);  // every gradient below carries the factor sigma
+  // every gradient below carries the factor sigma
+  ft_scale_to_e(dY, w.dyb, (long long)T * D.H, w.scale, w.scale_parity++, 8 - c->lora.grad_headroom_log2, st);
   const int r = c->lora.rank;
   {  // dm = dy Wd (+ gs A_d^T) -> da, du
     Gemm2Args g = wg_begin(c, T);
@@ -703,9 +710,14 @@ extern "C" harli_status harli_lora_bwd(harli_ctx* c, int32_t layer, const float*
     RUNB(gemm2_launch(g, st));
   }
   // ---- attention ----
-  ft_transpose_heads(w.dob, w.doT, B_f, S, D.nq, D.d, st);
-  ft_transpose_heads(sv->q, w.qT, B_f, S, D.nq, D.d, st);
-  ft_transpose_heads(sv->k, w.kT, B_f, S, D.nkv, D.d, st);
+  {
+    TransposeJobs tj{};
+    tj.in[0] = w.dob, tj.out[0] = w.doT, tj.C[0] = D.QD;
+    tj.in[1] = sv->q, tj.out[1] = w.qT, tj.C[1] = D.QD;
+    tj.in[2] = sv->k, tj.out[2] = w.kT, tj.C[2] = D.KVD;
+    tj.n = 3;
+    ft_transpose_heads(tj, B_f, S, st);
+  }
   RUNB(ft_attn_bwd(sv->q, sv->k, sv->v, sv->o, w.qT, w.kT, w.dob, w.doT, sv->lse, w.delta, w.dq, w.dkq, w.dvq, B_f, S, D.nq,
                    D.nkv, D.d, c->dw.err_flag, st));
   const bf *dk = w.dkq, *dv = w.dvq;

@@ -18,13 +18,11 @@ void ft_rmsnorm_bwd(const float* dh, const float* x, const float* rho, const flo
                     int T, int H, const float* res_mul, const float* out_mul, int* flag, hipStream_t st);
 // rotary embedding in place on [T, heads*d] bf16, position = t % S; inverse rotates by the negative angle
 void ft_rope(bf* t, int T, int S, int heads, int d, const double* inv_freq, bool inverse, int* flag, hipStream_t st);
-// y = 16-bit(x * *scale)   (scale: optional device scalar)
-void ft_f32_to_e(const float* x, bf* y, long long n, const float* scale, hipStream_t st);
-// scale[0] = sigma = power of two bringing max|x| to 2^target_log2, scale[1] = 1/sigma (scale[2] is scratch)
-void ft_make_scale(const float* x, long long n, float* scale, int target_log2, hipStream_t st);
-// bf16 storage -> compute element: plain copy and [R][C] -> [C][R] transpose
-void ft_from_bf16(const bf* in, bf* out, long long n, hipStream_t st);
-void ft_transpose_from_bf16(const bf* in, bf* out, int R, int C, hipStream_t st);
+// Gradient scaling in two launches: the largest |x| (n a multiple of 4), then y = 16-bit(x * sigma) with sigma the power
+// of two that brings it to 2^target_log2; scale[0] = sigma and scale[1] = 1 / sigma are left for the kernels downstream.
+// scale[2], scale[3] hold the maximum (as bits) of this call and the next: they must be zero before the first call, and
+// `parity` alternates between calls (each call clears the slot of the next).
+void ft_scale_to_e(const float* x, bf* y, long long n, float* scale, int parity, int target_log2, hipStream_t st);
 // Several storage -> compute-element conversions in one launch: src [R][C] (bf16, or fp32 when src_f32 is set) ->
 // dst [R][C], or dst [C][R] when transpose is set (meant for adapter matrices and one-time weight copies: the
 // strided side is not tuned)
@@ -39,11 +37,15 @@ struct FtConvJobs {
   int* flag;  // device int or null: bit 8 is set when a value lay beyond the compute element's range
 };
 void ft_convert_jobs(const FtConvJobs& jobs, hipStream_t st);
-// batched transpose: in [Z][R][C] (row stride ldi, batch stride bsi) -> out [Z][C][R]
-void ft_transpose(const bf* in, bf* out, int Z, int R, int C, long long ldi, long long bsi, long long ldo, long long bso,
-                  hipStream_t st);
-// head-wise transpose of a [T, heads*d] tensor into [Bf][heads][d][S]
-void ft_transpose_heads(const bf* in, bf* out, int Bf, int S, int heads, int d, hipStream_t st);
+// head-wise transposes of [Bf*S, C] tensors (C = heads * d, S and C multiples of 8) into [Bf][C][S], up to three in one
+// launch
+struct TransposeJobs {
+  const bf* in[3];
+  bf* out[3];
+  int C[3];
+  int n;
+};
+void ft_transpose_heads(const TransposeJobs& jobs, int Bf, int S, hipStream_t st);
 // skinny NT GEMMs: C[M, N] = alpha * X[M, K] . Bm[N, K]^T, N <= 64 and N % 16 == 0 after padding by the caller's layout;
 // several such products with the same M and alpha in one launch (job = blockIdx.y).
 constexpr int kSkinnyMaxJobs = 4;

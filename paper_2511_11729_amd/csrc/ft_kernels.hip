@@ -133,26 +133,35 @@ __global__ void __launch_bounds__(256) k_rope(bf* x, int S, int heads, int d, co
   elem_flag(over, flag);
 }
 
-// ---------------------------------------------------------------- transposes (64 x 64 tiles through LDS)
-template <bool FROM_BF16>
-__global__ void __launch_bounds__(256) k_transpose(const bf* in, bf* out, int R, int C, long long ldi, long long bsi,
-                                                   long long ldo, long long bso) {
-  __shared__ bf tile[64][66];
-  const bf* src = in + blockIdx.z * bsi;
-  bf* dst = out + blockIdx.z * bso;
+// ---------------------------------------------------------------- head-wise transposes (64 x 64 tiles through LDS)
+// Per sequence b: [S][heads*d] -> [heads*d][S].  Up to three tensors per launch (blockIdx.z = job * Bf + b).  Both
+// global sides move 16 bytes per lane (S and heads*d are multiples of 8); the transposition happens in the 2-byte LDS
+// writes.
+__global__ void __launch_bounds__(256) k_transpose_heads(TransposeJobs jobs, int Bf, int S) {
+  __shared__ __align__(16) bf tile[64][72];  // [column][row], rows padded to 144 bytes
+  const int job = blockIdx.z / Bf, b = blockIdx.z - job * Bf;
+  const int C = jobs.C[job];
   const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
-  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-  for (int r = ty; r < 64; r += 4)
-    tile[r][tx] = (r0 + r < R && c0 + tx < C) ? src[(long long)(r0 + r) * ldi + c0 + tx] : (bf)0;
+  if (c0 >= C) return;
+  const bf* src = jobs.in[job] + (long long)b * S * C;
+  bf* dst = jobs.out[job] + (long long)b * S * C;
+  const int t = threadIdx.x, q8 = (t & 7) * 8, p = t >> 3;
+#pragma unroll
+  for (int pass = 0; pass < 2; ++pass) {
+    const int r = p + 32 * pass;
+    uint4 v = make_uint4(0u, 0u, 0u, 0u);
+    if (r0 + r < S && c0 + q8 < C) v = *reinterpret_cast<const uint4*>(src + (long long)(r0 + r) * C + c0 + q8);
+    const unsigned wv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int e = 0; e < 8; ++e) tile[q8 + e][r] = (bf)(wv[e >> 1] >> (16 * (e & 1)));
+  }
   __syncthreads();
-  for (int c = ty; c < 64; c += 4)
-    if (c0 + c < C && r0 + tx < R) dst[(long long)(c0 + c) * ldo + r0 + tx] = FROM_BF16 ? F2E(bf2f(tile[tx][c])) : tile[tx][c];
-}
-
-// storage bf16 -> compute element (identity when the element type is bf16)
-__global__ void __launch_bounds__(256) k_from_bf16(const bf* in, bf* out, long long n) {
-  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
-  if (i < n) out[i] = F2E(bf2f(in[i]));
+#pragma unroll
+  for (int pass = 0; pass < 2; ++pass) {
+    const int c = p + 32 * pass;
+    if (c0 + c < C && r0 + q8 < S)
+      *reinterpret_cast<uint4*>(dst + (long long)(c0 + c) * S + r0 + q8) = *reinterpret_cast<const uint4*>(&tile[c][q8]);
+  }
 }
 
 // ---------------------------------------------------------------- gradient scaling
@@ -179,22 +188,27 @@ __global__ void __launch_bounds__(256) k_amax(const float* x, long long n4, unsi
   if (threadIdx.x == 0)
     atomicMax(amax_bits, __float_as_uint(fmaxf(fmaxf(wmax[0], wmax[1]), fmaxf(wmax[2], wmax[3]))));  // non-negative floats order like their bits
 }
-__global__ void k_scale_reset(unsigned* amax_bits) { *amax_bits = 0u; }
-__global__ void k_scale_make(const unsigned* amax_bits, float* scale, int target_log2) {
-  const float a = __uint_as_float(*amax_bits);
-  float sg = 1.f;
-  if (a > 0.f && a < INFINITY) {
-    int e;
-    frexpf(a, &e);                       // a = f * 2^e, f in [0.5, 1)
-    sg = ldexpf(1.f, min(max(target_log2 - e, -100), 100));
-  }
-  scale[0] = sg;
-  scale[1] = 1.f / sg;
+// sigma from the largest magnitude: the power of two that brings it to 2^target_log2 (1 for an all-zero or non-finite dY)
+__device__ __forceinline__ float sigma_of(unsigned amax_bits, int target_log2) {
+  const float a = __uint_as_float(amax_bits);
+  if (!(a > 0.f && a < INFINITY)) return 1.f;
+  int e;
+  frexpf(a, &e);  // a = f * 2^e, f in [0.5, 1)
+  return ldexpf(1.f, min(max(target_log2 - e, -100), 100));
 }
-__global__ void __launch_bounds__(256) k_f32_to_e_scaled(const float* x, bf* y, long long n4, const float* scale) {
+// y = 16-bit(x * sigma).  Every workgroup derives sigma from the maximum that k_amax left in bits[0]; workgroup 0 also
+// publishes scale[0] = sigma, scale[1] = 1 / sigma for the kernels downstream and clears bits[1], the slot the next
+// call's k_amax will use (the two slots alternate, so no launch is spent on a reset).
+__global__ void __launch_bounds__(256) k_f32_to_e_scaled(const float* x, bf* y, long long n4, const unsigned* bits_now,
+                                                         unsigned* bits_next, float* scale, int target_log2) {
+  const float sg = sigma_of(*bits_now, target_log2);
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    scale[0] = sg;
+    scale[1] = 1.f / sg;
+    *bits_next = 0u;
+  }
   const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
   if (i >= n4) return;
-  const float sg = scale ? *scale : 1.f;
   const float4 v = reinterpret_cast<const float4*>(x)[i];
   reinterpret_cast<uint2*>(y)[i] = make_uint2(PACK2(v.x * sg, v.y * sg), PACK2(v.z * sg, v.w * sg));
 }
@@ -207,14 +221,14 @@ __device__ __forceinline__ f32x4 mma16(const u32x4& a, const u32x4& b, f32x4 c) 
   return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
 }
 template <int NT>
-__global__ void __launch_bounds__(512) k_skinny_nt(SkinnyNtJobs jobs, int M, float alpha, int* flag) {
+__global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) k_skinny_nt(SkinnyNtJobs jobs, int M, float alpha, int* flag) {
   const SkinnyNtJob& jb = jobs.j[blockIdx.y];
   const bf* X = jb.X;
   const bf* Bm = jb.Bm;
   bf* C = jb.C;
   const long long ldx = jb.ldx, ldb = jb.ldb, ldc = jb.ldc;
   const int N = jb.N, K = jb.K;
-  constexpr int NW = 8, U = 4;
+  constexpr int NW = 8, U = NT == 1 ? 16 : NT == 2 ? 8 : 4;  // K steps in flight per wave: a wave has few steps, latency is what it waits for
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, i16 = lane & 15, g = lane >> 4;
   const int m0 = blockIdx.x * 16;
   const int mr = min(m0 + i16, M - 1);
@@ -236,6 +250,7 @@ __global__ void __launch_bounds__(512) k_skinny_nt(SkinnyNtJobs jobs, int M, flo
 #pragma unroll
       for (int t = 0; t < NT; ++t) bfr[t][u] = *reinterpret_cast<const u32x4*>(br[t] + ((s + u) << 5));
     }
+    __builtin_amdgcn_sched_barrier(0);  // every load of the group is issued before the first product waits for one
 #pragma unroll
     for (int u = 0; u < U; ++u)
 #pragma unroll
@@ -515,32 +530,20 @@ void ft_rmsnorm_bwd(const float* dh, const float* x, const float* rho, const flo
 void ft_rope(bf* t, int T, int S, int heads, int d, const double* inv_freq, bool inverse, int* flag, hipStream_t st) {
   hipLaunchKernelGGL(k_rope, dim3(T), dim3(256), 0, st, t, S, heads, d, inv_freq, inverse ? -1.f : 1.f, flag);
 }
-void ft_f32_to_e(const float* x, bf* y, long long n, const float* scale, hipStream_t st) {
-  hipLaunchKernelGGL(k_f32_to_e_scaled, dim3(nblk(n / 4, 256)), dim3(256), 0, st, x, y, n / 4, scale);
-}
-void ft_transpose(const bf* in, bf* out, int Z, int R, int C, long long ldi, long long bsi, long long ldo, long long bso,
-                  hipStream_t st) {
-  hipLaunchKernelGGL(k_transpose<false>, dim3((C + 63) / 64, (R + 63) / 64, Z), dim3(256), 0, st, in, out, R, C, ldi, bsi, ldo, bso);
-}
-void ft_transpose_from_bf16(const bf* in, bf* out, int R, int C, hipStream_t st) {
-  hipLaunchKernelGGL(k_transpose<true>, dim3((C + 63) / 64, (R + 63) / 64, 1), dim3(256), 0, st, in, out, R, C,
-                     (long long)C, 0LL, (long long)R, 0LL);
-}
 void ft_convert_jobs(const FtConvJobs& jobs, hipStream_t st) {
   hipLaunchKernelGGL(k_convert_jobs, dim3(64, jobs.n), dim3(256), 0, st, jobs);
 }
-void ft_from_bf16(const bf* in, bf* out, long long n, hipStream_t st) {
-  hipLaunchKernelGGL(k_from_bf16, dim3(nblk(n, 256)), dim3(256), 0, st, in, out, n);
-}
-void ft_make_scale(const float* x, long long n, float* scale, int target_log2, hipStream_t st) {
+void ft_scale_to_e(const float* x, bf* y, long long n, float* scale, int parity, int target_log2, hipStream_t st) {
   unsigned* bits = reinterpret_cast<unsigned*>(scale + 2);
-  hipLaunchKernelGGL(k_scale_reset, dim3(1), dim3(1), 0, st, bits);
-  hipLaunchKernelGGL(k_amax, dim3(std::min(nblk(n / 4, 1024), 1024u)), dim3(256), 0, st, x, n / 4, bits);
-  hipLaunchKernelGGL(k_scale_make, dim3(1), dim3(1), 0, st, bits, scale, target_log2);
+  hipLaunchKernelGGL(k_amax, dim3(std::min(nblk(n / 4, 1024), 1024u)), dim3(256), 0, st, x, n / 4, bits + (parity & 1));
+  hipLaunchKernelGGL(k_f32_to_e_scaled, dim3(nblk(n / 4, 256)), dim3(256), 0, st, x, y, n / 4, bits + (parity & 1),
+                     bits + ((parity & 1) ^ 1), scale, target_log2);
 }
-void ft_transpose_heads(const bf* in, bf* out, int Bf, int S, int heads, int d, hipStream_t st) {
-  // per sequence b: [S][heads*d] -> [heads*d][S] = [heads][d][S]
-  ft_transpose(in, out, Bf, S, heads * d, (long long)heads * d, (long long)S * heads * d, S, (long long)S * heads * d, st);
+void ft_transpose_heads(const TransposeJobs& jobs, int Bf, int S, hipStream_t st) {
+  if (jobs.n < 1) return;
+  int cmax = 0;
+  for (int i = 0; i < jobs.n; ++i) cmax = std::max(cmax, jobs.C[i]);
+  hipLaunchKernelGGL(k_transpose_heads, dim3((cmax + 63) / 64, (S + 63) / 64, Bf * jobs.n), dim3(256), 0, st, jobs, Bf, S);
 }
 void ft_skinny_nt_multi(const SkinnyNtJobs& jobs, int M, float alpha, int* flag, hipStream_t st) {
   if (jobs.n < 1) return;
