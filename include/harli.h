@@ -162,6 +162,13 @@ typedef struct {
   int32_t max_batch;      /* largest decode batch (1..256) */
   int32_t max_seq_len;    /* largest kv_len[b] + 1 a decode step may see */
   int32_t max_ft_tokens;  /* largest B_f*S of a finetune call (0: finetune unused) */
+  /* Where the library's own device memory for this context lives: the decode instance's pre-shuffled weight copies and
+   * step buffers, the finetune instance's weight copies, and both workspaces.  0: the library allocates it.  1: all of
+   * it is taken from the unified pool (Sec. 4.2: one pool holds every tensor of both tasks; TENSOR allocations, small
+   * buffers from the SMALL pool), so that harli_pool_stats accounts for every byte the context holds, and
+   * harli_ctx_create / harli_lora_attach return HARLI_ERR_OOM when the pool cannot hold it (the caller sizes the slab:
+   * harli_ctx_device_bytes reports what a context took).  It implies harli_lora_cfg.workspace_in_pool. */
+  int32_t memory_in_pool;
 } harli_model_cfg;
 
 typedef struct {

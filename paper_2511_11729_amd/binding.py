@@ -50,7 +50,7 @@ class ModelCfg(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("hidden", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
                 ("head_dim", C.c_int32), ("ffn", C.c_int32), ("vocab", C.c_int32), ("rms_eps", C.c_float),
                 ("rope_base", C.c_float), ("dtype", C.c_int32), ("max_batch", C.c_int32), ("max_seq_len", C.c_int32),
-                ("max_ft_tokens", C.c_int32)]
+                ("max_ft_tokens", C.c_int32), ("memory_in_pool", C.c_int32)]
 
 
 class LayerWeights(C.Structure):
@@ -274,11 +274,11 @@ class Context:
 
     def __init__(self, pool: Pool, *, n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab=0,
                  rms_eps=1e-6, rope_base=10000.0, dtype=HARLI_BF16, max_batch=16, max_seq_len=4096,
-                 max_ft_tokens=0, layers, emb=None, g_final=None, w_lm=None):
+                 max_ft_tokens=0, layers, emb=None, g_final=None, w_lm=None, memory_in_pool=False):
         self.pool = pool
         self._keep = (layers, emb, g_final, w_lm)
         self.cfg = ModelCfg(n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab, rms_eps, rope_base, dtype,
-                            max_batch, max_seq_len, max_ft_tokens)
+                            max_batch, max_seq_len, max_ft_tokens, int(bool(memory_in_pool)))
         arr = (LayerWeights * n_layers)()
         for i, lw in enumerate(layers):
             for n in ("wq", "wk", "wv", "wo", "wg", "wu", "wd", "g1", "g2"):

@@ -2,6 +2,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 
+#include <unordered_map>
 #include <vector>
 
 #include "common.h"
@@ -38,7 +39,6 @@ struct DecodeWs {
   float* rope = nullptr;      // [bpad][d/2][2]
   double* inv_freq = nullptr; // [d/2] base^(-2i/d)
   float* att_part = nullptr;  // [bpad][n_q][max_chunks][d+2]
-  int* att_cnt = nullptr;     // [bpad][n_kv]
   float* amax_v = nullptr;    // [bpad][64] per-slice maxima of the logits (full-model mode)
   int* amax_i = nullptr;      // [bpad][64] and their indices
   float* scores = nullptr;    // fp32 path only: [bpad][n_q][max_seq_len]
@@ -70,9 +70,14 @@ struct harli_ctx {
   void* window = nullptr;    // window over the finetune task's frozen weights (library-owned), or null
   int n_cu = 0;
   size_t decode_ws_bytes = 0, decode_weight_bytes = 0;  // device memory harli_ctx_create allocated
+  std::unordered_map<void*, harli_alloc> pool_allocs;   // library buffers that are allocations of the pool (cfg.memory_in_pool)
 };
 
 namespace harli {
+// A device buffer the library keeps for the context: from the pool when cfg.memory_in_pool is set (HARLI_ERR_OOM when
+// it has no room), else a library allocation.  lib_free takes either kind (and null).
+harli_status lib_alloc(harli_ctx* c, void** p, size_t bytes);
+void lib_free(harli_ctx* c, void* p);
 size_t packed_weight_elems(int N, int K);
 harli_status pack_weight(const void* src, void* dst, int N, int K, int row_tile0, hipStream_t st);
 // element size of the storage dtype

@@ -17,10 +17,35 @@ int event_done(void* hip_event) {
 
 void event_destroy(void* hip_event) { (void)hipEventDestroy(static_cast<hipEvent_t>(hip_event)); }
 
+harli_status lib_alloc(harli_ctx* c, void** p, size_t bytes) {
+  if (bytes == 0) bytes = 16;
+  if (!c->cfg.memory_in_pool) {
+    HARLI_HIP(hipMalloc(p, bytes));
+    return HARLI_OK;
+  }
+  harli_alloc a{};
+  harli_status s = harli_pool_alloc(c->pool, HARLI_CLS_AUTO, bytes, &a);
+  if (s != HARLI_OK) return s;
+  c->pool_allocs[a.ptr] = a;
+  *p = a.ptr;
+  return HARLI_OK;
+}
+void lib_free(harli_ctx* c, void* p) {
+  if (!p) return;
+  auto it = c->pool_allocs.find(p);
+  if (it == c->pool_allocs.end()) {
+    (void)hipFree(p);
+    return;
+  }
+  (void)harli_pool_free(c->pool, &it->second, nullptr);
+  c->pool_allocs.erase(it);
+}
+
 static size_t g_tally = 0;  // bytes handed out by dev_alloc since the caller last read it (harli_ctx_create is not re-entrant)
 template <typename T>
-static harli_status dev_alloc(T** p, size_t bytes, bool zero) {
-  HARLI_HIP(hipMalloc(reinterpret_cast<void**>(p), bytes ? bytes : 16));
+static harli_status dev_alloc(harli_ctx* c, T** p, size_t bytes, bool zero) {
+  harli_status s = lib_alloc(c, reinterpret_cast<void**>(p), bytes);
+  if (s != HARLI_OK) return s;
   if (zero) HARLI_HIP(hipMemset(*p, 0, bytes ? bytes : 16));
   g_tally += bytes ? bytes : 16;
   return HARLI_OK;
@@ -124,22 +149,22 @@ extern "C" harli_status harli_ctx_create(const harli_model_cfg* cfg, const harli
   d.bpad = (m.max_batch + 15) / 16 * 16;
   d.max_chunks = (m.max_seq_len + 127) / 128;  // the smallest attention chunk is 128 tokens
   const size_t bp = d.bpad;
-  TRY(dev_alloc(&d.hx1, bp * m.hidden * 4, true));
-  TRY(dev_alloc(&d.obuf, bp * QD * 4, true));
-  TRY(dev_alloc(&d.hx2, bp * m.hidden * 4, true));
-  TRY(dev_alloc(&d.mbuf, bp * m.ffn * 4, true));
-  TRY(dev_alloc(&d.qbuf, bp * QD * 4, true));
-  TRY(dev_alloc(&d.x1, bp * m.hidden * 4, true));
-  TRY(dev_alloc(&d.xa, bp * m.hidden * 4, true));
-  TRY(dev_alloc(&d.xb, bp * m.hidden * 4, true));
-  TRY(dev_alloc(&d.ssq, bp * (2 * m.n_layers + 1) * 16, true));
-  TRY(dev_alloc(&d.rope, bp * m.head_dim * 4, true));
+  TRY(dev_alloc(c, &d.hx1, bp * m.hidden * 4, true));
+  TRY(dev_alloc(c, &d.obuf, bp * QD * 4, true));
+  TRY(dev_alloc(c, &d.hx2, bp * m.hidden * 4, true));
+  TRY(dev_alloc(c, &d.mbuf, bp * m.ffn * 4, true));
+  TRY(dev_alloc(c, &d.qbuf, bp * QD * 4, true));
+  TRY(dev_alloc(c, &d.x1, bp * m.hidden * 4, true));
+  TRY(dev_alloc(c, &d.xa, bp * m.hidden * 4, true));
+  TRY(dev_alloc(c, &d.xb, bp * m.hidden * 4, true));
+  TRY(dev_alloc(c, &d.ssq, bp * (2 * m.n_layers + 1) * 16, true));
+  TRY(dev_alloc(c, &d.rope, bp * m.head_dim * 4, true));
   if (m.vocab > 0) {
-    TRY(dev_alloc(&d.amax_v, bp * 64 * 4, true));
-    TRY(dev_alloc(&d.amax_i, bp * 64 * 4, true));
+    TRY(dev_alloc(c, &d.amax_v, bp * 64 * 4, true));
+    TRY(dev_alloc(c, &d.amax_i, bp * 64 * 4, true));
   }
   {
-    TRY(dev_alloc(&d.inv_freq, (m.head_dim / 2) * sizeof(double), false));
+    TRY(dev_alloc(c, &d.inv_freq, (m.head_dim / 2) * sizeof(double), false));
     std::vector<double> f(m.head_dim / 2);
     for (int i = 0; i < m.head_dim / 2; ++i) f[i] = std::pow((double)m.rope_base, -2.0 * i / (double)m.head_dim);
     if (hipMemcpy(d.inv_freq, f.data(), f.size() * sizeof(double), hipMemcpyHostToDevice) != hipSuccess) {
@@ -147,16 +172,15 @@ extern "C" harli_status harli_ctx_create(const harli_model_cfg* cfg, const harli
       return fail(HARLI_ERR_HIP, "ctx_create: copying the rotary table failed");
     }
   }
-  TRY(dev_alloc(&d.att_part, bp * m.n_q_heads * d.max_chunks * (m.head_dim + 2) * 4, true));
-  TRY(dev_alloc(&d.att_cnt, bp * m.n_kv_heads * 4, true));
-  TRY(dev_alloc(&d.err_flag, 16, true));
+  TRY(dev_alloc(c, &d.att_part, bp * m.n_q_heads * d.max_chunks * (m.head_dim + 2) * 4, true));
+  TRY(dev_alloc(c, &d.err_flag, 16, true));
   // fp32 path: scratch for attention scores, one row of max_seq_len per (sequence, query head)
   if (m.dtype == HARLI_F32) {
-    TRY(dev_alloc(&d.scores, bp * m.n_q_heads * (size_t)m.max_seq_len * 4, true));
-    TRY(dev_alloc(&d.fk, bp * m.n_kv_heads * m.head_dim * 4, true));
-    TRY(dev_alloc(&d.fv, bp * m.n_kv_heads * m.head_dim * 4, true));
-    TRY(dev_alloc(&d.fa, bp * m.ffn * 4, true));
-    TRY(dev_alloc(&d.fu, bp * m.ffn * 4, true));
+    TRY(dev_alloc(c, &d.scores, bp * m.n_q_heads * (size_t)m.max_seq_len * 4, true));
+    TRY(dev_alloc(c, &d.fk, bp * m.n_kv_heads * m.head_dim * 4, true));
+    TRY(dev_alloc(c, &d.fv, bp * m.n_kv_heads * m.head_dim * 4, true));
+    TRY(dev_alloc(c, &d.fa, bp * m.ffn * 4, true));
+    TRY(dev_alloc(c, &d.fu, bp * m.ffn * 4, true));
   }
   c->decode_ws_bytes = g_tally;
   g_tally = 0;
@@ -165,19 +189,19 @@ extern "C" harli_status harli_ctx_create(const harli_model_cfg* cfg, const harli
     const int KVD = m.n_kv_heads * m.head_dim;
     for (int l = 0; l < m.n_layers; ++l) {
       LayerDev& ld = c->layers[l];
-      TRY(dev_alloc(&ld.wp[0], packed_weight_elems(QD + 2 * KVD, m.hidden) * 2, false));
+      TRY(dev_alloc(c, &ld.wp[0], packed_weight_elems(QD + 2 * KVD, m.hidden) * 2, false));
       TRY(pack_weight(ld.w[0], ld.wp[0], QD, m.hidden, 0, nullptr));
       TRY(pack_weight(ld.w[1], ld.wp[0], KVD, m.hidden, QD / 16, nullptr));
       TRY(pack_weight(ld.w[2], ld.wp[0], KVD, m.hidden, (QD + KVD) / 16, nullptr));
       for (int t = 3; t < kTargets; ++t) {
         int o, i;
         proj_shape(m, t, &o, &i);
-        TRY(dev_alloc(&ld.wp[t], packed_weight_elems(o, i) * 2, false));
+        TRY(dev_alloc(c, &ld.wp[t], packed_weight_elems(o, i) * 2, false));
         TRY(pack_weight(ld.w[t], ld.wp[t], o, i, 0, nullptr));
       }
     }
     if (c->w_lm) {
-      TRY(dev_alloc(&c->wlm_p, packed_weight_elems(m.vocab, m.hidden) * 2, false));
+      TRY(dev_alloc(c, &c->wlm_p, packed_weight_elems(m.vocab, m.hidden) * 2, false));
       TRY(pack_weight(c->w_lm, c->wlm_p, m.vocab, m.hidden, 0, nullptr));
     }
     if (hipDeviceSynchronize() != hipSuccess) {
@@ -198,9 +222,9 @@ extern "C" harli_status harli_ctx_device_bytes(const harli_ctx* c, harli_device_
   int ft_pool = 0, head_pool = 0;
   finetune_device_bytes(c, &b.finetune_weights, &b.finetune_workspace, &ft_pool);
   head_device_bytes(c, &b.head_weights, &b.head_workspace, &head_pool);
-  b.in_pool = (ft_pool ? b.finetune_workspace : 0) + (head_pool ? b.head_workspace : 0);
-  b.outside_pool = b.decode_weights + b.decode_workspace + b.finetune_weights + b.finetune_workspace + b.head_weights +
-                   b.head_workspace - b.in_pool;
+  const size_t all = b.decode_weights + b.decode_workspace + b.finetune_weights + b.finetune_workspace + b.head_weights + b.head_workspace;
+  b.in_pool = c->cfg.memory_in_pool ? all : (ft_pool ? b.finetune_workspace : 0) + (head_pool ? b.head_workspace : 0);
+  b.outside_pool = all - b.in_pool;
   *out = b;
   return HARLI_OK;
 }
@@ -208,13 +232,12 @@ extern "C" harli_status harli_ctx_device_bytes(const harli_ctx* c, harli_device_
 extern "C" void harli_ctx_destroy(harli_ctx* c) {
   if (!c) return;
   DecodeWs& d = c->dw;
-  void* bufs[] = {d.hx1, d.obuf, d.hx2, d.mbuf, d.qbuf, d.x1, d.xa, d.xb, d.ssq, d.rope, d.att_part, d.att_cnt, d.amax_v, d.amax_i, d.err_flag, d.scores, d.inv_freq, d.fk, d.fv, d.fa, d.fu};
-  for (void* p : bufs)
-    if (p) (void)hipFree(p);
+  void* bufs[] = {d.hx1, d.obuf, d.hx2, d.mbuf, d.qbuf, d.x1, d.xa, d.xb, d.ssq, d.rope, d.att_part, d.amax_v, d.amax_i, d.err_flag, d.scores, d.inv_freq, d.fk, d.fv, d.fa, d.fu};
+  (void)hipDeviceSynchronize();  // steps in flight may still read what goes back to the pool here
+  for (void* p : bufs) lib_free(c, p);
   for (LayerDev& ld : c->layers)
-    for (int t = 0; t < kTargets; ++t)
-      if (ld.wp[t]) (void)hipFree(ld.wp[t]);
-  if (c->wlm_p) (void)hipFree(c->wlm_p);
+    for (int t = 0; t < kTargets; ++t) lib_free(c, ld.wp[t]);
+  lib_free(c, c->wlm_p);
   if (c->window) detach_layers(c);  // the weight tables point into window slots
   free_window_state(c);
   free_finetune_state(c);

@@ -132,7 +132,7 @@ harli_status make_ws(harli_ctx* c) {
   const size_t o_dob = take(T * D.QD * 2), o_dq = take(T * D.QD * 2), o_dkq = take(T * D.QD * 2), o_dvq = take(T * D.QD * 2);
   const size_t o_dk = take(T * D.KVD * 2), o_dv = take(T * D.KVD * 2), o_gs = take(3 * al(T * D.r * 2));
   const size_t o_gpart = take(ft_lora_grad_ws_floats((int)maxdim, D.r) * 4);
-  const bool want_pool = c->lora.workspace_in_pool != 0;
+  const bool want_pool = c->lora.workspace_in_pool != 0 || c->cfg.memory_in_pool != 0;
   if (off != w.bytes || want_pool != fs->ws_in_pool) {  // first attach, or another rank / placement than before
     harli_status r = free_ws(c);
     if (r != HARLI_OK) return r;
@@ -356,19 +356,19 @@ void free_finetune_state(harli_ctx* c) {
   for (LayerDev& L : c->layers)
     for (int t = 0; t < 3; ++t)
       if (L.b16[t]) {
-        (void)hipFree(L.b16[t]);
+        lib_free(c, L.b16[t]);
         L.b16[t] = nullptr;
       }
   if (c->ones16) {
-    (void)hipFree(c->ones16);
+    lib_free(c, c->ones16);
     c->ones16 = nullptr;
   }
   for (LayerDev& L : c->layers)
     for (int t = 0; t < kTargets; ++t)
       if (L.wt[t]) {
-        (void)hipFree(L.wt[t]);
+        lib_free(c, L.wt[t]);
         L.wt[t] = nullptr;
-        if (L.w16[t]) (void)hipFree(L.w16[t]);
+        lib_free(c, L.w16[t]);
         L.w16[t] = nullptr;
       }
   if (c->ft_ws) {
@@ -407,8 +407,13 @@ extern "C" harli_status harli_lora_attach(harli_ctx* c, const harli_lora_cfg* cf
         int out, in;   // blocked order: W as the operand [out rows, in] of the forward pass, W^T [in rows, out] for dx = dy W
         proj_shape(c->cfg, t, &out, &in);
         const size_t nb = ft_weight_copy_bytes(out, in);
-        HARLI_HIP(hipMalloc(&L.wt[t], nb));
-        HARLI_HIP(hipMalloc(&L.w16[t], nb));
+        harli_status am = lib_alloc(c, &L.wt[t], nb);
+        if (am == HARLI_OK) am = lib_alloc(c, &L.w16[t], nb);
+        if (am != HARLI_OK) {  // a half-made pair would look attached to the next call
+          lib_free(c, L.wt[t]);
+          L.wt[t] = L.w16[t] = nullptr;
+          return am;
+        }
         const int f32 = c->cfg.dtype == HARLI_F32 ? 1 : 0;
         BlockJobs jobs{};
         jobs.half = 1;
@@ -433,13 +438,19 @@ extern "C" harli_status harli_lora_attach(harli_ctx* c, const harli_lora_cfg* cf
       // blocked operand [out rows, K = 8]: one K step per row tile, row n of a tile at 32 n, the bias in column 0
       std::vector<unsigned short> h16(blocked_elems(out, 8), 0);
       for (int n = 0; n < out; ++n) h16[(size_t)(n / kG2TileN) * (kG2TileN * kG2StepK) + (size_t)(n % kG2TileN) * kG2StepK] = host_to_elem(hb[n]);
-      HARLI_HIP(hipMalloc(&L.b16[t], h16.size() * 2));
+      {
+        harli_status am = lib_alloc(c, &L.b16[t], h16.size() * 2);
+        if (am != HARLI_OK) return am;
+      }
       HARLI_HIP(hipMemcpy(L.b16[t], h16.data(), h16.size() * 2, hipMemcpyHostToDevice));
     }
   }
   if (any_bias && !c->ones16) {
     std::vector<unsigned short> ones((size_t)c->cfg.max_ft_tokens * 8, host_to_elem(1.0f));
-    HARLI_HIP(hipMalloc(&c->ones16, ones.size() * 2));
+    {
+      harli_status am = lib_alloc(c, &c->ones16, ones.size() * 2);
+      if (am != HARLI_OK) return am;
+    }
     HARLI_HIP(hipMemcpy(c->ones16, ones.data(), ones.size() * 2, hipMemcpyHostToDevice));
   }
   HARLI_HIP(hipDeviceSynchronize());
@@ -451,8 +462,8 @@ extern "C" harli_status harli_lora_attach(harli_ctx* c, const harli_lora_cfg* cf
       HARLI_HIP(hipMemcpy(c->dw.err_flag, &flag, sizeof(int), hipMemcpyHostToDevice));
       for (LayerDev& L : c->layers)
         for (int t = 0; t < kTargets; ++t) {
-          if (L.wt[t]) (void)hipFree(L.wt[t]);
-          if (L.w16[t]) (void)hipFree(L.w16[t]);
+          lib_free(c, L.wt[t]);
+          lib_free(c, L.w16[t]);
           L.wt[t] = L.w16[t] = nullptr;
         }
       return fail(HARLI_ERR_INVALID, "lora_attach: a frozen weight lies beyond the range of the 16-bit compute element (|w| > 65504)");

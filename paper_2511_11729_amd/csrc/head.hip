@@ -135,8 +135,13 @@ harli_status head_prepare(harli_ctx* c) {
   const int V = c->cfg.vocab, H = c->cfg.hidden, T = c->cfg.max_ft_tokens;
   const int Vp = (V + 7) & ~7;
   if (!w.weights_ready) {
-    HARLI_HIP(hipMalloc(reinterpret_cast<void**>(&w.w16), blocked_elems(V, H) * 2));
-    HARLI_HIP(hipMalloc(reinterpret_cast<void**>(&w.wT), blocked_elems(H, Vp) * 2));
+    harli_status am = lib_alloc(c, reinterpret_cast<void**>(&w.w16), blocked_elems(V, H) * 2);
+    if (am == HARLI_OK) am = lib_alloc(c, reinterpret_cast<void**>(&w.wT), blocked_elems(H, Vp) * 2);
+    if (am != HARLI_OK) {
+      lib_free(c, w.w16);
+      w.w16 = w.wT = nullptr;
+      return am;
+    }
     const int f32 = c->cfg.dtype == HARLI_F32 ? 1 : 0;
     BlockJobs jobs{};
     jobs.half = 1;
@@ -159,7 +164,7 @@ harli_status head_prepare(harli_ctx* c) {
   };
   const size_t o_h = take((size_t)T * H * 2), o_rho = take((size_t)T * 4), o_log = take((size_t)TC * Vp * 4);
   const size_t o_dlog = take((size_t)TC * Vp * 2), o_dh = take((size_t)T * H * 4), o_acc = take(64), o_rl = take((size_t)T * 4);
-  const bool want_pool = c->lora.workspace_in_pool != 0;
+  const bool want_pool = c->lora.workspace_in_pool != 0 || c->cfg.memory_in_pool != 0;
   if (off != w.bytes || want_pool != w.in_pool) {
     harli_status r = head_free_ws(c);
     if (r != HARLI_OK) return r;
@@ -195,8 +200,8 @@ void free_head_state(harli_ctx* c) {
   if (!c->head_ws) return;
   HeadWs* w = ws_of(c);
   (void)head_free_ws(c);
-  if (w->w16) (void)hipFree(w->w16);
-  if (w->wT) (void)hipFree(w->wT);
+  lib_free(c, w->w16);
+  lib_free(c, w->wT);
   delete w;
   c->head_ws = nullptr;
 }

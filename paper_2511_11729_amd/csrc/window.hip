@@ -218,8 +218,8 @@ extern "C" harli_status harli_ft_window_enable(harli_ctx* c, int32_t n_slots) {
   for (int l = 0; l < L; ++l)
     for (int t = 0; t < kTargets; ++t) {
       LayerDev& Ld = c->layers[l];
-      (void)hipFree(Ld.w16[t]);
-      (void)hipFree(Ld.wt[t]);
+      lib_free(c, Ld.w16[t]);
+      lib_free(c, Ld.wt[t]);
       Ld.w16[t] = Ld.wt[t] = nullptr;
     }
   return fill_empty(w);
@@ -239,8 +239,9 @@ extern "C" harli_status harli_ft_window_disable(harli_ctx* c) {
       int out, in;
       proj_shape(c->cfg, t, &out, &in);
       const size_t nb = ft_weight_copy_bytes(out, in);
-      HARLI_HIP(hipMalloc(&Ld.w16[t], nb));
-      HARLI_HIP(hipMalloc(&Ld.wt[t], nb));
+      harli_status am = lib_alloc(c, &Ld.w16[t], nb);
+      if (am == HARLI_OK) am = lib_alloc(c, &Ld.wt[t], nb);
+      if (am != HARLI_OK) return am;
       HARLI_HIP(hipMemcpy(Ld.w16[t], w->host + (size_t)l * w->item_bytes + w->off[t], nb, hipMemcpyHostToDevice));
       HARLI_HIP(hipMemcpy(Ld.wt[t], w->host + (size_t)(2 * L - 1 - l) * w->item_bytes + w->off[t], nb, hipMemcpyHostToDevice));
     }

@@ -51,7 +51,8 @@ class DecodeCase:
     """One decode step on both sides.  `model` may differ from the workload's (shape variants)."""
 
     def __init__(self, w: wl.Workload, model: wl.ModelCfg, lengths, *, full_model=False, block_bytes=2 << 20,
-                 small_pool_bytes=0, extra_chunks=1, max_batch=None, reserve=0, tweak=None):
+                 small_pool_bytes=0, extra_chunks=1, max_batch=None, reserve=0, tweak=None,
+                 memory_in_pool=False):
         self.w, self.m = w, model
         m = model
         self.B = B = len(lengths)
@@ -119,7 +120,7 @@ class DecodeCase:
                               head_dim=m.head_dim, ffn=m.ffn, rms_eps=m.rms_eps, rope_base=m.rope_base,
                               dtype=hb.HARLI_BF16 if m.dtype == "bf16" else hb.HARLI_F32,
                               max_batch=max_batch or B, max_seq_len=int(max(self.kv_len)) + 8,
-                              layers=self.layers_dev, **kw)
+                              layers=self.layers_dev, memory_in_pool=memory_in_pool, **kw)
         self.kv_len_dev = torch.from_numpy(self.kv_len.astype(np.int32)).to(DEV)
         self.table_dev = torch.from_numpy(self.table).to(DEV)
         self.x_dev = f32_dev(self.x_np)
@@ -179,7 +180,7 @@ class FinetuneCase:
 
     def __init__(self, w: wl.Workload, model: wl.ModelCfg, lora: wl.LoraCfg, ft: wl.FinetuneCfg, *,
                  block_bytes=2 << 20, small_pool_bytes=8 << 20, zero_b=False, n_chunks=None, sets=1, tweak=None,
-                 grad_headroom_log2=0, attach=True):
+                 grad_headroom_log2=0, attach=True, memory_in_pool=False):
         """tweak(case): edits W_np / lora_np / X_np (both sides then see the edited values)."""
         self.w, self.m, self.lora, self.ft = w, model, lora, ft
         m = model
@@ -207,7 +208,7 @@ class FinetuneCase:
         self.ctx = hb.Context(self.pool, n_layers=m.n_layers, hidden=m.hidden, n_q_heads=m.n_q, n_kv_heads=m.n_kv,
                               head_dim=m.head_dim, ffn=m.ffn, rms_eps=m.rms_eps, rope_base=m.rope_base,
                               dtype=hb.HARLI_BF16 if m.dtype == "bf16" else hb.HARLI_F32, max_batch=1, max_seq_len=16,
-                              max_ft_tokens=T,
+                              max_ft_tokens=T, memory_in_pool=memory_in_pool,
                               layers=[self.layer_dev])
         self.A_dev = {p: to_dev(a, m.dtype) for p, (a, b) in self.lora_np.items()}
         self.B_dev = {p: to_dev(b, m.dtype) for p, (a, b) in self.lora_np.items()}

@@ -105,3 +105,46 @@ def test_pool_and_context_may_be_destroyed_in_either_order():
     fc2.ctx.lora_attach(fc2.lora.rank, fc2.lora.alpha, fc2.lora.targets, [fc2.A_dev], [fc2.B_dev], workspace_in_pool=True)
     fc2.pool.close()
     fc2.ctx.close()
+
+
+def test_all_library_memory_in_the_pool_is_accounted_and_changes_no_result():
+    """memory_in_pool: the decode instance's weight copies and step buffers, the finetune instance's weight copies and
+    both workspaces are allocations of the unified pool (Sec. 4.2); the pool's statistics cover every byte the context
+    reports, nothing is left outside, results are the bits of a context that allocates for itself, and destroying the
+    context gives everything back."""
+    w = wl.workload(0)
+    m = dataclasses.replace(w.model, dtype="bf16")
+    ref = FinetuneCase(w, m, w.lora, w.finetune, n_chunks=64)
+    _, _, dY, _, _ = ref.oracle()
+    Y0, dX0, g0 = unit(ref, dY)
+    fc = FinetuneCase(w, m, w.lora, w.finetune, n_chunks=96, memory_in_pool=True)
+    b = fc.ctx.device_bytes()
+    assert b.outside_pool == 0 and b.in_pool == (b.decode_weights + b.decode_workspace + b.finetune_weights
+                                                 + b.finetune_workspace + b.head_weights + b.head_workspace) > 0
+    st = fc.pool.stats()
+    assert st.reserved_bytes_live >= b.in_pool and st.requested_bytes_live >= b.in_pool
+    assert ref.ctx.device_bytes().outside_pool == b.in_pool       # the same buffers, only placed elsewhere
+    Y1, dX1, g1 = unit(fc, dY)
+    assert np.array_equal(Y0, Y1) and np.array_equal(dX0, dX1)
+    for p in g0:
+        assert np.array_equal(g0[p][0], g1[p][0]) and np.array_equal(g0[p][1], g1[p][1])
+    fc.ctx.check()
+    fc.ctx.close()
+    torch.cuda.synchronize()
+    st = fc.pool.stats()
+    assert st.tensor_blocks_live == 0 and st.small_bytes_live == 0 and st.free_chunks == st.n_chunks
+
+
+def test_decode_from_pool_memory_gives_the_same_step_and_a_full_pool_refuses_the_context():
+    from tests.gpu_util import DecodeCase
+    w = wl.workload(0)
+    m = dataclasses.replace(w.model, dtype="bf16")
+    lengths = [70, 121, 64, 99]
+    a = DecodeCase(w, m, lengths)
+    b = DecodeCase(w, m, lengths, extra_chunks=24, memory_in_pool=True)
+    ya, yb = a.run_gpu(), b.run_gpu()
+    assert np.array_equal(np.asarray(ya), np.asarray(yb))
+    assert b.ctx.device_bytes().outside_pool == 0 and b.pool.stats().tensor_blocks_live > 0
+    with pytest.raises(hb.HarliError) as e:                      # one spare chunk cannot hold the weight copies
+        DecodeCase(w, m, lengths, extra_chunks=1, memory_in_pool=True)
+    assert e.value.status == hb.HARLI_ERR_OOM
