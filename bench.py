@@ -103,6 +103,10 @@ def main():
     log("[bench] generating config-1 weights and inputs")
     hz = LayerHarness(w, in_flight=8, decode_capacity=(64, 2048))
     ctx, pool, B, kv_len = hz.ctx, hz.pool, hz.B, hz.kv_len
+    db = ctx.device_bytes()
+    lib_mem = {"library_MB_in_pool": db.in_pool / 1e6, "library_MB_outside_pool": db.outside_pool / 1e6,
+               "slab_MB": hz.slab_bytes / 1e6,
+               "note": "weight copies of both instances and both workspaces are allocations of the one pool (Sec. 4.2)"}
     W_np, lora_np, X_np = hz.W_np, hz.lora_np, hz.X_np
 
     sD, sF = torch.cuda.Stream(), torch.cuda.Stream()   # default priority on both
@@ -360,6 +364,7 @@ def main():
         "solo": {"decode_ms_per_step": dec_solo_ms, "finetune_ms_per_step": ft_solo_ms,
                  "finetune_tokens_per_s": T / ft_solo_ms * 1e3},
         "measured_peaks": peaks,
+        "memory": lib_mem,
         "full_depth": full,
         "notes": {"finetune_unit": "a unit is one layer forward + backward on a fixed seeded dY (no loss between them: the loss "
                                    "belongs to the whole-model step, which the full_depth leg times with its output layer, "

@@ -76,7 +76,10 @@ def run(args):
     total_pages = sum(n_pages)
     per_layer = T * H * 12 + T * m.n_q * m.head_dim * 4 + T * m.n_kv * m.head_dim * 4 + T * m.ffn * 6
     kv_chunks = -(-total_pages // ppb) + 1
-    n_chunks = kv_chunks + (L + 1) * (per_layer // chunk + 2) + 4
+    # the library's own memory (decode weight copies, the finetune instance's two copies per layer, the output layer's
+    # copies, both workspaces) is taken from the same pool
+    lib_bytes = 6 * m.layer_params * L + 6 * m.vocab * H + 4 * per_layer + (2 << 30)
+    n_chunks = kv_chunks + (L + 1) * (per_layer // chunk + 2) + lib_bytes // chunk + 8
     small = 256 << 20
     slab_bytes = small + n_chunks * chunk
     slab = torch.zeros(slab_bytes, dtype=torch.uint8, device=dev)
@@ -91,7 +94,8 @@ def run(args):
         k += n_pages[b]
     ctx = hb.Context(pool, n_layers=L, hidden=H, n_q_heads=m.n_q, n_kv_heads=m.n_kv, head_dim=m.head_dim, ffn=m.ffn,
                      vocab=m.vocab, rms_eps=m.rms_eps, rope_base=m.rope_base, dtype=hb.HARLI_BF16, max_batch=B,
-                     max_seq_len=int(kv_len.max()) + 8, max_ft_tokens=T, layers=[layer] * L, emb=emb, g_final=gf, w_lm=wlm)
+                     max_seq_len=int(kv_len.max()) + 8, max_ft_tokens=T, layers=[layer] * L, emb=emb, g_final=gf, w_lm=wlm,
+                     memory_in_pool=True)
     ctx.lora_attach(lora.rank, lora.alpha, lora.targets, A, Bm)
 
     # ---- decode instance
@@ -228,7 +232,8 @@ def run(args):
            "colocated_paced": dict(summarise(paced), decode_interval_ms=pace,
                                    finetune_TFLOPs=ft_flops / (paced["ms_per_step"] * 1e-3) / 1e12,
                                    finetune_frac_of_2500_TFLOPs=ft_flops / (paced["ms_per_step"] * 1e-3) / 1e12 / 2500.0),
-           "pool": {"chunks": st.n_chunks, "kv_chunks": st.kv_chunks, "chunk_MB": chunk / 1e6, "slab_GB": slab_bytes / 1e9},
+           "pool": {"chunks": st.n_chunks, "kv_chunks": st.kv_chunks, "chunk_MB": chunk / 1e6, "slab_GB": slab_bytes / 1e9,
+                    "library_GB_in_pool": ctx.device_bytes().in_pool / 1e9, "library_GB_outside_pool": ctx.device_bytes().outside_pool / 1e9},
            "loss_last": float(loss)}
     # let go of the device memory before the caller goes on
     del graph

@@ -50,7 +50,10 @@ class LayerHarness:
         ppb = block // (P * m.kv_row_bytes)
         act = (T * m.hidden * 12 + T * m.n_q * m.head_dim * 4 + T * m.n_kv * m.head_dim * 4 + T * m.ffn * 6)
         self.in_flight = in_flight
-        n_chunks = -(-total_pages // ppb) + in_flight * (act // chunk + 2) + 4
+        # every byte the library keeps (the decode instance's weight copy, the finetune instance's two, both workspaces)
+        # comes from the pool as well: one pool for all tensors of both tasks (Sec. 4.2)
+        lib_bytes = 6 * m.layer_params + 3 * act + (128 << 20)
+        n_chunks = -(-total_pages // ppb) + in_flight * (act // chunk + 2) + lib_bytes // chunk + 8
         small = 64 << 20
         self.slab_bytes = small + n_chunks * chunk
         self.slab = torch.zeros(self.slab_bytes, dtype=torch.uint8, device=DEV)
@@ -87,7 +90,7 @@ class LayerHarness:
         self.layer = layer
         self.ctx = hb.Context(self.pool, n_layers=1, hidden=m.hidden, n_q_heads=m.n_q, n_kv_heads=m.n_kv, head_dim=m.head_dim,
                               ffn=m.ffn, rms_eps=m.rms_eps, rope_base=m.rope_base, dtype=hb.HARLI_BF16, max_batch=cap_b,
-                              max_seq_len=cap_n + 8, max_ft_tokens=T, layers=[layer])
+                              max_seq_len=cap_n + 8, max_ft_tokens=T, layers=[layer], memory_in_pool=True)
         self.A_dev = {p: dev_bf16(a) for p, (a, b) in self.lora_np.items()}
         self.B_dev = {p: dev_bf16(b) for p, (a, b) in self.lora_np.items()}
         self.ctx.lora_attach(lora.rank, lora.alpha, lora.targets, [self.A_dev], [self.B_dev])
