@@ -35,7 +35,7 @@ struct DecodeWs {
   int bpad = 0;
   void *hx1 = nullptr, *obuf = nullptr, *hx2 = nullptr, *mbuf = nullptr;  // GEMM operands in storage dtype
   float *qbuf = nullptr, *x1 = nullptr, *xa = nullptr, *xb = nullptr;    // fp32
-  unsigned long long* ssq = nullptr;  // [2*L+1][bpad][2]: sums of squares as (hi, lo) integer pairs
+  float* ssq = nullptr;       // [2*L+1][bpad][ssq_entries(hidden)]: per-tile partial sums of squares of the residual rows
   float* rope = nullptr;      // [bpad][d/2][2]
   double* inv_freq = nullptr; // [d/2] base^(-2i/d)
   float* att_part = nullptr;  // [bpad][n_q][max_chunks][d+2]
@@ -74,6 +74,8 @@ struct harli_ctx {
 };
 
 namespace harli {
+// entries per row of DecodeWs::ssq: one per 16 columns of the hidden size, padded to a multiple of 16
+inline int ssq_entries(int hidden) { return (((hidden + 15) >> 4) + 15) & ~15; }
 // A device buffer the library keeps for the context: from the pool when cfg.memory_in_pool is set (HARLI_ERR_OOM when
 // it has no room), else a library allocation.  lib_free takes either kind (and null).
 harli_status lib_alloc(harli_ctx* c, void** p, size_t bytes);

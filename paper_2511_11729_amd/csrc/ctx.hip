@@ -157,7 +157,7 @@ extern "C" harli_status harli_ctx_create(const harli_model_cfg* cfg, const harli
   TRY(dev_alloc(c, &d.x1, bp * m.hidden * 4, true));
   TRY(dev_alloc(c, &d.xa, bp * m.hidden * 4, true));
   TRY(dev_alloc(c, &d.xb, bp * m.hidden * 4, true));
-  TRY(dev_alloc(c, &d.ssq, bp * (2 * m.n_layers + 1) * 16, true));
+  TRY(dev_alloc(c, &d.ssq, bp * (2 * m.n_layers + 1) * (size_t)ssq_entries(m.hidden) * 4, true));
   TRY(dev_alloc(c, &d.rope, bp * m.head_dim * 4, true));
   if (m.vocab > 0) {
     TRY(dev_alloc(c, &d.amax_v, bp * 64 * 4, true));

@@ -48,7 +48,8 @@ struct SkinnyArgs {
   int B, b0, K;             // batch size, first batch row of this pass, contraction length
   int n_rows;               // output rows (tail masking of stores)
   const unsigned short *w0, *w1;  // pre-shuffled weights
-  const unsigned long long* ssq_in;  // sum of squares of the operand's source row (rho) as a (hi, lo) pair, or null
+  const float* ssq_in;  // partial sums of squares of the operand's source row (rho): [row][ssq_np], or null
+  int ssq_np;           // entries per row (a multiple of 16; entries past the producer's tiles are zero)
   float eps, inv_dim;
   // QKV
   float* qbuf;
@@ -65,7 +66,7 @@ struct SkinnyArgs {
   float* out;
   const float* gnext;
   unsigned short* hxn;  // next operand (fragment order, K = n_rows) or null
-  unsigned long long* ssq_out;  // (hi, lo) pairs, see ssq_add
+  float* ssq_out;       // [row][ssq_np]: this launch writes entry `tile` of every row it finishes
   // GATEUP
   unsigned short* mbuf;  // next operand (fragment order, K = n_rows)
   // LM
@@ -74,25 +75,21 @@ struct SkinnyArgs {
 
 __device__ __forceinline__ uint4 ld16(const unsigned short* p) { return *reinterpret_cast<const uint4*>(p); }
 
-// Sum of squares of a residual row, accumulated across workgroups.  The workgroups of a launch finish in any order,
-// and a float sum depends on that order in its last bit (which then flips bf16 roundings downstream), so the
-// partial sums are added as integers, where the order does not matter: a non-negative float v <= 2^60 is split
-// exactly into hi = floor(v / 2^8) and lo = floor((v - 2^8 hi) 2^40) < 2^48 (only bits below 2^-40 are dropped,
-// the same ones for a given partial in every run), and the two 64-bit counters take up to 2^11 such partials.
-__device__ __forceinline__ void ssq_split(float v, unsigned long long* hi, unsigned long long* lo) {
-  const double dv = (double)fminf(v, 0x1p60f);
-  *hi = (unsigned long long)(dv * 0x1p-8);
-  *lo = (unsigned long long)((dv - (double)*hi * 0x1p8) * 0x1p40);
-}
-__device__ __forceinline__ void ssq_add(unsigned long long* slot, float v) {
-  unsigned long long hi, lo;
-  ssq_split(v, &hi, &lo);
-  atomicAdd(slot, hi);
-  atomicAdd(slot + 1, lo);
-}
-__device__ __forceinline__ float ssq_value(const unsigned long long* slot) {
-  const ulonglong2 p = *reinterpret_cast<const ulonglong2*>(slot);
-  return (float)((double)p.x * 0x1p8 + (double)p.y * 0x1p-40);
+// Sum of squares of a residual row (the next RMSNorm's denominator).  The row is produced 16 columns per weight tile
+// by many workgroups, which finish in any order, and a float sum taken in completion order differs in its last bit
+// from run to run (which then flips bf16 roundings downstream).  So nothing is accumulated across workgroups: every
+// tile writes its own partial to entry `tile` of the row, and the kernel that needs the sum adds the row's entries in
+// a fixed order (lane group g takes the float4 chunks g, g + 4, ..; then the four groups are added).  No atomics,
+// and the bits of a step do not depend on scheduling.
+__device__ __forceinline__ float ssq_row_sum(const float* row, int np, int g) {
+  float s = 0.f;
+  for (int i = g * 4; i < np; i += 16) {
+    const float4 v = *reinterpret_cast<const float4*>(row + i);
+    s += (v.x + v.y) + (v.z + v.w);
+  }
+  s += __shfl_xor(s, 16, 64);
+  s += __shfl_xor(s, 32, 64);
+  return s;
 }
 
 // RT = 16-row weight tiles per wave: a wave holds RT x NB accumulator tiles, so that a batch fragment fetched for a
@@ -173,8 +170,9 @@ __global__ void __launch_bounds__(TW * KW * 64) k_skinny(SkinnyArgs a) {
 #pragma unroll
     for (int e = 0; e < 4; ++e) pre_cs[r][e] = make_float2(1.f, 0.f);
   }
+  if (MODE != MODE_RESID && epi)  // whole waves: the sum ends in shuffles (rows past the batch read row B - 1)
+    pre_ssq = ssq_row_sum(a.ssq_in + (size_t)min(jb, a.B - 1) * a.ssq_np, a.ssq_np, g);
   if (active) {
-    if (MODE != MODE_RESID) pre_ssq = ssq_value(a.ssq_in + 2 * (size_t)jb);
     if (MODE == MODE_QKV) {
 #pragma unroll
       for (int r = 0; r < RT; ++r) {
@@ -257,7 +255,6 @@ __global__ void __launch_bounds__(TW * KW * 64) k_skinny(SkinnyArgs a) {
   float rho = 1.f;
   if (MODE != MODE_RESID && active) rho = rsqrtf(pre_ssq * a.inv_dim + a.eps);
   const int steps_n = (a.n_rows + 31) >> 5;
-  float s2 = 0.f;  // RESID: this lane's share of sum x1^2 over the rounds
 
 #pragma unroll
   for (int r = 0; r < RT; ++r) {
@@ -320,6 +317,7 @@ __global__ void __launch_bounds__(TW * KW * 64) k_skinny(SkinnyArgs a) {
       }
     } else if (MODE == MODE_RESID) {
       const int n0 = tile_row0(0, r) + 4 * g;
+      float s2 = 0.f;
       if (active && n0 < a.n_rows) {  // n_rows is a multiple of 8, so the four rows are all in or all out
         const float4 rs = pre_res[r];
         const float o0 = rs.x + v[0][0], o1 = rs.y + v[0][1], o2 = rs.z + v[0][2], o3 = rs.w + v[0][3];
@@ -329,8 +327,12 @@ __global__ void __launch_bounds__(TW * KW * 64) k_skinny(SkinnyArgs a) {
           *reinterpret_cast<uint2*>(a.hxn + xfrag_off(jb, n0, steps_n)) =
               make_uint2(pack_bf2(o0 * gn.x, o1 * gn.y), pack_bf2(o2 * gn.z, o3 * gn.w));
         }
-        s2 += o0 * o0 + o1 * o1 + o2 * o2 + o3 * o3;
+        s2 = o0 * o0 + o1 * o1 + o2 * o2 + o3 * o3;
       }
+      // this tile's share of sum x1^2 per batch row (whole wave: shuffles)
+      s2 += __shfl_xor(s2, 16, 64);
+      s2 += __shfl_xor(s2, 32, 64);
+      if (active && g == 0 && a.ssq_out && n0 < a.n_rows) a.ssq_out[(size_t)jb * a.ssq_np + (n0 >> 4)] = s2;
     } else if (MODE == MODE_GATEUP) {
       const int n0 = tile_row0(0, r) + 4 * g;
       if (active && n0 < a.n_rows) {
@@ -353,11 +355,6 @@ __global__ void __launch_bounds__(TW * KW * 64) k_skinny(SkinnyArgs a) {
         }
       }
     }
-  }
-  if (MODE == MODE_RESID && epi) {
-    s2 += __shfl_xor(s2, 16, 64);
-    s2 += __shfl_xor(s2, 32, 64);
-    if (active && g == 0 && a.ssq_out) ssq_add(a.ssq_out + 2 * (size_t)jb, s2);
   }
 }
 
@@ -383,9 +380,9 @@ __global__ void __launch_bounds__(256) k_pack_weight(const unsigned short* src, 
 // accumulators.  One workgroup per sequence; loads are issued in groups of four 16-byte words
 // so that the kernel costs a couple of memory round trips, not one per element.
 // ---------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(256) k_decode_prep(int H, int d, int n_ssq, int bpad, const int* token_ids,
+__global__ void __launch_bounds__(256) k_decode_prep(int H, int d, int n_ssq, int bpad, int ssq_np, const int* token_ids,
                                                      const unsigned short* emb, int vocab, const float* x_in, float* xa,
-                                                     const float* g1, unsigned short* hx1, unsigned long long* ssq, float* rope,
+                                                     const float* g1, unsigned short* hx1, float* ssq, float* rope,
                                                      const int* kv_len, const double* inv_freq, int* err_flag) {
   const int b = blockIdx.x, tid = threadIdx.x;
   const int steps = (H + 31) >> 5;
@@ -419,10 +416,13 @@ __global__ void __launch_bounds__(256) k_decode_prep(int H, int d, int n_ssq, in
   s2 = wave_sum(s2);
   if ((tid & 63) == 0) sh[tid >> 6] = s2;
   __syncthreads();
-  if (tid == 0) ssq_split(sh[0] + sh[1] + sh[2] + sh[3], ssq + 2 * (size_t)b, ssq + 2 * (size_t)b + 1);
-  for (int i = 1 + tid; i < n_ssq; i += 256) {
-    ssq[2 * ((size_t)i * bpad + b)] = 0ull;
-    ssq[2 * ((size_t)i * bpad + b) + 1] = 0ull;
+  // slot 0 of this row: the whole sum in entry 0, zeros in the others; and in every later slot the padding entries past
+  // the tiles their producers write (the consumers add all ssq_np entries of a row)
+  const int n_tiles = (H + 15) >> 4;
+  for (int i = tid; i < ssq_np; i += 256) ssq[(size_t)b * ssq_np + i] = i == 0 ? (sh[0] + sh[1]) + (sh[2] + sh[3]) : 0.f;
+  for (int i = tid; i < (n_ssq - 1) * (ssq_np - n_tiles); i += 256) {
+    const int slot = 1 + i / (ssq_np - n_tiles), e = n_tiles + i % (ssq_np - n_tiles);
+    ssq[((size_t)slot * bpad + b) * ssq_np + e] = 0.f;
   }
   const int half = d >> 1;
   const double pos = (double)kv_len[b];
@@ -814,7 +814,8 @@ harli_status decode_step_bf16(harli_ctx* c, const harli_decode_batch* b, hipStre
   const harli_model_cfg& m = c->cfg;
   const int B = b->batch, H = m.hidden, d = m.head_dim, QD = m.n_q_heads * d, F = m.ffn, L = m.n_layers;
   const int n_ssq = 2 * L + 1;
-  hipLaunchKernelGGL(k_decode_prep, dim3(B), dim3(256), 0, st, H, d, n_ssq, w.bpad, b->token_ids,
+  const int np = ssq_entries(H);
+  hipLaunchKernelGGL(k_decode_prep, dim3(B), dim3(256), 0, st, H, d, n_ssq, w.bpad, np, b->token_ids,
                      static_cast<const unsigned short*>(c->emb), m.vocab, b->x_in, w.xa, c->layers[0].g1,
                      static_cast<unsigned short*>(w.hx1), w.ssq, w.rope, b->kv_len, w.inv_freq, w.err_flag);
 
@@ -834,7 +835,8 @@ harli_status decode_step_bf16(harli_ctx* c, const harli_decode_batch* b, hipStre
     a.K = H;
     a.n_rows = QD;
     a.w0 = static_cast<const unsigned short*>(lw.wp[0]);
-    a.ssq_in = w.ssq + 2 * (size_t)(2 * l) * w.bpad;
+    a.ssq_np = np;
+    a.ssq_in = w.ssq + (size_t)(2 * l) * w.bpad * np;
     a.qbuf = w.qbuf;
     a.rope = w.rope;
     a.kv_len = b->kv_len;
@@ -870,7 +872,7 @@ harli_status decode_step_bf16(harli_ctx* c, const harli_decode_batch* b, hipStre
     a.out = w.x1;
     a.gnext = lw.g2;
     a.hxn = static_cast<unsigned short*>(w.hx2);
-    a.ssq_out = w.ssq + 2 * (size_t)(2 * l + 1) * w.bpad;
+    a.ssq_out = w.ssq + (size_t)(2 * l + 1) * w.bpad * np;
     dispatch_skinny<MODE_RESID, 1, 8>(a, (H + 15) / 16, st);
     // --- gate/up + SwiGLU
     a.x = static_cast<const unsigned short*>(w.hx2);
@@ -878,7 +880,7 @@ harli_status decode_step_bf16(harli_ctx* c, const harli_decode_batch* b, hipStre
     a.n_rows = F;
     a.w0 = static_cast<const unsigned short*>(lw.wp[4]);
     a.w1 = static_cast<const unsigned short*>(lw.wp[5]);
-    a.ssq_in = w.ssq + 2 * (size_t)(2 * l + 1) * w.bpad;
+    a.ssq_in = w.ssq + (size_t)(2 * l + 1) * w.bpad * np;
     a.mbuf = static_cast<unsigned short*>(w.mbuf);
     dispatch_skinny<MODE_GATEUP, 2, 4>(a, (F + 15) / 16, st);
     // --- down projection + residual, operand of the next layer (or of the output layer)
@@ -892,7 +894,7 @@ harli_status decode_step_bf16(harli_ctx* c, const harli_decode_batch* b, hipStre
     a.out = xnext;
     a.gnext = last ? c->g_final : c->layers[l + 1].g1;
     a.hxn = (last && !b->logits) ? nullptr : static_cast<unsigned short*>(w.hx1);
-    a.ssq_out = w.ssq + 2 * (size_t)(2 * l + 2) * w.bpad;
+    a.ssq_out = w.ssq + (size_t)(2 * l + 2) * w.bpad * np;
     dispatch_skinny<MODE_RESID, 1, 8>(a, (H + 15) / 16, st);
     xcur = xnext;
   }
@@ -905,7 +907,8 @@ harli_status decode_step_bf16(harli_ctx* c, const harli_decode_batch* b, hipStre
     a.K = H;
     a.n_rows = m.vocab;
     a.w0 = static_cast<const unsigned short*>(c->wlm_p);
-    a.ssq_in = w.ssq + 2 * (size_t)(2 * L) * w.bpad;
+    a.ssq_np = np;
+    a.ssq_in = w.ssq + (size_t)(2 * L) * w.bpad * np;
     a.logits = b->logits;
     dispatch_skinny<MODE_LM, 2, 4>(a, (m.vocab + 31) / 32, st);
     if (b->next_token) {
@@ -970,7 +973,7 @@ extern "C" size_t harli_decode_step_static_bytes(const harli_ctx* c, int32_t bat
   const size_t chunks = ((size_t)max_kv_len + 127) / 128;
   size_t n = al(bp * r32(H) * 2) * 2 + al(bp * r32(QD) * 2) + al(bp * r32(F) * 2);       // GEMM operands
   n += al(bp * QD * 4) + 3 * al(bp * H * 4);                                             // q, x1, xa, xb
-  n += al(bp * (2 * (size_t)m.n_layers + 1) * 16) + al(bp * m.head_dim * 4);             // row norms, rotary table
+  n += al(bp * (2 * (size_t)m.n_layers + 1) * ssq_entries(m.hidden) * 4) + al(bp * m.head_dim * 4);  // row norms, rotary table
   n += al(bp * m.n_q_heads * chunks * ((size_t)m.head_dim + 2) * 4);                     // attention partials
   n += 2 * al(bp * 64 * 4);                                                              // argmax partials
   return n;
@@ -1012,7 +1015,7 @@ extern "C" harli_status harli_decode_step_static(harli_ctx* c, const harli_decod
   w.x1 = reinterpret_cast<float*>(take(bp * H * 4));
   w.xa = reinterpret_cast<float*>(take(bp * H * 4));
   w.xb = reinterpret_cast<float*>(take(bp * H * 4));
-  w.ssq = reinterpret_cast<unsigned long long*>(take(bp * (2 * (size_t)m.n_layers + 1) * 16));
+  w.ssq = reinterpret_cast<float*>(take(bp * (2 * (size_t)m.n_layers + 1) * ssq_entries(m.hidden) * 4));
   w.rope = reinterpret_cast<float*>(take(bp * m.head_dim * 4));
   w.att_part = reinterpret_cast<float*>(take(bp * m.n_q_heads * chunks * ((size_t)m.head_dim + 2) * 4));
   w.amax_v = reinterpret_cast<float*>(take(bp * 64 * 4));
@@ -1022,8 +1025,8 @@ extern "C" harli_status harli_decode_step_static(harli_ctx* c, const harli_decod
   if (off != need) return fail(HARLI_ERR_STATE, "decode_step_static: layout of %zu bytes against %zu counted", off, need);
   // The array keeps what the last call (of any shape) left.  The GEMM operands must start at zero: contraction
   // positions past K (up to the next multiple of 32) are multiplied with the zero padding of the weights, and stale
-  // bits there may read as NaN.  Everything else is written before it is read (the row-norm counters are cleared by
-  // the step's first kernel; batch rows past `batch` only reach output columns that are never stored).
+  // bits there may read as NaN.  Everything else is written before it is read (the row-norm partials are written by their
+  // producers and their padding by the step's first kernel; batch rows past `batch` only reach output columns that are never stored).
   const size_t n16 = operand_bytes / 16;
   hipLaunchKernelGGL(k_zero16, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, st, reinterpret_cast<uint4*>(base), n16);
   return decode_step_bf16(c, b, st, w);
