@@ -170,8 +170,25 @@ __global__ void __launch_bounds__(TW * KW * 64) k_skinny(SkinnyArgs a) {
 #pragma unroll
     for (int e = 0; e < 4; ++e) pre_cs[r][e] = make_float2(1.f, 0.f);
   }
-  if (MODE != MODE_RESID && epi)  // whole waves: the sum ends in shuffles (rows past the batch read row B - 1)
-    pre_ssq = ssq_row_sum(a.ssq_in + (size_t)min(jb, a.B - 1) * a.ssq_np, a.ssq_np, g);
+  // The partial sums of squares of this wave's 16 batch rows.  Small batches (NB <= 2, where a step is short enough
+  // for a memory round trip to show): the rows are copied to LDS by loads that need no register and no wait here, and
+  // are added up after the stream; otherwise they are added now (the wave waits for them once, before its stream).
+  constexpr bool kSsqLds = MODE != MODE_RESID && NB <= 2;
+  extern __shared__ __attribute__((aligned(1024))) char ssq_lds[];
+  const int ssq_stride = (a.ssq_np * 4 + 1023) & ~1023;  // bytes per staged row
+  if (MODE != MODE_RESID && epi) {  // whole waves; rows past the batch read row B - 1
+    if constexpr (kSsqLds) {
+      for (int r = 0; r < 16; ++r) {
+        const float* row = a.ssq_in + (size_t)min(a.b0 + wave * 16 + r, a.B - 1) * a.ssq_np;
+        __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(row), 0, a.ssq_np * 4, 0x00020000);
+        for (int k = 0; k < ssq_stride; k += 1024)  // lanes past the row are out of the resource's range: zeros
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (__attribute__((address_space(3))) void*)(ssq_lds + (wave * 16 + r) * ssq_stride + k),
+                                                   16, lane * 16 + k, 0, 0, 0);
+      }
+    } else {
+      pre_ssq = ssq_row_sum(a.ssq_in + (size_t)min(jb, a.B - 1) * a.ssq_np, a.ssq_np, g);
+    }
+  }
   if (active) {
     if (MODE == MODE_QKV) {
 #pragma unroll
@@ -253,6 +270,20 @@ __global__ void __launch_bounds__(TW * KW * 64) k_skinny(SkinnyArgs a) {
   __shared__ float4 red[TW][KW][NB][64];
   static_assert(NB <= WAVES, "one epilogue wave per batch tile");
   float rho = 1.f;
+  if constexpr (kSsqLds) {
+    if (epi) {  // the same chunks in the same order as ssq_row_sum, from the staged copy
+      __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's own copies have landed
+      const float* row = reinterpret_cast<const float*>(ssq_lds + (wave * 16 + i16) * ssq_stride);
+      float s = 0.f;
+      for (int i = g * 4; i < a.ssq_np; i += 16) {
+        const float4 v = *reinterpret_cast<const float4*>(row + i);
+        s += (v.x + v.y) + (v.z + v.w);
+      }
+      s += __shfl_xor(s, 16, 64);
+      s += __shfl_xor(s, 32, 64);
+      pre_ssq = s;
+    }
+  }
   if (MODE != MODE_RESID && active) rho = rsqrtf(pre_ssq * a.inv_dim + a.eps);
   const int steps_n = (a.n_rows + 31) >> 5;
 
@@ -714,7 +745,9 @@ __global__ void __launch_bounds__(64) k_argmax_final(const float* part_v, const 
 
 template <int MODE, int NB, int TW, int KW, int U, int RT>
 void launch_skinny(const SkinnyArgs& a, int n_wg, hipStream_t st) {
-  hipLaunchKernelGGL((k_skinny<MODE, NB, TW, KW, U, RT>), dim3((n_wg + RT - 1) / RT), dim3(TW * KW * 64), 0, st, a);
+  // dynamic LDS: the staged partial sums of squares of NB x 16 batch rows (small batches of the normalised GEMMs)
+  const size_t lds = (MODE != MODE_RESID && NB <= 2) ? (size_t)NB * 16 * (((size_t)a.ssq_np * 4 + 1023) & ~size_t(1023)) : 0;
+  hipLaunchKernelGGL((k_skinny<MODE, NB, TW, KW, U, RT>), dim3((n_wg + RT - 1) / RT), dim3(TW * KW * 64), lds, st, a);
 }
 
 // passes of at most 64 batch rows (128 where the workgroup has eight waves to finish eight batch tiles and more than
