@@ -79,7 +79,8 @@ def run(args):
     # the library's own memory (decode weight copies, the finetune instance's two copies per layer, the output layer's
     # copies, both workspaces) is taken from the same pool
     lib_bytes = 6 * m.layer_params * L + 6 * m.vocab * H + 6 * T * m.vocab + 4 * per_layer + (2 << 30)
-    n_chunks = kv_chunks + (L + 1) * (per_layer // chunk + 2) + lib_bytes // chunk + 8
+    # (a third more than the bytes: matrices larger than a chunk take runs of adjacent chunks and leave gaps)
+    n_chunks = kv_chunks + (L + 1) * (per_layer // chunk + 2) + lib_bytes * 4 // (3 * chunk) + 8
     small = 256 << 20
     slab_bytes = small + n_chunks * chunk
     slab = torch.zeros(slab_bytes, dtype=torch.uint8, device=dev)
