@@ -154,6 +154,20 @@ def main():
         sD.synchronize()
         return e0.elapsed_time(e1) / n
 
+    def time_decode_solo_direct(n=300):
+        """The same step issued kernel by kernel from the host (no graph): the launches of a step overlap the step
+        before, which a replayed graph's nodes do not on this runtime."""
+        for _ in range(20):
+            decode_launch()
+        sD.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(sD)
+        for _ in range(n):
+            decode_launch()
+        e1.record(sD)
+        sD.synchronize()
+        return e0.elapsed_time(e1) / n
+
     def time_finetune_solo(n):
         for _ in range(2):
             finetune_unit()
@@ -168,6 +182,7 @@ def main():
 
     log("[bench] solo runs")
     dec_solo_ms = time_decode_solo()
+    dec_solo_direct_ms = time_decode_solo_direct()
     ft_solo_ms = time_finetune_solo(max(3, min(K, 10)))
     pool.stats()                                       # polls release events
 
@@ -352,7 +367,12 @@ def main():
         "roofline_decode": {"bound": "hbm", "achieved": dec_bytes / (tpot_mean * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
                             "unit": "GB/s", "frac": dec_bytes / (tpot_mean * 1e-3) / 1e9 / PEAK_HBM_GBS, "traffic": traffic_decode,
                             "bytes_per_step": dec_bytes, "solo_achieved": dec_bytes / (dec_solo_ms * 1e-3) / 1e9,
-                            "solo_frac": dec_bytes / (dec_solo_ms * 1e-3) / 1e9 / PEAK_HBM_GBS},
+                            "solo_frac": dec_bytes / (dec_solo_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                            "solo_step_ms_graph_replay": dec_solo_ms, "solo_step_ms_direct_launches": dec_solo_direct_ms,
+                            "solo_direct_achieved": dec_bytes / (dec_solo_direct_ms * 1e-3) / 1e9,
+                            "solo_direct_frac": dec_bytes / (dec_solo_direct_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                            "note": "solo_* time the step as a graph replay, as the co-located runs issue it; solo_direct_* time "
+                                    "the same kernels launched one by one from the host"},
         "slo_paced": {"decode_interval_ms": pace_ms, "value": paced["tokens_per_s"], "unit": "tokens/s",
                       "ms_per_step": paced["ms_per_step"],
                       "tpot_ms_p50": float(np.percentile(paced["tpot"], 50)), "tpot_ms_p99": float(np.percentile(paced["tpot"], 99)),
