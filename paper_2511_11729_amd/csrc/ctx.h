@@ -45,6 +45,8 @@ struct DecodeWs {
   float *fk = nullptr, *fv = nullptr, *fa = nullptr, *fu = nullptr;  // fp32 path only: k, v [bpad, n_kv*d]; gate, up [bpad, ffn]
   int* err_flag = nullptr;    // device int set when a kernel sees an out-of-range page id
   int max_chunks = 0;
+  float* part = nullptr;      // partial tiles of the large-batch GEMMs (null: batches stay on the small-batch kernels)
+  size_t part_bytes = 0;
 };
 
 }  // namespace harli

@@ -1,6 +1,8 @@
 // Model context: shapes, borrowed weight pointers and the library-owned device workspace.
 #include "ctx.h"
 
+#include "decode_large.h"
+
 #include <cmath>
 
 using namespace harli;
@@ -174,6 +176,8 @@ extern "C" harli_status harli_ctx_create(const harli_model_cfg* cfg, const harli
   }
   TRY(dev_alloc(c, &d.att_part, bp * m.n_q_heads * d.max_chunks * (m.head_dim + 2) * 4, true));
   TRY(dev_alloc(c, &d.err_flag, 16, true));
+  d.part_bytes = dg_workspace_bytes(m, c->n_cu);
+  if (d.part_bytes) TRY(dev_alloc(c, &d.part, d.part_bytes, false));
   // fp32 path: scratch for attention scores, one row of max_seq_len per (sequence, query head)
   if (m.dtype == HARLI_F32) {
     TRY(dev_alloc(c, &d.scores, bp * m.n_q_heads * (size_t)m.max_seq_len * 4, true));
@@ -232,7 +236,7 @@ extern "C" harli_status harli_ctx_device_bytes(const harli_ctx* c, harli_device_
 extern "C" void harli_ctx_destroy(harli_ctx* c) {
   if (!c) return;
   DecodeWs& d = c->dw;
-  void* bufs[] = {d.hx1, d.obuf, d.hx2, d.mbuf, d.qbuf, d.x1, d.xa, d.xb, d.ssq, d.rope, d.att_part, d.amax_v, d.amax_i, d.err_flag, d.scores, d.inv_freq, d.fk, d.fv, d.fa, d.fu};
+  void* bufs[] = {d.hx1, d.obuf, d.hx2, d.mbuf, d.qbuf, d.x1, d.xa, d.xb, d.ssq, d.rope, d.att_part, d.amax_v, d.amax_i, d.err_flag, d.part, d.scores, d.inv_freq, d.fk, d.fv, d.fa, d.fu};
   (void)hipDeviceSynchronize();  // steps in flight may still read what goes back to the pool here
   for (void* p : bufs) lib_free(c, p);
   for (LayerDev& ld : c->layers)

@@ -26,7 +26,9 @@
 #include <mutex>
 
 #include "ctx.h"
+#include "decode_large.h"
 #include "device_utils.h"
+#include "gemm2.h"
 
 using namespace harli;
 
@@ -37,60 +39,7 @@ constexpr int kComputeUnits = 256;  // MI355X; only steers a tiling choice
 
 enum { MODE_QKV = 0, MODE_RESID = 1, MODE_GATEUP = 2, MODE_LM = 3 };
 
-// Element (jb, k) of an x operand with `steps` = ceil(K/32) k-steps, fragment order:
-// [batch tile][k-step][lane = (k%32)/8*16 + jb%16][8].
-__device__ __forceinline__ size_t xfrag_off(int jb, int k, int steps) {
-  return ((((size_t)(jb >> 4) * steps + (k >> 5)) * 64) + ((k >> 3) & 3) * 16 + (jb & 15)) * 8 + (k & 7);
-}
-
-struct SkinnyArgs {
-  const unsigned short* x;  // fragment-order operand
-  int B, b0, K;             // batch size, first batch row of this pass, contraction length
-  int n_rows;               // output rows (tail masking of stores)
-  const unsigned short *w0, *w1;  // pre-shuffled weights
-  const float* ssq_in;  // partial sums of squares of the operand's source row (rho): [row][ssq_np], or null
-  int ssq_np;           // entries per row (a multiple of 16; entries past the producer's tiles are zero)
-  float eps, inv_dim;
-  // QKV
-  float* qbuf;
-  const float* rope;
-  const int* kv_len;
-  const int* page_table;
-  int max_pages, layer, n_q, n_kv, d;
-  char* slab;
-  KvGeom geom;
-  int* err_flag;
-  const float* bias[3];  // q, k, v biases (fp32, indexed by output row of that projection) or null
-  // RESID
-  const float* res;
-  float* out;
-  const float* gnext;
-  unsigned short* hxn;  // next operand (fragment order, K = n_rows) or null
-  float* ssq_out;       // [row][ssq_np]: this launch writes entry `tile` of every row it finishes
-  // GATEUP
-  unsigned short* mbuf;  // next operand (fragment order, K = n_rows)
-  // LM
-  float* logits;
-};
-
 __device__ __forceinline__ uint4 ld16(const unsigned short* p) { return *reinterpret_cast<const uint4*>(p); }
-
-// Sum of squares of a residual row (the next RMSNorm's denominator).  The row is produced 16 columns per weight tile
-// by many workgroups, which finish in any order, and a float sum taken in completion order differs in its last bit
-// from run to run (which then flips bf16 roundings downstream).  So nothing is accumulated across workgroups: every
-// tile writes its own partial to entry `tile` of the row, and the kernel that needs the sum adds the row's entries in
-// a fixed order (lane group g takes the float4 chunks g, g + 4, ..; then the four groups are added).  No atomics,
-// and the bits of a step do not depend on scheduling.
-__device__ __forceinline__ float ssq_row_sum(const float* row, int np, int g) {
-  float s = 0.f;
-  for (int i = g * 4; i < np; i += 16) {
-    const float4 v = *reinterpret_cast<const float4*>(row + i);
-    s += (v.x + v.y) + (v.z + v.w);
-  }
-  s += __shfl_xor(s, 16, 64);
-  s += __shfl_xor(s, 32, 64);
-  return s;
-}
 
 // RT = 16-row weight tiles per wave: a wave holds RT x NB accumulator tiles, so that a batch fragment fetched for a
 // k-step serves RT weight fragments (at 64 batch rows every wave otherwise pulls four batch fragments through the
@@ -855,6 +804,12 @@ harli_status decode_step_bf16(harli_ctx* c, const harli_decode_batch* b, hipStre
   const float* xcur = b->token_ids ? w.xa : b->x_in;
   float* ping[2] = {w.xb, w.xa};  // layer l writes ping[l&1]; layer 0 must not overwrite xa (it can be its input)
   const int G = m.n_q_heads / m.n_kv_heads;
+  // above 64 sequences the layer GEMMs run as tiled MFMA GEMMs with their epilogues in a second kernel (decode_large.h);
+  // a caller's buffer without the workspace for their partial tiles keeps every batch on the small-batch kernels
+  const bool large = B > 64 && w.part != nullptr;
+  int n_cu = cu_stream_count(st);  // a stream confined to a share of the compute units (Sec. 6.2)
+  if (n_cu < 1) n_cu = c->n_cu;
+  const int x_tiles = w.bpad / 16;
 
   for (int l = 0; l < L; ++l) {
     const LayerDev& lw = c->layers[l];
@@ -882,7 +837,12 @@ harli_status decode_step_bf16(harli_ctx* c, const harli_decode_batch* b, hipStre
     a.slab = c->slab;
     a.geom = c->geom;
     for (int t = 0; t < 3; ++t) a.bias[t] = lw.bias[t];
-    dispatch_skinny<MODE_QKV, 2, 2>(a, (m.n_q_heads + 2 * m.n_kv_heads) * (d / 32), st);
+    if (large) {
+      harli_status rc = dg_launch(DG_QKV, a, x_tiles, w.part, w.part_bytes, n_cu, st);
+      if (rc != HARLI_OK) return rc;
+    } else {
+      dispatch_skinny<MODE_QKV, 2, 2>(a, (m.n_q_heads + 2 * m.n_kv_heads) * (d / 32), st);
+    }
     // --- attention
     if (d == 128 && G == 1) launch_attn<128, 1, 256>(c, w, b, l, st);
     else if (d == 128 && G == 2) launch_attn<128, 2, 256>(c, w, b, l, st);
@@ -906,7 +866,12 @@ harli_status decode_step_bf16(harli_ctx* c, const harli_decode_batch* b, hipStre
     a.gnext = lw.g2;
     a.hxn = static_cast<unsigned short*>(w.hx2);
     a.ssq_out = w.ssq + (size_t)(2 * l + 1) * w.bpad * np;
-    dispatch_skinny<MODE_RESID, 1, 8>(a, (H + 15) / 16, st);
+    if (large) {
+      harli_status rc = dg_launch(DG_RESID, a, x_tiles, w.part, w.part_bytes, n_cu, st);
+      if (rc != HARLI_OK) return rc;
+    } else {
+      dispatch_skinny<MODE_RESID, 1, 8>(a, (H + 15) / 16, st);
+    }
     // --- gate/up + SwiGLU
     a.x = static_cast<const unsigned short*>(w.hx2);
     a.K = H;
@@ -915,7 +880,12 @@ harli_status decode_step_bf16(harli_ctx* c, const harli_decode_batch* b, hipStre
     a.w1 = static_cast<const unsigned short*>(lw.wp[5]);
     a.ssq_in = w.ssq + (size_t)(2 * l + 1) * w.bpad * np;
     a.mbuf = static_cast<unsigned short*>(w.mbuf);
-    dispatch_skinny<MODE_GATEUP, 2, 4>(a, (F + 15) / 16, st);
+    if (large) {
+      harli_status rc = dg_launch(DG_GATEUP, a, x_tiles, w.part, w.part_bytes, n_cu, st);
+      if (rc != HARLI_OK) return rc;
+    } else {
+      dispatch_skinny<MODE_GATEUP, 2, 4>(a, (F + 15) / 16, st);
+    }
     // --- down projection + residual, operand of the next layer (or of the output layer)
     const bool last = (l == L - 1);
     float* xnext = (last && b->x_out) ? b->x_out : ping[l & 1];
@@ -928,7 +898,12 @@ harli_status decode_step_bf16(harli_ctx* c, const harli_decode_batch* b, hipStre
     a.gnext = last ? c->g_final : c->layers[l + 1].g1;
     a.hxn = (last && !b->logits) ? nullptr : static_cast<unsigned short*>(w.hx1);
     a.ssq_out = w.ssq + (size_t)(2 * l + 2) * w.bpad * np;
-    dispatch_skinny<MODE_RESID, 1, 8>(a, (H + 15) / 16, st);
+    if (large) {
+      harli_status rc = dg_launch(DG_RESID, a, x_tiles, w.part, w.part_bytes, n_cu, st);
+      if (rc != HARLI_OK) return rc;
+    } else {
+      dispatch_skinny<MODE_RESID, 1, 8>(a, (H + 15) / 16, st);
+    }
     xcur = xnext;
   }
   if (b->logits) {
