@@ -263,11 +263,14 @@ typedef struct {
 harli_status harli_decode_step(harli_ctx* c, const harli_decode_batch* b, void* hip_stream);
 
 /* The same step for callers that cannot allocate device memory or rely on memory allocated for them: code under
- * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and the
- * same results as harli_decode_step, but every intermediate buffer of the step (GEMM operands, q, attention
- * partials, row norms, rotary table, argmax partials) lives in one array of HARLI_STATIC_SCRATCH_BYTES that is part
- * of the library's device image (each GPU the library runs on holds its copy until the process ends) instead of
- * the workspace harli_ctx_create allocated.  The call itself allocates and frees nothing, on the host side of the
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments as harli_decode_step and,
+ * up to 64 sequences, the same kernels and the same bits, but every intermediate buffer of the step (GEMM operands,
+ * q, attention partials, row norms, rotary table, argmax partials) lives in one array of HARLI_STATIC_SCRATCH_BYTES
+ * that is part of the library's device image (each GPU the library runs on holds its copy until the process ends)
+ * instead of the workspace harli_ctx_create allocated.  Above 64 sequences harli_decode_step runs its GEMMs tiled over
+ * ranges of K with partial tiles in that workspace (tens of MB, which the array has no room for): this entry point
+ * then keeps the kernels that take the batch in passes of 64 or 128 rows, and agrees with harli_decode_step to
+ * rounding, not bit for bit.  The call itself allocates and frees nothing, on the host side of the
  * device or through any library.  bf16 storage only.
  *   - harli_decode_step_static_bytes(c, batch, max_kv_len) is what a step of that batch and length bound needs
  *     (host arithmetic; 0 for bad arguments).  A step that needs more than HARLI_STATIC_SCRATCH_BYTES is refused

@@ -150,6 +150,8 @@ _SIGS = {
                                         C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
     "harli_dbg_gemm2": (C.c_int, [C.c_void_p, C.c_void_p]),
     "harli_dbg_gemm2_plan": (C.c_int, [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int32)]),
+    "harli_dbg_decode_gemm_plan": (C.c_int, [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int64, C.POINTER(C.c_int64)]),
+    "harli_dbg_decode_gemm_time": (C.c_int, [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_float), C.c_void_p]),
 }
 
 
@@ -533,6 +535,20 @@ class DbgGemm2Desc(C.Structure):
                 ("ldcf", C.c_int64 * 3), ("e0", C.c_void_p), ("e1", C.c_void_p), ("o0", C.c_void_p), ("o1", C.c_void_p),
                 ("lde", C.c_int64), ("overflow_flag", C.c_void_p), ("tflops", C.POINTER(C.c_double)),
                 ("shader_mhz", C.POINTER(C.c_double)), ("n_cu", C.c_int32)]
+
+
+def dbg_decode_gemm_plan(batch: int, n_rows: int, n_mat: int, K: int, n_cu: int, ws_bytes: int) -> dict:
+    """How one GEMM of a decode step above 64 sequences is cut (host logic only)."""
+    out = (C.c_int64 * 7)()
+    _check(lib().harli_dbg_decode_gemm_plan(batch, n_rows, n_mat, K, n_cu, ws_bytes, out))
+    return dict(zip(("FM", "tiles_m", "Mpad", "tiles_n", "ksplit", "rounds", "part_bytes"), [int(v) for v in out]))
+
+
+def dbg_decode_gemm_time(batch: int, n_rows: int, n_mat: int, K: int, ksplit: int = 0, reps: int = 10, stream=None) -> dict:
+    """Average microseconds of the two launches of one large-batch decode GEMM on operands the call allocates."""
+    out = (C.c_float * 4)()
+    _check(lib().harli_dbg_decode_gemm_time(batch, n_rows, n_mat, K, ksplit, reps, out, _stream(stream)))
+    return {"gemm_us": float(out[0]), "epilogue_us": float(out[1]), "ksplit": int(out[2]), "FM": int(out[3])}
 
 
 def dbg_gemm2_plan(M: int, tiles_n: int, tile_rows: int, n_cu: int) -> dict:

@@ -2,6 +2,7 @@
 #include "harli_debug.h"
 
 #include "ctx.h"
+#include "decode_large.h"
 #include "gemm_timer.h"
 #include "gemm2.h"
 
@@ -199,4 +200,93 @@ extern "C" harli_status harli_dbg_read_bandwidth(const void* buf, size_t bytes, 
   (void)hipFree(sink);
   *gbs = (double)wgs * per_wg * reps / (ms * 1e-3) / 1e9;
   return HARLI_OK;
+}
+
+extern "C" harli_status harli_dbg_decode_gemm_plan(int32_t batch, int32_t n_rows, int32_t n_mat, int32_t K, int32_t n_cu, int64_t ws_bytes,
+                                                   int64_t* out) {
+  if (!out || batch < 1 || n_rows < 1 || n_mat < 1 || n_mat > 2 || K < 1 || n_cu < 1 || ws_bytes < 0)
+    return fail(HARLI_ERR_INVALID, "dbg_decode_gemm_plan: bad argument");
+  const DgPlan p = dg_plan(batch, n_rows, n_mat, K, n_cu, (size_t)ws_bytes);
+  const int64_t v[7] = {p.FM, p.tiles_m, p.Mpad, p.tiles_n, p.ksplit, p.rounds, (int64_t)p.part_bytes};
+  for (int i = 0; i < 7; ++i) out[i] = v[i];
+  return HARLI_OK;
+}
+
+extern "C" harli_status harli_dbg_decode_gemm_time(int32_t batch, int32_t n_rows, int32_t n_mat, int32_t K, int32_t ksplit, int32_t reps,
+                                                   float* out_us, void* hip_stream) {
+  if (!out_us || batch < 1 || batch > 4096 || n_rows < 8 || (n_rows & 7) || n_mat < 1 || n_mat > 2 || K < 32 || reps < 1)
+    return fail(HARLI_ERR_INVALID, "dbg_decode_gemm_time: bad argument");
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  int dev = 0;
+  hipDeviceProp_t prop;
+  HARLI_HIP(hipGetDevice(&dev));
+  HARLI_HIP(hipGetDeviceProperties(&prop, dev));
+  int n_cu = cu_stream_count(st);
+  if (n_cu < 1) n_cu = prop.multiProcessorCount;
+  const int x_tiles = (batch + 15) / 16, steps = (K + 31) / 32;
+  const size_t xb = (size_t)x_tiles * steps * 1024, wb = packed_weight_elems(n_rows, K) * 2, ob = (size_t)x_tiles * 16 * n_rows * 4;
+  const size_t pb = (size_t)192 << 20;
+  void *x = nullptr, *w0 = nullptr, *w1 = nullptr, *res = nullptr, *out = nullptr, *part = nullptr, *ssq = nullptr, *mb = nullptr;
+  auto cleanup = [&]() {
+    for (void* p : {x, w0, w1, res, out, part, ssq, mb}) (void)hipFree(p);
+  };
+  hipError_t e = hipMalloc(&x, xb);
+  if (e == hipSuccess) e = hipMalloc(&w0, wb);
+  if (e == hipSuccess && n_mat == 2) e = hipMalloc(&w1, wb);
+  if (e == hipSuccess) e = hipMalloc(&res, ob);
+  if (e == hipSuccess) e = hipMalloc(&out, ob);
+  if (e == hipSuccess) e = hipMalloc(&part, pb);
+  if (e == hipSuccess) e = hipMalloc(&ssq, (size_t)x_tiles * 16 * 1024 * 4);
+  if (e == hipSuccess) e = hipMalloc(&mb, (size_t)x_tiles * ((n_rows + 31) / 32) * 1024);
+  // 0x3c3c as bf16 is about 0.0115: finite products of ordinary size
+  if (e == hipSuccess) e = hipMemset(x, 0x3c, xb);
+  if (e == hipSuccess) e = hipMemset(w0, 0x3c, wb);
+  if (e == hipSuccess && w1) e = hipMemset(w1, 0x3c, wb);
+  if (e == hipSuccess) e = hipMemset(res, 0, ob);
+  if (e == hipSuccess) e = hipMemset(ssq, 0, (size_t)x_tiles * 16 * 1024 * 4);
+  if (e != hipSuccess) {
+    cleanup();
+    return fail(HARLI_ERR_HIP, "dbg_decode_gemm_time: %s", hipGetErrorString(e));
+  }
+  SkinnyArgs a{};
+  a.x = static_cast<const unsigned short*>(x);
+  a.B = batch;
+  a.K = K;
+  a.n_rows = n_rows;
+  a.w0 = static_cast<const unsigned short*>(w0);
+  a.w1 = static_cast<const unsigned short*>(w1);
+  a.ssq_in = static_cast<const float*>(ssq);
+  a.ssq_np = 16;
+  a.eps = 1e-6f;
+  a.inv_dim = 1.f / (float)K;
+  a.res = static_cast<const float*>(res);
+  a.out = static_cast<float*>(out);
+  a.mbuf = static_cast<unsigned short*>(mb);
+  const DgKind kind = n_mat == 2 ? DG_GATEUP : DG_RESID;
+  hipEvent_t ev[3];
+  for (auto& v : ev) (void)hipEventCreate(&v);
+  dg_force_ksplit(ksplit);
+  harli_status rc = HARLI_OK;
+  double us_g = 0, us_e = 0;
+  DgPlan p{};
+  for (int r = -2; r < reps && rc == HARLI_OK; ++r) {  // two untimed launches first
+    (void)hipEventRecord(ev[0], st);
+    rc = dg_gemm(kind, a, x_tiles, static_cast<float*>(part), pb, n_cu, st, &p);
+    (void)hipEventRecord(ev[1], st);
+    if (rc == HARLI_OK) rc = dg_epilogue(kind, a, p, static_cast<const float*>(part), st);
+    (void)hipEventRecord(ev[2], st);
+    if (hipStreamSynchronize(st) != hipSuccess) rc = fail(HARLI_ERR_HIP, "dbg_decode_gemm_time: the launch failed");
+    float g = 0, ep = 0;
+    (void)hipEventElapsedTime(&g, ev[0], ev[1]);
+    (void)hipEventElapsedTime(&ep, ev[1], ev[2]);
+    if (r >= 0) us_g += g * 1e3, us_e += ep * 1e3;
+  }
+  dg_force_ksplit(0);
+  for (auto& v : ev) (void)hipEventDestroy(v);
+  cleanup();
+  out_us[0] = (float)(us_g / reps);
+  out_us[1] = (float)(us_e / reps);
+  out_us[2] = (float)p.ksplit;
+  out_us[3] = (float)p.FM;
+  return rc;
 }

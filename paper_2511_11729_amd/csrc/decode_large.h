@@ -87,5 +87,10 @@ size_t dg_workspace_bytes(const harli_model_cfg& m, int n_cu);
 // One GEMM of the step with its epilogue; `a` as the small-batch kernels take it (b0 ignored: all rows at once).
 // x_tiles: 16-row batch tiles the operand buffer was allocated for.  part: workspace of part_bytes.
 harli_status dg_launch(DgKind kind, const SkinnyArgs& a, int x_tiles, float* part, size_t part_bytes, int n_cu, hipStream_t st);
+// its two launches on their own (the partial products; their sum with the epilogue), and a measurement hook that fixes
+// the number of K ranges of every later plan (0 gives the choice back)
+harli_status dg_gemm(DgKind kind, const SkinnyArgs& a, int x_tiles, float* part, size_t part_bytes, int n_cu, hipStream_t st, DgPlan* used);
+harli_status dg_epilogue(DgKind kind, const SkinnyArgs& a, const DgPlan& p, const float* part, hipStream_t st);
+void dg_force_ksplit(int ksplit);
 
 }  // namespace harli

@@ -19,7 +19,7 @@
 namespace harli {
 namespace {
 
-constexpr int BK = 32, BN = 256, NT = 256, NS = 4;
+constexpr int BK = 32, BN = 256, NT = 256;
 constexpr int BSZ = BN * BK * 2;  // 16 KiB: one stage of the weight side
 constexpr int ER = (128 + 8) * 4;  // staged row of the epilogue in bytes
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
@@ -38,9 +38,14 @@ struct DgemmArgs {
 #define DG_SB0() __builtin_amdgcn_sched_barrier(0)
 #define DG_SGB(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0)
 
+// LDS stages: the weights come from HBM, whose latency under load is several K steps long, so the ring is as deep as
+// 160 KiB of LDS allow (bytes in flight per compute unit are what the stream's rate follows).
+template <int FM>
+constexpr int dg_stages() { return FM == 2 ? 6 : FM == 3 ? 5 : 4; }
+
 template <int FM>
 __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1))) k_dgemm(DgemmArgs a) {
-  constexpr int BM = 64 * FM, ASZ = BM * BK * 2, STG = ASZ + BSZ;
+  constexpr int BM = 64 * FM, ASZ = BM * BK * 2, STG = ASZ + BSZ, NS = dg_stages<FM>();
   constexpr int LOADS = FM + 4;  // direct-to-LDS loads a wave issues per stage
   static_assert(4 * 32 * ER <= NS * STG, "epilogue staging must fit the stage buffers");
   extern __shared__ __attribute__((aligned(1024))) char smem[];
@@ -162,7 +167,7 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1)))
     DG_PIPE1();                                                                                  \
     DG_SB0();                                                                                    \
     DG_ADVANCE();                                                                                \
-    DG_WAITV((NS - 3) * LOADS); /* all but the newest stage in flight have landed */            \
+    DG_WAITV((NS - 3) * LOADS); /* all but the NS - 3 newest stages in flight have landed */    \
     __builtin_amdgcn_s_barrier();                                                                \
     DG_SB0();                                                                                    \
     DG_RD(fa0, fb0, nxt, 0);                                                                     \
@@ -173,20 +178,18 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1)))
   } while (0)
 
   if (n_stage > 0) {
-    DG_ISSUE(0);
-    DG_ADVANCE();
-    DG_ISSUE(1);
-    DG_ADVANCE();
-    DG_ISSUE(2);
+#pragma unroll
+    for (int i = 0; i < NS - 1; ++i) {
+      if (i > 0) DG_ADVANCE();
+      DG_ISSUE(i);
+    }
     DG_WAITV((NS - 2) * LOADS);
     __builtin_amdgcn_s_barrier();
     DG_RD(fa0, fb0, 0, 0);
     DG_SB0();
     for (int st = 0; st < n_step; st += NS) {
-      DG_STEP(0, 1, 3);
-      DG_STEP(1, 2, 0);
-      DG_STEP(2, 3, 1);
-      DG_STEP(3, 0, 2);
+#pragma unroll
+      for (int i = 0; i < NS; ++i) DG_STEP(i, (i + 1) % NS, (i + NS - 1) % NS);
     }
     DG_WAITV(0);
   }
@@ -335,12 +338,15 @@ __global__ void __launch_bounds__(256) k_dg_qkv(SkinnyArgs a, const float* part,
 }
 
 template <int FM>
-constexpr int dg_lds_bytes() { return NS * (64 * FM * BK * 2 + BSZ); }
+constexpr int dg_lds_bytes() { return dg_stages<FM>() * (64 * FM * BK * 2 + BSZ); }
 
 std::once_flag g_attr_once;
 hipError_t g_attr_err = hipSuccess;
+int g_force_ksplit = 0;  // measurement hook: ranges of K whatever the cost model says
 
 }  // namespace
+
+void dg_force_ksplit(int ksplit) { g_force_ksplit = ksplit > 0 ? ksplit : 0; }
 
 DgPlan dg_plan(int B, int n_rows, int n_mat, int K, int n_cu, size_t ws_bytes) {
   DgPlan p{};
@@ -351,16 +357,20 @@ DgPlan dg_plan(int B, int n_rows, int n_mat, int K, int n_cu, size_t ws_bytes) {
   p.tiles_n = ((n_rows + BN - 1) / BN) * n_mat;
   const int steps = (K + BK - 1) / BK, T = p.tiles_m * p.tiles_n;
   if (n_cu < 1) n_cu = 1;
-  // A range of K costs its steps plus a fixed share (filling the pipeline, writing the partial tile, reading it back);
-  // ranges shorter than two passes of the four-stage loop are not worth a workgroup.
+  // Cost of a cut in microseconds, fitted to measurements on 256 compute units: a round of workgroups takes its K steps
+  // (0.71 / 0.83 / 0.93 us per step at 128 / 192 / 256 batch rows: the pace of one wave per SIMD on its own) plus about
+  // 8 us of filling and draining; every range adds a partial matrix that is written once and read once (0.30 us per MB).
+  // Ranges shorter than two passes of the stage ring are not worth a workgroup.
+  const double t_step = p.FM == 2 ? 0.71 : p.FM == 3 ? 0.83 : 0.93, t_fixed = 8.0, t_part_mb = 0.30;
   const int ks_max = std::max(1, std::min(32, steps / 8));
-  long long best = -1;
+  double best = -1.0;
   for (int ks = 1; ks <= ks_max; ++ks) {
     const size_t bytes = (size_t)ks * p.Mpad * p.tiles_n * BN * 4;
     if (bytes > ws_bytes) break;
     const int rounds = (T * ks + n_cu - 1) / n_cu;
-    const long long cost = (long long)rounds * ((steps + ks - 1) / ks + 10);
-    if (best < 0 || cost < best) best = cost, p.ksplit = ks, p.rounds = rounds, p.part_bytes = bytes;
+    const double cost = rounds * (((steps + ks - 1) / ks) * t_step + t_fixed) + (double)bytes / 1048576.0 * t_part_mb;
+    if (best < 0 || cost < best || ks == g_force_ksplit) best = cost, p.ksplit = ks, p.rounds = rounds, p.part_bytes = bytes;
+    if (ks == g_force_ksplit) break;
   }
   return p;  // ksplit 0: not even one range fits the workspace
 }
@@ -380,7 +390,7 @@ size_t dg_workspace_bytes(const harli_model_cfg& m, int n_cu) {
   return std::min(need, (size_t)192 << 20);
 }
 
-harli_status dg_launch(DgKind kind, const SkinnyArgs& a, int x_tiles, float* part, size_t part_bytes, int n_cu, hipStream_t st) {
+harli_status dg_gemm(DgKind kind, const SkinnyArgs& a, int x_tiles, float* part, size_t part_bytes, int n_cu, hipStream_t st, DgPlan* used) {
   std::call_once(g_attr_once, [] {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_dgemm<2>), hipFuncAttributeMaxDynamicSharedMemorySize, dg_lds_bytes<2>());
     if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_dgemm<3>), hipFuncAttributeMaxDynamicSharedMemorySize, dg_lds_bytes<3>());
@@ -417,18 +427,31 @@ harli_status dg_launch(DgKind kind, const SkinnyArgs& a, int x_tiles, float* par
   if (p.FM == 2) hipLaunchKernelGGL(k_dgemm<2>, grid, dim3(NT), dg_lds_bytes<2>(), st, g);
   else if (p.FM == 3) hipLaunchKernelGGL(k_dgemm<3>, grid, dim3(NT), dg_lds_bytes<3>(), st, g);
   else hipLaunchKernelGGL(k_dgemm<4>, grid, dim3(NT), dg_lds_bytes<4>(), st, g);
+  HARLI_HIP(hipGetLastError());
+  *used = p;
+  return HARLI_OK;
+}
+
+harli_status dg_epilogue(DgKind kind, const SkinnyArgs& a, const DgPlan& p, const float* part, hipStream_t st) {
   const size_t ncols = (size_t)p.tiles_n * BN, split_stride = (size_t)p.Mpad * ncols;
   if (kind == DG_RESID) {
     hipLaunchKernelGGL(k_dg_resid, dim3((unsigned)((a.n_rows / 4 + 255) / 256), (unsigned)a.B), dim3(256), 0, st, a, part, p.ksplit, split_stride, ncols);
   } else if (kind == DG_GATEUP) {
     hipLaunchKernelGGL(k_dg_gateup, dim3((unsigned)((a.n_rows / 4 + 255) / 256), (unsigned)a.B), dim3(256), 0, st, a, part, p.ksplit, split_stride, ncols,
-                       g.tiles_n1 * BN);
+                       (p.tiles_n / 2) * BN);
   } else {
     const int threads = (a.n_q + 2 * a.n_kv) * (a.d / 8);
     hipLaunchKernelGGL(k_dg_qkv, dim3((unsigned)((threads + 255) / 256), (unsigned)a.B), dim3(256), 0, st, a, part, p.ksplit, split_stride, ncols);
   }
   HARLI_HIP(hipGetLastError());
   return HARLI_OK;
+}
+
+harli_status dg_launch(DgKind kind, const SkinnyArgs& a, int x_tiles, float* part, size_t part_bytes, int n_cu, hipStream_t st) {
+  DgPlan p{};
+  harli_status rc = dg_gemm(kind, a, x_tiles, part, part_bytes, n_cu, st, &p);
+  if (rc != HARLI_OK) return rc;
+  return dg_epilogue(kind, a, p, part, st);
 }
 
 }  // namespace harli

@@ -59,6 +59,48 @@ def test_batch_above_64_runs_in_passes():
     run_case(w, m, [7 + (i * 5) % 90 for i in range(100)], block_bytes=64 << 10)
 
 
+def test_three_layers_at_batch_250_with_embedding_and_logits():
+    """Above 64 sequences the layer GEMMs take the tiled path: here one batch tile of 256 rows with 250 real ones (the
+    last 16-row group ragged), a ragged last weight tile (ffn 688 of 768), three layers chained through the row norms
+    and the output layer after them."""
+    w, m = variant(0, dtype="bf16", n_layers=3, vocab=1000)
+    lengths = np.asarray([(i * 29) % 150 for i in range(250)], np.int32)
+    case = DecodeCase(w, m, lengths, full_model=True, block_bytes=64 << 10)
+    tok = wl.make_token_ids(dataclasses.replace(w, model=m), (250,))
+    hid = case.run_gpu(token_ids=tok)
+    ref_hid, ref_logits, _ = case.run_oracle(token_ids=tok)
+    assert_close(hid, ref_hid, "hidden state")
+    assert_close(case.logits_dev.cpu().numpy(), ref_logits, "logits")
+    case.check_cache()
+    first = (case.y_dev.clone(), case.logits_dev.clone(), case.slab.clone())
+    case.slab.copy_(torch.from_numpy(case.img0.view(np.uint8)))
+    case.run_gpu(token_ids=tok)                      # the partial tiles are added in a fixed order: the same bits again
+    assert torch.equal(case.y_dev, first[0]) and torch.equal(case.logits_dev, first[1]) and torch.equal(case.slab, first[2])
+
+
+def test_a_context_for_large_batches_serves_small_ones_on_the_streaming_kernels():
+    """max_batch decides whether the workspace of the tiled path exists; the batch of the step decides the path: a step
+    of 9 sequences gives the same bits in a context made for 200 as in one made for 9."""
+    w, m = variant(0, dtype="bf16", n_layers=2)
+    lengths = np.asarray([12, 200, 0, 77, 300, 33, 5, 129, 64], np.int32)
+    small = DecodeCase(w, m, lengths, block_bytes=64 << 10)
+    roomy = DecodeCase(w, m, lengths, block_bytes=64 << 10, max_batch=200)
+    assert roomy.ctx.device_bytes().decode_workspace > small.ctx.device_bytes().decode_workspace
+    assert np.array_equal(np.asarray(small.run_gpu()), np.asarray(roomy.run_gpu()))
+
+
+def test_out_of_range_page_id_is_reported_at_large_batch():
+    from paper_2511_11729_amd import binding as hb
+    w, m = variant(0, dtype="bf16")
+    case = DecodeCase(w, m, np.asarray([20 + i % 30 for i in range(80)], np.int32), block_bytes=64 << 10)
+    case.table_dev[70, 1] = 10_000_000
+    with pytest.raises(hb.HarliError) as e:
+        case.run_gpu()
+    assert "page id" in str(e.value)
+    case.table_dev[70, 1] = int(case.table[70, 1])
+    case.run_gpu()
+
+
 @pytest.mark.parametrize("n_q,n_kv,d", [(8, 2, 64), (8, 8, 128), (8, 4, 128), (8, 2, 128), (8, 1, 128), (6, 2, 128), (5, 1, 128),
                                         (6, 1, 128), (7, 1, 128)])
 def test_head_layouts(n_q, n_kv, d):
@@ -242,6 +284,13 @@ def test_config4_width_batches_that_split_into_uneven_passes(batch):
     batch tiles; 150: 128 + 22; 200: 128 + 72), the q,k,v GEMM 64."""
     w, m = variant(4, n_layers=1)
     run_case(w, m, [60 + (i * 53) % 300 for i in range(batch)])
+
+
+def test_config5_width_biases_at_batch_80():
+    """The tiled path with q, k, v biases and groups of seven query heads per KV head (hidden 3584: 14 weight tiles of
+    256 rows exactly; ffn 18944: 74)."""
+    w, m = variant(5, n_layers=1)
+    run_case(w, m, [40 + (i * 31) % 200 for i in range(80)])
 
 
 def test_config3_width_layer_lognormal_lengths():

@@ -53,6 +53,23 @@ def test_static_scratch_step_equals_the_allocating_step_twice_in_a_row():
         assert_close(l1.cpu().numpy(), ref_logits, "logits on the static scratch")
 
 
+def test_static_scratch_step_above_64_sequences_meets_the_oracle():
+    """Above 64 sequences harli_decode_step runs its GEMMs tiled, with partial tiles in a workspace of its context; the
+    static array has no room for that, so this entry point keeps the pass-wise kernels there.  Different summation
+    orders, hence the comparison at the parity bar instead of bit for bit."""
+    w = wl.workload(0)
+    m = dataclasses.replace(w.model, dtype="bf16", n_layers=2, vocab=1000)
+    wm = dataclasses.replace(w, model=m)
+    case = DecodeCase(w, m, np.asarray([5 + (i * 13) % 120 for i in range(100)], np.int32), full_model=True, block_bytes=64 << 10)
+    tok = wl.make_token_ids(wm, (case.B,))
+    assert 0 < case.ctx.decode_step_static_bytes(case.B, int(case.kv_len.max()) + 1) <= 64 << 20
+    (y0, l0, n0, s0), (y1, l1, n1, s1) = both_ways(case, tok)
+    ref_hid, ref_logits, _ = case.run_oracle(token_ids=tok)
+    for y, l, what in ((y0, l0, "allocating step"), (y1, l1, "static scratch")):
+        assert_close(y.cpu().numpy(), ref_hid, "hidden state, " + what)
+        assert_close(l.cpu().numpy(), ref_logits, "logits, " + what)
+
+
 def test_static_scratch_step_refuses_what_does_not_fit():
     w = wl.workload(0)
     m = dataclasses.replace(w.model, dtype="bf16")
