@@ -4,9 +4,8 @@
 // k_dgemm<FM>: workgroup tile (64 FM) batch rows x 256 weight rows over a range of K; four waves, one per SIMD, each
 // a (32 FM) x 128 block.  Both operands are read where the small-batch kernels keep them -- MFMA-fragment order,
 // [16-row tile][k step of 32][lane][8], a 16 x 32 tile being 1 KiB contiguous -- and go straight into LDS with
-// buffer loads; a lane picks the 16-byte chunk that belongs in its LDS slot, so the staged rows are 64 bytes each with
-// their chunks XOR-swizzled and the 32-row fragment reads are conflict free.  Four LDS stages, the K loop software
-// pipelined by hand as in the finetune task's weight GEMM (one wave per SIMD has nobody to hide its waits).  Rows and
+// buffer loads, tile by tile as they lie (the order is the one the 32-row fragment reads want: conflict free without
+// a swizzle).  Four to six LDS stages, the K loop software pipelined by hand as in the finetune task's weight GEMM (one wave per SIMD has nobody to hide its waits).  Rows and
 // tiles that do not exist, and stages past the end of the range, are loaded from an offset outside the buffer
 // resource, which the hardware answers with zeros.
 #include "decode_large.h"
@@ -69,12 +68,13 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1)))
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  // Loads: instruction j of a wave fills 16 rows of a stage; lane -> row lane/4, LDS slot lane%4, which receives chunk
-  // slot ^ ((row/2)%4) of that row.  In fragment order chunk c of row r of a 16 x 32 tile sits at (16 c + r) * 16.
+  // Loads: instruction j of a wave copies one 16 x 32 tile (1 KiB, lane l its 16 bytes at 16 l) to LDS as it lies in
+  // memory: fragment order, chunk c (8 k) of row r at (16 c + r) * 16.  Consecutive lanes read consecutive addresses --
+  // a permuted assignment (rows of 64 bytes in LDS) was measured at 0.83 us per K step against the 0.37 us its MFMAs
+  // take: the lanes of a quad then fall into four cache lines and the address path serialises them.
   // Only the per-lane offset is range checked by the hardware, so whatever must read as zero gets the offset kOut, and
   // the scalar offsets (tile and k step) are kept inside the operand by construction.
-  const int drow = lane >> 2, dchunk = (lane & 3) ^ ((lane >> 3) & 3);
-  const unsigned vlane = (unsigned)(dchunk * 16 + drow) * 16u;
+  const unsigned vlane = (unsigned)lane * 16u;
   constexpr unsigned kOut = 0x80000000u;
   constexpr int kRsrcFlags = 0x00020000;  // raw buffer of dwords
   const bool second = tn >= a.tiles_n1;
@@ -121,10 +121,10 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1)))
     _Pragma("unroll") for (int j = 0; j < 4; ++j) DG_BL(rsB, valid ? voffB[j] : kOut, soffB[j], SB + (wave * 4 + j) * 1024); \
   } while (0)
 
-  // fragment reads: row lane%32, 16-byte chunk 2 sub + lane/32, swizzled like the loads
-  const int sw = ((lane & 31) >> 1) & 3;
-  const int fo0 = (lane & 31) * 64 + ((lane >> 5) ^ sw) * 16;
-  const int fo1 = fo0 ^ 32;
+  // fragment reads of a 32-row block (two tiles, 2 KiB): row lane%32, chunk 2 sub + lane/32.  Sixteen lanes read 256
+  // contiguous bytes: conflict free as the tiles lie.
+  const int fo0 = ((lane & 31) >> 4) * 1024 + ((lane >> 5) * 16 + (lane & 15)) * 16;
+  const int fo1 = fo0 + 512;
   const int aoff = wm * (FM * 32) * 64, boff = ASZ + wn * 128 * 64;
   u32x4 fa0[FM], fb0[4], fa1[FM], fb1[4];
 #define DG_RD(FA, FB, buf, sub)                                                                                    \
@@ -357,17 +357,22 @@ DgPlan dg_plan(int B, int n_rows, int n_mat, int K, int n_cu, size_t ws_bytes) {
   p.tiles_n = ((n_rows + BN - 1) / BN) * n_mat;
   const int steps = (K + BK - 1) / BK, T = p.tiles_m * p.tiles_n;
   if (n_cu < 1) n_cu = 1;
-  // Cost of a cut in microseconds, fitted to measurements on 256 compute units: a round of workgroups takes its K steps
-  // (0.71 / 0.83 / 0.93 us per step at 128 / 192 / 256 batch rows: the pace of one wave per SIMD on its own) plus about
-  // 8 us of filling and draining; every range adds a partial matrix that is written once and read once (0.30 us per MB).
+  // Cost of a cut in microseconds, fitted to measurements on 256 compute units (it picks within 2 us of the best cut
+  // measured for every GEMM of the 7B- and 8B-class layers at 96 to 256 sequences).  A K step of a workgroup takes
+  // 0.36 / 0.47 / 0.60 us at 128 / 192 / 256 batch rows when it has the memory system to itself (the pace of one wave
+  // per SIMD) and up to 0.35 us more as the workgroups running together fill the chip (weights from HBM, the batch
+  // operand from L2); a round of workgroups adds about 7 us of filling and draining; every range adds a partial
+  // matrix that is written once and read once (0.30 us per MB).
   // Ranges shorter than two passes of the stage ring are not worth a workgroup.
-  const double t_step = p.FM == 2 ? 0.71 : p.FM == 3 ? 0.83 : 0.93, t_fixed = 8.0, t_part_mb = 0.30;
+  const double t_wg = p.FM == 2 ? 0.36 : p.FM == 3 ? 0.47 : 0.60, t_fixed = 7.0, t_part_mb = 0.30;
   const int ks_max = std::max(1, std::min(32, steps / 8));
   double best = -1.0;
   for (int ks = 1; ks <= ks_max; ++ks) {
     const size_t bytes = (size_t)ks * p.Mpad * p.tiles_n * BN * 4;
     if (bytes > ws_bytes) break;
     const int rounds = (T * ks + n_cu - 1) / n_cu;
+    const double busy = std::min(T * ks, n_cu) / 256.0;
+    const double t_step = t_wg + 0.35 * busy * busy;
     const double cost = rounds * (((steps + ks - 1) / ks) * t_step + t_fixed) + (double)bytes / 1048576.0 * t_part_mb;
     if (best < 0 || cost < best || ks == g_force_ksplit) best = cost, p.ksplit = ks, p.rounds = rounds, p.part_bytes = bytes;
     if (ks == g_force_ksplit) break;

@@ -136,4 +136,5 @@ def test_runtime_scheduler_replays_a_load_trace(hz):
     assert heavy >= light
     # the phase after a starvation episode re-plans
     assert ph[24]["action"] == hb.SCHED_REPLAN and ph[103]["action"] == hb.SCHED_REPLAN
-    assert hz.pool.stats().pending_frees <= 16
+    torch.cuda.synchronize()                          # units the feeder issued last may still be running
+    assert hz.pool.stats().pending_frees == 0          # every saved activation went back once its unit was done
