@@ -918,7 +918,13 @@ harli_status decode_step_bf16(harli_ctx* c, const harli_decode_batch* b, hipStre
     a.ssq_np = np;
     a.ssq_in = w.ssq + (size_t)(2 * L) * w.bpad * np;
     a.logits = b->logits;
-    dispatch_skinny<MODE_LM, 2, 4>(a, (m.vocab + 31) / 32, st);
+    // the output layer through the tiled path too, when one partial matrix of [batch, vocabulary] fits the workspace
+    if (large && dg_plan(B, m.vocab, 1, H, n_cu, w.part_bytes).ksplit >= 1 && (long long)((m.vocab + 15) / 16 + 16) * ((H + 31) / 32) * 1024 < (1ll << 31)) {
+      harli_status rc = dg_launch(DG_LM, a, x_tiles, w.part, w.part_bytes, n_cu, st);
+      if (rc != HARLI_OK) return rc;
+    } else {
+      dispatch_skinny<MODE_LM, 2, 4>(a, (m.vocab + 31) / 32, st);
+    }
     if (b->next_token) {
       hipLaunchKernelGGL(k_argmax_part, dim3(kArgSeg, B), dim3(256), 0, st, b->logits, m.vocab, w.amax_v, w.amax_i);
       hipLaunchKernelGGL(k_argmax_final, dim3(B), dim3(64), 0, st, w.amax_v, w.amax_i, b->next_token);

@@ -69,7 +69,7 @@ __device__ __forceinline__ float ssq_row_sum(const float* row, int np, int g) {
 
 
 // ---- large-batch path ---------------------------------------------------------------------------------------------
-enum DgKind { DG_QKV = 0, DG_RESID = 1, DG_GATEUP = 2 };
+enum DgKind { DG_QKV = 0, DG_RESID = 1, DG_GATEUP = 2, DG_LM = 3 };
 
 // How one GEMM of the step is cut: (64 FM)-row batch tiles x 256-row weight tiles x ksplit ranges of K.
 struct DgPlan {

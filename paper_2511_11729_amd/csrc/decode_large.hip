@@ -265,16 +265,37 @@ __global__ void __launch_bounds__(256) k_dg_resid(SkinnyArgs a, const float* par
 // m = silu(rho * gate) * (rho * up) as the next operand in fragment order.
 __global__ void __launch_bounds__(256) k_dg_gateup(SkinnyArgs a, const float* part, int ksplit, size_t split_stride, size_t ncols,
                                                    int up_col0) {
-  const int b = blockIdx.y, n0 = (blockIdx.x * 256 + threadIdx.x) * 4;
+  const int b = blockIdx.y;
+  // every wave adds up the row's norm for itself (a few KB from L2); a workgroup then takes several groups of 1024
+  // columns so that this is paid once per 4096 columns
   const float rho = rsqrtf(ssq_row_sum(a.ssq_in + (size_t)b * a.ssq_np, a.ssq_np, (threadIdx.x & 63) >> 4) * a.inv_dim + a.eps);
-  if (n0 >= a.n_rows) return;
-  const float4 ga = part_sum4(part, ksplit, split_stride, (size_t)b * ncols + n0);
-  const float4 up = part_sum4(part, ksplit, split_stride, (size_t)b * ncols + up_col0 + n0);
-  const float gv[4] = {ga.x * rho, ga.y * rho, ga.z * rho, ga.w * rho}, uv[4] = {up.x * rho, up.y * rho, up.z * rho, up.w * rho};
-  float m[4];
+  const int steps_n = (a.n_rows + 31) >> 5;
+  for (int n0 = (blockIdx.x * 256 + threadIdx.x) * 4; n0 < a.n_rows; n0 += gridDim.x * 1024) {
+    const float4 ga = part_sum4(part, ksplit, split_stride, (size_t)b * ncols + n0);
+    const float4 up = part_sum4(part, ksplit, split_stride, (size_t)b * ncols + up_col0 + n0);
+    const float gv[4] = {ga.x * rho, ga.y * rho, ga.z * rho, ga.w * rho}, uv[4] = {up.x * rho, up.y * rho, up.z * rho, up.w * rho};
+    float m[4];
 #pragma unroll
-  for (int e = 0; e < 4; ++e) m[e] = gv[e] / (1.f + __expf(-gv[e])) * uv[e];
-  *reinterpret_cast<uint2*>(a.mbuf + xfrag_off(b, n0, (a.n_rows + 31) >> 5)) = make_uint2(pack_bf2(m[0], m[1]), pack_bf2(m[2], m[3]));
+    for (int e = 0; e < 4; ++e) m[e] = gv[e] / (1.f + __expf(-gv[e])) * uv[e];
+    *reinterpret_cast<uint2*>(a.mbuf + xfrag_off(b, n0, steps_n)) = make_uint2(pack_bf2(m[0], m[1]), pack_bf2(m[2], m[3]));
+  }
+}
+
+// logits = rho * sum (the output layer after the last layer's norm)
+__global__ void __launch_bounds__(256) k_dg_lm(SkinnyArgs a, const float* part, int ksplit, size_t split_stride, size_t ncols) {
+  const int b = blockIdx.y;
+  const float rho = rsqrtf(ssq_row_sum(a.ssq_in + (size_t)b * a.ssq_np, a.ssq_np, (threadIdx.x & 63) >> 4) * a.inv_dim + a.eps);
+  const bool vec = (a.n_rows & 3) == 0;  // rows of the logits are 16-byte aligned
+  for (int n0 = (blockIdx.x * 256 + threadIdx.x) * 4; n0 < a.n_rows; n0 += gridDim.x * 1024) {
+    const float4 s = part_sum4(part, ksplit, split_stride, (size_t)b * ncols + n0);  // the partial rows are padded to whole tiles
+    float* o = a.logits + (size_t)b * a.n_rows + n0;
+    if (vec) {
+      *reinterpret_cast<float4*>(o) = make_float4(s.x * rho, s.y * rho, s.z * rho, s.w * rho);
+    } else {
+      const float v[4] = {s.x * rho, s.y * rho, s.z * rho, s.w * rho};
+      for (int e = 0; e < 4 && n0 + e < a.n_rows; ++e) o[e] = v[e];
+    }
+  }
 }
 
 // q, k, v = rho * sum + bias; rotary embedding on q and k; q to the attention's query buffer, k and v to the page the
@@ -391,6 +412,7 @@ size_t dg_workspace_bytes(const harli_model_cfg& m, int n_cu) {
     need = std::max(need, dg_plan(B, m.hidden, 1, QD, n_cu, ~size_t(0)).part_bytes);
     need = std::max(need, dg_plan(B, m.ffn, 2, m.hidden, n_cu, ~size_t(0)).part_bytes);
     need = std::max(need, dg_plan(B, m.hidden, 1, m.ffn, n_cu, ~size_t(0)).part_bytes);
+    if (m.vocab > 0) need = std::max(need, dg_plan(B, m.vocab, 1, m.hidden, n_cu, ~size_t(0)).part_bytes);
   }
   return std::min(need, (size_t)192 << 20);
 }
@@ -408,7 +430,7 @@ harli_status dg_gemm(DgKind kind, const SkinnyArgs& a, int x_tiles, float* part,
   const int steps = (a.K + BK - 1) / BK, w_tiles16 = (n_rows + 15) / 16;
   if (!part || a.B < 1 || x_tiles * 16 < a.B || (kind == DG_GATEUP && !a.w1))
     return fail(HARLI_ERR_INVALID, "decode (large batch): bad arguments (batch %d, %d operand tiles)", a.B, x_tiles);
-  if ((a.n_rows & 7) || (kind == DG_QKV && (a.d & 15)))
+  if ((kind != DG_LM && (a.n_rows & 7)) || (kind == DG_QKV && (a.d & 15)))
     return fail(HARLI_ERR_INVALID, "decode (large batch): %d output rows, head size %d", a.n_rows, a.d);
   // the kernel addresses both operands with 32-bit byte offsets below 2^31
   if ((long long)(w_tiles16 + 16) * steps * 1024 >= (1ll << 31) || (long long)x_tiles * steps * 1024 >= (1ll << 31))
@@ -442,8 +464,10 @@ harli_status dg_epilogue(DgKind kind, const SkinnyArgs& a, const DgPlan& p, cons
   if (kind == DG_RESID) {
     hipLaunchKernelGGL(k_dg_resid, dim3((unsigned)((a.n_rows / 4 + 255) / 256), (unsigned)a.B), dim3(256), 0, st, a, part, p.ksplit, split_stride, ncols);
   } else if (kind == DG_GATEUP) {
-    hipLaunchKernelGGL(k_dg_gateup, dim3((unsigned)((a.n_rows / 4 + 255) / 256), (unsigned)a.B), dim3(256), 0, st, a, part, p.ksplit, split_stride, ncols,
+    hipLaunchKernelGGL(k_dg_gateup, dim3((unsigned)((a.n_rows + 4095) / 4096), (unsigned)a.B), dim3(256), 0, st, a, part, p.ksplit, split_stride, ncols,
                        (p.tiles_n / 2) * BN);
+  } else if (kind == DG_LM) {
+    hipLaunchKernelGGL(k_dg_lm, dim3((unsigned)((a.n_rows + 4095) / 4096), (unsigned)a.B), dim3(256), 0, st, a, part, p.ksplit, split_stride, ncols);
   } else {
     const int threads = (a.n_q + 2 * a.n_kv) * (a.d / 8);
     hipLaunchKernelGGL(k_dg_qkv, dim3((unsigned)((threads + 255) / 256), (unsigned)a.B), dim3(256), 0, st, a, part, p.ksplit, split_stride, ncols);
