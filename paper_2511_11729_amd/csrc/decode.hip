@@ -426,8 +426,33 @@ __global__ void __launch_bounds__(256) k_decode_prep(int H, int d, int n_ssq, in
 // in the grid every workgroup writes a (max, sum, unnormalised output) partial that
 // k_attn_merge combines.
 // ---------------------------------------------------------------------------------------------
+// Sum over the LPT (8 or 16) lanes that share a token, the same bits in every one of them.  The exchanges are DPP
+// operands of the adds (mirror of the 16-lane row, mirror of its 8-lane halves, then inside quads): the cross-lane
+// network of the vector ALU, not LDS -- with wavefront shuffles (ds_bpermute) the four query heads of a grouped-query
+// chunk kept the LDS pipe busier than the K/V stream kept HBM.  Every step adds the two values of a pair in both
+// lanes of the pair, so all lanes end with identical sums.
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, false));
+}
+template <int LPT>
+__device__ __forceinline__ float token_lanes_sum(float s) {
+  static_assert(LPT == 8 || LPT == 16, "a token's head vector spans 8 or 16 lanes");
+  if (LPT == 16) s += dpp_f<0x140>(s);  // lane i with 15 - i
+  s += dpp_f<0x141>(s);                 // lane i with 7 - i of its half row
+  s += dpp_f<0x4E>(s);                  // i with i ^ 2
+  s += dpp_f<0xB1>(s);                  // i with i ^ 1
+  return s;
+}
+
+// Waves per SIMD the register allocation aims at.  What the K/V stream reaches follows the bytes in flight per compute
+// unit (a workgroup keeps all of its CH tokens in flight): four query heads per KV head at d = 128 need 131 registers
+// left alone, three short of a fourth wave per SIMD, that is of 256 instead of 192 KiB in flight.
+template <int D, int G>
+constexpr int attn_min_waves() { return (D == 128 && G == 4) ? 4 : 1; }
+
 template <int D, int G, int CH>
-__global__ void __launch_bounds__(256) k_paged_attn(const float* qbuf, const int* kv_len, const int* page_table,
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(attn_min_waves<D, G>(), 8))) k_paged_attn(const float* qbuf, const int* kv_len, const int* page_table,
                                                     int max_pages, int layer, int n_q, int n_kv, const char* slab,
                                                     KvGeom geom, float* part, int max_chunks, unsigned short* obuf,
                                                     int* err_flag) {
@@ -510,8 +535,7 @@ __global__ void __launch_bounds__(256) k_paged_attn(const float* qbuf, const int
         float s = 0.f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) s += qv[gq][e] * kk[e];
-#pragma unroll
-        for (int o = 1; o < LPT; o <<= 1) s += __shfl_xor(s, o, 64);
+        s = token_lanes_sum<LPT>(s);
         s = ok[pp][it] ? s : -INFINITY;
         sc[gq][pp][it] = s;
         mw[gq] = fmaxf(mw[gq], s);
