@@ -159,7 +159,9 @@ typedef struct {
   float rms_eps;    /* 1e-6 */
   float rope_base;  /* 10000 */
   int32_t dtype;    /* harli_dtype: storage of weights, KV cache, saved activations */
-  int32_t max_batch;      /* largest decode batch (1..256) */
+  int32_t max_batch;      /* largest decode batch (1..256).  From 17 on the context also holds the workspace of the tiled
+                           * GEMMs that steps of more than 32 sequences run (Sec. 1: decode is served up to batch 256):
+                           * up to 192 MiB for the partial tiles, part of decode_workspace in harli_ctx_device_bytes */
   int32_t max_seq_len;    /* largest kv_len[b] + 1 a decode step may see */
   int32_t max_ft_tokens;  /* largest B_f*S of a finetune call (0: finetune unused) */
   /* Where the library's own device memory for this context lives: the decode instance's pre-shuffled weight copies and
@@ -264,10 +266,10 @@ harli_status harli_decode_step(harli_ctx* c, const harli_decode_batch* b, void* 
 
 /* The same step for callers that cannot allocate device memory or rely on memory allocated for them: code under
  * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments as harli_decode_step and,
- * up to 64 sequences, the same kernels and the same bits, but every intermediate buffer of the step (GEMM operands,
+ * up to 32 sequences, the same kernels and the same bits, but every intermediate buffer of the step (GEMM operands,
  * q, attention partials, row norms, rotary table, argmax partials) lives in one array of HARLI_STATIC_SCRATCH_BYTES
  * that is part of the library's device image (each GPU the library runs on holds its copy until the process ends)
- * instead of the workspace harli_ctx_create allocated.  Above 64 sequences harli_decode_step runs its GEMMs tiled over
+ * instead of the workspace harli_ctx_create allocated.  Above 32 sequences harli_decode_step runs its GEMMs tiled over
  * ranges of K with partial tiles in that workspace (tens of MB, which the array has no room for): this entry point
  * then keeps the kernels that take the batch in passes of 64 or 128 rows, and agrees with harli_decode_step to
  * rounding, not bit for bit.  The call itself allocates and frees nothing, on the host side of the

@@ -60,7 +60,7 @@ harli_status harli_dbg_gemm2(const harli_dbg_gemm2_desc* d, void* hip_stream);
  * round of 256-row tiles. */
 harli_status harli_dbg_gemm2_plan(int32_t M, int32_t tiles_n, int32_t tile_rows, int32_t n_cu, int32_t* out);
 
-/* How one GEMM of a decode step above 64 sequences is cut (host logic only, no device needed): `batch` sequences,
+/* How one GEMM of a decode step above 32 sequences is cut (host logic only, no device needed): `batch` sequences,
  * n_mat (1, or 2 for gate and up) weight matrices of n_rows rows, contraction length K, on n_cu compute units, with
  * ws_bytes of workspace for the partial tiles.  out[7] (host): batch rows per tile / 64, batch tiles, rows of a partial
  * matrix, 256-row weight tiles of all matrices, ranges of K (0: not even one fits the workspace), rounds of workgroups
@@ -74,6 +74,10 @@ harli_status harli_dbg_decode_gemm_plan(int32_t batch, int32_t n_rows, int32_t n
  * of the first and of the second launch over `reps` runs, the ranges of K and the tile height / 64 that ran. */
 harli_status harli_dbg_decode_gemm_time(int32_t batch, int32_t n_rows, int32_t n_mat, int32_t K, int32_t ksplit, int32_t reps,
                                         float* out_us, void* hip_stream);
+
+/* Measurement hook: the smallest batch whose decode steps run the tiled GEMMs (process-wide; 0 gives the library's
+ * own threshold back).  A context takes the workspace of that path when its max_batch is 17 or more. */
+void harli_dbg_decode_large_min_batch(int32_t batch);
 
 /* The residency plan of harli_ft_window_* on its own (host logic only, no device needed): a window of n_slots over the
  * 2 * n_layers cyclic items, prefilled with items 0..n_slots-1, is driven through `items[0..n_access)`; for every

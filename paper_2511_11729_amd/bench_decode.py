@@ -26,6 +26,7 @@ def main():
     ap.add_argument("--kv-len", type=int, default=None, help="cached tokens per sequence (default: the workload's draw)")
     ap.add_argument("--layers", type=int, default=None, help="depth override")
     ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--large-min-batch", type=int, default=0, help="measurement hook: smallest batch that runs the tiled GEMMs (0: the library's own)")
     args = ap.parse_args()
 
     import dataclasses
@@ -34,6 +35,8 @@ def main():
     from paper_2511_11729_amd import binding as hb
 
     hb.lib()
+    if args.large_min_batch:
+        hb.dbg_decode_large_min_batch(args.large_min_batch)
     dev = "cuda:0"
     torch.cuda.set_device(0)
     w = wl.workload(args.config)

@@ -150,6 +150,7 @@ _SIGS = {
                                         C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
     "harli_dbg_gemm2": (C.c_int, [C.c_void_p, C.c_void_p]),
     "harli_dbg_gemm2_plan": (C.c_int, [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int32)]),
+    "harli_dbg_decode_large_min_batch": (None, [C.c_int32]),
     "harli_dbg_decode_gemm_plan": (C.c_int, [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int64, C.POINTER(C.c_int64)]),
     "harli_dbg_decode_gemm_time": (C.c_int, [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_float), C.c_void_p]),
 }
@@ -537,8 +538,13 @@ class DbgGemm2Desc(C.Structure):
                 ("shader_mhz", C.POINTER(C.c_double)), ("n_cu", C.c_int32)]
 
 
+def dbg_decode_large_min_batch(batch: int) -> None:
+    """Measurement hook: the smallest batch whose decode steps run the tiled GEMMs (0: the library's own)."""
+    lib().harli_dbg_decode_large_min_batch(batch)
+
+
 def dbg_decode_gemm_plan(batch: int, n_rows: int, n_mat: int, K: int, n_cu: int, ws_bytes: int) -> dict:
-    """How one GEMM of a decode step above 64 sequences is cut (host logic only)."""
+    """How one GEMM of a decode step above 32 sequences is cut (host logic only)."""
     out = (C.c_int64 * 7)()
     _check(lib().harli_dbg_decode_gemm_plan(batch, n_rows, n_mat, K, n_cu, ws_bytes, out))
     return dict(zip(("FM", "tiles_m", "Mpad", "tiles_n", "ksplit", "rounds", "part_bytes"), [int(v) for v in out]))

@@ -290,3 +290,5 @@ extern "C" harli_status harli_dbg_decode_gemm_time(int32_t batch, int32_t n_rows
   out_us[3] = (float)p.FM;
   return rc;
 }
+
+extern "C" void harli_dbg_decode_large_min_batch(int32_t batch) { dg_set_min_batch(batch); }

@@ -828,9 +828,9 @@ harli_status decode_step_bf16(harli_ctx* c, const harli_decode_batch* b, hipStre
   const float* xcur = b->token_ids ? w.xa : b->x_in;
   float* ping[2] = {w.xb, w.xa};  // layer l writes ping[l&1]; layer 0 must not overwrite xa (it can be its input)
   const int G = m.n_q_heads / m.n_kv_heads;
-  // above 64 sequences the layer GEMMs run as tiled MFMA GEMMs with their epilogues in a second kernel (decode_large.h);
+  // above 32 sequences the layer GEMMs run as tiled MFMA GEMMs with their epilogues in a second kernel (decode_large.h);
   // a caller's buffer without the workspace for their partial tiles keeps every batch on the small-batch kernels
-  const bool large = B > 64 && w.part != nullptr;
+  const bool large = B >= dg_min_batch() && w.part != nullptr;
   int n_cu = cu_stream_count(st);  // a stream confined to a share of the compute units (Sec. 6.2)
   if (n_cu < 1) n_cu = c->n_cu;
   const int x_tiles = w.bpad / 16;

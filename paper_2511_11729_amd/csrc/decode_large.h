@@ -1,6 +1,6 @@
 // Decode step, shared between the small-batch kernels (decode.hip) and the large-batch path (decode_large.hip).
 //
-// Large batches (Harli Sec. 1: a decode instance is served at batch sizes up to 256 before it saturates): above 64
+// Large batches (Harli Sec. 1: a decode instance is served at batch sizes up to 256 before it saturates): above 32
 // sequences the step's GEMMs are no longer pure weight streams -- every 16-row weight tile would be multiplied with
 // 4..16 batch fragments that each wave pulls through the vector cache for itself.  The large-batch path runs them as
 // tiled MFMA GEMMs instead: both operands staged through LDS once per workgroup, the contraction cut into ranges over
@@ -92,5 +92,8 @@ harli_status dg_launch(DgKind kind, const SkinnyArgs& a, int x_tiles, float* par
 harli_status dg_gemm(DgKind kind, const SkinnyArgs& a, int x_tiles, float* part, size_t part_bytes, int n_cu, hipStream_t st, DgPlan* used);
 harli_status dg_epilogue(DgKind kind, const SkinnyArgs& a, const DgPlan& p, const float* part, hipStream_t st);
 void dg_force_ksplit(int ksplit);
+// smallest batch that takes the tiled path (measurement hook; 0 gives the default back)
+void dg_set_min_batch(int b);
+int dg_min_batch();
 
 }  // namespace harli

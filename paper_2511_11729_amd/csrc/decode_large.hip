@@ -1,7 +1,7 @@
 // Large-batch GEMMs of the decode step (see decode_large.h): partial products on 32x32x16 bf16 MFMA tiles, then one
 // small kernel per GEMM that adds the partials and applies the step's epilogue.
 //
-// k_dgemm<FM>: workgroup tile (64 FM) batch rows x 256 weight rows over a range of K; four waves, one per SIMD, each
+// k_dgemm<FM>: workgroup tile (64 FM) batch rows (FM = 1..4) x 256 weight rows over a range of K; four waves, one per SIMD, each
 // a (32 FM) x 128 block.  Both operands are read where the small-batch kernels keep them -- MFMA-fragment order,
 // [16-row tile][k step of 32][lane][8], a 16 x 32 tile being 1 KiB contiguous -- and go straight into LDS with
 // buffer loads, tile by tile as they lie (the order is the one the 32-row fragment reads want: conflict free without
@@ -40,7 +40,7 @@ struct DgemmArgs {
 // LDS stages: the weights come from HBM, whose latency under load is several K steps long, so the ring is as deep as
 // 160 KiB of LDS allow (bytes in flight per compute unit are what the stream's rate follows).
 template <int FM>
-constexpr int dg_stages() { return FM == 2 ? 6 : FM == 3 ? 5 : 4; }
+constexpr int dg_stages() { return FM <= 2 ? 6 : FM == 3 ? 5 : 4; }
 
 template <int FM>
 __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1))) k_dgemm(DgemmArgs a) {
@@ -369,9 +369,16 @@ int g_force_ksplit = 0;  // measurement hook: ranges of K whatever the cost mode
 
 void dg_force_ksplit(int ksplit) { g_force_ksplit = ksplit > 0 ? ksplit : 0; }
 
+// Smallest batch on the tiled path.  Measured on the 7B/8B-class models at full depth: at 48 and 64 sequences the
+// tiled step is 9-24 % shorter than the pass-wise one, at 24 and 32 it is 1-3 % longer.
+constexpr int kMinBatch = 33;
+int g_min_batch = kMinBatch;
+void dg_set_min_batch(int b) { g_min_batch = b > 0 ? b : kMinBatch; }
+int dg_min_batch() { return g_min_batch; }
+
 DgPlan dg_plan(int B, int n_rows, int n_mat, int K, int n_cu, size_t ws_bytes) {
   DgPlan p{};
-  p.FM = B <= 128 ? 2 : B <= 192 ? 3 : 4;
+  p.FM = B <= 64 ? 1 : B <= 128 ? 2 : B <= 192 ? 3 : 4;
   const int BM = 64 * p.FM;
   p.tiles_m = (B + BM - 1) / BM;
   p.Mpad = p.tiles_m * BM;
@@ -385,7 +392,7 @@ DgPlan dg_plan(int B, int n_rows, int n_mat, int K, int n_cu, size_t ws_bytes) {
   // operand from L2); a round of workgroups adds about 7 us of filling and draining; every range adds a partial
   // matrix that is written once and read once (0.30 us per MB).
   // Ranges shorter than two passes of the stage ring are not worth a workgroup.
-  const double t_wg = p.FM == 2 ? 0.36 : p.FM == 3 ? 0.47 : 0.60, t_fixed = 7.0, t_part_mb = 0.30;
+  const double t_wg = p.FM == 1 ? 0.30 : p.FM == 2 ? 0.36 : p.FM == 3 ? 0.47 : 0.60, t_fixed = 7.0, t_part_mb = 0.30;
   const int ks_max = std::max(1, std::min(32, steps / 8));
   double best = -1.0;
   for (int ks = 1; ks <= ks_max; ++ks) {
@@ -402,10 +409,10 @@ DgPlan dg_plan(int B, int n_rows, int n_mat, int K, int n_cu, size_t ws_bytes) {
 }
 
 size_t dg_workspace_bytes(const harli_model_cfg& m, int n_cu) {
-  if (m.dtype != HARLI_BF16 || m.max_batch <= 64) return 0;
+  if (m.dtype != HARLI_BF16 || m.max_batch < 17) return 0;  // 17: the lowest setting of the measurement hook
   const int QKV = (m.n_q_heads + 2 * m.n_kv_heads) * m.head_dim, QD = m.n_q_heads * m.head_dim;
   size_t need = 0;
-  const int bs[4] = {128, 192, 256, m.max_batch};
+  const int bs[5] = {64, 128, 192, 256, m.max_batch};
   for (int B : bs) {
     if (B > m.max_batch) continue;
     need = std::max(need, dg_plan(B, QKV, 1, m.hidden, n_cu, ~size_t(0)).part_bytes);
@@ -419,7 +426,8 @@ size_t dg_workspace_bytes(const harli_model_cfg& m, int n_cu) {
 
 harli_status dg_gemm(DgKind kind, const SkinnyArgs& a, int x_tiles, float* part, size_t part_bytes, int n_cu, hipStream_t st, DgPlan* used) {
   std::call_once(g_attr_once, [] {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_dgemm<2>), hipFuncAttributeMaxDynamicSharedMemorySize, dg_lds_bytes<2>());
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_dgemm<1>), hipFuncAttributeMaxDynamicSharedMemorySize, dg_lds_bytes<1>());
+    if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_dgemm<2>), hipFuncAttributeMaxDynamicSharedMemorySize, dg_lds_bytes<2>());
     if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_dgemm<3>), hipFuncAttributeMaxDynamicSharedMemorySize, dg_lds_bytes<3>());
     if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_dgemm<4>), hipFuncAttributeMaxDynamicSharedMemorySize, dg_lds_bytes<4>());
     g_attr_err = e;
@@ -451,7 +459,8 @@ harli_status dg_gemm(DgKind kind, const SkinnyArgs& a, int x_tiles, float* part,
   g.Mpad = p.Mpad;
   g.part = part;
   const dim3 grid((unsigned)(p.tiles_n * p.tiles_m * p.ksplit));
-  if (p.FM == 2) hipLaunchKernelGGL(k_dgemm<2>, grid, dim3(NT), dg_lds_bytes<2>(), st, g);
+  if (p.FM == 1) hipLaunchKernelGGL(k_dgemm<1>, grid, dim3(NT), dg_lds_bytes<1>(), st, g);
+  else if (p.FM == 2) hipLaunchKernelGGL(k_dgemm<2>, grid, dim3(NT), dg_lds_bytes<2>(), st, g);
   else if (p.FM == 3) hipLaunchKernelGGL(k_dgemm<3>, grid, dim3(NT), dg_lds_bytes<3>(), st, g);
   else hipLaunchKernelGGL(k_dgemm<4>, grid, dim3(NT), dg_lds_bytes<4>(), st, g);
   HARLI_HIP(hipGetLastError());

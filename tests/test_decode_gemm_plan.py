@@ -11,7 +11,7 @@ def plan(B, n_rows, n_mat, K, n_cu=256, ws=WS):
     return hb.dbg_decode_gemm_plan(B, n_rows, n_mat, K, n_cu, ws)
 
 
-@pytest.mark.parametrize("B,fm", [(65, 2), (128, 2), (129, 3), (192, 3), (193, 4), (256, 4), (257, 4), (600, 4)])
+@pytest.mark.parametrize("B,fm", [(33, 1), (64, 1), (65, 2), (128, 2), (129, 3), (192, 3), (193, 4), (256, 4), (257, 4), (600, 4)])
 def test_tile_height_follows_the_batch(B, fm):
     p = plan(B, 4096, 1, 4096)
     assert p["FM"] == fm

@@ -60,7 +60,7 @@ def test_batch_above_64_runs_in_passes():
 
 
 def test_three_layers_at_batch_250_with_embedding_and_logits():
-    """Above 64 sequences the layer GEMMs take the tiled path: here one batch tile of 256 rows with 250 real ones (the
+    """Above 32 sequences the layer GEMMs take the tiled path: here one batch tile of 256 rows with 250 real ones (the
     last 16-row group ragged), a ragged last weight tile (ffn 688 of 768), three layers chained through the row norms
     and the output layer after them."""
     w, m = variant(0, dtype="bf16", n_layers=3, vocab=1000)
@@ -273,15 +273,15 @@ def test_config2_width_two_layers_batch16_with_logits():
 
 
 def test_config2_width_batch256():
-    """The largest decode batch of the sweep (passes of 64 or 128 rows) on one 7B-class layer."""
+    """The largest decode batch (one tile of 256 batch rows, no idle row) on one 7B-class layer."""
     w, m = variant(2, n_layers=1)
     run_case(w, m, [100 + (i * 37) % 400 for i in range(256)])
 
 
 @pytest.mark.parametrize("batch", [70, 150, 200])
 def test_config4_width_batches_that_split_into_uneven_passes(batch):
-    """Batches above 64 rows on the GQA layer: the eight-wave GEMMs take 128 rows per pass (70: one pass with three idle
-    batch tiles; 150: 128 + 22; 200: 128 + 72), the q,k,v GEMM 64."""
+    """Batches above 64 rows on the GQA layer: tiles of 128, 192 and 256 batch rows (70: 58 idle rows; 150: 42; 200: 56),
+    every GEMM cut into ranges of K."""
     w, m = variant(4, n_layers=1)
     run_case(w, m, [60 + (i * 53) % 300 for i in range(batch)])
 
