@@ -342,6 +342,17 @@ def main():
         fa = argparse.Namespace(config=2, layers=None, batch=16, kv_len=1024, steps=3, slo_ms=SLO_MS_FULL_MODEL, pace_ms=None)
         full = bench_colocate.run(fa)
 
+    # ------------------------------------------------------------------ a large decode batch at full depth (Sec. 1: up to 256)
+    large = None
+    if not args.no_full_depth:
+        log("[bench] large-batch decode leg: config 4 (32 layers + output layer, grouped-query attention), batch 192 x 1100")
+        gc.collect()
+        torch.cuda.empty_cache()
+        from paper_2511_11729_amd import bench_decode
+        large = bench_decode.run(argparse.Namespace(config=4, batch=192, kv_len=1100, layers=None, steps=5, large_min_batch=0))
+        large["note"] = ("decode alone; above 32 sequences the step's GEMMs run tiled over ranges of K with their epilogues in a "
+                         "second kernel per GEMM")
+
     ach_tf = gemm_flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else float("nan")
     traffic_gemm, traffic_decode = measured_traffic()
     out = {
@@ -386,6 +397,7 @@ def main():
         "measured_peaks": peaks,
         "memory": lib_mem,
         "full_depth": full,
+        "decode_large_batch": large,
         "notes": {"finetune_unit": "a unit is one layer forward + backward on a fixed seeded dY (no loss between them: the loss "
                                    "belongs to the whole-model step, which the full_depth leg times with its output layer, "
                                    "cross entropy and AdamW)"},

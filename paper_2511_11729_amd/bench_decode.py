@@ -28,7 +28,12 @@ def main():
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--large-min-batch", type=int, default=0, help="measurement hook: smallest batch that runs the tiled GEMMs (0: the library's own)")
     args = ap.parse_args()
+    print(json.dumps(run(args)))
 
+
+def run(args):
+    """The measurement itself; `args` carries config, batch, kv_len, layers, steps, large_min_batch.  Returns the result
+    dictionary (bench.py calls this for its large-batch decode leg)."""
     import dataclasses
     import torch
     import workloads as wl
@@ -115,10 +120,10 @@ def main():
     kv_bytes = int(sum(int(n) + 1 for n in kv_len)) * 2 * m.kv_row_bytes * L
     w_bytes = 2 * (L * m.layer_params + m.vocab * m.hidden)
     total = w_bytes + kv_bytes
-    print(json.dumps({"workload": "config %d decode, %d layers, batch %d, cached tokens %d..%d" % (args.config, L, B, kv_len.min(), kv_len.max()),
-                      "tpot_ms": ms, "tokens_per_s": B / ms * 1e3, "bytes_per_step": total, "weight_bytes": w_bytes,
-                      "kv_bytes": kv_bytes, "achieved_GBs": total / ms / 1e6, "frac_of_8TBs": total / ms / 1e6 / 8000.0,
-                      "steps": args.steps}))
+    return {"workload": "config %d decode, %d layers, batch %d, cached tokens %d..%d" % (args.config, L, B, kv_len.min(), kv_len.max()),
+            "tpot_ms": ms, "tokens_per_s": B / ms * 1e3, "bytes_per_step": total, "weight_bytes": w_bytes,
+            "kv_bytes": kv_bytes, "achieved_GBs": total / ms / 1e6, "frac_of_8TBs": total / ms / 1e6 / 8000.0,
+            "steps": args.steps}
 
 
 if __name__ == "__main__":

@@ -53,6 +53,8 @@ class LayerHarness:
         # every byte the library keeps (the decode instance's weight copy, the finetune instance's two, both workspaces)
         # comes from the pool as well: one pool for all tensors of both tasks (Sec. 4.2)
         lib_bytes = 6 * m.layer_params + 3 * act + (128 << 20)
+        if cap_b >= 17:                                  # the partial tiles of the decode GEMMs above 32 sequences (at most 192 MiB)
+            lib_bytes += 192 << 20
         n_chunks = -(-total_pages // ppb) + in_flight * (act // chunk + 2) + lib_bytes // chunk + 8
         small = 64 << 20
         self.slab_bytes = small + n_chunks * chunk

@@ -1,4 +1,5 @@
-"""Measurement hooks of the debug ABI: the read-bandwidth probe and the weight GEMM's in-kernel clock probe."""
+"""Measurement hooks of the debug ABI: the read-bandwidth probe, the weight GEMM's in-kernel clock probe, the timing hook of
+the decode GEMMs above 32 sequences."""
 import pytest
 import torch
 
@@ -32,3 +33,19 @@ def test_clock_probe_reports_the_clock_and_leaves_the_product_intact():
     assert 500.0 < mhz < 2600.0 and tf > 0.0
     ref = A.double().cpu() @ B.double().cpu().T
     assert float((Cb.double().cpu() - ref).abs().max()) <= 2e-3 * float(ref.abs().max())
+
+
+def test_decode_gemm_timing_hook_runs_the_cut_it_is_asked_for():
+    """harli_dbg_decode_gemm_time: the plan's own cut, a forced number of K ranges, the SwiGLU pair; times are positive and
+    the hook gives the choice back afterwards."""
+    own = hb.dbg_decode_gemm_time(150, 1024, 1, 2048, 0, 3)
+    assert own["gemm_us"] > 0 and own["epilogue_us"] > 0 and own["FM"] == 3
+    assert own["ksplit"] == hb.dbg_decode_gemm_plan(150, 1024, 1, 2048, torch.cuda.get_device_properties(0).multi_processor_count, 192 << 20)["ksplit"]
+    forced = hb.dbg_decode_gemm_time(150, 1024, 1, 2048, 3, 3)
+    assert forced["ksplit"] == 3
+    pair = hb.dbg_decode_gemm_time(40, 688, 2, 256, 0, 3)            # a ragged last weight tile, one K range
+    assert pair["ksplit"] == 1 and pair["FM"] == 1 and pair["gemm_us"] > 0
+    again = hb.dbg_decode_gemm_time(150, 1024, 1, 2048, 0, 3)
+    assert again["ksplit"] == own["ksplit"]
+    with pytest.raises(hb.HarliError):
+        hb.dbg_decode_gemm_time(150, 1023, 1, 2048, 0, 3)             # rows must be a multiple of 8
