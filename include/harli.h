@@ -283,6 +283,10 @@ harli_status harli_decode_step(harli_ctx* c, const harli_decode_batch* b, void* 
  *     stream order.  harli_decode_step does not touch the array and may run beside it. */
 #define HARLI_STATIC_SCRATCH_BYTES (64u << 20)
 harli_status harli_decode_step_static(harli_ctx* c, const harli_decode_batch* b, void* hip_stream);
+/* Smallest batch whose harli_decode_step runs the tiled GEMMs (33 unless a measurement hook moved it): the step time
+ * is linear in the batch size on either side with different slopes, which a latency predictor may want to know
+ * (harli_pred_set_batch_split). */
+int32_t harli_decode_tiled_min_batch(void);
 size_t harli_decode_step_static_bytes(const harli_ctx* c, int32_t batch, int32_t max_kv_len);
 
 /* ======================================================================== *

@@ -70,6 +70,16 @@ harli_status harli_pred_observe(harli_predictor* p, int32_t level, double predic
 harli_status harli_pred_solo_coef(const harli_predictor* p, int32_t level, double* solo);
 harli_status harli_pred_colo_coef(const harli_predictor* p, double* colo);
 
+/* Eq. 1 per kernel family.  Eq. 1 is one line in the batch size; the decode step of this library runs two kernel
+ * families, each linear with a slope of its own (weight-streaming GEMMs, and from harli_decode_tiled_min_batch()
+ * sequences on tiled GEMMs), and one line through both is off by up to 25 % at the switch.  bs_split > 0: samples and
+ * predictions with bs >= bs_split use a second set of Eq. 1 coefficients per level (harli_pred_solo_coef_upper); a
+ * family whose samples of a level do not determine a line (fewer than three, one batch size, one sequence length)
+ * takes the other family's line.  0, the default: one line per level, Eq. 1 as printed.  A change discards the solo
+ * fits (call harli_pred_fit again); calibration factors and the co-located fit stay. */
+harli_status harli_pred_set_batch_split(harli_predictor* p, int32_t bs_split);
+harli_status harli_pred_solo_coef_upper(const harli_predictor* p, int32_t level, double* solo);
+
 /* Predictions (host out-pointer).  Co-located: max(1, SM_infer*b1 + SM_ft*k1) * solo(infer_level): Eq. 2's slowdown
  * factor is derived (Sec. 5.2.2) for the contended case only, where it is at least 1; below that the two tasks do not
  * contend and the prediction is the solo latency. */

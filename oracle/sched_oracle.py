@@ -38,7 +38,40 @@ def fit_solo(samples):
     return tuple(float(b) for b in beta)
 
 
+class SplitCoef:
+    """Eq. 1 per kernel family (an addition to the paper's predictor, which has one line per compute-unit level):
+    `lo` = (b0, c0, k0) for batches below `bs_split`, `hi` for batches from `bs_split` on.  The decode step under
+    test runs two kernel families whose step times are linear in the batch size with different slopes."""
+
+    def __init__(self, bs_split, lo, hi):
+        self.bs_split, self.lo, self.hi = int(bs_split), tuple(lo), tuple(hi)
+
+
+def _determined(s):
+    """Do the samples fix a line of Eq. 1?  Three of them with a design matrix of full rank."""
+    if len(s) < 3:
+        return False
+    s = np.asarray(s, np.float64)
+    X = np.stack([s[:, 0], np.ones(len(s)), s[:, 0] * s[:, 1]], axis=1)
+    return int(np.linalg.matrix_rank(X)) == 3
+
+
+def fit_solo_split(samples, bs_split):
+    """One least-squares fit of Eq. 1 per family; a family its samples do not determine takes the other's line."""
+    samples = list(samples)
+    lo = [t for t in samples if t[0] < bs_split]
+    hi = [t for t in samples if t[0] >= bs_split]
+    ok_lo, ok_hi = _determined(lo), _determined(hi)
+    if not ok_lo and not ok_hi:
+        raise ValueError("the samples determine neither line")
+    c_lo = fit_solo(lo) if ok_lo else None
+    c_hi = fit_solo(hi) if ok_hi else None
+    return SplitCoef(bs_split, c_lo if ok_lo else c_hi, c_hi if ok_hi else c_lo)
+
+
 def predict_solo(coef, bs, seqlen):
+    if isinstance(coef, SplitCoef):
+        coef = coef.hi if bs >= coef.bs_split else coef.lo
     b0, c0, k0 = coef
     return bs * b0 + c0 + bs * k0 * seqlen
 
@@ -46,6 +79,8 @@ def predict_solo(coef, bs, seqlen):
 def calibrated(coef, scale):
     """Eq. 1 coefficients whose prediction is `scale` times that of `coef` (the library's per-level calibration
     factor, an addition to the paper's predictor: measured / predicted, folded back in at run time)."""
+    if isinstance(coef, SplitCoef):
+        return SplitCoef(coef.bs_split, calibrated(coef.lo, scale), calibrated(coef.hi, scale))
     return tuple(scale * c for c in coef)
 
 

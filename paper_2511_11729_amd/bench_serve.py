@@ -201,14 +201,15 @@ def make_plan(args, m, ft, pool, ctx, ft_step, server, log):
         def finetune_unit(self, stream):
             ft_step(Fixed(stream))
 
-    grid_b = tuple(b for b in (4, 16, 64, 160) if b <= PB)
+    grid_b = tuple(b for b in (4, 16, 32, 64, 160) if b <= PB)   # two or three per kernel family of the decode step
     grid_n = tuple(n for n in (128, 512, 1024, 1536) if n <= PN)
-    held = tuple((b, n) for b, n in ((8, 256), (32, 768), (96, 1280)) if b <= PB and n <= PN)
+    held = tuple((b, n) for b, n in ((8, 256), (24, 768), (96, 1280)) if b <= PB and n <= PN)
     pred, rep = colocate.profile(Hz(), steps=3, log=log, batches=grid_b, seqlens=grid_n, heldout=held)
     pool.free_pages(ids)
     log("[sched] decode alone by level (ms): " + " ".join("%.1f" % v for v in rep["solo_ms_by_level_workload_batch"]))
     log("[sched] decode beside finetune (ms): " + " ".join("%s=%.1f" % kv for kv in rep["colo_ms"].items()))
-    rep = {k: rep[k] for k in ("eq1_mean_abs_err_fitted_points", "eq1_mean_abs_err_heldout", "eq2_b1_k1", "eq2_mean_abs_err")}
+    rep = {k: rep[k] for k in ("eq1_mean_abs_err_fitted_points", "eq1_mean_abs_err_heldout", "eq1_batch_split",
+                               "eq1_as_printed_mean_abs_err_fitted_points", "eq1_as_printed_mean_abs_err_heldout", "eq2_b1_k1", "eq2_mean_abs_err")}
     cs = colocate.CuStreams()
     low, high = cs.pairs(log)
     ft_all = None

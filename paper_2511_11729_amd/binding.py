@@ -127,6 +127,9 @@ _SIGS = {
     "harli_pred_observe": (C.c_int, [C.c_void_p, C.c_int32, C.c_double, C.c_double, C.c_double]),
     "harli_pred_fit": (C.c_int, [C.c_void_p]),
     "harli_pred_solo_coef": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_double)]),
+    "harli_pred_solo_coef_upper": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_double)]),
+    "harli_pred_set_batch_split": (C.c_int, [C.c_void_p, C.c_int32]),
+    "harli_decode_tiled_min_batch": (C.c_int32, []),
     "harli_pred_colo_coef": (C.c_int, [C.c_void_p, C.POINTER(C.c_double)]),
     "harli_pred_set_colo_floor": (C.c_int, [C.c_void_p, C.c_int32]),
     "harli_pred_solo": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_double)]),
@@ -454,6 +457,16 @@ class Predictor:
         _check(lib().harli_pred_solo_coef(self.handle, level, c))
         return tuple(c)
 
+    def solo_coef_upper(self, level: int):
+        """Eq. 1 coefficients of `level` for batches from the split on (those of solo_coef without a split)."""
+        c = (C.c_double * 3)()
+        _check(lib().harli_pred_solo_coef_upper(self.handle, level, c))
+        return tuple(c)
+
+    def set_batch_split(self, bs_split: int) -> None:
+        """Batches from bs_split on get Eq. 1 coefficients of their own (0: one line per level, as printed)."""
+        _check(lib().harli_pred_set_batch_split(self.handle, bs_split))
+
     def set_colo_floor(self, enabled: bool) -> None:
         _check(lib().harli_pred_set_colo_floor(self.handle, 1 if enabled else 0))
 
@@ -536,6 +549,11 @@ class DbgGemm2Desc(C.Structure):
                 ("ldcf", C.c_int64 * 3), ("e0", C.c_void_p), ("e1", C.c_void_p), ("o0", C.c_void_p), ("o1", C.c_void_p),
                 ("lde", C.c_int64), ("overflow_flag", C.c_void_p), ("tflops", C.POINTER(C.c_double)),
                 ("shader_mhz", C.POINTER(C.c_double)), ("n_cu", C.c_int32)]
+
+
+def decode_tiled_min_batch() -> int:
+    """Smallest batch whose decode steps run the tiled GEMMs."""
+    return int(lib().harli_decode_tiled_min_batch())
 
 
 def dbg_decode_large_min_batch(batch: int) -> None:

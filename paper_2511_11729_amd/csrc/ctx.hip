@@ -177,7 +177,10 @@ extern "C" harli_status harli_ctx_create(const harli_model_cfg* cfg, const harli
   TRY(dev_alloc(c, &d.att_part, bp * m.n_q_heads * d.max_chunks * (m.head_dim + 2) * 4, true));
   TRY(dev_alloc(c, &d.err_flag, 16, true));
   d.part_bytes = dg_workspace_bytes(m, c->n_cu);
-  if (d.part_bytes) TRY(dev_alloc(c, &d.part, d.part_bytes, false));
+  if (d.part_bytes) {
+    TRY(dev_alloc(c, &d.part, d.part_bytes, false));
+    TRY(dg_init());
+  }
   // fp32 path: scratch for attention scores, one row of max_seq_len per (sequence, query head)
   if (m.dtype == HARLI_F32) {
     TRY(dev_alloc(c, &d.scores, bp * m.n_q_heads * (size_t)m.max_seq_len * 4, true));

@@ -1002,6 +1002,8 @@ extern "C" harli_status harli_decode_step(harli_ctx* c, const harli_decode_batch
   return decode_step_bf16(c, b, st, c->dw);
 }
 
+extern "C" int32_t harli_decode_tiled_min_batch(void) { return dg_min_batch(); }
+
 extern "C" size_t harli_decode_step_static_bytes(const harli_ctx* c, int32_t batch, int32_t max_kv_len) {
   if (!c || batch < 1 || max_kv_len < 1) return 0;
   const harli_model_cfg& m = c->cfg;

@@ -84,6 +84,8 @@ struct DgPlan {
 DgPlan dg_plan(int B, int n_rows, int n_mat, int K, int n_cu, size_t ws_bytes);
 // workspace a context needs for batches up to max_batch (0 when the large-batch path can never run)
 size_t dg_workspace_bytes(const harli_model_cfg& m, int n_cu);
+// once per process, before the first launch (harli_ctx_create calls it when it takes the workspace)
+harli_status dg_init();
 // One GEMM of the step with its epilogue; `a` as the small-batch kernels take it (b0 ignored: all rows at once).
 // x_tiles: 16-row batch tiles the operand buffer was allocated for.  part: workspace of part_bytes.
 harli_status dg_launch(DgKind kind, const SkinnyArgs& a, int x_tiles, float* part, size_t part_bytes, int n_cu, hipStream_t st);

@@ -424,7 +424,9 @@ size_t dg_workspace_bytes(const harli_model_cfg& m, int n_cu) {
   return std::min(need, (size_t)192 << 20);
 }
 
-harli_status dg_gemm(DgKind kind, const SkinnyArgs& a, int x_tiles, float* part, size_t part_bytes, int n_cu, hipStream_t st, DgPlan* used) {
+// The tile kernels need more dynamic LDS than the default limit; set once per process (harli_ctx_create calls this when
+// it takes the workspace, so that no step -- a captured one included -- is the first to ask).
+harli_status dg_init() {
   std::call_once(g_attr_once, [] {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_dgemm<1>), hipFuncAttributeMaxDynamicSharedMemorySize, dg_lds_bytes<1>());
     if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_dgemm<2>), hipFuncAttributeMaxDynamicSharedMemorySize, dg_lds_bytes<2>());
@@ -433,6 +435,14 @@ harli_status dg_gemm(DgKind kind, const SkinnyArgs& a, int x_tiles, float* part,
     g_attr_err = e;
   });
   HARLI_HIP(g_attr_err);
+  return HARLI_OK;
+}
+
+harli_status dg_gemm(DgKind kind, const SkinnyArgs& a, int x_tiles, float* part, size_t part_bytes, int n_cu, hipStream_t st, DgPlan* used) {
+  {
+    harli_status rc = dg_init();
+    if (rc != HARLI_OK) return rc;
+  }
   const int n_mat = kind == DG_GATEUP ? 2 : 1;
   const int n_rows = kind == DG_QKV ? (a.n_q + 2 * a.n_kv) * a.d : a.n_rows;
   const int steps = (a.K + BK - 1) / BK, w_tiles16 = (n_rows + 15) / 16;

@@ -64,6 +64,8 @@ struct harli_predictor {
   std::vector<std::vector<SoloSample>> solo;  // per level (index level-1)
   std::vector<ColoSample> colo;
   std::vector<double> coef;       // 3 per level
+  std::vector<double> coef_hi;    // 3 per level: the line for batches from bs_split on (equal to coef without a split)
+  int bs_split = 0;               // 0: one line per level (Eq. 1 as printed)
   std::vector<char> fitted;       // per level
   std::vector<double> scale;      // per level: calibration factor on Eq. 1's prediction (1 unless the caller sets it)
   std::vector<char> observed;     // per level: a measured step has been folded into `scale` (harli_pred_observe)
@@ -76,7 +78,8 @@ namespace {
 constexpr double kScaleMin = 0.6, kScaleMax = 2.5;  // one measured step moves a prediction by no more than this
 bool level_ok(const harli_predictor* p, int level) { return level >= 1 && level <= p->n_levels; }
 double eval_solo(const harli_predictor* p, int level, double bs, double seqlen) {
-  const double* c = &p->coef[(size_t)(level - 1) * 3];
+  const std::vector<double>& all = (p->bs_split > 0 && bs >= p->bs_split) ? p->coef_hi : p->coef;
+  const double* c = &all[(size_t)(level - 1) * 3];
   return p->scale[level - 1] * (bs * c[0] + c[1] + bs * c[2] * seqlen);
 }
 // Eq. 2, with the slowdown factor floored at 1: the paper derives the factor as (f_infer + f_ft) / B for the
@@ -93,6 +96,7 @@ extern "C" harli_status harli_pred_create(int32_t n_levels, harli_predictor** ou
   p->n_levels = n_levels;
   p->solo.resize(n_levels);
   p->coef.assign((size_t)n_levels * 3, 0.0);
+  p->coef_hi.assign((size_t)n_levels * 3, 0.0);
   p->fitted.assign(n_levels, 0);
   p->scale.assign(n_levels, 1.0);
   p->observed.assign(n_levels, 0);
@@ -125,15 +129,28 @@ extern "C" harli_status harli_pred_fit(harli_predictor* p) {
     if (s.empty()) continue;
     const int n = (int)s.size();
     if (n < 3) return fail(HARLI_ERR_STATE, "pred_fit: level %d has %d samples, Eq. 1 needs 3", l + 1, n);
-    std::vector<double> X((size_t)n * 3), y(n);
-    for (int i = 0; i < n; ++i) {
-      X[i * 3 + 0] = s[i].bs;
-      X[i * 3 + 1] = 1.0;
-      X[i * 3 + 2] = s[i].bs * s[i].seqlen;
-      y[i] = s[i].lat;
-    }
-    if (!lstsq(X, y, n, 3, &p->coef[(size_t)l * 3]))
+    // one least-squares line per batch family (a single family without a split)
+    auto fit_family = [&](bool upper, double* beta) -> bool {
+      std::vector<double> X, y;
+      for (const SoloSample& q : s) {
+        if (p->bs_split > 0 && (q.bs >= p->bs_split) != upper) continue;
+        X.push_back(q.bs);
+        X.push_back(1.0);
+        X.push_back(q.bs * q.seqlen);
+        y.push_back(q.lat);
+      }
+      const int m = (int)y.size();
+      return m >= 3 && lstsq(X, y, m, 3, beta);
+    };
+    double lo[3], hi[3];
+    const bool ok_lo = fit_family(false, lo), ok_hi = p->bs_split > 0 && fit_family(true, hi);
+    if (!ok_lo && !ok_hi)
       return fail(HARLI_ERR_STATE, "pred_fit: level %d samples do not determine Eq. 1 (vary batch size and sequence length)", l + 1);
+    // a family the samples do not determine takes the other family's line
+    for (int i = 0; i < 3; ++i) {
+      p->coef[(size_t)l * 3 + i] = ok_lo ? lo[i] : hi[i];
+      p->coef_hi[(size_t)l * 3 + i] = ok_hi ? hi[i] : lo[i];
+    }
     p->fitted[l] = 1;
   }
   if (!p->colo.empty()) {
@@ -221,6 +238,22 @@ extern "C" harli_status harli_pred_solo_coef(const harli_predictor* p, int32_t l
   if (!p || !solo || !level_ok(p, level)) return fail(HARLI_ERR_INVALID, "pred_solo_coef: bad argument");
   if (!p->fitted[level - 1]) return fail(HARLI_ERR_STATE, "pred_solo_coef: level %d is not fitted", level);
   for (int i = 0; i < 3; ++i) solo[i] = p->coef[(size_t)(level - 1) * 3 + i];
+  return HARLI_OK;
+}
+
+extern "C" harli_status harli_pred_solo_coef_upper(const harli_predictor* p, int32_t level, double* solo) {
+  if (!p || !solo || !level_ok(p, level)) return fail(HARLI_ERR_INVALID, "pred_solo_coef_upper: bad argument");
+  if (!p->fitted[level - 1]) return fail(HARLI_ERR_STATE, "pred_solo_coef_upper: level %d is not fitted", level);
+  for (int i = 0; i < 3; ++i) solo[i] = p->coef_hi[(size_t)(level - 1) * 3 + i];
+  return HARLI_OK;
+}
+
+extern "C" harli_status harli_pred_set_batch_split(harli_predictor* p, int32_t bs_split) {
+  if (!p || bs_split < 0) return fail(HARLI_ERR_INVALID, "pred_set_batch_split: bad argument");
+  if (bs_split != p->bs_split) {
+    p->bs_split = bs_split;
+    std::fill(p->fitted.begin(), p->fitted.end(), 0);  // the lines were fitted for the other reading
+  }
   return HARLI_OK;
 }
 

@@ -243,3 +243,98 @@ def test_run_time_feedback_equals_the_model_and_moves_the_predictions():
         with pytest.raises(hb.HarliError) as e:
             p.observe(*bad)
         assert e.value.status == hb.HARLI_ERR_INVALID
+
+
+# ---- Eq. 1 per kernel family (batch split) -------------------------------------------------------------------------
+def two_family_samples(rng, lv, noise=0.0, upper_batches=(40, 64, 160), knee=33):
+    """Step times that are linear in the batch size on either side of `knee` with different slopes (the shape of a
+    decode step that switches kernel families there)."""
+    r = lv / 10.0
+    lo = (0.0016 / r ** 0.5, 0.09 / r ** 0.7 + 0.03, 2.0e-6 / r ** 0.8)
+    hi = (0.0007 / r ** 0.5, 0.13 / r ** 0.7 + 0.05, 1.6e-6 / r ** 0.8)
+    pts = []
+    for bs in (4, 16) + tuple(upper_batches):
+        b0, c0, k0 = hi if bs >= knee else lo
+        for n in (64, 128, 256, 512):
+            pts.append((bs, n, (bs * b0 + c0 + bs * k0 * n) * (1 + noise * rng.standard_normal())))
+    return pts, lo, hi
+
+
+def test_oracle_split_fit_recovers_both_lines_exactly_from_noiseless_samples():
+    """Pin of the oracle's own split fit: samples generated from two known lines give those lines back, one plain line
+    through all of them does not, and a family with a single batch size borrows the other family's line."""
+    rng = np.random.default_rng(0)
+    pts, lo, hi = two_family_samples(rng, 5)
+    c = S.fit_solo_split(pts, 33)
+    assert np.allclose(c.lo, lo, rtol=1e-9) and np.allclose(c.hi, hi, rtol=1e-9)
+    for bs, n, lat in pts:
+        assert abs(S.predict_solo(c, bs, n) - lat) <= 1e-9 * lat
+    one = S.fit_solo(pts)
+    assert max(abs(S.predict_solo(one, bs, n) - lat) / lat for bs, n, lat in pts) > 0.05
+    # the upper family measured at one batch size only: its line is not determined
+    pts1, lo1, _ = two_family_samples(rng, 5, upper_batches=(64,))
+    c1 = S.fit_solo_split(pts1, 33)
+    assert np.allclose(c1.lo, lo1, rtol=1e-9) and c1.hi == c1.lo
+    # a split below every sample: the lower family is empty and borrows the upper line, which is the plain fit
+    c2 = S.fit_solo_split(pts, 2)
+    assert np.allclose(c2.lo, one, rtol=1e-9) and np.allclose(c2.hi, one, rtol=1e-9)
+    with pytest.raises(ValueError):
+        S.fit_solo_split(pts[:2], 33)
+
+
+@pytest.mark.parametrize("seed", [0, 1])
+def test_batch_split_in_the_library_matches_the_oracle(seed):
+    rng = np.random.default_rng(40 + seed)
+    p = hb.Predictor(10)
+    o = []
+    samples = {}
+    for lv in range(1, 11):
+        pts, _, _ = two_family_samples(rng, lv, noise=0.01, upper_batches=(64,) if lv == 4 else (40, 64, 160))
+        samples[lv] = pts
+        for bs, n, lat in pts:
+            p.add_solo(lv, bs, n, lat)
+    colo = [(i, f, 1.0 + 0.1 * f, 1.0) for i, f in S.pairs(10)]
+    for i, f, lc, ls in colo:
+        p.add_colo(i, f, lc, ls)
+    p.fit()
+    plain = [S.fit_solo(samples[lv]) for lv in range(1, 11)]
+    for lv in range(1, 11):                          # no split: one line, and the upper coefficients are the same line
+        assert np.allclose(p.solo_coef(lv), plain[lv - 1], rtol=1e-8, atol=1e-14)
+        assert p.solo_coef_upper(lv) == p.solo_coef(lv)
+    p.set_batch_split(33)
+    with pytest.raises(hb.HarliError):               # the lines of the other reading are gone
+        p.solo_coef(1)
+    p.fit()
+    o = [S.fit_solo_split(samples[lv], 33) for lv in range(1, 11)]
+    o_colo = S.fit_colo([(i / 10, f / 10, lc, ls) for i, f, lc, ls in colo])
+    for lv in range(1, 11):
+        assert np.allclose(p.solo_coef(lv), o[lv - 1].lo, rtol=1e-8, atol=1e-14)
+        assert np.allclose(p.solo_coef_upper(lv), o[lv - 1].hi, rtol=1e-8, atol=1e-14)
+        for bs, n in [(1, 0), (32, 500), (33, 500), (200, 1500)]:
+            want = S.predict_solo(o[lv - 1], bs, n)
+            assert abs(p.solo(lv, bs, n) - want) <= 1e-8 * abs(want)
+    assert p.solo_coef_upper(4) == p.solo_coef(4)    # level 4 saw one batch size above the split
+    # the split line predicts the upper family better than the single line did
+    lv = 7
+    err_split = np.mean([abs(S.predict_solo(o[lv - 1], bs, n) - lat) / lat for bs, n, lat in samples[lv]])
+    err_plain = np.mean([abs(S.predict_solo(plain[lv - 1], bs, n) - lat) / lat for bs, n, lat in samples[lv]])
+    assert err_split < 0.02 < err_plain
+    # allocation choices and the runtime scheduler follow the split predictions
+    for bs, n, slo in [(8, 512, 0.4), (42, 1024, 0.9), (150, 300, 0.6), (64, 2048, 3.0)]:
+        wi, wf, wl_ = S.pick(o, o_colo, bs, n, slo)
+        gi, gf, gl = p.pick(bs, n, slo)
+        assert (gi, gf) == (wi, wf) and abs(gl - wl_) <= 1e-8 * abs(wl_)
+    ora = S.RuntimeScheduler(o, o_colo, 0.6, 10, 8)
+    sch = hb.Scheduler(p, 0.6, 8)
+    for k in range(80):
+        bs, n, ready = int(rng.integers(1, 200)), int(rng.integers(16, 2000)), bool(rng.random() > 0.1)
+        assert sch.step(bs, n, ready)[:2] == ora.step(bs, n, ready)[:2]
+    p.set_batch_split(0)
+    p.fit()
+    assert np.allclose(p.solo_coef(7), plain[6], rtol=1e-8, atol=1e-14)
+    with pytest.raises(hb.HarliError):
+        p.set_batch_split(-1)
+
+
+def test_tiled_min_batch_is_reported():
+    assert hb.decode_tiled_min_batch() == 33
