@@ -7,6 +7,9 @@ compared with.
 * Eq. 1 (solo decode latency, one model per compute-unit ratio):
       latency = bs*b0 + c0 + bs*k0*seqlen
   fitted by ordinary least squares over profiled (bs, seqlen, latency) samples.
+  Addition to the paper (SplitCoef, fit_solo_split): one such line per kernel family of the decode step under test,
+  samples and predictions below a batch threshold using one set of coefficients and those from it on another;
+  pinned by samples drawn from two known lines, which the split fit gives back and a single line cannot.
 * Eq. 2 (co-located decode latency):
       latency_colo = (SM_infer*b1 + SM_ft*k1) * latency_solo(SM_infer)
   fitted by ordinary least squares of latency_colo on the two regressors SM_infer*latency_solo and
