@@ -558,7 +558,9 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(attn_m
       unpack8(vf[pp][it], vv);
 #pragma unroll
       for (int gq = 0; gq < G; ++gq) {
-        const float p = ok[pp][it] ? exp2f(sc[gq][pp][it] - mw[gq]) : 0.f;
+        // the hardware exponential as it is: the argument is <= 0 and a result below the normal range may go to zero
+        // (the library call rescales around the instruction to return subnormals)
+        const float p = ok[pp][it] ? __builtin_amdgcn_exp2f(sc[gq][pp][it] - mw[gq]) : 0.f;
         lw[gq] += p;
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[gq][e] += p * vv[e];
