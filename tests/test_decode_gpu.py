@@ -327,3 +327,61 @@ def test_biases_small_shapes_bf16_and_fp32():
     for dtype in ("bf16", "f32"):
         w, m = variant(0, dtype=dtype, n_layers=2, qkv_bias=True)
         run_case(w, m, [0, 5, 16, 31, 77])
+
+
+def test_tiled_path_on_a_compute_unit_partition_and_in_a_replayed_graph():
+    """The cut of the tiled GEMMs follows the compute units of the stream the step runs on (fewer ranges of K on a small
+    partition): the result meets the oracle there too.  And the step is capturable: a replayed HIP graph gives the bits
+    of the eager step on every replay, with eager work in between."""
+    from paper_2511_11729_amd import colocate
+    w, m = variant(0, dtype="bf16", n_layers=2, hidden=1024, n_q=8, n_kv=2, head_dim=128, ffn=2816, vocab=1000)
+    lengths = np.asarray([5 + (i * 13) % 120 for i in range(100)], np.int32)
+    case = DecodeCase(w, m, lengths, full_model=True, block_bytes=256 << 10)
+    tok = wl.make_token_ids(dataclasses.replace(w, model=m), (100,))
+    ref_hid, ref_logits, _ = case.run_oracle(token_ids=tok)
+    img0 = torch.from_numpy(case.img0.view(np.uint8))
+    hid = case.run_gpu(token_ids=tok)
+    assert_close(hid, ref_hid, "hidden state, whole chip")
+    eager = (case.y_dev.clone(), case.logits_dev.clone(), case.slab.clone())
+    cs = colocate.CuStreams()
+    part = cs.low(2)                                   # 20 % of the compute units: other cuts
+    case.slab.copy_(img0)
+    torch.cuda.synchronize()
+    hid_p = case.run_gpu(token_ids=tok, stream=part)
+    assert_close(hid_p, ref_hid, "hidden state on 2/10 of the compute units")
+    assert_close(case.logits_dev.cpu().numpy(), ref_logits, "logits on 2/10 of the compute units")
+    case.check_cache()
+    torch.cuda.synchronize()
+    cs.close()
+    # graph: captured on an ordinary stream, replayed three times with eager steps between the replays
+    st = torch.cuda.Stream()
+    tok_dev = torch.from_numpy(np.asarray(tok, np.int32)).to("cuda:0")
+    y_g, logits_g, next_g = torch.empty_like(eager[0]), torch.empty_like(eager[1]), torch.empty_like(case.next_dev)
+
+    def step():
+        case.ctx.decode_step(batch=case.B, kv_len=case.kv_len_dev, page_table=case.table_dev, max_pages=case.max_pages,
+                             max_kv_len=int(case.kv_len.max()) + 1, token_ids=tok_dev, logits=logits_g,
+                             next_token=next_g, x_out=y_g, stream=st)
+
+    case.slab.copy_(img0)
+    torch.cuda.synchronize()
+    step()
+    st.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=st):
+        step()
+    for rep in range(3):
+        case.slab.copy_(img0)
+        y_g.zero_()
+        logits_g.zero_()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(st):
+            g.replay()
+        st.synchronize()
+        assert torch.equal(y_g, eager[0]) and torch.equal(logits_g, eager[1]) and torch.equal(case.slab, eager[2])
+        case.slab.copy_(img0)                          # the program's own eager work between replays
+        torch.cuda.synchronize()
+        case.run_gpu(token_ids=tok)
+        assert torch.equal(case.y_dev, eager[0])
+    case.ctx.check()
+    del g
