@@ -385,3 +385,19 @@ def test_tiled_path_on_a_compute_unit_partition_and_in_a_replayed_graph():
         assert torch.equal(case.y_dev, eager[0])
     case.ctx.check()
     del g
+
+
+@pytest.mark.parametrize("batch", [4, 40])
+def test_vocabulary_that_is_not_a_multiple_of_four(batch):
+    """Rows of the logits that are not 16-byte aligned (vocabulary 1003) on both kernel families: the streaming output
+    layer at batch 4, the tiled one at batch 40."""
+    w, m = variant(0, dtype="bf16", n_layers=1, vocab=1003)
+    lengths = np.asarray([3 + (i * 11) % 90 for i in range(batch)], np.int32)
+    case = DecodeCase(w, m, lengths, full_model=True, block_bytes=64 << 10)
+    tok = wl.make_token_ids(dataclasses.replace(w, model=m), (batch,))
+    hid = case.run_gpu(token_ids=tok)
+    ref_hid, ref_logits, _ = case.run_oracle(token_ids=tok)
+    assert_close(hid, ref_hid, "hidden state")
+    logits = case.logits_dev.cpu().numpy()
+    assert_close(logits, ref_logits, "logits")
+    assert np.array_equal(case.next_dev.cpu().numpy(), np.argmax(logits, axis=-1))
