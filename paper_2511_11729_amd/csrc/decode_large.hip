@@ -1,13 +1,13 @@
 // Large-batch GEMMs of the decode step (see decode_large.h): partial products on 32x32x16 bf16 MFMA tiles, then one
 // small kernel per GEMM that adds the partials and applies the step's epilogue.
 //
-// k_dgemm<FM>: workgroup tile (64 FM) batch rows (FM = 1..4) x 256 weight rows over a range of K; four waves, one per SIMD, each
-// a (32 FM) x 128 block.  Both operands are read where the small-batch kernels keep them -- MFMA-fragment order,
-// [16-row tile][k step of 32][lane][8], a 16 x 32 tile being 1 KiB contiguous -- and go straight into LDS with
+// k_dgemm<FM>: workgroup tile (64 FM) batch rows (FM = 1..4) x 256 weight rows over a range of K; four waves, one per
+// SIMD, each a (32 FM) x 128 block.  Both operands are read where the small-batch kernels keep them -- MFMA-fragment
+// order, [16-row tile][k step of 32][lane][8], a 16 x 32 tile being 1 KiB contiguous -- and go straight into LDS with
 // buffer loads, tile by tile as they lie (the order is the one the 32-row fragment reads want: conflict free without
-// a swizzle).  Four to six LDS stages, the K loop software pipelined by hand as in the finetune task's weight GEMM (one wave per SIMD has nobody to hide its waits).  Rows and
-// tiles that do not exist, and stages past the end of the range, are loaded from an offset outside the buffer
-// resource, which the hardware answers with zeros.
+// a swizzle).  Four to six LDS stages, the K loop software pipelined by hand as in the finetune task's weight GEMM
+// (one wave per SIMD has nobody to hide its waits).  Rows and tiles that do not exist, and stages past the end of the
+// range, are loaded from an offset outside the buffer resource, which the hardware answers with zeros.
 #include "decode_large.h"
 
 #include <algorithm>
